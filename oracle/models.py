@@ -1,0 +1,104 @@
+"""The two networks of the measured workloads, forward and backward, in float64.
+
+MLP: 3072 -> 128 (ReLU) -> 10 on flattened images.  ResNetCifar: the CIFAR residual network of
+He et al. (2016) that the paper calls ResNet20 (Section 5): 3x3 stem, 3 stages x 3 basic blocks
+of widths 16/32/64, parameter-free shortcuts, global average pooling and a linear classifier.
+Widths, depth and image size are arguments so that tiny instances can be checked by finite
+differences.  Parameters and buffers are dicts of float64 arrays keyed by tensor name.
+"""
+import numpy as np
+
+from . import layers as L
+
+
+def _f64(d):
+    return {k: np.asarray(v, dtype=np.float64) for k, v in d.items()}
+
+
+class MLP:
+    has_buffers = False
+
+    def forward(self, params, buffers, x, train):
+        p = _f64(params)
+        x2 = np.asarray(x, dtype=np.float64).reshape(x.shape[0], -1)
+        h = L.relu(L.linear(x2, p["fc1.weight"], p["fc1.bias"]))
+        logits = L.linear(h, p["fc2.weight"], p["fc2.bias"])
+        return logits, (p, x2, h), dict(buffers)
+
+    def backward(self, cache, dlogits):
+        p, x2, h = cache
+        dh, dw2, db2 = L.linear_backward(h, p["fc2.weight"], dlogits)
+        dpre = L.relu_backward(dh, h)
+        _, dw1, db1 = L.linear_backward(x2, p["fc1.weight"], dpre)
+        return {"fc1.weight": dw1, "fc1.bias": db1, "fc2.weight": dw2, "fc2.bias": db2}
+
+
+class ResNetCifar:
+    has_buffers = True
+
+    def __init__(self, widths=(16, 32, 64), blocks=3):
+        self.widths = tuple(widths)
+        self.blocks = blocks
+
+    def _block_list(self):
+        out, c_prev = [], self.widths[0]
+        for s, c in enumerate(self.widths):
+            for b in range(self.blocks):
+                out.append(("s%d.b%d" % (s + 1, b), c_prev, c, 2 if (b == 0 and s > 0) else 1))
+                c_prev = c
+        return out
+
+    def _bn(self, name, x, p, bufs, new_bufs, train):
+        g, b = p[name + ".weight"], p[name + ".bias"]
+        rm, rv = bufs[name + ".running_mean"], bufs[name + ".running_var"]
+        if not train:
+            return L.batchnorm_eval(x, g, b, rm, rv), None
+        y, cache, nrm, nrv = L.batchnorm_train(x, g, b, rm, rv)
+        new_bufs[name + ".running_mean"], new_bufs[name + ".running_var"] = nrm, nrv
+        return y, cache
+
+    def forward(self, params, buffers, x, train):
+        """Returns (logits [B, classes], cache for backward, buffers after this pass)."""
+        p, bufs = _f64(params), _f64(buffers)
+        new_bufs = dict(bufs)
+        x = np.asarray(x, dtype=np.float64)
+        cache = {"p": p, "x": x}
+        y0 = L.conv3x3(x, p["stem.conv.weight"], 1)
+        z0, cache["stem.bn"] = self._bn("stem.bn", y0, p, bufs, new_bufs, train)
+        a = L.relu(z0)
+        cache["stem.out"] = a
+        for name, c_in, c_out, stride in self._block_list():
+            cache[name + ".in"] = a
+            y1 = L.conv3x3(a, p[name + ".conv1.weight"], stride)
+            z1, cache[name + ".bn1"] = self._bn(name + ".bn1", y1, p, bufs, new_bufs, train)
+            h1 = L.relu(z1)
+            cache[name + ".h1"] = h1
+            y2 = L.conv3x3(h1, p[name + ".conv2.weight"], 1)
+            z2, cache[name + ".bn2"] = self._bn(name + ".bn2", y2, p, bufs, new_bufs, train)
+            a = L.relu(z2 + L.shortcut(a, c_out, stride))
+            cache[name + ".out"] = a
+        cache["final"] = a
+        pooled = L.global_avgpool(a)
+        cache["pooled"] = pooled
+        logits = L.linear(pooled, p["fc.weight"], p["fc.bias"])
+        return logits, cache, new_bufs
+
+    def backward(self, cache, dlogits):
+        """Gradients of sum_b <dlogits_b, logits_b> with respect to every parameter (train mode)."""
+        p = cache["p"]
+        g = {}
+        dpooled, g["fc.weight"], g["fc.bias"] = L.linear_backward(cache["pooled"], p["fc.weight"], dlogits)
+        da = L.global_avgpool_backward(dpooled, cache["final"].shape)
+        for name, c_in, c_out, stride in reversed(self._block_list()):
+            dz = L.relu_backward(da, cache[name + ".out"])
+            dy2, g[name + ".bn2.weight"], g[name + ".bn2.bias"] = L.batchnorm_train_backward(dz, cache[name + ".bn2"])
+            dh1, g[name + ".conv2.weight"] = L.conv3x3_backward(cache[name + ".h1"], p[name + ".conv2.weight"], dy2, 1)
+            dz1 = L.relu_backward(dh1, cache[name + ".h1"])
+            dy1, g[name + ".bn1.weight"], g[name + ".bn1.bias"] = L.batchnorm_train_backward(dz1, cache[name + ".bn1"])
+            x_in = cache[name + ".in"]
+            dx, g[name + ".conv1.weight"] = L.conv3x3_backward(x_in, p[name + ".conv1.weight"], dy1, stride)
+            da = dx + L.shortcut_backward(dz, x_in.shape, stride)
+        dz0 = L.relu_backward(da, cache["stem.out"])
+        dy0, g["stem.bn.weight"], g["stem.bn.bias"] = L.batchnorm_train_backward(dz0, cache["stem.bn"])
+        _, g["stem.conv.weight"] = L.conv3x3_backward(cache["x"], p["stem.conv.weight"], dy0, 1, need_dx=False)
+        return g
