@@ -1,0 +1,159 @@
+/*
+ * bls.h - C ABI of the biased-local-SGD fast path for AMD MI355X (gfx950).
+ *
+ * The four operations are the fast worker's share of one communication round of the
+ * system-aware biased local SGD framework (arXiv 2508.08540, Algorithm 1):
+ *
+ *   score_losses        one loss value per candidate sample (Section 4.2: samples are ranked
+ *                       by loss value; Section 4.3 limitations: one float per sample)
+ *   topk_by_loss        deterministic selection of the k highest-loss samples (Section 4.2,
+ *                       first sampling step of Algorithm 1)
+ *   local_step          tau local mini-batch SGD updates on the selected samples, recording the
+ *                       individual losses of the processed samples (Section 2 update rule;
+ *                       local-update and loss-recording steps of Algorithm 1)
+ *   weighted_aggregate  x_{t+1} = sum_i (tau_i / sum_j tau_j) x^i_t (Section 4.3, Eq. 4)
+ *
+ * Conventions for every call
+ *   - "device" pointers are HIP device memory on the context's GPU, owned by the caller and not
+ *     retained after the call returns; "host" pointers are ordinary memory, read before return.
+ *   - Work is enqueued on the context's stream and the call returns without waiting; the caller
+ *     synchronises the stream before reading results.  Scratch memory belongs to the context.
+ *   - Return value: BLS_OK (0) or a negative bls_status.  Argument errors are detected on the
+ *     host before anything is enqueued and leave all outputs untouched; bls_last_error() then
+ *     describes the problem.  Nothing is printed and nothing aborts.
+ *   - Results are bit-reproducible run to run (no floating-point atomics).
+ *   - One context must not be used from two threads at once.
+ */
+#ifndef BLS_H
+#define BLS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BLS_OK = 0,
+    BLS_EINVAL = -1,       /* bad argument (NULL, size out of range, k > N, ...)          */
+    BLS_ENOMEM = -2,       /* device or host allocation failed                            */
+    BLS_EHIP = -3,         /* a HIP runtime call failed; see bls_last_error()              */
+    BLS_EUNSUPPORTED = -4  /* valid request outside what the kernels are built for        */
+} bls_status;
+
+typedef struct bls_ctx bls_ctx;     /* device, stream (borrowed) and library-owned scratch */
+typedef struct bls_model bls_model; /* architecture and flat-parameter layout (host only)  */
+
+enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1 };
+
+/* Architecture description.
+ *   MLP:           image_hw*image_hw*in_channels -> hidden (ReLU) -> classes.
+ *   RESNET_CIFAR:  3x3 stem conv to widths[0], three stages of `blocks` two-convolution residual
+ *                  blocks with widths[0..2] (stride 2 and a parameter-free zero-padded shortcut at
+ *                  the start of stages 2 and 3), batch norm after every convolution, global
+ *                  average pooling, linear classifier.  ResNet20 (Section 5) is widths 16/32/64,
+ *                  blocks 3, image_hw 32, in_channels 3, classes 10. */
+typedef struct {
+    int32_t kind;        /* BLS_MODEL_*                                    */
+    int32_t classes;     /* 2 .. 64                                        */
+    int32_t image_hw;    /* square images; RESNET: multiple of 8, 8 .. 64  */
+    int32_t in_channels; /* RESNET: 1 .. 4                                 */
+    int32_t hidden;      /* MLP only: multiple of 16, 16 .. 1024           */
+    int32_t widths[3];   /* RESNET only: each of 16, 32 or 64              */
+    int32_t blocks;      /* RESNET only: 1 .. 18                           */
+} bls_model_desc;
+
+/* One tensor of the flat parameter vector (is_buffer = 0) or of the flat buffer vector that
+ * holds batch-norm running means and variances (is_buffer = 1).  Offsets count floats.
+ * Convolution weights are [C_out, 3, 3, C_in]; linear weights are [out, in]. */
+typedef struct {
+    char name[56];
+    int64_t offset;
+    int32_t ndim;
+    int32_t shape[4];
+    int32_t is_buffer;
+} bls_tensor_info;
+
+/* SGD hyper-parameters with the semantics of the optimiser the paper trains with (Appendix A.1):
+ * g += weight_decay * x;  buf = momentum * buf + g;  x -= lr * buf. */
+typedef struct {
+    float lr;
+    float momentum;
+    float weight_decay;
+} bls_sgd;
+
+enum {
+    BLS_AGG_NORMALISE = 1, /* divide the weights by their sum instead of requiring sum == 1 */
+    BLS_AGG_BROADCAST = 2  /* also store the result into every replica (start of next round) */
+};
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Creates a context on HIP device `device`.  `hip_stream` is a hipStream_t owned by the caller
+ * (NULL = the default stream); all work of this context is enqueued there. */
+int bls_ctx_create(bls_ctx** out, int device, void* hip_stream);
+/* Waits for the stream, frees the scratch memory and the context.  NULL is allowed. */
+void bls_ctx_destroy(bls_ctx* ctx);
+/* Text of the most recent error on this context ("" if none).  Owned by the context. */
+const char* bls_last_error(const bls_ctx* ctx);
+/* Blocks until everything enqueued on the context's stream has finished. */
+int bls_ctx_synchronize(bls_ctx* ctx);
+
+/* ---- model description (host only; no GPU needed) ------------------------------------------- */
+
+int bls_model_create(const bls_model_desc* desc, bls_model** out);
+void bls_model_destroy(bls_model* model);
+/* d: number of trainable floats.  Buffers: batch-norm running statistics (0 for the MLP). */
+int64_t bls_model_num_params(const bls_model* model);
+int64_t bls_model_num_buffers(const bls_model* model);
+/* Number of tensors (parameters and buffers together). */
+int32_t bls_model_num_tensors(const bls_model* model);
+/* Fills out[0 .. capacity-1]; returns the number of tensors written or BLS_EINVAL. */
+int bls_model_tensor_layout(const bls_model* model, bls_tensor_info* out, int32_t capacity);
+
+/* ---- the four operations ------------------------------------------------------------------ */
+
+/* Loss of every candidate under the current parameters (Section 4.2).
+ *   params   device float[d]; buffers device float[num_buffers] (may be NULL for the MLP)
+ *   x        device float[N, H, W, C] (channels last); y device int32[N], labels in [0, classes)
+ *   losses_out device float[N]: softmax cross-entropy of sample i, natural logarithm
+ * Batch-norm layers use their running statistics, so a score does not depend on the rest of the
+ * pool.  N == 0 is a no-op.  Labels are not range-checked on the device. */
+int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, const float* buffers,
+                 const float* x, const int32_t* y, int64_t N, float* losses_out);
+
+/* Indices of the k largest losses in rank order (Section 4.2; deterministic).
+ *   losses device float[N]; idx_out device int32[k]; val_out device float[k] or NULL
+ * Total order: NaN ranks above +inf, -0 equals +0, equal losses rank by ascending index.
+ * 0 <= k <= N < 2^31; k == 0 is a no-op.  val_out[r] = losses[idx_out[r]] bit for bit. */
+int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out);
+
+/* tau mini-batch SGD updates on the selected samples (Algorithm 1, fast-worker branch).
+ *   params, momentum  device float[d], updated in place; buffers device float[num_buffers],
+ *                     updated in place (batch norm trains with batch statistics)
+ *   x_pool, y_pool    the candidate pool as in score_losses (N samples)
+ *   sel_idx           device int32[k], indices into the pool (e.g. from topk_by_loss)
+ *   step j (0 <= j < tau) trains on sel_idx[(j*batch + b) mod k], b = 0 .. batch-1; the batch loss
+ *   is the mean of the per-sample losses
+ *   step_losses_out   device float[tau * batch] or NULL: the loss of every processed sample
+ * Requires 1 <= k, 1 <= batch; tau == 0 is a no-op.  A zero momentum vector before the first step
+ * gives buf = g there.  Indices are not range-checked on the device. */
+int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffers, float* momentum,
+               const float* x_pool, const int32_t* y_pool, int64_t N, const int32_t* sel_idx, int64_t k,
+               int64_t batch, int64_t tau, const bls_sgd* opt, float* step_losses_out);
+
+/* out[j] = sum_i w_i * replicas[i][j], i ascending, in fp32 (Eq. 4).
+ *   replicas host array of P device pointers to float[d]; weights host float[P], finite,
+ *   non-negative, summing to 1 within 1e-5 unless BLS_AGG_NORMALISE is given
+ *   out device float[d]; may be one of the replicas
+ * 1 <= P <= 64.  d == 0 is a no-op.  Non-finite parameter values propagate (IEEE). */
+int weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* weights, int P, int64_t d,
+                       float* out, int flags);
+
+/* w_i = tau_i / sum_j tau_j (Eq. 4), computed in double and rounded once.  Host only. */
+int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLS_H */

@@ -1,0 +1,203 @@
+"""ctypes binding with the same names as the C ABI in include/bls.h (argument marshalling only)."""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+MODEL_MLP, MODEL_RESNET_CIFAR = 0, 1
+AGG_NORMALISE, AGG_BROADCAST = 1, 2
+
+DECLARED_SYMBOLS = (
+    "bls_ctx_create", "bls_ctx_destroy", "bls_last_error", "bls_ctx_synchronize", "bls_model_create",
+    "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
+    "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
+    "bls_weights_from_tau",
+)
+
+
+class BlsError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("bls status %d: %s" % (code, message))
+        self.code = code
+
+
+class _ModelDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("classes", C.c_int32), ("image_hw", C.c_int32), ("in_channels", C.c_int32),
+                ("hidden", C.c_int32), ("widths", C.c_int32 * 3), ("blocks", C.c_int32)]
+
+
+class _TensorInfo(C.Structure):
+    _fields_ = [("name", C.c_char * 56), ("offset", C.c_int64), ("ndim", C.c_int32), ("shape", C.c_int32 * 4),
+                ("is_buffer", C.c_int32)]
+
+
+class _Sgd(C.Structure):
+    _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+
+
+def library_path():
+    return os.path.join(_HERE, "libbls.so")
+
+
+def _load():
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError("libbls.so is not built: run `python -m paper_2508_08540_amd.build` (needs hipcc)")
+    L = C.CDLL(path)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+    L.bls_ctx_create.argtypes = [C.POINTER(vp), C.c_int, vp]
+    L.bls_ctx_destroy.argtypes = [vp]
+    L.bls_ctx_destroy.restype = None
+    L.bls_last_error.argtypes = [vp]
+    L.bls_last_error.restype = C.c_char_p
+    L.bls_ctx_synchronize.argtypes = [vp]
+    L.bls_model_create.argtypes = [C.POINTER(_ModelDesc), C.POINTER(vp)]
+    L.bls_model_destroy.argtypes = [vp]
+    L.bls_model_destroy.restype = None
+    for f in (L.bls_model_num_params, L.bls_model_num_buffers):
+        f.argtypes = [vp]
+        f.restype = i64
+    L.bls_model_num_tensors.argtypes = [vp]
+    L.bls_model_num_tensors.restype = i32
+    L.bls_model_tensor_layout.argtypes = [vp, C.POINTER(_TensorInfo), i32]
+    L.score_losses.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
+    L.topk_by_loss.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.local_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i64, C.POINTER(_Sgd), vp]
+    L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
+    L.bls_weights_from_tau.argtypes = [C.POINTER(i64), C.c_int, C.POINTER(C.c_float)]
+    return L
+
+
+lib = _load()
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / None."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to the library must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """A device, the HIP stream work is enqueued on (torch's current stream by default) and scratch memory."""
+
+    def __init__(self, device=0, stream=None):
+        import torch
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+        h = C.c_void_p()
+        rc = lib.bls_ctx_create(C.byref(h), int(device), C.c_void_p(stream))
+        if rc != 0:
+            raise BlsError(rc, "bls_ctx_create failed (is a GPU visible?)")
+        self.handle, self.device = h, device
+
+    def check(self, rc):
+        if rc != 0:
+            raise BlsError(rc, lib.bls_last_error(self.handle).decode())
+
+    def synchronize(self):
+        self.check(lib.bls_ctx_synchronize(self.handle))
+
+    def close(self):
+        if self.handle:
+            lib.bls_ctx_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Model:
+    """Architecture description and flat layout; host only."""
+
+    def __init__(self, kind, classes=10, image_hw=32, in_channels=3, hidden=128, widths=(16, 32, 64), blocks=3):
+        desc = _ModelDesc(kind, classes, image_hw, in_channels, hidden, (C.c_int32 * 3)(*widths), blocks)
+        h = C.c_void_p()
+        rc = lib.bls_model_create(C.byref(desc), C.byref(h))
+        if rc != 0:
+            raise BlsError(rc, "bls_model_create rejected the description")
+        self.handle = h
+        self.num_params = lib.bls_model_num_params(h)
+        self.num_buffers = lib.bls_model_num_buffers(h)
+        n = lib.bls_model_num_tensors(h)
+        arr = (_TensorInfo * n)()
+        got = lib.bls_model_tensor_layout(h, arr, n)
+        assert got == n
+        self.tensors = [dict(name=t.name.decode(), offset=t.offset, shape=tuple(t.shape[:t.ndim]),
+                             is_buffer=bool(t.is_buffer)) for t in arr]
+
+    @classmethod
+    def mlp(cls, d_hw=32, in_channels=3, hidden=128, classes=10):
+        return cls(MODEL_MLP, classes, d_hw, in_channels, hidden)
+
+    @classmethod
+    def resnet_cifar(cls, widths=(16, 32, 64), blocks=3, classes=10, image_hw=32, in_channels=3):
+        return cls(MODEL_RESNET_CIFAR, classes, image_hw, in_channels, 0, widths, blocks)
+
+    def pack(self, tensors, buffers=False):
+        """dict name -> array  =>  flat float32 numpy vector in the library's layout."""
+        out = np.zeros(self.num_buffers if buffers else self.num_params, dtype=np.float32)
+        for t in self.tensors:
+            if t["is_buffer"] == buffers:
+                a = np.asarray(tensors[t["name"]], dtype=np.float32)
+                assert a.shape == t["shape"], (t["name"], a.shape, t["shape"])
+                out[t["offset"]:t["offset"] + a.size] = a.reshape(-1)
+        return out
+
+    def unpack(self, flat, buffers=False):
+        flat = np.asarray(flat)
+        return {t["name"]: flat[t["offset"]:t["offset"] + int(np.prod(t["shape"]))].reshape(t["shape"])
+                for t in self.tensors if t["is_buffer"] == buffers}
+
+    def __del__(self):
+        try:
+            if self.handle:
+                lib.bls_model_destroy(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+
+def score_losses(ctx, model, params, buffers, x, y, losses_out):
+    ctx.check(lib.score_losses(ctx.handle, model.handle, _ptr(params), _ptr(buffers), _ptr(x), _ptr(y),
+                               x.shape[0], _ptr(losses_out)))
+    return losses_out
+
+
+def topk_by_loss(ctx, losses, k, idx_out, val_out=None):
+    ctx.check(lib.topk_by_loss(ctx.handle, _ptr(losses), losses.shape[0], k, _ptr(idx_out), _ptr(val_out)))
+    return idx_out
+
+
+def local_step(ctx, model, params, buffers, momentum, x_pool, y_pool, sel_idx, batch, tau, lr, mu=0.0,
+               weight_decay=0.0, step_losses_out=None, k=None):
+    opt = _Sgd(lr, mu, weight_decay)
+    ctx.check(lib.local_step(ctx.handle, model.handle, _ptr(params), _ptr(buffers), _ptr(momentum), _ptr(x_pool),
+                             _ptr(y_pool), x_pool.shape[0], _ptr(sel_idx), sel_idx.shape[0] if k is None else k,
+                             batch, tau, C.byref(opt), _ptr(step_losses_out)))
+
+
+def weighted_aggregate(ctx, replicas, weights, out, flags=0):
+    P = len(replicas)
+    d = out.numel()
+    ptrs = (C.c_void_p * P)(*[r.data_ptr() for r in replicas])
+    w = (C.c_float * P)(*[float(v) for v in weights])
+    ctx.check(lib.weighted_aggregate(ctx.handle, ptrs, w, P, d, _ptr(out), flags))
+    return out
+
+
+def weights_from_tau(tau):
+    P = len(tau)
+    t = (C.c_int64 * P)(*[int(v) for v in tau])
+    w = (C.c_float * P)()
+    rc = lib.bls_weights_from_tau(t, P, w)
+    if rc != 0:
+        raise BlsError(rc, "bls_weights_from_tau rejected the step counts")
+    return np.array(list(w), dtype=np.float32)

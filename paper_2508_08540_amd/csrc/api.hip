@@ -1,0 +1,280 @@
+// C ABI entry points: argument checking, scratch sizing and dispatch to the kernel launchers.
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+#include "model.h"
+#include "net.h"
+
+int bls_fail(bls_ctx* ctx, int code, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->error = buf;
+    }
+    return code;
+}
+
+int bls_arena_reserve(bls_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->arena_bytes) return BLS_OK;
+    BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->arena) BLS_HIP(ctx, hipFree(ctx->arena));
+    ctx->arena = nullptr;
+    ctx->arena_bytes = 0;
+    size_t want = bytes + bytes / 8;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&ctx->arena), want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return bls_fail(ctx, BLS_ENOMEM, "scratch allocation of %zu bytes failed: %s", want, hipGetErrorString(e));
+    }
+    ctx->arena_bytes = want;
+    return BLS_OK;
+}
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int bls_ctx_create(bls_ctx** out, int device, void* hip_stream) {
+    if (!out) return BLS_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) {
+        (void)hipGetLastError();
+        return BLS_EHIP;
+    }
+    if (hipSetDevice(device) != hipSuccess) return BLS_EHIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return BLS_EHIP;
+    bls_ctx* ctx = new (std::nothrow) bls_ctx();
+    if (!ctx) return BLS_ENOMEM;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    ctx->num_cus = prop.multiProcessorCount;
+    ctx->max_lds = prop.sharedMemPerBlock;
+    int optin = 0;
+    if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess &&
+        (size_t)optin > ctx->max_lds)
+        ctx->max_lds = (size_t)optin;
+    (void)hipGetLastError();
+    *out = ctx;
+    return BLS_OK;
+}
+
+void bls_ctx_destroy(bls_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    net_release(ctx);
+    if (ctx->arena) (void)hipFree(ctx->arena);
+    delete ctx;
+}
+
+const char* bls_last_error(const bls_ctx* ctx) { return ctx ? ctx->error.c_str() : ""; }
+
+int bls_ctx_synchronize(bls_ctx* ctx) {
+    if (!ctx) return BLS_EINVAL;
+    BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return BLS_OK;
+}
+
+// ---- model ----------------------------------------------------------------------------------------
+
+static void add_tensor(bls_model* m, const std::string& name, bool is_buffer, int ndim, int s0, int s1 = 1, int s2 = 1,
+                       int s3 = 1) {
+    TensorSlot t;
+    t.name = name;
+    t.ndim = ndim;
+    t.shape[0] = s0; t.shape[1] = s1; t.shape[2] = s2; t.shape[3] = s3;
+    t.is_buffer = is_buffer;
+    int64_t& total = is_buffer ? m->num_buffers : m->num_params;
+    t.offset = total;
+    total += t.count();
+    m->tensors.push_back(t);
+}
+
+static void add_conv_bn(bls_model* m, const std::string& conv, const std::string& bn, int c_in, int c_out, int stride,
+                        int h_in) {
+    ConvBn l;
+    l.c_in = c_in; l.c_out = c_out; l.stride = stride; l.h_in = h_in; l.h_out = (h_in - 1) / stride + 1;
+    l.w_off = m->num_params;
+    add_tensor(m, conv + ".weight", false, 4, c_out, 3, 3, c_in);
+    l.gamma_off = m->num_params;
+    add_tensor(m, bn + ".weight", false, 1, c_out);
+    l.beta_off = m->num_params;
+    add_tensor(m, bn + ".bias", false, 1, c_out);
+    l.rmean_off = m->num_buffers;
+    add_tensor(m, bn + ".running_mean", true, 1, c_out);
+    l.rvar_off = m->num_buffers;
+    add_tensor(m, bn + ".running_var", true, 1, c_out);
+    m->layers.push_back(l);
+}
+
+int bls_model_create(const bls_model_desc* desc, bls_model** out) {
+    if (!desc || !out) return BLS_EINVAL;
+    *out = nullptr;
+    if (desc->classes < 2 || desc->classes > 64) return BLS_EINVAL;
+    bls_model* m = new (std::nothrow) bls_model();
+    if (!m) return BLS_ENOMEM;
+    m->desc = *desc;
+    if (desc->kind == BLS_MODEL_MLP) {
+        if (desc->image_hw < 1 || desc->in_channels < 1 || desc->hidden < 16 || desc->hidden > 1024 ||
+            desc->hidden % 16 != 0 || (int64_t)desc->image_hw * desc->image_hw * desc->in_channels > (1 << 20)) {
+            delete m;
+            return BLS_EINVAL;
+        }
+        m->d_in = desc->image_hw * desc->image_hw * desc->in_channels;
+        m->fc1_w = m->num_params; add_tensor(m, "fc1.weight", false, 2, desc->hidden, m->d_in);
+        m->fc1_b = m->num_params; add_tensor(m, "fc1.bias", false, 1, desc->hidden);
+        m->fc2_w = m->num_params; add_tensor(m, "fc2.weight", false, 2, desc->classes, desc->hidden);
+        m->fc2_b = m->num_params; add_tensor(m, "fc2.bias", false, 1, desc->classes);
+    } else if (desc->kind == BLS_MODEL_RESNET_CIFAR) {
+        bool ok = desc->image_hw >= 8 && desc->image_hw <= 64 && desc->image_hw % 8 == 0 && desc->in_channels >= 1 &&
+                  desc->in_channels <= 4 && desc->blocks >= 1 && desc->blocks <= 18;
+        for (int s = 0; s < 3; ++s) {
+            int w = desc->widths[s];
+            ok = ok && (w == 16 || w == 32 || w == 64);
+            // the zero-padded shortcut needs an even number of extra channels and never fewer
+            if (s > 0) ok = ok && w >= desc->widths[s - 1] && (w - desc->widths[s - 1]) % 2 == 0;
+        }
+        if (!ok) {
+            delete m;
+            return BLS_EINVAL;
+        }
+        int hw = desc->image_hw;
+        add_conv_bn(m, "stem.conv", "stem.bn", desc->in_channels, desc->widths[0], 1, hw);
+        int c_prev = desc->widths[0];
+        for (int s = 0; s < 3; ++s) {
+            int c = desc->widths[s];
+            for (int b = 0; b < desc->blocks; ++b) {
+                int stride = (b == 0 && s > 0) ? 2 : 1;
+                char p[32];
+                snprintf(p, sizeof p, "s%d.b%d", s + 1, b);
+                add_conv_bn(m, std::string(p) + ".conv1", std::string(p) + ".bn1", c_prev, c, stride, hw);
+                hw = (hw - 1) / stride + 1;
+                add_conv_bn(m, std::string(p) + ".conv2", std::string(p) + ".bn2", c, c, 1, hw);
+                c_prev = c;
+            }
+        }
+        m->final_c = c_prev;
+        m->final_hw = hw;
+        m->fc_w = m->num_params; add_tensor(m, "fc.weight", false, 2, desc->classes, c_prev);
+        m->fc_b = m->num_params; add_tensor(m, "fc.bias", false, 1, desc->classes);
+    } else {
+        delete m;
+        return BLS_EINVAL;
+    }
+    *out = m;
+    return BLS_OK;
+}
+
+void bls_model_destroy(bls_model* model) { delete model; }
+int64_t bls_model_num_params(const bls_model* model) { return model ? model->num_params : BLS_EINVAL; }
+int64_t bls_model_num_buffers(const bls_model* model) { return model ? model->num_buffers : BLS_EINVAL; }
+int32_t bls_model_num_tensors(const bls_model* model) { return model ? (int32_t)model->tensors.size() : BLS_EINVAL; }
+
+int bls_model_tensor_layout(const bls_model* model, bls_tensor_info* out, int32_t capacity) {
+    if (!model || !out || capacity < 0) return BLS_EINVAL;
+    int n = (int)model->tensors.size() < capacity ? (int)model->tensors.size() : capacity;
+    for (int i = 0; i < n; ++i) {
+        const TensorSlot& t = model->tensors[i];
+        memset(&out[i], 0, sizeof out[i]);
+        strncpy(out[i].name, t.name.c_str(), sizeof out[i].name - 1);
+        out[i].offset = t.offset;
+        out[i].ndim = t.ndim;
+        for (int j = 0; j < 4; ++j) out[i].shape[j] = j < t.ndim ? t.shape[j] : 1;
+        out[i].is_buffer = t.is_buffer ? 1 : 0;
+    }
+    return n;
+}
+
+// ---- operations -----------------------------------------------------------------------------------
+
+int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, const float* buffers, const float* x,
+                 const int32_t* y, int64_t N, float* losses_out) {
+    if (!ctx) return BLS_EINVAL;
+    if (!model || N < 0) return bls_fail(ctx, BLS_EINVAL, "score_losses: model is NULL or N < 0");
+    if (N == 0) return BLS_OK;
+    if (!params || !x || !y || !losses_out) return bls_fail(ctx, BLS_EINVAL, "score_losses: NULL pointer");
+    if (model->num_buffers > 0 && !buffers) return bls_fail(ctx, BLS_EINVAL, "score_losses: this model needs buffers");
+    if (N >= (int64_t(1) << 31)) return bls_fail(ctx, BLS_EINVAL, "score_losses: N must be below 2^31");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    return net_score(ctx, model, params, buffers, x, y, N, losses_out);
+}
+
+int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
+    if (!ctx) return BLS_EINVAL;
+    if (N < 0 || k < 0 || k > N) return bls_fail(ctx, BLS_EINVAL, "topk_by_loss: need 0 <= k <= N (N=%lld, k=%lld)", (long long)N, (long long)k);
+    if (N >= (int64_t(1) << 31)) return bls_fail(ctx, BLS_EINVAL, "topk_by_loss: N must be below 2^31");
+    if (k == 0) return BLS_OK;
+    if (!losses || !idx_out) return bls_fail(ctx, BLS_EINVAL, "topk_by_loss: NULL pointer");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    return launch_topk(ctx, losses, N, k, idx_out, val_out);
+}
+
+int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffers, float* momentum,
+               const float* x_pool, const int32_t* y_pool, int64_t N, const int32_t* sel_idx, int64_t k, int64_t batch,
+               int64_t tau, const bls_sgd* opt, float* step_losses_out) {
+    if (!ctx) return BLS_EINVAL;
+    if (!model || !opt) return bls_fail(ctx, BLS_EINVAL, "local_step: model or opt is NULL");
+    if (N < 1 || k < 1 || batch < 1 || tau < 0) return bls_fail(ctx, BLS_EINVAL, "local_step: need N, k, batch >= 1 and tau >= 0");
+    if (N >= (int64_t(1) << 31) || batch > 65536) return bls_fail(ctx, BLS_EINVAL, "local_step: N < 2^31 and batch <= 65536 required");
+    if (!(isfinite(opt->lr) && isfinite(opt->momentum) && isfinite(opt->weight_decay)))
+        return bls_fail(ctx, BLS_EINVAL, "local_step: non-finite optimiser setting");
+    if (tau == 0) return BLS_OK;
+    if (!params || !momentum || !x_pool || !y_pool || !sel_idx) return bls_fail(ctx, BLS_EINVAL, "local_step: NULL pointer");
+    if (model->num_buffers > 0 && !buffers) return bls_fail(ctx, BLS_EINVAL, "local_step: this model needs buffers");
+    if (model->desc.kind == BLS_MODEL_RESNET_CIFAR && batch * model->final_hw * model->final_hw < 2)
+        return bls_fail(ctx, BLS_EINVAL, "local_step: batch norm needs more than one value per channel");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    return net_local_step(ctx, model, params, buffers, momentum, x_pool, y_pool, N, sel_idx, k, batch, tau, *opt,
+                          step_losses_out);
+}
+
+int weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* weights, int P, int64_t d, float* out,
+                       int flags) {
+    if (!ctx) return BLS_EINVAL;
+    if (P < 1 || P > 64 || d < 0) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: need 1 <= P <= 64 and d >= 0");
+    if (!replicas || !weights) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: NULL pointer");
+    if (flags & ~(BLS_AGG_NORMALISE | BLS_AGG_BROADCAST)) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: unknown flag");
+    double sum = 0.0;
+    for (int i = 0; i < P; ++i) {
+        if (!isfinite(weights[i]) || weights[i] < 0.f)
+            return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: weight %d is negative or not finite", i);
+        sum += (double)weights[i];
+    }
+    float w[64];
+    if (flags & BLS_AGG_NORMALISE) {
+        if (!(sum > 0.0)) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: weights sum to zero");
+        for (int i = 0; i < P; ++i) w[i] = (float)((double)weights[i] / sum);
+    } else {
+        if (fabs(sum - 1.0) > 1e-5) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: weights sum to %.9g, not 1", sum);
+        for (int i = 0; i < P; ++i) w[i] = weights[i];
+    }
+    if (d == 0) return BLS_OK;
+    if (!out) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: NULL output");
+    for (int i = 0; i < P; ++i)
+        if (!replicas[i]) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: replica %d is NULL", i);
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    return launch_weighted_aggregate(ctx, replicas, w, P, d, out, (flags & BLS_AGG_BROADCAST) != 0);
+}
+
+int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out) {
+    if (!tau || !weights_out || P < 1) return BLS_EINVAL;
+    double sum = 0.0;
+    for (int i = 0; i < P; ++i) {
+        if (tau[i] < 0) return BLS_EINVAL;
+        sum += (double)tau[i];
+    }
+    if (!(sum > 0.0)) return BLS_EINVAL;
+    for (int i = 0; i < P; ++i) weights_out[i] = (float)((double)tau[i] / sum);
+    return BLS_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

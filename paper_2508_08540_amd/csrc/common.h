@@ -1,0 +1,52 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+#include <vector>
+
+#include "../../include/bls.h"
+
+struct bls_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char* arena = nullptr;      // one scratch allocation, grown on demand
+    size_t arena_bytes = 0;
+    int num_cus = 0;
+    size_t max_lds = 0;
+    std::string error;
+};
+
+int bls_fail(bls_ctx* ctx, int code, const char* fmt, ...);
+
+#define BLS_HIP(ctx, expr)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return bls_fail((ctx), BLS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// Makes the context's scratch arena at least `bytes` large.  Growing waits for the stream first.
+int bls_arena_reserve(bls_ctx* ctx, size_t bytes);
+
+// Bump allocator over the arena; every block is 256-byte aligned.
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(char* b) : base(b) {}
+    template <typename T>
+    T* take(size_t count) {
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += (count * sizeof(T) + 255) & ~size_t(255);
+        return p;
+    }
+};
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- launchers (each enqueues on ctx->stream and returns a bls_status) ------------------------
+int launch_weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* weights, int P, int64_t d,
+                              float* out, bool broadcast);
+size_t topk_scratch_bytes(int64_t N, int64_t k);
+int launch_topk(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out);

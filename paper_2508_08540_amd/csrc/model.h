@@ -1,0 +1,39 @@
+// Architecture description and flat-vector layout (host side).
+#pragma once
+#include "common.h"
+
+struct TensorSlot {
+    std::string name;
+    int64_t offset;
+    int ndim;
+    int shape[4];
+    bool is_buffer;
+    int64_t count() const {
+        int64_t n = 1;
+        for (int i = 0; i < ndim; ++i) n *= shape[i];
+        return n;
+    }
+};
+
+// One batch-normalised 3x3 convolution of the residual network.
+struct ConvBn {
+    int c_in, c_out, stride;
+    int h_in, h_out;          // square feature maps
+    int64_t w_off;            // conv weight [c_out,3,3,c_in] in params
+    int64_t gamma_off, beta_off;
+    int64_t rmean_off, rvar_off;  // in buffers
+};
+
+struct bls_model {
+    bls_model_desc desc;
+    int64_t num_params = 0;
+    int64_t num_buffers = 0;
+    std::vector<TensorSlot> tensors;
+    // MLP
+    int64_t fc1_w = 0, fc1_b = 0, fc2_w = 0, fc2_b = 0;
+    int d_in = 0;
+    // residual network: layers[0] is the stem, then conv1/conv2 of every block in order
+    std::vector<ConvBn> layers;
+    int64_t fc_w = 0, fc_b = 0;
+    int final_c = 0, final_hw = 0;
+};

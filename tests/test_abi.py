@@ -1,0 +1,54 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/bls.h declares, and
+the model layout matches the tensor order the synthetic weight generator uses."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "bls.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(\w+)\s*\([^;{}]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2508_08540_amd as bls
+    names = _declared_functions()
+    assert set(names) == set(bls.DECLARED_SYMBOLS)
+    raw = ctypes.CDLL(bls.library_path())
+    for n in names:
+        assert hasattr(raw, n), n
+
+
+def test_layout_matches_generator_order_and_counts():
+    import paper_2508_08540_amd as bls
+    m = bls.Model.resnet_cifar()
+    assert m.num_params == 269722 and m.num_buffers == 1376
+    p_specs, b_specs = synth.resnet_tensor_specs()
+    assert [(t["name"], t["shape"]) for t in m.tensors if not t["is_buffer"]] == p_specs
+    assert [(t["name"], t["shape"]) for t in m.tensors if t["is_buffer"]] == b_specs
+    mlp = bls.Model.mlp()
+    assert mlp.num_params == 394634 and mlp.num_buffers == 0
+    assert [(t["name"], t["shape"]) for t in mlp.tensors] == synth.mlp_tensor_specs()
+    p, b = synth.resnet_init(1)
+    flat = m.pack(p)
+    back = m.unpack(flat)
+    for k in p:
+        np.testing.assert_array_equal(back[k], p[k])
+    with pytest.raises(bls.BlsError):
+        bls.Model.resnet_cifar(widths=(16, 24, 64))
+
+
+def test_weights_from_tau_host_helper():
+    import paper_2508_08540_amd as bls
+    w = bls.weights_from_tau([32] * 8 + [16] * 2)
+    np.testing.assert_array_equal(w, np.array([1 / 9] * 8 + [1 / 18] * 2, dtype=np.float32))
+    with pytest.raises(bls.BlsError):
+        bls.weights_from_tau([0, 0])

@@ -1,0 +1,126 @@
+"""GPU parity: weighted_aggregate and topk_by_loss through the C ABI against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    yield torch, bls, ctx
+    ctx.close()
+
+
+def _agg_check(torch, bls, ctx, reps, w32, flags=0, out_alias=None):
+    dev = [torch.from_numpy(r.copy()).cuda() for r in reps]
+    out = dev[out_alias] if out_alias is not None else torch.empty(reps.shape[1], dtype=torch.float32, device="cuda")
+    bls.weighted_aggregate(ctx, dev, w32, out, flags)
+    ctx.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    w64 = np.asarray(w32, dtype=np.float32).astype(np.float64)
+    if flags & bls.AGG_NORMALISE:
+        w64 = (w64 / w64.sum()).astype(np.float32).astype(np.float64)
+    ref = oracle.weighted_aggregate(reps, w64)
+    bound = 1e-6 * (np.abs(w64)[:, None] * np.abs(reps.astype(np.float64))).sum(axis=0)
+    assert np.all(np.abs(got - ref) <= bound + 1e-45), float(np.max(np.abs(got - ref) / (bound + 1e-45)))
+    return dev, got
+
+
+@pytest.mark.parametrize("d", [0, 1, 3, 4, 1023, 4099, 269722 + 1376, 394634, 11007540])
+@pytest.mark.parametrize("P,wl", [(4, "mlp"), (10, "resnet20_fp32")])
+def test_aggregate_matches_oracle(env, d, P, wl):
+    torch, bls, ctx = env
+    cfg = synth.workload(wl)
+    base = synth.normal(11, d, d).astype(np.float32) * 0.1
+    reps = synth.replicas(base, P, cfg["id"])
+    w32 = synth.aggregation_weights(cfg).astype(np.float32)
+    if d == 0:
+        out = torch.empty(0, device="cuda")
+        bls.weighted_aggregate(ctx, [out] * P, w32, out)
+        return
+    _agg_check(torch, bls, ctx, reps, w32)
+
+
+def test_aggregate_special_cases(env):
+    torch, bls, ctx = env
+    base = synth.normal(12, 0, 5000).astype(np.float32)
+    same = np.stack([base] * 4)
+    _, got = _agg_check(torch, bls, ctx, same, [0.25] * 4)
+    np.testing.assert_array_equal(got, base.astype(np.float64))        # dyadic weights: exact
+    reps = synth.replicas(base, 10, 1)
+    e = np.zeros(10, dtype=np.float32)
+    e[7] = 1.0
+    _, got = _agg_check(torch, bls, ctx, reps, e)
+    np.testing.assert_array_equal(got, reps[7].astype(np.float64))     # unit weight: a copy
+    _, got = _agg_check(torch, bls, ctx, reps[:1], [1.0])
+    np.testing.assert_array_equal(got, reps[0].astype(np.float64))
+    # step counts as weights, normalised by the library
+    _agg_check(torch, bls, ctx, reps, [32.0] * 8 + [16.0] * 2, flags=bls.AGG_NORMALISE)
+    # output aliases a replica; broadcast stores the result everywhere
+    w = bls.weights_from_tau([32] * 8 + [1] * 2)
+    dev, got = _agg_check(torch, bls, ctx, reps, w, flags=bls.AGG_BROADCAST, out_alias=3)
+    for t in dev:
+        np.testing.assert_array_equal(t.cpu().numpy().astype(np.float64), got)
+    # misaligned views take the scalar path
+    big = torch.from_numpy(np.concatenate([np.zeros(1, np.float32), reps.reshape(-1)])).cuda()
+    views = [big[1 + i * 5000: 1 + (i + 1) * 5000] for i in range(10)]
+    out = torch.empty(5000, dtype=torch.float32, device="cuda")
+    bls.weighted_aggregate(ctx, views, w, out)
+    ctx.synchronize()
+    ref = oracle.weighted_aggregate(reps, w.astype(np.float64))
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=1e-6)
+    # NaN propagates
+    reps2 = reps.copy()
+    reps2[2, 17] = np.nan
+    dev = [torch.from_numpy(r.copy()).cuda() for r in reps2]
+    bls.weighted_aggregate(ctx, dev, w, out)
+    ctx.synchronize()
+    o = out.cpu().numpy()
+    assert np.isnan(o[17]) and np.isfinite(np.delete(o, 17)).all()
+
+
+def test_aggregate_rejects_bad_arguments(env):
+    torch, bls, ctx = env
+    t = torch.zeros(8, device="cuda")
+    for w in ([0.5, 0.6], [float("nan"), 1.0], [-0.5, 1.5]):
+        with pytest.raises(bls.BlsError):
+            bls.weighted_aggregate(ctx, [t, t], w, t)
+    with pytest.raises(bls.BlsError):
+        bls.weighted_aggregate(ctx, [t] * 65, [1 / 65] * 65, t)
+
+
+def _topk_check(torch, bls, ctx, arr, k):
+    d = torch.from_numpy(arr).cuda()
+    idx = torch.full((max(k, 1),), -1, dtype=torch.int32, device="cuda")
+    val = torch.zeros(max(k, 1), dtype=torch.float32, device="cuda")
+    bls.topk_by_loss(ctx, d, k, idx, val)
+    ctx.synchronize()
+    ref = oracle.topk_by_loss(arr, k)
+    got = idx.cpu().numpy()[:k]
+    np.testing.assert_array_equal(got, ref)                           # bit-exact indices
+    np.testing.assert_array_equal(val.cpu().numpy()[:k].view(np.uint32), arr[ref].view(np.uint32))
+
+
+@pytest.mark.parametrize("kind", synth.LOSS_ARRAY_KINDS)
+@pytest.mark.parametrize("n", [1, 2, 63, 256, 512, 1000, 2048, 4096, 4097, 16384])
+def test_topk_matches_oracle_small(env, kind, n):
+    torch, bls, ctx = env
+    arr = synth.loss_array(kind, n)
+    for k in sorted({0, 1, n // 4, n}):
+        _topk_check(torch, bls, ctx, arr, k)
+
+
+def test_topk_rejects_bad_arguments(env):
+    torch, bls, ctx = env
+    t = torch.zeros(8, device="cuda")
+    i = torch.zeros(16, dtype=torch.int32, device="cuda")
+    with pytest.raises(bls.BlsError):
+        bls.topk_by_loss(ctx, t, 9, i)
+    with pytest.raises(bls.BlsError):
+        bls.topk_by_loss(ctx, t, -1, i)
