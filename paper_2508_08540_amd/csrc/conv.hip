@@ -1,0 +1,388 @@
+// 3x3 convolutions (padding 1, stride 1 or 2) as implicit GEMMs on the fp32 matrix cores, NHWC.
+//
+// Forward / input gradient (conv_kernel).  A workgroup owns 4 consecutive output rows (all columns; more rows when maps are narrower than 8)
+// and stages the input rows they touch, with a zero halo, into LDS as [row][col][C_in + 4]; the
+// 4-float pad spreads consecutive pixels over all LDS banks for 16-byte reads.  Each wavefront keeps
+// the weights of one block of 16 output channels in registers for the whole kernel (9*C_in/4 VGPRs)
+// and walks 16-pixel tiles: v_mfma_f32_16x16x4_f32 with A = weights (row = output channel) and
+// B = pixels (column = pixel), so lane l ends with 4 consecutive channels of pixel (l % 16) and
+// stores them with one 16-byte write.  Lane group g = l / 16 supplies input channels 16s+4g .. +3
+// of a tap as one 16-byte LDS read that feeds four MFMAs (the K order inside a tap is free as long
+// as both operands agree).  The epilogue optionally reduces per-channel sum and sum of squares of
+// the tile for batch normalisation (deterministic: fixed shuffle tree, then a fixed wave order).
+// The input gradient of a stride-1 layer is the same kernel with weights read transposed and
+// flipped; for a stride-2 layer the upstream gradient is staged with zeros inserted between
+// samples, which turns the transposed convolution into a stride-1 one.
+//
+// Weight gradient (wgrad_kernel).  dW[o][tap][i] = sum_pixels dy[p][o] * x[p + tap][i] is a GEMM with
+// K = B*H*W.  Workgroups walk disjoint sets of pixel tiles (same staging as above plus the dy tile),
+// every wavefront accumulates its 16x16 (o, i) blocks for all 9 taps in registers across all its
+// tiles, and writes one partial per wavefront; a second kernel adds the partials in a fixed order.
+#include "kernels.h"
+
+#define CONV_THREADS 256
+
+struct ConvGeom {
+    int B, h_in, h_out, c_out, stride, ups;  // ups: input is read with zeros inserted (h_in is the virtual size)
+    int rpi_log2, imgs, in_rows, lw;          // rows per image part (log2), image parts per tile, LDS rows per part, LDS row width
+    int wout_log2;
+    int total_rows;                           // B * h_out
+    int w_ci;                                 // input channels actually present in the weight tensor
+    int n_tiles;
+    int rows_tile;                            // output rows per tile: 4, or more so that a tile has >= 32 pixels
+};
+
+static inline int ilog2(int v) {
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return l;
+}
+
+static ConvGeom make_geom(int B, int h_in, int h_out, int c_out, int stride, int ups, int w_ci) {
+    ConvGeom g;
+    g.B = B; g.h_in = h_in; g.h_out = h_out; g.c_out = c_out; g.stride = stride; g.ups = ups;
+    g.rows_tile = h_out >= 8 ? 4 : 32 / h_out;
+    int rpi = h_out < g.rows_tile ? h_out : g.rows_tile;
+    g.rpi_log2 = ilog2(rpi);
+    g.imgs = g.rows_tile / rpi;
+    g.in_rows = (rpi - 1) * stride + 3;
+    g.lw = h_in + 2;
+    g.wout_log2 = ilog2(h_out);
+    g.total_rows = B * h_out;
+    g.w_ci = w_ci;
+    g.n_tiles = (g.total_rows + g.rows_tile - 1) / g.rows_tile;
+    return g;
+}
+
+template <int CIN>
+static size_t input_lds_floats(const ConvGeom& g) {
+    return (size_t)g.imgs * g.in_rows * g.lw * (CIN + 4);
+}
+
+// Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + 4], zero outside the image.
+template <int CIN>
+__device__ __forceinline__ void stage_input(float* __restrict__ lds, const float* __restrict__ x, const ConvGeom& g,
+                                            int tile) {
+    constexpr int CP = CIN + 4, CQ = CIN / 4;
+    const int rpi = 1 << g.rpi_log2;
+    const int row0 = tile * g.rows_tile;
+    const int n_pix = g.imgs * g.in_rows * g.lw;
+    const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
+    for (int i = threadIdx.x; i < n_pix * CQ; i += CONV_THREADS) {
+        int cq = i % CQ, pix = i / CQ;
+        int lc = pix % g.lw, lr = pix / g.lw;
+        int part = lr / g.in_rows, li = lr - part * g.in_rows;
+        int grow = row0 + part * rpi;
+        int n = grow >> g.wout_log2;  // h_out == w_out
+        int h0 = grow & (g.h_out - 1);
+        int hi = h0 * g.stride - 1 + li, wi = lc - 1;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (n < g.B && hi >= 0 && hi < g.h_in && wi >= 0 && wi < g.h_in) {
+            if (!g.ups) {
+                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + hi) * src_h + wi) * CIN + cq * 4);
+            } else if (((hi | wi) & 1) == 0) {
+                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + (hi >> 1)) * src_h + (wi >> 1)) * CIN + cq * 4);
+            }
+        }
+        *reinterpret_cast<f32x4*>(lds + pix * CP + cq * 4) = v;
+    }
+}
+
+// LDS float offset of the top-left tap of output pixel q (index inside the tile).
+template <int CIN>
+__device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
+    int rowq = q >> g.wout_log2, col = q & (g.h_out - 1);
+    int part = rowq >> g.rpi_log2, r = rowq & ((1 << g.rpi_log2) - 1);
+    return ((part * g.in_rows + r * g.stride) * g.lw + col * g.stride) * (CIN + 4);
+}
+
+// MODE 0: forward weights w[o][tap][i]; MODE 1: transposed and flipped, w[i][8 - tap][o] (input gradient).
+template <int CIN, int MT, int MODE>
+__global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                            float* __restrict__ y, float* __restrict__ stats, ConvGeom g) {
+    extern __shared__ float lds[];
+    constexpr int CP = CIN + 4, S = CIN / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, grp = lane >> 4;
+    const int NO = g.c_out, NOB = NO >> 4;
+    const int ob = wave % NOB;
+    const int tile = blockIdx.x;
+
+    // weights of output-channel block `ob` into registers: wr[tap][s] holds input channels 16s+4grp .. +3
+    f32x4 wr[9][S];
+    {
+        const int o = ob * 16 + r16;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const int i0 = 16 * s + 4 * grp;
+                f32x4 v;
+                if (MODE == 0) {
+                    const float* p = w + ((int64_t)o * 9 + t) * g.w_ci + i0;
+                    if (g.w_ci == CIN) {
+                        v = *reinterpret_cast<const f32x4*>(p);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = (i0 + j < g.w_ci) ? p[j] : 0.f;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = w[((int64_t)(i0 + j) * 9 + (8 - t)) * NO + o];
+                }
+                wr[t][s] = v;
+            }
+    }
+
+    stage_input<CIN>(lds, x, g, tile);
+    __syncthreads();
+
+    const int tile_pixels = g.rows_tile << g.wout_log2;
+    const int n_groups = tile_pixels / (16 * MT);
+    const int64_t pix0 = (int64_t)tile * tile_pixels;
+    const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
+    f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
+
+    for (int mg = wave / NOB; mg < n_groups; mg += 4 / NOB) {
+        int base[MT];
+        f32x4 acc[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            base[m] = pixel_lds_base<CIN>(g, (mg * MT + m) * 16 + r16) + 4 * grp;
+            acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int tap_off = ((t / 3) * g.lw + (t % 3)) * CP;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                f32x4 b[MT];
+#pragma unroll
+                for (int m = 0; m < MT; ++m) b[m] = *reinterpret_cast<const f32x4*>(lds + base[m] + tap_off + 16 * s);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[t][s][j], b[m][j], acc[m], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            int64_t p = pix0 + (mg * MT + m) * 16 + r16;
+            if (p < total_pixels) {
+                *reinterpret_cast<f32x4*>(y + p * NO + ob * 16 + 4 * grp) = acc[m];
+                ssum += acc[m];
+                ssq += acc[m] * acc[m];
+            }
+        }
+    }
+
+    if (stats) {
+        // lanes of one group hold the same 4 channels for 16 different pixels: fold the pixels
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ssum[j] += __shfl_xor(ssum[j], o, 64);
+                ssq[j] += __shfl_xor(ssq[j], o, 64);
+            }
+        __syncthreads();  // all waves are done reading the input tile; reuse LDS
+        float* red = lds;  // [wave][2][16]
+        if (r16 == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                red[(wave * 2 + 0) * 16 + 4 * grp + j] = ssum[j];
+                red[(wave * 2 + 1) * 16 + 4 * grp + j] = ssq[j];
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 2 * NO) {
+            int which = threadIdx.x / NO, c = threadIdx.x % NO;
+            int cb = c >> 4;
+            float acc = 0.f;
+            for (int wv = cb; wv < 4; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
+            stats[((int64_t)tile * 2 + which) * NO + c] = acc;
+        }
+    }
+}
+
+template <int CIN, int MODE>
+static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, float* stats) {
+    size_t lds = input_lds_floats<CIN>(g) * sizeof(float);
+    auto kern = conv_kernel<CIN, 2, MODE>;
+    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(CONV_THREADS), lds, s, x, w, y, stats, g);
+}
+
+int conv_fwd_tiles(const ConvShape& cs) {
+    int h_out = (cs.h_in - 1) / cs.stride + 1;
+    return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
+}
+
+void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, float* stats_partials) {
+    int h_out = (cs.h_in - 1) / cs.stride + 1;
+    ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
+    switch (cs.c_in) {
+        case 16: launch_conv_t<16, 0>(s, g, x, w, y, stats_partials); break;
+        case 32: launch_conv_t<32, 0>(s, g, x, w, y, stats_partials); break;
+        default: launch_conv_t<64, 0>(s, g, x, w, y, stats_partials); break;
+    }
+}
+
+void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx) {
+    // The gradient with respect to the input is a stride-1 convolution whose input channels are the
+    // layer's output channels and whose output channels are the layer's input channels.
+    int ups = cs.stride == 2 ? 1 : 0;
+    ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in);
+    switch (cs.c_out) {
+        case 16: launch_conv_t<16, 1>(s, g, dy, w, dx, nullptr); break;
+        case 32: launch_conv_t<32, 1>(s, g, dy, w, dx, nullptr); break;
+        default: launch_conv_t<64, 1>(s, g, dy, w, dx, nullptr); break;
+    }
+}
+
+// ---- weight gradient ------------------------------------------------------------------------------
+
+struct WgradPlan {
+    int groups;  // workgroups (pixel chunks)
+    int wp;      // pixel splits among the waves of a workgroup
+};
+
+template <int NO, int NI, int NOB_W, int NIB_W>
+struct WgradCfg {
+    static constexpr int NOB = NO / 16, NIB = NI / 16;
+    static constexpr int WT = (NOB / NOB_W) * (NIB / NIB_W);  // waves that split the (o, i) blocks
+    static constexpr int WP = 4 / WT;                          // waves that split the pixels
+    static_assert(WT >= 1 && WT <= 4 && 4 % WT == 0, "wave split");
+};
+
+template <int NO, int NI, int NOB_W, int NIB_W>
+__global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                             float* __restrict__ partials, ConvGeom g, int tiles_per_group) {
+    using Cfg = WgradCfg<NO, NI, NOB_W, NIB_W>;
+    extern __shared__ float lds[];
+    constexpr int CP = NI + 4;
+    constexpr int DP = (NO % 32 == 16) ? NO : NO + 16;  // dy row pitch: 16 mod 32 floats
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, grp = lane >> 4;
+    const int ws = wave % Cfg::WT, wp = wave / Cfg::WT;
+    const int ob0 = (ws / (Cfg::NIB / NIB_W)) * NOB_W, ib0 = (ws % (Cfg::NIB / NIB_W)) * NIB_W;
+    const int tile_pixels = g.rows_tile << g.wout_log2;
+    const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
+    float* lds_x = lds;
+    float* lds_dy = lds + (size_t)g.imgs * g.in_rows * g.lw * CP;
+
+    f32x4 acc[NOB_W][NIB_W][9];
+#pragma unroll
+    for (int a = 0; a < NOB_W; ++a)
+#pragma unroll
+        for (int b = 0; b < NIB_W; ++b)
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc[a][b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int tile_begin = blockIdx.x * tiles_per_group;
+    const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        __syncthreads();  // previous tile fully consumed
+        stage_input<NI>(lds_x, x, g, tile);
+        const int64_t pix0 = (int64_t)tile * tile_pixels;
+        for (int i = threadIdx.x; i < tile_pixels * (NO / 4); i += CONV_THREADS) {
+            int q = i / (NO / 4), c4 = i % (NO / 4);
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (pix0 + q < total_pixels) v = *reinterpret_cast<const f32x4*>(dy + (pix0 + q) * NO + c4 * 4);
+            *reinterpret_cast<f32x4*>(lds_dy + q * DP + c4 * 4) = v;
+        }
+        __syncthreads();
+        // one MFMA consumes 4 pixels (one per lane group); this wave takes every WP-th quad
+        for (int qd = wp; qd < tile_pixels / 4; qd += Cfg::WP) {
+            const int q = 4 * qd + grp;
+            float a[NOB_W];
+#pragma unroll
+            for (int oa = 0; oa < NOB_W; ++oa) a[oa] = lds_dy[q * DP + (ob0 + oa) * 16 + r16];
+            const int xb = pixel_lds_base<NI>(g, q) + r16;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int tap_off = ((t / 3) * g.lw + (t % 3)) * CP;
+#pragma unroll
+                for (int ib = 0; ib < NIB_W; ++ib) {
+                    float b = lds_x[xb + tap_off + (ib0 + ib) * 16];
+#pragma unroll
+                    for (int oa = 0; oa < NOB_W; ++oa)
+                        acc[oa][ib][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[oa], b, acc[oa][ib][t], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // partial of this wave: part = blockIdx.x * WP + wp; element ((o*9 + t)*NI + i)
+    float* out = partials + ((int64_t)blockIdx.x * Cfg::WP + wp) * (NO * 9 * NI);
+#pragma unroll
+    for (int oa = 0; oa < NOB_W; ++oa)
+#pragma unroll
+        for (int ib = 0; ib < NIB_W; ++ib)
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int o = (ob0 + oa) * 16 + 4 * grp + j, i = (ib0 + ib) * 16 + r16;
+                    out[((int64_t)o * 9 + t) * NI + i] = acc[oa][ib][t][j];
+                }
+}
+
+// dw[(o*9+t)*ci_real + i] = sum_parts partials[part][(o*9+t)*NI + i]
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int n_parts, int n_out9,
+                                                           int NI, int ci_real, float* __restrict__ dw) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_out9 * ci_real) return;
+    int ot = idx / ci_real, i = idx - ot * ci_real;
+    int64_t src = (int64_t)ot * NI + i;
+    int64_t pitch = (int64_t)n_out9 * NI;
+    float acc = 0.f;
+    for (int p = 0; p < n_parts; ++p) acc += partials[p * pitch + src];
+    dw[idx] = acc;
+}
+
+static int wgrad_groups(const ConvShape& cs, int n_tiles) {
+    // Bound the partial traffic: each group writes c_out*9*c_in floats per pixel split.
+    int cap = (cs.c_in * cs.c_out <= 512) ? 256 : (cs.c_in * cs.c_out <= 1024 ? 128 : 64);
+    return n_tiles < cap ? n_tiles : cap;
+}
+
+static int wgrad_wp(const ConvShape& cs) {
+    if (cs.c_out == 16 && cs.c_in == 16) return 4;
+    if (cs.c_out == 32 && cs.c_in == 16) return 2;
+    return 1;
+}
+
+int conv_wgrad_partials(const ConvShape& cs) {
+    return wgrad_groups(cs, conv_fwd_tiles(cs)) * wgrad_wp(cs);
+}
+
+template <int NO, int NI, int NOB_W, int NIB_W>
+static void launch_wgrad_t(hipStream_t s, const ConvGeom& g, int groups, const float* x, const float* dy, float* partials) {
+    constexpr int DP = (NO % 32 == 16) ? NO : NO + 16;
+    size_t lds = (input_lds_floats<NI>(g) + (size_t)(g.rows_tile << g.wout_log2) * DP) * sizeof(float);
+    auto kern = wgrad_kernel<NO, NI, NOB_W, NIB_W>;
+    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int tiles_per_group = (g.n_tiles + groups - 1) / groups;
+    hipLaunchKernelGGL(kern, dim3(groups), dim3(CONV_THREADS), lds, s, x, dy, partials, g, tiles_per_group);
+}
+
+void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials, float* dw) {
+    int h_out = (cs.h_in - 1) / cs.stride + 1;
+    ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
+    int groups = wgrad_groups(cs, g.n_tiles);
+    // groups may leave the last ones empty after rounding tiles_per_group up; they then write zeros
+    int key = cs.c_out * 100 + cs.c_in;
+    switch (key) {
+        case 1616: launch_wgrad_t<16, 16, 1, 1>(s, g, groups, x, dy, partials); break;
+        case 3216: launch_wgrad_t<32, 16, 1, 1>(s, g, groups, x, dy, partials); break;
+        case 6416: launch_wgrad_t<64, 16, 1, 1>(s, g, groups, x, dy, partials); break;
+        case 3232: launch_wgrad_t<32, 32, 1, 1>(s, g, groups, x, dy, partials); break;
+        case 6432: launch_wgrad_t<64, 32, 1, 2>(s, g, groups, x, dy, partials); break;
+        default:   launch_wgrad_t<64, 64, 2, 2>(s, g, groups, x, dy, partials); break;
+    }
+    int n_parts = groups * wgrad_wp(cs);
+    int n = cs.c_out * 9 * cs.c_in_real;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partials, n_parts, cs.c_out * 9,
+                       cs.c_in, cs.c_in_real, dw);
+}

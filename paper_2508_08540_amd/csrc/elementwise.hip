@@ -1,0 +1,77 @@
+// Small memory-bound kernels around the contractions: batch gather, SGD update, column sums.
+#include "kernels.h"
+
+__global__ __launch_bounds__(256) void gather_images_kernel(const float* __restrict__ src, const int32_t* __restrict__ y_src,
+                                                            const int32_t* __restrict__ sel, int64_t k, int64_t start,
+                                                            int64_t first, int batch, int pixels, int c_src, int c_dst,
+                                                            float* __restrict__ dst, int32_t* __restrict__ y_dst) {
+    int b = blockIdx.y;
+    int64_t img = sel ? (int64_t)sel[(start + b) % k] : first + b;
+    const float* s = src + img * pixels * c_src;
+    float* d = dst + (int64_t)b * pixels * c_dst;
+    int total = pixels * c_dst;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        int p = i / c_dst, c = i - p * c_dst;
+        d[i] = c < c_src ? s[p * c_src + c] : 0.f;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && y_dst) y_dst[b] = y_src[img];
+}
+
+void launch_gather_images(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
+                          int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, float* dst,
+                          int32_t* y_dst) {
+    int total = pixels * c_dst;
+    int bx = (total + 255) / 256;
+    if (bx > 16) bx = 16;
+    hipLaunchKernelGGL(gather_images_kernel, dim3(bx, batch), dim3(256), 0, s, src, y_src, sel, k, start, first, batch,
+                       pixels, c_src, c_dst, dst, y_dst);
+}
+
+void launch_gather_rows(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
+                        int64_t start, int batch, int64_t row, float* dst, int32_t* y_dst) {
+    launch_gather_images(s, src, y_src, sel, k, start, 0, batch, 1, (int)row, (int)row, dst, y_dst);
+}
+
+// SGD with momentum and coupled weight decay: g += wd*x; buf = mu*buf + g; x -= lr*buf.
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ params, float* __restrict__ momentum,
+                                                  const float* __restrict__ grad, int64_t d, float lr, float mu, float wd) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < d; i += stride) {
+        float x = params[i];
+        float g = __fmaf_rn(wd, x, grad[i]);
+        float buf = __fmaf_rn(mu, momentum[i], g);
+        momentum[i] = buf;
+        params[i] = __fmaf_rn(-lr, buf, x);
+    }
+}
+
+void launch_sgd(hipStream_t s, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
+                float wd) {
+    int64_t blocks = (d + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)blocks), dim3(256), 0, s, params, momentum, grad, d, lr, mu, wd);
+}
+
+__global__ __launch_bounds__(256) void colsum_kernel(const float* __restrict__ in, int rows, int cols, float* __restrict__ out) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= cols) return;
+    float acc = 0.f;
+    for (int b = 0; b < rows; ++b) acc += in[(int64_t)b * cols + n];
+    out[n] = acc;
+}
+
+void launch_colsum(hipStream_t s, const float* in, int rows, int cols, float* out) {
+    hipLaunchKernelGGL(colsum_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, in, rows, cols, out);
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* p, int64_t n) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+}
+
+void launch_fill_zero(hipStream_t s, float* p, int64_t n) {
+    if (n <= 0) return;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, n);
+}

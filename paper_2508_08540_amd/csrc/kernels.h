@@ -1,0 +1,78 @@
+// Launchers of the network kernels.  Every function enqueues on `s` and returns nothing; argument
+// shapes are validated by the callers in net.hip before any launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---- elementwise.hip ----------------------------------------------------------------------------
+// dst[b][0..row) = src[idx[(start + b) % k]][0..row_src) zero-padded to `row` floats per `group`:
+// each source row is `row_src/group_src`... see gather_rows for the image variant.
+void launch_gather_rows(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
+                        int64_t start, int batch, int64_t row, float* dst, int32_t* y_dst);
+// Images [n][pixels][c_src] -> [batch][pixels][c_dst] with zero-filled extra channels; sel == nullptr copies
+// images first .. first+batch-1, otherwise image b is sel[(start + b) % k].
+void launch_gather_images(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
+                          int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, float* dst,
+                          int32_t* y_dst);
+void launch_sgd(hipStream_t s, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
+                float wd);
+// out[n] = sum_b in[b][n]
+void launch_colsum(hipStream_t s, const float* in, int rows, int cols, float* out);
+void launch_fill_zero(hipStream_t s, float* p, int64_t n);
+
+// ---- gemm.hip ---------------------------------------------------------------------------------------
+// C[m][n] = sum_k A(m,k) * B(n,k); A(m,k) = a_kmajor ? A[k*lda+m] : A[m*lda+k], likewise B.
+// Split over `splits` K-ranges into part[splits][M][N], then reduced in split order into out with
+// optional bias[n] add, ReLU, and multiplication by (mask[m][n] > 0).
+size_t gemm_partial_floats(int M, int N, int splits);
+void launch_gemm(hipStream_t s, const float* A, int lda, bool a_kmajor, const float* B, int ldb, bool b_kmajor, int M,
+                 int N, int K, int splits, float* part, float* out, const float* bias, bool relu, const float* mask);
+
+// ---- head.hip ---------------------------------------------------------------------------------------
+// One wave per sample: feature = mean over `positions` of act[b][p][F]; logits = W feature + bias;
+// loss = softmax cross-entropy.  Training outputs (all optional, nullptr to skip): feat [B][F],
+// dlogits [B][C] scaled by grad_scale, dact [B][F] = (W^T dlogits) / positions, masked by feature > 0
+// when relu_mask is set.
+void launch_head_forward(hipStream_t s, const float* act, int B, int positions, int F, const float* W, const float* bias,
+                         int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
+                         float grad_scale, bool relu_mask);
+// dW[c][f] = sum_b dlogits[b][c] feat[b][f]; db[c] = sum_b dlogits[b][c]
+void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db);
+
+// ---- norm.hip ---------------------------------------------------------------------------------------
+// Per-channel statistics from per-tile partial sums (sum, sum of squares), in double.
+void launch_bn_finalize(hipStream_t s, const float* partials, int n_partials, int C, int64_t count, float* mean,
+                        float* invstd, float* running_mean, float* running_var);
+// mean/invstd from running statistics (inference mode)
+void launch_bn_eval_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean,
+                          float* invstd);
+// a = relu(gamma * (y - mean) * invstd + beta [+ shortcut(res)]); res has c_res channels at res_stride x resolution
+void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const float* mean, const float* invstd,
+                     const float* gamma, const float* beta, const float* res, int c_res, int res_stride, int h_out,
+                     float* out);
+// Backward of relu(bn(y) [+ shortcut]): g = dout * (out > 0); writes per-block partial sums of g and g*xhat.
+int bn_bwd_partials(int64_t pixels);
+void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+                          int64_t pixels, int C, const float* mean, const float* invstd, float* partials);
+// Sums the partials, writes dgamma, dbeta, and dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M); g_out optional.
+void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+                         int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
+                         const float* partials, int n_partials, float* dgamma, float* dbeta, float* dy, float* g_out);
+// dx[n][h][w][c] += shortcut_backward(g): identity or stride-2 zero-padded-channel shortcut
+void launch_shortcut_grad_add(hipStream_t s, float* dx, int B, int h_in, int c_in, const float* g, int c_out, int stride);
+
+// ---- conv.hip ---------------------------------------------------------------------------------------
+struct ConvShape {
+    int B, h_in, c_in, c_out, stride;  // square maps; 3x3, padding 1; c_in, c_out in {16, 32, 64}
+    int c_in_real;                     // weights hold this many input channels (<= c_in); the rest are zero
+};
+int conv_fwd_tiles(const ConvShape& cs);
+// y = conv(x, w); stats_partials (optional) receives per-tile per-channel (sum, sum of squares) of y.
+void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, float* stats_partials);
+// dx = conv_transpose(dy, w)
+void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx);
+int conv_wgrad_partials(const ConvShape& cs);
+// dw[c_out][3][3][c_in_real] = sum over pixels of dy * shifted x, via partials [n][c_out*9*c_in] reduced in order
+void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials, float* dw);

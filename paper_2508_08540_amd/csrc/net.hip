@@ -1,10 +1,266 @@
+// Network passes: scoring (inference-mode forward + per-sample loss) and the local SGD steps
+// (train-mode forward, backward, update) for the MLP and the CIFAR residual network.
 #include "net.h"
 
-int net_score(bls_ctx* ctx, const bls_model*, const float*, const float*, const float*, const int32_t*, int64_t, float*) {
-    return bls_fail(ctx, BLS_EUNSUPPORTED, "score_losses is not built yet");
+#include "kernels.h"
+
+namespace {
+
+constexpr int PAD_C = 16;       // the stem's input is zero-padded to 16 channels so it runs on the same kernels
+constexpr int SCORE_CHUNK = 512;
+constexpr int MLP_SPLITS = 8;
+
+int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
+
+ConvShape shape_of(const ConvBn& l, int B) {
+    ConvShape cs;
+    cs.B = B; cs.h_in = l.h_in; cs.c_out = l.c_out; cs.stride = l.stride;
+    cs.c_in = l.c_in < PAD_C ? PAD_C : l.c_in;
+    cs.c_in_real = l.c_in;
+    return cs;
 }
-int net_local_step(bls_ctx* ctx, const bls_model*, float*, float*, float*, const float*, const int32_t*, int64_t,
-                   const int32_t*, int64_t, int64_t, int64_t, const bls_sgd&, float*) {
-    return bls_fail(ctx, BLS_EUNSUPPORTED, "local_step is not built yet");
+
+int64_t out_floats(const ConvBn& l, int B) { return (int64_t)B * l.h_out * l.h_out * l.c_out; }
+
+// ---- MLP ----------------------------------------------------------------------------------------
+
+struct MlpScratch {
+    float *xb, *h, *part, *loss, *dlogits, *dpre, *grad;
+    int32_t* yb;
+};
+
+MlpScratch carve_mlp(Carver& c, const bls_model* m, int B, bool train) {
+    MlpScratch s{};
+    const int hid = m->desc.hidden;
+    s.h = c.take<float>((size_t)B * hid);
+    s.part = c.take<float>(max64(gemm_partial_floats(B, hid, MLP_SPLITS), train ? gemm_partial_floats(hid, m->d_in, 1) : 0));
+    s.loss = c.take<float>(B);
+    if (train) {
+        s.xb = c.take<float>((size_t)B * m->d_in);
+        s.yb = c.take<int32_t>(B);
+        s.dlogits = c.take<float>((size_t)B * m->desc.classes);
+        s.dpre = c.take<float>((size_t)B * hid);
+        s.grad = c.take<float>(m->num_params);
+    }
+    return s;
 }
+
+void mlp_hidden(hipStream_t st, const bls_model* m, const float* params, const float* x, int B, const MlpScratch& s) {
+    launch_gemm(st, x, m->d_in, false, params + m->fc1_w, m->d_in, false, B, m->desc.hidden, m->d_in, MLP_SPLITS, s.part,
+                s.h, params + m->fc1_b, true, nullptr);
+}
+
+// ---- residual network ---------------------------------------------------------------------------------
+
+struct ResScratch {
+    float* xpad;
+    int32_t* yb;
+    std::vector<float*> y, a, mean, invstd;  // per layer
+    float *stats, *d1, *d2, *g, *bnpart, *wpart, *grad;
+    float *loss, *feat, *dlogits, *dfeat;
+};
+
+ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
+    ResScratch s{};
+    const int L = (int)m->layers.size();
+    const int hw = m->desc.image_hw;
+    s.xpad = c.take<float>((size_t)B * hw * hw * PAD_C);
+    s.yb = c.take<int32_t>(B);
+    s.loss = c.take<float>(B);
+    s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L);
+    int64_t max_act = 0, max_stats = 0, max_wpart = 0;
+    for (int l = 0; l < L; ++l) {
+        const ConvBn& cb = m->layers[l];
+        ConvShape cs = shape_of(cb, B);
+        max_act = max64(max_act, out_floats(cb, B));
+        max_stats = max64(max_stats, (int64_t)conv_fwd_tiles(cs) * 2 * cb.c_out);
+        max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);
+        s.mean[l] = c.take<float>(cb.c_out);
+        s.invstd[l] = c.take<float>(cb.c_out);
+    }
+    if (train) {
+        for (int l = 0; l < L; ++l) {
+            s.y[l] = c.take<float>(out_floats(m->layers[l], B));
+            s.a[l] = c.take<float>(out_floats(m->layers[l], B));
+        }
+        s.stats = c.take<float>(max_stats);
+        s.d1 = c.take<float>(max_act);
+        s.d2 = c.take<float>(max_act);
+        s.g = c.take<float>(max_act);
+        s.bnpart = c.take<float>((size_t)1024 * 2 * 64);
+        s.wpart = c.take<float>(max_wpart);
+        s.grad = c.take<float>(m->num_params);
+        s.feat = c.take<float>((size_t)B * m->final_c);
+        s.dlogits = c.take<float>((size_t)B * m->desc.classes);
+        s.dfeat = c.take<float>((size_t)B * m->final_c);
+    } else {
+        // inference keeps no activations: four rotating buffers are enough
+        float* pool[4];
+        for (float*& p : pool) p = c.take<float>(max_act);
+        for (int l = 0; l < L; ++l) {
+            // layer l writes y into pool[(2l) % 4 .. ]: see resnet_forward for the rotation
+            s.y[l] = nullptr;
+            s.a[l] = nullptr;
+        }
+        s.d1 = pool[0]; s.d2 = pool[1]; s.g = pool[2]; s.stats = pool[3];
+    }
+    return s;
+}
+
+// Forward pass over a batch already gathered into s.xpad.  Train mode keeps every layer's
+// convolution output and activation for the backward pass and updates the running statistics.
+// Returns the final activation.
+const float* resnet_forward(hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, ResScratch& s,
+                            bool train) {
+    const int L = (int)m->layers.size();
+    float* rot[4] = {s.d1, s.d2, s.g, s.stats};  // inference-only rotation
+    int next = 0;
+    auto take = [&](const float* keep0, const float* keep1) {
+        for (;;) {
+            float* p = rot[next];
+            next = (next + 1) & 3;
+            if (p != keep0 && p != keep1) return p;
+        }
+    };
+    const float* block_in = nullptr;
+    const float* cur = s.xpad;
+    for (int l = 0; l < L; ++l) {
+        const ConvBn& cb = m->layers[l];
+        ConvShape cs = shape_of(cb, B);
+        const bool is_conv2 = l > 0 && (l % 2 == 0);
+        if (l > 0 && !is_conv2) block_in = cur;
+        float* y = train ? s.y[l] : take(cur, block_in);
+        launch_conv_fwd(st, cs, cur, params + cb.w_off, y, train ? s.stats : nullptr);
+        const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
+        if (train)
+            launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
+                               buffers + cb.rmean_off, buffers + cb.rvar_off);
+        else
+            launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]);
+        float* a = train ? s.a[l] : take(y, block_in);
+        const float* res = nullptr;
+        int c_res = cb.c_out, res_stride = 1;
+        if (is_conv2) {
+            const ConvBn& c1 = m->layers[l - 1];
+            res = block_in;
+            c_res = c1.c_in;
+            res_stride = c1.stride;
+        }
+        launch_bn_apply(st, y, pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off, params + cb.beta_off, res,
+                        c_res, res_stride, cb.h_out, a);
+        cur = a;
+    }
+    return cur;
+}
+
+void resnet_backward(hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s) {
+    const int L = (int)m->layers.size();
+    const ConvBn& last = m->layers[L - 1];
+    const float* dout = s.dfeat;
+    int shared = last.h_out * last.h_out;
+    for (int l = L - 1; l >= 0; --l) {
+        const ConvBn& cb = m->layers[l];
+        ConvShape cs = shape_of(cb, B);
+        const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
+        const bool is_conv2 = l > 0 && (l % 2 == 0);
+        const float* x_in = l == 0 ? s.xpad : s.a[l - 1];
+        launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], s.bnpart);
+        launch_bn_bwd_apply(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
+                            s.bnpart, bn_bwd_partials(pixels), s.grad + cb.gamma_off, s.grad + cb.beta_off, s.d1,
+                            is_conv2 ? s.g : nullptr);
+        launch_conv_wgrad(st, cs, x_in, s.d1, s.wpart, s.grad + cb.w_off);
+        if (l == 0) break;
+        launch_conv_dgrad(st, cs, s.d1, params + cb.w_off, s.d2);
+        if (!is_conv2) {
+            // conv1 of a block: add the gradient that bypassed the block through the shortcut
+            const ConvBn& c2 = m->layers[l + 1];
+            launch_shortcut_grad_add(st, s.d2, B, cb.h_in, cb.c_in, s.g, c2.c_out, cb.stride);
+        }
+        dout = s.d2;
+        shared = 0;
+    }
+}
+
+size_t scratch_bytes(const bls_model* m, int B, bool train) {
+    Carver c(nullptr);
+    if (m->desc.kind == BLS_MODEL_MLP) carve_mlp(c, m, B, train);
+    else carve_resnet(c, m, B, train);
+    return c.off;
+}
+
+}  // namespace
+
+int net_score(bls_ctx* ctx, const bls_model* m, const float* params, const float* buffers, const float* x,
+              const int32_t* y, int64_t N, float* losses_out) {
+    const int chunk = (int)(N < SCORE_CHUNK ? N : SCORE_CHUNK);
+    int rc = bls_arena_reserve(ctx, scratch_bytes(m, chunk, false));
+    if (rc != BLS_OK) return rc;
+    hipStream_t st = ctx->stream;
+    Carver c(ctx->arena);
+    if (m->desc.kind == BLS_MODEL_MLP) {
+        MlpScratch s = carve_mlp(c, m, chunk, false);
+        for (int64_t first = 0; first < N; first += chunk) {
+            int B = (int)(N - first < chunk ? N - first : chunk);
+            mlp_hidden(st, m, params, x + first * m->d_in, B, s);
+            launch_head_forward(st, s.h, B, 1, m->desc.hidden, params + m->fc2_w, params + m->fc2_b, m->desc.classes,
+                                y + first, losses_out + first, nullptr, nullptr, nullptr, 0.f, false);
+        }
+    } else {
+        ResScratch s = carve_resnet(c, m, chunk, false);
+        const int hw = m->desc.image_hw;
+        for (int64_t first = 0; first < N; first += chunk) {
+            int B = (int)(N - first < chunk ? N - first : chunk);
+            launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb);
+            const float* fin = resnet_forward(st, m, params, const_cast<float*>(buffers), B, s, false);
+            launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
+                                m->desc.classes, s.yb, losses_out + first, nullptr, nullptr, nullptr, 0.f, false);
+        }
+    }
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}
+
+int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffers, float* momentum, const float* x_pool,
+                   const int32_t* y_pool, int64_t N, const int32_t* sel, int64_t k, int64_t batch, int64_t tau,
+                   const bls_sgd& opt, float* step_losses_out) {
+    (void)N;
+    const int B = (int)batch;
+    int rc = bls_arena_reserve(ctx, scratch_bytes(m, B, true));
+    if (rc != BLS_OK) return rc;
+    hipStream_t st = ctx->stream;
+    Carver c(ctx->arena);
+    const float inv_b = 1.f / (float)B;
+    if (m->desc.kind == BLS_MODEL_MLP) {
+        MlpScratch s = carve_mlp(c, m, B, true);
+        const int hid = m->desc.hidden, C = m->desc.classes;
+        for (int64_t j = 0; j < tau; ++j) {
+            float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
+            launch_gather_rows(st, x_pool, y_pool, sel, k, j * B, B, m->d_in, s.xb, s.yb);
+            mlp_hidden(st, m, params, s.xb, B, s);
+            launch_head_forward(st, s.h, B, 1, hid, params + m->fc2_w, params + m->fc2_b, C, s.yb, loss, nullptr, s.dlogits,
+                                s.dpre, inv_b, true);
+            launch_head_wgrad(st, s.dlogits, s.h, B, C, hid, s.grad + m->fc2_w, s.grad + m->fc2_b);
+            launch_gemm(st, s.dpre, hid, true, s.xb, m->d_in, true, hid, m->d_in, B, 1, s.part, s.grad + m->fc1_w, nullptr,
+                        false, nullptr);
+            launch_colsum(st, s.dpre, B, hid, s.grad + m->fc1_b);
+            launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay);
+        }
+    } else {
+        ResScratch s = carve_resnet(c, m, B, true);
+        const int hw = m->desc.image_hw, C = m->desc.classes;
+        for (int64_t j = 0; j < tau; ++j) {
+            float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
+            launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb);
+            const float* fin = resnet_forward(st, m, params, buffers, B, s, true);
+            launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
+                                loss, s.feat, s.dlogits, s.dfeat, inv_b, false);
+            launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b);
+            resnet_backward(st, m, params, B, s);
+            launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay);
+        }
+    }
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}
+
 void net_release(bls_ctx*) {}

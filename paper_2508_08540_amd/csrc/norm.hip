@@ -1,0 +1,256 @@
+// Batch normalisation around the convolutions: statistics finalisation, normalise + ReLU (+ shortcut),
+// and the backward pass (two reductions and one elementwise pass).  Activations are [pixels][C] with
+// C a multiple of 16, so every thread works on 4 consecutive channels with 16-byte accesses.
+#include "kernels.h"
+
+#define BN_EPS 1e-5
+#define BN_MOMENTUM 0.1
+
+// partials: [n_partials][2][C] = per-tile (sum, sum of squares)
+__global__ __launch_bounds__(64) void bn_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
+                                                         double count, float* __restrict__ mean, float* __restrict__ invstd,
+                                                         float* __restrict__ running_mean, float* __restrict__ running_var) {
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double s = 0.0, ss = 0.0;
+    for (int i = 0; i < n_partials; ++i) {
+        s += (double)partials[((int64_t)i * 2) * C + c];
+        ss += (double)partials[((int64_t)i * 2 + 1) * C + c];
+    }
+    double mu = s / count;
+    double var = ss / count - mu * mu;
+    if (var < 0.0) var = 0.0;
+    mean[c] = (float)mu;
+    invstd[c] = (float)(1.0 / sqrt(var + BN_EPS));
+    double unbiased = count > 1.0 ? var * count / (count - 1.0) : var;
+    running_mean[c] = (float)((1.0 - BN_MOMENTUM) * (double)running_mean[c] + BN_MOMENTUM * mu);
+    running_var[c] = (float)((1.0 - BN_MOMENTUM) * (double)running_var[c] + BN_MOMENTUM * unbiased);
+}
+
+void launch_bn_finalize(hipStream_t s, const float* partials, int n_partials, int C, int64_t count, float* mean,
+                        float* invstd, float* running_mean, float* running_var) {
+    hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 63) / 64), dim3(64), 0, s, partials, n_partials, C, (double)count,
+                       mean, invstd, running_mean, running_var);
+}
+
+__global__ __launch_bounds__(64) void bn_eval_stats_kernel(const float* __restrict__ running_mean,
+                                                           const float* __restrict__ running_var, int C,
+                                                           float* __restrict__ mean, float* __restrict__ invstd) {
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    mean[c] = running_mean[c];
+    invstd[c] = (float)(1.0 / sqrt((double)running_var[c] + BN_EPS));
+}
+
+void launch_bn_eval_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean,
+                          float* invstd) {
+    hipLaunchKernelGGL(bn_eval_stats_kernel, dim3((C + 63) / 64), dim3(64), 0, s, running_mean, running_var, C, mean, invstd);
+}
+
+// out = relu(gamma*(y-mean)*invstd + beta + shortcut(res))
+__global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__ y, int64_t pixels, int C,
+                                                       const float* __restrict__ mean, const float* __restrict__ invstd,
+                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                       const float* __restrict__ res, int c_res, int res_stride, int h_out,
+                                                       float* __restrict__ out) {
+    const int cq = C >> 2;
+    int64_t total = pixels * cq;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int lo = (C - c_res) >> 1;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        int64_t p = i / cq;
+        int c = (int)(i - p * cq) << 2;
+        f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
+        f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
+        f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
+        f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
+        f32x4 be = *reinterpret_cast<const f32x4*>(beta + c);
+        f32x4 r = {0.f, 0.f, 0.f, 0.f};
+        if (res && c >= lo && c < lo + c_res) {
+            int64_t rp = p;
+            if (res_stride != 1) {
+                int hw = h_out * h_out;
+                int64_t n = p / hw;
+                int q = (int)(p - n * hw);
+                int h = q / h_out, w = q - h * h_out;
+                int h_in = h_out * res_stride;
+                rp = (n * h_in + (int64_t)h * res_stride) * h_in + (int64_t)w * res_stride;
+            }
+            r = *reinterpret_cast<const f32x4*>(res + rp * c_res + (c - lo));
+        }
+        f32x4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float t = __fmaf_rn((v[j] - mu[j]) * is[j], ga[j], be[j]) + r[j];
+            o[j] = fmaxf(t, 0.f);
+        }
+        *reinterpret_cast<f32x4*>(out + p * C + c) = o;
+    }
+}
+
+void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const float* mean, const float* invstd,
+                     const float* gamma, const float* beta, const float* res, int c_res, int res_stride, int h_out,
+                     float* out) {
+    int64_t total = pixels * (C / 4);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(bn_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, y, pixels, C, mean, invstd, gamma, beta,
+                       res, c_res, res_stride, h_out, out);
+}
+
+// ---- backward -------------------------------------------------------------------------------------
+
+int bn_bwd_partials(int64_t pixels) {
+    int64_t n = pixels / 128;
+    if (n < 1) n = 1;
+    if (n > 1024) n = 1024;
+    return (int)n;
+}
+
+// Upstream gradient of pixel p, channels c..c+3: either a full tensor or one vector per sample
+// shared by all `shared` positions of that sample (gradient of a global average pool).
+__device__ __forceinline__ f32x4 load_dout(const float* __restrict__ dout, int shared, int64_t p, int C, int c) {
+    int64_t row = shared ? p / shared : p;
+    return *reinterpret_cast<const f32x4*>(dout + row * C + c);
+}
+
+// partials: [n_blocks][2][C] = (sum g, sum g*xhat), g = dout * (out > 0)
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const float* __restrict__ dout, int shared,
+                                                            const float* __restrict__ out, const float* __restrict__ y,
+                                                            int64_t pixels, int C, const float* __restrict__ mean,
+                                                            const float* __restrict__ invstd, float* __restrict__ partials) {
+    __shared__ float red[2][256][4];
+    const int cq = C >> 2;              // threads per pixel
+    const int lanes_p = 256 / cq;       // pixels in flight per block
+    const int cg = threadIdx.x % cq, pl = threadIdx.x / cq;
+    const int c = cg << 2;
+    int64_t chunk = (pixels + gridDim.x - 1) / gridDim.x;
+    int64_t p0 = (int64_t)blockIdx.x * chunk, p1 = p0 + chunk < pixels ? p0 + chunk : pixels;
+    f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
+    f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
+    f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sgx = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t p = p0 + pl; p < p1; p += lanes_p) {
+        f32x4 d = load_dout(dout, shared, p, C, c);
+        f32x4 o = *reinterpret_cast<const f32x4*>(out + p * C + c);
+        f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float g = o[j] > 0.f ? d[j] : 0.f;
+            sg[j] += g;
+            sgx[j] = __fmaf_rn(g, (v[j] - mu[j]) * is[j], sgx[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        red[0][threadIdx.x][j] = sg[j];
+        red[1][threadIdx.x][j] = sgx[j];
+    }
+    __syncthreads();
+    // thread t < 2*C sums column (which, channel) over the pixel lanes in a fixed order
+    if (threadIdx.x < 2 * C) {
+        int which = threadIdx.x / C, ch = threadIdx.x % C;
+        float acc = 0.f;
+        for (int l = 0; l < lanes_p; ++l) acc += red[which][l * cq + (ch >> 2)][ch & 3];
+        partials[((int64_t)blockIdx.x * 2 + which) * C + ch] = acc;
+    }
+}
+
+void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+                          int64_t pixels, int C, const float* mean, const float* invstd, float* partials) {
+    int n = bn_bwd_partials(pixels);
+    hipLaunchKernelGGL(bn_bwd_reduce_kernel, dim3(n), dim3(256), 0, s, dout, dout_positions_shared, out, y, pixels, C,
+                       mean, invstd, partials);
+}
+
+__global__ __launch_bounds__(64) void bn_bwd_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
+                                                             float* __restrict__ dgamma, float* __restrict__ dbeta) {
+    int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double sg = 0.0, sgx = 0.0;
+    for (int i = 0; i < n_partials; ++i) {
+        sg += (double)partials[((int64_t)i * 2) * C + c];
+        sgx += (double)partials[((int64_t)i * 2 + 1) * C + c];
+    }
+    dbeta[c] = (float)sg;
+    dgamma[c] = (float)sgx;
+}
+
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restrict__ dout, int shared,
+                                                           const float* __restrict__ out, const float* __restrict__ y,
+                                                           int64_t pixels, int C, const float* __restrict__ mean,
+                                                           const float* __restrict__ invstd, const float* __restrict__ gamma,
+                                                           const float* __restrict__ dgamma, const float* __restrict__ dbeta,
+                                                           float inv_count, float* __restrict__ dy, float* __restrict__ g_out) {
+    const int cq = C >> 2;
+    int64_t total = pixels * cq;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        int64_t p = i / cq;
+        int c = (int)(i - p * cq) << 2;
+        f32x4 d = load_dout(dout, shared, p, C, c);
+        f32x4 o = *reinterpret_cast<const f32x4*>(out + p * C + c);
+        f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
+        f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
+        f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
+        f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
+        f32x4 dg = *reinterpret_cast<const f32x4*>(dgamma + c);
+        f32x4 db = *reinterpret_cast<const f32x4*>(dbeta + c);
+        f32x4 r, gq;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float g = o[j] > 0.f ? d[j] : 0.f;
+            float xhat = (v[j] - mu[j]) * is[j];
+            gq[j] = g;
+            r[j] = ga[j] * is[j] * (g - db[j] * inv_count - xhat * (dg[j] * inv_count));
+        }
+        *reinterpret_cast<f32x4*>(dy + p * C + c) = r;
+        if (g_out) *reinterpret_cast<f32x4*>(g_out + p * C + c) = gq;
+    }
+}
+
+void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+                         int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
+                         const float* partials, int n_partials, float* dgamma, float* dbeta, float* dy, float* g_out) {
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 63) / 64), dim3(64), 0, s, partials, n_partials, C, dgamma, dbeta);
+    int64_t total = pixels * (C / 4);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dout, dout_positions_shared, out, y,
+                       pixels, C, mean, invstd, gamma, dgamma, dbeta, 1.f / (float)pixels, dy, g_out);
+}
+
+// dx += shortcut_backward(g): identity (stride 1, equal channels) or stride-2 zero-padded-channel shortcut
+__global__ __launch_bounds__(256) void shortcut_grad_add_kernel(float* __restrict__ dx, int64_t pixels_in, int h_in, int c_in,
+                                                                const float* __restrict__ g, int c_out, int stride) {
+    const int cq = c_in >> 2;
+    const int lo = (c_out - c_in) >> 1;
+    const int h_out = h_in / stride;
+    int64_t total = pixels_in * cq;
+    int64_t gstride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gstride) {
+        int64_t p = i / cq;
+        int c = (int)(i - p * cq) << 2;
+        int64_t gp = p;
+        if (stride != 1) {
+            int hw = h_in * h_in;
+            int64_t n = p / hw;
+            int q = (int)(p - n * hw);
+            int h = q / h_in, w = q - h * h_in;
+            if ((h % stride) | (w % stride)) continue;
+            gp = (n * h_out + h / stride) * h_out + w / stride;
+        }
+        f32x4 a = *reinterpret_cast<f32x4*>(dx + p * c_in + c);
+        f32x4 b = *reinterpret_cast<const f32x4*>(g + gp * c_out + lo + c);
+        a += b;
+        *reinterpret_cast<f32x4*>(dx + p * c_in + c) = a;
+    }
+}
+
+void launch_shortcut_grad_add(hipStream_t s, float* dx, int B, int h_in, int c_in, const float* g, int c_out, int stride) {
+    int64_t pixels_in = (int64_t)B * h_in * h_in;
+    int64_t total = pixels_in * (c_in / 4);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(shortcut_grad_add_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dx, pixels_in, h_in, c_in, g,
+                       c_out, stride);
+}

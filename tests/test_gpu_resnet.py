@@ -1,0 +1,100 @@
+"""GPU parity of score_losses / local_step for the CIFAR residual network against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_helpers import Harness, assert_losses_close, assert_tensors_close
+
+pytestmark = pytest.mark.gpu
+CFG = synth.workload("resnet20_fp32")
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    yield torch, bls, ctx
+    ctx.close()
+
+
+def _harness(env, widths=(16, 32, 64), blocks=3, hw=32, classes=10):
+    torch, bls, ctx = env
+    return Harness(torch, bls, ctx, bls.Model.resnet_cifar(widths, blocks, classes, hw), oracle.ResNetCifar(widths, blocks))
+
+
+def _zeros(p):
+    return {k: np.zeros_like(v) for k, v in p.items()}
+
+
+def _grad_case(env, widths, blocks, hw, batch, classes=10, tol=1e-4):
+    h = _harness(env, widths, blocks, hw, classes)
+    p, b = synth.resnet_init(CFG["id"], widths, blocks, classes, perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], batch + 5, classes, hw=hw)
+    sel = (np.arange(batch) * 3) % (batch + 5)
+    losses, grads, nb = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+    newp, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses)
+    assert_tensors_close(mom, grads, tol, "gradients")
+    assert_tensors_close(gb, nb, 1e-5, "running statistics")
+
+
+@pytest.mark.parametrize("widths,blocks,hw,batch", [
+    ((16, 32, 64), 1, 8, 4),      # tiles spanning several images, ragged last tile
+    ((16, 32, 64), 1, 16, 6),
+    ((16, 16, 32), 2, 16, 3),     # identity transition between stages 1 and 2 in channels
+    ((32, 32, 64), 1, 32, 2),
+    ((16, 64, 64), 1, 16, 5),     # 16 -> 64 shortcut
+    ((64, 64, 64), 1, 8, 9),
+])
+def test_gradients_small_nets(env, widths, blocks, hw, batch):
+    _grad_case(env, widths, blocks, hw, batch)
+
+
+def test_gradients_resnet20_one_batch(env):
+    _grad_case(env, (16, 32, 64), 3, 32, 16)
+
+
+def test_scores_resnet20(env):
+    h = _harness(env)
+    p, b = synth.resnet_init(CFG["id"], perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], 70, 10)
+    ref = oracle.score_losses(h.oracle_model, p, b, x, y)
+    assert_losses_close(h.score(p, b, x, y), ref)
+    assert_losses_close(h.score(p, b, x[:3], y[:3]), ref[:3])          # a score does not depend on the rest of the pool
+    p0, b0 = synth.resnet_init(CFG["id"])
+    p0["fc.weight"][:] = 0
+    p0["fc.bias"][:] = 0
+    np.testing.assert_allclose(h.score(p0, b0, x[:9], y[:9]), np.log(10.0), rtol=1e-6)
+
+
+def test_steps_teacher_forced_and_free_running(env):
+    h = _harness(env, (16, 32, 64), 1, 16)
+    widths, blocks, hw = (16, 32, 64), 1, 16
+    p, b = synth.resnet_init(CFG["id"], widths, blocks, 10, perturb_bn=0.1)
+    x, y = synth.image_pool(CFG["id"], 40, 10, hw=hw)
+    sel = oracle.topk_by_loss(oracle.score_losses(h.oracle_model, p, b, x, y).astype(np.float32), 10)
+    B, tau, lr, mu, wd = 4, 3, 0.1, 0.9, 1e-4          # 3 * 4 > 10: the batches wrap around the selection
+    # free-running: tau steps on both sides from the same start
+    rp, rb, rm, rl = oracle.local_step(h.oracle_model, p, b, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    gp, gb, gm, gl = h.local_step(p, b, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    assert_losses_close(gl, rl, rtol=1e-3)
+    assert_tensors_close(gb, rb, 1e-4, "running statistics")
+    assert_tensors_close(gm, rm, 2e-3, "momentum after tau steps (drift allowed)")
+    # teacher-forced: every step starts from the oracle's state, compared at the single-step tolerance
+    cp, cb, cm = p, b, _zeros(p)
+    for j in range(tau):
+        ids = np.roll(sel, -((j * B) % 10))
+        op, ob, om, ol = oracle.local_step(h.oracle_model, cp, cb, cm, x, y, ids, B, 1, lr, mu, wd)
+        gp, gb, gm, gl = h.local_step({k: v.astype(np.float32) for k, v in cp.items()},
+                                      {k: v.astype(np.float32) for k, v in cb.items()},
+                                      {k: v.astype(np.float32) for k, v in cm.items()}, x, y, ids, B, 1, lr, mu, wd)
+        o32 = lambda d: {k: v.astype(np.float32).astype(np.float64) for k, v in d.items()}
+        op2, ob2, om2, ol2 = oracle.local_step(h.oracle_model, o32(cp), o32(cb), o32(cm), x, y, ids, B, 1, lr, mu, wd)
+        assert_losses_close(gl, ol2)
+        assert_tensors_close(gm, om2, 1e-4, "momentum, step %d" % j)
+        assert_tensors_close(gb, ob2, 1e-5, "running statistics, step %d" % j)
+        delta = lambda a: {k: a[k] - o32(cp)[k] for k in cp}
+        assert_tensors_close(delta(gp), delta(op2), 2e-4, "parameter change, step %d" % j)
+        cp, cb, cm = op, ob, om
