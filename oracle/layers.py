@@ -85,9 +85,20 @@ def relu(x):
     return np.maximum(x, 0.0)
 
 
-def relu_backward(dy, y):
-    """ReLU'(0) = 0: the gradient passes only where the output is positive."""
-    return dy * (y > 0.0)
+def relu_backward(dy, y, toggle=None):
+    """ReLU'(0) = 0: the gradient passes only where the output is positive.
+
+    `toggle` (flat indices) inverts the pass/block decision of those units.  It exists for
+    comparisons with lower-precision implementations: where a pre-activation lies within rounding
+    error of zero the two sides may legitimately land on different sides of the kink, and both
+    one-sided derivatives are valid there.
+    """
+    mask = y > 0.0
+    if toggle is not None and len(toggle):
+        mask = mask.copy()
+        flat = mask.reshape(-1)
+        flat[np.asarray(toggle, dtype=np.int64)] ^= True
+    return dy * mask
 
 
 def shortcut(x, c_out, stride):

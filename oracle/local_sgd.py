@@ -31,6 +31,34 @@ def loss_and_grads(model, params, buffers, xb, yb):
     return losses, grads, new_bufs
 
 
+class GradientProbe:
+    """One training forward pass kept for repeated backward passes with different ReLU decisions.
+
+    near_zero_units(rel) lists the ReLU units whose pre-activation is within rel * rms of zero: there
+    an fp32 implementation may land on the other side of the kink, and either one-sided derivative
+    is a valid result.  grads(toggles) is the gradient with the listed units' decisions inverted.
+    """
+
+    def __init__(self, model, params, buffers, xb, yb):
+        logits, self.cache, self.new_buffers = model.forward(params, buffers, xb, train=True)
+        self.losses, dlogits = softmax_cross_entropy(logits, yb)
+        self.dlogits = dlogits / xb.shape[0]
+        self.model = model
+
+    def grads(self, toggles=None):
+        if toggles:
+            return self.model.backward(self.cache, self.dlogits, toggles)
+        return self.model.backward(self.cache, self.dlogits)
+
+    def near_zero_units(self, rel=1e-5):
+        out = []
+        for name, z in self.cache.get("z", {}).items():
+            rms = float(np.sqrt(np.mean(z * z)))
+            for i in np.flatnonzero(np.abs(z.reshape(-1)) <= rel * rms):
+                out.append((name, int(i)))
+        return out
+
+
 def local_step(model, params, buffers, momentum_bufs, x_pool, y_pool, sel, batch, tau,
                lr, momentum=0.0, weight_decay=0.0):
     """tau SGD updates; step j trains on sel[(j*batch + b) mod k], b = 0..batch-1.

@@ -62,20 +62,24 @@ class ResNetCifar:
         p, bufs = _f64(params), _f64(buffers)
         new_bufs = dict(bufs)
         x = np.asarray(x, dtype=np.float64)
-        cache = {"p": p, "x": x}
+        cache = {"p": p, "x": x, "z": {}}   # "z": pre-activation of every ReLU, keyed by the name of its output
         y0 = L.conv3x3(x, p["stem.conv.weight"], 1)
         z0, cache["stem.bn"] = self._bn("stem.bn", y0, p, bufs, new_bufs, train)
+        cache["z"]["stem.out"] = z0
         a = L.relu(z0)
         cache["stem.out"] = a
         for name, c_in, c_out, stride in self._block_list():
             cache[name + ".in"] = a
             y1 = L.conv3x3(a, p[name + ".conv1.weight"], stride)
             z1, cache[name + ".bn1"] = self._bn(name + ".bn1", y1, p, bufs, new_bufs, train)
+            cache["z"][name + ".h1"] = z1
             h1 = L.relu(z1)
             cache[name + ".h1"] = h1
             y2 = L.conv3x3(h1, p[name + ".conv2.weight"], 1)
             z2, cache[name + ".bn2"] = self._bn(name + ".bn2", y2, p, bufs, new_bufs, train)
-            a = L.relu(z2 + L.shortcut(a, c_out, stride))
+            zo = z2 + L.shortcut(a, c_out, stride)
+            cache["z"][name + ".out"] = zo
+            a = L.relu(zo)
             cache[name + ".out"] = a
         cache["final"] = a
         pooled = L.global_avgpool(a)
@@ -83,22 +87,25 @@ class ResNetCifar:
         logits = L.linear(pooled, p["fc.weight"], p["fc.bias"])
         return logits, cache, new_bufs
 
-    def backward(self, cache, dlogits):
-        """Gradients of sum_b <dlogits_b, logits_b> with respect to every parameter (train mode)."""
+    def backward(self, cache, dlogits, toggles=None):
+        """Gradients of sum_b <dlogits_b, logits_b> with respect to every parameter (train mode).
+
+        toggles: optional {relu output name: flat indices} passed to relu_backward."""
         p = cache["p"]
         g = {}
+        tg = toggles or {}
         dpooled, g["fc.weight"], g["fc.bias"] = L.linear_backward(cache["pooled"], p["fc.weight"], dlogits)
         da = L.global_avgpool_backward(dpooled, cache["final"].shape)
         for name, c_in, c_out, stride in reversed(self._block_list()):
-            dz = L.relu_backward(da, cache[name + ".out"])
+            dz = L.relu_backward(da, cache[name + ".out"], tg.get(name + ".out"))
             dy2, g[name + ".bn2.weight"], g[name + ".bn2.bias"] = L.batchnorm_train_backward(dz, cache[name + ".bn2"])
             dh1, g[name + ".conv2.weight"] = L.conv3x3_backward(cache[name + ".h1"], p[name + ".conv2.weight"], dy2, 1)
-            dz1 = L.relu_backward(dh1, cache[name + ".h1"])
+            dz1 = L.relu_backward(dh1, cache[name + ".h1"], tg.get(name + ".h1"))
             dy1, g[name + ".bn1.weight"], g[name + ".bn1.bias"] = L.batchnorm_train_backward(dz1, cache[name + ".bn1"])
             x_in = cache[name + ".in"]
             dx, g[name + ".conv1.weight"] = L.conv3x3_backward(x_in, p[name + ".conv1.weight"], dy1, stride)
             da = dx + L.shortcut_backward(dz, x_in.shape, stride)
-        dz0 = L.relu_backward(da, cache["stem.out"])
+        dz0 = L.relu_backward(da, cache["stem.out"], tg.get("stem.out"))
         dy0, g["stem.bn.weight"], g["stem.bn.bias"] = L.batchnorm_train_backward(dz0, cache["stem.bn"])
         _, g["stem.conv.weight"] = L.conv3x3_backward(cache["x"], p["stem.conv.weight"], dy0, 1, need_dx=False)
         return g

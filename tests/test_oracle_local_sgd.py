@@ -154,3 +154,28 @@ def test_batchnorm_buffers_follow_the_steps():
         y0 = L.conv3x3(x[ids], p["stem.conv.weight"], 1)
         rm = 0.9 * rm + 0.1 * y0.reshape(-1, 2).mean(axis=0)
     np.testing.assert_allclose(nb["stem.bn.running_mean"], rm, rtol=1e-12)
+
+
+def test_relu_toggle_is_the_other_one_sided_derivative():
+    # A unit whose pre-activation is exactly zero: the default takes derivative 0 (the left limit);
+    # toggling it gives derivative 1 (the right limit).  One-sided finite differences pin both.
+    from oracle import layers as L
+    z = np.array([[-1.0, 0.0, 2.0]])
+    r = np.array([[0.3, -0.7, 1.1]])
+    f = lambda zz: float((L.relu(zz) * r).sum())
+    eps = 1e-7
+    left = np.array([(f(z) - f(z - eps * np.eye(3)[i])) / eps for i in range(3)])
+    right = np.array([(f(z + eps * np.eye(3)[i]) - f(z)) / eps for i in range(3)])
+    np.testing.assert_allclose(L.relu_backward(r, L.relu(z))[0], left, atol=1e-6)
+    np.testing.assert_allclose(L.relu_backward(r, L.relu(z), toggle=[1])[0], right, atol=1e-6)
+    # probe: without toggles it is loss_and_grads; near-zero units are found where they are planted
+    model, p, b, x, y = _tiny_resnet()
+    probe = oracle.GradientProbe(model, p, b, x, y)
+    _, g, _ = oracle.loss_and_grads(model, p, b, x, y)
+    for k in g:
+        np.testing.assert_array_equal(probe.grads()[k], g[k])
+    assert probe.near_zero_units(1e-9) == []
+    units = probe.near_zero_units(0.05)
+    assert units and all(abs(probe.cache["z"][n].reshape(-1)[i]) <= 0.05 * np.sqrt(np.mean(probe.cache["z"][n] ** 2)) for n, i in units)
+    g2 = probe.grads({units[0][0]: [units[0][1]]})
+    assert any(np.abs(g2[k] - g[k]).max() > 0 for k in g)
