@@ -1,0 +1,173 @@
+"""Throughput of the fast-process local step on one MI355X.
+
+One "step" is one pass of the whole hot path on the ResNet20 fp32 workload: score the 512-image
+pool, select the 128 highest-loss samples, run 20 local SGD steps of batch 128 on them, and aggregate
+10 parameter replicas with step-count weights.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def resnet_conv_flops(widths, blocks, hw, in_ch):
+    """Algorithmic forward multiply-add flops (2 per MAC) of all 3x3 convolutions for one image."""
+    total, c_prev, h = 2 * 9 * in_ch * widths[0] * hw * hw, widths[0], hw
+    for s, c in enumerate(widths):
+        for b in range(blocks):
+            stride = 2 if (b == 0 and s > 0) else 1
+            h = h // stride
+            total += 2 * 9 * c_prev * c * h * h + 2 * 9 * c * c * h * h
+            c_prev = c
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the path has no multi-GPU part in this build (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    import synth
+    import paper_2508_08540_amd as bls
+
+    cfg = synth.workload("resnet20_fp32")
+    N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
+    model = bls.Model.resnet_cifar()
+    d = model.num_params
+    p, b = synth.resnet_init(cfg["id"])
+    x, y = synth.image_pool(cfg["id"], N, cfg["classes"])
+    flat = model.pack(p)
+    ctx = bls.Context(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    p0, b0 = dev(flat), dev(model.pack(b, buffers=True))
+    dp, db, dm = p0.clone(), b0.clone(), torch.zeros_like(p0)
+    dx, dy = dev(x), dev(y)
+    others = [dev(r) for r in synth.replicas(flat, P - 1, cfg["id"])]
+    w = bls.weights_from_tau(cfg["tau_workers"])
+    losses = torch.empty(N, dtype=torch.float32, device="cuda")
+    idx = torch.empty(k, dtype=torch.int32, device="cuda")
+    sl = torch.empty(tau * B, dtype=torch.float32, device="cuda")
+    agg = torch.empty_like(p0)
+
+    def one_step():
+        dp.copy_(p0); db.copy_(b0); dm.zero_()          # every step starts the round from the same global model
+        bls.score_losses(ctx, model, dp, db, dx, dy, losses)
+        bls.topk_by_loss(ctx, losses, k, idx)
+        bls.local_step(ctx, model, dp, db, dm, dx, dy, idx, B, tau, cfg["lr"], cfg["momentum"], cfg["weight_decay"], sl)
+        bls.weighted_aggregate(ctx, [dp] + others, w, agg)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = tau * B / (elapsed / args.steps)
+    finite = bool(torch.isfinite(agg).all().item() and torch.isfinite(sl).all().item())
+
+    # Same steps again with the library's per-class HIP-event timing switched on (on the stream the
+    # kernels run on), for the roofline of the dominant kernel class.
+    ctx.profile_begin()
+    for _ in range(args.steps):
+        one_step()
+    prof = ctx.profile_end()
+    phases = {name: round(ms / args.steps, 4) for name, (ms, cnt) in prof.items() if cnt}
+    conv_flops_img = resnet_conv_flops((16, 32, 64), 3, 32, 3)
+    # forward flops of one local step / one scoring pass; the input gradient skips the stem
+    stem_flops = 2 * 9 * 3 * 16 * 32 * 32
+    flops = {
+        "conv_fwd": conv_flops_img * (tau * B + N),
+        "conv_dgrad": (conv_flops_img - stem_flops) * tau * B,
+        "conv_wgrad": conv_flops_img * tau * B,
+    }
+    dom = max(("conv_fwd", "conv_dgrad", "conv_wgrad"), key=lambda c: prof[c][0])
+    dom_ms, dom_cnt = prof[dom]
+    achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2), "launches_per_step": dom_cnt // args.steps}
+
+    # Aggregation bandwidth on a vector large enough to leave the caches (WRN-16-8 sized, P = 10),
+    # rotating three buffer sets; algorithmic bytes = (P + 1) * d * 4.
+    d_big, sets = 11007540, 3
+    big = [[torch.randn(d_big, device="cuda") for _ in range(P)] for _ in range(sets)]
+    out_big = torch.empty(d_big, device="cuda")
+    for s in range(sets):
+        bls.weighted_aggregate(ctx, big[s], w, out_big)
+    torch.cuda.synchronize()
+    reps_n = 30
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps_n):
+        bls.weighted_aggregate(ctx, big[i % sets], w, out_big)
+    e1.record()
+    torch.cuda.synchronize()
+    agg_gbs = (P + 1) * d_big * 4 * reps_n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del big
+
+    line = {
+        "metric": "selected samples/s per local step (ResNet20)", "value": round(value, 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "resnet20_fp32", "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(d)},
+        "finite": finite, "phase_ms_per_step": phases, "roofline": roofline,
+        "aggregation": {"d": d_big, "P": P, "GB/s": round(agg_gbs, 1), "frac_hbm_peak": round(agg_gbs / HBM_PEAK_GBS, 4)},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, p, b, x, y)
+    print(json.dumps(line))
+
+
+def cpu_baseline(cfg, p, b, x, y):
+    """The oracle timed on the host cores on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    import synth
+    from threadpoolctl import threadpool_info
+    N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
+    m = oracle.ResNetCifar()
+    n_score = 64
+    t = time.perf_counter()
+    ls = oracle.score_losses(m, p, b, x[:n_score], y[:n_score])
+    t_score_img = (time.perf_counter() - t) / n_score
+    full = np.concatenate([ls, ls[::-1]] * (N // (2 * n_score))).astype(np.float32)
+    t = time.perf_counter()
+    sel = oracle.topk_by_loss(full, k)
+    t_topk = time.perf_counter() - t
+    zeros = {n: np.zeros_like(v) for n, v in p.items()}
+    t = time.perf_counter()
+    oracle.local_step(m, p, b, zeros, x, y, sel, B, 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+    t_step = time.perf_counter() - t
+    import paper_2508_08540_amd as bls
+    flat = bls.Model.resnet_cifar().pack(p)
+    reps = synth.replicas(flat, P, cfg["id"])
+    t = time.perf_counter()
+    oracle.weighted_aggregate(reps, synth.aggregation_weights(cfg))
+    t_agg = time.perf_counter() - t
+    total = N * t_score_img + t_topk + tau * t_step + t_agg
+    threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    return {"value": round(tau * B / total, 2), "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": "scored %d of %d pool images, full top-k, 1 of %d local steps at batch %d, full aggregation; "
+                      "per-part times scaled to the whole pass" % (n_score, N, tau, B),
+            "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

@@ -56,7 +56,7 @@ enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1 };
 typedef struct {
     int32_t kind;        /* BLS_MODEL_*                                    */
     int32_t classes;     /* 2 .. 64                                        */
-    int32_t image_hw;    /* square images; RESNET: multiple of 8, 8 .. 64  */
+    int32_t image_hw;    /* square images; RESNET: 8, 16, 32 or 64          */
     int32_t in_channels; /* RESNET: 1 .. 4                                 */
     int32_t hidden;      /* MLP only: multiple of 16, 16 .. 1024           */
     int32_t widths[3];   /* RESNET only: each of 16, 32 or 64              */
@@ -98,6 +98,17 @@ void bls_ctx_destroy(bls_ctx* ctx);
 const char* bls_last_error(const bls_ctx* ctx);
 /* Blocks until everything enqueued on the context's stream has finished. */
 int bls_ctx_synchronize(bls_ctx* ctx);
+
+/* Optional per-class kernel timing for benchmarks.  Between begin and end every group of launches
+ * is bracketed by HIP events on the context's stream (this slows the calls down; do not time
+ * throughput while it is on).  bls_profile_end waits for the stream, adds the elapsed time and the
+ * number of bracketed groups per class into the caller's host arrays (capacity entries each,
+ * either may be NULL) and returns the number of classes.  Class order: 0 conv forward, 1 conv input
+ * gradient, 2 conv weight gradient (kernel plus its partial-sum reduction), 3 batch norm and
+ * shortcut kernels, 4 classifier head, 5 fully connected GEMM, 6 SGD update, 7 batch gather,
+ * 8 top-k, 9 aggregation. */
+int bls_profile_begin(bls_ctx* ctx);
+int bls_profile_end(bls_ctx* ctx, double* ms_by_class, int64_t* launches_by_class, int capacity);
 
 /* ---- model description (host only; no GPU needed) ------------------------------------------- */
 

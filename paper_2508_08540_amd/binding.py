@@ -13,8 +13,10 @@ DECLARED_SYMBOLS = (
     "bls_ctx_create", "bls_ctx_destroy", "bls_last_error", "bls_ctx_synchronize", "bls_model_create",
     "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
-    "bls_weights_from_tau",
+    "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end",
 )
+PROFILE_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "norm", "head", "gemm", "update", "gather", "topk",
+                   "aggregate")
 
 
 class BlsError(RuntimeError):
@@ -67,6 +69,8 @@ def _load():
     L.local_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i64, C.POINTER(_Sgd), vp]
     L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
     L.bls_weights_from_tau.argtypes = [C.POINTER(i64), C.c_int, C.POINTER(C.c_float)]
+    L.bls_profile_begin.argtypes = [vp]
+    L.bls_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), C.c_int]
     return L
 
 
@@ -101,6 +105,18 @@ class Context:
 
     def synchronize(self):
         self.check(lib.bls_ctx_synchronize(self.handle))
+
+    def profile_begin(self):
+        self.check(lib.bls_profile_begin(self.handle))
+
+    def profile_end(self):
+        """{class: (milliseconds, bracketed launch groups)} since profile_begin."""
+        n = len(PROFILE_CLASSES)
+        ms, cnt = (C.c_double * n)(), (C.c_int64 * n)()
+        got = lib.bls_profile_end(self.handle, ms, cnt, n)
+        if got < 0:
+            self.check(got)
+        return {name: (ms[i], cnt[i]) for i, name in enumerate(PROFILE_CLASSES)}
 
     def close(self):
         if self.handle:

@@ -83,6 +83,33 @@ int bls_ctx_synchronize(bls_ctx* ctx) {
     return BLS_OK;
 }
 
+int bls_profile_begin(bls_ctx* ctx) {
+    if (!ctx) return BLS_EINVAL;
+    ctx->profiling = true;
+    return BLS_OK;
+}
+
+int bls_profile_end(bls_ctx* ctx, double* ms_by_class, int64_t* launches_by_class, int capacity) {
+    if (!ctx) return BLS_EINVAL;
+    ctx->profiling = false;
+    BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (int i = 0; i < capacity; ++i) {
+        if (ms_by_class) ms_by_class[i] = 0.0;
+        if (launches_by_class) launches_by_class[i] = 0;
+    }
+    for (ProfSpan& sp : ctx->spans) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.start, sp.stop) == hipSuccess && sp.cls < capacity) {
+            if (ms_by_class) ms_by_class[sp.cls] += (double)ms;
+            if (launches_by_class) launches_by_class[sp.cls] += 1;
+        }
+        (void)hipEventDestroy(sp.start);
+        (void)hipEventDestroy(sp.stop);
+    }
+    ctx->spans.clear();
+    return PROF_NUM_CLASSES;
+}
+
 // ---- model ----------------------------------------------------------------------------------------
 
 static void add_tensor(bls_model* m, const std::string& name, bool is_buffer, int ndim, int s0, int s1 = 1, int s2 = 1,
@@ -134,7 +161,7 @@ int bls_model_create(const bls_model_desc* desc, bls_model** out) {
         m->fc2_w = m->num_params; add_tensor(m, "fc2.weight", false, 2, desc->classes, desc->hidden);
         m->fc2_b = m->num_params; add_tensor(m, "fc2.bias", false, 1, desc->classes);
     } else if (desc->kind == BLS_MODEL_RESNET_CIFAR) {
-        bool ok = desc->image_hw >= 8 && desc->image_hw <= 64 && desc->image_hw % 8 == 0 && desc->in_channels >= 1 &&
+        bool ok = (desc->image_hw == 8 || desc->image_hw == 16 || desc->image_hw == 32 || desc->image_hw == 64) && desc->in_channels >= 1 &&
                   desc->in_channels <= 4 && desc->blocks >= 1 && desc->blocks <= 18;
         for (int s = 0; s < 3; ++s) {
             int w = desc->widths[s];
@@ -214,6 +241,7 @@ int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_
     if (k == 0) return BLS_OK;
     if (!losses || !idx_out) return bls_fail(ctx, BLS_EINVAL, "topk_by_loss: NULL pointer");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
+    ProfScope prof(ctx, PROF_TOPK);
     return launch_topk(ctx, losses, N, k, idx_out, val_out);
 }
 
@@ -261,6 +289,7 @@ int weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* 
     for (int i = 0; i < P; ++i)
         if (!replicas[i]) return bls_fail(ctx, BLS_EINVAL, "weighted_aggregate: replica %d is NULL", i);
     BLS_HIP(ctx, hipSetDevice(ctx->device));
+    ProfScope prof(ctx, PROF_AGGREGATE);
     return launch_weighted_aggregate(ctx, replicas, w, P, d, out, (flags & BLS_AGG_BROADCAST) != 0);
 }
 

@@ -8,7 +8,18 @@
 
 #include "../../include/bls.h"
 
+// Kernel classes for the optional per-class timing (bls_profile_begin / bls_profile_end).
+enum ProfClass { PROF_CONV_FWD = 0, PROF_CONV_DGRAD, PROF_CONV_WGRAD, PROF_NORM, PROF_HEAD, PROF_GEMM, PROF_UPDATE,
+                 PROF_GATHER, PROF_TOPK, PROF_AGGREGATE, PROF_NUM_CLASSES };
+
+struct ProfSpan {
+    int cls;
+    hipEvent_t start, stop;
+};
+
 struct bls_ctx {
+    bool profiling = false;
+    std::vector<ProfSpan> spans;
     int device = 0;
     hipStream_t stream = nullptr;
     char* arena = nullptr;      // one scratch allocation, grown on demand
@@ -26,6 +37,27 @@ int bls_fail(bls_ctx* ctx, int code, const char* fmt, ...);
         if (e_ != hipSuccess)                                                               \
             return bls_fail((ctx), BLS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
     } while (0)
+
+// Brackets the launches issued during its lifetime with HIP events when profiling is on.
+struct ProfScope {
+    bls_ctx* ctx;
+    ProfSpan span;
+    bool on;
+    ProfScope(bls_ctx* c, int cls) : ctx(c), on(c->profiling) {
+        if (!on) return;
+        span.cls = cls;
+        if (hipEventCreate(&span.start) != hipSuccess || hipEventCreate(&span.stop) != hipSuccess) {
+            on = false;
+            return;
+        }
+        (void)hipEventRecord(span.start, ctx->stream);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(span.stop, ctx->stream);
+        ctx->spans.push_back(span);
+    }
+};
 
 // Makes the context's scratch arena at least `bytes` large.  Growing waits for the stream first.
 int bls_arena_reserve(bls_ctx* ctx, size_t bytes);

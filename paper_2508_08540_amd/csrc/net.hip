@@ -4,6 +4,12 @@
 
 #include "kernels.h"
 
+#define PROF(ctx, cls, call) \
+    do {                     \
+        ProfScope prof_(ctx, cls); \
+        call;                \
+    } while (0)
+
 namespace {
 
 constexpr int PAD_C = 16;       // the stem's input is zero-padded to 16 channels so it runs on the same kernels
@@ -45,9 +51,9 @@ MlpScratch carve_mlp(Carver& c, const bls_model* m, int B, bool train) {
     return s;
 }
 
-void mlp_hidden(hipStream_t st, const bls_model* m, const float* params, const float* x, int B, const MlpScratch& s) {
-    launch_gemm(st, x, m->d_in, false, params + m->fc1_w, m->d_in, false, B, m->desc.hidden, m->d_in, MLP_SPLITS, s.part,
-                s.h, params + m->fc1_b, true, nullptr);
+void mlp_hidden(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, const float* x, int B, const MlpScratch& s) {
+    PROF(ctx, PROF_GEMM, launch_gemm(st, x, m->d_in, false, params + m->fc1_w, m->d_in, false, B, m->desc.hidden, m->d_in, MLP_SPLITS, s.part,
+                s.h, params + m->fc1_b, true, nullptr));
 }
 
 // ---- residual network ---------------------------------------------------------------------------------
@@ -110,7 +116,7 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
 // Forward pass over a batch already gathered into s.xpad.  Train mode keeps every layer's
 // convolution output and activation for the backward pass and updates the running statistics.
 // Returns the final activation.
-const float* resnet_forward(hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, ResScratch& s,
+const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, ResScratch& s,
                             bool train) {
     const int L = (int)m->layers.size();
     float* rot[4] = {s.d1, s.d2, s.g, s.stats};  // inference-only rotation
@@ -130,13 +136,13 @@ const float* resnet_forward(hipStream_t st, const bls_model* m, const float* par
         const bool is_conv2 = l > 0 && (l % 2 == 0);
         if (l > 0 && !is_conv2) block_in = cur;
         float* y = train ? s.y[l] : take(cur, block_in);
-        launch_conv_fwd(st, cs, cur, params + cb.w_off, y, train ? s.stats : nullptr);
+        PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, params + cb.w_off, y, train ? s.stats : nullptr));
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         if (train)
-            launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
-                               buffers + cb.rmean_off, buffers + cb.rvar_off);
+            PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
+                               buffers + cb.rmean_off, buffers + cb.rvar_off));
         else
-            launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]);
+            PROF(ctx, PROF_NORM, launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]));
         float* a = train ? s.a[l] : take(y, block_in);
         const float* res = nullptr;
         int c_res = cb.c_out, res_stride = 1;
@@ -146,14 +152,14 @@ const float* resnet_forward(hipStream_t st, const bls_model* m, const float* par
             c_res = c1.c_in;
             res_stride = c1.stride;
         }
-        launch_bn_apply(st, y, pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off, params + cb.beta_off, res,
-                        c_res, res_stride, cb.h_out, a);
+        PROF(ctx, PROF_NORM, launch_bn_apply(st, y, pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off, params + cb.beta_off, res,
+                        c_res, res_stride, cb.h_out, a));
         cur = a;
     }
     return cur;
 }
 
-void resnet_backward(hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s) {
+void resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s) {
     const int L = (int)m->layers.size();
     const ConvBn& last = m->layers[L - 1];
     const float* dout = s.dfeat;
@@ -164,17 +170,17 @@ void resnet_backward(hipStream_t st, const bls_model* m, const float* params, in
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         const bool is_conv2 = l > 0 && (l % 2 == 0);
         const float* x_in = l == 0 ? s.xpad : s.a[l - 1];
-        launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], s.bnpart);
-        launch_bn_bwd_apply(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
+        PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], s.bnpart));
+        PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
                             s.bnpart, bn_bwd_partials(pixels), s.grad + cb.gamma_off, s.grad + cb.beta_off, s.d1,
-                            is_conv2 ? s.g : nullptr);
-        launch_conv_wgrad(st, cs, x_in, s.d1, s.wpart, s.grad + cb.w_off);
+                            is_conv2 ? s.g : nullptr));
+        PROF(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(st, cs, x_in, s.d1, s.wpart, s.grad + cb.w_off));
         if (l == 0) break;
-        launch_conv_dgrad(st, cs, s.d1, params + cb.w_off, s.d2);
+        PROF(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.d1, params + cb.w_off, s.d2));
         if (!is_conv2) {
             // conv1 of a block: add the gradient that bypassed the block through the shortcut
             const ConvBn& c2 = m->layers[l + 1];
-            launch_shortcut_grad_add(st, s.d2, B, cb.h_in, cb.c_in, s.g, c2.c_out, cb.stride);
+            PROF(ctx, PROF_NORM, launch_shortcut_grad_add(st, s.d2, B, cb.h_in, cb.c_in, s.g, c2.c_out, cb.stride));
         }
         dout = s.d2;
         shared = 0;
@@ -201,19 +207,19 @@ int net_score(bls_ctx* ctx, const bls_model* m, const float* params, const float
         MlpScratch s = carve_mlp(c, m, chunk, false);
         for (int64_t first = 0; first < N; first += chunk) {
             int B = (int)(N - first < chunk ? N - first : chunk);
-            mlp_hidden(st, m, params, x + first * m->d_in, B, s);
-            launch_head_forward(st, s.h, B, 1, m->desc.hidden, params + m->fc2_w, params + m->fc2_b, m->desc.classes,
-                                y + first, losses_out + first, nullptr, nullptr, nullptr, 0.f, false);
+            mlp_hidden(ctx, st, m, params, x + first * m->d_in, B, s);
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.h, B, 1, m->desc.hidden, params + m->fc2_w, params + m->fc2_b, m->desc.classes,
+                                y + first, losses_out + first, nullptr, nullptr, nullptr, 0.f, false));
         }
     } else {
         ResScratch s = carve_resnet(c, m, chunk, false);
         const int hw = m->desc.image_hw;
         for (int64_t first = 0; first < N; first += chunk) {
             int B = (int)(N - first < chunk ? N - first : chunk);
-            launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb);
-            const float* fin = resnet_forward(st, m, params, const_cast<float*>(buffers), B, s, false);
-            launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
-                                m->desc.classes, s.yb, losses_out + first, nullptr, nullptr, nullptr, 0.f, false);
+            PROF(ctx, PROF_GATHER, launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb));
+            const float* fin = resnet_forward(ctx, st, m, params, const_cast<float*>(buffers), B, s, false);
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
+                                m->desc.classes, s.yb, losses_out + first, nullptr, nullptr, nullptr, 0.f, false));
         }
     }
     BLS_HIP(ctx, hipGetLastError());
@@ -235,28 +241,28 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         const int hid = m->desc.hidden, C = m->desc.classes;
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
-            launch_gather_rows(st, x_pool, y_pool, sel, k, j * B, B, m->d_in, s.xb, s.yb);
-            mlp_hidden(st, m, params, s.xb, B, s);
-            launch_head_forward(st, s.h, B, 1, hid, params + m->fc2_w, params + m->fc2_b, C, s.yb, loss, nullptr, s.dlogits,
-                                s.dpre, inv_b, true);
-            launch_head_wgrad(st, s.dlogits, s.h, B, C, hid, s.grad + m->fc2_w, s.grad + m->fc2_b);
-            launch_gemm(st, s.dpre, hid, true, s.xb, m->d_in, true, hid, m->d_in, B, 1, s.part, s.grad + m->fc1_w, nullptr,
-                        false, nullptr);
-            launch_colsum(st, s.dpre, B, hid, s.grad + m->fc1_b);
-            launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay);
+            PROF(ctx, PROF_GATHER, launch_gather_rows(st, x_pool, y_pool, sel, k, j * B, B, m->d_in, s.xb, s.yb));
+            mlp_hidden(ctx, st, m, params, s.xb, B, s);
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.h, B, 1, hid, params + m->fc2_w, params + m->fc2_b, C, s.yb, loss, nullptr, s.dlogits,
+                                s.dpre, inv_b, true));
+            PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.h, B, C, hid, s.grad + m->fc2_w, s.grad + m->fc2_b));
+            PROF(ctx, PROF_GEMM, launch_gemm(st, s.dpre, hid, true, s.xb, m->d_in, true, hid, m->d_in, B, 1, s.part, s.grad + m->fc1_w, nullptr,
+                        false, nullptr));
+            PROF(ctx, PROF_UPDATE, launch_colsum(st, s.dpre, B, hid, s.grad + m->fc1_b));
+            PROF(ctx, PROF_UPDATE, launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay));
         }
     } else {
         ResScratch s = carve_resnet(c, m, B, true);
         const int hw = m->desc.image_hw, C = m->desc.classes;
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
-            launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb);
-            const float* fin = resnet_forward(st, m, params, buffers, B, s, true);
-            launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
-                                loss, s.feat, s.dlogits, s.dfeat, inv_b, false);
-            launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b);
-            resnet_backward(st, m, params, B, s);
-            launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay);
+            PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb));
+            const float* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true);
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
+                                loss, s.feat, s.dlogits, s.dfeat, inv_b, false));
+            PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b));
+            resnet_backward(ctx, st, m, params, B, s);
+            PROF(ctx, PROF_UPDATE, launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay));
         }
     }
     BLS_HIP(ctx, hipGetLastError());
