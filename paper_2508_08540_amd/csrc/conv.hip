@@ -17,7 +17,7 @@
 // Weight gradient (wgrad_kernel).  dW[o][tap][i] = sum_pixels dy[p][o] * x[p + tap][i] is a GEMM with
 // K = B*H*W.  Workgroups walk disjoint sets of pixel tiles (same staging as above plus the dy tile),
 // every wavefront accumulates its 16x16 (o, i) blocks for all 9 taps in registers across all its
-// tiles, and writes one partial per wavefront; a second kernel adds the partials in a fixed order.
+// tiles; a workgroup writes one partial and a second kernel adds the partials in a fixed order.
 #include "kernels.h"
 
 #define CONV_THREADS 256
@@ -313,8 +313,31 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
             }
         }
     }
-    // partial of this wave: part = blockIdx.x * WP + wp; element ((o*9 + t)*NI + i)
-    float* out = partials + ((int64_t)blockIdx.x * Cfg::WP + wp) * (NO * 9 * NI);
+    // One partial per workgroup, element ((o*9 + t)*NI + i).  Waves that split the pixels first add
+    // their accumulators through LDS in wave order.
+    float* out = partials + (int64_t)blockIdx.x * (NO * 9 * NI);
+    if (Cfg::WP > 1) {
+        __syncthreads();  // staged tiles are no longer needed
+#pragma unroll
+        for (int oa = 0; oa < NOB_W; ++oa)
+#pragma unroll
+            for (int ib = 0; ib < NIB_W; ++ib)
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        int o = (ob0 + oa) * 16 + 4 * grp + j, i = (ib0 + ib) * 16 + r16;
+                        lds[(int64_t)wp * (NO * 9 * NI) + ((int64_t)o * 9 + t) * NI + i] = acc[oa][ib][t][j];
+                    }
+        __syncthreads();
+        for (int e = threadIdx.x; e < NO * 9 * NI; e += CONV_THREADS) {
+            float v = lds[e];
+#pragma unroll
+            for (int q = 1; q < Cfg::WP; ++q) v += lds[q * (NO * 9 * NI) + e];
+            out[e] = v;
+        }
+        return;
+    }
 #pragma unroll
     for (int oa = 0; oa < NOB_W; ++oa)
 #pragma unroll
@@ -328,17 +351,29 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
                 }
 }
 
-// dw[(o*9+t)*ci_real + i] = sum_parts partials[part][(o*9+t)*NI + i]
+// dw[(o*9+t)*ci_real + i] = sum_parts partials[part][(o*9+t)*NI + i].  A block covers 32 outputs; its 8
+// thread rows take every 8th partial and are folded through LDS in row order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int n_parts, int n_out9,
                                                            int NI, int ci_real, float* __restrict__ dw) {
-    int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n_out9 * ci_real) return;
-    int ot = idx / ci_real, i = idx - ot * ci_real;
-    int64_t src = (int64_t)ot * NI + i;
-    int64_t pitch = (int64_t)n_out9 * NI;
+    __shared__ float red[8][32];
+    const int col = threadIdx.x & 31, row = threadIdx.x >> 5;
+    const int idx = blockIdx.x * 32 + col;
+    const bool live = idx < n_out9 * ci_real;
     float acc = 0.f;
-    for (int p = 0; p < n_parts; ++p) acc += partials[p * pitch + src];
-    dw[idx] = acc;
+    if (live) {
+        int ot = idx / ci_real, i = idx - ot * ci_real;
+        int64_t src = (int64_t)ot * NI + i;
+        int64_t pitch = (int64_t)n_out9 * NI;
+        for (int p = row; p < n_parts; p += 8) acc += partials[p * pitch + src];
+    }
+    red[row][col] = acc;
+    __syncthreads();
+    if (row == 0 && live) {
+        float v = red[0][col];
+#pragma unroll
+        for (int r = 1; r < 8; ++r) v += red[r][col];
+        dw[idx] = v;
+    }
 }
 
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
@@ -347,20 +382,16 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     return n_tiles < cap ? n_tiles : cap;
 }
 
-static int wgrad_wp(const ConvShape& cs) {
-    if (cs.c_out == 16 && cs.c_in == 16) return 4;
-    if (cs.c_out == 32 && cs.c_in == 16) return 2;
-    return 1;
-}
-
 int conv_wgrad_partials(const ConvShape& cs) {
-    return wgrad_groups(cs, conv_fwd_tiles(cs)) * wgrad_wp(cs);
+    return wgrad_groups(cs, conv_fwd_tiles(cs));
 }
 
 template <int NO, int NI, int NOB_W, int NIB_W>
 static void launch_wgrad_t(hipStream_t s, const ConvGeom& g, int groups, const float* x, const float* dy, float* partials) {
     constexpr int DP = (NO % 32 == 16) ? NO : NO + 16;
     size_t lds = (input_lds_floats<NI>(g) + (size_t)(g.rows_tile << g.wout_log2) * DP) * sizeof(float);
+    constexpr int WP = WgradCfg<NO, NI, NOB_W, NIB_W>::WP;
+    if (WP > 1 && lds < (size_t)WP * NO * 9 * NI * sizeof(float)) lds = (size_t)WP * NO * 9 * NI * sizeof(float);
     auto kern = wgrad_kernel<NO, NI, NOB_W, NIB_W>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;
@@ -381,8 +412,8 @@ void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const
         case 6432: launch_wgrad_t<64, 32, 1, 2>(s, g, groups, x, dy, partials); break;
         default:   launch_wgrad_t<64, 64, 2, 2>(s, g, groups, x, dy, partials); break;
     }
-    int n_parts = groups * wgrad_wp(cs);
+    int n_parts = groups;
     int n = cs.c_out * 9 * cs.c_in_real;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partials, n_parts, cs.c_out * 9,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 31) / 32), dim3(256), 0, s, partials, n_parts, cs.c_out * 9,
                        cs.c_in, cs.c_in_real, dw);
 }

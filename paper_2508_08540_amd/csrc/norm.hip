@@ -6,17 +6,38 @@
 #define BN_EPS 1e-5
 #define BN_MOMENTUM 0.1
 
-// partials: [n_partials][2][C] = per-tile (sum, sum of squares)
-__global__ __launch_bounds__(64) void bn_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
-                                                         double count, float* __restrict__ mean, float* __restrict__ invstd,
-                                                         float* __restrict__ running_mean, float* __restrict__ running_var) {
-    int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    double s = 0.0, ss = 0.0;
-    for (int i = 0; i < n_partials; ++i) {
-        s += (double)partials[((int64_t)i * 2) * C + c];
-        ss += (double)partials[((int64_t)i * 2 + 1) * C + c];
+// Sums column (which, c) of partials[n_partials][2][C] in double: each of the 256 threads of the block
+// takes every 256th partial, then a fixed LDS tree folds the threads (deterministic).
+__device__ __forceinline__ void block_sum2(const float* __restrict__ partials, int n_partials, int C, int c, double& s0,
+                                           double& s1) {
+    __shared__ double red[2][256];
+    double a = 0.0, b = 0.0;
+    for (int i = threadIdx.x; i < n_partials; i += 256) {
+        a += (double)partials[((int64_t)i * 2) * C + c];
+        b += (double)partials[((int64_t)i * 2 + 1) * C + c];
     }
+    red[0][threadIdx.x] = a;
+    red[1][threadIdx.x] = b;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + w];
+            red[1][threadIdx.x] += red[1][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    s0 = red[0][0];
+    s1 = red[1][0];
+}
+
+// partials: [n_partials][2][C] = per-tile (sum, sum of squares); one block per channel
+__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
+                                                          double count, float* __restrict__ mean, float* __restrict__ invstd,
+                                                          float* __restrict__ running_mean, float* __restrict__ running_var) {
+    const int c = blockIdx.x;
+    double s, ss;
+    block_sum2(partials, n_partials, C, c, s, ss);
+    if (threadIdx.x != 0) return;
     double mu = s / count;
     double var = ss / count - mu * mu;
     if (var < 0.0) var = 0.0;
@@ -29,7 +50,7 @@ __global__ __launch_bounds__(64) void bn_finalize_kernel(const float* __restrict
 
 void launch_bn_finalize(hipStream_t s, const float* partials, int n_partials, int C, int64_t count, float* mean,
                         float* invstd, float* running_mean, float* running_var) {
-    hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 63) / 64), dim3(64), 0, s, partials, n_partials, C, (double)count,
+    hipLaunchKernelGGL(bn_finalize_kernel, dim3(C), dim3(256), 0, s, partials, n_partials, C, (double)count,
                        mean, invstd, running_mean, running_var);
 }
 
@@ -162,15 +183,12 @@ void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_s
                        mean, invstd, partials);
 }
 
-__global__ __launch_bounds__(64) void bn_bwd_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
-                                                             float* __restrict__ dgamma, float* __restrict__ dbeta) {
-    int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    double sg = 0.0, sgx = 0.0;
-    for (int i = 0; i < n_partials; ++i) {
-        sg += (double)partials[((int64_t)i * 2) * C + c];
-        sgx += (double)partials[((int64_t)i * 2 + 1) * C + c];
-    }
+__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
+                                                              float* __restrict__ dgamma, float* __restrict__ dbeta) {
+    const int c = blockIdx.x;
+    double sg, sgx;
+    block_sum2(partials, n_partials, C, c, sg, sgx);
+    if (threadIdx.x != 0) return;
     dbeta[c] = (float)sg;
     dgamma[c] = (float)sgx;
 }
@@ -211,7 +229,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
 void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
                          const float* partials, int n_partials, float* dgamma, float* dbeta, float* dy, float* g_out) {
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3((C + 63) / 64), dim3(64), 0, s, partials, n_partials, C, dgamma, dbeta);
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(C), dim3(256), 0, s, partials, n_partials, C, dgamma, dbeta);
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
