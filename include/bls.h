@@ -60,7 +60,7 @@ typedef struct {
     int32_t in_channels; /* RESNET: 1 .. 4                                 */
     int32_t hidden;      /* MLP only: multiple of 16, 16 .. 1024           */
     int32_t widths[3];   /* RESNET only: each of 16, 32 or 64              */
-    int32_t blocks;      /* RESNET only: 1 .. 18                           */
+    int32_t blocks;      /* RESNET only: 1 .. 6                            */
 } bls_model_desc;
 
 /* One tensor of the flat parameter vector (is_buffer = 0) or of the flat buffer vector that

@@ -162,7 +162,7 @@ int bls_model_create(const bls_model_desc* desc, bls_model** out) {
         m->fc2_b = m->num_params; add_tensor(m, "fc2.bias", false, 1, desc->classes);
     } else if (desc->kind == BLS_MODEL_RESNET_CIFAR) {
         bool ok = (desc->image_hw == 8 || desc->image_hw == 16 || desc->image_hw == 32 || desc->image_hw == 64) && desc->in_channels >= 1 &&
-                  desc->in_channels <= 4 && desc->blocks >= 1 && desc->blocks <= 18;
+                  desc->in_channels <= 4 && desc->blocks >= 1 && desc->blocks <= 6;
         for (int s = 0; s < 3; ++s) {
             int w = desc->widths[s];
             ok = ok && (w == 16 || w == 32 || w == 64);

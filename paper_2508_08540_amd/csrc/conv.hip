@@ -15,9 +15,7 @@
 // samples, which turns the transposed convolution into a stride-1 one.
 //
 // Weight gradient (wgrad_kernel).  dW[o][tap][i] = sum_pixels dy[p][o] * x[p + tap][i] is a GEMM with
-// K = B*H*W.  Workgroups walk disjoint sets of pixel tiles (same staging as above plus the dy tile),
-// every wavefront accumulates its 16x16 (o, i) blocks for all 9 taps in registers across all its
-// tiles; a workgroup writes one partial and a second kernel adds the partials in a fixed order.
+// K = B*H*W: see the comment above that kernel.
 #include "kernels.h"
 
 #define CONV_THREADS 256
@@ -60,9 +58,10 @@ static size_t input_lds_floats(const ConvGeom& g) {
 }
 
 // Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + 4], zero outside the image.
+// `pitch` is the channel count of the tensor in memory and `c_off` the first channel of the CIN-wide slice.
 template <int CIN>
-__device__ __forceinline__ void stage_input(float* __restrict__ lds, const float* __restrict__ x, const ConvGeom& g,
-                                            int tile) {
+__device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const float* __restrict__ x, const ConvGeom& g,
+                                            int tile, int pitch = CIN, int c_off = 0) {
     constexpr int CP = CIN + 4, CQ = CIN / 4;
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
@@ -79,12 +78,12 @@ __device__ __forceinline__ void stage_input(float* __restrict__ lds, const float
         f32x4 v = {0.f, 0.f, 0.f, 0.f};
         if (n < g.B && hi >= 0 && hi < g.h_in && wi >= 0 && wi < g.h_in) {
             if (!g.ups) {
-                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + hi) * src_h + wi) * CIN + cq * 4);
+                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + hi) * src_h + wi) * pitch + c_off + cq * 4);
             } else if (((hi | wi) & 1) == 0) {
-                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + (hi >> 1)) * src_h + (wi >> 1)) * CIN + cq * 4);
+                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + (hi >> 1)) * src_h + (wi >> 1)) * pitch + c_off + cq * 4);
             }
         }
-        *reinterpret_cast<f32x4*>(lds + pix * CP + cq * 4) = v;
+        lds4[pix * (CP / 4) + cq] = v;
     }
 }
 
@@ -96,11 +95,12 @@ __device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
     return ((part * g.in_rows + r * g.stride) * g.lw + col * g.stride) * (CIN + 4);
 }
 
-// MODE 0: forward weights w[o][tap][i]; MODE 1: transposed and flipped, w[i][8 - tap][o] (input gradient).
-template <int CIN, int MT, int MODE>
+// `w` is the packed copy of the layer's weights made by pack_weights_kernel (forward or input-gradient form).
+template <int CIN, int MT>
 __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                             float* __restrict__ y, float* __restrict__ stats, ConvGeom g) {
-    extern __shared__ float lds[];
+    extern __shared__ f32x4 lds4[];  // float4-typed so that tile reads and writes are single 16-byte LDS accesses
+    float* lds = reinterpret_cast<float*>(lds4);
     constexpr int CP = CIN + 4, S = CIN / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;
@@ -108,33 +108,18 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
     const int ob = wave % NOB;
     const int tile = blockIdx.x;
 
-    // weights of output-channel block `ob` into registers: wr[tap][s] holds input channels 16s+4grp .. +3
+    // weights of output-channel block `ob` into registers: wr[tap][s] holds input channels 16s+4grp .. +3 of
+    // output channel 16*ob + r16, read from the lane-major packed copy (one contiguous 1 KB load each)
     f32x4 wr[9][S];
     {
-        const int o = ob * 16 + r16;
+        const f32x4* wp = reinterpret_cast<const f32x4*>(w) + (int64_t)ob * 9 * S * 64 + lane;
 #pragma unroll
         for (int t = 0; t < 9; ++t)
 #pragma unroll
-            for (int s = 0; s < S; ++s) {
-                const int i0 = 16 * s + 4 * grp;
-                f32x4 v;
-                if (MODE == 0) {
-                    const float* p = w + ((int64_t)o * 9 + t) * g.w_ci + i0;
-                    if (g.w_ci == CIN) {
-                        v = *reinterpret_cast<const f32x4*>(p);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) v[j] = (i0 + j < g.w_ci) ? p[j] : 0.f;
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = w[((int64_t)(i0 + j) * 9 + (8 - t)) * NO + o];
-                }
-                wr[t][s] = v;
-            }
+            for (int s = 0; s < S; ++s) wr[t][s] = wp[(t * S + s) * 64];
     }
 
-    stage_input<CIN>(lds, x, g, tile);
+    stage_input<CIN>(lds4, x, g, tile);
     __syncthreads();
 
     const int tile_pixels = g.rows_tile << g.wout_log2;
@@ -148,17 +133,17 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
         f32x4 acc[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
-            base[m] = pixel_lds_base<CIN>(g, (mg * MT + m) * 16 + r16) + 4 * grp;
+            base[m] = pixel_lds_base<CIN>(g, (mg * MT + m) * 16 + r16) / 4 + grp;  // float4 units
             acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
-            const int tap_off = ((t / 3) * g.lw + (t % 3)) * CP;
+            const int tap_off = ((t / 3) * g.lw + (t % 3)) * (CP / 4);
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 f32x4 b[MT];
 #pragma unroll
-                for (int m = 0; m < MT; ++m) b[m] = *reinterpret_cast<const f32x4*>(lds + base[m] + tap_off + 16 * s);
+                for (int m = 0; m < MT; ++m) b[m] = lds4[base[m] + tap_off + 4 * s];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -206,12 +191,55 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
     }
 }
 
-template <int CIN, int MODE>
+template <int CIN>
 static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, float* stats) {
     size_t lds = input_lds_floats<CIN>(g) * sizeof(float);
-    auto kern = conv_kernel<CIN, 2, MODE>;
+    auto kern = conv_kernel<CIN, 2>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(CONV_THREADS), lds, s, x, w, y, stats, g);
+}
+
+// ---- weight packing -----------------------------------------------------------------------------------
+//
+// Lane-major copies of every convolution's weights, rebuilt after each parameter update.  For a layer
+// with (padded) input channels CI and output channels CO the forward copy holds, as float4 number
+// ((ob*9 + t)*(CI/16) + s)*64 + lane, the values w[16*ob + lane%16][t][16*s + 4*(lane/16) + 0..3] (zero
+// beyond the real input channels).  The input-gradient copy describes the transposed convolution:
+// roles of CI and CO swap and the taps are flipped, value j = w[16*s + 4*(lane/16) + j][8 - t][16*ob + lane%16].
+
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ params, float* __restrict__ packed,
+                                                           PackTable tab) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // float4 index
+    if (i >= tab.total_vec4) return;
+    int l = 0;
+    while (l + 1 < tab.n && i >= tab.e[l + 1].pack_off) ++l;
+    const PackEntry e = tab.e[l];
+    int64_t r = i - e.pack_off;
+    const int lane = (int)(r & 63);
+    r >>= 6;
+    const int r16 = lane & 15, grp = lane >> 4;
+    const float* w = params + e.w_off;
+    f32x4 v;
+    if (!e.dgrad) {
+        const int S = e.c_in >> 4;
+        const int s = (int)(r % S), t = (int)((r / S) % 9), ob = (int)(r / (S * 9));
+        const int o = ob * 16 + r16, i0 = 16 * s + 4 * grp;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (i0 + j < e.c_in_real) ? w[((int64_t)o * 9 + t) * e.c_in_real + i0 + j] : 0.f;
+    } else {
+        // transposed convolution: its input channels are the layer's outputs, its outputs the layer's inputs
+        const int S = e.c_out >> 4;
+        const int s = (int)(r % S), t = (int)((r / S) % 9), ob = (int)(r / (S * 9));
+        const int o = ob * 16 + r16, i0 = 16 * s + 4 * grp;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = w[((int64_t)(i0 + j) * 9 + (8 - t)) * e.c_in_real + o];
+    }
+    reinterpret_cast<f32x4*>(packed)[i] = v;
+}
+
+void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab) {
+    int64_t blocks = (tab.total_vec4 + 255) / 256;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, params, packed, tab);
 }
 
 int conv_fwd_tiles(const ConvShape& cs) {
@@ -223,9 +251,9 @@ void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const f
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
     switch (cs.c_in) {
-        case 16: launch_conv_t<16, 0>(s, g, x, w, y, stats_partials); break;
-        case 32: launch_conv_t<32, 0>(s, g, x, w, y, stats_partials); break;
-        default: launch_conv_t<64, 0>(s, g, x, w, y, stats_partials); break;
+        case 16: launch_conv_t<16>(s, g, x, w, y, stats_partials); break;
+        case 32: launch_conv_t<32>(s, g, x, w, y, stats_partials); break;
+        default: launch_conv_t<64>(s, g, x, w, y, stats_partials); break;
     }
 }
 
@@ -235,136 +263,94 @@ void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, cons
     int ups = cs.stride == 2 ? 1 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in);
     switch (cs.c_out) {
-        case 16: launch_conv_t<16, 1>(s, g, dy, w, dx, nullptr); break;
-        case 32: launch_conv_t<32, 1>(s, g, dy, w, dx, nullptr); break;
-        default: launch_conv_t<64, 1>(s, g, dy, w, dx, nullptr); break;
+        case 16: launch_conv_t<16>(s, g, dy, w, dx, nullptr); break;
+        case 32: launch_conv_t<32>(s, g, dy, w, dx, nullptr); break;
+        default: launch_conv_t<64>(s, g, dy, w, dx, nullptr); break;
     }
 }
 
 // ---- weight gradient ------------------------------------------------------------------------------
+//
+// Workgroup (pg, ob, ib) owns the 16x16 block (output channels 16*ob.., input channels 16*ib..) of dW
+// for all 9 taps over pixel group pg.  It stages only those 16-channel slices of x and dy, its four
+// waves take every 4th pixel quad, fold their 9 accumulators through LDS in wave order and write one
+// 2304-float partial.  All layer shapes therefore run the same code, the grid has
+// groups * (C_out/16) * (C_in/16) workgroups, and the partial traffic stays near 5 MB per layer.
 
-struct WgradPlan {
-    int groups;  // workgroups (pixel chunks)
-    int wp;      // pixel splits among the waves of a workgroup
-};
+#define WG_BLOCK_FLOATS (16 * 9 * 16)
 
-template <int NO, int NI, int NOB_W, int NIB_W>
-struct WgradCfg {
-    static constexpr int NOB = NO / 16, NIB = NI / 16;
-    static constexpr int WT = (NOB / NOB_W) * (NIB / NIB_W);  // waves that split the (o, i) blocks
-    static constexpr int WP = 4 / WT;                          // waves that split the pixels
-    static_assert(WT >= 1 && WT <= 4 && 4 % WT == 0, "wave split");
-};
-
-template <int NO, int NI, int NOB_W, int NIB_W>
 __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
-                                                             float* __restrict__ partials, ConvGeom g, int tiles_per_group) {
-    using Cfg = WgradCfg<NO, NI, NOB_W, NIB_W>;
-    extern __shared__ float lds[];
-    constexpr int CP = NI + 4;
-    constexpr int DP = (NO % 32 == 16) ? NO : NO + 16;  // dy row pitch: 16 mod 32 floats
+                                                             float* __restrict__ partials, ConvGeom g, int tiles_per_group,
+                                                             int NI, int NO) {
+    extern __shared__ f32x4 lds4[];
+    float* lds = reinterpret_cast<float*>(lds4);
+    constexpr int CP = 16 + 4, DP = 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;
-    const int ws = wave % Cfg::WT, wp = wave / Cfg::WT;
-    const int ob0 = (ws / (Cfg::NIB / NIB_W)) * NOB_W, ib0 = (ws % (Cfg::NIB / NIB_W)) * NIB_W;
+    const int NIB = NI >> 4;
+    const int ob = blockIdx.y / NIB, ib = blockIdx.y - ob * NIB;
     const int tile_pixels = g.rows_tile << g.wout_log2;
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
     float* lds_x = lds;
     float* lds_dy = lds + (size_t)g.imgs * g.in_rows * g.lw * CP;
 
-    f32x4 acc[NOB_W][NIB_W][9];
+    f32x4 acc[9];
 #pragma unroll
-    for (int a = 0; a < NOB_W; ++a)
-#pragma unroll
-        for (int b = 0; b < NIB_W; ++b)
-#pragma unroll
-            for (int t = 0; t < 9; ++t) acc[a][b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 9; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int tile_begin = blockIdx.x * tiles_per_group;
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         __syncthreads();  // previous tile fully consumed
-        stage_input<NI>(lds_x, x, g, tile);
+        stage_input<16>(lds4, x, g, tile, NI, ib * 16);
         const int64_t pix0 = (int64_t)tile * tile_pixels;
-        for (int i = threadIdx.x; i < tile_pixels * (NO / 4); i += CONV_THREADS) {
-            int q = i / (NO / 4), c4 = i % (NO / 4);
+        for (int i = threadIdx.x; i < tile_pixels * 4; i += CONV_THREADS) {
+            int q = i >> 2, c4 = i & 3;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (pix0 + q < total_pixels) v = *reinterpret_cast<const f32x4*>(dy + (pix0 + q) * NO + c4 * 4);
-            *reinterpret_cast<f32x4*>(lds_dy + q * DP + c4 * 4) = v;
+            if (pix0 + q < total_pixels) v = *reinterpret_cast<const f32x4*>(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
+            reinterpret_cast<f32x4*>(lds_dy)[q * (DP / 4) + c4] = v;
         }
         __syncthreads();
-        // one MFMA consumes 4 pixels (one per lane group); this wave takes every WP-th quad
-        for (int qd = wp; qd < tile_pixels / 4; qd += Cfg::WP) {
+        // one MFMA consumes 4 pixels (one per lane group); this wave takes every 4th quad
+        for (int qd = wave; qd < tile_pixels / 4; qd += 4) {
             const int q = 4 * qd + grp;
-            float a[NOB_W];
-#pragma unroll
-            for (int oa = 0; oa < NOB_W; ++oa) a[oa] = lds_dy[q * DP + (ob0 + oa) * 16 + r16];
-            const int xb = pixel_lds_base<NI>(g, q) + r16;
+            const float a = lds_dy[q * DP + r16];
+            const int xb = pixel_lds_base<16>(g, q) + r16;
 #pragma unroll
             for (int t = 0; t < 9; ++t) {
-                const int tap_off = ((t / 3) * g.lw + (t % 3)) * CP;
-#pragma unroll
-                for (int ib = 0; ib < NIB_W; ++ib) {
-                    float b = lds_x[xb + tap_off + (ib0 + ib) * 16];
-#pragma unroll
-                    for (int oa = 0; oa < NOB_W; ++oa)
-                        acc[oa][ib][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[oa], b, acc[oa][ib][t], 0, 0, 0);
-                }
+                const float b = lds_x[xb + ((t / 3) * g.lw + (t % 3)) * CP];
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[t], 0, 0, 0);
             }
         }
     }
-    // One partial per workgroup, element ((o*9 + t)*NI + i).  Waves that split the pixels first add
-    // their accumulators through LDS in wave order.
-    float* out = partials + (int64_t)blockIdx.x * (NO * 9 * NI);
-    if (Cfg::WP > 1) {
-        __syncthreads();  // staged tiles are no longer needed
+    // fold the four waves in wave order; element (o*9 + t)*16 + i of the block
+    __syncthreads();
 #pragma unroll
-        for (int oa = 0; oa < NOB_W; ++oa)
+    for (int t = 0; t < 9; ++t)
 #pragma unroll
-            for (int ib = 0; ib < NIB_W; ++ib)
-#pragma unroll
-                for (int t = 0; t < 9; ++t)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        int o = (ob0 + oa) * 16 + 4 * grp + j, i = (ib0 + ib) * 16 + r16;
-                        lds[(int64_t)wp * (NO * 9 * NI) + ((int64_t)o * 9 + t) * NI + i] = acc[oa][ib][t][j];
-                    }
-        __syncthreads();
-        for (int e = threadIdx.x; e < NO * 9 * NI; e += CONV_THREADS) {
-            float v = lds[e];
-#pragma unroll
-            for (int q = 1; q < Cfg::WP; ++q) v += lds[q * (NO * 9 * NI) + e];
-            out[e] = v;
-        }
-        return;
-    }
-#pragma unroll
-    for (int oa = 0; oa < NOB_W; ++oa)
-#pragma unroll
-        for (int ib = 0; ib < NIB_W; ++ib)
-#pragma unroll
-            for (int t = 0; t < 9; ++t)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    int o = (ob0 + oa) * 16 + 4 * grp + j, i = (ib0 + ib) * 16 + r16;
-                    out[((int64_t)o * 9 + t) * NI + i] = acc[oa][ib][t][j];
-                }
+        for (int j = 0; j < 4; ++j) lds[wave * WG_BLOCK_FLOATS + ((4 * grp + j) * 9 + t) * 16 + r16] = acc[t][j];
+    __syncthreads();
+    float* out = partials + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * WG_BLOCK_FLOATS;
+    for (int e = threadIdx.x; e < WG_BLOCK_FLOATS; e += CONV_THREADS)
+        out[e] = ((lds[e] + lds[WG_BLOCK_FLOATS + e]) + lds[2 * WG_BLOCK_FLOATS + e]) + lds[3 * WG_BLOCK_FLOATS + e];
 }
 
-// dw[(o*9+t)*ci_real + i] = sum_parts partials[part][(o*9+t)*NI + i].  A block covers 32 outputs; its 8
-// thread rows take every 8th partial and are folded through LDS in row order.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int n_parts, int n_out9,
-                                                           int NI, int ci_real, float* __restrict__ dw) {
+// dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over pixel groups of partial (pg, ob, ib)[(o*9 + t)*16 + i].
+// A block covers 32 outputs; its 8 thread rows take every 8th group and are folded through LDS in row order.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int groups, int NO, int NI,
+                                                           int ci_real, float* __restrict__ dw) {
     __shared__ float red[8][32];
     const int col = threadIdx.x & 31, row = threadIdx.x >> 5;
     const int idx = blockIdx.x * 32 + col;
-    const bool live = idx < n_out9 * ci_real;
+    const bool live = idx < NO * 9 * ci_real;
     float acc = 0.f;
     if (live) {
-        int ot = idx / ci_real, i = idx - ot * ci_real;
-        int64_t src = (int64_t)ot * NI + i;
-        int64_t pitch = (int64_t)n_out9 * NI;
-        for (int p = row; p < n_parts; p += 8) acc += partials[p * pitch + src];
+        int ot = idx / ci_real, ci = idx - ot * ci_real;
+        int co = ot / 9, t = ot - co * 9;
+        int blocks = (NO >> 4) * (NI >> 4);
+        int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + ((co & 15) * 9 + t) * 16 + (ci & 15);
+        int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
+        for (int p = row; p < groups; p += 8) acc += partials[p * pitch + src];
     }
     red[row][col] = acc;
     __syncthreads();
@@ -377,43 +363,25 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 }
 
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
-    // Bound the partial traffic: each group writes c_out*9*c_in floats per pixel split.
-    int cap = (cs.c_in * cs.c_out <= 512) ? 256 : (cs.c_in * cs.c_out <= 1024 ? 128 : 64);
+    int blocks = (cs.c_in / 16) * (cs.c_out / 16);
+    int cap = 512 / blocks;
     return n_tiles < cap ? n_tiles : cap;
 }
 
-int conv_wgrad_partials(const ConvShape& cs) {
-    return wgrad_groups(cs, conv_fwd_tiles(cs));
-}
-
-template <int NO, int NI, int NOB_W, int NIB_W>
-static void launch_wgrad_t(hipStream_t s, const ConvGeom& g, int groups, const float* x, const float* dy, float* partials) {
-    constexpr int DP = (NO % 32 == 16) ? NO : NO + 16;
-    size_t lds = (input_lds_floats<NI>(g) + (size_t)(g.rows_tile << g.wout_log2) * DP) * sizeof(float);
-    constexpr int WP = WgradCfg<NO, NI, NOB_W, NIB_W>::WP;
-    if (WP > 1 && lds < (size_t)WP * NO * 9 * NI * sizeof(float)) lds = (size_t)WP * NO * 9 * NI * sizeof(float);
-    auto kern = wgrad_kernel<NO, NI, NOB_W, NIB_W>;
-    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    int tiles_per_group = (g.n_tiles + groups - 1) / groups;
-    hipLaunchKernelGGL(kern, dim3(groups), dim3(CONV_THREADS), lds, s, x, dy, partials, g, tiles_per_group);
-}
+int conv_wgrad_partials(const ConvShape& cs) { return wgrad_groups(cs, conv_fwd_tiles(cs)); }
 
 void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials, float* dw) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
     int groups = wgrad_groups(cs, g.n_tiles);
-    // groups may leave the last ones empty after rounding tiles_per_group up; they then write zeros
-    int key = cs.c_out * 100 + cs.c_in;
-    switch (key) {
-        case 1616: launch_wgrad_t<16, 16, 1, 1>(s, g, groups, x, dy, partials); break;
-        case 3216: launch_wgrad_t<32, 16, 1, 1>(s, g, groups, x, dy, partials); break;
-        case 6416: launch_wgrad_t<64, 16, 1, 1>(s, g, groups, x, dy, partials); break;
-        case 3232: launch_wgrad_t<32, 32, 1, 1>(s, g, groups, x, dy, partials); break;
-        case 6432: launch_wgrad_t<64, 32, 1, 2>(s, g, groups, x, dy, partials); break;
-        default:   launch_wgrad_t<64, 64, 2, 2>(s, g, groups, x, dy, partials); break;
-    }
-    int n_parts = groups;
+    int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
+    size_t lds = (input_lds_floats<16>(g) + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
+    if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
+    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    int blocks = (cs.c_in / 16) * (cs.c_out / 16);
+    hipLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(CONV_THREADS), lds, s, x, dy, partials, g, tiles_per_group,
+                       cs.c_in, cs.c_out);
     int n = cs.c_out * 9 * cs.c_in_real;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 31) / 32), dim3(256), 0, s, partials, n_parts, cs.c_out * 9,
-                       cs.c_in, cs.c_in_real, dw);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 31) / 32), dim3(256), 0, s, partials, groups, cs.c_out, cs.c_in,
+                       cs.c_in_real, dw);
 }

@@ -68,7 +68,21 @@ struct ConvShape {
     int B, h_in, c_in, c_out, stride;  // square maps; 3x3, padding 1; c_in, c_out in {16, 32, 64}
     int c_in_real;                     // weights hold this many input channels (<= c_in); the rest are zero
 };
+// Packed (lane-major) weight copies for the convolution kernels; see pack_weights_kernel.
+#define PACK_MAX_ENTRIES 80
+struct PackEntry {
+    int64_t w_off;     // offset of w[c_out][3][3][c_in_real] in the parameter vector
+    int64_t pack_off;  // float4 offset of this entry in the packed buffer
+    int c_in, c_out, c_in_real, dgrad;
+};
+struct PackTable {
+    int n;
+    int64_t total_vec4;
+    PackEntry e[PACK_MAX_ENTRIES];
+};
+void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab);
 int conv_fwd_tiles(const ConvShape& cs);
+// In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
 // y = conv(x, w); stats_partials (optional) receives per-tile per-channel (sum, sum of squares) of y.
 void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, float* stats_partials);
 // dx = conv_transpose(dy, w)

@@ -59,6 +59,9 @@ void mlp_hidden(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* p
 // ---- residual network ---------------------------------------------------------------------------------
 
 struct ResScratch {
+    float* wpack;                      // packed weights: forward copies of all layers, then input-gradient copies
+    std::vector<int64_t> fwd_off, dgrad_off;  // float offsets into wpack per layer
+    PackTable tab;
     float* xpad;
     int32_t* yb;
     std::vector<float*> y, a, mean, invstd;  // per layer
@@ -70,6 +73,25 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     ResScratch s{};
     const int L = (int)m->layers.size();
     const int hw = m->desc.image_hw;
+    s.fwd_off.assign(L, 0);
+    s.dgrad_off.assign(L, 0);
+    s.tab.n = 0;
+    int64_t vec4 = 0;
+    for (int pass = 0; pass < (train ? 2 : 1); ++pass)
+        for (int l = (pass == 0 ? 0 : 1); l < L; ++l) {
+            const ConvBn& cb = m->layers[l];
+            PackEntry& e = s.tab.e[s.tab.n++];
+            e.w_off = cb.w_off;
+            e.pack_off = vec4;
+            e.c_in = cb.c_in < PAD_C ? PAD_C : cb.c_in;
+            e.c_out = cb.c_out;
+            e.c_in_real = cb.c_in;
+            e.dgrad = pass;
+            (pass == 0 ? s.fwd_off : s.dgrad_off)[l] = vec4 * 4;
+            vec4 += (int64_t)e.c_in * e.c_out * 9 / 4;
+        }
+    s.tab.total_vec4 = vec4;
+    s.wpack = c.take<float>(vec4 * 4);
     s.xpad = c.take<float>((size_t)B * hw * hw * PAD_C);
     s.yb = c.take<int32_t>(B);
     s.loss = c.take<float>(B);
@@ -80,7 +102,7 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
         ConvShape cs = shape_of(cb, B);
         max_act = max64(max_act, out_floats(cb, B));
         max_stats = max64(max_stats, (int64_t)conv_fwd_tiles(cs) * 2 * cb.c_out);
-        max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);
+        max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);  // groups * blocks * 2304
         s.mean[l] = c.take<float>(cb.c_out);
         s.invstd[l] = c.take<float>(cb.c_out);
     }
@@ -128,6 +150,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             if (p != keep0 && p != keep1) return p;
         }
     };
+    PROF(ctx, PROF_UPDATE, launch_pack_weights(st, params, s.wpack, s.tab));
     const float* block_in = nullptr;
     const float* cur = s.xpad;
     for (int l = 0; l < L; ++l) {
@@ -136,7 +159,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
         const bool is_conv2 = l > 0 && (l % 2 == 0);
         if (l > 0 && !is_conv2) block_in = cur;
         float* y = train ? s.y[l] : take(cur, block_in);
-        PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, params + cb.w_off, y, train ? s.stats : nullptr));
+        PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, train ? s.stats : nullptr));
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         if (train)
             PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
@@ -176,7 +199,7 @@ void resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const flo
                             is_conv2 ? s.g : nullptr));
         PROF(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(st, cs, x_in, s.d1, s.wpart, s.grad + cb.w_off));
         if (l == 0) break;
-        PROF(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.d1, params + cb.w_off, s.d2));
+        PROF(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.d1, s.wpack + s.dgrad_off[l], s.d2));
         if (!is_conv2) {
             // conv1 of a block: add the gradient that bypassed the block through the shortcut
             const ConvBn& c2 = m->layers[l + 1];
