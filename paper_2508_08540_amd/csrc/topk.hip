@@ -55,10 +55,304 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_lds_bitonic_kernel(const fl
     }
 }
 
+// ---- large pools ----------------------------------------------------------------------------------
+//
+// 1. 2048-bin histogram of the top 11 key bits; the bin b* that contains the k-th largest key follows.
+// 2. Every element with bin >= b* (M of them, M >= k, usually M is close to k) is compacted, in index
+//    order, into (sort key, index) arrays; the sort key is ~key so that ascending order is rank order.
+// 3. Stable LSD radix sort of the M pairs by the 32-bit sort key, 8 bits per pass.  Stability keeps
+//    equal losses in ascending index order, which is the tie rule.
+// 4. The first k pairs are the result.
+// Nothing is read back to the host: grids are sized for the worst case M == N and blocks past M exit.
+
+#define SEL_BINS 2048
+#define TILE 2048          // elements per 256-thread block: 8 consecutive elements per thread
+#define SCAN_CHUNK 2048
+
+struct SelInfo {
+    uint32_t bin;    // b*
+    uint32_t M;      // elements with bin >= b*
+};
+
+__global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* p, int64_t n) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void sel_hist_kernel(const float* __restrict__ losses, int64_t N, uint32_t* __restrict__ hist) {
+    __shared__ uint32_t h[SEL_BINS];
+    for (int i = threadIdx.x; i < SEL_BINS; i += 256) h[i] = 0u;
+    __syncthreads();
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride)
+        atomicAdd(&h[loss_key(losses[i]) >> 21], 1u);
+    __syncthreads();
+    for (int i = threadIdx.x; i < SEL_BINS; i += 256)
+        if (h[i]) atomicAdd(&hist[i], h[i]);
+}
+
+// One block: suffix counts over the bins; b* is the largest bin whose suffix count reaches k.
+__global__ __launch_bounds__(256) void sel_threshold_kernel(const uint32_t* __restrict__ hist, uint32_t k, SelInfo* __restrict__ info) {
+    __shared__ uint32_t part[256];
+    uint32_t mine[8], tot = 0;
+    for (int j = 0; j < 8; ++j) {
+        mine[j] = hist[threadIdx.x * 8 + j];
+        tot += mine[j];
+    }
+    part[threadIdx.x] = tot;
+    __syncthreads();
+    // inclusive suffix sum over threads (thread t: bins 8t .. 8t+7)
+    for (int o = 1; o < 256; o <<= 1) {
+        uint32_t add = (threadIdx.x + o < 256) ? part[threadIdx.x + o] : 0u;
+        __syncthreads();
+        part[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t above = part[threadIdx.x] - tot;  // elements in bins of higher threads
+    for (int j = 7; j >= 0; --j) {
+        uint32_t with = above + mine[j];
+        if (above < k && with >= k) {
+            info->bin = threadIdx.x * 8 + j;
+            info->M = with;
+        }
+        above = with;
+    }
+}
+
+__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* total) {
+    __shared__ uint32_t sc[256];
+    sc[threadIdx.x] = v;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+        uint32_t add = threadIdx.x >= (unsigned)o ? sc[threadIdx.x - o] : 0u;
+        __syncthreads();
+        sc[threadIdx.x] += add;
+        __syncthreads();
+    }
+    uint32_t incl = sc[threadIdx.x];
+    if (total) *total = sc[255];
+    __syncthreads();
+    return incl - v;
+}
+
+__global__ __launch_bounds__(256) void sel_count_kernel(const float* __restrict__ losses, int64_t N, const SelInfo* __restrict__ info,
+                                                        uint32_t* __restrict__ counts) {
+    const uint32_t bin = info->bin;
+    int64_t base = (int64_t)blockIdx.x * TILE + threadIdx.x * 8;
+    uint32_t c = 0;
+    for (int j = 0; j < 8; ++j)
+        if (base + j < N && (loss_key(losses[base + j]) >> 21) >= bin) ++c;
+    uint32_t total;
+    block_exclusive_scan_256(c, &total);
+    if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+// counts has been exclusive-scanned into offsets
+__global__ __launch_bounds__(256) void sel_compact_kernel(const float* __restrict__ losses, int64_t N, const SelInfo* __restrict__ info,
+                                                          const uint32_t* __restrict__ offsets, uint32_t* __restrict__ keys,
+                                                          uint32_t* __restrict__ idx) {
+    const uint32_t bin = info->bin;
+    int64_t base = (int64_t)blockIdx.x * TILE + threadIdx.x * 8;
+    uint32_t key[8], c = 0;
+    for (int j = 0; j < 8; ++j) {
+        key[j] = base + j < N ? loss_key(losses[base + j]) : 0u;
+        if (base + j < N && (key[j] >> 21) >= bin) ++c;
+    }
+    uint32_t pos = offsets[blockIdx.x] + block_exclusive_scan_256(c, nullptr);
+    for (int j = 0; j < 8; ++j)
+        if (base + j < N && (key[j] >> 21) >= bin) {
+            keys[pos] = ~key[j];
+            idx[pos] = (uint32_t)(base + j);
+            ++pos;
+        }
+}
+
+// ---- exclusive scan of a uint32 array (three kernels) -------------------------------------------------
+
+__global__ __launch_bounds__(256) void scan_chunk_sums_kernel(const uint32_t* __restrict__ data, int64_t n, uint32_t* __restrict__ sums) {
+    int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + threadIdx.x * 8;
+    uint32_t c = 0;
+    for (int j = 0; j < 8; ++j)
+        if (base + j < n) c += data[base + j];
+    uint32_t total;
+    block_exclusive_scan_256(c, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void scan_sums_kernel(uint32_t* __restrict__ sums, int n_chunks) {
+    uint32_t carry = 0;
+    for (int b0 = 0; b0 < n_chunks; b0 += 256) {
+        int i = b0 + threadIdx.x;
+        uint32_t v = i < n_chunks ? sums[i] : 0u, total;
+        uint32_t ex = block_exclusive_scan_256(v, &total);
+        if (i < n_chunks) sums[i] = carry + ex;
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ data, int64_t n, const uint32_t* __restrict__ sums) {
+    int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + threadIdx.x * 8;
+    uint32_t v[8], c = 0;
+    for (int j = 0; j < 8; ++j) {
+        v[j] = base + j < n ? data[base + j] : 0u;
+        c += v[j];
+    }
+    uint32_t run = sums[blockIdx.x] + block_exclusive_scan_256(c, nullptr);
+    for (int j = 0; j < 8; ++j)
+        if (base + j < n) {
+            data[base + j] = run;
+            run += v[j];
+        }
+}
+
+static void exclusive_scan_u32(hipStream_t s, uint32_t* data, int64_t n, uint32_t* sums) {
+    int n_chunks = (int)((n + SCAN_CHUNK - 1) / SCAN_CHUNK);
+    hipLaunchKernelGGL(scan_chunk_sums_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sums, n_chunks);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums);
+}
+
+// ---- radix sort passes --------------------------------------------------------------------------------
+
+// table[d * n_blocks + b] = number of elements of block b's tile with digit d (zero for tiles past M)
+__global__ __launch_bounds__(256) void radix_count_kernel(const uint32_t* __restrict__ keys, const SelInfo* __restrict__ info,
+                                                          int shift, uint32_t* __restrict__ table, int n_blocks) {
+    __shared__ uint32_t cnt[256];
+    cnt[threadIdx.x] = 0u;
+    __syncthreads();
+    const uint32_t M = info->M;
+    int64_t base = (int64_t)blockIdx.x * TILE;
+    if (base < M)
+        for (int j = 0; j < 8; ++j) {
+            int64_t i = base + j * 256 + threadIdx.x;
+            if (i < M) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u);
+        }
+    __syncthreads();
+    table[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = cnt[threadIdx.x];
+}
+
+// table has been exclusive-scanned: table[d * n_blocks + b] = first output slot of digit d in block b.
+// Each wave owns 512 consecutive elements of the tile and ranks them 64 at a time with ballots, so the
+// order of equal digits is the input order (stable).
+__global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ idx_in,
+                                                            uint32_t* __restrict__ keys_out, uint32_t* __restrict__ idx_out,
+                                                            const SelInfo* __restrict__ info, int shift,
+                                                            const uint32_t* __restrict__ table, int n_blocks) {
+    __shared__ uint32_t cnt[4][256];
+    const uint32_t M = info->M;
+    const int64_t base = (int64_t)blockIdx.x * TILE;
+    if (base >= M) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int w = 0; w < 4; ++w) cnt[w][threadIdx.x] = 0u;
+    __syncthreads();
+    const int64_t wbase = base + wave * 512;
+    uint32_t key[8], id[8];
+    for (int it = 0; it < 8; ++it) {
+        int64_t i = wbase + it * 64 + lane;
+        bool valid = i < M;
+        key[it] = valid ? keys_in[i] : 0u;
+        id[it] = valid ? idx_in[i] : 0u;
+        if (valid) atomicAdd(&cnt[wave][(key[it] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    {   // per digit: turn wave counts into starting slots (global start + counts of lower waves)
+        uint32_t run = table[(int64_t)threadIdx.x * n_blocks + blockIdx.x];
+        for (int w = 0; w < 4; ++w) {
+            uint32_t c = cnt[w][threadIdx.x];
+            cnt[w][threadIdx.x] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    const uint64_t lt = lane ? (~0ull >> (64 - lane)) : 0ull;
+    for (int it = 0; it < 8; ++it) {
+        int64_t i = wbase + it * 64 + lane;
+        bool valid = i < M;
+        uint32_t d = (key[it] >> shift) & 255u;
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            uint64_t v = __ballot((d >> b) & 1u);
+            peers &= ((d >> b) & 1u) ? v : ~v;
+        }
+        if (valid) {
+            uint32_t rank = __popcll(peers & lt);
+            uint32_t pos = cnt[wave][d] + rank;
+            keys_out[pos] = key[it];
+            idx_out[pos] = id[it];
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (valid && (peers & lt) == 0ull) cnt[wave][d] += (uint32_t)__popcll(peers);  // lowest peer advances the slot
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+__global__ __launch_bounds__(256) void topk_emit_kernel(const uint32_t* __restrict__ idx_sorted, const float* __restrict__ losses,
+                                                        int64_t k, int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < k; r += stride) {
+        uint32_t i = idx_sorted[r];
+        idx_out[r] = (int32_t)i;
+        if (val_out) val_out[r] = losses[i];
+    }
+}
+
+struct TopkScratch {
+    uint32_t *hist, *counts, *sums, *table, *keys_a, *idx_a, *keys_b, *idx_b;
+    SelInfo* info;
+    int n_blocks;
+};
+
+static TopkScratch carve_topk(Carver& c, int64_t N) {
+    TopkScratch t;
+    t.n_blocks = (int)((N + TILE - 1) / TILE);
+    t.hist = c.take<uint32_t>(SEL_BINS);
+    t.info = c.take<SelInfo>(1);
+    t.counts = c.take<uint32_t>(t.n_blocks);
+    t.table = c.take<uint32_t>((size_t)256 * t.n_blocks);
+    t.sums = c.take<uint32_t>(((size_t)256 * t.n_blocks + SCAN_CHUNK - 1) / SCAN_CHUNK + 1);
+    t.keys_a = c.take<uint32_t>(N);
+    t.idx_a = c.take<uint32_t>(N);
+    t.keys_b = c.take<uint32_t>(N);
+    t.idx_b = c.take<uint32_t>(N);
+    return t;
+}
+
 size_t topk_scratch_bytes(int64_t N, int64_t k) {
-    (void)N;
     (void)k;
-    return 0;
+    if (N <= TOPK_LDS_MAX) return 0;
+    Carver c(nullptr);
+    carve_topk(c, N);
+    return c.off;
+}
+
+static int launch_topk_large(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
+    int rc = bls_arena_reserve(ctx, topk_scratch_bytes(N, k));
+    if (rc != BLS_OK) return rc;
+    Carver c(ctx->arena);
+    TopkScratch t = carve_topk(c, N);
+    hipStream_t s = ctx->stream;
+    const int nb = t.n_blocks;
+    int hist_blocks = nb < ctx->num_cus * 8 ? nb : ctx->num_cus * 8;
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(8), dim3(256), 0, s, t.hist, (int64_t)SEL_BINS);
+    hipLaunchKernelGGL(sel_hist_kernel, dim3(hist_blocks), dim3(256), 0, s, losses, N, t.hist);
+    hipLaunchKernelGGL(sel_threshold_kernel, dim3(1), dim3(256), 0, s, t.hist, (uint32_t)k, t.info);
+    hipLaunchKernelGGL(sel_count_kernel, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts);
+    exclusive_scan_u32(s, t.counts, nb, t.sums);
+    hipLaunchKernelGGL(sel_compact_kernel, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts, t.keys_a, t.idx_a);
+    uint32_t *ka = t.keys_a, *ia = t.idx_a, *kb = t.keys_b, *ib = t.idx_b;
+    for (int pass = 0; pass < 4; ++pass) {
+        hipLaunchKernelGGL(radix_count_kernel, dim3(nb), dim3(256), 0, s, ka, t.info, pass * 8, t.table, nb);
+        exclusive_scan_u32(s, t.table, (int64_t)256 * nb, t.sums);
+        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nb), dim3(256), 0, s, ka, ia, kb, ib, t.info, pass * 8, t.table, nb);
+        uint32_t* tmp = ka; ka = kb; kb = tmp;
+        tmp = ia; ia = ib; ib = tmp;
+    }
+    int64_t eb = (k + 255) / 256;
+    if (eb > 2048) eb = 2048;
+    hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)eb), dim3(256), 0, s, ia, losses, k, idx_out, val_out);
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
 }
 
 int launch_topk(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
@@ -75,5 +369,5 @@ int launch_topk(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t
         BLS_HIP(ctx, hipGetLastError());
         return BLS_OK;
     }
-    return bls_fail(ctx, BLS_EUNSUPPORTED, "top-k for N > %d is not built yet", TOPK_LDS_MAX);
+    return launch_topk_large(ctx, losses, N, k, idx_out, val_out);
 }

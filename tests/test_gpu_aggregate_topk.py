@@ -116,6 +116,24 @@ def test_topk_matches_oracle_small(env, kind, n):
         _topk_check(torch, bls, ctx, arr, k)
 
 
+@pytest.mark.parametrize("kind", synth.LOSS_ARRAY_KINDS)
+@pytest.mark.parametrize("n", [16385, 50000, 100000, (1 << 20) + 3])
+def test_topk_matches_oracle_large(env, kind, n):
+    # pools beyond one workgroup's LDS: radix select, ordered compaction, stable radix sort
+    torch, bls, ctx = env
+    arr = synth.loss_array(kind, n)
+    for k in sorted({1, n // 4, n}):
+        _topk_check(torch, bls, ctx, arr, k)
+
+
+def test_topk_of_scores_then_smaller_pool(env):
+    # scratch is reused between calls of different sizes
+    torch, bls, ctx = env
+    for n in (70000, 20000, 300, 70001):
+        arr = synth.loss_array("ties16", n, seed=n)
+        _topk_check(torch, bls, ctx, arr, n // 4)
+
+
 def test_topk_rejects_bad_arguments(env):
     torch, bls, ctx = env
     t = torch.zeros(8, device="cuda")
