@@ -24,6 +24,7 @@ int bls_fail(bls_ctx* ctx, int code, const char* fmt, ...) {
 int bls_arena_reserve(bls_ctx* ctx, size_t bytes) {
     if (bytes <= ctx->arena_bytes) return BLS_OK;
     BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->aux) BLS_HIP(ctx, hipStreamSynchronize(ctx->aux));
     if (ctx->arena) BLS_HIP(ctx, hipFree(ctx->arena));
     ctx->arena = nullptr;
     ctx->arena_bytes = 0;
@@ -62,6 +63,11 @@ int bls_ctx_create(bls_ctx** out, int device, void* hip_stream) {
         (size_t)optin > ctx->max_lds)
         ctx->max_lds = (size_t)optin;
     (void)hipGetLastError();
+    if (hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->join_event, hipEventDisableTiming) != hipSuccess) {
+        delete ctx;
+        return BLS_EHIP;
+    }
     *out = ctx;
     return BLS_OK;
 }
@@ -71,6 +77,12 @@ void bls_ctx_destroy(bls_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
     net_release(ctx);
+    if (ctx->aux) {
+        (void)hipStreamSynchronize(ctx->aux);
+        (void)hipStreamDestroy(ctx->aux);
+    }
+    for (hipEvent_t e : ctx->fork_events) (void)hipEventDestroy(e);
+    if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
     if (ctx->arena) (void)hipFree(ctx->arena);
     delete ctx;
 }

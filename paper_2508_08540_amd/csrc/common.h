@@ -22,6 +22,9 @@ struct bls_ctx {
     std::vector<ProfSpan> spans;
     int device = 0;
     hipStream_t stream = nullptr;
+    hipStream_t aux = nullptr;             // library-owned side stream for work off the critical path
+    std::vector<hipEvent_t> fork_events;   // main -> aux dependencies, one per use inside a call
+    hipEvent_t join_event = nullptr;       // aux -> main
     char* arena = nullptr;      // one scratch allocation, grown on demand
     size_t arena_bytes = 0;
     int num_cus = 0;
@@ -43,18 +46,19 @@ struct ProfScope {
     bls_ctx* ctx;
     ProfSpan span;
     bool on;
-    ProfScope(bls_ctx* c, int cls) : ctx(c), on(c->profiling) {
+    hipStream_t st;
+    ProfScope(bls_ctx* c, int cls, hipStream_t stream = nullptr) : ctx(c), on(c->profiling), st(stream ? stream : c->stream) {
         if (!on) return;
         span.cls = cls;
         if (hipEventCreate(&span.start) != hipSuccess || hipEventCreate(&span.stop) != hipSuccess) {
             on = false;
             return;
         }
-        (void)hipEventRecord(span.start, ctx->stream);
+        (void)hipEventRecord(span.start, st);
     }
     ~ProfScope() {
         if (!on) return;
-        (void)hipEventRecord(span.stop, ctx->stream);
+        (void)hipEventRecord(span.stop, st);
         ctx->spans.push_back(span);
     }
 };

@@ -19,6 +19,10 @@
 #include "kernels.h"
 
 #define CONV_THREADS 256
+#ifndef CONV_MT
+#define CONV_MT 2   // 16-pixel tiles a wave accumulates at once
+#define CONV_NW 4   // waves per workgroup of the forward / input-gradient kernel
+#endif
 
 struct ConvGeom {
     int B, h_in, h_out, c_out, stride, ups;  // ups: input is read with zeros inserted (h_in is the virtual size)
@@ -59,7 +63,7 @@ static size_t input_lds_floats(const ConvGeom& g) {
 
 // Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + 4], zero outside the image.
 // `pitch` is the channel count of the tensor in memory and `c_off` the first channel of the CIN-wide slice.
-template <int CIN>
+template <int CIN, int THREADS = CONV_THREADS>
 __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const float* __restrict__ x, const ConvGeom& g,
                                             int tile, int pitch = CIN, int c_off = 0) {
     constexpr int CP = CIN + 4, CQ = CIN / 4;
@@ -67,7 +71,7 @@ __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const floa
     const int row0 = tile * g.rows_tile;
     const int n_pix = g.imgs * g.in_rows * g.lw;
     const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
-    for (int i = threadIdx.x; i < n_pix * CQ; i += CONV_THREADS) {
+    for (int i = threadIdx.x; i < n_pix * CQ; i += THREADS) {
         int cq = i % CQ, pix = i / CQ;
         int lc = pix % g.lw, lr = pix / g.lw;
         int part = lr / g.in_rows, li = lr - part * g.in_rows;
@@ -96,9 +100,13 @@ __device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
 }
 
 // `w` is the packed copy of the layer's weights made by pack_weights_kernel (forward or input-gradient form).
-template <int CIN, int MT>
-__global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                            float* __restrict__ y, float* __restrict__ stats, ConvGeom g) {
+// EPI 0: plain store.  EPI 1: also per-channel sum / sum of squares of the output (batch-norm statistics).
+// EPI 2 (input gradient): the shortcut gradient is added before the store, and the output is masked by
+// the ReLU of the layer below and reduced to the two sums of that layer's batch-norm backward pass.
+// For EPI 1 and 2 every tile writes its partial sums; a small kernel folds them in a fixed order.
+template <int CIN, int MT, int NW, int EPI>
+__global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                            float* __restrict__ y, ConvEpi e, ConvGeom g) {
     extern __shared__ f32x4 lds4[];  // float4-typed so that tile reads and writes are single 16-byte LDS accesses
     float* lds = reinterpret_cast<float*>(lds4);
     constexpr int CP = CIN + 4, S = CIN / 16;
@@ -119,7 +127,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
             for (int s = 0; s < S; ++s) wr[t][s] = wp[(t * S + s) * 64];
     }
 
-    stage_input<CIN>(lds4, x, g, tile);
+    stage_input<CIN, NW * 64>(lds4, x, g, tile);
     __syncthreads();
 
     const int tile_pixels = g.rows_tile << g.wout_log2;
@@ -128,7 +136,7 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
     f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
 
-    for (int mg = wave / NOB; mg < n_groups; mg += 4 / NOB) {
+    for (int mg = wave / NOB; mg < n_groups; mg += NW / NOB) {
         int base[MT];
         f32x4 acc[MT];
 #pragma unroll
@@ -155,14 +163,46 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
         for (int m = 0; m < MT; ++m) {
             int64_t p = pix0 + (mg * MT + m) * 16 + r16;
             if (p < total_pixels) {
-                *reinterpret_cast<f32x4*>(y + p * NO + ob * 16 + 4 * grp) = acc[m];
-                ssum += acc[m];
-                ssq += acc[m] * acc[m];
+                const int c0 = ob * 16 + 4 * grp;
+                f32x4 v = acc[m];
+                if (EPI == 2) {
+                    if (e.sc_g) {
+                        // gradient that bypassed the block below through its shortcut
+                        if (e.sc_stride == 1) {
+                            v += *reinterpret_cast<const f32x4*>(e.sc_g + p * e.sc_c + c0);
+                        } else {
+                            const int wq = (int)(p & (g.h_out - 1));
+                            const int64_t row = p >> g.wout_log2;
+                            const int hq = (int)(row & (g.h_out - 1));
+                            if (((wq | hq) & 1) == 0) {
+                                const int64_t n = row >> g.wout_log2;
+                                const int hs = g.h_out >> 1;
+                                v += *reinterpret_cast<const f32x4*>(e.sc_g + ((n * hs + (hq >> 1)) * hs + (wq >> 1)) * e.sc_c + e.sc_lo + c0);
+                            }
+                        }
+                    }
+                    *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
+                    const f32x4 av = *reinterpret_cast<const f32x4*>(e.a_prev + p * NO + c0);
+                    const f32x4 yv = *reinterpret_cast<const f32x4*>(e.y_prev + p * NO + c0);
+                    const f32x4 mu = *reinterpret_cast<const f32x4*>(e.mean_prev + c0);
+                    const f32x4 is = *reinterpret_cast<const f32x4*>(e.invstd_prev + c0);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float gq = av[j] > 0.f ? v[j] : 0.f;
+                        ssum[j] += gq;
+                        ssq[j] = __fmaf_rn(gq, (yv[j] - mu[j]) * is[j], ssq[j]);
+                    }
+                } else {
+                    *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
+                    ssum += v;
+                    ssq += v * v;
+                }
             }
         }
     }
 
-    if (stats) {
+    if (EPI != 0) {
+        float* stats = e.partials;
         // lanes of one group hold the same 4 channels for 16 different pixels: fold the pixels
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1)
@@ -185,18 +225,29 @@ __global__ __launch_bounds__(CONV_THREADS) void conv_kernel(const float* __restr
             int which = threadIdx.x / NO, c = threadIdx.x % NO;
             int cb = c >> 4;
             float acc = 0.f;
-            for (int wv = cb; wv < 4; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
+            for (int wv = cb; wv < NW; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
             stats[((int64_t)tile * 2 + which) * NO + c] = acc;
         }
     }
 }
 
-template <int CIN>
-static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, float* stats) {
+template <int CIN, int EPI>
+static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e) {
+    constexpr int MT = CONV_MT, NW = CONV_NW;
     size_t lds = input_lds_floats<CIN>(g) * sizeof(float);
-    auto kern = conv_kernel<CIN, 2>;
+    if (EPI != 0 && lds < 1024) lds = 1024;  // per-wave partial sums
+    auto kern = conv_kernel<CIN, MT, NW, EPI>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(CONV_THREADS), lds, s, x, w, y, stats, g);
+    hipLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(NW * 64), lds, s, x, w, y, e, g);
+}
+
+template <int EPI>
+static void launch_conv_c(hipStream_t s, int c_in, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e) {
+    switch (c_in) {
+        case 16: launch_conv_t<16, EPI>(s, g, x, w, y, e); break;
+        case 32: launch_conv_t<32, EPI>(s, g, x, w, y, e); break;
+        default: launch_conv_t<64, EPI>(s, g, x, w, y, e); break;
+    }
 }
 
 // ---- weight packing -----------------------------------------------------------------------------------
@@ -242,31 +293,29 @@ void launch_pack_weights(hipStream_t s, const float* params, float* packed, cons
     hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, params, packed, tab);
 }
 
+int conv_dgrad_tiles(const ConvShape& cs) {
+    return make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, cs.stride == 2 ? 1 : 0, cs.c_in).n_tiles;
+}
+
 int conv_fwd_tiles(const ConvShape& cs) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
 }
 
-void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, float* stats_partials) {
+void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
-    switch (cs.c_in) {
-        case 16: launch_conv_t<16>(s, g, x, w, y, stats_partials); break;
-        case 32: launch_conv_t<32>(s, g, x, w, y, stats_partials); break;
-        default: launch_conv_t<64>(s, g, x, w, y, stats_partials); break;
-    }
+    if (stats) launch_conv_c<1>(s, cs.c_in, g, x, w, y, *stats);
+    else launch_conv_c<0>(s, cs.c_in, g, x, w, y, ConvEpi{});
 }
 
-void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx) {
+void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below) {
     // The gradient with respect to the input is a stride-1 convolution whose input channels are the
     // layer's output channels and whose output channels are the layer's input channels.
     int ups = cs.stride == 2 ? 1 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in);
-    switch (cs.c_out) {
-        case 16: launch_conv_t<16>(s, g, dy, w, dx, nullptr); break;
-        case 32: launch_conv_t<32>(s, g, dy, w, dx, nullptr); break;
-        default: launch_conv_t<64>(s, g, dy, w, dx, nullptr); break;
-    }
+    if (bn_below) launch_conv_c<2>(s, cs.c_out, g, dy, w, dx, *bn_below);
+    else launch_conv_c<0>(s, cs.c_out, g, dy, w, dx, ConvEpi{});
 }
 
 // ---- weight gradient ------------------------------------------------------------------------------
@@ -336,12 +385,12 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
 }
 
 // dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over pixel groups of partial (pg, ob, ib)[(o*9 + t)*16 + i].
-// A block covers 32 outputs; its 8 thread rows take every 8th group and are folded through LDS in row order.
+// A block covers 16 outputs; its 16 thread rows take every 16th group and are folded through LDS in row order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int groups, int NO, int NI,
                                                            int ci_real, float* __restrict__ dw) {
-    __shared__ float red[8][32];
-    const int col = threadIdx.x & 31, row = threadIdx.x >> 5;
-    const int idx = blockIdx.x * 32 + col;
+    __shared__ float red[16][17];
+    const int col = threadIdx.x & 15, row = threadIdx.x >> 4;
+    const int idx = blockIdx.x * 16 + col;
     const bool live = idx < NO * 9 * ci_real;
     float acc = 0.f;
     if (live) {
@@ -350,14 +399,14 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
         int blocks = (NO >> 4) * (NI >> 4);
         int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + ((co & 15) * 9 + t) * 16 + (ci & 15);
         int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
-        for (int p = row; p < groups; p += 8) acc += partials[p * pitch + src];
+        for (int p = row; p < groups; p += 16) acc += partials[p * pitch + src];
     }
     red[row][col] = acc;
     __syncthreads();
     if (row == 0 && live) {
         float v = red[0][col];
 #pragma unroll
-        for (int r = 1; r < 8; ++r) v += red[r][col];
+        for (int r = 1; r < 16; ++r) v += red[r][col];
         dw[idx] = v;
     }
 }
@@ -382,6 +431,6 @@ void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const
     hipLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(CONV_THREADS), lds, s, x, dy, partials, g, tiles_per_group,
                        cs.c_in, cs.c_out);
     int n = cs.c_out * 9 * cs.c_in_real;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 31) / 32), dim3(256), 0, s, partials, groups, cs.c_out, cs.c_in,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, s, partials, groups, cs.c_out, cs.c_in,
                        cs.c_in_real, dw);
 }

@@ -56,10 +56,12 @@ void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const
 int bn_bwd_partials(int64_t pixels);
 void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
                           int64_t pixels, int C, const float* mean, const float* invstd, float* partials);
-// Sums the partials, writes dgamma, dbeta, and dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M); g_out optional.
+// dgamma, dbeta from the partials of launch_bn_bwd_reduce.
+void launch_bn_bwd_finalize(hipStream_t s, const float* partials, int n_partials, int C, float* dgamma, float* dbeta);
+// dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M) with g = dout * (out > 0); g_out (optional) receives g.
 void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const float* partials, int n_partials, float* dgamma, float* dbeta, float* dy, float* g_out);
+                         const float* dgamma, const float* dbeta, float* dy, float* g_out);
 // dx[n][h][w][c] += shortcut_backward(g): identity or stride-2 zero-padded-channel shortcut
 void launch_shortcut_grad_add(hipStream_t s, float* dx, int B, int h_in, int c_in, const float* g, int c_out, int stride);
 
@@ -81,12 +83,23 @@ struct PackTable {
     PackEntry e[PACK_MAX_ENTRIES];
 };
 void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab);
+// Fused epilogue of the convolution kernels (see conv_kernel).  `partials` receives [tiles][2][channels] floats:
+// forward (sum, sum of squares) of the output; input gradient (sum g, sum g*xhat) of the layer below.
+struct ConvEpi {
+    float* partials;
+    // input gradient: shortcut gradient to add (sc_g may be nullptr), then batch-norm backward sums of the layer below
+    const float* sc_g;
+    int sc_c, sc_lo, sc_stride;
+    const float *a_prev, *y_prev, *mean_prev, *invstd_prev;
+};
 int conv_fwd_tiles(const ConvShape& cs);
+int conv_dgrad_tiles(const ConvShape& cs);
 // In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
-// y = conv(x, w); stats_partials (optional) receives per-tile per-channel (sum, sum of squares) of y.
-void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, float* stats_partials);
-// dx = conv_transpose(dy, w)
-void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx);
+// y = conv(x, w); with `stats` the kernel also writes per-tile (sum, sum of squares) of y for launch_bn_finalize.
+void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats);
+// dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also per-tile batch-norm backward sums of the
+// layer that produced x, for launch_bn_bwd_finalize.
+void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below);
 int conv_wgrad_partials(const ConvShape& cs);
 // dw[c_out][3][3][c_in_real] = sum over pixels of dy * shifted x, via partials [n][c_out*9*c_in] reduced in order
 void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials, float* dw);

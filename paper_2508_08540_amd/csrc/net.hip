@@ -64,7 +64,7 @@ struct ResScratch {
     PackTable tab;
     float* xpad;
     int32_t* yb;
-    std::vector<float*> y, a, mean, invstd;  // per layer
+    std::vector<float*> y, a, mean, invstd, dy;  // per layer
     float *stats, *d1, *d2, *g, *bnpart, *wpart, *grad;
     float *loss, *feat, *dlogits, *dfeat;
 };
@@ -95,13 +95,14 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     s.xpad = c.take<float>((size_t)B * hw * hw * PAD_C);
     s.yb = c.take<int32_t>(B);
     s.loss = c.take<float>(B);
-    s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L);
-    int64_t max_act = 0, max_stats = 0, max_wpart = 0;
+    s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L); s.dy.assign(L, nullptr);
+    int64_t max_act = 0, max_stats = 0, max_wpart = 0, max_bnpart = 1024 * 2 * 64;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         max_act = max64(max_act, out_floats(cb, B));
         max_stats = max64(max_stats, (int64_t)conv_fwd_tiles(cs) * 2 * cb.c_out);
+        max_bnpart = max64(max_bnpart, (int64_t)conv_dgrad_tiles(cs) * 2 * cs.c_in);
         max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);  // groups * blocks * 2304
         s.mean[l] = c.take<float>(cb.c_out);
         s.invstd[l] = c.take<float>(cb.c_out);
@@ -110,12 +111,13 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
         for (int l = 0; l < L; ++l) {
             s.y[l] = c.take<float>(out_floats(m->layers[l], B));
             s.a[l] = c.take<float>(out_floats(m->layers[l], B));
+            s.dy[l] = c.take<float>(out_floats(m->layers[l], B));  // kept per layer: the side stream reads it later
         }
         s.stats = c.take<float>(max_stats);
         s.d1 = c.take<float>(max_act);
         s.d2 = c.take<float>(max_act);
         s.g = c.take<float>(max_act);
-        s.bnpart = c.take<float>((size_t)1024 * 2 * 64);
+        s.bnpart = c.take<float>(max_bnpart);
         s.wpart = c.take<float>(max_wpart);
         s.grad = c.take<float>(m->num_params);
         s.feat = c.take<float>((size_t)B * m->final_c);
@@ -159,13 +161,18 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
         const bool is_conv2 = l > 0 && (l % 2 == 0);
         if (l > 0 && !is_conv2) block_in = cur;
         float* y = train ? s.y[l] : take(cur, block_in);
-        PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, train ? s.stats : nullptr));
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
-        if (train)
+        if (train) {
+            // the convolution writes per-tile sums of its output; a one-block kernel turns them into statistics
+            ConvEpi e{};
+            e.partials = s.stats;
+            PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e));
             PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
                                buffers + cb.rmean_off, buffers + cb.rvar_off));
-        else
+        } else {
+            PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, nullptr));
             PROF(ctx, PROF_NORM, launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]));
+        }
         float* a = train ? s.a[l] : take(y, block_in);
         const float* res = nullptr;
         int c_res = cb.c_out, res_stride = 1;
@@ -182,8 +189,16 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
     return cur;
 }
 
-void resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s) {
+// The weight gradients are off the critical path (only the update needs them), so they run on the
+// context's side stream, each after the event that marks its dy as ready; the caller joins the side
+// stream before the update.
+int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s) {
     const int L = (int)m->layers.size();
+    while ((int)ctx->fork_events.size() < L) {
+        hipEvent_t e;
+        BLS_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        ctx->fork_events.push_back(e);
+    }
     const ConvBn& last = m->layers[L - 1];
     const float* dout = s.dfeat;
     int shared = last.h_out * last.h_out;
@@ -193,21 +208,42 @@ void resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const flo
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         const bool is_conv2 = l > 0 && (l % 2 == 0);
         const float* x_in = l == 0 ? s.xpad : s.a[l - 1];
-        PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], s.bnpart));
+        if (l == L - 1) {
+            // top layer: its upstream gradient comes from the head; lower layers get these sums from the
+            // input-gradient kernel of the layer above
+            PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], s.bnpart));
+            PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, bn_bwd_partials(pixels), cb.c_out, s.grad + cb.gamma_off, s.grad + cb.beta_off));
+        }
         PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
-                            s.bnpart, bn_bwd_partials(pixels), s.grad + cb.gamma_off, s.grad + cb.beta_off, s.d1,
-                            is_conv2 ? s.g : nullptr));
-        PROF(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(st, cs, x_in, s.d1, s.wpart, s.grad + cb.w_off));
+                            s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
+        BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
+        BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
+        {
+            ProfScope prof_(ctx, PROF_CONV_WGRAD, ctx->aux);
+            launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wpart, s.grad + cb.w_off);
+        }
         if (l == 0) break;
-        PROF(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.d1, s.wpack + s.dgrad_off[l], s.d2));
-        if (!is_conv2) {
-            // conv1 of a block: add the gradient that bypassed the block through the shortcut
-            const ConvBn& c2 = m->layers[l + 1];
-            PROF(ctx, PROF_NORM, launch_shortcut_grad_add(st, s.d2, B, cb.h_in, cb.c_in, s.g, c2.c_out, cb.stride));
+        {
+            // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
+            // batch-norm backward sums of layer l-1
+            const ConvBn& below = m->layers[l - 1];
+            ConvEpi e{};
+            e.partials = s.bnpart;
+            e.a_prev = s.a[l - 1]; e.y_prev = s.y[l - 1]; e.mean_prev = s.mean[l - 1]; e.invstd_prev = s.invstd[l - 1];
+            if (!is_conv2) {
+                const ConvBn& c2 = m->layers[l + 1];
+                e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
+            }
+            PROF(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e));
+            PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, conv_dgrad_tiles(cs), below.c_out, s.grad + below.gamma_off,
+                                                        s.grad + below.beta_off));
         }
         dout = s.d2;
         shared = 0;
     }
+    BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
+    BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
+    return BLS_OK;
 }
 
 size_t scratch_bytes(const bls_model* m, int B, bool train) {
@@ -284,7 +320,8 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
             PROF(ctx, PROF_HEAD, launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
                                 loss, s.feat, s.dlogits, s.dfeat, inv_b, false));
             PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b));
-            resnet_backward(ctx, st, m, params, B, s);
+            rc = resnet_backward(ctx, st, m, params, B, s);
+            if (rc != BLS_OK) return rc;
             PROF(ctx, PROF_UPDATE, launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay));
         }
     }

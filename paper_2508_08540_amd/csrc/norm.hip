@@ -226,10 +226,13 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
     }
 }
 
+void launch_bn_bwd_finalize(hipStream_t s, const float* partials, int n_partials, int C, float* dgamma, float* dbeta) {
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(C), dim3(256), 0, s, partials, n_partials, C, dgamma, dbeta);
+}
+
 void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const float* partials, int n_partials, float* dgamma, float* dbeta, float* dy, float* g_out) {
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(C), dim3(256), 0, s, partials, n_partials, C, dgamma, dbeta);
+                         const float* dgamma, const float* dbeta, float* dy, float* g_out) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
