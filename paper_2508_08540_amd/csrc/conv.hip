@@ -61,42 +61,63 @@ static size_t input_lds_floats(const ConvGeom& g) {
     return (size_t)g.imgs * g.in_rows * g.lw * (CIN + 4);
 }
 
-// Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + 4], zero outside the image.
+// Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + PAD], zero outside the image.
 // `pitch` is the channel count of the tensor in memory and `c_off` the first channel of the CIN-wide slice.
-template <int CIN, int THREADS = CONV_THREADS>
+// A thread owns one 16-byte column (lc, channel quad) and walks the rows, so the row arithmetic is
+// wave-uniform (scalar unit) and no per-element division is needed; loads are issued six rows at a time.
+template <int CIN, int THREADS = CONV_THREADS, int PAD = 4>
 __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const float* __restrict__ x, const ConvGeom& g,
                                             int tile, int pitch = CIN, int c_off = 0) {
-    constexpr int CP = CIN + 4, CQ = CIN / 4;
+    constexpr int CP4 = (CIN + PAD) / 4, CQ = CIN / 4;
+    constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
+    constexpr int R = 6;
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
-    const int n_pix = g.imgs * g.in_rows * g.lw;
+    const int n_cols = g.lw * CQ;
+    const int rows_total = g.imgs * g.in_rows;
     const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
-    for (int i = threadIdx.x; i < n_pix * CQ; i += THREADS) {
-        int cq = i % CQ, pix = i / CQ;
-        int lc = pix % g.lw, lr = pix / g.lw;
-        int part = lr / g.in_rows, li = lr - part * g.in_rows;
-        int grow = row0 + part * rpi;
-        int n = grow >> g.wout_log2;  // h_out == w_out
-        int h0 = grow & (g.h_out - 1);
-        int hi = h0 * g.stride - 1 + li, wi = lc - 1;
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (n < g.B && hi >= 0 && hi < g.h_in && wi >= 0 && wi < g.h_in) {
-            if (!g.ups) {
-                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + hi) * src_h + wi) * pitch + c_off + cq * 4);
-            } else if (((hi | wi) & 1) == 0) {
-                v = *reinterpret_cast<const f32x4*>(x + (((int64_t)n * src_h + (hi >> 1)) * src_h + (wi >> 1)) * pitch + c_off + cq * 4);
-            }
+    for (int col = threadIdx.x; col < n_cols; col += THREADS) {
+        const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
+        const int wi = lc - 1;
+        bool wok = (unsigned)wi < (unsigned)g.h_in;
+        int wsrc = wi;
+        if (g.ups) {
+            wok = wok && ((wi & 1) == 0);
+            wsrc = wi >> 1;
         }
-        lds4[pix * (CP / 4) + cq] = v;
+        const float* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + c_off + cq * 4;
+        f32x4* dst = lds4 + lc * CP4 + cq;
+        for (int r0 = 0; r0 < rows_total; r0 += R) {
+            f32x4 v[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int lr = r0 + r;                               // wave-uniform
+                const int part = lr / g.in_rows, li = lr - part * g.in_rows;
+                const int grow = row0 + part * rpi;
+                const int n = grow >> g.wout_log2;                   // h_out == w_out
+                const int hi = (grow & (g.h_out - 1)) * g.stride - 1 + li;
+                bool ok = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
+                int hsrc = hi;
+                if (g.ups) {
+                    ok = ok && ((hi & 1) == 0);
+                    hsrc = hi >> 1;
+                }
+                v[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (ok) v[r] = *reinterpret_cast<const f32x4*>(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r0 + r < rows_total) dst[(r0 + r) * g.lw * CP4] = v[r];
+        }
     }
 }
 
 // LDS float offset of the top-left tap of output pixel q (index inside the tile).
-template <int CIN>
+template <int CIN, int PAD = 4>
 __device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
     int rowq = q >> g.wout_log2, col = q & (g.h_out - 1);
     int part = rowq >> g.rpi_log2, r = rowq & ((1 << g.rpi_log2) - 1);
-    return ((part * g.in_rows + r * g.stride) * g.lw + col * g.stride) * (CIN + 4);
+    return ((part * g.in_rows + r * g.stride) * g.lw + col * g.stride) * (CIN + PAD);
 }
 
 // `w` is the packed copy of the layer's weights made by pack_weights_kernel (forward or input-gradient form).
@@ -333,7 +354,9 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
                                                              int NI, int NO) {
     extern __shared__ f32x4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
-    constexpr int CP = 16 + 4, DP = 16;
+    // pixel pitch 16 floats: the four lane groups of a read (4 consecutive pixels x 16 channels) cover the
+    // 32 banks exactly twice, the minimum for 256 bytes
+    constexpr int CP = 16, DP = 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;
     const int NIB = NI >> 4;
@@ -351,7 +374,7 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         __syncthreads();  // previous tile fully consumed
-        stage_input<16>(lds4, x, g, tile, NI, ib * 16);
+        stage_input<16, CONV_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
         const int64_t pix0 = (int64_t)tile * tile_pixels;
         for (int i = threadIdx.x; i < tile_pixels * 4; i += CONV_THREADS) {
             int q = i >> 2, c4 = i & 3;
@@ -364,7 +387,7 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
         for (int qd = wave; qd < tile_pixels / 4; qd += 4) {
             const int q = 4 * qd + grp;
             const float a = lds_dy[q * DP + r16];
-            const int xb = pixel_lds_base<16>(g, q) + r16;
+            const int xb = pixel_lds_base<16, 0>(g, q) + r16;
 #pragma unroll
             for (int t = 0; t < 9; ++t) {
                 const float b = lds_x[xb + ((t / 3) * g.lw + (t % 3)) * CP];
@@ -424,7 +447,7 @@ void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
-    size_t lds = (input_lds_floats<16>(g) + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
+    size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
     if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
