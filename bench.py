@@ -100,7 +100,9 @@ def main():
     dom = max(("conv_fwd", "conv_dgrad", "conv_wgrad"), key=lambda c: prof[c][0])
     dom_ms, dom_cnt = prof[dom]
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
+    symbol = {"conv_fwd": "conv_kernel (forward launches)", "conv_dgrad": "conv_kernel (input-gradient launches)",
+              "conv_wgrad": "wgrad_kernel"}[dom]
+    roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
                 "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2), "launches_per_step": dom_cnt // args.steps}
 

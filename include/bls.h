@@ -99,14 +99,15 @@ const char* bls_last_error(const bls_ctx* ctx);
 /* Blocks until everything enqueued on the context's stream has finished. */
 int bls_ctx_synchronize(bls_ctx* ctx);
 
-/* Optional per-class kernel timing for benchmarks.  Between begin and end every group of launches
- * is bracketed by HIP events on the context's stream (this slows the calls down; do not time
- * throughput while it is on).  bls_profile_end waits for the stream, adds the elapsed time and the
+/* Optional per-class kernel timing for benchmarks.  Between begin and end the convolution kernels carry
+ * start/stop events on their own dispatch (duration of that kernel alone) and every other group of
+ * launches is bracketed by HIP events on the stream it runs on (this slows the calls down; do not
+ * time throughput while it is on).  bls_profile_end waits for the stream, adds the elapsed time and the
  * number of bracketed groups per class into the caller's host arrays (capacity entries each,
  * either may be NULL) and returns the number of classes.  Class order: 0 conv forward, 1 conv input
- * gradient, 2 conv weight gradient (kernel plus its partial-sum reduction), 3 batch norm and
- * shortcut kernels, 4 classifier head, 5 fully connected GEMM, 6 SGD update, 7 batch gather,
- * 8 top-k, 9 aggregation. */
+ * gradient, 2 conv weight gradient kernel, 3 batch norm kernels, 4 classifier head, 5 fully connected
+ * GEMM, 6 SGD update and weight packing, 7 batch gather, 8 top-k, 9 aggregation, 10 reduction of the
+ * weight-gradient partial sums. */
 int bls_profile_begin(bls_ctx* ctx);
 int bls_profile_end(bls_ctx* ctx, double* ms_by_class, int64_t* launches_by_class, int capacity);
 

@@ -16,7 +16,7 @@ DECLARED_SYMBOLS = (
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end",
 )
 PROFILE_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "norm", "head", "gemm", "update", "gather", "topk",
-                   "aggregate")
+                   "aggregate", "wgrad_reduce")
 
 
 class BlsError(RuntimeError):

@@ -10,7 +10,7 @@
 
 // Kernel classes for the optional per-class timing (bls_profile_begin / bls_profile_end).
 enum ProfClass { PROF_CONV_FWD = 0, PROF_CONV_DGRAD, PROF_CONV_WGRAD, PROF_NORM, PROF_HEAD, PROF_GEMM, PROF_UPDATE,
-                 PROF_GATHER, PROF_TOPK, PROF_AGGREGATE, PROF_NUM_CLASSES };
+                 PROF_GATHER, PROF_TOPK, PROF_AGGREGATE, PROF_WGRAD_REDUCE, PROF_NUM_CLASSES };
 
 struct ProfSpan {
     int cls;
@@ -60,6 +60,21 @@ struct ProfScope {
         if (!on) return;
         (void)hipEventRecord(span.stop, st);
         ctx->spans.push_back(span);
+    }
+};
+
+// Timing of exactly one kernel: the events are attached to the dispatch by the launcher.
+struct ProfKernel {
+    bls_ctx* ctx;
+    ProfSpan span;
+    bool on;
+    ProfKernel(bls_ctx* c, int cls) : ctx(c), on(c->profiling) {
+        if (!on) return;
+        span.cls = cls;
+        if (hipEventCreate(&span.start) != hipSuccess || hipEventCreate(&span.stop) != hipSuccess) on = false;
+    }
+    ~ProfKernel() {
+        if (on) ctx->spans.push_back(span);
     }
 };
 

@@ -253,21 +253,24 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
 }
 
 template <int CIN, int EPI>
-static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e) {
+static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e,
+                          const KernelTiming* kt) {
     constexpr int MT = CONV_MT, NW = CONV_NW;
     size_t lds = input_lds_floats<CIN>(g) * sizeof(float);
     if (EPI != 0 && lds < 1024) lds = 1024;  // per-wave partial sums
     auto kern = conv_kernel<CIN, MT, NW, EPI>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(NW * 64), lds, s, x, w, y, e, g);
+    // with timing events the dispatch itself is stamped (start and end of this kernel only)
+    hipExtLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(NW * 64), lds, s, kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, w, y, e, g);
 }
 
 template <int EPI>
-static void launch_conv_c(hipStream_t s, int c_in, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e) {
+static void launch_conv_c(hipStream_t s, int c_in, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e,
+                          const KernelTiming* kt) {
     switch (c_in) {
-        case 16: launch_conv_t<16, EPI>(s, g, x, w, y, e); break;
-        case 32: launch_conv_t<32, EPI>(s, g, x, w, y, e); break;
-        default: launch_conv_t<64, EPI>(s, g, x, w, y, e); break;
+        case 16: launch_conv_t<16, EPI>(s, g, x, w, y, e, kt); break;
+        case 32: launch_conv_t<32, EPI>(s, g, x, w, y, e, kt); break;
+        default: launch_conv_t<64, EPI>(s, g, x, w, y, e, kt); break;
     }
 }
 
@@ -323,20 +326,22 @@ int conv_fwd_tiles(const ConvShape& cs) {
     return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
 }
 
-void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats) {
+void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,
+                     const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
-    if (stats) launch_conv_c<1>(s, cs.c_in, g, x, w, y, *stats);
-    else launch_conv_c<0>(s, cs.c_in, g, x, w, y, ConvEpi{});
+    if (stats) launch_conv_c<1>(s, cs.c_in, g, x, w, y, *stats, kt);
+    else launch_conv_c<0>(s, cs.c_in, g, x, w, y, ConvEpi{}, kt);
 }
 
-void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below) {
+void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below,
+                       const KernelTiming* kt) {
     // The gradient with respect to the input is a stride-1 convolution whose input channels are the
     // layer's output channels and whose output channels are the layer's input channels.
     int ups = cs.stride == 2 ? 1 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in);
-    if (bn_below) launch_conv_c<2>(s, cs.c_out, g, dy, w, dx, *bn_below);
-    else launch_conv_c<0>(s, cs.c_out, g, dy, w, dx, ConvEpi{});
+    if (bn_below) launch_conv_c<2>(s, cs.c_out, g, dy, w, dx, *bn_below, kt);
+    else launch_conv_c<0>(s, cs.c_out, g, dy, w, dx, ConvEpi{}, kt);
 }
 
 // ---- weight gradient ------------------------------------------------------------------------------
@@ -442,7 +447,8 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
 
 int conv_wgrad_partials(const ConvShape& cs) { return wgrad_groups(cs, conv_fwd_tiles(cs)); }
 
-void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials, float* dw) {
+void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials,
+                       const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
     int groups = wgrad_groups(cs, g.n_tiles);
@@ -451,8 +457,12 @@ void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const
     if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(CONV_THREADS), lds, s, x, dy, partials, g, tiles_per_group,
-                       cs.c_in, cs.c_out);
+    hipExtLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(CONV_THREADS), lds, s, kt ? kt->start : nullptr,
+                          kt ? kt->stop : nullptr, 0, x, dy, partials, g, tiles_per_group, cs.c_in, cs.c_out);
+}
+
+void launch_conv_wgrad_reduce(hipStream_t s, const ConvShape& cs, const float* partials, float* dw) {
+    int groups = conv_wgrad_partials(cs);
     int n = cs.c_out * 9 * cs.c_in_real;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, s, partials, groups, cs.c_out, cs.c_in,
                        cs.c_in_real, dw);

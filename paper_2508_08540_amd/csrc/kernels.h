@@ -2,9 +2,15 @@
 // shapes are validated by the callers in net.hip before any launch.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Optional pair of events that a launcher attaches to its kernel dispatch (start and end of that kernel).
+struct KernelTiming {
+    hipEvent_t start, stop;
+};
 
 // ---- elementwise.hip ----------------------------------------------------------------------------
 // dst[b][0..row) = src[idx[(start + b) % k]][0..row_src) zero-padded to `row` floats per `group`:
@@ -96,10 +102,15 @@ int conv_fwd_tiles(const ConvShape& cs);
 int conv_dgrad_tiles(const ConvShape& cs);
 // In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
 // y = conv(x, w); with `stats` the kernel also writes per-tile (sum, sum of squares) of y for launch_bn_finalize.
-void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats);
+void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,
+                     const KernelTiming* kt = nullptr);
 // dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also per-tile batch-norm backward sums of the
 // layer that produced x, for launch_bn_bwd_finalize.
-void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below);
+void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below,
+                       const KernelTiming* kt = nullptr);
 int conv_wgrad_partials(const ConvShape& cs);
-// dw[c_out][3][3][c_in_real] = sum over pixels of dy * shifted x, via partials [n][c_out*9*c_in] reduced in order
-void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials, float* dw);
+// partials[groups][c_out/16][c_in/16][2304] = per pixel group sums of dy * shifted x ...
+void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials,
+                       const KernelTiming* kt = nullptr);
+// ... and dw[c_out][3][3][c_in_real] = their sum over the groups, in group order.
+void launch_conv_wgrad_reduce(hipStream_t s, const ConvShape& cs, const float* partials, float* dw);

@@ -4,6 +4,15 @@
 
 #include "kernels.h"
 
+// Runs `call` with a KernelTiming* named kt that is non-null while profiling is on.
+#define PROF_KERNEL(ctx, cls, call)                                   \
+    do {                                                              \
+        ProfKernel pk_(ctx, cls);                                     \
+        KernelTiming kt_{pk_.span.start, pk_.span.stop};              \
+        const KernelTiming* kt = pk_.on ? &kt_ : nullptr;             \
+        call;                                                         \
+    } while (0)
+
 #define PROF(ctx, cls, call) \
     do {                     \
         ProfScope prof_(ctx, cls); \
@@ -166,11 +175,11 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             // the convolution writes per-tile sums of its output; a one-block kernel turns them into statistics
             ConvEpi e{};
             e.partials = s.stats;
-            PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e));
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
             PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
                                buffers + cb.rmean_off, buffers + cb.rvar_off));
         } else {
-            PROF(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, nullptr));
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, nullptr, kt));
             PROF(ctx, PROF_NORM, launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]));
         }
         float* a = train ? s.a[l] : take(y, block_in);
@@ -218,9 +227,10 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                             s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
         BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
         BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
+        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wpart, kt));
         {
-            ProfScope prof_(ctx, PROF_CONV_WGRAD, ctx->aux);
-            launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wpart, s.grad + cb.w_off);
+            ProfScope prof_(ctx, PROF_WGRAD_REDUCE, ctx->aux);
+            launch_conv_wgrad_reduce(ctx->aux, cs, s.wpart, s.grad + cb.w_off);
         }
         if (l == 0) break;
         {
@@ -234,7 +244,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                 const ConvBn& c2 = m->layers[l + 1];
                 e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
             }
-            PROF(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e));
+            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e, kt));
             PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, conv_dgrad_tiles(cs), below.c_out, s.grad + below.gamma_off,
                                                         s.grad + below.beta_off));
         }
