@@ -56,23 +56,25 @@ def assert_tensors_close(got, ref, tol=1e-4, what=""):
     assert not worst, (what, worst)
 
 
-def assert_grads_match_up_to_relu_ties(probe, got, tol=1e-4, rel_margin=1e-5, max_units=32, what="gradients"):
+def assert_grads_match_up_to_relu_ties(probe, got, tol=1e-4, rel_margin=1e-5, max_units=32, what="gradients",
+                                       tensors=None, relus=None):
     """Gradients must match the oracle's per tensor (norm-wise `tol`).
 
     A ReLU unit whose fp64 pre-activation lies within rel_margin * rms of zero can land on either
     side of the kink in fp32; both one-sided derivatives are valid there.  If the plain comparison
     fails, the oracle's decisions for exactly those units (found from the oracle's own forward pass)
     are inverted one at a time, keeping an inversion when it brings the oracle closer; the result
-    must then match at `tol`.  Units outside the margin are never touched.
+    must then match at `tol`.  Units outside the margin are never touched.  `tensors` restricts the
+    comparison to some gradient tensors and `relus` the search to the ReLUs that can influence them.
     """
     def worst(ref):
-        return max(rel_err(got[k], ref[k]) for k in ref)
+        return max(rel_err(got[k], ref[k]) for k in ref if tensors is None or k in tensors)
 
     ref = probe.grads()
     best = worst(ref)
     if best <= tol:
         return 0
-    units = probe.near_zero_units(rel_margin)
+    units = [u for u in probe.near_zero_units(rel_margin) if relus is None or u[0] in relus]
     assert units, (what, "no ReLU unit near zero, yet error", best)
     assert len(units) <= max_units, (what, "too many near-zero units to search", len(units))
     toggles, flipped = {}, 0
