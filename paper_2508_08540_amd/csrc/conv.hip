@@ -40,10 +40,10 @@ static inline int ilog2(int v) {
     return l;
 }
 
-static ConvGeom make_geom(int B, int h_in, int h_out, int c_out, int stride, int ups, int w_ci) {
+static ConvGeom make_geom(int B, int h_in, int h_out, int c_out, int stride, int ups, int w_ci, int rows_tile = 0) {
     ConvGeom g;
     g.B = B; g.h_in = h_in; g.h_out = h_out; g.c_out = c_out; g.stride = stride; g.ups = ups;
-    g.rows_tile = h_out >= 8 ? 4 : 32 / h_out;
+    g.rows_tile = rows_tile ? rows_tile : (h_out >= 8 ? 4 : 32 / h_out);
     int rpi = h_out < g.rows_tile ? h_out : g.rows_tile;
     g.rpi_log2 = ilog2(rpi);
     g.imgs = g.rows_tile / rpi;
@@ -112,6 +112,58 @@ __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const floa
     }
 }
 
+// The same staging split in two for software pipelining: tile_load issues the global loads of a tile into
+// registers (column per thread, up to PRE_ROWS rows), tile_store writes them to an LDS buffer later.
+#define PRE_ROWS 12
+template <int CIN, int PAD = 4>
+__device__ __forceinline__ void tile_load(f32x4 (&v)[PRE_ROWS], const float* __restrict__ x, const ConvGeom& g, int tile,
+                                          int pitch = CIN, int c_off = 0) {
+    constexpr int CQ = CIN / 4;
+    constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
+    const int rpi = 1 << g.rpi_log2;
+    const int row0 = tile * g.rows_tile;
+    const int rows_total = g.imgs * g.in_rows;
+    const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
+    const int col = threadIdx.x;
+    const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
+    const int wi = lc - 1;
+    bool wok = col < g.lw * CQ && (unsigned)wi < (unsigned)g.h_in;
+    int wsrc = wi;
+    if (g.ups) {
+        wok = wok && ((wi & 1) == 0);
+        wsrc = wi >> 1;
+    }
+    const float* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + c_off + cq * 4;
+#pragma unroll
+    for (int r = 0; r < PRE_ROWS; ++r) {
+        const int part = r / g.in_rows, li = r - part * g.in_rows;  // wave-uniform
+        const int grow = row0 + part * rpi;
+        const int n = grow >> g.wout_log2;
+        const int hi = (grow & (g.h_out - 1)) * g.stride - 1 + li;
+        bool ok = r < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
+        int hsrc = hi;
+        if (g.ups) {
+            ok = ok && ((hi & 1) == 0);
+            hsrc = hi >> 1;
+        }
+        v[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (ok) v[r] = *reinterpret_cast<const f32x4*>(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
+    }
+}
+
+template <int CIN, int PAD = 4>
+__device__ __forceinline__ void tile_store(const f32x4 (&v)[PRE_ROWS], f32x4* __restrict__ lds4, const ConvGeom& g) {
+    constexpr int CP4 = (CIN + PAD) / 4, CQ = CIN / 4;
+    constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
+    const int col = threadIdx.x;
+    if (col >= g.lw * CQ) return;
+    const int rows_total = g.imgs * g.in_rows;
+    f32x4* dst = lds4 + (col >> CQ_LOG2) * CP4 + (col & (CQ - 1));
+#pragma unroll
+    for (int r = 0; r < PRE_ROWS; ++r)
+        if (r < rows_total) dst[r * g.lw * CP4] = v[r];
+}
+
 // LDS float offset of the top-left tap of output pixel q (index inside the tile).
 template <int CIN, int PAD = 4>
 __device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
@@ -120,43 +172,19 @@ __device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
     return ((part * g.in_rows + r * g.stride) * g.lw + col * g.stride) * (CIN + PAD);
 }
 
-// `w` is the packed copy of the layer's weights made by pack_weights_kernel (forward or input-gradient form).
-// EPI 0: plain store.  EPI 1: also per-channel sum / sum of squares of the output (batch-norm statistics).
-// EPI 2 (input gradient): the shortcut gradient is added before the store, and the output is masked by
-// the ReLU of the layer below and reduced to the two sums of that layer's batch-norm backward pass.
-// For EPI 1 and 2 every tile writes its partial sums; a small kernel folds them in a fixed order.
+// MFMAs, epilogue and store of one staged tile for this wave.
 template <int CIN, int MT, int NW, int EPI>
-__global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                            float* __restrict__ y, ConvEpi e, ConvGeom g) {
-    extern __shared__ f32x4 lds4[];  // float4-typed so that tile reads and writes are single 16-byte LDS accesses
-    float* lds = reinterpret_cast<float*>(lds4);
+__device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const f32x4 (&wr)[9][CIN / 16], float* __restrict__ y,
+                                          const ConvEpi& e, const ConvGeom& g, int tile, f32x4& ssum, f32x4& ssq) {
     constexpr int CP = CIN + 4, S = CIN / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;
     const int NO = g.c_out, NOB = NO >> 4;
     const int ob = wave % NOB;
-    const int tile = blockIdx.x;
-
-    // weights of output-channel block `ob` into registers: wr[tap][s] holds input channels 16s+4grp .. +3 of
-    // output channel 16*ob + r16, read from the lane-major packed copy (one contiguous 1 KB load each)
-    f32x4 wr[9][S];
-    {
-        const f32x4* wp = reinterpret_cast<const f32x4*>(w) + (int64_t)ob * 9 * S * 64 + lane;
-#pragma unroll
-        for (int t = 0; t < 9; ++t)
-#pragma unroll
-            for (int s = 0; s < S; ++s) wr[t][s] = wp[(t * S + s) * 64];
-    }
-
-    stage_input<CIN, NW * 64>(lds4, x, g, tile);
-    __syncthreads();
-
     const int tile_pixels = g.rows_tile << g.wout_log2;
     const int n_groups = tile_pixels / (16 * MT);
     const int64_t pix0 = (int64_t)tile * tile_pixels;
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
-    f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
-
     for (int mg = wave / NOB; mg < n_groups; mg += NW / NOB) {
         int base[MT];
         f32x4 acc[MT];
@@ -221,6 +249,62 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
             }
         }
     }
+}
+
+// `w` is the packed copy of the layer's weights made by pack_weights_kernel (forward or input-gradient form).
+// EPI 0: plain store.  EPI 1: also per-channel sum / sum of squares of the output (batch-norm statistics).
+// EPI 2 (input gradient): the shortcut gradient is added before the store, and the output is masked by
+// the ReLU of the layer below and reduced to the two sums of that layer's batch-norm backward pass.
+// For EPI 1 and 2 every workgroup writes one row of partial sums; a small kernel folds them in a fixed order.
+//
+// The grid is persistent: workgroup b handles tiles b, b + gridDim.x, ...  While the MFMAs of one tile
+// run from one LDS buffer, the global loads of the next tile are in flight into registers and are then
+// written to the other buffer (one barrier per tile).
+template <int CIN, int MT, int NW, int EPI>
+__global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                            float* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
+    extern __shared__ f32x4 lds4[];  // float4-typed so that tile reads and writes are single 16-byte LDS accesses
+    float* lds = reinterpret_cast<float*>(lds4);
+    constexpr int S = CIN / 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, grp = lane >> 4;
+    const int NO = g.c_out, NOB = NO >> 4;
+    const int ob = wave % NOB;
+
+    // weights of output-channel block `ob` into registers: wr[tap][s] holds input channels 16s+4grp .. +3 of
+    // output channel 16*ob + r16, read from the lane-major packed copy (one contiguous 1 KB load each)
+    f32x4 wr[9][S];
+    {
+        const f32x4* wp = reinterpret_cast<const f32x4*>(w) + (int64_t)ob * 9 * S * 64 + lane;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int s = 0; s < S; ++s) wr[t][s] = wp[(t * S + s) * 64];
+    }
+    f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
+
+    if (pipelined) {
+        const int buf_f4 = g.imgs * g.in_rows * g.lw * ((CIN + 4) / 4);
+        f32x4 pre[PRE_ROWS];
+        int tile = blockIdx.x;
+        tile_load<CIN>(pre, x, g, tile);
+        tile_store<CIN>(pre, lds4, g);
+        __syncthreads();
+        for (int it = 0; tile < g.n_tiles; ++it, tile += gridDim.x) {
+            const int next = tile + gridDim.x;
+            if (next < g.n_tiles) tile_load<CIN>(pre, x, g, next);
+            conv_tile<CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
+            if (next < g.n_tiles) tile_store<CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
+            __syncthreads();
+        }
+    } else {
+        for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
+            stage_input<CIN, NW * 64>(lds4, x, g, tile);
+            __syncthreads();
+            conv_tile<CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
+            __syncthreads();
+        }
+    }
 
     if (EPI != 0) {
         float* stats = e.partials;
@@ -232,8 +316,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
                 ssum[j] += __shfl_xor(ssum[j], o, 64);
                 ssq[j] += __shfl_xor(ssq[j], o, 64);
             }
-        __syncthreads();  // all waves are done reading the input tile; reuse LDS
-        float* red = lds;  // [wave][2][16]
+        float* red = lds;  // [wave][2][16]; every wave is past its last tile read (barrier above)
         if (r16 == 0) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -247,21 +330,32 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
             int cb = c >> 4;
             float acc = 0.f;
             for (int wv = cb; wv < NW; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
-            stats[((int64_t)tile * 2 + which) * NO + c] = acc;
+            stats[((int64_t)blockIdx.x * 2 + which) * NO + c] = acc;
         }
     }
 }
+
+// Workgroups per launch: at most CONV_GRID_CAP (two per compute unit on a 256-CU part).
+#ifndef CONV_GRID_CAP
+#define CONV_GRID_CAP 512
+#endif
+static int conv_grid(const ConvGeom& g) { return g.n_tiles < CONV_GRID_CAP ? g.n_tiles : CONV_GRID_CAP; }
 
 template <int CIN, int EPI>
 static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e,
                           const KernelTiming* kt) {
     constexpr int MT = CONV_MT, NW = CONV_NW;
-    size_t lds = input_lds_floats<CIN>(g) * sizeof(float);
+    const int grid = conv_grid(g);
+    // prefetching needs the whole tile in PRE_ROWS registers per thread, one column per thread, and more
+    // than one tile per workgroup to pay off
+    const int pipelined = (g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
+    size_t lds = input_lds_floats<CIN>(g) * sizeof(float) * (pipelined ? 2 : 1);
     if (EPI != 0 && lds < 1024) lds = 1024;  // per-wave partial sums
     auto kern = conv_kernel<CIN, MT, NW, EPI>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)
-    hipExtLaunchKernelGGL(kern, dim3(g.n_tiles), dim3(NW * 64), lds, s, kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, w, y, e, g);
+    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, s, kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, w, y, e, g,
+                          pipelined);
 }
 
 template <int EPI>
@@ -317,8 +411,13 @@ void launch_pack_weights(hipStream_t s, const float* params, float* packed, cons
     hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, params, packed, tab);
 }
 
-int conv_dgrad_tiles(const ConvShape& cs) {
-    return make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, cs.stride == 2 ? 1 : 0, cs.c_in).n_tiles;
+int conv_dgrad_partials(const ConvShape& cs) {
+    return conv_grid(make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, cs.stride == 2 ? 1 : 0, cs.c_in));
+}
+
+int conv_fwd_partials(const ConvShape& cs) {
+    int h_out = (cs.h_in - 1) / cs.stride + 1;
+    return conv_grid(make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real));
 }
 
 int conv_fwd_tiles(const ConvShape& cs) {
@@ -439,18 +538,30 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     }
 }
 
+// Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller
+// when the staged 16-channel input slice would exceed 40 KB of LDS.
+static ConvGeom wgrad_geom(const ConvShape& cs) {
+    int h_out = (cs.h_in - 1) / cs.stride + 1;
+    int rows = 256 / h_out;
+    if (rows < 4) rows = 4;
+    for (;;) {
+        ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows);
+        if ((size_t)g.imgs * g.in_rows * g.lw * 16 * sizeof(float) <= 40960 || rows * h_out <= 32) return g;
+        rows >>= 1;
+    }
+}
+
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    int cap = 512 / blocks;
+    int cap = 1024 / blocks;
     return n_tiles < cap ? n_tiles : cap;
 }
 
-int conv_wgrad_partials(const ConvShape& cs) { return wgrad_groups(cs, conv_fwd_tiles(cs)); }
+int conv_wgrad_partials(const ConvShape& cs) { return wgrad_groups(cs, wgrad_geom(cs).n_tiles); }
 
 void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials,
                        const KernelTiming* kt) {
-    int h_out = (cs.h_in - 1) / cs.stride + 1;
-    ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
+    ConvGeom g = wgrad_geom(cs);
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);

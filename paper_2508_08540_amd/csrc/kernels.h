@@ -89,7 +89,7 @@ struct PackTable {
     PackEntry e[PACK_MAX_ENTRIES];
 };
 void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab);
-// Fused epilogue of the convolution kernels (see conv_kernel).  `partials` receives [tiles][2][channels] floats:
+// Fused epilogue of the convolution kernels (see conv_kernel).  `partials` receives [workgroups][2][channels] floats:
 // forward (sum, sum of squares) of the output; input gradient (sum g, sum g*xhat) of the layer below.
 struct ConvEpi {
     float* partials;
@@ -99,7 +99,9 @@ struct ConvEpi {
     const float *a_prev, *y_prev, *mean_prev, *invstd_prev;
 };
 int conv_fwd_tiles(const ConvShape& cs);
-int conv_dgrad_tiles(const ConvShape& cs);
+// rows of partial sums the fused epilogues write (one per workgroup of the persistent grid)
+int conv_fwd_partials(const ConvShape& cs);
+int conv_dgrad_partials(const ConvShape& cs);
 // In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
 // y = conv(x, w); with `stats` the kernel also writes per-tile (sum, sum of squares) of y for launch_bn_finalize.
 void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,

@@ -110,8 +110,8 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         max_act = max64(max_act, out_floats(cb, B));
-        max_stats = max64(max_stats, (int64_t)conv_fwd_tiles(cs) * 2 * cb.c_out);
-        max_bnpart = max64(max_bnpart, (int64_t)conv_dgrad_tiles(cs) * 2 * cs.c_in);
+        max_stats = max64(max_stats, (int64_t)conv_fwd_partials(cs) * 2 * cb.c_out);
+        max_bnpart = max64(max_bnpart, (int64_t)conv_dgrad_partials(cs) * 2 * cs.c_in);
         max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);  // groups * blocks * 2304
         s.mean[l] = c.take<float>(cb.c_out);
         s.invstd[l] = c.take<float>(cb.c_out);
@@ -176,7 +176,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             ConvEpi e{};
             e.partials = s.stats;
             PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
-            PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_tiles(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
+            PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_partials(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
                                buffers + cb.rmean_off, buffers + cb.rvar_off));
         } else {
             PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, nullptr, kt));
@@ -245,7 +245,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                 e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
             }
             PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e, kt));
-            PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, conv_dgrad_tiles(cs), below.c_out, s.grad + below.gamma_off,
+            PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, conv_dgrad_partials(cs), below.c_out, s.grad + below.gamma_off,
                                                         s.grad + below.beta_off));
         }
         dout = s.d2;
