@@ -447,15 +447,17 @@ void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, cons
 //
 // Workgroup (pg, ob, ib) owns the 16x16 block (output channels 16*ob.., input channels 16*ib..) of dW
 // for all 9 taps over pixel group pg.  It stages only those 16-channel slices of x and dy, its four
-// waves take every 4th pixel quad, fold their 9 accumulators through LDS in wave order and write one
-// 2304-float partial.  All layer shapes therefore run the same code, the grid has
-// groups * (C_out/16) * (C_in/16) workgroups, and the partial traffic stays near 5 MB per layer.
+// waves take output rows in turn (9 MFMAs per pixel quad), fold their 9 accumulators through LDS in
+// wave order and write one 2304-float partial.  All layer shapes run the same code; the grid has
+// groups * (C_out/16) * (C_in/16) workgroups and the partial traffic stays near 5 MB per layer.
 
 #define WG_BLOCK_FLOATS (16 * 9 * 16)
 
-__global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
-                                                             float* __restrict__ partials, ConvGeom g, int tiles_per_group,
-                                                             int NI, int NO) {
+#define WGRAD_THREADS 256
+
+__global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+                                                              float* __restrict__ partials, ConvGeom g, int tiles_per_group,
+                                                              int NI, int NO) {
     extern __shared__ f32x4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
     // pixel pitch 16 floats: the four lane groups of a read (4 consecutive pixels x 16 channels) cover the
@@ -465,6 +467,7 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
     const int r16 = lane & 15, grp = lane >> 4;
     const int NIB = NI >> 4;
     const int ob = blockIdx.y / NIB, ib = blockIdx.y - ob * NIB;
+    const int w_out = g.h_out;
     const int tile_pixels = g.rows_tile << g.wout_log2;
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
     float* lds_x = lds;
@@ -478,40 +481,61 @@ __global__ __launch_bounds__(CONV_THREADS) void wgrad_kernel(const float* __rest
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         __syncthreads();  // previous tile fully consumed
-        stage_input<16, CONV_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
+        stage_input<16, WGRAD_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
         const int64_t pix0 = (int64_t)tile * tile_pixels;
-        for (int i = threadIdx.x; i < tile_pixels * 4; i += CONV_THREADS) {
+        for (int i = threadIdx.x; i < tile_pixels * 4; i += WGRAD_THREADS) {
             int q = i >> 2, c4 = i & 3;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (pix0 + q < total_pixels) v = *reinterpret_cast<const f32x4*>(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
             reinterpret_cast<f32x4*>(lds_dy)[q * (DP / 4) + c4] = v;
         }
         __syncthreads();
-        // one MFMA consumes 4 pixels (one per lane group); this wave takes every 4th quad
-        for (int qd = wave; qd < tile_pixels / 4; qd += 4) {
-            const int q = 4 * qd + grp;
-            const float a = lds_dy[q * DP + r16];
-            const int xb = pixel_lds_base<16, 0>(g, q) + r16;
+        // One MFMA consumes 4 pixels (one per lane group).
+        if (w_out >= 4) {
+            // a quad lies inside one output row: the waves take rows in turn and the row base is wave-uniform
+            const int lane_x = grp * g.stride * CP + r16, lane_dy = grp * DP + r16;
+            for (int row = wave; row < g.rows_tile; row += 4) {
+                const int part = row >> g.rpi_log2, r = row & ((1 << g.rpi_log2) - 1);
+                const float* xr = lds_x + (part * g.in_rows + r * g.stride) * g.lw * CP + lane_x;
+                const float* dr = lds_dy + (row << g.wout_log2) * DP + lane_dy;
+#pragma unroll 2
+                for (int qc = 0; qc < (w_out >> 2); ++qc) {
+                    const float a = dr[qc * 4 * DP];
+                    const float* xq = xr + qc * 4 * g.stride * CP;
 #pragma unroll
-            for (int t = 0; t < 9; ++t) {
-                const float b = lds_x[xb + ((t / 3) * g.lw + (t % 3)) * CP];
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[t], 0, 0, 0);
+                    for (int t = 0; t < 9; ++t) {
+                        const float b = xq[((t / 3) * g.lw + (t % 3)) * CP];
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[t], 0, 0, 0);
+                    }
+                }
+            }
+        } else {
+            for (int qd = wave; qd < tile_pixels / 4; qd += 4) {
+                const int q = 4 * qd + grp;
+                const float a = lds_dy[q * DP + r16];
+                const int xb = pixel_lds_base<16, 0>(g, q) + r16;
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const float b = lds_x[xb + ((t / 3) * g.lw + (t % 3)) * CP];
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[t], 0, 0, 0);
+                }
             }
         }
     }
-    // fold the four waves in wave order; element (o*9 + t)*16 + i of the block
+    // Fold the four waves in wave order.  LDS and the partial are lane-major, element (t*4 + j)*64 + lane
+    // holds dW[o = 4*(lane/16) + j][t][i = lane%16] of the block: conflict-free writes, coalesced stores.
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < 9; ++t)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) lds[wave * WG_BLOCK_FLOATS + ((4 * grp + j) * 9 + t) * 16 + r16] = acc[t][j];
+        for (int j = 0; j < 4; ++j) lds[wave * WG_BLOCK_FLOATS + (t * 4 + j) * 64 + lane] = acc[t][j];
     __syncthreads();
     float* out = partials + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * WG_BLOCK_FLOATS;
-    for (int e = threadIdx.x; e < WG_BLOCK_FLOATS; e += CONV_THREADS)
+    for (int e = threadIdx.x; e < WG_BLOCK_FLOATS; e += WGRAD_THREADS)
         out[e] = ((lds[e] + lds[WG_BLOCK_FLOATS + e]) + lds[2 * WG_BLOCK_FLOATS + e]) + lds[3 * WG_BLOCK_FLOATS + e];
 }
 
-// dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over pixel groups of partial (pg, ob, ib)[(o*9 + t)*16 + i].
+// dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over pixel groups of partial (pg, ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i].
 // A block covers 16 outputs; its 16 thread rows take every 16th group and are folded through LDS in row order.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int groups, int NO, int NI,
                                                            int ci_real, float* __restrict__ dw) {
@@ -524,7 +548,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
         int ot = idx / ci_real, ci = idx - ot * ci_real;
         int co = ot / 9, t = ot - co * 9;
         int blocks = (NO >> 4) * (NI >> 4);
-        int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + ((co & 15) * 9 + t) * 16 + (ci & 15);
+        int o = co & 15;
+        int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
         int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
         for (int p = row; p < groups; p += 16) acc += partials[p * pitch + src];
     }
@@ -565,10 +590,10 @@ void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
-    if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipExtLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(CONV_THREADS), lds, s, kt ? kt->start : nullptr,
+    hipExtLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
                           kt ? kt->stop : nullptr, 0, x, dy, partials, g, tiles_per_group, cs.c_in, cs.c_out);
 }
 

@@ -11,21 +11,35 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+// PER_LANE = ceil(F / 64) is a template parameter so that the feature slice stays in registers.
+template <int PER_LANE>
 __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restrict__ act, int positions, int F,
                                                           const float* __restrict__ W, const float* __restrict__ bias,
                                                           int C, const int32_t* __restrict__ y, float* __restrict__ loss,
                                                           float* __restrict__ feat, float* __restrict__ dlogits,
                                                           float* __restrict__ dfeat, float grad_scale, int relu_mask) {
     const int b = blockIdx.x, lane = threadIdx.x;
-    const int per_lane = (F + 63) / 64;
-    float f[HEAD_MAX_F_PER_LANE];
+    constexpr int per_lane = PER_LANE;
+    float f[PER_LANE];
     const float inv_pos = 1.f / (float)positions;
     const float* a = act + (int64_t)b * positions * F;
+#pragma unroll
     for (int i = 0; i < per_lane; ++i) {
         int c = lane + 64 * i;
         float acc = 0.f;
-        if (c < F)
-            for (int p = 0; p < positions; ++p) acc += a[(int64_t)p * F + c];
+        if (c < F) {
+            // four independent partial sums keep several loads in flight; they are combined in a fixed order
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int p = 0;
+            for (; p + 3 < positions; p += 4) {
+                s0 += a[(int64_t)p * F + c];
+                s1 += a[(int64_t)(p + 1) * F + c];
+                s2 += a[(int64_t)(p + 2) * F + c];
+                s3 += a[(int64_t)(p + 3) * F + c];
+            }
+            for (; p < positions; ++p) s0 += a[(int64_t)p * F + c];
+            acc = (s0 + s1) + (s2 + s3);
+        }
         f[i] = acc * inv_pos;
         if (feat && c < F) feat[(int64_t)b * F + c] = f[i];
     }
@@ -33,6 +47,7 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restric
     float z_mine = -INFINITY;
     for (int c = 0; c < C; ++c) {
         float part = 0.f;
+#pragma unroll
         for (int i = 0; i < per_lane; ++i) {
             int k = lane + 64 * i;
             if (k < F) part = __fmaf_rn(f[i], W[(int64_t)c * F + k], part);
@@ -52,6 +67,7 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restric
     float dz = lane < C ? (e / sum - (lane == label ? 1.f : 0.f)) * grad_scale : 0.f;
     if (lane < C) dlogits[(int64_t)b * C + lane] = dz;
     if (!dfeat) return;
+#pragma unroll
     for (int i = 0; i < per_lane; ++i) {
         int k = lane + 64 * i;
         float acc = 0.f;
@@ -70,27 +86,44 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restric
 void launch_head_forward(hipStream_t s, const float* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
                          float grad_scale, bool relu_mask) {
-    hipLaunchKernelGGL(head_forward_kernel, dim3(B), dim3(64), 0, s, act, positions, F, W, bias, C, y, loss, feat, dlogits,
-                       dfeat, grad_scale, relu_mask ? 1 : 0);
+#define HEAD_LAUNCH(PL)                                                                                                    \
+    hipLaunchKernelGGL(head_forward_kernel<PL>, dim3(B), dim3(64), 0, s, act, positions, F, W, bias, C, y, loss, feat, dlogits, \
+                       dfeat, grad_scale, relu_mask ? 1 : 0)
+    const int per_lane = (F + 63) / 64;
+    if (per_lane <= 1) HEAD_LAUNCH(1);
+    else if (per_lane <= 2) HEAD_LAUNCH(2);
+    else if (per_lane <= 4) HEAD_LAUNCH(4);
+    else if (per_lane <= 8) HEAD_LAUNCH(8);
+    else HEAD_LAUNCH(16);
+#undef HEAD_LAUNCH
 }
 
+// One workgroup per class c: thread (f mod 64, slice) adds every 4th sample for its features, the four
+// slices are folded through LDS in order.  db[c] comes from the same workgroup.
 __global__ __launch_bounds__(256) void head_wgrad_kernel(const float* __restrict__ dlogits, const float* __restrict__ feat,
                                                          int B, int C, int F, float* __restrict__ dW, float* __restrict__ db) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < C * F) {
-        int c = i / F, k = i - c * F;
+    __shared__ float red[4][64];
+    const int c = blockIdx.x, fl = threadIdx.x & 63, sl = threadIdx.x >> 6;
+    for (int f0 = 0; f0 < F; f0 += 64) {
+        const int f = f0 + fl;
         float acc = 0.f;
-        for (int b = 0; b < B; ++b) acc = __fmaf_rn(dlogits[(int64_t)b * C + c], feat[(int64_t)b * F + k], acc);
-        dW[i] = acc;
-    } else if (i < C * F + C) {
-        int c = i - C * F;
-        float acc = 0.f;
-        for (int b = 0; b < B; ++b) acc += dlogits[(int64_t)b * C + c];
-        db[c] = acc;
+        if (f < F)
+            for (int b = sl; b < B; b += 4) acc = __fmaf_rn(dlogits[(int64_t)b * C + c], feat[(int64_t)b * F + f], acc);
+        red[sl][fl] = acc;
+        __syncthreads();
+        if (sl == 0 && f < F) dW[(int64_t)c * F + f] = (red[0][fl] + red[1][fl]) + (red[2][fl] + red[3][fl]);
+        __syncthreads();
     }
+    // bias gradient: 256 threads take every 256th sample
+    float acc = 0.f;
+    for (int b = threadIdx.x; b < B; b += 256) acc += dlogits[(int64_t)b * C + c];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (fl == 0) red[sl][0] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) db[c] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
 }
 
 void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db) {
-    int total = C * F + C;
-    hipLaunchKernelGGL(head_wgrad_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dlogits, feat, B, C, F, dW, db);
+    hipLaunchKernelGGL(head_wgrad_kernel, dim3(C), dim3(256), 0, s, dlogits, feat, B, C, F, dW, db);
 }
