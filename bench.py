@@ -35,9 +35,13 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the workload step, time top-k and aggregation stand-alone over a range of sizes")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part in this build (run with --gpus 1)")
+    if args.sweep:
+        return sweep()
 
     import numpy as np
     import torch
@@ -135,6 +139,54 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, p, b, x, y)
     print(json.dumps(line))
+
+
+def _time_calls(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(reps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def sweep():
+    """Stand-alone top-k (k = N/4, |N(0,1)| + ln 10 losses) and aggregation timings; one JSON line.
+
+    GB/s figures use the algorithmic bytes: 4N + 8k for top-k (read every loss, write k indices and
+    values), (P + 1) * 4 * d for aggregation.  Buffers rotate so that repeats are not served from cache.
+    """
+    import math
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    torch.manual_seed(250808540)
+    out = {"metric": "stand-alone top-k and aggregation", "unit": "GB/s (algorithmic bytes)", "hbm_peak": HBM_PEAK_GBS,
+           "topk": [], "aggregate": []}
+    for N in (512, 4096, 50000, 100000, 1 << 20, 1 << 24, 1 << 26):
+        k = N // 4
+        sets = 3 if N * 4 < (1 << 28) else 2
+        arrs = [torch.randn(N, device="cuda").abs_() + math.log(10.0) for _ in range(sets)]
+        idx = torch.empty(k, dtype=torch.int32, device="cuda")
+        val = torch.empty(k, dtype=torch.float32, device="cuda")
+        reps = 50 if N <= (1 << 20) else 10
+        t = _time_calls(torch, lambda i=0: bls.topk_by_loss(ctx, arrs[i % sets], k, idx, val), reps)
+        gbs = (4 * N + 8 * k) / t / 1e9
+        out["topk"].append({"N": N, "k": k, "us": round(t * 1e6, 2), "GB/s": round(gbs, 2), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
+        del arrs
+    for P, d in ((4, 394634), (10, 269722 + 1376), (10, 11007540), (10, 44000000), (10, 51747840)):
+        sets = 3
+        reps_sets = [[torch.randn(d, device="cuda") for _ in range(P)] for _ in range(sets)]
+        w = [1.0 / P] * P
+        o = torch.empty(d, device="cuda")
+        t = _time_calls(torch, lambda i=0: bls.weighted_aggregate(ctx, reps_sets[i % sets], w, o), 30)
+        gbs = (P + 1) * 4 * d / t / 1e9
+        out["aggregate"].append({"P": P, "d": d, "us": round(t * 1e6, 2), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
+        del reps_sets
+    print(json.dumps(out))
 
 
 def cpu_baseline(cfg, p, b, x, y):

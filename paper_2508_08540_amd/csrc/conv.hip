@@ -9,7 +9,8 @@
 // stores them with one 16-byte write.  Lane group g = l / 16 supplies input channels 16s+4g .. +3
 // of a tap as one 16-byte LDS read that feeds four MFMAs (the K order inside a tap is free as long
 // as both operands agree).  The epilogue optionally reduces per-channel sum and sum of squares of
-// the tile for batch normalisation (deterministic: fixed shuffle tree, then a fixed wave order).
+// the tile for batch normalisation (fixed shuffle tree, fixed wave order, then order-independent
+// fixed-point integer atomics across workgroups).
 // The input gradient of a stride-1 layer is the same kernel with weights read transposed and
 // flipped; for a stride-2 layer the upstream gradient is staged with zeros inserted between
 // samples, which turns the transposed convolution into a stride-1 one.
@@ -255,7 +256,7 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
 // EPI 0: plain store.  EPI 1: also per-channel sum / sum of squares of the output (batch-norm statistics).
 // EPI 2 (input gradient): the shortcut gradient is added before the store, and the output is masked by
 // the ReLU of the layer below and reduced to the two sums of that layer's batch-norm backward pass.
-// For EPI 1 and 2 every workgroup writes one row of partial sums; a small kernel folds them in a fixed order.
+// For EPI 1 and 2 every workgroup adds its sums into per-channel fixed-point accumulators (integer atomics).
 //
 // The grid is persistent: workgroup b handles tiles b, b + gridDim.x, ...  While the MFMAs of one tile
 // run from one LDS buffer, the global loads of the next tile are in flight into registers and are then
@@ -307,7 +308,6 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
     }
 
     if (EPI != 0) {
-        float* stats = e.partials;
         // lanes of one group hold the same 4 channels for 16 different pixels: fold the pixels
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1)
@@ -330,7 +330,8 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
             int cb = c >> 4;
             float acc = 0.f;
             for (int wv = cb; wv < NW; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
-            stats[((int64_t)blockIdx.x * 2 + which) * NO + c] = acc;
+            // order-independent accumulation across workgroups: 64-bit fixed point, integer atomic add
+            atomicAdd(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + c, (fixsum_t)__double2ll_rn((double)acc * e.scale));
         }
     }
 }
@@ -409,15 +410,6 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
 void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab) {
     int64_t blocks = (tab.total_vec4 + 255) / 256;
     hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, params, packed, tab);
-}
-
-int conv_dgrad_partials(const ConvShape& cs) {
-    return conv_grid(make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, cs.stride == 2 ? 1 : 0, cs.c_in));
-}
-
-int conv_fwd_partials(const ConvShape& cs) {
-    int h_out = (cs.h_in - 1) / cs.stride + 1;
-    return conv_grid(make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real));
 }
 
 int conv_fwd_tiles(const ConvShape& cs) {

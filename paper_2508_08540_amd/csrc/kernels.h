@@ -7,6 +7,25 @@
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Per-channel sums that cross workgroups are accumulated as 64-bit fixed-point integers with atomic adds:
+// integer addition is associative, so the result does not depend on the order in which workgroups arrive
+// (bit-reproducible), and no partial-sum rows or finalisation kernels are needed.  A float partial p
+// contributes llrint(p * scale); forward statistics use 2^32 (|sum| < 2^31, resolution 2^-32), backward
+// sums 2^44 (|sum| < 2^19, resolution 2^-44).  The accumulators must be zero before the producing kernel.
+typedef unsigned long long fixsum_t;
+// Each accumulator is replicated FIX_REPLICAS times (workgroup b adds into replica b % FIX_REPLICAS) to
+// spread the atomic traffic; readers add the replicas (integer, exact).  One set = FIX_SET entries.
+#define FIX_REPLICAS 16
+#define FIX_SET (FIX_REPLICAS * 2 * 64)
+__device__ __forceinline__ long long fixsum_read(const fixsum_t* sums, int C, int which, int c) {
+    long long t = 0;
+#pragma unroll
+    for (int r = 0; r < FIX_REPLICAS; ++r) t += (long long)sums[(r * 2 + which) * C + c];
+    return t;
+}
+#define FIX_FWD_SCALE 4294967296.0
+#define FIX_BWD_SCALE 17592186044416.0
+
 // Optional pair of events that a launcher attaches to its kernel dispatch (start and end of that kernel).
 struct KernelTiming {
     hipEvent_t start, stop;
@@ -48,26 +67,30 @@ void launch_head_forward(hipStream_t s, const float* act, int B, int positions, 
 void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db);
 
 // ---- norm.hip ---------------------------------------------------------------------------------------
-// Per-channel statistics from per-tile partial sums (sum, sum of squares), in double.
-void launch_bn_finalize(hipStream_t s, const float* partials, int n_partials, int C, int64_t count, float* mean,
-                        float* invstd, float* running_mean, float* running_var);
 // mean/invstd from running statistics (inference mode)
 void launch_bn_eval_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean,
                           float* invstd);
+// Where the normalisation statistics of bn_apply come from.  Training: `sums` holds the fixed-point
+// (sum, sum of squares) of y over `count` values; every workgroup derives mean and invstd from them, and
+// workgroup 0 also stores them into mean/invstd and moves the running statistics.  Inference: sums == nullptr
+// and mean/invstd are read.
+struct BnStats {
+    const fixsum_t* sums;
+    double count;
+    float *mean, *invstd, *running_mean, *running_var;
+};
 // a = relu(gamma * (y - mean) * invstd + beta [+ shortcut(res)]); res has c_res channels at res_stride x resolution
-void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const float* mean, const float* invstd,
-                     const float* gamma, const float* beta, const float* res, int c_res, int res_stride, int h_out,
-                     float* out);
-// Backward of relu(bn(y) [+ shortcut]): g = dout * (out > 0); writes per-block partial sums of g and g*xhat.
-int bn_bwd_partials(int64_t pixels);
+void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
+                     const float* beta, const float* res, int c_res, int res_stride, int h_out, float* out);
+// Backward of relu(bn(y) [+ shortcut]) for a layer whose upstream gradient does not come from an input-gradient
+// kernel: g = dout * (out > 0); adds (sum g, sum g*xhat) into the fixed-point accumulators `sums` [2][C].
 void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
-                          int64_t pixels, int C, const float* mean, const float* invstd, float* partials);
-// dgamma, dbeta from the partials of launch_bn_bwd_reduce.
-void launch_bn_bwd_finalize(hipStream_t s, const float* partials, int n_partials, int C, float* dgamma, float* dbeta);
-// dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M) with g = dout * (out > 0); g_out (optional) receives g.
+                          int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums);
+// dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M) with g = dout * (out > 0) and (dbeta, dgamma) read from `sums`;
+// workgroup 0 stores dgamma and dbeta; g_out (optional) receives g.
 void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const float* dgamma, const float* dbeta, float* dy, float* g_out);
+                         const fixsum_t* sums, float* dgamma, float* dbeta, float* dy, float* g_out);
 // dx[n][h][w][c] += shortcut_backward(g): identity or stride-2 zero-padded-channel shortcut
 void launch_shortcut_grad_add(hipStream_t s, float* dx, int B, int h_in, int c_in, const float* g, int c_out, int stride);
 
@@ -89,25 +112,23 @@ struct PackTable {
     PackEntry e[PACK_MAX_ENTRIES];
 };
 void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab);
-// Fused epilogue of the convolution kernels (see conv_kernel).  `partials` receives [workgroups][2][channels] floats:
+// Fused epilogue of the convolution kernels (see conv_kernel).  `sums` points at [replica][2][channels] accumulators:
 // forward (sum, sum of squares) of the output; input gradient (sum g, sum g*xhat) of the layer below.
 struct ConvEpi {
-    float* partials;
+    fixsum_t* sums;
+    double scale;
     // input gradient: shortcut gradient to add (sc_g may be nullptr), then batch-norm backward sums of the layer below
     const float* sc_g;
     int sc_c, sc_lo, sc_stride;
     const float *a_prev, *y_prev, *mean_prev, *invstd_prev;
 };
 int conv_fwd_tiles(const ConvShape& cs);
-// rows of partial sums the fused epilogues write (one per workgroup of the persistent grid)
-int conv_fwd_partials(const ConvShape& cs);
-int conv_dgrad_partials(const ConvShape& cs);
 // In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
-// y = conv(x, w); with `stats` the kernel also writes per-tile (sum, sum of squares) of y for launch_bn_finalize.
+// y = conv(x, w); with `stats` the kernel also accumulates (sum, sum of squares) of y per channel.
 void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,
                      const KernelTiming* kt = nullptr);
-// dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also per-tile batch-norm backward sums of the
-// layer that produced x, for launch_bn_bwd_finalize.
+// dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also the batch-norm backward sums of the layer
+// that produced x.
 void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt = nullptr);
 int conv_wgrad_partials(const ConvShape& cs);

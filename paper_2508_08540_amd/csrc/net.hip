@@ -74,7 +74,8 @@ struct ResScratch {
     float* xpad;
     int32_t* yb;
     std::vector<float*> y, a, mean, invstd, dy;  // per layer
-    float *stats, *d1, *d2, *g, *bnpart, *wpart, *grad;
+    float *stats, *d1, *d2, *g, *wpart, *grad;
+    fixsum_t* sums;  // per layer: a forward and a backward set of fixed-point accumulators, zeroed every step
     float *loss, *feat, *dlogits, *dfeat;
 };
 
@@ -105,13 +106,11 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     s.yb = c.take<int32_t>(B);
     s.loss = c.take<float>(B);
     s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L); s.dy.assign(L, nullptr);
-    int64_t max_act = 0, max_stats = 0, max_wpart = 0, max_bnpart = 1024 * 2 * 64;
+    int64_t max_act = 0, max_wpart = 0;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         max_act = max64(max_act, out_floats(cb, B));
-        max_stats = max64(max_stats, (int64_t)conv_fwd_partials(cs) * 2 * cb.c_out);
-        max_bnpart = max64(max_bnpart, (int64_t)conv_dgrad_partials(cs) * 2 * cs.c_in);
         max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);  // groups * blocks * 2304
         s.mean[l] = c.take<float>(cb.c_out);
         s.invstd[l] = c.take<float>(cb.c_out);
@@ -122,11 +121,11 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
             s.a[l] = c.take<float>(out_floats(m->layers[l], B));
             s.dy[l] = c.take<float>(out_floats(m->layers[l], B));  // kept per layer: the side stream reads it later
         }
-        s.stats = c.take<float>(max_stats);
+        s.stats = nullptr;
+        s.sums = c.take<fixsum_t>((size_t)L * 2 * FIX_SET);
         s.d1 = c.take<float>(max_act);
         s.d2 = c.take<float>(max_act);
         s.g = c.take<float>(max_act);
-        s.bnpart = c.take<float>(max_bnpart);
         s.wpart = c.take<float>(max_wpart);
         s.grad = c.take<float>(m->num_params);
         s.feat = c.take<float>((size_t)B * m->final_c);
@@ -142,6 +141,7 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
             s.a[l] = nullptr;
         }
         s.d1 = pool[0]; s.d2 = pool[1]; s.g = pool[2]; s.stats = pool[3];
+        s.sums = nullptr;
     }
     return s;
 }
@@ -162,6 +162,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
         }
     };
     PROF(ctx, PROF_UPDATE, launch_pack_weights(st, params, s.wpack, s.tab));
+    if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), (int64_t)m->layers.size() * 2 * FIX_SET * 2));
     const float* block_in = nullptr;
     const float* cur = s.xpad;
     for (int l = 0; l < L; ++l) {
@@ -172,16 +173,20 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
         float* y = train ? s.y[l] : take(cur, block_in);
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         if (train) {
-            // the convolution writes per-tile sums of its output; a one-block kernel turns them into statistics
+            // the convolution accumulates the sums of its output; bn_apply turns them into statistics
             ConvEpi e{};
-            e.partials = s.stats;
+            e.sums = s.sums + (size_t)l * 2 * FIX_SET;
+            e.scale = FIX_FWD_SCALE;
             PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
-            PROF(ctx, PROF_NORM, launch_bn_finalize(st, s.stats, conv_fwd_partials(cs), cb.c_out, pixels, s.mean[l], s.invstd[l],
-                               buffers + cb.rmean_off, buffers + cb.rvar_off));
         } else {
             PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, nullptr, kt));
             PROF(ctx, PROF_NORM, launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]));
         }
+        BnStats bs{};
+        bs.sums = train ? s.sums + (size_t)l * 2 * FIX_SET : nullptr;
+        bs.count = (double)pixels;
+        bs.mean = s.mean[l]; bs.invstd = s.invstd[l];
+        bs.running_mean = buffers + cb.rmean_off; bs.running_var = buffers + cb.rvar_off;
         float* a = train ? s.a[l] : take(y, block_in);
         const float* res = nullptr;
         int c_res = cb.c_out, res_stride = 1;
@@ -191,7 +196,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             c_res = c1.c_in;
             res_stride = c1.stride;
         }
-        PROF(ctx, PROF_NORM, launch_bn_apply(st, y, pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off, params + cb.beta_off, res,
+        PROF(ctx, PROF_NORM, launch_bn_apply(st, y, pixels, cb.c_out, bs, params + cb.gamma_off, params + cb.beta_off, res,
                         c_res, res_stride, cb.h_out, a));
         cur = a;
     }
@@ -220,11 +225,11 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         if (l == L - 1) {
             // top layer: its upstream gradient comes from the head; lower layers get these sums from the
             // input-gradient kernel of the layer above
-            PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], s.bnpart));
-            PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, bn_bwd_partials(pixels), cb.c_out, s.grad + cb.gamma_off, s.grad + cb.beta_off));
+            PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l],
+                                                      s.sums + ((size_t)l * 2 + 1) * FIX_SET));
         }
         PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
-                            s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
+                            s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
         BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
         BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
         PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wpart, kt));
@@ -236,17 +241,15 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         {
             // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
             // batch-norm backward sums of layer l-1
-            const ConvBn& below = m->layers[l - 1];
             ConvEpi e{};
-            e.partials = s.bnpart;
+            e.sums = s.sums + ((size_t)(l - 1) * 2 + 1) * FIX_SET;
+            e.scale = FIX_BWD_SCALE;
             e.a_prev = s.a[l - 1]; e.y_prev = s.y[l - 1]; e.mean_prev = s.mean[l - 1]; e.invstd_prev = s.invstd[l - 1];
             if (!is_conv2) {
                 const ConvBn& c2 = m->layers[l + 1];
                 e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
             }
             PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e, kt));
-            PROF(ctx, PROF_NORM, launch_bn_bwd_finalize(st, s.bnpart, conv_dgrad_partials(cs), below.c_out, s.grad + below.gamma_off,
-                                                        s.grad + below.beta_off));
         }
         dout = s.d2;
         shared = 0;

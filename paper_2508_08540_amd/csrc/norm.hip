@@ -6,54 +6,6 @@
 #define BN_EPS 1e-5
 #define BN_MOMENTUM 0.1
 
-// Sums column (which, c) of partials[n_partials][2][C] in double: each of the 256 threads of the block
-// takes every 256th partial, then a fixed LDS tree folds the threads (deterministic).
-__device__ __forceinline__ void block_sum2(const float* __restrict__ partials, int n_partials, int C, int c, double& s0,
-                                           double& s1) {
-    __shared__ double red[2][256];
-    double a = 0.0, b = 0.0;
-    for (int i = threadIdx.x; i < n_partials; i += 256) {
-        a += (double)partials[((int64_t)i * 2) * C + c];
-        b += (double)partials[((int64_t)i * 2 + 1) * C + c];
-    }
-    red[0][threadIdx.x] = a;
-    red[1][threadIdx.x] = b;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) {
-            red[0][threadIdx.x] += red[0][threadIdx.x + w];
-            red[1][threadIdx.x] += red[1][threadIdx.x + w];
-        }
-        __syncthreads();
-    }
-    s0 = red[0][0];
-    s1 = red[1][0];
-}
-
-// partials: [n_partials][2][C] = per-tile (sum, sum of squares); one block per channel
-__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
-                                                          double count, float* __restrict__ mean, float* __restrict__ invstd,
-                                                          float* __restrict__ running_mean, float* __restrict__ running_var) {
-    const int c = blockIdx.x;
-    double s, ss;
-    block_sum2(partials, n_partials, C, c, s, ss);
-    if (threadIdx.x != 0) return;
-    double mu = s / count;
-    double var = ss / count - mu * mu;
-    if (var < 0.0) var = 0.0;
-    mean[c] = (float)mu;
-    invstd[c] = (float)(1.0 / sqrt(var + BN_EPS));
-    double unbiased = count > 1.0 ? var * count / (count - 1.0) : var;
-    running_mean[c] = (float)((1.0 - BN_MOMENTUM) * (double)running_mean[c] + BN_MOMENTUM * mu);
-    running_var[c] = (float)((1.0 - BN_MOMENTUM) * (double)running_var[c] + BN_MOMENTUM * unbiased);
-}
-
-void launch_bn_finalize(hipStream_t s, const float* partials, int n_partials, int C, int64_t count, float* mean,
-                        float* invstd, float* running_mean, float* running_var) {
-    hipLaunchKernelGGL(bn_finalize_kernel, dim3(C), dim3(256), 0, s, partials, n_partials, C, (double)count,
-                       mean, invstd, running_mean, running_var);
-}
-
 __global__ __launch_bounds__(64) void bn_eval_stats_kernel(const float* __restrict__ running_mean,
                                                            const float* __restrict__ running_var, int C,
                                                            float* __restrict__ mean, float* __restrict__ invstd) {
@@ -68,12 +20,37 @@ void launch_bn_eval_stats(hipStream_t s, const float* running_mean, const float*
     hipLaunchKernelGGL(bn_eval_stats_kernel, dim3((C + 63) / 64), dim3(64), 0, s, running_mean, running_var, C, mean, invstd);
 }
 
-// out = relu(gamma*(y-mean)*invstd + beta + shortcut(res))
-__global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__ y, int64_t pixels, int C,
-                                                       const float* __restrict__ mean, const float* __restrict__ invstd,
+// out = relu(gamma*(y-mean)*invstd + beta + shortcut(res)).  In training the statistics come from the
+// fixed-point sums: threads 0..C-1 of every workgroup turn them into mean and invstd (double), workgroup 0
+// also stores them and moves the running statistics (momentum 0.1, unbiased variance).
+__global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__ y, int64_t pixels, int C, BnStats st,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const float* __restrict__ res, int c_res, int res_stride, int h_out,
                                                        float* __restrict__ out) {
+    __shared__ float s_mean[64], s_invstd[64];
+    if ((int)threadIdx.x < C) {
+        const int c = threadIdx.x;
+        if (st.sums) {
+            const double s1 = (double)fixsum_read(st.sums, C, 0, c) * (1.0 / FIX_FWD_SCALE);
+            const double s2 = (double)fixsum_read(st.sums, C, 1, c) * (1.0 / FIX_FWD_SCALE);
+            const double mu = s1 / st.count;
+            double var = s2 / st.count - mu * mu;
+            if (var < 0.0) var = 0.0;
+            s_mean[c] = (float)mu;
+            s_invstd[c] = (float)(1.0 / sqrt(var + BN_EPS));
+            if (blockIdx.x == 0) {
+                st.mean[c] = s_mean[c];
+                st.invstd[c] = s_invstd[c];
+                const double unbiased = st.count > 1.0 ? var * st.count / (st.count - 1.0) : var;
+                st.running_mean[c] = (float)((1.0 - BN_MOMENTUM) * (double)st.running_mean[c] + BN_MOMENTUM * mu);
+                st.running_var[c] = (float)((1.0 - BN_MOMENTUM) * (double)st.running_var[c] + BN_MOMENTUM * unbiased);
+            }
+        } else {
+            s_mean[c] = st.mean[c];
+            s_invstd[c] = st.invstd[c];
+        }
+    }
+    __syncthreads();
     const int cq = C >> 2;
     int64_t total = pixels * cq;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -82,8 +59,6 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
         int64_t p = i / cq;
         int c = (int)(i - p * cq) << 2;
         f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
-        f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
-        f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
         f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
         f32x4 be = *reinterpret_cast<const f32x4*>(beta + c);
         f32x4 r = {0.f, 0.f, 0.f, 0.f};
@@ -102,21 +77,20 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
         f32x4 o;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            float t = __fmaf_rn((v[j] - mu[j]) * is[j], ga[j], be[j]) + r[j];
+            float t = __fmaf_rn((v[j] - s_mean[c + j]) * s_invstd[c + j], ga[j], be[j]) + r[j];
             o[j] = fmaxf(t, 0.f);
         }
         *reinterpret_cast<f32x4*>(out + p * C + c) = o;
     }
 }
 
-void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const float* mean, const float* invstd,
-                     const float* gamma, const float* beta, const float* res, int c_res, int res_stride, int h_out,
-                     float* out) {
+void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
+                     const float* beta, const float* res, int c_res, int res_stride, int h_out, float* out) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(bn_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, y, pixels, C, mean, invstd, gamma, beta,
-                       res, c_res, res_stride, h_out, out);
+    hipLaunchKernelGGL(bn_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, y, pixels, C, st, gamma, beta, res, c_res,
+                       res_stride, h_out, out);
 }
 
 // ---- backward -------------------------------------------------------------------------------------
@@ -135,11 +109,11 @@ __device__ __forceinline__ f32x4 load_dout(const float* __restrict__ dout, int s
     return *reinterpret_cast<const f32x4*>(dout + row * C + c);
 }
 
-// partials: [n_blocks][2][C] = (sum g, sum g*xhat), g = dout * (out > 0)
+// adds (sum g, sum g*xhat), g = dout * (out > 0), into the fixed-point accumulators sums[2][C]
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const float* __restrict__ dout, int shared,
                                                             const float* __restrict__ out, const float* __restrict__ y,
                                                             int64_t pixels, int C, const float* __restrict__ mean,
-                                                            const float* __restrict__ invstd, float* __restrict__ partials) {
+                                                            const float* __restrict__ invstd, fixsum_t* __restrict__ sums) {
     __shared__ float red[2][256][4];
     const int cq = C >> 2;              // threads per pixel
     const int lanes_p = 256 / cq;       // pixels in flight per block
@@ -172,33 +146,35 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const float* __restr
         int which = threadIdx.x / C, ch = threadIdx.x % C;
         float acc = 0.f;
         for (int l = 0; l < lanes_p; ++l) acc += red[which][l * cq + (ch >> 2)][ch & 3];
-        partials[((int64_t)blockIdx.x * 2 + which) * C + ch] = acc;
+        atomicAdd(sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * C + ch, (fixsum_t)__double2ll_rn((double)acc * FIX_BWD_SCALE));
     }
 }
 
 void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
-                          int64_t pixels, int C, const float* mean, const float* invstd, float* partials) {
+                          int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums) {
     int n = bn_bwd_partials(pixels);
     hipLaunchKernelGGL(bn_bwd_reduce_kernel, dim3(n), dim3(256), 0, s, dout, dout_positions_shared, out, y, pixels, C,
-                       mean, invstd, partials);
-}
-
-__global__ __launch_bounds__(256) void bn_bwd_finalize_kernel(const float* __restrict__ partials, int n_partials, int C,
-                                                              float* __restrict__ dgamma, float* __restrict__ dbeta) {
-    const int c = blockIdx.x;
-    double sg, sgx;
-    block_sum2(partials, n_partials, C, c, sg, sgx);
-    if (threadIdx.x != 0) return;
-    dbeta[c] = (float)sg;
-    dgamma[c] = (float)sgx;
+                       mean, invstd, sums);
 }
 
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restrict__ dout, int shared,
                                                            const float* __restrict__ out, const float* __restrict__ y,
                                                            int64_t pixels, int C, const float* __restrict__ mean,
                                                            const float* __restrict__ invstd, const float* __restrict__ gamma,
-                                                           const float* __restrict__ dgamma, const float* __restrict__ dbeta,
-                                                           float inv_count, float* __restrict__ dy, float* __restrict__ g_out) {
+                                                           const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
+                                                           float* __restrict__ dbeta, float inv_count, float* __restrict__ dy,
+                                                           float* __restrict__ g_out) {
+    __shared__ float s_dg[64], s_db[64];
+    if ((int)threadIdx.x < C) {
+        const int c = threadIdx.x;
+        s_db[c] = (float)((double)fixsum_read(sums, C, 0, c) * (1.0 / FIX_BWD_SCALE));
+        s_dg[c] = (float)((double)fixsum_read(sums, C, 1, c) * (1.0 / FIX_BWD_SCALE));
+        if (blockIdx.x == 0) {
+            dbeta[c] = s_db[c];
+            dgamma[c] = s_dg[c];
+        }
+    }
+    __syncthreads();
     const int cq = C >> 2;
     int64_t total = pixels * cq;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -211,33 +187,27 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
         f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
         f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
         f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
-        f32x4 dg = *reinterpret_cast<const f32x4*>(dgamma + c);
-        f32x4 db = *reinterpret_cast<const f32x4*>(dbeta + c);
         f32x4 r, gq;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float g = o[j] > 0.f ? d[j] : 0.f;
             float xhat = (v[j] - mu[j]) * is[j];
             gq[j] = g;
-            r[j] = ga[j] * is[j] * (g - db[j] * inv_count - xhat * (dg[j] * inv_count));
+            r[j] = ga[j] * is[j] * (g - s_db[c + j] * inv_count - xhat * (s_dg[c + j] * inv_count));
         }
         *reinterpret_cast<f32x4*>(dy + p * C + c) = r;
         if (g_out) *reinterpret_cast<f32x4*>(g_out + p * C + c) = gq;
     }
 }
 
-void launch_bn_bwd_finalize(hipStream_t s, const float* partials, int n_partials, int C, float* dgamma, float* dbeta) {
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(C), dim3(256), 0, s, partials, n_partials, C, dgamma, dbeta);
-}
-
 void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const float* dgamma, const float* dbeta, float* dy, float* g_out) {
+                         const fixsum_t* sums, float* dgamma, float* dbeta, float* dy, float* g_out) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dout, dout_positions_shared, out, y,
-                       pixels, C, mean, invstd, gamma, dgamma, dbeta, 1.f / (float)pixels, dy, g_out);
+                       pixels, C, mean, invstd, gamma, sums, dgamma, dbeta, 1.f / (float)pixels, dy, g_out);
 }
 
 // dx += shortcut_backward(g): identity (stride 1, equal channels) or stride-2 zero-padded-channel shortcut
