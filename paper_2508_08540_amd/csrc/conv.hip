@@ -440,15 +440,18 @@ void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, cons
 // Workgroup (pg, ob, ib) owns the 16x16 block (output channels 16*ob.., input channels 16*ib..) of dW
 // for all 9 taps over pixel group pg.  It stages only those 16-channel slices of x and dy, its four
 // waves take output rows in turn (9 MFMAs per pixel quad), fold their 9 accumulators through LDS in
-// wave order and write one 2304-float partial.  All layer shapes run the same code; the grid has
-// groups * (C_out/16) * (C_in/16) workgroups and the partial traffic stays near 5 MB per layer.
+// wave order and add the 2304 sums into replicated 64-bit fixed-point accumulators with integer atomics
+// (order-independent, hence reproducible).  All layer shapes run the same code; the grid has
+// groups * (C_out/16) * (C_in/16) workgroups.
 
 #define WG_BLOCK_FLOATS (16 * 9 * 16)
+#define WGRAD_REPLICAS 8
+#define FIX_WGRAD_SCALE 1099511627776.0  // 2^40: |dW| < 2^23, resolution 2^-40
 
 #define WGRAD_THREADS 256
 
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
-                                                              float* __restrict__ partials, ConvGeom g, int tiles_per_group,
+                                                              fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
                                                               int NI, int NO) {
     extern __shared__ f32x4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
@@ -522,37 +525,39 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const float* __res
 #pragma unroll
         for (int j = 0; j < 4; ++j) lds[wave * WG_BLOCK_FLOATS + (t * 4 + j) * 64 + lane] = acc[t][j];
     __syncthreads();
-    float* out = partials + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * WG_BLOCK_FLOATS;
-    for (int e = threadIdx.x; e < WG_BLOCK_FLOATS; e += WGRAD_THREADS)
-        out[e] = ((lds[e] + lds[WG_BLOCK_FLOATS + e]) + lds[2 * WG_BLOCK_FLOATS + e]) + lds[3 * WG_BLOCK_FLOATS + e];
+    // order-independent accumulation across pixel groups: replicated 64-bit fixed point, integer atomic add
+    fixsum_t* out = gacc + ((int64_t)(blockIdx.x % WGRAD_REPLICAS) * gridDim.y + blockIdx.y) * WG_BLOCK_FLOATS;
+    for (int e = threadIdx.x; e < WG_BLOCK_FLOATS; e += WGRAD_THREADS) {
+        const float v = ((lds[e] + lds[WG_BLOCK_FLOATS + e]) + lds[2 * WG_BLOCK_FLOATS + e]) + lds[3 * WG_BLOCK_FLOATS + e];
+        atomicAdd(out + e, (fixsum_t)__double2ll_rn((double)v * FIX_WGRAD_SCALE));
+    }
 }
 
-// dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over pixel groups of partial (pg, ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i].
-// A block covers 16 outputs; its 16 thread rows take every 16th group and are folded through LDS in row order.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partials, int groups, int NO, int NI,
-                                                           int ci_real, float* __restrict__ dw) {
-    __shared__ float red[16][17];
-    const int col = threadIdx.x & 15, row = threadIdx.x >> 4;
-    const int idx = blockIdx.x * 16 + col;
-    const bool live = idx < NO * 9 * ci_real;
-    float acc = 0.f;
-    if (live) {
-        int ot = idx / ci_real, ci = idx - ot * ci_real;
-        int co = ot / 9, t = ot - co * 9;
-        int blocks = (NO >> 4) * (NI >> 4);
-        int o = co & 15;
-        int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
-        int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
-        for (int p = row; p < groups; p += 16) acc += partials[p * pitch + src];
-    }
-    red[row][col] = acc;
-    __syncthreads();
-    if (row == 0 && live) {
-        float v = red[0][col];
+// For every convolution of the table: dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over the replicas of
+// accumulator (ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i], converted back to float; the accumulators are cleared
+// for the next step.  One launch converts all layers.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(fixsum_t* __restrict__ gacc, float* __restrict__ grad, WgradTable tab) {
+    const int64_t gi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // over the padded [NO][9][NI] spaces of all layers
+    if (gi >= tab.total) return;
+    int l = 0;
+    while (l + 1 < tab.n && gi >= tab.e[l + 1].first) ++l;
+    const WgradEntry e = tab.e[l];
+    const int idx = (int)(gi - e.first);
+    const int NI = e.c_in, NO = e.c_out;
+    int ot = idx / NI, ci = idx - ot * NI;
+    int co = ot / 9, t = ot - co * 9;
+    int blocks = (NO >> 4) * (NI >> 4);
+    int o = co & 15;
+    int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
+    int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
+    fixsum_t* acc_l = gacc + e.acc_off;
+    long long acc = 0;
 #pragma unroll
-        for (int r = 1; r < 16; ++r) v += red[r][col];
-        dw[idx] = v;
+    for (int r = 0; r < WGRAD_REPLICAS; ++r) {
+        acc += (long long)acc_l[r * pitch + src];
+        acc_l[r * pitch + src] = 0ull;
     }
+    if (ci < e.c_in_real) grad[e.w_off + (int64_t)ot * e.c_in_real + ci] = (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));
 }
 
 // Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller
@@ -574,9 +579,9 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     return n_tiles < cap ? n_tiles : cap;
 }
 
-int conv_wgrad_partials(const ConvShape& cs) { return wgrad_groups(cs, wgrad_geom(cs).n_tiles); }
+int64_t conv_wgrad_accumulators(const ConvShape& cs) { return (int64_t)WGRAD_REPLICAS * cs.c_out * 9 * cs.c_in; }
 
-void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials,
+void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, fixsum_t* gacc,
                        const KernelTiming* kt) {
     ConvGeom g = wgrad_geom(cs);
     int groups = wgrad_groups(cs, g.n_tiles);
@@ -586,12 +591,9 @@ void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const
     if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
     hipExtLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
-                          kt ? kt->stop : nullptr, 0, x, dy, partials, g, tiles_per_group, cs.c_in, cs.c_out);
+                          kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out);
 }
 
-void launch_conv_wgrad_reduce(hipStream_t s, const ConvShape& cs, const float* partials, float* dw) {
-    int groups = conv_wgrad_partials(cs);
-    int n = cs.c_out * 9 * cs.c_in_real;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, s, partials, groups, cs.c_out, cs.c_in,
-                       cs.c_in_real, dw);
+void launch_conv_wgrad_reduce(hipStream_t s, fixsum_t* gacc, float* grad, const WgradTable& tab) {
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((tab.total + 255) / 256)), dim3(256), 0, s, gacc, grad, tab);
 }

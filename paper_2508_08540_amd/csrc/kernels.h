@@ -131,9 +131,22 @@ void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const f
 // that produced x.
 void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt = nullptr);
-int conv_wgrad_partials(const ConvShape& cs);
-// partials[groups][c_out/16][c_in/16][2304] = per pixel group sums of dy * shifted x ...
-void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, float* partials,
+// Adds dy (x) shifted x over all pixels into gacc: [replica][c_out/16][c_in/16][2304] fixed-point accumulators
+// (conv_wgrad_accumulators entries, zero before the call) ...
+int64_t conv_wgrad_accumulators(const ConvShape& cs);
+void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, fixsum_t* gacc,
                        const KernelTiming* kt = nullptr);
-// ... and dw[c_out][3][3][c_in_real] = their sum over the groups, in group order.
-void launch_conv_wgrad_reduce(hipStream_t s, const ConvShape& cs, const float* partials, float* dw);
+// ... and, for all layers at once, grad[w_off ..] = sum of the replicas as float; clears the accumulators again.
+#define WGRAD_MAX_ENTRIES 40
+struct WgradEntry {
+    int64_t w_off;    // offset of dw[c_out][3][3][c_in_real] in the gradient vector
+    int64_t acc_off;  // offset of this layer's accumulators in gacc
+    int64_t first;    // first index of this layer in the concatenated padded [c_out][9][c_in] spaces
+    int c_in, c_out, c_in_real, pad_;
+};
+struct WgradTable {
+    int n;
+    int64_t total;
+    WgradEntry e[WGRAD_MAX_ENTRIES];
+};
+void launch_conv_wgrad_reduce(hipStream_t s, fixsum_t* gacc, float* grad, const WgradTable& tab);

@@ -74,7 +74,10 @@ struct ResScratch {
     float* xpad;
     int32_t* yb;
     std::vector<float*> y, a, mean, invstd, dy;  // per layer
-    float *stats, *d1, *d2, *g, *wpart, *grad;
+    float *stats, *d1, *d2, *g, *grad;
+    fixsum_t* wacc;  // weight-gradient accumulators of all layers (kept zero between uses)
+    int64_t wacc_count;
+    WgradTable wtab;
     fixsum_t* sums;  // per layer: a forward and a backward set of fixed-point accumulators, zeroed every step
     float *loss, *feat, *dlogits, *dfeat;
 };
@@ -107,11 +110,19 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     s.loss = c.take<float>(B);
     s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L); s.dy.assign(L, nullptr);
     int64_t max_act = 0, max_wpart = 0;
+    s.wtab.n = 0;
+    s.wtab.total = 0;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         max_act = max64(max_act, out_floats(cb, B));
-        max_wpart = max64(max_wpart, (int64_t)conv_wgrad_partials(cs) * cb.c_out * 9 * cs.c_in);  // groups * blocks * 2304
+        {
+            WgradEntry& we = s.wtab.e[s.wtab.n++];
+            we.w_off = cb.w_off; we.acc_off = max_wpart; we.first = s.wtab.total;
+            we.c_in = cs.c_in; we.c_out = cs.c_out; we.c_in_real = cs.c_in_real; we.pad_ = 0;
+            s.wtab.total += (int64_t)cs.c_out * 9 * cs.c_in;
+            max_wpart += conv_wgrad_accumulators(cs);
+        }
         s.mean[l] = c.take<float>(cb.c_out);
         s.invstd[l] = c.take<float>(cb.c_out);
     }
@@ -126,7 +137,8 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
         s.d1 = c.take<float>(max_act);
         s.d2 = c.take<float>(max_act);
         s.g = c.take<float>(max_act);
-        s.wpart = c.take<float>(max_wpart);
+        s.wacc = c.take<fixsum_t>(max_wpart);
+        s.wacc_count = max_wpart;
         s.grad = c.take<float>(m->num_params);
         s.feat = c.take<float>((size_t)B * m->final_c);
         s.dlogits = c.take<float>((size_t)B * m->desc.classes);
@@ -232,11 +244,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                             s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
         BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
         BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
-        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wpart, kt));
-        {
-            ProfScope prof_(ctx, PROF_WGRAD_REDUCE, ctx->aux);
-            launch_conv_wgrad_reduce(ctx->aux, cs, s.wpart, s.grad + cb.w_off);
-        }
+        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wacc + s.wtab.e[l].acc_off, kt));
         if (l == 0) break;
         {
             // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
@@ -253,6 +261,10 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         }
         dout = s.d2;
         shared = 0;
+    }
+    {
+        ProfScope prof_(ctx, PROF_WGRAD_REDUCE, ctx->aux);
+        launch_conv_wgrad_reduce(ctx->aux, s.wacc, s.grad, s.wtab);
     }
     BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
     BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
@@ -326,6 +338,8 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
     } else {
         ResScratch s = carve_resnet(c, m, B, true);
         const int hw = m->desc.image_hw, C = m->desc.classes;
+        // the weight-gradient accumulators start at zero; every reduction leaves them at zero again
+        PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.wacc), s.wacc_count * 2));
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
             PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb));
