@@ -68,6 +68,8 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_lds_bitonic_kernel(const fl
 #define SEL_BINS 2048
 #define TILE 2048          // elements per 256-thread block: 8 consecutive elements per thread
 #define SCAN_CHUNK 2048
+// Radix passes: a block of 256 threads handles RITER * 256 elements (each wave ranks RITER * 64 of them in
+// rounds of 64); 8 rounds for moderate pools, 16 for very large ones (longer runs per digit when scattering).
 
 struct SelInfo {
     uint32_t bin;    // b*
@@ -215,15 +217,17 @@ static void exclusive_scan_u32(hipStream_t s, uint32_t* data, int64_t n, uint32_
 // ---- radix sort passes --------------------------------------------------------------------------------
 
 // table[d * n_blocks + b] = number of elements of block b's tile with digit d (zero for tiles past M)
+template <int RITER>
 __global__ __launch_bounds__(256) void radix_count_kernel(const uint32_t* __restrict__ keys, const SelInfo* __restrict__ info,
                                                           int shift, uint32_t* __restrict__ table, int n_blocks) {
     __shared__ uint32_t cnt[256];
     cnt[threadIdx.x] = 0u;
     __syncthreads();
     const uint32_t M = info->M;
-    int64_t base = (int64_t)blockIdx.x * TILE;
+    constexpr int RTILE = RITER * 256;
+    int64_t base = (int64_t)blockIdx.x * RTILE;
     if (base < M)
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < RITER; ++j) {
             int64_t i = base + j * 256 + threadIdx.x;
             if (i < M) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u);
         }
@@ -232,22 +236,25 @@ __global__ __launch_bounds__(256) void radix_count_kernel(const uint32_t* __rest
 }
 
 // table has been exclusive-scanned: table[d * n_blocks + b] = first output slot of digit d in block b.
-// Each wave owns 512 consecutive elements of the tile and ranks them 64 at a time with ballots, so the
+// Each wave owns RTILE/4 consecutive elements of the tile and ranks them 64 at a time with ballots, so the
 // order of equal digits is the input order (stable).
+template <int RITER>
 __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ idx_in,
                                                             uint32_t* __restrict__ keys_out, uint32_t* __restrict__ idx_out,
                                                             const SelInfo* __restrict__ info, int shift,
                                                             const uint32_t* __restrict__ table, int n_blocks) {
     __shared__ uint32_t cnt[4][256];
     const uint32_t M = info->M;
-    const int64_t base = (int64_t)blockIdx.x * TILE;
+    constexpr int RTILE = RITER * 256;
+    const int64_t base = (int64_t)blockIdx.x * RTILE;
     if (base >= M) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int w = 0; w < 4; ++w) cnt[w][threadIdx.x] = 0u;
     __syncthreads();
-    const int64_t wbase = base + wave * 512;
-    uint32_t key[8], id[8];
-    for (int it = 0; it < 8; ++it) {
+    const int64_t wbase = base + wave * (RTILE / 4);
+    uint32_t key[RITER], id[RITER];
+#pragma unroll
+    for (int it = 0; it < RITER; ++it) {
         int64_t i = wbase + it * 64 + lane;
         bool valid = i < M;
         key[it] = valid ? keys_in[i] : 0u;
@@ -265,7 +272,8 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __re
     }
     __syncthreads();
     const uint64_t lt = lane ? (~0ull >> (64 - lane)) : 0ull;
-    for (int it = 0; it < 8; ++it) {
+#pragma unroll
+    for (int it = 0; it < RITER; ++it) {
         int64_t i = wbase + it * 64 + lane;
         bool valid = i < M;
         uint32_t d = (key[it] >> shift) & 255u;
@@ -287,29 +295,47 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __re
     }
 }
 
-__global__ __launch_bounds__(256) void topk_emit_kernel(const uint32_t* __restrict__ idx_sorted, const float* __restrict__ losses,
-                                                        int64_t k, int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
+// Inverse of loss_key for every key that determines the float uniquely; NaN keys and the zero key
+// (shared by +0 and -0) do not, those values are fetched from the loss array.
+__device__ __forceinline__ bool key_to_loss(uint32_t key, float* v) {
+    if (key == 0xffffffffu || key == 0x80000000u) return false;
+    uint32_t u = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
+    *v = __uint_as_float(u);
+    return true;
+}
+
+__global__ __launch_bounds__(256) void topk_emit_kernel(const uint32_t* __restrict__ keys_sorted, const uint32_t* __restrict__ idx_sorted,
+                                                        const float* __restrict__ losses, int64_t k, int32_t* __restrict__ idx_out,
+                                                        float* __restrict__ val_out) {
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < k; r += stride) {
         uint32_t i = idx_sorted[r];
         idx_out[r] = (int32_t)i;
-        if (val_out) val_out[r] = losses[i];
+        if (val_out) {
+            float v;
+            if (!key_to_loss(~keys_sorted[r], &v)) v = losses[i];
+            val_out[r] = v;
+        }
     }
 }
 
 struct TopkScratch {
     uint32_t *hist, *counts, *sums, *table, *keys_a, *idx_a, *keys_b, *idx_b;
     SelInfo* info;
-    int n_blocks;
+    int n_blocks;    // selection tiles (TILE elements)
+    int r_iter;      // rounds per wave in the radix passes (8 or 16)
+    int r_blocks;    // radix tiles (r_iter * 256 elements)
 };
 
 static TopkScratch carve_topk(Carver& c, int64_t N) {
     TopkScratch t;
     t.n_blocks = (int)((N + TILE - 1) / TILE);
+    t.r_iter = N >= (int64_t(1) << 22) ? 16 : 8;
+    t.r_blocks = (int)((N + t.r_iter * 256 - 1) / (t.r_iter * 256));
     t.hist = c.take<uint32_t>(SEL_BINS);
     t.info = c.take<SelInfo>(1);
     t.counts = c.take<uint32_t>(t.n_blocks);
-    t.table = c.take<uint32_t>((size_t)256 * t.n_blocks);
+    t.table = c.take<uint32_t>((size_t)256 * t.r_blocks);
     t.sums = c.take<uint32_t>(((size_t)256 * t.n_blocks + SCAN_CHUNK - 1) / SCAN_CHUNK + 1);
     t.keys_a = c.take<uint32_t>(N);
     t.idx_a = c.take<uint32_t>(N);
@@ -332,7 +358,7 @@ static int launch_topk_large(bls_ctx* ctx, const float* losses, int64_t N, int64
     Carver c(ctx->arena);
     TopkScratch t = carve_topk(c, N);
     hipStream_t s = ctx->stream;
-    const int nb = t.n_blocks;
+    const int nb = t.n_blocks, rb = t.r_blocks;
     int hist_blocks = nb < ctx->num_cus * 8 ? nb : ctx->num_cus * 8;
     hipLaunchKernelGGL(zero_u32_kernel, dim3(8), dim3(256), 0, s, t.hist, (int64_t)SEL_BINS);
     hipLaunchKernelGGL(sel_hist_kernel, dim3(hist_blocks), dim3(256), 0, s, losses, N, t.hist);
@@ -342,15 +368,19 @@ static int launch_topk_large(bls_ctx* ctx, const float* losses, int64_t N, int64
     hipLaunchKernelGGL(sel_compact_kernel, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts, t.keys_a, t.idx_a);
     uint32_t *ka = t.keys_a, *ia = t.idx_a, *kb = t.keys_b, *ib = t.idx_b;
     for (int pass = 0; pass < 4; ++pass) {
-        hipLaunchKernelGGL(radix_count_kernel, dim3(nb), dim3(256), 0, s, ka, t.info, pass * 8, t.table, nb);
-        exclusive_scan_u32(s, t.table, (int64_t)256 * nb, t.sums);
-        hipLaunchKernelGGL(radix_scatter_kernel, dim3(nb), dim3(256), 0, s, ka, ia, kb, ib, t.info, pass * 8, t.table, nb);
+        if (t.r_iter == 16) hipLaunchKernelGGL(radix_count_kernel<16>, dim3(rb), dim3(256), 0, s, ka, t.info, pass * 8, t.table, rb);
+        else hipLaunchKernelGGL(radix_count_kernel<8>, dim3(rb), dim3(256), 0, s, ka, t.info, pass * 8, t.table, rb);
+        exclusive_scan_u32(s, t.table, (int64_t)256 * rb, t.sums);
+        if (t.r_iter == 16)
+            hipLaunchKernelGGL(radix_scatter_kernel<16>, dim3(rb), dim3(256), 0, s, ka, ia, kb, ib, t.info, pass * 8, t.table, rb);
+        else
+            hipLaunchKernelGGL(radix_scatter_kernel<8>, dim3(rb), dim3(256), 0, s, ka, ia, kb, ib, t.info, pass * 8, t.table, rb);
         uint32_t* tmp = ka; ka = kb; kb = tmp;
         tmp = ia; ia = ib; ib = tmp;
     }
     int64_t eb = (k + 255) / 256;
     if (eb > 2048) eb = 2048;
-    hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)eb), dim3(256), 0, s, ia, losses, k, idx_out, val_out);
+    hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)eb), dim3(256), 0, s, ka, ia, losses, k, idx_out, val_out);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }
