@@ -13,6 +13,13 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM traffic per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; KiB per
+# dispatch averaged over all launches of a bench run), each scaled by what the same counter reads for a plain
+# 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
+MEASURED_TRAFFIC = {
+    "wgrad_kernel": {"fetch_kib": 5456.7, "fetch_scale": 2.0, "write_kib": 9216.0, "write_scale": 1.0,
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "8c06aad0eda1b394"},
+}
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
@@ -35,6 +42,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
+                         "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the workload step, time top-k and aggregation stand-alone over a range of sizes")
     args = ap.parse_args()
@@ -106,8 +116,15 @@ def main():
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
     symbol = {"conv_fwd": "conv_kernel (forward launches)", "conv_dgrad": "conv_kernel (input-gradient launches)",
               "conv_wgrad": "wgrad_kernel"}[dom]
+    traffic = None
+    rec = MEASURED_TRAFFIC.get(symbol)
+    if rec:
+        import hashlib
+        with open(os.path.join(ROOT, rec["source"]), "rb") as fh:
+            if hashlib.sha256(fh.read()).hexdigest()[:16] == rec["sha256_16"]:
+                traffic = int(1024 * (rec["fetch_kib"] * rec["fetch_scale"] + rec["write_kib"] * rec["write_scale"]))
     roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2), "launches_per_step": dom_cnt // args.steps}
 
     # Aggregation bandwidth on a vector large enough to leave the caches (WRN-16-8 sized, P = 10),
@@ -136,6 +153,13 @@ def main():
         "finite": finite, "phase_ms_per_step": phases, "roofline": roofline,
         "aggregation": {"d": d_big, "P": P, "GB/s": round(agg_gbs, 1), "frac_hbm_peak": round(agg_gbs / HBM_PEAK_GBS, 4)},
     }
+    if args.copy_calibration:
+        n_cal = 64 * 1024 * 1024
+        src, dst = torch.ones(n_cal, device="cuda"), torch.empty(n_cal, device="cuda")
+        for _ in range(3):
+            bls.weighted_aggregate(ctx, [src], [1.0], dst)
+        torch.cuda.synchronize()
+        line["copy_calibration"] = {"kernel": "agg_vec4_kernel", "last_launches": 3, "bytes_read": 4 * n_cal, "bytes_written": 4 * n_cal}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, p, b, x, y)
     print(json.dumps(line))
