@@ -575,7 +575,7 @@ static ConvGeom wgrad_geom(const ConvShape& cs) {
 
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    int cap = 1024 / blocks;
+    int cap = 512 / blocks;
     return n_tiles < cap ? n_tiles : cap;
 }
 
