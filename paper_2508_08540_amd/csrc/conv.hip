@@ -242,6 +242,31 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
                         ssum[j] += gq;
                         ssq[j] = __fmaf_rn(gq, (yv[j] - mu[j]) * is[j], ssq[j]);
                     }
+                } else if (EPI == 3) {
+                    // inference: batch norm with running statistics, shortcut, ReLU
+                    const f32x4 mu = *reinterpret_cast<const f32x4*>(e.mean_prev + c0);
+                    const f32x4 rv = *reinterpret_cast<const f32x4*>(e.invstd_prev + c0);  // running variance
+                    const f32x4 ga = *reinterpret_cast<const f32x4*>(e.gamma + c0);
+                    const f32x4 be = *reinterpret_cast<const f32x4*>(e.beta + c0);
+                    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+                    if (e.sc_g && c0 >= e.sc_lo && c0 < e.sc_lo + e.sc_c) {
+                        int64_t rp = p;
+                        if (e.sc_stride != 1) {
+                            const int wq = (int)(p & (g.h_out - 1));
+                            const int64_t row = p >> g.wout_log2;
+                            const int hq = (int)(row & (g.h_out - 1));
+                            const int64_t n = row >> g.wout_log2;
+                            const int hr = g.h_out * e.sc_stride;
+                            rp = (n * hr + (int64_t)hq * e.sc_stride) * hr + (int64_t)wq * e.sc_stride;
+                        }
+                        r = *reinterpret_cast<const f32x4*>(e.sc_g + rp * e.sc_c + (c0 - e.sc_lo));
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float is = (float)(1.0 / sqrt((double)rv[j] + 1e-5));
+                        v[j] = fmaxf(__fmaf_rn((v[j] - mu[j]) * is, ga[j], be[j]) + r[j], 0.f);
+                    }
+                    *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
                 } else {
                     *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
                     ssum += v;
@@ -257,6 +282,7 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
 // EPI 2 (input gradient): the shortcut gradient is added before the store, and the output is masked by
 // the ReLU of the layer below and reduced to the two sums of that layer's batch-norm backward pass.
 // For EPI 1 and 2 every workgroup adds its sums into per-channel fixed-point accumulators (integer atomics).
+// EPI 3 (inference): batch norm with the running statistics, shortcut add and ReLU are applied before the store.
 //
 // The grid is persistent: workgroup b handles tiles b, b + gridDim.x, ...  While the MFMAs of one tile
 // run from one LDS buffer, the global loads of the next tile are in flight into registers and are then
@@ -307,7 +333,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
         }
     }
 
-    if (EPI != 0) {
+    if (EPI == 1 || EPI == 2) {
         // lanes of one group hold the same 4 channels for 16 different pixels: fold the pixels
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1)
@@ -351,7 +377,7 @@ static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, cons
     // than one tile per workgroup to pay off
     const int pipelined = (g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
     size_t lds = input_lds_floats<CIN>(g) * sizeof(float) * (pipelined ? 2 : 1);
-    if (EPI != 0 && lds < 1024) lds = 1024;  // per-wave partial sums
+    if ((EPI == 1 || EPI == 2) && lds < 1024) lds = 1024;  // per-wave partial sums
     auto kern = conv_kernel<CIN, MT, NW, EPI>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)
@@ -421,7 +447,8 @@ void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const f
                      const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
-    if (stats) launch_conv_c<1>(s, cs.c_in, g, x, w, y, *stats, kt);
+    if (stats && stats->gamma) launch_conv_c<3>(s, cs.c_in, g, x, w, y, *stats, kt);
+    else if (stats) launch_conv_c<1>(s, cs.c_in, g, x, w, y, *stats, kt);
     else launch_conv_c<0>(s, cs.c_in, g, x, w, y, ConvEpi{}, kt);
 }
 

@@ -121,10 +121,14 @@ struct ConvEpi {
     const float* sc_g;
     int sc_c, sc_lo, sc_stride;
     const float *a_prev, *y_prev, *mean_prev, *invstd_prev;
+    // inference forward (gamma != nullptr): out = relu(bn(y) + shortcut) with mean_prev = running mean, invstd_prev =
+    // running variance, sc_g = shortcut source (c channels sc_c, first output channel sc_lo, spatial stride sc_stride)
+    const float *gamma, *beta;
 };
 int conv_fwd_tiles(const ConvShape& cs);
 // In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
-// y = conv(x, w); with `stats` the kernel also accumulates (sum, sum of squares) of y per channel.
+// y = conv(x, w); with `stats` the kernel also accumulates (sum, sum of squares) of y per channel, or, when
+// stats->gamma is set, applies inference batch norm + shortcut + ReLU before storing.
 void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,
                      const KernelTiming* kt = nullptr);
 // dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also the batch-norm backward sums of the layer

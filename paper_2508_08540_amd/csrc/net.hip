@@ -191,11 +191,20 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             e.scale = FIX_FWD_SCALE;
             PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
         } else {
-            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, nullptr, kt));
-            PROF(ctx, PROF_NORM, launch_bn_eval_stats(st, buffers + cb.rmean_off, buffers + cb.rvar_off, cb.c_out, s.mean[l], s.invstd[l]));
+            // inference: one kernel per layer, batch norm (running statistics), shortcut and ReLU in the epilogue
+            ConvEpi e{};
+            e.mean_prev = buffers + cb.rmean_off; e.invstd_prev = buffers + cb.rvar_off;
+            e.gamma = params + cb.gamma_off; e.beta = params + cb.beta_off;
+            if (is_conv2) {
+                const ConvBn& c1 = m->layers[l - 1];
+                e.sc_g = block_in; e.sc_c = c1.c_in; e.sc_lo = (cb.c_out - c1.c_in) / 2; e.sc_stride = c1.stride;
+            }
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
+            cur = y;
+            continue;
         }
         BnStats bs{};
-        bs.sums = train ? s.sums + (size_t)l * 2 * FIX_SET : nullptr;
+        bs.sums = s.sums + (size_t)l * 2 * FIX_SET;
         bs.count = (double)pixels;
         bs.mean = s.mean[l]; bs.invstd = s.invstd[l];
         bs.running_mean = buffers + cb.rmean_off; bs.running_var = buffers + cb.rvar_off;
