@@ -150,3 +150,13 @@ def test_full_workload_configuration(env):
             np.testing.assert_array_equal(a_[name], b_[name])
     np.testing.assert_array_equal(r1[3], r2[3])
     assert r1[3][-1].mean() < r1[3][0].mean()                 # training on the selected batch lowers its loss
+
+
+def test_scoring_in_several_chunks_and_wide_images(env):
+    # pools larger than the library's scoring chunk (512) are processed in pieces; 64x64 images take the
+    # non-prefetching staging path of the convolution kernel
+    h = _harness(env, (16, 32, 64), 1, 8)
+    p, b = synth.resnet_init(CFG["id"], (16, 32, 64), 1, 10, perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], 1100, 10, hw=8)
+    assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y))
+    _grad_case(env, (16, 16, 32), 1, 64, 2)
