@@ -3,6 +3,9 @@
 One "step" is one pass of the whole hot path on the ResNet20 fp32 workload: score the 512-image
 pool, select the 128 highest-loss samples, run 20 local SGD steps of batch 128 on them, and aggregate
 10 parameter replicas with step-count weights.  Prints one JSON line.
+
+--workload resnet20_bf16 measures the mixed-precision variant instead (bf16 activations, fp32 master
+weights, pool 4096, k 1024, 50 local steps); the default line stays the fp32 workload.
 """
 import argparse
 import json
@@ -22,6 +25,7 @@ MEASURED_TRAFFIC = {
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
+BF16_MFMA_PEAK_TFLOPS = 2500.0
 
 
 def resnet_conv_flops(widths, blocks, hw, in_ch):
@@ -42,6 +46,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16"])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -58,9 +63,10 @@ def main():
     import synth
     import paper_2508_08540_amd as bls
 
-    cfg = synth.workload("resnet20_fp32")
+    cfg = synth.workload(args.workload)
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
-    model = bls.Model.resnet_cifar()
+    act_dtype = cfg.get("act_dtype", "f32")
+    model = bls.Model.resnet_cifar(act_dtype=act_dtype)
     d = model.num_params
     p, b = synth.resnet_init(cfg["id"])
     x, y = synth.image_pool(cfg["id"], N, cfg["classes"])
@@ -116,15 +122,18 @@ def main():
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
     symbol = {"conv_fwd": "conv_kernel (forward launches)", "conv_dgrad": "conv_kernel (input-gradient launches)",
               "conv_wgrad": "wgrad_kernel"}[dom]
+    # forward and input-gradient convolutions run on the matrix instruction of the storage type; the weight
+    # gradient always multiplies in fp32
+    peak = BF16_MFMA_PEAK_TFLOPS if (act_dtype == "bf16" and dom != "conv_wgrad") else FP32_MFMA_PEAK_TFLOPS
     traffic = None
-    rec = MEASURED_TRAFFIC.get(symbol)
+    rec = MEASURED_TRAFFIC.get(symbol) if act_dtype == "f32" else None
     if rec:
         import hashlib
         with open(os.path.join(ROOT, rec["source"]), "rb") as fh:
             if hashlib.sha256(fh.read()).hexdigest()[:16] == rec["sha256_16"]:
                 traffic = int(1024 * (rec["fetch_kib"] * rec["fetch_scale"] + rec["write_kib"] * rec["write_scale"]))
-    roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
+    roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2), "launches_per_step": dom_cnt // args.steps}
 
     # Aggregation bandwidth on a vector large enough to leave the caches (WRN-16-8 sized, P = 10),
@@ -148,8 +157,8 @@ def main():
     line = {
         "metric": "selected samples/s per local step (ResNet20)", "value": round(value, 1), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "resnet20_fp32", "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(d)},
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": act_dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(d)},
         "finite": finite, "phase_ms_per_step": phases, "roofline": roofline,
         "aggregation": {"d": d_big, "P": P, "GB/s": round(agg_gbs, 1), "frac_hbm_peak": round(agg_gbs / HBM_PEAK_GBS, 4)},
     }
@@ -220,7 +229,7 @@ def cpu_baseline(cfg, p, b, x, y):
     import synth
     from threadpoolctl import threadpool_info
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
-    m = oracle.ResNetCifar()
+    m = oracle.ResNetCifar(storage=oracle.round_bf16 if cfg.get("act_dtype") == "bf16" else None)
     n_score = 64
     t = time.perf_counter()
     ls = oracle.score_losses(m, p, b, x[:n_score], y[:n_score])

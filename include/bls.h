@@ -46,6 +46,11 @@ typedef struct bls_model bls_model; /* architecture and flat-parameter layout (h
 
 enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1 };
 
+/* Storage type of the activations (and of the copies of the convolution weights the kernels read).
+ * Parameters, momentum, gradients, batch-norm statistics, losses and every reduction stay fp32: with
+ * BLS_ACT_BF16 the parameter vector is the fp32 master copy of a mixed-precision run. */
+enum { BLS_ACT_F32 = 0, BLS_ACT_BF16 = 1 };
+
 /* Architecture description.
  *   MLP:           image_hw*image_hw*in_channels -> hidden (ReLU) -> classes.
  *   RESNET_CIFAR:  3x3 stem conv to widths[0], three stages of `blocks` two-convolution residual
@@ -61,6 +66,7 @@ typedef struct {
     int32_t hidden;      /* MLP only: multiple of 16, 16 .. 1024           */
     int32_t widths[3];   /* RESNET only: each of 16, 32 or 64              */
     int32_t blocks;      /* RESNET only: 1 .. 6                            */
+    int32_t act_dtype;   /* BLS_ACT_*; the MLP supports BLS_ACT_F32 only   */
 } bls_model_desc;
 
 /* One tensor of the flat parameter vector (is_buffer = 0) or of the flat buffer vector that

@@ -5,6 +5,15 @@ He et al. (2016) that the paper calls ResNet20 (Section 5): 3x3 stem, 3 stages x
 of widths 16/32/64, parameter-free shortcuts, global average pooling and a linear classifier.
 Widths, depth and image size are arguments so that tiny instances can be checked by finite
 differences.  Parameters and buffers are dicts of float64 arrays keyed by tensor name.
+
+Mixed precision.  ResNetCifar takes an optional `storage` function (e.g. precision.round_bf16)
+that maps an array onto the grid of the format activations are kept in.  It is applied wherever a
+mixed-precision run holds a tensor in that format: the input images, the convolution weights as the
+convolutions read them (the parameters themselves stay full precision), every convolution output
+that batch norm takes its batch statistics from, every activation, and in the backward pass every
+gradient with respect to a convolution output or a convolution input.  Sums, statistics, the
+classifier, losses and parameter gradients are never rounded.  With storage=None (the default) this
+is the plain float64 model.
 """
 import numpy as np
 
@@ -36,9 +45,10 @@ class MLP:
 class ResNetCifar:
     has_buffers = True
 
-    def __init__(self, widths=(16, 32, 64), blocks=3):
+    def __init__(self, widths=(16, 32, 64), blocks=3, storage=None):
         self.widths = tuple(widths)
         self.blocks = blocks
+        self.q = storage if storage is not None else (lambda a: a)
 
     def _block_list(self):
         out, c_prev = [], self.widths[0]
@@ -60,26 +70,31 @@ class ResNetCifar:
     def forward(self, params, buffers, x, train):
         """Returns (logits [B, classes], cache for backward, buffers after this pass)."""
         p, bufs = _f64(params), _f64(buffers)
+        q = self.q
+        qy = q if train else (lambda a: a)   # in inference batch norm is applied to the unrounded convolution result
+        # "w": the convolution weights as the convolutions read them
+        cache_w = {k: q(v) for k, v in p.items() if k.endswith("conv.weight") or ".conv1." in k or ".conv2." in k}
         new_bufs = dict(bufs)
-        x = np.asarray(x, dtype=np.float64)
-        cache = {"p": p, "x": x, "z": {}}   # "z": pre-activation of every ReLU, keyed by the name of its output
-        y0 = L.conv3x3(x, p["stem.conv.weight"], 1)
+        x = q(np.asarray(x, dtype=np.float64))
+        cache = {"p": p, "w": cache_w, "x": x, "z": {}}   # "z": pre-activation of every ReLU, keyed by the name of its output
+        w = cache_w
+        y0 = qy(L.conv3x3(x, w["stem.conv.weight"], 1))
         z0, cache["stem.bn"] = self._bn("stem.bn", y0, p, bufs, new_bufs, train)
         cache["z"]["stem.out"] = z0
-        a = L.relu(z0)
+        a = q(L.relu(z0))
         cache["stem.out"] = a
         for name, c_in, c_out, stride in self._block_list():
             cache[name + ".in"] = a
-            y1 = L.conv3x3(a, p[name + ".conv1.weight"], stride)
+            y1 = qy(L.conv3x3(a, w[name + ".conv1.weight"], stride))
             z1, cache[name + ".bn1"] = self._bn(name + ".bn1", y1, p, bufs, new_bufs, train)
             cache["z"][name + ".h1"] = z1
-            h1 = L.relu(z1)
+            h1 = q(L.relu(z1))
             cache[name + ".h1"] = h1
-            y2 = L.conv3x3(h1, p[name + ".conv2.weight"], 1)
+            y2 = qy(L.conv3x3(h1, w[name + ".conv2.weight"], 1))
             z2, cache[name + ".bn2"] = self._bn(name + ".bn2", y2, p, bufs, new_bufs, train)
             zo = z2 + L.shortcut(a, c_out, stride)
             cache["z"][name + ".out"] = zo
-            a = L.relu(zo)
+            a = q(L.relu(zo))
             cache[name + ".out"] = a
         cache["final"] = a
         pooled = L.global_avgpool(a)
@@ -91,7 +106,7 @@ class ResNetCifar:
         """Gradients of sum_b <dlogits_b, logits_b> with respect to every parameter (train mode).
 
         toggles: optional {relu output name: flat indices} passed to relu_backward."""
-        p = cache["p"]
+        p, w, q = cache["p"], cache["w"], self.q
         g = {}
         tg = toggles or {}
         dpooled, g["fc.weight"], g["fc.bias"] = L.linear_backward(cache["pooled"], p["fc.weight"], dlogits)
@@ -99,13 +114,15 @@ class ResNetCifar:
         for name, c_in, c_out, stride in reversed(self._block_list()):
             dz = L.relu_backward(da, cache[name + ".out"], tg.get(name + ".out"))
             dy2, g[name + ".bn2.weight"], g[name + ".bn2.bias"] = L.batchnorm_train_backward(dz, cache[name + ".bn2"])
-            dh1, g[name + ".conv2.weight"] = L.conv3x3_backward(cache[name + ".h1"], p[name + ".conv2.weight"], dy2, 1)
-            dz1 = L.relu_backward(dh1, cache[name + ".h1"], tg.get(name + ".h1"))
+            dy2 = q(dy2)
+            dh1, g[name + ".conv2.weight"] = L.conv3x3_backward(cache[name + ".h1"], w[name + ".conv2.weight"], dy2, 1)
+            dz1 = L.relu_backward(q(dh1), cache[name + ".h1"], tg.get(name + ".h1"))
             dy1, g[name + ".bn1.weight"], g[name + ".bn1.bias"] = L.batchnorm_train_backward(dz1, cache[name + ".bn1"])
+            dy1 = q(dy1)
             x_in = cache[name + ".in"]
-            dx, g[name + ".conv1.weight"] = L.conv3x3_backward(x_in, p[name + ".conv1.weight"], dy1, stride)
-            da = dx + L.shortcut_backward(dz, x_in.shape, stride)
+            dx, g[name + ".conv1.weight"] = L.conv3x3_backward(x_in, w[name + ".conv1.weight"], dy1, stride)
+            da = q(dx + L.shortcut_backward(q(dz), x_in.shape, stride))
         dz0 = L.relu_backward(da, cache["stem.out"], tg.get("stem.out"))
         dy0, g["stem.bn.weight"], g["stem.bn.bias"] = L.batchnorm_train_backward(dz0, cache["stem.bn"])
-        _, g["stem.conv.weight"] = L.conv3x3_backward(cache["x"], p["stem.conv.weight"], dy0, 1, need_dx=False)
+        _, g["stem.conv.weight"] = L.conv3x3_backward(cache["x"], w["stem.conv.weight"], q(dy0), 1, need_dx=False)
         return g

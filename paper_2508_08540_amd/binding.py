@@ -7,6 +7,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 MODEL_MLP, MODEL_RESNET_CIFAR = 0, 1
+ACT_DTYPES = {"f32": 0, "bf16": 1}
 AGG_NORMALISE, AGG_BROADCAST = 1, 2
 
 DECLARED_SYMBOLS = (
@@ -27,7 +28,7 @@ class BlsError(RuntimeError):
 
 class _ModelDesc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("classes", C.c_int32), ("image_hw", C.c_int32), ("in_channels", C.c_int32),
-                ("hidden", C.c_int32), ("widths", C.c_int32 * 3), ("blocks", C.c_int32)]
+                ("hidden", C.c_int32), ("widths", C.c_int32 * 3), ("blocks", C.c_int32), ("act_dtype", C.c_int32)]
 
 
 class _TensorInfo(C.Structure):
@@ -133,8 +134,11 @@ class Context:
 class Model:
     """Architecture description and flat layout; host only."""
 
-    def __init__(self, kind, classes=10, image_hw=32, in_channels=3, hidden=128, widths=(16, 32, 64), blocks=3):
-        desc = _ModelDesc(kind, classes, image_hw, in_channels, hidden, (C.c_int32 * 3)(*widths), blocks)
+    def __init__(self, kind, classes=10, image_hw=32, in_channels=3, hidden=128, widths=(16, 32, 64), blocks=3,
+                 act_dtype="f32"):
+        desc = _ModelDesc(kind, classes, image_hw, in_channels, hidden, (C.c_int32 * 3)(*widths), blocks,
+                          ACT_DTYPES[act_dtype])
+        self.act_dtype = act_dtype
         h = C.c_void_p()
         rc = lib.bls_model_create(C.byref(desc), C.byref(h))
         if rc != 0:
@@ -154,8 +158,9 @@ class Model:
         return cls(MODEL_MLP, classes, d_hw, in_channels, hidden)
 
     @classmethod
-    def resnet_cifar(cls, widths=(16, 32, 64), blocks=3, classes=10, image_hw=32, in_channels=3):
-        return cls(MODEL_RESNET_CIFAR, classes, image_hw, in_channels, 0, widths, blocks)
+    def resnet_cifar(cls, widths=(16, 32, 64), blocks=3, classes=10, image_hw=32, in_channels=3, act_dtype="f32"):
+        """act_dtype "bf16": activations and the kernels' weight copies in bf16, everything else fp32."""
+        return cls(MODEL_RESNET_CIFAR, classes, image_hw, in_channels, 0, widths, blocks, act_dtype)
 
     def pack(self, tensors, buffers=False):
         """dict name -> array  =>  flat float32 numpy vector in the library's layout."""

@@ -158,6 +158,8 @@ int bls_model_create(const bls_model_desc* desc, bls_model** out) {
     if (!desc || !out) return BLS_EINVAL;
     *out = nullptr;
     if (desc->classes < 2 || desc->classes > 64) return BLS_EINVAL;
+    if (desc->act_dtype != BLS_ACT_F32 && desc->act_dtype != BLS_ACT_BF16) return BLS_EINVAL;
+    if (desc->kind == BLS_MODEL_MLP && desc->act_dtype != BLS_ACT_F32) return BLS_EUNSUPPORTED;
     bls_model* m = new (std::nothrow) bls_model();
     if (!m) return BLS_ENOMEM;
     m->desc = *desc;

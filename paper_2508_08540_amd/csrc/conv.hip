@@ -17,7 +17,41 @@
 //
 // Weight gradient (wgrad_kernel).  dW[o][tap][i] = sum_pixels dy[p][o] * x[p + tap][i] is a GEMM with
 // K = B*H*W: see the comment above that kernel.
-#include "kernels.h"
+//
+// Storage type.  All kernels are templates on the type T activations are stored in.  With bf16 the tile
+// in LDS and the packed weights are bf16 too (half the bytes everywhere), the same lane-to-channel
+// assignment feeds v_mfma_f32_16x16x16_bf16 (one instruction per tap and 16 input channels instead of four),
+// accumulation stays fp32 and results are rounded to bf16 once, at the store; the reductions of the epilogue
+// see the rounded values, i.e. exactly what later kernels read back.  The weight gradient converts
+// bf16 operands to fp32 while staging and runs the fp32 instruction, so master-weight gradients keep fp32
+// products.
+#include "act.h"
+
+// A "quad" is 4 consecutive channels as they sit in LDS and in the packed weights; vec16 is one 16-byte
+// global load (VQ quads).
+template <typename T>
+struct Tile;
+template <>
+struct Tile<float> {
+    typedef f32x4 quad;
+    typedef f32x4 vec16;
+    static constexpr int VQ = 1;
+    static __device__ __forceinline__ vec16 zero16() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    static __device__ __forceinline__ void store16(quad* dst, const vec16& v) { dst[0] = v; }
+};
+template <>
+struct Tile<bf16_t> {
+    typedef uint2 quad;
+    typedef uint4 vec16;
+    static constexpr int VQ = 2;
+    static __device__ __forceinline__ vec16 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
+    static __device__ __forceinline__ void store16(quad* dst, const vec16& v) {
+        dst[0] = make_uint2(v.x, v.y);
+        dst[1] = make_uint2(v.z, v.w);
+    }
+};
+
+constexpr int clog2(int v) { return v <= 1 ? 0 : 1 + clog2(v >> 1); }
 
 #define CONV_THREADS 256
 #ifndef CONV_MT
@@ -57,18 +91,21 @@ static ConvGeom make_geom(int B, int h_in, int h_out, int c_out, int stride, int
     return g;
 }
 
-template <int CIN>
-static size_t input_lds_floats(const ConvGeom& g) {
-    return (size_t)g.imgs * g.in_rows * g.lw * (CIN + 4);
+// LDS bytes of one staged tile: pixel pitch CIN/4 + 1 quads
+template <typename T, int CIN>
+static size_t input_lds_bytes(const ConvGeom& g) {
+    return (size_t)g.imgs * g.in_rows * g.lw * (CIN / 4 + 1) * sizeof(typename Tile<T>::quad);
 }
 
 // Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + PAD], zero outside the image.
 // `pitch` is the channel count of the tensor in memory and `c_off` the first channel of the CIN-wide slice.
-// A thread owns one 16-byte column (lc, channel quad) and walks the rows, so the row arithmetic is
+// A thread owns one quad column (lc, 4 channels) and walks the rows, so the row arithmetic is
 // wave-uniform (scalar unit) and no per-element division is needed; loads are issued six rows at a time.
-template <int CIN, int THREADS = CONV_THREADS, int PAD = 4>
-__device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const float* __restrict__ x, const ConvGeom& g,
+// D is the LDS element: the quad as stored, or f32x4 to widen bf16 to fp32 on the way in.
+template <typename T, typename D, int CIN, int THREADS = CONV_THREADS, int PAD = 4>
+__device__ __forceinline__ void stage_input(D* __restrict__ lds4, const T* __restrict__ x, const ConvGeom& g,
                                             int tile, int pitch = CIN, int c_off = 0) {
+    typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + PAD) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
     constexpr int R = 6;
@@ -86,10 +123,10 @@ __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const floa
             wok = wok && ((wi & 1) == 0);
             wsrc = wi >> 1;
         }
-        const float* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + c_off + cq * 4;
-        f32x4* dst = lds4 + lc * CP4 + cq;
+        const T* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + c_off + cq * 4;
+        D* dst = lds4 + lc * CP4 + cq;
         for (int r0 = 0; r0 < rows_total; r0 += R) {
-            f32x4 v[R];
+            raw4 v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int lr = r0 + r;                               // wave-uniform
@@ -103,12 +140,15 @@ __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const floa
                     ok = ok && ((hi & 1) == 0);
                     hsrc = hi >> 1;
                 }
-                v[r] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (ok) v[r] = *reinterpret_cast<const f32x4*>(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
+                v[r] = Act<T>::zero();
+                if (ok) v[r] = Act<T>::load_raw(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
             }
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                if (r0 + r < rows_total) dst[(r0 + r) * g.lw * CP4] = v[r];
+                if (r0 + r < rows_total) {
+                    if constexpr (sizeof(D) == sizeof(raw4)) dst[(r0 + r) * g.lw * CP4] = v[r];
+                    else dst[(r0 + r) * g.lw * CP4] = Act<T>::widen(v[r]);
+                }
         }
     }
 }
@@ -116,11 +156,11 @@ __device__ __forceinline__ void stage_input(f32x4* __restrict__ lds4, const floa
 // The same staging split in two for software pipelining: tile_load issues the global loads of a tile into
 // registers (column per thread, up to PRE_ROWS rows), tile_store writes them to an LDS buffer later.
 #define PRE_ROWS 12
-template <int CIN, int PAD = 4>
-__device__ __forceinline__ void tile_load(f32x4 (&v)[PRE_ROWS], const float* __restrict__ x, const ConvGeom& g, int tile,
-                                          int pitch = CIN, int c_off = 0) {
-    constexpr int CQ = CIN / 4;
-    constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
+template <typename T, int CIN>
+__device__ __forceinline__ void tile_load(typename Tile<T>::vec16 (&v)[PRE_ROWS], const T* __restrict__ x, const ConvGeom& g, int tile) {
+    constexpr int CQ = CIN / 4 / Tile<T>::VQ;  // 16-byte columns per pixel
+    constexpr int CQ_LOG2 = clog2(CQ);
+    constexpr int pitch = CIN;
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
     const int rows_total = g.imgs * g.in_rows;
@@ -134,7 +174,7 @@ __device__ __forceinline__ void tile_load(f32x4 (&v)[PRE_ROWS], const float* __r
         wok = wok && ((wi & 1) == 0);
         wsrc = wi >> 1;
     }
-    const float* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + c_off + cq * 4;
+    const T* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + cq * (4 * Tile<T>::VQ);
 #pragma unroll
     for (int r = 0; r < PRE_ROWS; ++r) {
         const int part = r / g.in_rows, li = r - part * g.in_rows;  // wave-uniform
@@ -147,22 +187,23 @@ __device__ __forceinline__ void tile_load(f32x4 (&v)[PRE_ROWS], const float* __r
             ok = ok && ((hi & 1) == 0);
             hsrc = hi >> 1;
         }
-        v[r] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (ok) v[r] = *reinterpret_cast<const f32x4*>(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
+        v[r] = Tile<T>::zero16();
+        if (ok) v[r] = *reinterpret_cast<const typename Tile<T>::vec16*>(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
     }
 }
 
-template <int CIN, int PAD = 4>
-__device__ __forceinline__ void tile_store(const f32x4 (&v)[PRE_ROWS], f32x4* __restrict__ lds4, const ConvGeom& g) {
-    constexpr int CP4 = (CIN + PAD) / 4, CQ = CIN / 4;
-    constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
+template <typename T, int CIN>
+__device__ __forceinline__ void tile_store(const typename Tile<T>::vec16 (&v)[PRE_ROWS], typename Tile<T>::quad* __restrict__ ldsq,
+                                           const ConvGeom& g) {
+    constexpr int CPQ = CIN / 4 + 1, CQ = CIN / 4 / Tile<T>::VQ;
+    constexpr int CQ_LOG2 = clog2(CQ);
     const int col = threadIdx.x;
     if (col >= g.lw * CQ) return;
     const int rows_total = g.imgs * g.in_rows;
-    f32x4* dst = lds4 + (col >> CQ_LOG2) * CP4 + (col & (CQ - 1));
+    typename Tile<T>::quad* dst = ldsq + (col >> CQ_LOG2) * CPQ + (col & (CQ - 1)) * Tile<T>::VQ;
 #pragma unroll
     for (int r = 0; r < PRE_ROWS; ++r)
-        if (r < rows_total) dst[r * g.lw * CP4] = v[r];
+        if (r < rows_total) Tile<T>::store16(dst + r * g.lw * CPQ, v[r]);
 }
 
 // LDS float offset of the top-left tap of output pixel q (index inside the tile).
@@ -174,10 +215,12 @@ __device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
 }
 
 // MFMAs, epilogue and store of one staged tile for this wave.
-template <int CIN, int MT, int NW, int EPI>
-__device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const f32x4 (&wr)[9][CIN / 16], float* __restrict__ y,
-                                          const ConvEpi& e, const ConvGeom& g, int tile, f32x4& ssum, f32x4& ssq) {
+template <typename T, int CIN, int MT, int NW, int EPI>
+__device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restrict__ lds4, const typename Tile<T>::quad (&wr)[9][CIN / 16],
+                                          T* __restrict__ y, const ConvEpi& e, const ConvGeom& g, int tile, f32x4& ssum, f32x4& ssq) {
+    typedef typename Tile<T>::quad quad;
     constexpr int CP = CIN + 4, S = CIN / 16;
+    const T* sc_g = static_cast<const T*>(e.sc_g);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;
     const int NO = g.c_out, NOB = NO >> 4;
@@ -199,14 +242,22 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
             const int tap_off = ((t / 3) * g.lw + (t % 3)) * (CP / 4);
 #pragma unroll
             for (int s = 0; s < S; ++s) {
-                f32x4 b[MT];
+                quad b[MT];
 #pragma unroll
                 for (int m = 0; m < MT; ++m) b[m] = lds4[base[m] + tap_off + 4 * s];
+                if constexpr (sizeof(T) == 4) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int m = 0; m < MT; ++m)
+                            acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[t][s][j], b[m][j], acc[m], 0, 0, 0);
+                } else {
+                    // K = 16: lane group g supplies channels 16s + 4g .. +3 of both operands
 #pragma unroll
                     for (int m = 0; m < MT; ++m)
-                        acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[t][s][j], b[m][j], acc[m], 0, 0, 0);
+                        acc[m] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, wr[t][s]),
+                                                                           __builtin_bit_cast(s16x4, b[m]), acc[m], 0, 0, 0);
+                }
             }
         }
 #pragma unroll
@@ -219,7 +270,7 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
                     if (e.sc_g) {
                         // gradient that bypassed the block below through its shortcut
                         if (e.sc_stride == 1) {
-                            v += *reinterpret_cast<const f32x4*>(e.sc_g + p * e.sc_c + c0);
+                            v += Act<T>::load4(sc_g + p * e.sc_c + c0);
                         } else {
                             const int wq = (int)(p & (g.h_out - 1));
                             const int64_t row = p >> g.wout_log2;
@@ -227,13 +278,14 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
                             if (((wq | hq) & 1) == 0) {
                                 const int64_t n = row >> g.wout_log2;
                                 const int hs = g.h_out >> 1;
-                                v += *reinterpret_cast<const f32x4*>(e.sc_g + ((n * hs + (hq >> 1)) * hs + (wq >> 1)) * e.sc_c + e.sc_lo + c0);
+                                v += Act<T>::load4(sc_g + ((n * hs + (hq >> 1)) * hs + (wq >> 1)) * e.sc_c + e.sc_lo + c0);
                             }
                         }
                     }
-                    *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
-                    const f32x4 av = *reinterpret_cast<const f32x4*>(e.a_prev + p * NO + c0);
-                    const f32x4 yv = *reinterpret_cast<const f32x4*>(e.y_prev + p * NO + c0);
+                    v = Act<T>::rounded(v);  // the sums below see what later kernels read back
+                    Act<T>::store4(y + p * NO + c0, v);
+                    const f32x4 av = Act<T>::load4(static_cast<const T*>(e.a_prev) + p * NO + c0);
+                    const f32x4 yv = Act<T>::load4(static_cast<const T*>(e.y_prev) + p * NO + c0);
                     const f32x4 mu = *reinterpret_cast<const f32x4*>(e.mean_prev + c0);
                     const f32x4 is = *reinterpret_cast<const f32x4*>(e.invstd_prev + c0);
 #pragma unroll
@@ -259,16 +311,17 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
                             const int hr = g.h_out * e.sc_stride;
                             rp = (n * hr + (int64_t)hq * e.sc_stride) * hr + (int64_t)wq * e.sc_stride;
                         }
-                        r = *reinterpret_cast<const f32x4*>(e.sc_g + rp * e.sc_c + (c0 - e.sc_lo));
+                        r = Act<T>::load4(sc_g + rp * e.sc_c + (c0 - e.sc_lo));
                     }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float is = (float)(1.0 / sqrt((double)rv[j] + 1e-5));
                         v[j] = fmaxf(__fmaf_rn((v[j] - mu[j]) * is, ga[j], be[j]) + r[j], 0.f);
                     }
-                    *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
+                    Act<T>::store4(y + p * NO + c0, v);
                 } else {
-                    *reinterpret_cast<f32x4*>(y + p * NO + c0) = v;
+                    v = Act<T>::rounded(v);
+                    Act<T>::store4(y + p * NO + c0, v);
                     ssum += v;
                     ssq += v * v;
                 }
@@ -287,11 +340,13 @@ __device__ __forceinline__ void conv_tile(const f32x4* __restrict__ lds4, const 
 // The grid is persistent: workgroup b handles tiles b, b + gridDim.x, ...  While the MFMAs of one tile
 // run from one LDS buffer, the global loads of the next tile are in flight into registers and are then
 // written to the other buffer (one barrier per tile).
-template <int CIN, int MT, int NW, int EPI>
-__global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                            float* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
-    extern __shared__ f32x4 lds4[];  // float4-typed so that tile reads and writes are single 16-byte LDS accesses
-    float* lds = reinterpret_cast<float*>(lds4);
+template <typename T, int CIN, int MT, int NW, int EPI>
+__global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
+                                                            T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
+    typedef typename Tile<T>::quad quad;
+    extern __shared__ f32x4 lds_raw[];  // vector-typed so that tile reads and writes are single 16- or 8-byte LDS accesses
+    quad* lds4 = reinterpret_cast<quad*>(lds_raw);
+    float* lds = reinterpret_cast<float*>(lds_raw);
     constexpr int S = CIN / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;
@@ -300,9 +355,9 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
 
     // weights of output-channel block `ob` into registers: wr[tap][s] holds input channels 16s+4grp .. +3 of
     // output channel 16*ob + r16, read from the lane-major packed copy (one contiguous 1 KB load each)
-    f32x4 wr[9][S];
+    quad wr[9][S];
     {
-        const f32x4* wp = reinterpret_cast<const f32x4*>(w) + (int64_t)ob * 9 * S * 64 + lane;
+        const quad* wp = reinterpret_cast<const quad*>(w) + (int64_t)ob * 9 * S * 64 + lane;
 #pragma unroll
         for (int t = 0; t < 9; ++t)
 #pragma unroll
@@ -312,23 +367,23 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
 
     if (pipelined) {
         const int buf_f4 = g.imgs * g.in_rows * g.lw * ((CIN + 4) / 4);
-        f32x4 pre[PRE_ROWS];
+        typename Tile<T>::vec16 pre[PRE_ROWS];
         int tile = blockIdx.x;
-        tile_load<CIN>(pre, x, g, tile);
-        tile_store<CIN>(pre, lds4, g);
+        tile_load<T, CIN>(pre, x, g, tile);
+        tile_store<T, CIN>(pre, lds4, g);
         __syncthreads();
         for (int it = 0; tile < g.n_tiles; ++it, tile += gridDim.x) {
             const int next = tile + gridDim.x;
-            if (next < g.n_tiles) tile_load<CIN>(pre, x, g, next);
-            conv_tile<CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
-            if (next < g.n_tiles) tile_store<CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
+            if (next < g.n_tiles) tile_load<T, CIN>(pre, x, g, next);
+            conv_tile<T, CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
+            if (next < g.n_tiles) tile_store<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
             __syncthreads();
         }
     } else {
         for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
-            stage_input<CIN, NW * 64>(lds4, x, g, tile);
+            stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();
-            conv_tile<CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
+            conv_tile<T, CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
             __syncthreads();
         }
     }
@@ -368,44 +423,52 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const float* __restrict__
 #endif
 static int conv_grid(const ConvGeom& g) { return g.n_tiles < CONV_GRID_CAP ? g.n_tiles : CONV_GRID_CAP; }
 
-template <int CIN, int EPI>
-static void launch_conv_t(hipStream_t s, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e,
+template <typename T, int CIN, int EPI>
+static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const void* w, T* y, const ConvEpi& e,
                           const KernelTiming* kt) {
     constexpr int MT = CONV_MT, NW = CONV_NW;
     const int grid = conv_grid(g);
     // prefetching needs the whole tile in PRE_ROWS registers per thread, one column per thread, and more
     // than one tile per workgroup to pay off
-    const int pipelined = (g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
-    size_t lds = input_lds_floats<CIN>(g) * sizeof(float) * (pipelined ? 2 : 1);
+    const int pipelined = (g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
+    size_t lds = input_lds_bytes<T, CIN>(g) * (pipelined ? 2 : 1);
     if ((EPI == 1 || EPI == 2) && lds < 1024) lds = 1024;  // per-wave partial sums
-    auto kern = conv_kernel<CIN, MT, NW, EPI>;
+    auto kern = conv_kernel<T, CIN, MT, NW, EPI>;
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)
     hipExtLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, s, kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, w, y, e, g,
                           pipelined);
 }
 
-template <int EPI>
-static void launch_conv_c(hipStream_t s, int c_in, const ConvGeom& g, const float* x, const float* w, float* y, const ConvEpi& e,
-                          const KernelTiming* kt) {
+template <typename T, int EPI>
+static void launch_conv_ct(hipStream_t s, int c_in, const ConvGeom& g, const void* x, const void* w, void* y, const ConvEpi& e,
+                           const KernelTiming* kt) {
     switch (c_in) {
-        case 16: launch_conv_t<16, EPI>(s, g, x, w, y, e, kt); break;
-        case 32: launch_conv_t<32, EPI>(s, g, x, w, y, e, kt); break;
-        default: launch_conv_t<64, EPI>(s, g, x, w, y, e, kt); break;
+        case 16: launch_conv_t<T, 16, EPI>(s, g, (const T*)x, w, (T*)y, e, kt); break;
+        case 32: launch_conv_t<T, 32, EPI>(s, g, (const T*)x, w, (T*)y, e, kt); break;
+        default: launch_conv_t<T, 64, EPI>(s, g, (const T*)x, w, (T*)y, e, kt); break;
     }
+}
+
+template <int EPI>
+static void launch_conv_c(hipStream_t s, int act, int c_in, const ConvGeom& g, const void* x, const void* w, void* y, const ConvEpi& e,
+                          const KernelTiming* kt) {
+    if (act == ACT_BF16) launch_conv_ct<bf16_t, EPI>(s, c_in, g, x, w, y, e, kt);
+    else launch_conv_ct<float, EPI>(s, c_in, g, x, w, y, e, kt);
 }
 
 // ---- weight packing -----------------------------------------------------------------------------------
 //
 // Lane-major copies of every convolution's weights, rebuilt after each parameter update.  For a layer
-// with (padded) input channels CI and output channels CO the forward copy holds, as float4 number
+// with (padded) input channels CI and output channels CO the forward copy holds, as quad (4 values of the storage type) number
 // ((ob*9 + t)*(CI/16) + s)*64 + lane, the values w[16*ob + lane%16][t][16*s + 4*(lane/16) + 0..3] (zero
 // beyond the real input channels).  The input-gradient copy describes the transposed convolution:
 // roles of CI and CO swap and the taps are flipped, value j = w[16*s + 4*(lane/16) + j][8 - t][16*ob + lane%16].
 
-__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ params, float* __restrict__ packed,
+template <typename T>
+__global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ params, typename Tile<T>::quad* __restrict__ packed,
                                                            PackTable tab) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // float4 index
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // quad index
     if (i >= tab.total_vec4) return;
     int l = 0;
     while (l + 1 < tab.n && i >= tab.e[l + 1].pack_off) ++l;
@@ -430,12 +493,13 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = w[((int64_t)(i0 + j) * 9 + (8 - t)) * e.c_in_real + o];
     }
-    reinterpret_cast<f32x4*>(packed)[i] = v;
+    Act<T>::store4(reinterpret_cast<T*>(packed + i), v);
 }
 
-void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab) {
+void launch_pack_weights(hipStream_t s, int act, const float* params, void* packed, const PackTable& tab) {
     int64_t blocks = (tab.total_vec4 + 255) / 256;
-    hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, s, params, packed, tab);
+    ACT_DISPATCH(act, hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, params,
+                                         (typename Tile<T>::quad*)packed, tab));
 }
 
 int conv_fwd_tiles(const ConvShape& cs) {
@@ -443,23 +507,23 @@ int conv_fwd_tiles(const ConvShape& cs) {
     return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
 }
 
-void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,
+void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
                      const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
-    if (stats && stats->gamma) launch_conv_c<3>(s, cs.c_in, g, x, w, y, *stats, kt);
-    else if (stats) launch_conv_c<1>(s, cs.c_in, g, x, w, y, *stats, kt);
-    else launch_conv_c<0>(s, cs.c_in, g, x, w, y, ConvEpi{}, kt);
+    if (stats && stats->gamma) launch_conv_c<3>(s, act, cs.c_in, g, x, w, y, *stats, kt);
+    else if (stats) launch_conv_c<1>(s, act, cs.c_in, g, x, w, y, *stats, kt);
+    else launch_conv_c<0>(s, act, cs.c_in, g, x, w, y, ConvEpi{}, kt);
 }
 
-void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below,
+void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt) {
     // The gradient with respect to the input is a stride-1 convolution whose input channels are the
     // layer's output channels and whose output channels are the layer's input channels.
     int ups = cs.stride == 2 ? 1 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in);
-    if (bn_below) launch_conv_c<2>(s, cs.c_out, g, dy, w, dx, *bn_below, kt);
-    else launch_conv_c<0>(s, cs.c_out, g, dy, w, dx, ConvEpi{}, kt);
+    if (bn_below) launch_conv_c<2>(s, act, cs.c_out, g, dy, w, dx, *bn_below, kt);
+    else launch_conv_c<0>(s, act, cs.c_out, g, dy, w, dx, ConvEpi{}, kt);
 }
 
 // ---- weight gradient ------------------------------------------------------------------------------
@@ -477,7 +541,8 @@ void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, cons
 
 #define WGRAD_THREADS 256
 
-__global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+template <typename T>
+__global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
                                                               int NI, int NO) {
     extern __shared__ f32x4 lds4[];
@@ -503,12 +568,12 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const float* __res
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         __syncthreads();  // previous tile fully consumed
-        stage_input<16, WGRAD_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
+        stage_input<T, f32x4, 16, WGRAD_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
         const int64_t pix0 = (int64_t)tile * tile_pixels;
         for (int i = threadIdx.x; i < tile_pixels * 4; i += WGRAD_THREADS) {
             int q = i >> 2, c4 = i & 3;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (pix0 + q < total_pixels) v = *reinterpret_cast<const f32x4*>(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
+            if (pix0 + q < total_pixels) v = Act<T>::load4(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
             reinterpret_cast<f32x4*>(lds_dy)[q * (DP / 4) + c4] = v;
         }
         __syncthreads();
@@ -608,17 +673,22 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
 
 int64_t conv_wgrad_accumulators(const ConvShape& cs) { return (int64_t)WGRAD_REPLICAS * cs.c_out * 9 * cs.c_in; }
 
-void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, fixsum_t* gacc,
-                       const KernelTiming* kt) {
+template <typename T>
+static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, const T* dy, fixsum_t* gacc, const KernelTiming* kt) {
     ConvGeom g = wgrad_geom(cs);
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
-    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipExtLaunchKernelGGL(wgrad_kernel, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
+    hipExtLaunchKernelGGL(wgrad_kernel<T>, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
                           kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out);
+}
+
+void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
+                       const KernelTiming* kt) {
+    ACT_DISPATCH(act, launch_conv_wgrad_t<T>(s, cs, (const T*)x, (const T*)dy, gacc, kt));
 }
 
 void launch_conv_wgrad_reduce(hipStream_t s, fixsum_t* gacc, float* grad, const WgradTable& tab) {

@@ -1,35 +1,43 @@
 // Small memory-bound kernels around the contractions: batch gather, SGD update, column sums.
-#include "kernels.h"
+#include "act.h"
 
+template <typename T>
+__device__ __forceinline__ T to_act(float v);
+template <>
+__device__ __forceinline__ float to_act<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ bf16_t to_act<bf16_t>(float v) { return f32_to_bf16(v); }
+
+template <typename T>
 __global__ __launch_bounds__(256) void gather_images_kernel(const float* __restrict__ src, const int32_t* __restrict__ y_src,
                                                             const int32_t* __restrict__ sel, int64_t k, int64_t start,
                                                             int64_t first, int batch, int pixels, int c_src, int c_dst,
-                                                            float* __restrict__ dst, int32_t* __restrict__ y_dst) {
+                                                            T* __restrict__ dst, int32_t* __restrict__ y_dst) {
     int b = blockIdx.y;
     int64_t img = sel ? (int64_t)sel[(start + b) % k] : first + b;
     const float* s = src + img * pixels * c_src;
-    float* d = dst + (int64_t)b * pixels * c_dst;
+    T* d = dst + (int64_t)b * pixels * c_dst;
     int total = pixels * c_dst;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
         int p = i / c_dst, c = i - p * c_dst;
-        d[i] = c < c_src ? s[p * c_src + c] : 0.f;
+        d[i] = to_act<T>(c < c_src ? s[p * c_src + c] : 0.f);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0 && y_dst) y_dst[b] = y_src[img];
 }
 
 void launch_gather_images(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
-                          int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, float* dst,
+                          int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, int act, void* dst,
                           int32_t* y_dst) {
     int total = pixels * c_dst;
     int bx = (total + 255) / 256;
     if (bx > 16) bx = 16;
-    hipLaunchKernelGGL(gather_images_kernel, dim3(bx, batch), dim3(256), 0, s, src, y_src, sel, k, start, first, batch,
-                       pixels, c_src, c_dst, dst, y_dst);
+    ACT_DISPATCH(act, hipLaunchKernelGGL(gather_images_kernel<T>, dim3(bx, batch), dim3(256), 0, s, src, y_src, sel, k, start, first,
+                                         batch, pixels, c_src, c_dst, (T*)dst, y_dst));
 }
 
 void launch_gather_rows(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
                         int64_t start, int batch, int64_t row, float* dst, int32_t* y_dst) {
-    launch_gather_images(s, src, y_src, sel, k, start, 0, batch, 1, (int)row, (int)row, dst, y_dst);
+    launch_gather_images(s, src, y_src, sel, k, start, 0, batch, 1, (int)row, (int)row, ACT_F32, dst, y_dst);
 }
 
 // SGD with momentum and coupled weight decay: g += wd*x; buf = mu*buf + g; x -= lr*buf.

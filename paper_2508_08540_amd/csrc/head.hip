@@ -1,6 +1,6 @@
 // Classifier head: (average pooling) + linear layer + per-sample softmax cross-entropy, one
 // wavefront per sample with shuffle reductions; and the head's weight gradient.
-#include "kernels.h"
+#include "act.h"
 
 #define HEAD_MAX_C 64
 #define HEAD_MAX_F_PER_LANE 16
@@ -12,8 +12,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // PER_LANE = ceil(F / 64) is a template parameter so that the feature slice stays in registers.
-template <int PER_LANE>
-__global__ __launch_bounds__(64) void head_forward_kernel(const float* __restrict__ act, int positions, int F,
+__device__ __forceinline__ float act_value(float v) { return v; }
+__device__ __forceinline__ float act_value(bf16_t v) { return bf16_to_f32(v); }
+
+template <int PER_LANE, typename T>
+__global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ act, int positions, int F,
                                                           const float* __restrict__ W, const float* __restrict__ bias,
                                                           int C, const int32_t* __restrict__ y, float* __restrict__ loss,
                                                           float* __restrict__ feat, float* __restrict__ dlogits,
@@ -22,7 +25,7 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restric
     constexpr int per_lane = PER_LANE;
     float f[PER_LANE];
     const float inv_pos = 1.f / (float)positions;
-    const float* a = act + (int64_t)b * positions * F;
+    const T* a = act + (int64_t)b * positions * F;
 #pragma unroll
     for (int i = 0; i < per_lane; ++i) {
         int c = lane + 64 * i;
@@ -32,12 +35,12 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restric
             float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
             int p = 0;
             for (; p + 3 < positions; p += 4) {
-                s0 += a[(int64_t)p * F + c];
-                s1 += a[(int64_t)(p + 1) * F + c];
-                s2 += a[(int64_t)(p + 2) * F + c];
-                s3 += a[(int64_t)(p + 3) * F + c];
+                s0 += act_value(a[(int64_t)p * F + c]);
+                s1 += act_value(a[(int64_t)(p + 1) * F + c]);
+                s2 += act_value(a[(int64_t)(p + 2) * F + c]);
+                s3 += act_value(a[(int64_t)(p + 3) * F + c]);
             }
-            for (; p < positions; ++p) s0 += a[(int64_t)p * F + c];
+            for (; p < positions; ++p) s0 += act_value(a[(int64_t)p * F + c]);
             acc = (s0 + s1) + (s2 + s3);
         }
         f[i] = acc * inv_pos;
@@ -83,12 +86,12 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const float* __restric
     }
 }
 
-void launch_head_forward(hipStream_t s, const float* act, int B, int positions, int F, const float* W, const float* bias,
+void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
                          float grad_scale, bool relu_mask) {
-#define HEAD_LAUNCH(PL)                                                                                                    \
-    hipLaunchKernelGGL(head_forward_kernel<PL>, dim3(B), dim3(64), 0, s, act, positions, F, W, bias, C, y, loss, feat, dlogits, \
-                       dfeat, grad_scale, relu_mask ? 1 : 0)
+#define HEAD_LAUNCH(PL)                                                                                                          \
+    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PL, T>), dim3(B), dim3(64), 0, s, (const T*)act, positions, F, W, \
+                                              bias, C, y, loss, feat, dlogits, dfeat, grad_scale, relu_mask ? 1 : 0))
     const int per_lane = (F + 63) / 64;
     if (per_lane <= 1) HEAD_LAUNCH(1);
     else if (per_lane <= 2) HEAD_LAUNCH(2);

@@ -7,6 +7,10 @@
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Storage type of activations in the launchers below (pointers to activations are void*).
+enum { ACT_F32 = 0, ACT_BF16 = 1 };
+static inline size_t act_bytes(int act) { return act == ACT_BF16 ? 2 : 4; }
+
 // Per-channel sums that cross workgroups are accumulated as 64-bit fixed-point integers with atomic adds:
 // integer addition is associative, so the result does not depend on the order in which workgroups arrive
 // (bit-reproducible), and no partial-sum rows or finalisation kernels are needed.  A float partial p
@@ -36,10 +40,10 @@ struct KernelTiming {
 // each source row is `row_src/group_src`... see gather_rows for the image variant.
 void launch_gather_rows(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
                         int64_t start, int batch, int64_t row, float* dst, int32_t* y_dst);
-// Images [n][pixels][c_src] -> [batch][pixels][c_dst] with zero-filled extra channels; sel == nullptr copies
+// Images float [n][pixels][c_src] -> storage type `act` [batch][pixels][c_dst] with zero-filled extra channels; sel == nullptr copies
 // images first .. first+batch-1, otherwise image b is sel[(start + b) % k].
 void launch_gather_images(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
-                          int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, float* dst,
+                          int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, int act, void* dst,
                           int32_t* y_dst);
 void launch_sgd(hipStream_t s, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
                 float wd);
@@ -56,20 +60,17 @@ void launch_gemm(hipStream_t s, const float* A, int lda, bool a_kmajor, const fl
                  int N, int K, int splits, float* part, float* out, const float* bias, bool relu, const float* mask);
 
 // ---- head.hip ---------------------------------------------------------------------------------------
-// One wave per sample: feature = mean over `positions` of act[b][p][F]; logits = W feature + bias;
+// One wave per sample: feature = mean over `positions` of act[b][p][F] (storage type act_type); logits = W feature + bias;
 // loss = softmax cross-entropy.  Training outputs (all optional, nullptr to skip): feat [B][F],
 // dlogits [B][C] scaled by grad_scale, dact [B][F] = (W^T dlogits) / positions, masked by feature > 0
 // when relu_mask is set.
-void launch_head_forward(hipStream_t s, const float* act, int B, int positions, int F, const float* W, const float* bias,
+void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
                          float grad_scale, bool relu_mask);
 // dW[c][f] = sum_b dlogits[b][c] feat[b][f]; db[c] = sum_b dlogits[b][c]
 void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db);
 
 // ---- norm.hip ---------------------------------------------------------------------------------------
-// mean/invstd from running statistics (inference mode)
-void launch_bn_eval_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean,
-                          float* invstd);
 // Where the normalisation statistics of bn_apply come from.  Training: `sums` holds the fixed-point
 // (sum, sum of squares) of y over `count` values; every workgroup derives mean and invstd from them, and
 // workgroup 0 also stores them into mean/invstd and moves the running statistics.  Inference: sums == nullptr
@@ -80,20 +81,18 @@ struct BnStats {
     float *mean, *invstd, *running_mean, *running_var;
 };
 // a = relu(gamma * (y - mean) * invstd + beta [+ shortcut(res)]); res has c_res channels at res_stride x resolution
-void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
-                     const float* beta, const float* res, int c_res, int res_stride, int h_out, float* out);
+void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
+                     const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out);
 // Backward of relu(bn(y) [+ shortcut]) for a layer whose upstream gradient does not come from an input-gradient
-// kernel: g = dout * (out > 0); adds (sum g, sum g*xhat) into the fixed-point accumulators `sums` [2][C].
-void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+// kernel: g = dout * (out > 0); dout is a tensor of the storage type, or, with dout_positions_shared > 0, an fp32
+// [samples][C] matrix whose rows are shared by that many positions; adds (sum g, sum g*xhat) into the fixed-point accumulators `sums` [2][C].
+void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                           int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums);
 // dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M) with g = dout * (out > 0) and (dbeta, dgamma) read from `sums`;
 // workgroup 0 stores dgamma and dbeta; g_out (optional) receives g.
-void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const fixsum_t* sums, float* dgamma, float* dbeta, float* dy, float* g_out);
-// dx[n][h][w][c] += shortcut_backward(g): identity or stride-2 zero-padded-channel shortcut
-void launch_shortcut_grad_add(hipStream_t s, float* dx, int B, int h_in, int c_in, const float* g, int c_out, int stride);
-
+                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out);
 // ---- conv.hip ---------------------------------------------------------------------------------------
 struct ConvShape {
     int B, h_in, c_in, c_out, stride;  // square maps; 3x3, padding 1; c_in, c_out in {16, 32, 64}
@@ -103,7 +102,7 @@ struct ConvShape {
 #define PACK_MAX_ENTRIES 80
 struct PackEntry {
     int64_t w_off;     // offset of w[c_out][3][3][c_in_real] in the parameter vector
-    int64_t pack_off;  // float4 offset of this entry in the packed buffer
+    int64_t pack_off;  // offset of this entry in the packed buffer, in quads (4 values of the storage type)
     int c_in, c_out, c_in_real, dgrad;
 };
 struct PackTable {
@@ -111,34 +110,35 @@ struct PackTable {
     int64_t total_vec4;
     PackEntry e[PACK_MAX_ENTRIES];
 };
-void launch_pack_weights(hipStream_t s, const float* params, float* packed, const PackTable& tab);
+void launch_pack_weights(hipStream_t s, int act, const float* params, void* packed, const PackTable& tab);
 // Fused epilogue of the convolution kernels (see conv_kernel).  `sums` points at [replica][2][channels] accumulators:
 // forward (sum, sum of squares) of the output; input gradient (sum g, sum g*xhat) of the layer below.
 struct ConvEpi {
     fixsum_t* sums;
     double scale;
     // input gradient: shortcut gradient to add (sc_g may be nullptr), then batch-norm backward sums of the layer below
-    const float* sc_g;
+    const void* sc_g;  // activations (storage type of the launch)
     int sc_c, sc_lo, sc_stride;
-    const float *a_prev, *y_prev, *mean_prev, *invstd_prev;
+    const void *a_prev, *y_prev;  // activations
+    const float *mean_prev, *invstd_prev;
     // inference forward (gamma != nullptr): out = relu(bn(y) + shortcut) with mean_prev = running mean, invstd_prev =
     // running variance, sc_g = shortcut source (c channels sc_c, first output channel sc_lo, spatial stride sc_stride)
     const float *gamma, *beta;
 };
 int conv_fwd_tiles(const ConvShape& cs);
-// In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
+// x, y, dy, dx are activations of storage type `act`.  In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).
 // y = conv(x, w); with `stats` the kernel also accumulates (sum, sum of squares) of y per channel, or, when
 // stats->gamma is set, applies inference batch norm + shortcut + ReLU before storing.
-void launch_conv_fwd(hipStream_t s, const ConvShape& cs, const float* x, const float* w, float* y, const ConvEpi* stats,
+void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
                      const KernelTiming* kt = nullptr);
 // dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also the batch-norm backward sums of the layer
 // that produced x.
-void launch_conv_dgrad(hipStream_t s, const ConvShape& cs, const float* dy, const float* w, float* dx, const ConvEpi* bn_below,
+void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt = nullptr);
 // Adds dy (x) shifted x over all pixels into gacc: [replica][c_out/16][c_in/16][2304] fixed-point accumulators
 // (conv_wgrad_accumulators entries, zero before the call) ...
 int64_t conv_wgrad_accumulators(const ConvShape& cs);
-void launch_conv_wgrad(hipStream_t s, const ConvShape& cs, const float* x, const float* dy, fixsum_t* gacc,
+void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt = nullptr);
 // ... and, for all layers at once, grad[w_off ..] = sum of the replicas as float; clears the accumulators again.
 #define WGRAD_MAX_ENTRIES 40

@@ -35,7 +35,9 @@ ConvShape shape_of(const ConvBn& l, int B) {
     return cs;
 }
 
-int64_t out_floats(const ConvBn& l, int B) { return (int64_t)B * l.h_out * l.h_out * l.c_out; }
+int64_t out_elems(const ConvBn& l, int B) { return (int64_t)B * l.h_out * l.h_out * l.c_out; }
+
+typedef uint8_t act_t;  // activations are addressed as bytes; the model's storage type gives the element size
 
 // ---- MLP ----------------------------------------------------------------------------------------
 
@@ -68,13 +70,16 @@ void mlp_hidden(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* p
 // ---- residual network ---------------------------------------------------------------------------------
 
 struct ResScratch {
-    float* wpack;                      // packed weights: forward copies of all layers, then input-gradient copies
-    std::vector<int64_t> fwd_off, dgrad_off;  // float offsets into wpack per layer
+    int act;                           // storage type of activations and packed weights
+    act_t* wpack;                      // packed weights: forward copies of all layers, then input-gradient copies
+    std::vector<int64_t> fwd_off, dgrad_off;  // byte offsets into wpack per layer
     PackTable tab;
-    float* xpad;
+    act_t* xpad;
     int32_t* yb;
-    std::vector<float*> y, a, mean, invstd, dy;  // per layer
-    float *stats, *d1, *d2, *g, *grad;
+    std::vector<act_t*> y, a, dy;      // per layer
+    std::vector<float*> mean, invstd;  // per layer
+    act_t *stats, *d1, *d2, *g;
+    float* grad;
     fixsum_t* wacc;  // weight-gradient accumulators of all layers (kept zero between uses)
     int64_t wacc_count;
     WgradTable wtab;
@@ -86,6 +91,8 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     ResScratch s{};
     const int L = (int)m->layers.size();
     const int hw = m->desc.image_hw;
+    s.act = m->desc.act_dtype == BLS_ACT_BF16 ? ACT_BF16 : ACT_F32;
+    const size_t esz = act_bytes(s.act);
     s.fwd_off.assign(L, 0);
     s.dgrad_off.assign(L, 0);
     s.tab.n = 0;
@@ -100,12 +107,12 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
             e.c_out = cb.c_out;
             e.c_in_real = cb.c_in;
             e.dgrad = pass;
-            (pass == 0 ? s.fwd_off : s.dgrad_off)[l] = vec4 * 4;
+            (pass == 0 ? s.fwd_off : s.dgrad_off)[l] = vec4 * 4 * (int64_t)esz;
             vec4 += (int64_t)e.c_in * e.c_out * 9 / 4;
         }
     s.tab.total_vec4 = vec4;
-    s.wpack = c.take<float>(vec4 * 4);
-    s.xpad = c.take<float>((size_t)B * hw * hw * PAD_C);
+    s.wpack = c.take<act_t>(vec4 * 4 * esz);
+    s.xpad = c.take<act_t>((size_t)B * hw * hw * PAD_C * esz);
     s.yb = c.take<int32_t>(B);
     s.loss = c.take<float>(B);
     s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L); s.dy.assign(L, nullptr);
@@ -115,7 +122,7 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
-        max_act = max64(max_act, out_floats(cb, B));
+        max_act = max64(max_act, out_elems(cb, B));
         {
             WgradEntry& we = s.wtab.e[s.wtab.n++];
             we.w_off = cb.w_off; we.acc_off = max_wpart; we.first = s.wtab.total;
@@ -128,15 +135,15 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     }
     if (train) {
         for (int l = 0; l < L; ++l) {
-            s.y[l] = c.take<float>(out_floats(m->layers[l], B));
-            s.a[l] = c.take<float>(out_floats(m->layers[l], B));
-            s.dy[l] = c.take<float>(out_floats(m->layers[l], B));  // kept per layer: the side stream reads it later
+            s.y[l] = c.take<act_t>(out_elems(m->layers[l], B) * esz);
+            s.a[l] = c.take<act_t>(out_elems(m->layers[l], B) * esz);
+            s.dy[l] = c.take<act_t>(out_elems(m->layers[l], B) * esz);  // kept per layer: the side stream reads it later
         }
         s.stats = nullptr;
         s.sums = c.take<fixsum_t>((size_t)L * 2 * FIX_SET);
-        s.d1 = c.take<float>(max_act);
-        s.d2 = c.take<float>(max_act);
-        s.g = c.take<float>(max_act);
+        s.d1 = c.take<act_t>(max_act * esz);
+        s.d2 = c.take<act_t>(max_act * esz);
+        s.g = c.take<act_t>(max_act * esz);
         s.wacc = c.take<fixsum_t>(max_wpart);
         s.wacc_count = max_wpart;
         s.grad = c.take<float>(m->num_params);
@@ -145,8 +152,8 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
         s.dfeat = c.take<float>((size_t)B * m->final_c);
     } else {
         // inference keeps no activations: four rotating buffers are enough
-        float* pool[4];
-        for (float*& p : pool) p = c.take<float>(max_act);
+        act_t* pool[4];
+        for (act_t*& p : pool) p = c.take<act_t>(max_act * esz);
         for (int l = 0; l < L; ++l) {
             // layer l writes y into pool[(2l) % 4 .. ]: see resnet_forward for the rotation
             s.y[l] = nullptr;
@@ -161,35 +168,35 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
 // Forward pass over a batch already gathered into s.xpad.  Train mode keeps every layer's
 // convolution output and activation for the backward pass and updates the running statistics.
 // Returns the final activation.
-const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, ResScratch& s,
+const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, ResScratch& s,
                             bool train) {
     const int L = (int)m->layers.size();
-    float* rot[4] = {s.d1, s.d2, s.g, s.stats};  // inference-only rotation
+    act_t* rot[4] = {s.d1, s.d2, s.g, s.stats};  // inference-only rotation
     int next = 0;
-    auto take = [&](const float* keep0, const float* keep1) {
+    auto take = [&](const act_t* keep0, const act_t* keep1) {
         for (;;) {
-            float* p = rot[next];
+            act_t* p = rot[next];
             next = (next + 1) & 3;
             if (p != keep0 && p != keep1) return p;
         }
     };
-    PROF(ctx, PROF_UPDATE, launch_pack_weights(st, params, s.wpack, s.tab));
+    PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab));
     if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), (int64_t)m->layers.size() * 2 * FIX_SET * 2));
-    const float* block_in = nullptr;
-    const float* cur = s.xpad;
+    const act_t* block_in = nullptr;
+    const act_t* cur = s.xpad;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         const bool is_conv2 = l > 0 && (l % 2 == 0);
         if (l > 0 && !is_conv2) block_in = cur;
-        float* y = train ? s.y[l] : take(cur, block_in);
+        act_t* y = train ? s.y[l] : take(cur, block_in);
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         if (train) {
             // the convolution accumulates the sums of its output; bn_apply turns them into statistics
             ConvEpi e{};
             e.sums = s.sums + (size_t)l * 2 * FIX_SET;
             e.scale = FIX_FWD_SCALE;
-            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
         } else {
             // inference: one kernel per layer, batch norm (running statistics), shortcut and ReLU in the epilogue
             ConvEpi e{};
@@ -199,7 +206,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
                 const ConvBn& c1 = m->layers[l - 1];
                 e.sc_g = block_in; e.sc_c = c1.c_in; e.sc_lo = (cb.c_out - c1.c_in) / 2; e.sc_stride = c1.stride;
             }
-            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
             cur = y;
             continue;
         }
@@ -208,8 +215,8 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
         bs.count = (double)pixels;
         bs.mean = s.mean[l]; bs.invstd = s.invstd[l];
         bs.running_mean = buffers + cb.rmean_off; bs.running_var = buffers + cb.rvar_off;
-        float* a = train ? s.a[l] : take(y, block_in);
-        const float* res = nullptr;
+        act_t* a = train ? s.a[l] : take(y, block_in);
+        const act_t* res = nullptr;
         int c_res = cb.c_out, res_stride = 1;
         if (is_conv2) {
             const ConvBn& c1 = m->layers[l - 1];
@@ -217,7 +224,7 @@ const float* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             c_res = c1.c_in;
             res_stride = c1.stride;
         }
-        PROF(ctx, PROF_NORM, launch_bn_apply(st, y, pixels, cb.c_out, bs, params + cb.gamma_off, params + cb.beta_off, res,
+        PROF(ctx, PROF_NORM, launch_bn_apply(st, s.act, y, pixels, cb.c_out, bs, params + cb.gamma_off, params + cb.beta_off, res,
                         c_res, res_stride, cb.h_out, a));
         cur = a;
     }
@@ -235,25 +242,25 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         ctx->fork_events.push_back(e);
     }
     const ConvBn& last = m->layers[L - 1];
-    const float* dout = s.dfeat;
+    const void* dout = s.dfeat;
     int shared = last.h_out * last.h_out;
     for (int l = L - 1; l >= 0; --l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         const int64_t pixels = (int64_t)B * cb.h_out * cb.h_out;
         const bool is_conv2 = l > 0 && (l % 2 == 0);
-        const float* x_in = l == 0 ? s.xpad : s.a[l - 1];
+        const act_t* x_in = l == 0 ? s.xpad : s.a[l - 1];
         if (l == L - 1) {
             // top layer: its upstream gradient comes from the head; lower layers get these sums from the
             // input-gradient kernel of the layer above
-            PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l],
+            PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l],
                                                       s.sums + ((size_t)l * 2 + 1) * FIX_SET));
         }
-        PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
+        PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
                             s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
         BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
         BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
-        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, cs, x_in, s.dy[l], s.wacc + s.wtab.e[l].acc_off, kt));
+        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, s.act, cs, x_in, s.dy[l], s.wacc + s.wtab.e[l].acc_off, kt));
         if (l == 0) break;
         {
             // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
@@ -266,7 +273,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                 const ConvBn& c2 = m->layers[l + 1];
                 e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
             }
-            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e, kt));
+            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, s.act, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e, kt));
         }
         dout = s.d2;
         shared = 0;
@@ -301,7 +308,7 @@ int net_score(bls_ctx* ctx, const bls_model* m, const float* params, const float
         for (int64_t first = 0; first < N; first += chunk) {
             int B = (int)(N - first < chunk ? N - first : chunk);
             mlp_hidden(ctx, st, m, params, x + first * m->d_in, B, s);
-            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.h, B, 1, m->desc.hidden, params + m->fc2_w, params + m->fc2_b, m->desc.classes,
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, ACT_F32, s.h, B, 1, m->desc.hidden, params + m->fc2_w, params + m->fc2_b, m->desc.classes,
                                 y + first, losses_out + first, nullptr, nullptr, nullptr, 0.f, false));
         }
     } else {
@@ -309,9 +316,9 @@ int net_score(bls_ctx* ctx, const bls_model* m, const float* params, const float
         const int hw = m->desc.image_hw;
         for (int64_t first = 0; first < N; first += chunk) {
             int B = (int)(N - first < chunk ? N - first : chunk);
-            PROF(ctx, PROF_GATHER, launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb));
-            const float* fin = resnet_forward(ctx, st, m, params, const_cast<float*>(buffers), B, s, false);
-            PROF(ctx, PROF_HEAD, launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
+            PROF(ctx, PROF_GATHER, launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
+            const act_t* fin = resnet_forward(ctx, st, m, params, const_cast<float*>(buffers), B, s, false);
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
                                 m->desc.classes, s.yb, losses_out + first, nullptr, nullptr, nullptr, 0.f, false));
         }
     }
@@ -336,7 +343,7 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
             PROF(ctx, PROF_GATHER, launch_gather_rows(st, x_pool, y_pool, sel, k, j * B, B, m->d_in, s.xb, s.yb));
             mlp_hidden(ctx, st, m, params, s.xb, B, s);
-            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.h, B, 1, hid, params + m->fc2_w, params + m->fc2_b, C, s.yb, loss, nullptr, s.dlogits,
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, ACT_F32, s.h, B, 1, hid, params + m->fc2_w, params + m->fc2_b, C, s.yb, loss, nullptr, s.dlogits,
                                 s.dpre, inv_b, true));
             PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.h, B, C, hid, s.grad + m->fc2_w, s.grad + m->fc2_b));
             PROF(ctx, PROF_GEMM, launch_gemm(st, s.dpre, hid, true, s.xb, m->d_in, true, hid, m->d_in, B, 1, s.part, s.grad + m->fc1_w, nullptr,
@@ -351,9 +358,9 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.wacc), s.wacc_count * 2));
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
-            PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.xpad, s.yb));
-            const float* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true);
-            PROF(ctx, PROF_HEAD, launch_head_forward(st, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
+            PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
+            const act_t* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true);
+            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
                                 loss, s.feat, s.dlogits, s.dfeat, inv_b, false));
             PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b));
             rc = resnet_backward(ctx, st, m, params, B, s);

@@ -1,32 +1,20 @@
 // Batch normalisation around the convolutions: statistics finalisation, normalise + ReLU (+ shortcut),
 // and the backward pass (two reductions and one elementwise pass).  Activations are [pixels][C] with
-// C a multiple of 16, so every thread works on 4 consecutive channels with 16-byte accesses.
-#include "kernels.h"
+// C a multiple of 16, so every thread works on 4 consecutive channels (16 bytes in fp32, 8 in bf16).
+// All kernels are templates on the storage type of the activations; arithmetic is fp32.
+#include "act.h"
 
 #define BN_EPS 1e-5
 #define BN_MOMENTUM 0.1
 
-__global__ __launch_bounds__(64) void bn_eval_stats_kernel(const float* __restrict__ running_mean,
-                                                           const float* __restrict__ running_var, int C,
-                                                           float* __restrict__ mean, float* __restrict__ invstd) {
-    int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
-    mean[c] = running_mean[c];
-    invstd[c] = (float)(1.0 / sqrt((double)running_var[c] + BN_EPS));
-}
-
-void launch_bn_eval_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean,
-                          float* invstd) {
-    hipLaunchKernelGGL(bn_eval_stats_kernel, dim3((C + 63) / 64), dim3(64), 0, s, running_mean, running_var, C, mean, invstd);
-}
-
 // out = relu(gamma*(y-mean)*invstd + beta + shortcut(res)).  In training the statistics come from the
 // fixed-point sums: threads 0..C-1 of every workgroup turn them into mean and invstd (double), workgroup 0
 // also stores them and moves the running statistics (momentum 0.1, unbiased variance).
-__global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__ y, int64_t pixels, int C, BnStats st,
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, int64_t pixels, int C, BnStats st,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                       const float* __restrict__ res, int c_res, int res_stride, int h_out,
-                                                       float* __restrict__ out) {
+                                                       const T* __restrict__ res, int c_res, int res_stride, int h_out,
+                                                       T* __restrict__ out) {
     __shared__ float s_mean[64], s_invstd[64];
     if ((int)threadIdx.x < C) {
         const int c = threadIdx.x;
@@ -58,7 +46,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         int64_t p = i / cq;
         int c = (int)(i - p * cq) << 2;
-        f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
+        f32x4 v = Act<T>::load4(y + p * C + c);
         f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
         f32x4 be = *reinterpret_cast<const f32x4*>(beta + c);
         f32x4 r = {0.f, 0.f, 0.f, 0.f};
@@ -72,7 +60,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
                 int h_in = h_out * res_stride;
                 rp = (n * h_in + (int64_t)h * res_stride) * h_in + (int64_t)w * res_stride;
             }
-            r = *reinterpret_cast<const f32x4*>(res + rp * c_res + (c - lo));
+            r = Act<T>::load4(res + rp * c_res + (c - lo));
         }
         f32x4 o;
 #pragma unroll
@@ -80,17 +68,17 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const float* __restrict__
             float t = __fmaf_rn((v[j] - s_mean[c + j]) * s_invstd[c + j], ga[j], be[j]) + r[j];
             o[j] = fmaxf(t, 0.f);
         }
-        *reinterpret_cast<f32x4*>(out + p * C + c) = o;
+        Act<T>::store4(out + p * C + c, o);
     }
 }
 
-void launch_bn_apply(hipStream_t s, const float* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
-                     const float* beta, const float* res, int c_res, int res_stride, int h_out, float* out) {
+void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
+                     const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(bn_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, y, pixels, C, st, gamma, beta, res, c_res,
-                       res_stride, h_out, out);
+    ACT_DISPATCH(act, hipLaunchKernelGGL(bn_apply_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st,
+                                         gamma, beta, (const T*)res, c_res, res_stride, h_out, (T*)out));
 }
 
 // ---- backward -------------------------------------------------------------------------------------
@@ -102,16 +90,18 @@ int bn_bwd_partials(int64_t pixels) {
     return (int)n;
 }
 
-// Upstream gradient of pixel p, channels c..c+3: either a full tensor or one vector per sample
-// shared by all `shared` positions of that sample (gradient of a global average pool).
-__device__ __forceinline__ f32x4 load_dout(const float* __restrict__ dout, int shared, int64_t p, int C, int c) {
-    int64_t row = shared ? p / shared : p;
-    return *reinterpret_cast<const f32x4*>(dout + row * C + c);
+// Upstream gradient of pixel p, channels c..c+3: either a full tensor of the storage type, or one fp32
+// vector per sample shared by all `shared` positions of that sample (gradient of a global average pool).
+template <typename T>
+__device__ __forceinline__ f32x4 load_dout(const void* __restrict__ dout, int shared, int64_t p, int C, int c) {
+    if (shared) return *reinterpret_cast<const f32x4*>(static_cast<const float*>(dout) + (p / shared) * C + c);
+    return Act<T>::load4(static_cast<const T*>(dout) + p * C + c);
 }
 
 // adds (sum g, sum g*xhat), g = dout * (out > 0), into the fixed-point accumulators sums[2][C]
-__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const float* __restrict__ dout, int shared,
-                                                            const float* __restrict__ out, const float* __restrict__ y,
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restrict__ dout, int shared,
+                                                            const T* __restrict__ out, const T* __restrict__ y,
                                                             int64_t pixels, int C, const float* __restrict__ mean,
                                                             const float* __restrict__ invstd, fixsum_t* __restrict__ sums) {
     __shared__ float red[2][256][4];
@@ -125,9 +115,9 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const float* __restr
     f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
     f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sgx = {0.f, 0.f, 0.f, 0.f};
     for (int64_t p = p0 + pl; p < p1; p += lanes_p) {
-        f32x4 d = load_dout(dout, shared, p, C, c);
-        f32x4 o = *reinterpret_cast<const f32x4*>(out + p * C + c);
-        f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
+        f32x4 d = load_dout<T>(dout, shared, p, C, c);
+        f32x4 o = Act<T>::load4(out + p * C + c);
+        f32x4 v = Act<T>::load4(y + p * C + c);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float g = o[j] > 0.f ? d[j] : 0.f;
@@ -150,20 +140,21 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const float* __restr
     }
 }
 
-void launch_bn_bwd_reduce(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                           int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums) {
     int n = bn_bwd_partials(pixels);
-    hipLaunchKernelGGL(bn_bwd_reduce_kernel, dim3(n), dim3(256), 0, s, dout, dout_positions_shared, out, y, pixels, C,
-                       mean, invstd, sums);
+    ACT_DISPATCH(act, hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, dim3(n), dim3(256), 0, s, dout, dout_positions_shared,
+                                         (const T*)out, (const T*)y, pixels, C, mean, invstd, sums));
 }
 
-__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restrict__ dout, int shared,
-                                                           const float* __restrict__ out, const float* __restrict__ y,
+template <typename T>
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restrict__ dout, int shared,
+                                                           const T* __restrict__ out, const T* __restrict__ y,
                                                            int64_t pixels, int C, const float* __restrict__ mean,
                                                            const float* __restrict__ invstd, const float* __restrict__ gamma,
                                                            const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
-                                                           float* __restrict__ dbeta, float inv_count, float* __restrict__ dy,
-                                                           float* __restrict__ g_out) {
+                                                           float* __restrict__ dbeta, float inv_count, T* __restrict__ dy,
+                                                           T* __restrict__ g_out) {
     __shared__ float s_dg[64], s_db[64];
     if ((int)threadIdx.x < C) {
         const int c = threadIdx.x;
@@ -181,9 +172,9 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         int64_t p = i / cq;
         int c = (int)(i - p * cq) << 2;
-        f32x4 d = load_dout(dout, shared, p, C, c);
-        f32x4 o = *reinterpret_cast<const f32x4*>(out + p * C + c);
-        f32x4 v = *reinterpret_cast<const f32x4*>(y + p * C + c);
+        f32x4 d = load_dout<T>(dout, shared, p, C, c);
+        f32x4 o = Act<T>::load4(out + p * C + c);
+        f32x4 v = Act<T>::load4(y + p * C + c);
         f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
         f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
         f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
@@ -195,53 +186,19 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const float* __restri
             gq[j] = g;
             r[j] = ga[j] * is[j] * (g - s_db[c + j] * inv_count - xhat * (s_dg[c + j] * inv_count));
         }
-        *reinterpret_cast<f32x4*>(dy + p * C + c) = r;
-        if (g_out) *reinterpret_cast<f32x4*>(g_out + p * C + c) = gq;
+        Act<T>::store4(dy + p * C + c, r);
+        if (g_out) Act<T>::store4(g_out + p * C + c, gq);
     }
 }
 
-void launch_bn_bwd_apply(hipStream_t s, const float* dout, int dout_positions_shared, const float* out, const float* y,
+void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const fixsum_t* sums, float* dgamma, float* dbeta, float* dy, float* g_out) {
+                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dout, dout_positions_shared, out, y,
-                       pixels, C, mean, invstd, gamma, sums, dgamma, dbeta, 1.f / (float)pixels, dy, g_out);
+    ACT_DISPATCH(act, hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, dout,
+                                         dout_positions_shared, (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums,
+                                         dgamma, dbeta, 1.f / (float)pixels, (T*)dy, (T*)g_out));
 }
 
-// dx += shortcut_backward(g): identity (stride 1, equal channels) or stride-2 zero-padded-channel shortcut
-__global__ __launch_bounds__(256) void shortcut_grad_add_kernel(float* __restrict__ dx, int64_t pixels_in, int h_in, int c_in,
-                                                                const float* __restrict__ g, int c_out, int stride) {
-    const int cq = c_in >> 2;
-    const int lo = (c_out - c_in) >> 1;
-    const int h_out = h_in / stride;
-    int64_t total = pixels_in * cq;
-    int64_t gstride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gstride) {
-        int64_t p = i / cq;
-        int c = (int)(i - p * cq) << 2;
-        int64_t gp = p;
-        if (stride != 1) {
-            int hw = h_in * h_in;
-            int64_t n = p / hw;
-            int q = (int)(p - n * hw);
-            int h = q / h_in, w = q - h * h_in;
-            if ((h % stride) | (w % stride)) continue;
-            gp = (n * h_out + h / stride) * h_out + w / stride;
-        }
-        f32x4 a = *reinterpret_cast<f32x4*>(dx + p * c_in + c);
-        f32x4 b = *reinterpret_cast<const f32x4*>(g + gp * c_out + lo + c);
-        a += b;
-        *reinterpret_cast<f32x4*>(dx + p * c_in + c) = a;
-    }
-}
-
-void launch_shortcut_grad_add(hipStream_t s, float* dx, int B, int h_in, int c_in, const float* g, int c_out, int stride) {
-    int64_t pixels_in = (int64_t)B * h_in * h_in;
-    int64_t total = pixels_in * (c_in / 4);
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(shortcut_grad_add_kernel, dim3((unsigned)blocks), dim3(256), 0, s, dx, pixels_in, h_in, c_in, g,
-                       c_out, stride);
-}

@@ -1,0 +1,186 @@
+"""GPU parity of the mixed-precision residual network (bf16 activations, fp32 master weights).
+
+The reference is the float64 oracle evaluated on the bf16 grid (oracle.ResNetCifar(storage=round_bf16)):
+the same roundings at the same places, everything between them exact.  Two kinds of checks:
+
+  * Where no rounding decision is a near-tie, the kernels must agree with it as closely as the fp32
+    path agrees with the plain oracle.
+  * A value that lies within fp32 rounding of the midpoint of two bf16 numbers may legitimately round
+    either way, and one such flip changes later roundings in turn.  On deeper nets and larger batches
+    this happens somewhere, and the gradient of a randomly initialised network reacts strongly: the
+    oracle itself moves by 10-30 % per tensor when its batch-norm parameters are perturbed at the level
+    of fp32 rounding.  There the kernels are held to that envelope, measured from the oracle in the
+    test, and to tight bounds on what is insensitive (losses, running statistics, classifier gradient).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_helpers import Harness, assert_losses_close, assert_tensors_close, rel_err
+
+pytestmark = pytest.mark.gpu
+CFG = synth.workload("resnet20_bf16")
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    yield torch, bls, ctx
+    ctx.close()
+
+
+def _harness(env, widths=(16, 32, 64), blocks=3, hw=32, classes=10):
+    torch, bls, ctx = env
+    return Harness(torch, bls, ctx, bls.Model.resnet_cifar(widths, blocks, classes, hw, act_dtype="bf16"),
+                   oracle.ResNetCifar(widths, blocks, storage=oracle.round_bf16))
+
+
+def _zeros(p):
+    return {k: np.zeros_like(v) for k, v in p.items()}
+
+
+def _case(widths, blocks, hw, batch, classes=10):
+    p, b = synth.resnet_init(CFG["id"], widths, blocks, classes, perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], batch + 5, classes, hw=hw)
+    sel = (np.arange(batch) * 3) % (batch + 5)
+    return p, b, x, y, sel
+
+
+def _flip_envelope(model, p, b, xb, yb, ref_grads, eps=1e-5, draws=4, seed=11):
+    """Per-tensor change of the oracle's gradients when its batch-norm scales and shifts move by eps relative
+    (largest of several draws): how far apart two correct evaluations can be once roundings flip."""
+    rs = np.random.RandomState(seed)
+    out = {k: 0.0 for k in ref_grads}
+    for _ in range(draws):
+        p2 = {k: (np.asarray(v, np.float64) * (1.0 + eps * rs.standard_normal(v.shape)) if ".bn" in k else v)
+              for k, v in p.items()}
+        _, g2, _ = oracle.loss_and_grads(model, p2, b, xb, yb)
+        for k in out:
+            out[k] = max(out[k], rel_err(g2[k], ref_grads[k]))
+    return out
+
+
+def _inside_envelope(h, p, b, xb, yb, grads, mom, floor=0.02):
+    env_err = _flip_envelope(h.oracle_model, p, b, xb, yb, grads)
+    return {k: (rel_err(mom[k], grads[k]), env_err[k]) for k in grads
+            if rel_err(mom[k], grads[k]) > 2.0 * max(env_err[k], floor)}
+
+
+SMALL = [((16, 32, 64), 1, 8, 4), ((16, 16, 32), 1, 8, 3), ((64, 64, 64), 1, 8, 2), ((16, 32, 32), 1, 8, 7),
+         ((16, 32, 64), 1, 16, 2), ((32, 32, 32), 1, 8, 1)]
+
+
+def test_small_nets_match_the_bf16_oracle_when_no_rounding_flips(env):
+    """Six small nets x four input seeds.  A run without a flipped rounding agrees with the oracle like the
+    fp32 path does (1e-4 on every gradient tensor, observed 1e-6); a run with one is 1e-4 .. 1e-1 off and
+    must stay inside the envelope.  Every net must have a flip-free seed and so must most runs overall."""
+    tight_total, runs = 0, 0
+    for widths, blocks, hw, batch in SMALL:
+        h = _harness(env, widths, blocks, hw)
+        tight_here = 0
+        for stream in range(4):
+            p, b = synth.resnet_init(CFG["id"], widths, blocks, 10, perturb_bn=0.2)
+            x, y = synth.image_pool(CFG["id"], batch + 5, 10, hw=hw, stream=stream)
+            sel = (np.arange(batch) * 3) % (batch + 5)
+            what = (widths, hw, batch, stream)
+            assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y), rtol=2e-3)
+            losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+            _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+            worst = max(rel_err(mom[k], grads[k]) for k in grads)
+            runs += 1
+            if worst <= 1e-4:
+                tight_here += 1
+                assert_losses_close(sl[0], losses)
+                assert_tensors_close(gb, new_b, 1e-5, "running statistics %r" % (what,))
+            else:
+                assert_losses_close(sl[0], losses, rtol=1e-2)
+                assert_tensors_close(gb, new_b, 3e-3, "running statistics %r" % (what,))
+                bad = _inside_envelope(h, p, b, x[sel], y[sel], grads, mom)
+                assert not bad, (what, bad)
+        assert tight_here >= 1, (widths, hw, batch, "no seed without a rounding flip")
+        tight_total += tight_here
+    assert 2 * tight_total >= runs, (tight_total, runs)
+
+
+@pytest.mark.parametrize("widths,blocks,hw,batch", [
+    ((16, 16, 32), 2, 16, 3),
+    ((32, 32, 64), 1, 32, 2),     # stride-2 input gradients, 32-channel stem
+    ((16, 64, 64), 1, 16, 5),
+    ((16, 32, 64), 3, 32, 16),    # ResNet20
+])
+def test_larger_nets_stay_inside_the_rounding_flip_envelope(env, widths, blocks, hw, batch):
+    h = _harness(env, widths, blocks, hw)
+    p, b, x, y, sel = _case(widths, blocks, hw, batch)
+    assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y), rtol=5e-3)
+    losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses, rtol=1e-2)
+    assert_tensors_close(gb, new_b, 3e-3, "running statistics")
+    floor = 0.02
+    bad = _inside_envelope(h, p, b, x[sel], y[sel], grads, mom, floor)
+    assert not bad, bad
+    # the classifier sees the perturbation only through the pooled features
+    assert rel_err(mom["fc.bias"], grads["fc.bias"]) < 2e-2
+    # and against the plain float64 model the kernels are no further off than the bf16 oracle is
+    plain = oracle.ResNetCifar(widths, blocks)
+    _, g64, _ = oracle.loss_and_grads(plain, p, b, x[sel], y[sel])
+    for k in grads:
+        assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + floor, k
+
+
+def test_steps_selection_and_determinism_at_the_workload_sizes(env):
+    """Pool 4096, k 1024, batch 128, 50 steps: scores against the oracle on a sample of the pool, the
+    selection bit for bit from the library's own scores, and the properties of the steps that hold at
+    any size."""
+    torch, bls, ctx = env
+    h = _harness(env)
+    N, k, B, tau = CFG["pool"], CFG["k"], CFG["batch"], CFG["tau"]
+    p, b = synth.resnet_init(CFG["id"], perturb_bn=0.1)
+    x, y = synth.image_pool(CFG["id"], N, CFG["classes"])
+    got = h.score(p, b, x, y)
+    sample = (np.arange(96) * 41 + 7) % N
+    assert_losses_close(got[sample], oracle.score_losses(h.oracle_model, p, b, x[sample], y[sample]), rtol=5e-3)
+    assert np.isfinite(got).all()
+    dl = torch.from_numpy(got.astype(np.float32)).cuda()
+    idx = torch.empty(k, dtype=torch.int32, device="cuda")
+    bls.topk_by_loss(ctx, dl, k, idx)
+    ctx.synchronize()
+    sel = idx.cpu().numpy()
+    np.testing.assert_array_equal(sel, oracle.topk_by_loss(got.astype(np.float32), k))
+    # lr = 0: weights stay, every pass over the selection (k / B = 8 steps) records the same losses for
+    # a batch as long as the running statistics do not enter (training mode uses batch statistics)
+    p2, b2, m2, sl = h.local_step(p, b, _zeros(p), x, y, sel, B, 2 * (k // B), lr=0.0, mu=0.0)
+    np.testing.assert_array_equal(sl[:k // B], sl[k // B:])
+    for name in p:
+        np.testing.assert_array_equal(p2[name], np.asarray(p[name], np.float64))
+    # batch 0 of the steps is scored in training mode: compare with the oracle's training pass
+    l0, _, _ = oracle.loss_and_grads(h.oracle_model, p, b, x[sel[:B]], y[sel[:B]])
+    assert_losses_close(sl[0], l0, rtol=1e-2)
+    # the real settings: finite, repeatable bit for bit, and the loss of the selected samples goes down
+    r1 = h.local_step(p, b, _zeros(p), x, y, sel, B, tau, CFG["lr"], CFG["momentum"], CFG["weight_decay"])
+    r2 = h.local_step(p, b, _zeros(p), x, y, sel, B, tau, CFG["lr"], CFG["momentum"], CFG["weight_decay"])
+    for a_, b_ in zip(r1[:3], r2[:3]):
+        for name in a_:
+            assert np.isfinite(a_[name]).all(), name
+            np.testing.assert_array_equal(a_[name], b_[name])
+    np.testing.assert_array_equal(r1[3], r2[3])
+    assert r1[3][-8:].mean() < r1[3][:8].mean()
+
+
+def test_bf16_and_fp32_paths_agree_to_bf16_accuracy(env):
+    torch, bls, ctx = env
+    p, b = synth.resnet_init(CFG["id"], perturb_bn=0.1)
+    x, y = synth.image_pool(CFG["id"], 64, 10)
+    hb = _harness(env)
+    hf = Harness(torch, bls, ctx, bls.Model.resnet_cifar(), oracle.ResNetCifar())
+    sb, sf = hb.score(p, b, x, y), hf.score(p, b, x, y)
+    assert 1e-6 < np.abs(sb - sf).max() < 0.05
+
+
+def test_mlp_rejects_bf16(env):
+    torch, bls, ctx = env
+    with pytest.raises(bls.BlsError):
+        bls.Model(0, act_dtype="bf16")
