@@ -229,6 +229,20 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
     const int n_groups = tile_pixels / (16 * MT);
     const int64_t pix0 = (int64_t)tile * tile_pixels;
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
+    // per-channel constants of the epilogue: this lane always owns channels c0 .. c0+3
+    const int c0 = ob * 16 + 4 * grp;
+    f32x4 ch_mu = {0.f, 0.f, 0.f, 0.f}, ch_is = ch_mu, ch_ga = ch_mu, ch_be = ch_mu;
+    if (EPI == 2 || EPI == 3) {
+        ch_mu = *reinterpret_cast<const f32x4*>(e.mean_prev + c0);
+        ch_is = *reinterpret_cast<const f32x4*>(e.invstd_prev + c0);
+    }
+    if (EPI == 3) {
+        // invstd_prev holds the running variance here
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ch_is[j] = (float)(1.0 / sqrt((double)ch_is[j] + 1e-5));
+        ch_ga = *reinterpret_cast<const f32x4*>(e.gamma + c0);
+        ch_be = *reinterpret_cast<const f32x4*>(e.beta + c0);
+    }
     for (int mg = wave / NOB; mg < n_groups; mg += NW / NOB) {
         int base[MT];
         f32x4 acc[MT];
@@ -236,6 +250,34 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
         for (int m = 0; m < MT; ++m) {
             base[m] = pixel_lds_base<CIN>(g, (mg * MT + m) * 16 + r16) / 4 + grp;  // float4 units
             acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        // input gradient: the epilogue's operands (activation and convolution output of the layer below, shortcut
+        // gradient) are requested before the MFMA loop so that their latency hides behind it
+        typename Act<T>::raw4 pre_a[MT], pre_y[MT], pre_s[MT];
+        if (EPI == 2) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const int64_t p = pix0 + (mg * MT + m) * 16 + r16;
+                pre_a[m] = pre_y[m] = pre_s[m] = Act<T>::zero();
+                if (p < total_pixels) {
+                    pre_a[m] = Act<T>::load_raw(static_cast<const T*>(e.a_prev) + p * NO + c0);
+                    pre_y[m] = Act<T>::load_raw(static_cast<const T*>(e.y_prev) + p * NO + c0);
+                    if (sc_g) {
+                        if (e.sc_stride == 1) {
+                            pre_s[m] = Act<T>::load_raw(sc_g + p * e.sc_c + c0);
+                        } else {
+                            const int wq = (int)(p & (g.h_out - 1));
+                            const int64_t row = p >> g.wout_log2;
+                            const int hq = (int)(row & (g.h_out - 1));
+                            if (((wq | hq) & 1) == 0) {
+                                const int64_t n = row >> g.wout_log2;
+                                const int hs = g.h_out >> 1;
+                                pre_s[m] = Act<T>::load_raw(sc_g + ((n * hs + (hq >> 1)) * hs + (wq >> 1)) * e.sc_c + e.sc_lo + c0);
+                            }
+                        }
+                    }
+                }
+            }
         }
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
@@ -264,42 +306,22 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
         for (int m = 0; m < MT; ++m) {
             int64_t p = pix0 + (mg * MT + m) * 16 + r16;
             if (p < total_pixels) {
-                const int c0 = ob * 16 + 4 * grp;
                 f32x4 v = acc[m];
                 if (EPI == 2) {
-                    if (e.sc_g) {
-                        // gradient that bypassed the block below through its shortcut
-                        if (e.sc_stride == 1) {
-                            v += Act<T>::load4(sc_g + p * e.sc_c + c0);
-                        } else {
-                            const int wq = (int)(p & (g.h_out - 1));
-                            const int64_t row = p >> g.wout_log2;
-                            const int hq = (int)(row & (g.h_out - 1));
-                            if (((wq | hq) & 1) == 0) {
-                                const int64_t n = row >> g.wout_log2;
-                                const int hs = g.h_out >> 1;
-                                v += Act<T>::load4(sc_g + ((n * hs + (hq >> 1)) * hs + (wq >> 1)) * e.sc_c + e.sc_lo + c0);
-                            }
-                        }
-                    }
+                    // gradient that bypassed the block below through its shortcut (zero when there is none)
+                    v += Act<T>::widen(pre_s[m]);
                     v = Act<T>::rounded(v);  // the sums below see what later kernels read back
                     Act<T>::store4(y + p * NO + c0, v);
-                    const f32x4 av = Act<T>::load4(static_cast<const T*>(e.a_prev) + p * NO + c0);
-                    const f32x4 yv = Act<T>::load4(static_cast<const T*>(e.y_prev) + p * NO + c0);
-                    const f32x4 mu = *reinterpret_cast<const f32x4*>(e.mean_prev + c0);
-                    const f32x4 is = *reinterpret_cast<const f32x4*>(e.invstd_prev + c0);
+                    const f32x4 av = Act<T>::widen(pre_a[m]);
+                    const f32x4 yv = Act<T>::widen(pre_y[m]);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float gq = av[j] > 0.f ? v[j] : 0.f;
                         ssum[j] += gq;
-                        ssq[j] = __fmaf_rn(gq, (yv[j] - mu[j]) * is[j], ssq[j]);
+                        ssq[j] = __fmaf_rn(gq, (yv[j] - ch_mu[j]) * ch_is[j], ssq[j]);
                     }
                 } else if (EPI == 3) {
                     // inference: batch norm with running statistics, shortcut, ReLU
-                    const f32x4 mu = *reinterpret_cast<const f32x4*>(e.mean_prev + c0);
-                    const f32x4 rv = *reinterpret_cast<const f32x4*>(e.invstd_prev + c0);  // running variance
-                    const f32x4 ga = *reinterpret_cast<const f32x4*>(e.gamma + c0);
-                    const f32x4 be = *reinterpret_cast<const f32x4*>(e.beta + c0);
                     f32x4 r = {0.f, 0.f, 0.f, 0.f};
                     if (e.sc_g && c0 >= e.sc_lo && c0 < e.sc_lo + e.sc_c) {
                         int64_t rp = p;
@@ -314,10 +336,8 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
                         r = Act<T>::load4(sc_g + rp * e.sc_c + (c0 - e.sc_lo));
                     }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float is = (float)(1.0 / sqrt((double)rv[j] + 1e-5));
-                        v[j] = fmaxf(__fmaf_rn((v[j] - mu[j]) * is, ga[j], be[j]) + r[j], 0.f);
-                    }
+                    for (int j = 0; j < 4; ++j)
+                        v[j] = fmaxf(__fmaf_rn((v[j] - ch_mu[j]) * ch_is[j], ch_ga[j], ch_be[j]) + r[j], 0.f);
                     Act<T>::store4(y + p * NO + c0, v);
                 } else {
                     v = Act<T>::rounded(v);
