@@ -187,7 +187,7 @@ def _time_calls(torch, fn, reps):
 
 
 def sweep():
-    """Stand-alone top-k (k = N/4, |N(0,1)| + ln 10 losses) and aggregation timings; one JSON line.
+    """Stand-alone top-k (k = N/4, |N(0,1)| + ln 10 losses), epoch sampler and aggregation timings; one JSON line.
 
     GB/s figures use the algorithmic bytes: 4N + 8k for top-k (read every loss, write k indices and
     values), (P + 1) * 4 * d for aggregation.  Buffers rotate so that repeats are not served from cache.
@@ -210,6 +210,17 @@ def sweep():
         gbs = (4 * N + 8 * k) / t / 1e9
         out["topk"].append({"N": N, "k": k, "us": round(t * 1e6, 2), "GB/s": round(gbs, 2), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
         del arrs
+    # epoch sampler at the paper's setting (8 fast and 2 slow workers, tau_F = 32, tau_S = 1), half of the fast
+    # allocation by loss; 3 selections over N per call
+    out["sample_epoch"] = []
+    for N in (50000, 100000, 1 << 20):
+        nf, k, ns = bls.epoch_allocation(N, 32, 8, 1, 2, 0.5)
+        losses = torch.randn(N, device="cuda").abs_() + math.log(10.0)
+        uf, us = torch.rand(N, device="cuda"), torch.rand(N, device="cuda")
+        fast = torch.empty(nf, dtype=torch.int32, device="cuda")
+        slow = torch.empty(max(ns, 1), dtype=torch.int32, device="cuda")
+        t = _time_calls(torch, lambda i=0: bls.sample_epoch(ctx, losses, uf, us, 32, 8, 1, 2, 0.5, fast, slow), 30)
+        out["sample_epoch"].append({"N": N, "n_fast": nf, "k": k, "n_slow": ns, "us": round(t * 1e6, 2)})
     for P, d in ((4, 394634), (10, 269722 + 1376), (10, 11007540), (10, 44000000), (10, 51747840)):
         sets = 3
         reps_sets = [[torch.randn(d, device="cuda") for _ in range(P)] for _ in range(sets)]

@@ -168,6 +168,31 @@ int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffe
 int weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* weights, int P, int64_t d,
                        float* out, int flags);
 
+/* ---- epoch sampler (Section 4.2; sampling steps at the top of every epoch of Algorithm 1) ------- */
+
+/* Sizes of one epoch's allocation.  N_F = floor(N tau_F P_F / (tau_F P_F + tau_S P_S)) samples go to the
+ * fast workers, the first k = floor(lambda N_F) of them by loss; N_S = N - N_F go to the slow workers.
+ * Host only.  0 <= N < 2^31, 1 <= tau_F <= 2^20, 0 <= tau_S <= 2^20, 1 <= P_F <= 1024, 0 <= P_S <= 1024,
+ * 0 < lambda <= 1; outputs may be NULL. */
+int bls_epoch_allocation(int64_t N, int64_t tau_f, int P_f, int64_t tau_s, int P_s, double lambda, int64_t* n_fast,
+                         int64_t* k_high, int64_t* n_slow);
+/* n ranked items dealt round-robin to P workers (worker p receives ranks p, p + P, ...): worker p's
+ * items sit at [offset, offset + count) of the worker-major output of sample_epoch.  Host only. */
+int bls_worker_share(int64_t n, int P, int p, int64_t* offset, int64_t* count);
+
+/* One epoch's sample assignment.
+ *   losses  device float[N]: current loss of every sample
+ *   u_fast, u_slow device float[N]: one finite random key per sample and per group, drawn by the caller
+ *           (uniform, independent); u_fast may be NULL when lambda selects everything by loss
+ *   fast_idx_out device int32[N_F], slow_idx_out device int32[N_S] (sizes from bls_epoch_allocation),
+ *           worker-major: the segment of worker p is given by bls_worker_share
+ * Fast workers: the k highest losses in rank order (as topk_by_loss), then the N_F - k samples with the
+ * largest u_fast among those not yet selected (uniform without replacement); equal keys rank by lower
+ * index.  Slow workers: the N_S samples with the largest u_slow among all N, independent of the fast
+ * draw.  Both lists are dealt round-robin by rank.  N == 0 is a no-op. */
+int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
+                 int P_f, int64_t tau_s, int P_s, double lambda, int32_t* fast_idx_out, int32_t* slow_idx_out);
+
 /* w_i = tau_i / sum_j tau_j (Eq. 4), computed in double and rounded once.  Host only. */
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out);
 

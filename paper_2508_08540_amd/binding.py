@@ -14,7 +14,8 @@ DECLARED_SYMBOLS = (
     "bls_ctx_create", "bls_ctx_destroy", "bls_last_error", "bls_ctx_synchronize", "bls_model_create",
     "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
-    "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end",
+    "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
+    "sample_epoch",
 )
 PROFILE_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "norm", "head", "gemm", "update", "gather", "topk",
                    "aggregate", "wgrad_reduce")
@@ -68,6 +69,10 @@ def _load():
     L.score_losses.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
     L.topk_by_loss.argtypes = [vp, vp, i64, i64, vp, vp]
     L.local_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i64, C.POINTER(_Sgd), vp]
+    L.bls_epoch_allocation.argtypes = [i64, i64, C.c_int, i64, C.c_int, C.c_double, C.POINTER(i64), C.POINTER(i64),
+                                       C.POINTER(i64)]
+    L.bls_worker_share.argtypes = [i64, C.c_int, C.c_int, C.POINTER(i64), C.POINTER(i64)]
+    L.sample_epoch.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, vp, vp]
     L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
     L.bls_weights_from_tau.argtypes = [C.POINTER(i64), C.c_int, C.POINTER(C.c_float)]
     L.bls_profile_begin.argtypes = [vp]
@@ -212,6 +217,29 @@ def weighted_aggregate(ctx, replicas, weights, out, flags=0):
     w = (C.c_float * P)(*[float(v) for v in weights])
     ctx.check(lib.weighted_aggregate(ctx.handle, ptrs, w, P, d, _ptr(out), flags))
     return out
+
+
+def epoch_allocation(N, tau_f, P_f, tau_s, P_s, lam):
+    """(N_F, k, N_S) of one epoch (host arithmetic)."""
+    nf, k, ns = C.c_int64(), C.c_int64(), C.c_int64()
+    rc = lib.bls_epoch_allocation(N, tau_f, P_f, tau_s, P_s, lam, C.byref(nf), C.byref(k), C.byref(ns))
+    if rc != 0:
+        raise BlsError(rc, "bls_epoch_allocation rejected the arguments")
+    return nf.value, k.value, ns.value
+
+
+def worker_share(n, P, p):
+    """(offset, count) of worker p's segment in a worker-major list of n items."""
+    off, cnt = C.c_int64(), C.c_int64()
+    rc = lib.bls_worker_share(n, P, p, C.byref(off), C.byref(cnt))
+    if rc != 0:
+        raise BlsError(rc, "bls_worker_share rejected the arguments")
+    return off.value, cnt.value
+
+
+def sample_epoch(ctx, losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, fast_idx_out, slow_idx_out):
+    ctx.check(lib.sample_epoch(ctx.handle, _ptr(losses), _ptr(u_fast), _ptr(u_slow), losses.shape[0], tau_f, P_f, tau_s,
+                               P_s, lam, _ptr(fast_idx_out), _ptr(slow_idx_out)))
 
 
 def weights_from_tau(tau):

@@ -307,6 +307,42 @@ int weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* 
     return launch_weighted_aggregate(ctx, replicas, w, P, d, out, (flags & BLS_AGG_BROADCAST) != 0);
 }
 
+int bls_epoch_allocation(int64_t N, int64_t tau_f, int P_f, int64_t tau_s, int P_s, double lambda, int64_t* n_fast,
+                         int64_t* k_high, int64_t* n_slow) {
+    if (N < 0 || N >= (int64_t(1) << 31) || tau_f < 1 || tau_f > (1 << 20) || tau_s < 0 || tau_s > (1 << 20) || P_f < 1 ||
+        P_f > 1024 || P_s < 0 || P_s > 1024 || !(lambda > 0.0 && lambda <= 1.0))
+        return BLS_EINVAL;
+    const int64_t fast = tau_f * P_f, slow = tau_s * P_s;
+    const int64_t nf = N * fast / (fast + slow);
+    if (n_fast) *n_fast = nf;
+    if (k_high) *k_high = (int64_t)floor(lambda * (double)nf);
+    if (n_slow) *n_slow = N - nf;
+    return BLS_OK;
+}
+
+int bls_worker_share(int64_t n, int P, int p, int64_t* offset, int64_t* count) {
+    if (n < 0 || P < 1 || p < 0 || p >= P) return BLS_EINVAL;
+    const int64_t base = n / P, rem = n % P;
+    if (offset) *offset = p * base + (p < rem ? p : rem);
+    if (count) *count = base + (p < rem ? 1 : 0);
+    return BLS_OK;
+}
+
+int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
+                 int P_f, int64_t tau_s, int P_s, double lambda, int32_t* fast_idx_out, int32_t* slow_idx_out) {
+    if (!ctx) return BLS_EINVAL;
+    int64_t nf, k, ns;
+    if (bls_epoch_allocation(N, tau_f, P_f, tau_s, P_s, lambda, &nf, &k, &ns) != BLS_OK)
+        return bls_fail(ctx, BLS_EINVAL, "sample_epoch: need 0 <= N < 2^31, 1 <= tau_F, 0 <= tau_S, 1 <= P_F, 0 <= P_S, 0 < lambda <= 1");
+    if (ns > 0 && P_s < 1) return bls_fail(ctx, BLS_EINVAL, "sample_epoch: slow samples but no slow worker");
+    if (N == 0) return BLS_OK;
+    if (!losses || (nf > k && !u_fast) || (ns > 0 && !u_slow) || (nf > 0 && !fast_idx_out) || (ns > 0 && !slow_idx_out))
+        return bls_fail(ctx, BLS_EINVAL, "sample_epoch: NULL pointer");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    ProfScope prof(ctx, PROF_TOPK);
+    return launch_sample_epoch(ctx, losses, u_fast, u_slow, N, nf, k, ns, P_f, P_s, fast_idx_out, slow_idx_out);
+}
+
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out) {
     if (!tau || !weights_out || P < 1) return BLS_EINVAL;
     double sum = 0.0;

@@ -52,3 +52,18 @@ def test_weights_from_tau_host_helper():
     np.testing.assert_array_equal(w, np.array([1 / 9] * 8 + [1 / 18] * 2, dtype=np.float32))
     with pytest.raises(bls.BlsError):
         bls.weights_from_tau([0, 0])
+
+
+def test_epoch_allocation_and_worker_share_match_the_oracle():
+    import oracle
+    import paper_2508_08540_amd as bls
+    for N, tf, pf, ts, ps, lam in [(50000, 32, 8, 1, 2, 1.0), (50000, 32, 8, 4, 2, 0.5), (100000, 32, 8, 1, 2, 0.25),
+                                   (7, 3, 2, 1, 1, 0.5), (0, 1, 1, 1, 1, 1.0), (12345, 5, 3, 0, 0, 0.1)]:
+        assert bls.epoch_allocation(N, tf, pf, ts, ps, lam) == oracle.allocation(N, tf, pf, ts, ps, lam)
+    ranked = list(range(23))
+    for P in (1, 2, 5, 23, 30):
+        parts = oracle.deal(ranked, P)
+        off = 0
+        for p in range(P):
+            assert bls.worker_share(len(ranked), P, p) == (off, len(parts[p]))
+            off += len(parts[p])
