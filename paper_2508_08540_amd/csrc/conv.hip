@@ -645,31 +645,80 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
     }
 }
 
-// For every convolution of the table: dw[((16*ob + o)*9 + t)*ci_real + 16*ib + i] = sum over the replicas of
-// accumulator (ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i], converted back to float; the accumulators are cleared
-// for the next step.  One launch converts all layers.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(fixsum_t* __restrict__ gacc, float* __restrict__ grad, WgradTable tab) {
-    const int64_t gi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // over the padded [NO][9][NI] spaces of all layers
-    if (gi >= tab.total) return;
-    int l = 0;
-    while (l + 1 < tab.n && gi >= tab.e[l + 1].first) ++l;
-    const WgradEntry e = tab.e[l];
-    const int idx = (int)(gi - e.first);
-    const int NI = e.c_in, NO = e.c_out;
-    int ot = idx / NI, ci = idx - ot * NI;
-    int co = ot / 9, t = ot - co * 9;
-    int blocks = (NO >> 4) * (NI >> 4);
-    int o = co & 15;
-    int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
-    int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
-    fixsum_t* acc_l = gacc + e.acc_off;
-    long long acc = 0;
+// End of a local step, one launch: for every parameter take the gradient, apply the SGD update
+// (g += wd*x; buf = mu*buf + g; x -= lr*buf), and for convolution weights also write the new value into the
+// packed copies that the next forward and input-gradient kernels read.  The gradient of a convolution weight
+// dw[16*ob + o][t][16*ib + i] is the sum over the replicas of accumulator (ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i],
+// converted back to float; the accumulators are cleared for the next step.  All other gradients come from grad[].
+// The kernel also clears the batch-norm accumulators of the next step.
+template <typename T>
+__global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params, float* __restrict__ momentum,
+                                                     const float* __restrict__ grad, int64_t d, float lr, float mu, float wd,
+                                                     fixsum_t* __restrict__ gacc, T* __restrict__ packed, UpdateTable tab,
+                                                     fixsum_t* __restrict__ sums, int64_t n_sums) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = first; i < n_sums; i += stride) sums[i] = 0ull;
+    for (int64_t i = first; i < d; i += stride) {
+        int l = -1;
+        for (int q = 0; q < tab.n; ++q)
+            if (i >= tab.e[q].w_off && i < tab.e[q].w_off + tab.e[q].n) l = q;
+        float g;
+        int co = 0, t = 0, ci = 0;
+        if (l >= 0) {
+            const UpdateEntry& e = tab.e[l];
+            const int r = (int)(i - e.w_off);
+            const int ot = r / e.c_in_real;
+            ci = r - ot * e.c_in_real;
+            co = ot / 9;
+            t = ot - co * 9;
+            const int NI = e.c_in, o = co & 15;
+            const int blocks = (e.c_out >> 4) * (NI >> 4);
+            const int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
+            const int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
+            fixsum_t* acc_l = gacc + e.acc_off;
+            long long acc = 0;
 #pragma unroll
-    for (int r = 0; r < WGRAD_REPLICAS; ++r) {
-        acc += (long long)acc_l[r * pitch + src];
-        acc_l[r * pitch + src] = 0ull;
+            for (int rep = 0; rep < WGRAD_REPLICAS; ++rep) {
+                acc += (long long)acc_l[rep * pitch + src];
+                acc_l[rep * pitch + src] = 0ull;
+            }
+            g = (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));
+        } else {
+            g = grad[i];
+        }
+        const float x = params[i];
+        g = __fmaf_rn(wd, x, g);
+        const float buf = __fmaf_rn(mu, momentum[i], g);
+        momentum[i] = buf;
+        const float xn = __fmaf_rn(-lr, buf, x);
+        params[i] = xn;
+        if (l >= 0) {
+            const UpdateEntry& e = tab.e[l];
+            T xs;
+            if constexpr (sizeof(T) == 4) xs = xn;
+            else xs = f32_to_bf16(xn);
+            {   // forward form: quad ((ob*9 + t)*S + s)*64 + lane holds w[16*ob + lane%16][t][16*s + 4*(lane/16) + 0..3]
+                const int S = e.c_in >> 4;
+                const int64_t quad = e.fwd_quad + ((int64_t)((co >> 4) * 9 + t) * S + (ci >> 4)) * 64 + (co & 15) + 16 * ((ci & 15) >> 2);
+                packed[quad * 4 + (ci & 3)] = xs;
+            }
+            if (e.dgrad_quad >= 0) {
+                // transposed, flipped form: roles of input and output channels swap
+                const int S = e.c_out >> 4;
+                const int64_t quad = e.dgrad_quad + ((int64_t)((ci >> 4) * 9 + (8 - t)) * S + (co >> 4)) * 64 + (ci & 15) + 16 * ((co & 15) >> 2);
+                packed[quad * 4 + (co & 3)] = xs;
+            }
+        }
     }
-    if (ci < e.c_in_real) grad[e.w_off + (int64_t)ot * e.c_in_real + ci] = (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));
+}
+
+void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
+                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums) {
+    int64_t blocks = (d + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    ACT_DISPATCH(act, hipLaunchKernelGGL(update_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, params, momentum, grad, d, lr, mu,
+                                         wd, gacc, (T*)packed, tab, sums, n_sums));
 }
 
 // Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller
@@ -711,6 +760,3 @@ void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
     ACT_DISPATCH(act, launch_conv_wgrad_t<T>(s, cs, (const T*)x, (const T*)dy, gacc, kt));
 }
 
-void launch_conv_wgrad_reduce(hipStream_t s, fixsum_t* gacc, float* grad, const WgradTable& tab) {
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((tab.total + 255) / 256)), dim3(256), 0, s, gacc, grad, tab);
-}

@@ -140,17 +140,20 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 int64_t conv_wgrad_accumulators(const ConvShape& cs);
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt = nullptr);
-// ... and, for all layers at once, grad[w_off ..] = sum of the replicas as float; clears the accumulators again.
+// End of a local step in one launch (see update_kernel): gradient of every parameter (convolution weights from the
+// accumulators, which are cleared; the rest from grad[]), SGD update, refresh of the packed weight copies, and
+// clearing of the n_sums batch-norm accumulators.
 #define WGRAD_MAX_ENTRIES 40
-struct WgradEntry {
-    int64_t w_off;    // offset of dw[c_out][3][3][c_in_real] in the gradient vector
-    int64_t acc_off;  // offset of this layer's accumulators in gacc
-    int64_t first;    // first index of this layer in the concatenated padded [c_out][9][c_in] spaces
+struct UpdateEntry {
+    int64_t w_off, n;     // w[c_out][3][3][c_in_real] in the parameter vector
+    int64_t acc_off;      // this layer's accumulators in gacc
+    int64_t fwd_quad;     // quad offset of the forward packed copy
+    int64_t dgrad_quad;   // quad offset of the input-gradient packed copy, -1 if the layer has none
     int c_in, c_out, c_in_real, pad_;
 };
-struct WgradTable {
+struct UpdateTable {
     int n;
-    int64_t total;
-    WgradEntry e[WGRAD_MAX_ENTRIES];
+    UpdateEntry e[WGRAD_MAX_ENTRIES];
 };
-void launch_conv_wgrad_reduce(hipStream_t s, fixsum_t* gacc, float* grad, const WgradTable& tab);
+void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
+                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums);

@@ -82,7 +82,7 @@ struct ResScratch {
     float* grad;
     fixsum_t* wacc;  // weight-gradient accumulators of all layers (kept zero between uses)
     int64_t wacc_count;
-    WgradTable wtab;
+    UpdateTable utab;  // per layer: where its weights, accumulators and packed copies are
     fixsum_t* sums;  // per layer: a forward and a backward set of fixed-point accumulators, zeroed every step
     float *loss, *feat, *dlogits, *dfeat;
 };
@@ -117,17 +117,17 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     s.loss = c.take<float>(B);
     s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L); s.dy.assign(L, nullptr);
     int64_t max_act = 0, max_wpart = 0;
-    s.wtab.n = 0;
-    s.wtab.total = 0;
+    s.utab.n = 0;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
         max_act = max64(max_act, out_elems(cb, B));
         {
-            WgradEntry& we = s.wtab.e[s.wtab.n++];
-            we.w_off = cb.w_off; we.acc_off = max_wpart; we.first = s.wtab.total;
-            we.c_in = cs.c_in; we.c_out = cs.c_out; we.c_in_real = cs.c_in_real; we.pad_ = 0;
-            s.wtab.total += (int64_t)cs.c_out * 9 * cs.c_in;
+            UpdateEntry& ue = s.utab.e[s.utab.n++];
+            ue.w_off = cb.w_off; ue.n = (int64_t)cs.c_out * 9 * cs.c_in_real; ue.acc_off = max_wpart;
+            ue.fwd_quad = s.fwd_off[l] / (4 * (int64_t)esz);
+            ue.dgrad_quad = (train && l > 0) ? s.dgrad_off[l] / (4 * (int64_t)esz) : -1;
+            ue.c_in = cs.c_in; ue.c_out = cs.c_out; ue.c_in_real = cs.c_in_real; ue.pad_ = 0;
             max_wpart += conv_wgrad_accumulators(cs);
         }
         s.mean[l] = c.take<float>(cb.c_out);
@@ -168,8 +168,10 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
 // Forward pass over a batch already gathered into s.xpad.  Train mode keeps every layer's
 // convolution output and activation for the backward pass and updates the running statistics.
 // Returns the final activation.
+// `prepare`: build the packed weight copies from the parameters and clear the batch-norm accumulators first (the update
+// at the end of a local step leaves both ready for the next step).
 const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, ResScratch& s,
-                            bool train) {
+                            bool train, bool prepare) {
     const int L = (int)m->layers.size();
     act_t* rot[4] = {s.d1, s.d2, s.g, s.stats};  // inference-only rotation
     int next = 0;
@@ -180,8 +182,10 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             if (p != keep0 && p != keep1) return p;
         }
     };
-    PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab));
-    if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), (int64_t)m->layers.size() * 2 * FIX_SET * 2));
+    if (prepare) {
+        PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab));
+        if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), (int64_t)m->layers.size() * 2 * FIX_SET * 2));
+    }
     const act_t* block_in = nullptr;
     const act_t* cur = s.xpad;
     for (int l = 0; l < L; ++l) {
@@ -260,7 +264,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                             s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
         BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
         BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
-        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, s.act, cs, x_in, s.dy[l], s.wacc + s.wtab.e[l].acc_off, kt));
+        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt));
         if (l == 0) break;
         {
             // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
@@ -277,10 +281,6 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         }
         dout = s.d2;
         shared = 0;
-    }
-    {
-        ProfScope prof_(ctx, PROF_WGRAD_REDUCE, ctx->aux);
-        launch_conv_wgrad_reduce(ctx->aux, s.wacc, s.grad, s.wtab);
     }
     BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
     BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
@@ -317,7 +317,7 @@ int net_score(bls_ctx* ctx, const bls_model* m, const float* params, const float
         for (int64_t first = 0; first < N; first += chunk) {
             int B = (int)(N - first < chunk ? N - first : chunk);
             PROF(ctx, PROF_GATHER, launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
-            const act_t* fin = resnet_forward(ctx, st, m, params, const_cast<float*>(buffers), B, s, false);
+            const act_t* fin = resnet_forward(ctx, st, m, params, const_cast<float*>(buffers), B, s, false, first == 0);
             PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
                                 m->desc.classes, s.yb, losses_out + first, nullptr, nullptr, nullptr, 0.f, false));
         }
@@ -359,13 +359,15 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
             PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
-            const act_t* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true);
+            const act_t* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true, j == 0);
             PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
                                 loss, s.feat, s.dlogits, s.dfeat, inv_b, false));
             PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b));
             rc = resnet_backward(ctx, st, m, params, B, s);
             if (rc != BLS_OK) return rc;
-            PROF(ctx, PROF_UPDATE, launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay));
+            // gradients of the convolution weights are still in the accumulators: the update reads them there
+            PROF(ctx, PROF_UPDATE, launch_update(st, s.act, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay,
+                                                 s.wacc, s.wpack, s.utab, s.sums, (int64_t)m->layers.size() * 2 * FIX_SET));
         }
     }
     BLS_HIP(ctx, hipGetLastError());
