@@ -2,8 +2,9 @@
 
 These are the textbook building blocks of the networks the paper trains (ResNet20 on
 CIFAR-10, Section 5): 3x3 convolution with zero padding 1, training- and inference-mode
-batch normalisation, ReLU, global average pooling and a linear layer.  Convolution weights
-are [C_out, 3, 3, C_in]; images are [N, H, W, C].
+batch normalisation, ReLU, global average pooling and a linear layer, plus the 1x1 projection of the
+wide residual networks (WRN16, Section 5).  Convolution weights are [C_out, kh, kw, C_in]; images are
+[N, H, W, C].
 """
 import numpy as np
 
@@ -42,6 +43,19 @@ def conv3x3_backward(x, w, dout, stride=1, need_dx=True):
             if need_dx:
                 dxp[sl] += dout @ w[:, kh, kw, :]
     return (dxp[:, 1:H + 1, 1:W + 1, :] if need_dx else None), dw
+
+
+def conv1x1(x, w, stride=1):
+    """out[n,h,w,o] = sum_i x[n, s*h, s*w, i] * w[o,0,0,i]: the projection shortcut of a residual block."""
+    return x[:, ::stride, ::stride, :] @ w[:, 0, 0, :].T
+
+
+def conv1x1_backward(x, w, dout, stride=1):
+    """(dx, dw): adjoints of conv1x1."""
+    dx = np.zeros(x.shape, dtype=np.float64)
+    dx[:, ::stride, ::stride, :] = dout @ w[:, 0, 0, :]
+    dw = np.tensordot(dout, x[:, ::stride, ::stride, :], axes=([0, 1, 2], [0, 1, 2])).reshape(w.shape)
+    return dx, dw
 
 
 def batchnorm_train(x, gamma, beta, running_mean, running_var):

@@ -1,4 +1,4 @@
-"""The two networks of the measured workloads, forward and backward, in float64.
+"""The networks of the measured workloads, forward and backward, in float64.
 
 MLP: 3072 -> 128 (ReLU) -> 10 on flattened images.  ResNetCifar: the CIFAR residual network of
 He et al. (2016) that the paper calls ResNet20 (Section 5): 3x3 stem, 3 stages x 3 basic blocks
@@ -125,4 +125,94 @@ class ResNetCifar:
         dz0 = L.relu_backward(da, cache["stem.out"], tg.get("stem.out"))
         dy0, g["stem.bn.weight"], g["stem.bn.bias"] = L.batchnorm_train_backward(dz0, cache["stem.bn"])
         _, g["stem.conv.weight"] = L.conv3x3_backward(cache["x"], w["stem.conv.weight"], q(dy0), 1, need_dx=False)
+        return g
+
+
+class WideResNet:
+    """Wide residual network for 32x32 images (Zagoruyko & Komodakis 2016), the WRN16 family of Section 5.
+
+    Depth 6 * blocks + 4 with widening factor widths[0] / 16: a 3x3 stem to `stem` channels, three stages of
+    `blocks` pre-activation blocks  out = shortcut + conv2(relu(bn2(conv1(relu(bn1(x))))))  where the first
+    block of stages 2 and 3 has stride 2, and the shortcut is the identity when the block keeps its shape
+    and otherwise a 1x1 convolution (same stride) of relu(bn1(x)); then batch norm, ReLU, global average
+    pooling and a linear classifier.  WRN-16-8 is widths (128, 256, 512), blocks 2, stem 16.
+    `storage` has the meaning described at the top of this file.
+    """
+    has_buffers = True
+
+    def __init__(self, widths=(128, 256, 512), blocks=2, stem=16, storage=None):
+        self.widths, self.blocks, self.stem = tuple(widths), blocks, stem
+        self.q = storage if storage is not None else (lambda a: a)
+
+    def block_list(self):
+        out, c_prev = [], self.stem
+        for s, c in enumerate(self.widths):
+            for b in range(self.blocks):
+                stride = 2 if (b == 0 and s > 0) else 1
+                out.append(("s%d.b%d" % (s + 1, b), c_prev, c, stride, c_prev != c or stride != 1))
+                c_prev = c
+        return out
+
+    def _bn(self, name, x, p, bufs, new_bufs, train):
+        g, b = p[name + ".weight"], p[name + ".bias"]
+        rm, rv = bufs[name + ".running_mean"], bufs[name + ".running_var"]
+        if not train:
+            return L.batchnorm_eval(x, g, b, rm, rv), None
+        y, cache, nrm, nrv = L.batchnorm_train(x, g, b, rm, rv)
+        new_bufs[name + ".running_mean"], new_bufs[name + ".running_var"] = nrm, nrv
+        return y, cache
+
+    def forward(self, params, buffers, x, train):
+        p, bufs = _f64(params), _f64(buffers)
+        q = self.q
+        w = {k: q(v) for k, v in p.items() if k.endswith("conv.weight") or ".conv1." in k or ".conv2." in k or ".shortcut." in k}
+        new_bufs = dict(bufs)
+        x = q(np.asarray(x, dtype=np.float64))
+        cache = {"p": p, "w": w, "x": x, "z": {}}
+        cur = q(L.conv3x3(x, w["stem.conv.weight"], 1))
+        for name, c_in, c_out, stride, proj in self.block_list():
+            cache[name + ".in"] = cur
+            z1, cache[name + ".bn1"] = self._bn(name + ".bn1", cur, p, bufs, new_bufs, train)
+            cache["z"][name + ".o1"] = z1
+            o1 = q(L.relu(z1))
+            cache[name + ".o1"] = o1
+            y1 = q(L.conv3x3(o1, w[name + ".conv1.weight"], stride))
+            z2, cache[name + ".bn2"] = self._bn(name + ".bn2", y1, p, bufs, new_bufs, train)
+            cache["z"][name + ".o2"] = z2
+            o2 = q(L.relu(z2))
+            cache[name + ".o2"] = o2
+            sc = q(L.conv1x1(o1, w[name + ".shortcut.weight"], stride)) if proj else cur
+            cur = q(L.conv3x3(o2, w[name + ".conv2.weight"], 1) + sc)
+        cache["last"] = cur
+        zf, cache["final.bn"] = self._bn("final.bn", cur, p, bufs, new_bufs, train)
+        cache["z"]["final"] = zf
+        a = q(L.relu(zf))
+        cache["final"] = a
+        pooled = L.global_avgpool(a)
+        cache["pooled"] = pooled
+        logits = L.linear(pooled, p["fc.weight"], p["fc.bias"])
+        return logits, cache, new_bufs
+
+    def backward(self, cache, dlogits, toggles=None):
+        p, w, q = cache["p"], cache["w"], self.q
+        g, tg = {}, toggles or {}
+        dpooled, g["fc.weight"], g["fc.bias"] = L.linear_backward(cache["pooled"], p["fc.weight"], dlogits)
+        da = L.global_avgpool_backward(dpooled, cache["final"].shape)
+        dzf = L.relu_backward(da, cache["final"], tg.get("final"))
+        dout, g["final.bn.weight"], g["final.bn.bias"] = L.batchnorm_train_backward(dzf, cache["final.bn"])
+        dout = q(dout)
+        for name, c_in, c_out, stride, proj in reversed(self.block_list()):
+            o1, o2 = cache[name + ".o1"], cache[name + ".o2"]
+            do2, g[name + ".conv2.weight"] = L.conv3x3_backward(o2, w[name + ".conv2.weight"], dout, 1)
+            dz2 = L.relu_backward(q(do2), o2, tg.get(name + ".o2"))
+            dy1, g[name + ".bn2.weight"], g[name + ".bn2.bias"] = L.batchnorm_train_backward(dz2, cache[name + ".bn2"])
+            dy1 = q(dy1)
+            do1, g[name + ".conv1.weight"] = L.conv3x3_backward(o1, w[name + ".conv1.weight"], dy1, stride)
+            if proj:
+                dsc, g[name + ".shortcut.weight"] = L.conv1x1_backward(o1, w[name + ".shortcut.weight"], dout, stride)
+                do1 = do1 + q(dsc)
+            dz1 = L.relu_backward(q(do1), o1, tg.get(name + ".o1"))
+            dx, g[name + ".bn1.weight"], g[name + ".bn1.bias"] = L.batchnorm_train_backward(dz1, cache[name + ".bn1"])
+            dout = q(dx if proj else dx + dout)
+        _, g["stem.conv.weight"] = L.conv3x3_backward(cache["x"], w["stem.conv.weight"], dout, 1, need_dx=False)
         return g

@@ -23,6 +23,9 @@ WORKLOADS = {
     # the same network with bf16 activations and fp32 master weights, larger pool and selection
     "resnet20_bf16": dict(id=2, model="resnet20", act_dtype="bf16", pool=4096, classes=10, k=1024, batch=128, tau=50,
                           lr=0.1, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
+    # wide residual network WRN-16-8, bf16 activations / fp32 master weights, 100 classes
+    "wrn16_8_bf16": dict(id=3, model="wrn16_8", act_dtype="bf16", pool=2048, classes=100, k=512, batch=128, tau=4,
+                         lr=0.1, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
 }
 
 
@@ -125,6 +128,69 @@ def resnet_init(workload_id, widths=(16, 32, 64), blocks=3, classes=10, in_chann
     for t, (name, shape) in enumerate(b_specs):
         n = int(np.prod(shape))
         stream = 6000 + 4 * t
+        if name.endswith("running_mean"):
+            buffers[name] = (perturb_bn * (2.0 * rng.uniform01(seed, stream, n) - 1.0)).astype(np.float32)
+        else:
+            buffers[name] = (1.0 + perturb_bn * rng.uniform01(seed, stream, n)).astype(np.float32)
+    return params, buffers
+
+
+def wrn_tensor_specs(widths=(128, 256, 512), blocks=2, classes=100, stem=16, in_channels=3):
+    """(params, buffers) of a pre-activation wide residual network, in flat-vector order.
+
+    Per block: bn1, conv1, bn2, conv2 and, where the block changes the shape, a 1x1 shortcut
+    convolution; after the last block a final batch norm and the linear classifier.
+    """
+    params, buffers = [], []
+
+    def bn(prefix, c):
+        params.append((prefix + ".weight", (c,)))
+        params.append((prefix + ".bias", (c,)))
+        buffers.append((prefix + ".running_mean", (c,)))
+        buffers.append((prefix + ".running_var", (c,)))
+
+    params.append(("stem.conv.weight", (stem, 3, 3, in_channels)))
+    c_prev = stem
+    for s, c in enumerate(widths):
+        for b in range(blocks):
+            p = "s%d.b%d" % (s + 1, b)
+            stride = 2 if (b == 0 and s > 0) else 1
+            bn(p + ".bn1", c_prev)
+            params.append((p + ".conv1.weight", (c, 3, 3, c_prev)))
+            bn(p + ".bn2", c)
+            params.append((p + ".conv2.weight", (c, 3, 3, c)))
+            if c_prev != c or stride != 1:
+                params.append((p + ".shortcut.weight", (c, 1, 1, c_prev)))
+            c_prev = c
+    bn("final.bn", widths[-1])
+    params.append(("fc.weight", (classes, widths[-1])))
+    params.append(("fc.bias", (classes,)))
+    return params, buffers
+
+
+def wrn_init(workload_id, widths=(128, 256, 512), blocks=2, classes=100, stem=16, in_channels=3, perturb_bn=0.0):
+    """(params dict, buffers dict) of float32 arrays for wrn_tensor_specs; same conventions as resnet_init."""
+    seed = _seed(workload_id)
+    p_specs, b_specs = wrn_tensor_specs(widths, blocks, classes, stem, in_channels)
+    params, buffers = {}, {}
+    for t, (name, shape) in enumerate(p_specs):
+        n = int(np.prod(shape))
+        stream = 12000 + 4 * t
+        if len(shape) == 4:
+            fan_out = shape[0] * shape[1] * shape[2]
+            params[name] = (rng.normal(seed, stream, n) * np.sqrt(2.0 / fan_out)).reshape(shape).astype(np.float32)
+        elif name == "fc.weight":
+            w, b = _linear_init(seed, stream, shape[0], shape[1])
+            params["fc.weight"], params["fc.bias"] = w, b
+        elif name == "fc.bias":
+            pass
+        elif name.endswith(".weight"):
+            params[name] = (1.0 + perturb_bn * (2.0 * rng.uniform01(seed, stream, n) - 1.0)).astype(np.float32)
+        else:
+            params[name] = (perturb_bn * (2.0 * rng.uniform01(seed, stream, n) - 1.0)).astype(np.float32)
+    for t, (name, shape) in enumerate(b_specs):
+        n = int(np.prod(shape))
+        stream = 16000 + 4 * t
         if name.endswith("running_mean"):
             buffers[name] = (perturb_bn * (2.0 * rng.uniform01(seed, stream, n) - 1.0)).astype(np.float32)
         else:
