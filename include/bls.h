@@ -44,7 +44,7 @@ typedef enum {
 typedef struct bls_ctx bls_ctx;     /* device, stream (borrowed) and library-owned scratch */
 typedef struct bls_model bls_model; /* architecture and flat-parameter layout (host only)  */
 
-enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1 };
+enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1, BLS_MODEL_WRN = 2 };
 
 /* Storage type of the activations (and of the copies of the convolution weights the kernels read).
  * Parameters, momentum, gradients, batch-norm statistics, losses and every reduction stay fp32: with
@@ -57,15 +57,22 @@ enum { BLS_ACT_F32 = 0, BLS_ACT_BF16 = 1 };
  *                  blocks with widths[0..2] (stride 2 and a parameter-free zero-padded shortcut at
  *                  the start of stages 2 and 3), batch norm after every convolution, global
  *                  average pooling, linear classifier.  ResNet20 (Section 5) is widths 16/32/64,
- *                  blocks 3, image_hw 32, in_channels 3, classes 10. */
+ *                  blocks 3, image_hw 32, in_channels 3, classes 10.
+ *   WRN:           pre-activation wide residual network (the WRN16 of Section 5): 3x3 stem conv to `hidden`
+ *                  channels, three stages of `blocks` blocks  out = shortcut + conv2(relu(bn2(conv1(relu(bn1(x))))))
+ *                  with widths[0..2], stride 2 at the start of stages 2 and 3, identity shortcut where the block
+ *                  keeps its shape and a 1x1 convolution of relu(bn1(x)) otherwise; batch norm, ReLU, global
+ *                  average pooling, linear classifier.  WRN-16-8 is hidden 16, widths 128/256/512, blocks 2,
+ *                  image_hw 32, classes 100.  Tensor order: stem.conv; per block bn1, conv1, bn2, conv2,
+ *                  [shortcut]; final.bn; fc. */
 typedef struct {
     int32_t kind;        /* BLS_MODEL_*                                    */
-    int32_t classes;     /* 2 .. 64                                        */
-    int32_t image_hw;    /* square images; RESNET: 8, 16, 32 or 64          */
-    int32_t in_channels; /* RESNET: 1 .. 4                                 */
-    int32_t hidden;      /* MLP only: multiple of 16, 16 .. 1024           */
-    int32_t widths[3];   /* RESNET only: each of 16, 32 or 64              */
-    int32_t blocks;      /* RESNET only: 1 .. 6                            */
+    int32_t classes;     /* 2 .. 64 (WRN: 2 .. 128)                        */
+    int32_t image_hw;    /* square images; RESNET: 8, 16, 32 or 64; WRN: 8, 16 or 32 */
+    int32_t in_channels; /* RESNET, WRN: 1 .. 4                            */
+    int32_t hidden;      /* MLP: multiple of 16, 16 .. 1024; WRN: stem channels, 16 or a multiple of 32 up to 512 */
+    int32_t widths[3];   /* RESNET: each of 16, 32 or 64; WRN: each 16 or a multiple of 32 up to 512 */
+    int32_t blocks;      /* RESNET: 1 .. 6; WRN: 1 .. 4                    */
     int32_t act_dtype;   /* BLS_ACT_*; the MLP supports BLS_ACT_F32 only   */
 } bls_model_desc;
 

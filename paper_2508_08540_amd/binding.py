@@ -6,7 +6,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
-MODEL_MLP, MODEL_RESNET_CIFAR = 0, 1
+MODEL_MLP, MODEL_RESNET_CIFAR, MODEL_WRN = 0, 1, 2
 ACT_DTYPES = {"f32": 0, "bf16": 1}
 AGG_NORMALISE, AGG_BROADCAST = 1, 2
 
@@ -166,6 +166,11 @@ class Model:
     def resnet_cifar(cls, widths=(16, 32, 64), blocks=3, classes=10, image_hw=32, in_channels=3, act_dtype="f32"):
         """act_dtype "bf16": activations and the kernels' weight copies in bf16, everything else fp32."""
         return cls(MODEL_RESNET_CIFAR, classes, image_hw, in_channels, 0, widths, blocks, act_dtype)
+
+    @classmethod
+    def wide_resnet(cls, widths=(128, 256, 512), blocks=2, classes=100, image_hw=32, in_channels=3, stem=16, act_dtype="f32"):
+        """Pre-activation wide residual network; the defaults are WRN-16-8."""
+        return cls(MODEL_WRN, classes, image_hw, in_channels, stem, widths, blocks, act_dtype)
 
     def pack(self, tensors, buffers=False):
         """dict name -> array  =>  flat float32 numpy vector in the library's layout."""

@@ -157,9 +157,11 @@ static void add_conv_bn(bls_model* m, const std::string& conv, const std::string
 int bls_model_create(const bls_model_desc* desc, bls_model** out) {
     if (!desc || !out) return BLS_EINVAL;
     *out = nullptr;
-    if (desc->classes < 2 || desc->classes > 64) return BLS_EINVAL;
+    if (desc->classes < 2 || desc->classes > (desc->kind == BLS_MODEL_WRN ? 128 : 64)) return BLS_EINVAL;
     if (desc->act_dtype != BLS_ACT_F32 && desc->act_dtype != BLS_ACT_BF16) return BLS_EINVAL;
     if (desc->kind == BLS_MODEL_MLP && desc->act_dtype != BLS_ACT_F32) return BLS_EUNSUPPORTED;
+    // a convolution's input width must be 16 or a multiple of 32 in the wide network
+    auto wide_ok = [](int c) { return c == 16 || (c >= 32 && c <= 512 && c % 32 == 0); };
     bls_model* m = new (std::nothrow) bls_model();
     if (!m) return BLS_ENOMEM;
     m->desc = *desc;
@@ -206,6 +208,59 @@ int bls_model_create(const bls_model_desc* desc, bls_model** out) {
         m->final_hw = hw;
         m->fc_w = m->num_params; add_tensor(m, "fc.weight", false, 2, desc->classes, c_prev);
         m->fc_b = m->num_params; add_tensor(m, "fc.bias", false, 1, desc->classes);
+    } else if (desc->kind == BLS_MODEL_WRN) {
+        bool ok = (desc->image_hw == 8 || desc->image_hw == 16 || desc->image_hw == 32) && desc->in_channels >= 1 &&
+                  desc->in_channels <= 4 && desc->blocks >= 1 && desc->blocks <= 4 && wide_ok(desc->hidden);
+        for (int s = 0; s < 3; ++s) ok = ok && wide_ok(desc->widths[s]);
+        if (!ok) {
+            delete m;
+            return BLS_EINVAL;
+        }
+        auto add_bn = [&](const std::string& name, int c) {
+            BnSlot b;
+            b.c = c;
+            b.gamma_off = m->num_params; add_tensor(m, name + ".weight", false, 1, c);
+            b.beta_off = m->num_params; add_tensor(m, name + ".bias", false, 1, c);
+            b.rmean_off = m->num_buffers; add_tensor(m, name + ".running_mean", true, 1, c);
+            b.rvar_off = m->num_buffers; add_tensor(m, name + ".running_var", true, 1, c);
+            return b;
+        };
+        auto add_conv = [&](const std::string& name, int c_in, int c_out, int stride, int taps, int h_in) {
+            ConvSlot c;
+            c.c_in = c_in; c.c_out = c_out; c.stride = stride; c.taps = taps; c.h_in = h_in; c.h_out = (h_in - 1) / stride + 1;
+            c.w_off = m->num_params;
+            const int k = taps == 9 ? 3 : 1;
+            add_tensor(m, name + ".weight", false, 4, c_out, k, k, c_in);
+            return c;
+        };
+        int hw = desc->image_hw;
+        m->wrn_stem = add_conv("stem.conv", desc->in_channels, desc->hidden, 1, 9, hw);
+        int c_prev = desc->hidden;
+        for (int s = 0; s < 3; ++s) {
+            int c = desc->widths[s];
+            for (int b = 0; b < desc->blocks; ++b) {
+                int stride = (b == 0 && s > 0) ? 2 : 1;
+                char pn[32];
+                snprintf(pn, sizeof pn, "s%d.b%d", s + 1, b);
+                const std::string p(pn);
+                WrnBlock blk{};
+                blk.proj = c_prev != c || stride != 1;
+                blk.bn1 = add_bn(p + ".bn1", c_prev);
+                blk.conv1 = add_conv(p + ".conv1", c_prev, c, stride, 9, hw);
+                const int h_out = (hw - 1) / stride + 1;
+                blk.bn2 = add_bn(p + ".bn2", c);
+                blk.conv2 = add_conv(p + ".conv2", c, c, 1, 9, h_out);
+                if (blk.proj) blk.shortcut = add_conv(p + ".shortcut", c_prev, c, stride, 1, hw);
+                m->wrn_blocks.push_back(blk);
+                hw = h_out;
+                c_prev = c;
+            }
+        }
+        m->wrn_final_bn = add_bn("final.bn", c_prev);
+        m->final_c = c_prev;
+        m->final_hw = hw;
+        m->fc_w = m->num_params; add_tensor(m, "fc.weight", false, 2, desc->classes, c_prev);
+        m->fc_b = m->num_params; add_tensor(m, "fc.bias", false, 1, desc->classes);
     } else {
         delete m;
         return BLS_EINVAL;
@@ -245,6 +300,7 @@ int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, cons
     if (model->num_buffers > 0 && !buffers) return bls_fail(ctx, BLS_EINVAL, "score_losses: this model needs buffers");
     if (N >= (int64_t(1) << 31)) return bls_fail(ctx, BLS_EINVAL, "score_losses: N must be below 2^31");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
+    if (model->desc.kind == BLS_MODEL_WRN) return wrn_score(ctx, model, params, buffers, x, y, N, losses_out);
     return net_score(ctx, model, params, buffers, x, y, N, losses_out);
 }
 
@@ -271,9 +327,11 @@ int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffe
     if (tau == 0) return BLS_OK;
     if (!params || !momentum || !x_pool || !y_pool || !sel_idx) return bls_fail(ctx, BLS_EINVAL, "local_step: NULL pointer");
     if (model->num_buffers > 0 && !buffers) return bls_fail(ctx, BLS_EINVAL, "local_step: this model needs buffers");
-    if (model->desc.kind == BLS_MODEL_RESNET_CIFAR && batch * model->final_hw * model->final_hw < 2)
+    if (model->desc.kind != BLS_MODEL_MLP && batch * model->final_hw * model->final_hw < 2)
         return bls_fail(ctx, BLS_EINVAL, "local_step: batch norm needs more than one value per channel");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
+    if (model->desc.kind == BLS_MODEL_WRN)
+        return wrn_local_step(ctx, model, params, buffers, momentum, x_pool, y_pool, N, sel_idx, k, batch, tau, *opt, step_losses_out);
     return net_local_step(ctx, model, params, buffers, momentum, x_pool, y_pool, N, sel_idx, k, batch, tau, *opt,
                           step_losses_out);
 }

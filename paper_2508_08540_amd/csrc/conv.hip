@@ -25,133 +25,7 @@
 // see the rounded values, i.e. exactly what later kernels read back.  The weight gradient converts
 // bf16 operands to fp32 while staging and runs the fp32 instruction, so master-weight gradients keep fp32
 // products.
-#include "act.h"
-
-// A "quad" is 4 consecutive channels as they sit in LDS and in the packed weights; vec16 is one 16-byte
-// global load (VQ quads).
-template <typename T>
-struct Tile;
-template <>
-struct Tile<float> {
-    typedef f32x4 quad;
-    typedef f32x4 vec16;
-    static constexpr int VQ = 1;
-    static __device__ __forceinline__ vec16 zero16() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
-    static __device__ __forceinline__ void store16(quad* dst, const vec16& v) { dst[0] = v; }
-};
-template <>
-struct Tile<bf16_t> {
-    typedef uint2 quad;
-    typedef uint4 vec16;
-    static constexpr int VQ = 2;
-    static __device__ __forceinline__ vec16 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
-    static __device__ __forceinline__ void store16(quad* dst, const vec16& v) {
-        dst[0] = make_uint2(v.x, v.y);
-        dst[1] = make_uint2(v.z, v.w);
-    }
-};
-
-constexpr int clog2(int v) { return v <= 1 ? 0 : 1 + clog2(v >> 1); }
-
-#define CONV_THREADS 256
-#ifndef CONV_MT
-#define CONV_MT 2   // 16-pixel tiles a wave accumulates at once
-#define CONV_NW 4   // waves per workgroup of the forward / input-gradient kernel
-#endif
-
-struct ConvGeom {
-    int B, h_in, h_out, c_out, stride, ups;  // ups: input is read with zeros inserted (h_in is the virtual size)
-    int rpi_log2, imgs, in_rows, lw;          // rows per image part (log2), image parts per tile, LDS rows per part, LDS row width
-    int wout_log2;
-    int total_rows;                           // B * h_out
-    int w_ci;                                 // input channels actually present in the weight tensor
-    int n_tiles;
-    int rows_tile;                            // output rows per tile: 4, or more so that a tile has >= 32 pixels
-};
-
-static inline int ilog2(int v) {
-    int l = 0;
-    while ((1 << l) < v) ++l;
-    return l;
-}
-
-static ConvGeom make_geom(int B, int h_in, int h_out, int c_out, int stride, int ups, int w_ci, int rows_tile = 0) {
-    ConvGeom g;
-    g.B = B; g.h_in = h_in; g.h_out = h_out; g.c_out = c_out; g.stride = stride; g.ups = ups;
-    g.rows_tile = rows_tile ? rows_tile : (h_out >= 8 ? 4 : 32 / h_out);
-    int rpi = h_out < g.rows_tile ? h_out : g.rows_tile;
-    g.rpi_log2 = ilog2(rpi);
-    g.imgs = g.rows_tile / rpi;
-    g.in_rows = (rpi - 1) * stride + 3;
-    g.lw = h_in + 2;
-    g.wout_log2 = ilog2(h_out);
-    g.total_rows = B * h_out;
-    g.w_ci = w_ci;
-    g.n_tiles = (g.total_rows + g.rows_tile - 1) / g.rows_tile;
-    return g;
-}
-
-// LDS bytes of one staged tile: pixel pitch CIN/4 + 1 quads
-template <typename T, int CIN>
-static size_t input_lds_bytes(const ConvGeom& g) {
-    return (size_t)g.imgs * g.in_rows * g.lw * (CIN / 4 + 1) * sizeof(typename Tile<T>::quad);
-}
-
-// Stages the input rows of tile `tile` into lds[(part*in_rows + li)*lw + lc][CIN + PAD], zero outside the image.
-// `pitch` is the channel count of the tensor in memory and `c_off` the first channel of the CIN-wide slice.
-// A thread owns one quad column (lc, 4 channels) and walks the rows, so the row arithmetic is
-// wave-uniform (scalar unit) and no per-element division is needed; loads are issued six rows at a time.
-// D is the LDS element: the quad as stored, or f32x4 to widen bf16 to fp32 on the way in.
-template <typename T, typename D, int CIN, int THREADS = CONV_THREADS, int PAD = 4>
-__device__ __forceinline__ void stage_input(D* __restrict__ lds4, const T* __restrict__ x, const ConvGeom& g,
-                                            int tile, int pitch = CIN, int c_off = 0) {
-    typedef typename Act<T>::raw4 raw4;
-    constexpr int CP4 = (CIN + PAD) / 4, CQ = CIN / 4;
-    constexpr int CQ_LOG2 = CQ == 4 ? 2 : (CQ == 8 ? 3 : 4);
-    constexpr int R = 6;
-    const int rpi = 1 << g.rpi_log2;
-    const int row0 = tile * g.rows_tile;
-    const int n_cols = g.lw * CQ;
-    const int rows_total = g.imgs * g.in_rows;
-    const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
-    for (int col = threadIdx.x; col < n_cols; col += THREADS) {
-        const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
-        const int wi = lc - 1;
-        bool wok = (unsigned)wi < (unsigned)g.h_in;
-        int wsrc = wi;
-        if (g.ups) {
-            wok = wok && ((wi & 1) == 0);
-            wsrc = wi >> 1;
-        }
-        const T* colp = x + (int64_t)(wok ? wsrc : 0) * pitch + c_off + cq * 4;
-        D* dst = lds4 + lc * CP4 + cq;
-        for (int r0 = 0; r0 < rows_total; r0 += R) {
-            raw4 v[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int lr = r0 + r;                               // wave-uniform
-                const int part = lr / g.in_rows, li = lr - part * g.in_rows;
-                const int grow = row0 + part * rpi;
-                const int n = grow >> g.wout_log2;                   // h_out == w_out
-                const int hi = (grow & (g.h_out - 1)) * g.stride - 1 + li;
-                bool ok = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
-                int hsrc = hi;
-                if (g.ups) {
-                    ok = ok && ((hi & 1) == 0);
-                    hsrc = hi >> 1;
-                }
-                v[r] = Act<T>::zero();
-                if (ok) v[r] = Act<T>::load_raw(colp + ((int64_t)n * src_h + hsrc) * src_h * pitch);
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (r0 + r < rows_total) {
-                    if constexpr (sizeof(D) == sizeof(raw4)) dst[(r0 + r) * g.lw * CP4] = v[r];
-                    else dst[(r0 + r) * g.lw * CP4] = Act<T>::widen(v[r]);
-                }
-        }
-    }
-}
+#include "conv_tile.h"
 
 // The same staging split in two for software pipelining: tile_load issues the global loads of a tile into
 // registers (column per thread, up to PRE_ROWS rows), tile_store writes them to an LDS buffer later.
@@ -167,7 +41,7 @@ __device__ __forceinline__ void tile_load(typename Tile<T>::vec16 (&v)[PRE_ROWS]
     const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
     const int col = threadIdx.x;
     const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
-    const int wi = lc - 1;
+    const int wi = lc - g.pad;
     bool wok = col < g.lw * CQ && (unsigned)wi < (unsigned)g.h_in;
     int wsrc = wi;
     if (g.ups) {
@@ -180,7 +54,7 @@ __device__ __forceinline__ void tile_load(typename Tile<T>::vec16 (&v)[PRE_ROWS]
         const int part = r / g.in_rows, li = r - part * g.in_rows;  // wave-uniform
         const int grow = row0 + part * rpi;
         const int n = grow >> g.wout_log2;
-        const int hi = (grow & (g.h_out - 1)) * g.stride - 1 + li;
+        const int hi = (grow & (g.h_out - 1)) * g.stride - g.pad + li;
         bool ok = r < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
         int hsrc = hi;
         if (g.ups) {
@@ -204,14 +78,6 @@ __device__ __forceinline__ void tile_store(const typename Tile<T>::vec16 (&v)[PR
 #pragma unroll
     for (int r = 0; r < PRE_ROWS; ++r)
         if (r < rows_total) Tile<T>::store16(dst + r * g.lw * CPQ, v[r]);
-}
-
-// LDS float offset of the top-left tap of output pixel q (index inside the tile).
-template <int CIN, int PAD = 4>
-__device__ __forceinline__ int pixel_lds_base(const ConvGeom& g, int q) {
-    int rowq = q >> g.wout_log2, col = q & (g.h_out - 1);
-    int part = rowq >> g.rpi_log2, r = rowq & ((1 << g.rpi_log2) - 1);
-    return ((part * g.in_rows + r * g.stride) * g.lw + col * g.stride) * (CIN + PAD);
 }
 
 // MFMAs, epilogue and store of one staged tile for this wave.
@@ -481,9 +347,10 @@ static void launch_conv_c(hipStream_t s, int act, int c_in, const ConvGeom& g, c
 //
 // Lane-major copies of every convolution's weights, rebuilt after each parameter update.  For a layer
 // with (padded) input channels CI and output channels CO the forward copy holds, as quad (4 values of the storage type) number
-// ((ob*9 + t)*(CI/16) + s)*64 + lane, the values w[16*ob + lane%16][t][16*s + 4*(lane/16) + 0..3] (zero
-// beyond the real input channels).  The input-gradient copy describes the transposed convolution:
-// roles of CI and CO swap and the taps are flipped, value j = w[16*s + 4*(lane/16) + j][8 - t][16*ob + lane%16].
+// ((ob*taps + t)*(CI/16) + s)*64 + lane, the values w[16*ob + lane%16][t][16*s + 4*(lane/16) + 0..3] (zero
+// beyond the real input channels; taps = 9 for 3x3 and 1 for 1x1 filters).  The input-gradient copy describes
+// the transposed convolution: roles of CI and CO swap and the taps are flipped,
+// value j = w[16*s + 4*(lane/16) + j][taps - 1 - t][16*ob + lane%16].
 
 template <typename T>
 __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ params, typename Tile<T>::quad* __restrict__ packed,
@@ -499,19 +366,20 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
     const int r16 = lane & 15, grp = lane >> 4;
     const float* w = params + e.w_off;
     f32x4 v;
+    const int taps = e.taps;
     if (!e.dgrad) {
         const int S = e.c_in >> 4;
-        const int s = (int)(r % S), t = (int)((r / S) % 9), ob = (int)(r / (S * 9));
+        const int s = (int)(r % S), t = (int)((r / S) % taps), ob = (int)(r / (S * taps));
         const int o = ob * 16 + r16, i0 = 16 * s + 4 * grp;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (i0 + j < e.c_in_real) ? w[((int64_t)o * 9 + t) * e.c_in_real + i0 + j] : 0.f;
+        for (int j = 0; j < 4; ++j) v[j] = (i0 + j < e.c_in_real) ? w[((int64_t)o * taps + t) * e.c_in_real + i0 + j] : 0.f;
     } else {
         // transposed convolution: its input channels are the layer's outputs, its outputs the layer's inputs
         const int S = e.c_out >> 4;
-        const int s = (int)(r % S), t = (int)((r / S) % 9), ob = (int)(r / (S * 9));
+        const int s = (int)(r % S), t = (int)((r / S) % taps), ob = (int)(r / (S * taps));
         const int o = ob * 16 + r16, i0 = 16 * s + 4 * grp;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = w[((int64_t)(i0 + j) * 9 + (8 - t)) * e.c_in_real + o];
+        for (int j = 0; j < 4; ++j) v[j] = w[((int64_t)(i0 + j) * taps + (taps - 1 - t)) * e.c_in_real + o];
     }
     Act<T>::store4(reinterpret_cast<T*>(packed + i), v);
 }
@@ -555,16 +423,16 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 // (order-independent, hence reproducible).  All layer shapes run the same code; the grid has
 // groups * (C_out/16) * (C_in/16) workgroups.
 
-#define WG_BLOCK_FLOATS (16 * 9 * 16)
+#define WG_BLOCK_FLOATS (16 * 9 * 16)   // one 16x16 channel block of a 3x3 filter; a 1x1 filter has 16 * 16
 #define WGRAD_REPLICAS 8
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40: |dW| < 2^23, resolution 2^-40
 
 #define WGRAD_THREADS 256
 
-template <typename T>
+template <typename T, int TAPS>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
-                                                              int NI, int NO) {
+                                                              int NI, int NO, int replicas) {
     extern __shared__ f32x4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
     // pixel pitch 16 floats: the four lane groups of a read (4 consecutive pixels x 16 channels) cover the
@@ -580,9 +448,10 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
     float* lds_x = lds;
     float* lds_dy = lds + (size_t)g.imgs * g.in_rows * g.lw * CP;
 
-    f32x4 acc[9];
+    constexpr int BLOCK_FLOATS = 16 * TAPS * 16;
+    f32x4 acc[TAPS];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < TAPS; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int tile_begin = blockIdx.x * tiles_per_group;
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
@@ -610,8 +479,8 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
                     const float a = dr[qc * 4 * DP];
                     const float* xq = xr + qc * 4 * g.stride * CP;
 #pragma unroll
-                    for (int t = 0; t < 9; ++t) {
-                        const float b = xq[((t / 3) * g.lw + (t % 3)) * CP];
+                    for (int t = 0; t < TAPS; ++t) {
+                        const float b = xq[TAPS == 9 ? ((t / 3) * g.lw + (t % 3)) * CP : 0];
                         acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[t], 0, 0, 0);
                     }
                 }
@@ -622,8 +491,8 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
                 const float a = lds_dy[q * DP + r16];
                 const int xb = pixel_lds_base<16, 0>(g, q) + r16;
 #pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const float b = lds_x[xb + ((t / 3) * g.lw + (t % 3)) * CP];
+                for (int t = 0; t < TAPS; ++t) {
+                    const float b = lds_x[xb + (TAPS == 9 ? ((t / 3) * g.lw + (t % 3)) * CP : 0)];
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[t], 0, 0, 0);
                 }
             }
@@ -633,14 +502,14 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
     // holds dW[o = 4*(lane/16) + j][t][i = lane%16] of the block: conflict-free writes, coalesced stores.
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+    for (int t = 0; t < TAPS; ++t)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) lds[wave * WG_BLOCK_FLOATS + (t * 4 + j) * 64 + lane] = acc[t][j];
+        for (int j = 0; j < 4; ++j) lds[wave * BLOCK_FLOATS + (t * 4 + j) * 64 + lane] = acc[t][j];
     __syncthreads();
     // order-independent accumulation across pixel groups: replicated 64-bit fixed point, integer atomic add
-    fixsum_t* out = gacc + ((int64_t)(blockIdx.x % WGRAD_REPLICAS) * gridDim.y + blockIdx.y) * WG_BLOCK_FLOATS;
-    for (int e = threadIdx.x; e < WG_BLOCK_FLOATS; e += WGRAD_THREADS) {
-        const float v = ((lds[e] + lds[WG_BLOCK_FLOATS + e]) + lds[2 * WG_BLOCK_FLOATS + e]) + lds[3 * WG_BLOCK_FLOATS + e];
+    fixsum_t* out = gacc + ((int64_t)(blockIdx.x % replicas) * gridDim.y + blockIdx.y) * BLOCK_FLOATS;
+    for (int e = threadIdx.x; e < BLOCK_FLOATS; e += WGRAD_THREADS) {
+        const float v = ((lds[e] + lds[BLOCK_FLOATS + e]) + lds[2 * BLOCK_FLOATS + e]) + lds[3 * BLOCK_FLOATS + e];
         atomicAdd(out + e, (fixsum_t)__double2ll_rn((double)v * FIX_WGRAD_SCALE));
     }
 }
@@ -648,7 +517,8 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
 // End of a local step, one launch: for every parameter take the gradient, apply the SGD update
 // (g += wd*x; buf = mu*buf + g; x -= lr*buf), and for convolution weights also write the new value into the
 // packed copies that the next forward and input-gradient kernels read.  The gradient of a convolution weight
-// dw[16*ob + o][t][16*ib + i] is the sum over the replicas of accumulator (ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i],
+// dw[16*ob + o][t][16*ib + i] is the sum over the replicas of accumulator (ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i]
+// (blocks of 16 * taps * 16 values),
 // converted back to float; the accumulators are cleared for the next step.  All other gradients come from grad[].
 // The kernel also clears the batch-norm accumulators of the next step.
 template <typename T>
@@ -670,16 +540,16 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
             const int r = (int)(i - e.w_off);
             const int ot = r / e.c_in_real;
             ci = r - ot * e.c_in_real;
-            co = ot / 9;
-            t = ot - co * 9;
+            co = ot / e.taps;
+            t = ot - co * e.taps;
             const int NI = e.c_in, o = co & 15;
             const int blocks = (e.c_out >> 4) * (NI >> 4);
-            const int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * WG_BLOCK_FLOATS + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
-            const int64_t pitch = (int64_t)blocks * WG_BLOCK_FLOATS;
+            const int block_floats = 16 * e.taps * 16;
+            const int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * block_floats + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
+            const int64_t pitch = (int64_t)blocks * block_floats;
             fixsum_t* acc_l = gacc + e.acc_off;
             long long acc = 0;
-#pragma unroll
-            for (int rep = 0; rep < WGRAD_REPLICAS; ++rep) {
+            for (int rep = 0; rep < e.replicas; ++rep) {
                 acc += (long long)acc_l[rep * pitch + src];
                 acc_l[rep * pitch + src] = 0ull;
             }
@@ -700,13 +570,13 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
             else xs = f32_to_bf16(xn);
             {   // forward form: quad ((ob*9 + t)*S + s)*64 + lane holds w[16*ob + lane%16][t][16*s + 4*(lane/16) + 0..3]
                 const int S = e.c_in >> 4;
-                const int64_t quad = e.fwd_quad + ((int64_t)((co >> 4) * 9 + t) * S + (ci >> 4)) * 64 + (co & 15) + 16 * ((ci & 15) >> 2);
+                const int64_t quad = e.fwd_quad + ((int64_t)((co >> 4) * e.taps + t) * S + (ci >> 4)) * 64 + (co & 15) + 16 * ((ci & 15) >> 2);
                 packed[quad * 4 + (ci & 3)] = xs;
             }
             if (e.dgrad_quad >= 0) {
                 // transposed, flipped form: roles of input and output channels swap
                 const int S = e.c_out >> 4;
-                const int64_t quad = e.dgrad_quad + ((int64_t)((ci >> 4) * 9 + (8 - t)) * S + (co >> 4)) * 64 + (ci & 15) + 16 * ((co & 15) >> 2);
+                const int64_t quad = e.dgrad_quad + ((int64_t)((ci >> 4) * e.taps + (e.taps - 1 - t)) * S + (co >> 4)) * 64 + (ci & 15) + 16 * ((co & 15) >> 2);
                 packed[quad * 4 + (co & 3)] = xs;
             }
         }
@@ -728,7 +598,7 @@ static ConvGeom wgrad_geom(const ConvShape& cs) {
     int rows = 256 / h_out;
     if (rows < 4) rows = 4;
     for (;;) {
-        ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows);
+        ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows, cs.taps == 9 ? 1 : 0);
         if ((size_t)g.imgs * g.in_rows * g.lw * 16 * sizeof(float) <= 40960 || rows * h_out <= 32) return g;
         rows >>= 1;
     }
@@ -737,26 +607,36 @@ static ConvGeom wgrad_geom(const ConvShape& cs) {
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
     int cap = 512 / blocks;
+    if (cap < 1) cap = 1;
     return n_tiles < cap ? n_tiles : cap;
 }
 
-int64_t conv_wgrad_accumulators(const ConvShape& cs) { return (int64_t)WGRAD_REPLICAS * cs.c_out * 9 * cs.c_in; }
+// Accumulator replicas of a layer: as many as there are pixel groups, at most WGRAD_REPLICAS.
+int conv_wgrad_replicas(const ConvShape& cs) {
+    int groups = wgrad_groups(cs, wgrad_geom(cs).n_tiles);
+    return groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS;
+}
 
-template <typename T>
+int64_t conv_wgrad_accumulators(const ConvShape& cs) { return (int64_t)conv_wgrad_replicas(cs) * cs.c_out * cs.taps * cs.c_in; }
+
+template <typename T, int TAPS>
 static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, const T* dy, fixsum_t* gacc, const KernelTiming* kt) {
     ConvGeom g = wgrad_geom(cs);
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
-    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (lds < 4 * WG_BLOCK_FLOATS * sizeof(float)) lds = 4 * WG_BLOCK_FLOATS * sizeof(float);
+    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<T, TAPS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds < 4 * 16 * TAPS * 16 * sizeof(float)) lds = 4 * 16 * TAPS * 16 * sizeof(float);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipExtLaunchKernelGGL(wgrad_kernel<T>, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
-                          kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out);
+    hipExtLaunchKernelGGL((wgrad_kernel<T, TAPS>), dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
+                          kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out, groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS);
 }
 
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt) {
-    ACT_DISPATCH(act, launch_conv_wgrad_t<T>(s, cs, (const T*)x, (const T*)dy, gacc, kt));
+    ACT_DISPATCH(act, {
+        if (cs.taps == 9) launch_conv_wgrad_t<T, 9>(s, cs, (const T*)x, (const T*)dy, gacc, kt);
+        else launch_conv_wgrad_t<T, 1>(s, cs, (const T*)x, (const T*)dy, gacc, kt);
+    });
 }
 

@@ -2,7 +2,7 @@
 // wavefront per sample with shuffle reductions; and the head's weight gradient.
 #include "act.h"
 
-#define HEAD_MAX_C 64
+#define HEAD_MAX_C 128   // two classes per lane
 #define HEAD_MAX_F_PER_LANE 16
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -46,8 +46,8 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ 
         f[i] = acc * inv_pos;
         if (feat && c < F) feat[(int64_t)b * F + c] = f[i];
     }
-    // logits: every lane ends up with all C values (C <= 64), kept by lane c in z_mine
-    float z_mine = -INFINITY;
+    // logits: lane l keeps those of classes l and l + 64
+    float z_mine[2] = {-INFINITY, -INFINITY};
     for (int c = 0; c < C; ++c) {
         float part = 0.f;
 #pragma unroll
@@ -56,26 +56,33 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ 
             if (k < F) part = __fmaf_rn(f[i], W[(int64_t)c * F + k], part);
         }
         float z = wave_sum(part) + bias[c];
-        if (lane == c) z_mine = z;
+        if (lane == (c & 63)) z_mine[c >> 6] = z;
     }
-    float m = z_mine;
+    float m = fmaxf(z_mine[0], z_mine[1]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    float e = lane < C ? expf(z_mine - m) : 0.f;
-    float sum = wave_sum(e);
+    float ex[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) ex[h] = lane + 64 * h < C ? expf(z_mine[h] - m) : 0.f;
+    float sum = wave_sum(ex[0]) + wave_sum(ex[1]);
     const int label = y[b];
-    float z_label = __shfl(z_mine, label, 64);
+    float z_label = __shfl(label < 64 ? z_mine[0] : z_mine[1], label & 63, 64);
     if (lane == 0) loss[b] = (m + logf(sum)) - z_label;
     if (!dlogits) return;
-    float dz = lane < C ? (e / sum - (lane == label ? 1.f : 0.f)) * grad_scale : 0.f;
-    if (lane < C) dlogits[(int64_t)b * C + lane] = dz;
+    float dz[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int c = lane + 64 * h;
+        dz[h] = c < C ? (ex[h] / sum - (c == label ? 1.f : 0.f)) * grad_scale : 0.f;
+        if (c < C) dlogits[(int64_t)b * C + c] = dz[h];
+    }
     if (!dfeat) return;
 #pragma unroll
     for (int i = 0; i < per_lane; ++i) {
         int k = lane + 64 * i;
         float acc = 0.f;
         for (int c = 0; c < C; ++c) {
-            float d = __shfl(dz, c, 64);
+            float d = __shfl(c < 64 ? dz[0] : dz[1], c & 63, 64);
             if (k < F) acc = __fmaf_rn(d, W[(int64_t)c * F + k], acc);
         }
         if (k < F) {

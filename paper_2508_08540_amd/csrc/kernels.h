@@ -74,7 +74,7 @@ void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, i
 // Where the normalisation statistics of bn_apply come from.  Training: `sums` holds the fixed-point
 // (sum, sum of squares) of y over `count` values; every workgroup derives mean and invstd from them, and
 // workgroup 0 also stores them into mean/invstd and moves the running statistics.  Inference: sums == nullptr
-// and mean/invstd are read.
+// and the running statistics are used.  At most 512 channels.
 struct BnStats {
     const fixsum_t* sums;
     double count;
@@ -89,21 +89,23 @@ void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int 
 void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                           int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums);
 // dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M) with g = dout * (out > 0) and (dbeta, dgamma) read from `sums`;
-// workgroup 0 stores dgamma and dbeta; g_out (optional) receives g.
+// workgroup 0 stores dgamma and dbeta; g_out (optional) receives g; `add` (optional, shape of dy) is added to dy.
 void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out);
+                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add = nullptr);
 // ---- conv.hip ---------------------------------------------------------------------------------------
 struct ConvShape {
     int B, h_in, c_in, c_out, stride;  // square maps; 3x3, padding 1; c_in, c_out in {16, 32, 64}
     int c_in_real;                     // weights hold this many input channels (<= c_in); the rest are zero
+    int taps = 9;                      // 9: 3x3 filter with padding 1; 1: 1x1 filter (weight-gradient and wide kernels only)
 };
 // Packed (lane-major) weight copies for the convolution kernels; see pack_weights_kernel.
-#define PACK_MAX_ENTRIES 80
+#define PACK_MAX_ENTRIES 72
 struct PackEntry {
     int64_t w_off;     // offset of w[c_out][3][3][c_in_real] in the parameter vector
     int64_t pack_off;  // offset of this entry in the packed buffer, in quads (4 values of the storage type)
     int c_in, c_out, c_in_real, dgrad;
+    int taps, pad_;    // 9 (3x3) or 1 (1x1)
 };
 struct PackTable {
     int n;
@@ -138,6 +140,7 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 // Adds dy (x) shifted x over all pixels into gacc: [replica][c_out/16][c_in/16][2304] fixed-point accumulators
 // (conv_wgrad_accumulators entries, zero before the call) ...
 int64_t conv_wgrad_accumulators(const ConvShape& cs);
+int conv_wgrad_replicas(const ConvShape& cs);
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt = nullptr);
 // End of a local step in one launch (see update_kernel): gradient of every parameter (convolution weights from the
@@ -149,7 +152,8 @@ struct UpdateEntry {
     int64_t acc_off;      // this layer's accumulators in gacc
     int64_t fwd_quad;     // quad offset of the forward packed copy
     int64_t dgrad_quad;   // quad offset of the input-gradient packed copy, -1 if the layer has none
-    int c_in, c_out, c_in_real, pad_;
+    int c_in, c_out, c_in_real, taps;
+    int replicas, pad_;   // accumulator replicas of this layer (conv_wgrad_replicas)
 };
 struct UpdateTable {
     int n;
@@ -157,3 +161,13 @@ struct UpdateTable {
 };
 void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
                    float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums);
+
+// ---- wconv.hip --------------------------------------------------------------------------------------
+// Convolution for wide layers: y = conv(x, w) [+ add] with a 3x3 (taps 9, padding 1) or 1x1 (taps 1) filter;
+// c_in is 16 or a multiple of 32, c_out a multiple of 16; `w` is the packed copy (forward form, or input-gradient
+// form when the call computes an input gradient: then c_in / c_out are the layer's output / input channels,
+// stride is 1 and ups = 1 reads x with zeros inserted, which undoes a stride-2 layer).  With `sums` the
+// (sum, sum of squares) of the stored values are added into [replica][2][c_out] accumulators scaled by `scale`.
+// Returns 0, or -1 for a shape the kernel does not cover (nothing is launched).
+int launch_wconv(hipStream_t s, int act, int taps, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const void* x,
+                 const void* w, void* y, const void* add, fixsum_t* sums, double scale);

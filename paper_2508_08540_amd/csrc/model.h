@@ -24,6 +24,23 @@ struct ConvBn {
     int64_t rmean_off, rvar_off;  // in buffers
 };
 
+// Pieces of the pre-activation wide residual network.
+struct BnSlot {
+    int c;
+    int64_t gamma_off, beta_off;   // in params
+    int64_t rmean_off, rvar_off;   // in buffers
+};
+struct ConvSlot {
+    int c_in, c_out, stride, taps;  // taps 9: 3x3 with padding 1; 1: 1x1
+    int h_in, h_out;
+    int64_t w_off;                  // weight [c_out, k, k, c_in] in params
+};
+struct WrnBlock {
+    BnSlot bn1, bn2;
+    ConvSlot conv1, conv2, shortcut;  // shortcut is used only when proj
+    bool proj;
+};
+
 struct bls_model {
     bls_model_desc desc;
     int64_t num_params = 0;
@@ -36,4 +53,8 @@ struct bls_model {
     std::vector<ConvBn> layers;
     int64_t fc_w = 0, fc_b = 0;
     int final_c = 0, final_hw = 0;
+    // wide residual network: stem convolution, blocks, batch norm before the classifier
+    ConvSlot wrn_stem{};
+    std::vector<WrnBlock> wrn_blocks;
+    BnSlot wrn_final_bn{};
 };

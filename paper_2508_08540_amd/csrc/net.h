@@ -9,3 +9,9 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
                    const int32_t* y_pool, int64_t N, const int32_t* sel, int64_t k, int64_t batch, int64_t tau,
                    const bls_sgd& opt, float* step_losses_out);
 void net_release(bls_ctx* ctx);
+// the same two passes for the wide residual network (net_wrn.hip)
+int wrn_score(bls_ctx* ctx, const bls_model* m, const float* params, const float* buffers, const float* x, const int32_t* y, int64_t N,
+              float* losses_out);
+int wrn_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffers, float* momentum, const float* x_pool,
+                   const int32_t* y_pool, int64_t N, const int32_t* sel, int64_t k, int64_t batch, int64_t tau, const bls_sgd& opt,
+                   float* step_losses_out);

@@ -107,6 +107,7 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
             e.c_out = cb.c_out;
             e.c_in_real = cb.c_in;
             e.dgrad = pass;
+            e.taps = 9; e.pad_ = 0;
             (pass == 0 ? s.fwd_off : s.dgrad_off)[l] = vec4 * 4 * (int64_t)esz;
             vec4 += (int64_t)e.c_in * e.c_out * 9 / 4;
         }
@@ -127,7 +128,8 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
             ue.w_off = cb.w_off; ue.n = (int64_t)cs.c_out * 9 * cs.c_in_real; ue.acc_off = max_wpart;
             ue.fwd_quad = s.fwd_off[l] / (4 * (int64_t)esz);
             ue.dgrad_quad = (train && l > 0) ? s.dgrad_off[l] / (4 * (int64_t)esz) : -1;
-            ue.c_in = cs.c_in; ue.c_out = cs.c_out; ue.c_in_real = cs.c_in_real; ue.pad_ = 0;
+            ue.c_in = cs.c_in; ue.c_out = cs.c_out; ue.c_in_real = cs.c_in_real; ue.taps = 9;
+            ue.replicas = conv_wgrad_replicas(cs); ue.pad_ = 0;
             max_wpart += conv_wgrad_accumulators(cs);
         }
         s.mean[l] = c.take<float>(cb.c_out);

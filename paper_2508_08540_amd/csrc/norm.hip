@@ -1,23 +1,24 @@
 // Batch normalisation around the convolutions: statistics finalisation, normalise + ReLU (+ shortcut),
 // and the backward pass (two reductions and one elementwise pass).  Activations are [pixels][C] with
-// C a multiple of 16, so every thread works on 4 consecutive channels (16 bytes in fp32, 8 in bf16).
+// C a multiple of 16 (at most BN_MAX_C), so every thread works on 4 consecutive channels (16 bytes in fp32, 8 in bf16).
 // All kernels are templates on the storage type of the activations; arithmetic is fp32.
 #include "act.h"
 
 #define BN_EPS 1e-5
 #define BN_MOMENTUM 0.1
+#define BN_MAX_C 512
 
 // out = relu(gamma*(y-mean)*invstd + beta + shortcut(res)).  In training the statistics come from the
 // fixed-point sums: threads 0..C-1 of every workgroup turn them into mean and invstd (double), workgroup 0
-// also stores them and moves the running statistics (momentum 0.1, unbiased variance).
+// also stores them and moves the running statistics (momentum 0.1, unbiased variance).  In inference (no sums) the
+// running statistics are used.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, int64_t pixels, int C, BnStats st,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const T* __restrict__ res, int c_res, int res_stride, int h_out,
                                                        T* __restrict__ out) {
-    __shared__ float s_mean[64], s_invstd[64];
-    if ((int)threadIdx.x < C) {
-        const int c = threadIdx.x;
+    __shared__ float s_mean[BN_MAX_C], s_invstd[BN_MAX_C];
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
         if (st.sums) {
             const double s1 = (double)fixsum_read(st.sums, C, 0, c) * (1.0 / FIX_FWD_SCALE);
             const double s2 = (double)fixsum_read(st.sums, C, 1, c) * (1.0 / FIX_FWD_SCALE);
@@ -34,8 +35,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
                 st.running_var[c] = (float)((1.0 - BN_MOMENTUM) * (double)st.running_var[c] + BN_MOMENTUM * unbiased);
             }
         } else {
-            s_mean[c] = st.mean[c];
-            s_invstd[c] = st.invstd[c];
+            s_mean[c] = st.running_mean[c];
+            s_invstd[c] = (float)(1.0 / sqrt((double)st.running_var[c] + BN_EPS));
         }
     }
     __syncthreads();
@@ -105,8 +106,8 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
                                                             int64_t pixels, int C, const float* __restrict__ mean,
                                                             const float* __restrict__ invstd, fixsum_t* __restrict__ sums) {
     __shared__ float red[2][256][4];
-    const int cq = C >> 2;              // threads per pixel
-    const int lanes_p = 256 / cq;       // pixels in flight per block
+    const int cq = C >> 2;              // threads per pixel (C <= BN_MAX_C: at most 128)
+    const int lanes_p = 256 / cq;       // pixels in flight per block; threads beyond lanes_p * cq idle
     const int cg = threadIdx.x % cq, pl = threadIdx.x / cq;
     const int c = cg << 2;
     int64_t chunk = (pixels + gridDim.x - 1) / gridDim.x;
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
     f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
     f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
     f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sgx = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t p = p0 + pl; p < p1; p += lanes_p) {
+    for (int64_t p = p0 + pl; p < p1 && pl < lanes_p; p += lanes_p) {
         f32x4 d = load_dout<T>(dout, shared, p, C, c);
         f32x4 o = Act<T>::load4(out + p * C + c);
         f32x4 v = Act<T>::load4(y + p * C + c);
@@ -131,9 +132,9 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
         red[1][threadIdx.x][j] = sgx[j];
     }
     __syncthreads();
-    // thread t < 2*C sums column (which, channel) over the pixel lanes in a fixed order
-    if (threadIdx.x < 2 * C) {
-        int which = threadIdx.x / C, ch = threadIdx.x % C;
+    // column (which, channel) is summed over the pixel lanes in a fixed order
+    for (int t = threadIdx.x; t < 2 * C; t += blockDim.x) {
+        int which = t / C, ch = t % C;
         float acc = 0.f;
         for (int l = 0; l < lanes_p; ++l) acc += red[which][l * cq + (ch >> 2)][ch & 3];
         atomicAdd(sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * C + ch, (fixsum_t)__double2ll_rn((double)acc * FIX_BWD_SCALE));
@@ -154,10 +155,9 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
                                                            const float* __restrict__ invstd, const float* __restrict__ gamma,
                                                            const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
                                                            float* __restrict__ dbeta, float inv_count, T* __restrict__ dy,
-                                                           T* __restrict__ g_out) {
-    __shared__ float s_dg[64], s_db[64];
-    if ((int)threadIdx.x < C) {
-        const int c = threadIdx.x;
+                                                           T* __restrict__ g_out, const T* __restrict__ add) {
+    __shared__ float s_dg[BN_MAX_C], s_db[BN_MAX_C];
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
         s_db[c] = (float)((double)fixsum_read(sums, C, 0, c) * (1.0 / FIX_BWD_SCALE));
         s_dg[c] = (float)((double)fixsum_read(sums, C, 1, c) * (1.0 / FIX_BWD_SCALE));
         if (blockIdx.x == 0) {
@@ -186,6 +186,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
             gq[j] = g;
             r[j] = ga[j] * is[j] * (g - s_db[c + j] * inv_count - xhat * (s_dg[c + j] * inv_count));
         }
+        if (add) r += Act<T>::load4(add + p * C + c);  // gradient arriving through an identity shortcut
         Act<T>::store4(dy + p * C + c, r);
         if (g_out) Act<T>::store4(g_out + p * C + c, gq);
     }
@@ -193,12 +194,12 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
 
 void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out) {
+                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     ACT_DISPATCH(act, hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, dout,
                                          dout_positions_shared, (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums,
-                                         dgamma, dbeta, 1.f / (float)pixels, (T*)dy, (T*)g_out));
+                                         dgamma, dbeta, 1.f / (float)pixels, (T*)dy, (T*)g_out, (const T*)add));
 }
 

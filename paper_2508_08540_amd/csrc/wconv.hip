@@ -1,0 +1,169 @@
+// Convolutions of wide layers (up to 512 channels): 3x3 (padding 1) and 1x1, stride 1 or 2, forward and input
+// gradient, as implicit GEMMs on the matrix cores.
+//
+// A workgroup owns a tile of 128 or 256 output pixels (whole rows, several images when maps are small) and a
+// group of 64 output channels, one block of 16 per wavefront.  The input channels are consumed in chunks of
+// CK = 16 or 32: the chunk of the input tile is staged with its zero halo into LDS as [row][col][CK + 4], the
+// wave loads the weights of its 16 output channels for this chunk and all taps into registers from the
+// lane-major packed copy, and the accumulators of all 8 or 16 pixel blocks of the tile stay in registers across
+// the chunks (A = weights, B = pixels, as in the narrow kernel: lane group g supplies channels 16s + 4g .. +3).
+// So a weight register feeds 8-16 MFMAs and a staged pixel is reused by 4 waves and all taps.  The epilogue
+// optionally adds a tensor of the output's shape (residual branch / second gradient branch) and reduces the
+// batch-norm sums of what it stores.
+#include "conv_tile.h"
+
+struct WEpi {
+    const void* add;   // tensor of the output's shape added before the store, or nullptr
+    fixsum_t* sums;    // [replica][2][c_out] accumulators for (sum, sum of squares) of the stored values, or nullptr
+    double scale;
+};
+
+template <typename T, int TAPS, int CK, int NPT>
+__global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, const void* __restrict__ wpk, T* __restrict__ y, WEpi e,
+                                                    ConvGeom g, int c_in) {
+    typedef typename Tile<T>::quad quad;
+    extern __shared__ f32x4 lds_raw[];
+    quad* lds4 = reinterpret_cast<quad*>(lds_raw);
+    float* lds = reinterpret_cast<float*>(lds_raw);
+    constexpr int S = CK / 16, CPQ = CK / 4 + 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, grp = lane >> 4;
+    const int NO = g.c_out, NOB = NO >> 4;
+    const int ob = blockIdx.y * 4 + wave;
+    const bool active = ob < NOB;  // the last channel group may be partly empty; idle waves still stage and synchronise
+    const int tile = blockIdx.x;
+    const int s_total = c_in >> 4;
+
+    int base[NPT];
+    f32x4 acc[NPT];
+#pragma unroll
+    for (int pt = 0; pt < NPT; ++pt) {
+        base[pt] = pixel_lds_base<CK>(g, pt * 16 + r16) / 4 + grp;  // quad units
+        acc[pt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const quad* wp = reinterpret_cast<const quad*>(wpk) + (int64_t)(active ? ob : 0) * TAPS * s_total * 64 + lane;
+
+    for (int ch = 0; ch < c_in / CK; ++ch) {
+        __syncthreads();  // the previous chunk has been consumed
+        stage_input<T, quad, CK, 256>(lds4, x, g, tile, c_in, ch * CK);
+        quad wr[TAPS][S];
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+            for (int s = 0; s < S; ++s) wr[t][s] = wp[(int64_t)(t * s_total + ch * S + s) * 64];
+        __syncthreads();
+        if (active) {
+#pragma unroll
+            for (int t = 0; t < TAPS; ++t) {
+                const int tap_off = TAPS == 9 ? ((t / 3) * g.lw + (t % 3)) * CPQ : 0;
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+#pragma unroll
+                    for (int pt = 0; pt < NPT; ++pt) {
+                        const quad b = lds4[base[pt] + tap_off + 4 * s];
+                        if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) acc[pt] = __builtin_amdgcn_mfma_f32_16x16x4f32(wr[t][s][j], b[j], acc[pt], 0, 0, 0);
+                        } else {
+                            acc[pt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, wr[t][s]),
+                                                                                __builtin_bit_cast(s16x4, b), acc[pt], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    // epilogue: lane holds channels c0 .. c0+3 of pixel (pt*16 + r16)
+    const int64_t pix0 = (int64_t)tile * (NPT * 16);
+    const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
+    const int c0 = ob * 16 + 4 * grp;
+    const T* add = static_cast<const T*>(e.add);
+    f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
+    if (active) {
+#pragma unroll
+        for (int pt = 0; pt < NPT; ++pt) {
+            const int64_t p = pix0 + pt * 16 + r16;
+            if (p < total_pixels) {
+                f32x4 v = acc[pt];
+                if (add) v += Act<T>::load4(add + p * NO + c0);
+                v = Act<T>::rounded(v);  // the sums see what later kernels read back
+                Act<T>::store4(y + p * NO + c0, v);
+                ssum += v;
+                ssq += v * v;
+            }
+        }
+    }
+    if (e.sums) {
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ssum[j] += __shfl_xor(ssum[j], o, 64);
+                ssq[j] += __shfl_xor(ssq[j], o, 64);
+            }
+        __syncthreads();  // every wave is past its last tile read
+        float* red = lds;  // [wave][2][16]
+        if (r16 == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                red[(wave * 2 + 0) * 16 + 4 * grp + j] = ssum[j];
+                red[(wave * 2 + 1) * 16 + 4 * grp + j] = ssq[j];
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < 128) {
+            const int which = threadIdx.x >> 6, c = threadIdx.x & 63;  // channel c of this group: wave c/16 holds it
+            const int ch = blockIdx.y * 64 + c;
+            if (ch < NO)
+                atomicAdd(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + ch,
+                          (fixsum_t)__double2ll_rn((double)red[((c >> 4) * 2 + which) * 16 + (c & 15)] * e.scale));
+        }
+    }
+}
+
+// Tile: 256 pixels when the staged chunk fits 64 KB (two workgroups per compute unit), else 128.
+template <typename T, int TAPS, int CK>
+static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const T* x, const void* w,
+                          T* y, const WEpi& e) {
+    const int pad = TAPS == 9 ? 1 : 0;
+    auto geom = [&](int npt) { return make_geom(B, h_in, h_out, c_out, stride, ups, c_in, (npt * 16) / h_out, pad); };
+    if (h_out > 128) return -1;
+    ConvGeom g = geom(16);
+    int npt = 16;
+    size_t lds = input_lds_bytes<T, CK>(g);
+    if (lds > 65536 || 256 / h_out < 1) {
+        g = geom(8);
+        npt = 8;
+        lds = input_lds_bytes<T, CK>(g);
+    }
+    if (lds > 160 * 1024 - 2048 || (npt * 16) / h_out < 1) return -1;
+    if (lds < 1024) lds = 1024;
+    dim3 grid(g.n_tiles, (c_out / 16 + 3) / 4);
+    if (npt == 16) {
+        auto kern = wconv_kernel<T, TAPS, CK, 16>;
+        if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, x, w, y, e, g, c_in);
+    } else {
+        auto kern = wconv_kernel<T, TAPS, CK, 8>;
+        if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, x, w, y, e, g, c_in);
+    }
+    return 0;
+}
+
+// c_in is 16 or a multiple of 32, c_out a multiple of 16, maps are squares with power-of-two sides.
+// Returns 0, or -1 when the shape is outside what the kernel is built for (nothing is launched then).
+int launch_wconv(hipStream_t s, int act, int taps, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const void* x,
+                 const void* w, void* y, const void* add, fixsum_t* sums, double scale) {
+    if (!(c_in == 16 || c_in % 32 == 0) || c_out % 16 != 0 || (taps != 9 && taps != 1)) return -1;
+    WEpi e{add, sums, scale};
+    int rc = -1;
+    ACT_DISPATCH(act, {
+        if (taps == 9) rc = c_in == 16 ? launch_wconv_t<T, 9, 16>(s, B, h_in, h_out, c_in, c_out, stride, ups, (const T*)x, w, (T*)y, e)
+                                       : launch_wconv_t<T, 9, 32>(s, B, h_in, h_out, c_in, c_out, stride, ups, (const T*)x, w, (T*)y, e);
+        else rc = c_in == 16 ? launch_wconv_t<T, 1, 16>(s, B, h_in, h_out, c_in, c_out, stride, ups, (const T*)x, w, (T*)y, e)
+                             : launch_wconv_t<T, 1, 32>(s, B, h_in, h_out, c_in, c_out, stride, ups, (const T*)x, w, (T*)y, e);
+    });
+    return rc;
+}

@@ -1,0 +1,124 @@
+"""GPU parity of score_losses / local_step for the pre-activation wide residual network."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_helpers import Harness, assert_grads_match_up_to_relu_ties, assert_losses_close, assert_tensors_close, rel_err
+
+pytestmark = pytest.mark.gpu
+CFG = synth.workload("wrn16_8_bf16")
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    yield torch, bls, ctx
+    ctx.close()
+
+
+def _harness(env, widths, blocks, hw, classes, stem, act="f32"):
+    torch, bls, ctx = env
+    storage = oracle.round_bf16 if act == "bf16" else None
+    return Harness(torch, bls, ctx, bls.Model.wide_resnet(widths, blocks, classes, hw, 3, stem, act),
+                   oracle.WideResNet(widths, blocks, stem, storage=storage))
+
+
+def _zeros(p):
+    return {k: np.zeros_like(v) for k, v in p.items()}
+
+
+def _case(widths, blocks, hw, batch, classes, stem, stream=0):
+    p, b = synth.wrn_init(CFG["id"], widths, blocks, classes, stem, perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], batch + 3, classes, hw=hw, stream=stream)
+    sel = (np.arange(batch) * 2) % (batch + 3)
+    return p, b, x, y, sel
+
+
+def test_layout_matches_the_generator(env):
+    torch, bls, ctx = env
+    m = bls.Model.wide_resnet()
+    ps, bs = synth.wrn_tensor_specs()
+    assert m.num_params == 11007540 and m.num_buffers == 7200
+    assert [(t["name"], t["shape"]) for t in m.tensors if not t["is_buffer"]] == [(n, tuple(s)) for n, s in ps]
+    assert [(t["name"], t["shape"]) for t in m.tensors if t["is_buffer"]] == [(n, tuple(s)) for n, s in bs]
+
+
+@pytest.mark.parametrize("widths,blocks,hw,batch,classes,stem", [
+    ((32, 32, 64), 1, 8, 4, 10, 16),        # every first block projects (16 -> 32, stride 2 twice)
+    ((32, 64, 96), 2, 16, 3, 7, 16),        # identity blocks, three input chunks, odd class count
+    ((32, 32, 32), 2, 8, 5, 100, 32),       # identity first block, 100 classes (two per lane in the head)
+    ((64, 128, 160), 1, 32, 2, 10, 16),     # 32x32 maps: 256-pixel tiles of 8 rows
+    ((128, 256, 512), 1, 8, 2, 10, 16),     # the real widths: up to 16 input chunks and 8 output-channel groups
+])
+def test_fp32_gradients_and_scores(env, widths, blocks, hw, batch, classes, stem):
+    h = _harness(env, widths, blocks, hw, classes, stem)
+    p, b, x, y, sel = _case(widths, blocks, hw, batch, classes, stem)
+    assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y))
+    probe = oracle.GradientProbe(h.oracle_model, p, b, x[sel], y[sel])
+    newp, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], probe.losses)
+    assert_grads_match_up_to_relu_ties(probe, mom, 1e-4)
+    assert_tensors_close(gb, probe.new_buffers, 1e-5, "running statistics")
+
+
+def test_fp32_steps_follow_the_oracle(env):
+    widths, blocks, hw, classes, stem = (32, 64, 64), 1, 8, 10, 16
+    h = _harness(env, widths, blocks, hw, classes, stem)
+    p, b = synth.wrn_init(CFG["id"], widths, blocks, classes, stem, perturb_bn=0.1)
+    x, y = synth.image_pool(CFG["id"], 30, classes, hw=hw)
+    sel = oracle.topk_by_loss(oracle.score_losses(h.oracle_model, p, b, x, y).astype(np.float32), 10)
+    B, tau, lr, mu, wd = 4, 3, 0.05, 0.9, 1e-4
+    rp, rb, rm, rl = oracle.local_step(h.oracle_model, p, b, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    gp, gb, gm, gl = h.local_step(p, b, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    assert_losses_close(gl, rl, rtol=1e-3)
+    assert_tensors_close(gb, rb, 1e-4, "running statistics")
+    assert_tensors_close(gm, rm, 2e-3, "momentum after tau steps")
+    assert_tensors_close({k: gp[k] - p[k] for k in p}, {k: rp[k] - p[k] for k in p}, 2e-3, "parameter change after tau steps")
+    # repeatable bit for bit
+    gp2, gb2, gm2, gl2 = h.local_step(p, b, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    for k in gp:
+        np.testing.assert_array_equal(gp[k], gp2[k])
+    np.testing.assert_array_equal(gl, gl2)
+
+
+def test_bf16_small_nets(env):
+    """As for the narrow network: flip-free seeds agree tightly, the others stay inside the rounding-flip envelope."""
+    tight, runs = 0, 0
+    for widths, blocks, hw, batch, stem in [((32, 32, 64), 1, 8, 3, 16), ((32, 64, 64), 2, 8, 2, 16)]:
+        h = _harness(env, widths, blocks, hw, 10, stem, "bf16")
+        for stream in range(4):
+            p, b, x, y, sel = _case(widths, blocks, hw, batch, 10, stem, stream)
+            assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y), rtol=5e-3)
+            losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+            _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+            worst = max(rel_err(mom[k], grads[k]) for k in grads)
+            runs += 1
+            if worst <= 1e-4:
+                tight += 1
+                assert_losses_close(sl[0], losses)
+                assert_tensors_close(gb, new_b, 1e-5, "running statistics")
+            else:
+                assert_losses_close(sl[0], losses, rtol=2e-2)
+                assert_tensors_close(gb, new_b, 5e-3, "running statistics")
+                assert worst < 0.6, worst
+    assert tight >= 1, (tight, runs)
+
+
+def test_wrn16_8_bf16_one_small_batch(env):
+    """The real network (11 M parameters) on 6 images: scores and training losses against the bf16 oracle,
+    gradients against the float64 oracle at the accuracy the bf16 oracle itself has."""
+    h = _harness(env, (128, 256, 512), 2, 32, 100, 16, "bf16")
+    p, b = synth.wrn_init(CFG["id"], perturb_bn=0.1)
+    x, y = synth.image_pool(CFG["id"], 6, 100)
+    sel = np.arange(6)
+    assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y), rtol=1e-2)
+    losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x, y)
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, 6, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses, rtol=2e-2)
+    assert_tensors_close(gb, new_b, 5e-3, "running statistics")
+    _, g64, _ = oracle.loss_and_grads(oracle.WideResNet(), p, b, x, y)
+    for k in grads:
+        assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
