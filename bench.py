@@ -5,7 +5,8 @@ pool, select the 128 highest-loss samples, run 20 local SGD steps of batch 128 o
 10 parameter replicas with step-count weights.  Prints one JSON line.
 
 --workload resnet20_bf16 measures the mixed-precision variant instead (bf16 activations, fp32 master
-weights, pool 4096, k 1024, 50 local steps); the default line stays the fp32 workload.
+weights, pool 4096, k 1024, 50 local steps) and --workload wrn16_8_bf16 the wide residual network
+(pool 2048, k 512, 4 local steps, 100 classes); the default line stays the fp32 workload.
 """
 import argparse
 import json
@@ -40,13 +41,28 @@ def resnet_conv_flops(widths, blocks, hw, in_ch):
     return total
 
 
+def wrn_conv_flops(widths, blocks, hw, in_ch, stem):
+    """(all convolutions, all but the stem): forward multiply-add flops for one image, 1x1 shortcuts included."""
+    first = 2 * 9 * in_ch * stem * hw * hw
+    total, c_prev, h = first, stem, hw
+    for s, c in enumerate(widths):
+        for b in range(blocks):
+            stride = 2 if (b == 0 and s > 0) else 1
+            h_out = h // stride
+            total += 2 * 9 * c_prev * c * h_out * h_out + 2 * 9 * c * c * h_out * h_out
+            if c_prev != c or stride != 1:
+                total += 2 * c_prev * c * h_out * h_out
+            h, c_prev = h_out, c
+    return total, total - first
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16"])
+    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16", "wrn16_8_bf16"])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -66,9 +82,14 @@ def main():
     cfg = synth.workload(args.workload)
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
     act_dtype = cfg.get("act_dtype", "f32")
-    model = bls.Model.resnet_cifar(act_dtype=act_dtype)
+    wide = cfg["model"] == "wrn16_8"
+    if wide:
+        model = bls.Model.wide_resnet(act_dtype=act_dtype)
+        p, b = synth.wrn_init(cfg["id"])
+    else:
+        model = bls.Model.resnet_cifar(act_dtype=act_dtype)
+        p, b = synth.resnet_init(cfg["id"])
     d = model.num_params
-    p, b = synth.resnet_init(cfg["id"])
     x, y = synth.image_pool(cfg["id"], N, cfg["classes"])
     flat = model.pack(p)
     ctx = bls.Context(0)
@@ -109,9 +130,13 @@ def main():
         one_step()
     prof = ctx.profile_end()
     phases = {name: round(ms / args.steps, 4) for name, (ms, cnt) in prof.items() if cnt}
-    conv_flops_img = resnet_conv_flops((16, 32, 64), 3, 32, 3)
     # forward flops of one local step / one scoring pass; the input gradient skips the stem
-    stem_flops = 2 * 9 * 3 * 16 * 32 * 32
+    if wide:
+        conv_flops_img, no_stem = wrn_conv_flops((128, 256, 512), 2, 32, 3, 16)
+        stem_flops = conv_flops_img - no_stem
+    else:
+        conv_flops_img = resnet_conv_flops((16, 32, 64), 3, 32, 3)
+        stem_flops = 2 * 9 * 3 * 16 * 32 * 32
     flops = {
         "conv_fwd": conv_flops_img * (tau * B + N),
         "conv_dgrad": (conv_flops_img - stem_flops) * tau * B,
@@ -122,6 +147,8 @@ def main():
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
     symbol = {"conv_fwd": "conv_kernel (forward launches)", "conv_dgrad": "conv_kernel (input-gradient launches)",
               "conv_wgrad": "wgrad_kernel"}[dom]
+    if wide and dom != "conv_wgrad":
+        symbol = symbol.replace("conv_kernel", "wconv_kernel")
     # forward and input-gradient convolutions run on the matrix instruction of the storage type; the weight
     # gradient always multiplies in fp32
     peak = BF16_MFMA_PEAK_TFLOPS if (act_dtype == "bf16" and dom != "conv_wgrad") else FP32_MFMA_PEAK_TFLOPS
@@ -155,7 +182,7 @@ def main():
     del big
 
     line = {
-        "metric": "selected samples/s per local step (ResNet20)", "value": round(value, 1), "unit": "samples/s",
+        "metric": "selected samples/s per local step (%s)" % ("WRN-16-8" if wide else "ResNet20"), "value": round(value, 1), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": act_dtype, "data": "synthetic",
         "config": {"workload": args.workload, "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(d)},
@@ -240,21 +267,24 @@ def cpu_baseline(cfg, p, b, x, y):
     import synth
     from threadpoolctl import threadpool_info
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
-    m = oracle.ResNetCifar(storage=oracle.round_bf16 if cfg.get("act_dtype") == "bf16" else None)
-    n_score = 64
+    storage = oracle.round_bf16 if cfg.get("act_dtype") == "bf16" else None
+    wide = cfg["model"] == "wrn16_8"
+    m = oracle.WideResNet(storage=storage) if wide else oracle.ResNetCifar(storage=storage)
+    n_score = 16 if wide else 64
+    b_step = 8 if wide else B        # the wide network's step is timed on a smaller batch and scaled per sample
     t = time.perf_counter()
     ls = oracle.score_losses(m, p, b, x[:n_score], y[:n_score])
     t_score_img = (time.perf_counter() - t) / n_score
-    full = np.concatenate([ls, ls[::-1]] * (N // (2 * n_score))).astype(np.float32)
+    full = np.resize(np.concatenate([ls, ls[::-1]]), N).astype(np.float32)
     t = time.perf_counter()
     sel = oracle.topk_by_loss(full, k)
     t_topk = time.perf_counter() - t
     zeros = {n: np.zeros_like(v) for n, v in p.items()}
     t = time.perf_counter()
-    oracle.local_step(m, p, b, zeros, x, y, sel, B, 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
-    t_step = time.perf_counter() - t
+    oracle.local_step(m, p, b, zeros, x, y, sel, b_step, 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+    t_step = (time.perf_counter() - t) * (B / b_step)
     import paper_2508_08540_amd as bls
-    flat = bls.Model.resnet_cifar().pack(p)
+    flat = (bls.Model.wide_resnet() if wide else bls.Model.resnet_cifar()).pack(p)
     reps = synth.replicas(flat, P, cfg["id"])
     t = time.perf_counter()
     oracle.weighted_aggregate(reps, synth.aggregation_weights(cfg))
@@ -262,8 +292,9 @@ def cpu_baseline(cfg, p, b, x, y):
     total = N * t_score_img + t_topk + tau * t_step + t_agg
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     return {"value": round(tau * B / total, 2), "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": "scored %d of %d pool images, full top-k, 1 of %d local steps at batch %d, full aggregation; "
-                      "per-part times scaled to the whole pass" % (n_score, N, tau, B),
+            "sample": "scored %d of %d pool images, full top-k, 1 of %d local steps at batch %d%s, full aggregation; "
+                      "per-part times scaled to the whole pass" % (n_score, N, tau, b_step,
+                                                                   " (scaled to batch %d)" % B if b_step != B else ""),
             "host_cpus": os.cpu_count()}
 
 

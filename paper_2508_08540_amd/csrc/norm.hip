@@ -12,13 +12,18 @@
 // fixed-point sums: threads 0..C-1 of every workgroup turn them into mean and invstd (double), workgroup 0
 // also stores them and moves the running statistics (momentum 0.1, unbiased variance).  In inference (no sums) the
 // running statistics are used.
-template <typename T>
+// MAXC: 64 (narrow layers: thread c handles channel c, the form the compiler schedules best: a loop there, even
+// with one trip, costs microseconds per launch) or BN_MAX_C (the per-channel prologue loops over 256-channel passes).
+template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, int64_t pixels, int C, BnStats st,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const T* __restrict__ res, int c_res, int res_stride, int h_out,
                                                        T* __restrict__ out) {
-    __shared__ float s_mean[BN_MAX_C], s_invstd[BN_MAX_C];
-    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    constexpr bool WIDE = MAXC > 64;
+    __shared__ float s_mean[MAXC], s_invstd[MAXC];
+    for (int c0 = 0; c0 < (WIDE ? C : 1); c0 += 256) {
+        const int c = c0 + (int)threadIdx.x;
+        if (c >= C) continue;
         if (st.sums) {
             const double s1 = (double)fixsum_read(st.sums, C, 0, c) * (1.0 / FIX_FWD_SCALE);
             const double s2 = (double)fixsum_read(st.sums, C, 1, c) * (1.0 / FIX_FWD_SCALE);
@@ -78,8 +83,14 @@ void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int 
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    ACT_DISPATCH(act, hipLaunchKernelGGL(bn_apply_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st,
-                                         gamma, beta, (const T*)res, c_res, res_stride, h_out, (T*)out));
+    ACT_DISPATCH(act, {
+        if (C > 64)
+            hipLaunchKernelGGL((bn_apply_kernel<T, BN_MAX_C>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
+                               (const T*)res, c_res, res_stride, h_out, (T*)out);
+        else
+            hipLaunchKernelGGL((bn_apply_kernel<T, 64>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
+                               (const T*)res, c_res, res_stride, h_out, (T*)out);
+    });
 }
 
 // ---- backward -------------------------------------------------------------------------------------
@@ -100,7 +111,7 @@ __device__ __forceinline__ f32x4 load_dout(const void* __restrict__ dout, int sh
 }
 
 // adds (sum g, sum g*xhat), g = dout * (out > 0), into the fixed-point accumulators sums[2][C]
-template <typename T>
+template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restrict__ dout, int shared,
                                                             const T* __restrict__ out, const T* __restrict__ y,
                                                             int64_t pixels, int C, const float* __restrict__ mean,
@@ -133,7 +144,9 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
     }
     __syncthreads();
     // column (which, channel) is summed over the pixel lanes in a fixed order
-    for (int t = threadIdx.x; t < 2 * C; t += blockDim.x) {
+    for (int t0 = 0; t0 < (WIDE ? 2 * C : 1); t0 += 256) {
+        const int t = t0 + (int)threadIdx.x;
+        if (t >= 2 * C) continue;
         int which = t / C, ch = t % C;
         float acc = 0.f;
         for (int l = 0; l < lanes_p; ++l) acc += red[which][l * cq + (ch >> 2)][ch & 3];
@@ -144,11 +157,17 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
 void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                           int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums) {
     int n = bn_bwd_partials(pixels);
-    ACT_DISPATCH(act, hipLaunchKernelGGL(bn_bwd_reduce_kernel<T>, dim3(n), dim3(256), 0, s, dout, dout_positions_shared,
-                                         (const T*)out, (const T*)y, pixels, C, mean, invstd, sums));
+    ACT_DISPATCH(act, {
+        if (2 * C > 256)
+            hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, true>), dim3(n), dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
+                               (const T*)y, pixels, C, mean, invstd, sums);
+        else
+            hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, false>), dim3(n), dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
+                               (const T*)y, pixels, C, mean, invstd, sums);
+    });
 }
 
-template <typename T>
+template <typename T, int MAXC, bool HAS_ADD>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restrict__ dout, int shared,
                                                            const T* __restrict__ out, const T* __restrict__ y,
                                                            int64_t pixels, int C, const float* __restrict__ mean,
@@ -156,14 +175,20 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
                                                            const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
                                                            float* __restrict__ dbeta, float inv_count, T* __restrict__ dy,
                                                            T* __restrict__ g_out, const T* __restrict__ add) {
-    __shared__ float s_dg[BN_MAX_C], s_db[BN_MAX_C];
-    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+    constexpr bool WIDE = MAXC > 64;
+    __shared__ float s_dg[MAXC], s_db[MAXC];
+    auto channel_sums = [&](int c) {
         s_db[c] = (float)((double)fixsum_read(sums, C, 0, c) * (1.0 / FIX_BWD_SCALE));
         s_dg[c] = (float)((double)fixsum_read(sums, C, 1, c) * (1.0 / FIX_BWD_SCALE));
         if (blockIdx.x == 0) {
             dbeta[c] = s_db[c];
             dgamma[c] = s_dg[c];
         }
+    };
+    if constexpr (WIDE) {
+        for (int c = threadIdx.x; c < C; c += 256) channel_sums(c);
+    } else {
+        if ((int)threadIdx.x < C) channel_sums(threadIdx.x);
     }
     __syncthreads();
     const int cq = C >> 2;
@@ -186,7 +211,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
             gq[j] = g;
             r[j] = ga[j] * is[j] * (g - s_db[c + j] * inv_count - xhat * (s_dg[c + j] * inv_count));
         }
-        if (add) r += Act<T>::load4(add + p * C + c);  // gradient arriving through an identity shortcut
+        if (HAS_ADD) r += Act<T>::load4(add + p * C + c);  // gradient arriving through an identity shortcut
         Act<T>::store4(dy + p * C + c, r);
         if (g_out) Act<T>::store4(g_out + p * C + c, gq);
     }
@@ -198,8 +223,17 @@ void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_posi
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    ACT_DISPATCH(act, hipLaunchKernelGGL(bn_bwd_apply_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, dout,
-                                         dout_positions_shared, (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums,
-                                         dgamma, dbeta, 1.f / (float)pixels, (T*)dy, (T*)g_out, (const T*)add));
+#define BN_BWD_APPLY(MAXC, HAS_ADD)                                                                                                   \
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MAXC, HAS_ADD>), dim3((unsigned)blocks), dim3(256), 0, s, dout, dout_positions_shared,   \
+                       (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums, dgamma, dbeta, 1.f / (float)pixels, (T*)dy,  \
+                       (T*)g_out, (const T*)add)
+    ACT_DISPATCH(act, {
+        if (C > 64 || add) {
+            if (add) BN_BWD_APPLY(BN_MAX_C, true);
+            else BN_BWD_APPLY(BN_MAX_C, false);
+        } else {
+            BN_BWD_APPLY(64, false);
+        }
+    });
+#undef BN_BWD_APPLY
 }
-
