@@ -611,13 +611,20 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     return n_tiles < cap ? n_tiles : cap;
 }
 
+// wgrad16.hip: the bf16 matrix-instruction kernel for wide stride-1 layers
+bool wgrad16_covers(int act, const ConvShape& cs);
+int wgrad16_groups(const ConvShape& cs);
+void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas);
+
 // Accumulator replicas of a layer: as many as there are pixel groups, at most WGRAD_REPLICAS.
-int conv_wgrad_replicas(const ConvShape& cs) {
-    int groups = wgrad_groups(cs, wgrad_geom(cs).n_tiles);
+int conv_wgrad_replicas(int act, const ConvShape& cs) {
+    int groups = wgrad16_covers(act, cs) ? wgrad16_groups(cs) : wgrad_groups(cs, wgrad_geom(cs).n_tiles);
     return groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS;
 }
 
-int64_t conv_wgrad_accumulators(const ConvShape& cs) { return (int64_t)conv_wgrad_replicas(cs) * cs.c_out * cs.taps * cs.c_in; }
+int64_t conv_wgrad_accumulators(int act, const ConvShape& cs) {
+    return (int64_t)conv_wgrad_replicas(act, cs) * cs.c_out * cs.taps * cs.c_in;
+}
 
 template <typename T, int TAPS>
 static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, const T* dy, fixsum_t* gacc, const KernelTiming* kt) {
@@ -634,6 +641,10 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
 
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt) {
+    if (wgrad16_covers(act, cs)) {
+        launch_wgrad16(s, cs, x, dy, gacc, conv_wgrad_replicas(act, cs));
+        return;
+    }
     ACT_DISPATCH(act, {
         if (cs.taps == 9) launch_conv_wgrad_t<T, 9>(s, cs, (const T*)x, (const T*)dy, gacc, kt);
         else launch_conv_wgrad_t<T, 1>(s, cs, (const T*)x, (const T*)dy, gacc, kt);

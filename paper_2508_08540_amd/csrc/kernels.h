@@ -139,8 +139,8 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
                        const KernelTiming* kt = nullptr);
 // Adds dy (x) shifted x over all pixels into gacc: [replica][c_out/16][c_in/16][2304] fixed-point accumulators
 // (conv_wgrad_accumulators entries, zero before the call) ...
-int64_t conv_wgrad_accumulators(const ConvShape& cs);
-int conv_wgrad_replicas(const ConvShape& cs);
+int64_t conv_wgrad_accumulators(int act, const ConvShape& cs);
+int conv_wgrad_replicas(int act, const ConvShape& cs);
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt = nullptr);
 // End of a local step in one launch (see update_kernel): gradient of every parameter (convolution weights from the

@@ -129,8 +129,8 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
             ue.fwd_quad = s.fwd_off[l] / (4 * (int64_t)esz);
             ue.dgrad_quad = (train && l > 0) ? s.dgrad_off[l] / (4 * (int64_t)esz) : -1;
             ue.c_in = cs.c_in; ue.c_out = cs.c_out; ue.c_in_real = cs.c_in_real; ue.taps = 9;
-            ue.replicas = conv_wgrad_replicas(cs); ue.pad_ = 0;
-            max_wpart += conv_wgrad_accumulators(cs);
+            ue.replicas = conv_wgrad_replicas(s.act, cs); ue.pad_ = 0;
+            max_wpart += conv_wgrad_accumulators(s.act, cs);
         }
         s.mean[l] = c.take<float>(cb.c_out);
         s.invstd[l] = c.take<float>(cb.c_out);

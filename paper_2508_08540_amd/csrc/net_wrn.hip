@@ -98,8 +98,8 @@ WrnScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         ue.fwd_quad = s.convs[i].fwd_off / (4 * (int64_t)esz);
         ue.dgrad_quad = s.convs[i].dgrad_off >= 0 ? s.convs[i].dgrad_off / (4 * (int64_t)esz) : -1;
         ue.c_in = cs.c_in; ue.c_out = cs.c_out; ue.c_in_real = cs.c_in_real; ue.taps = cv.taps;
-        ue.replicas = conv_wgrad_replicas(cs); ue.pad_ = 0;
-        acc += conv_wgrad_accumulators(cs);
+        ue.replicas = conv_wgrad_replicas(s.act, cs); ue.pad_ = 0;
+        acc += conv_wgrad_accumulators(s.act, cs);
     }
     // batch norms
     std::vector<const BnSlot*> bslots;

@@ -1,0 +1,190 @@
+// Weight gradient of wide bf16 layers on the bf16 matrix instruction.
+//
+// dW[o][tap][i] = sum over pixels p of dy[p][o] * x[p + tap][i] contracts over pixels, so both operands of
+// v_mfma_f32_16x16x16_bf16 must supply four *consecutive pixels* of one channel per lane.  Activations are
+// stored pixel-major with channels innermost, therefore the staging transposes 4x4 (pixel x channel) blocks in
+// registers and keeps channel-major planes in LDS: dyT[64 output channels][128 pixels] and
+// xT[64 input channels][rows with halo][row width + 4].  A k-step takes 16 consecutive output pixels; lane
+// group g reads the aligned pixel quad 4g of its channel (A: output channel lane%16 of the wave's block,
+// B: input channel lane%16 of one of four 16-channel blocks).  For a 3x3 filter the horizontal tap shifts the
+// x quad by 0, 1 or 2 pixels: the two aligned quads around it are read once and the shifted operands are cut
+// out with alignbit, so no shifted copies of the tile are needed.
+// Workgroup = (pixel group, 64 output channels, 64 input channels); wave w owns output-channel block w with
+// all four input-channel blocks and all taps (36 accumulators for 3x3).  Waves own distinct 16x16 blocks, so
+// the sums go from registers straight into the replicated 64-bit fixed-point accumulators (same layout and
+// scale as wgrad_kernel: block (ob, ib), element (t*4 + j)*64 + lane).
+// Covers stride 1, channel counts that are multiples of 64; other layers use wgrad_kernel.
+#include "conv_tile.h"
+
+#include <cstdlib>
+
+#define FIX_WGRAD_SCALE 1099511627776.0  // 2^40, as in wgrad_kernel
+#define W16_TILE_PX 128
+
+struct W16Geom {
+    int lwp;   // LDS row width of an xT plane: w_out + 4 (3x3) or w_out (1x1)
+    int xp;    // elements per xT plane (xp / 4 odd: channel rows fall into different banks)
+    int dp;    // elements per dyT row
+};
+
+template <int TAPS>
+__global__ __launch_bounds__(256) void wgrad16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, fixsum_t* __restrict__ gacc,
+                                                      ConvGeom g, W16Geom wg, int tiles_per_group, int NI, int NO, int replicas) {
+    extern __shared__ uint2 lds2[];
+    uint2* xT = lds2;                       // [64][xp / 4] quads
+    uint2* dyT = lds2 + 64 * (wg.xp / 4);   // [64][dp / 4] quads
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r16 = lane & 15, grp = lane >> 4;
+    const int nib = NI >> 6;
+    const int cob = blockIdx.y / nib, cib = blockIdx.y - cob * nib;
+    const int W = g.h_out, pad = g.pad;
+    const int rpi = 1 << g.rpi_log2;
+    const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
+    const int xq = wg.xp >> 2, dq = wg.dp >> 2, lwq = wg.lwp >> 2;
+
+    f32x4 acc[TAPS][4];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[t][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int tile_begin = blockIdx.x * tiles_per_group;
+    const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
+    for (int tile = tile_begin; tile < tile_end; ++tile) {
+        __syncthreads();  // previous tile consumed
+        const int row0 = tile * g.rows_tile;
+        // ---- stage x: task = (4 channels, 4 consecutive padded columns of one staged row) -----------------
+        const int rows_total = g.imgs * g.in_rows;
+        for (int id = threadIdx.x; id < 16 * rows_total * lwq; id += 256) {
+            const int cq = id & 15, rest = id >> 4;
+            const int lr = rest / lwq, pq = rest - lr * lwq;
+            const int part = lr / g.in_rows, li = lr - part * g.in_rows;
+            const int grow = row0 + part * rpi;
+            const int n = grow >> g.wout_log2;
+            const int hi = (grow & (g.h_out - 1)) - pad + li;
+            const bool rok = n < g.B && (unsigned)hi < (unsigned)g.h_in;
+            uint2 r[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int wi = pq * 4 + j - pad;
+                r[j] = make_uint2(0u, 0u);
+                if (rok && (unsigned)wi < (unsigned)W)
+                    r[j] = *reinterpret_cast<const uint2*>(x + (((int64_t)n * g.h_in + hi) * g.h_in + wi) * NI + cib * 64 + cq * 4);
+            }
+            uint2* dst = xT + (cq * 4) * xq + lr * lwq + pq;
+            dst[0 * xq] = make_uint2((r[0].x & 0xffffu) | (r[1].x << 16), (r[2].x & 0xffffu) | (r[3].x << 16));
+            dst[1 * xq] = make_uint2((r[0].x >> 16) | (r[1].x & 0xffff0000u), (r[2].x >> 16) | (r[3].x & 0xffff0000u));
+            dst[2 * xq] = make_uint2((r[0].y & 0xffffu) | (r[1].y << 16), (r[2].y & 0xffffu) | (r[3].y << 16));
+            dst[3 * xq] = make_uint2((r[0].y >> 16) | (r[1].y & 0xffff0000u), (r[2].y >> 16) | (r[3].y & 0xffff0000u));
+        }
+        // ---- stage dy ---------------------------------------------------------------------------------------
+        const int64_t pix0 = (int64_t)tile * W16_TILE_PX;
+        for (int id = threadIdx.x; id < 16 * (W16_TILE_PX / 4); id += 256) {
+            const int cq = id & 15, pq = id >> 4;
+            uint2 r[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t p = pix0 + pq * 4 + j;
+                r[j] = make_uint2(0u, 0u);
+                if (p < total_pixels) r[j] = *reinterpret_cast<const uint2*>(dy + p * NO + cob * 64 + cq * 4);
+            }
+            uint2* dst = dyT + (cq * 4) * dq + pq;
+            dst[0 * dq] = make_uint2((r[0].x & 0xffffu) | (r[1].x << 16), (r[2].x & 0xffffu) | (r[3].x << 16));
+            dst[1 * dq] = make_uint2((r[0].x >> 16) | (r[1].x & 0xffff0000u), (r[2].x >> 16) | (r[3].x & 0xffff0000u));
+            dst[2 * dq] = make_uint2((r[0].y & 0xffffu) | (r[1].y << 16), (r[2].y & 0xffffu) | (r[3].y << 16));
+            dst[3 * dq] = make_uint2((r[0].y >> 16) | (r[1].y & 0xffff0000u), (r[2].y >> 16) | (r[3].y & 0xffff0000u));
+        }
+        __syncthreads();
+        // ---- 8 k-steps of 16 pixels -------------------------------------------------------------------------
+        const uint2* arow = dyT + (wave * 16 + r16) * dq + grp;
+        const uint2* brow = xT + r16 * xq;
+#pragma unroll 1
+        for (int ks = 0; ks < W16_TILE_PX / 16; ++ks) {
+            const s16x4 a = __builtin_bit_cast(s16x4, arow[ks * 4]);
+            const int q = ks * 16 + 4 * grp;                      // first pixel of this lane group's quad inside the tile
+            const int orow = q >> g.wout_log2, ocol = q & (W - 1);
+            const int part = orow >> g.rpi_log2, rr = orow & (rpi - 1);
+            const int xoff = (part * g.in_rows + rr) * lwq + (ocol >> 2);  // quad index of tap (0, 0)
+            if (TAPS == 9) {
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh) {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint2 q0 = brow[b * 16 * xq + xoff + kh * lwq];
+                        const uint2 q1 = brow[b * 16 * xq + xoff + kh * lwq + 1];
+                        // pixels shifted by one and by two columns
+                        const uint2 s1 = make_uint2(__builtin_amdgcn_alignbit(q0.y, q0.x, 16), __builtin_amdgcn_alignbit(q1.x, q0.y, 16));
+                        const uint2 s2 = make_uint2(q0.y, q1.x);
+                        acc[kh * 3 + 0][b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(s16x4, q0), acc[kh * 3 + 0][b], 0, 0, 0);
+                        acc[kh * 3 + 1][b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(s16x4, s1), acc[kh * 3 + 1][b], 0, 0, 0);
+                        acc[kh * 3 + 2][b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(s16x4, s2), acc[kh * 3 + 2][b], 0, 0, 0);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint2 q0 = brow[b * 16 * xq + xoff];
+                    acc[0][b] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(s16x4, q0), acc[0][b], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // accumulators: block (ob, ib) of 16 * TAPS * 16 values, element (t*4 + j)*64 + lane
+    constexpr int BLOCK_FLOATS = 16 * TAPS * 16;
+    const int nblocks = (NO >> 4) * (NI >> 4);
+    fixsum_t* rep = gacc + (int64_t)(blockIdx.x % replicas) * nblocks * BLOCK_FLOATS;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        fixsum_t* out = rep + (int64_t)((cob * 4 + wave) * (NI >> 4) + cib * 4 + b) * BLOCK_FLOATS + lane;
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) atomicAdd(out + (t * 4 + j) * 64, (fixsum_t)__double2ll_rn((double)acc[t][b][j] * FIX_WGRAD_SCALE));
+    }
+}
+
+// BLS_WGRAD_FP32=1 in the environment sends every layer to wgrad_kernel (used by the tests to compare the two kernels
+// on identical operands).
+bool wgrad16_covers(int act, const ConvShape& cs) {
+    const char* off = getenv("BLS_WGRAD_FP32");
+    if (off && off[0] == '1') return false;
+    return act == ACT_BF16 && cs.stride == 1 && cs.c_in % 64 == 0 && cs.c_out % 64 == 0 && cs.c_in_real == cs.c_in && cs.h_in >= 4 &&
+           cs.h_in <= 64;
+}
+
+static ConvGeom wgrad16_geom(const ConvShape& cs) {
+    return make_geom(cs.B, cs.h_in, cs.h_in, cs.c_out, 1, 0, cs.c_in, W16_TILE_PX / cs.h_in, cs.taps == 9 ? 1 : 0);
+}
+
+// Pixel groups: about 256 workgroups in total (each dumps all its sums once, so fewer groups mean fewer atomics)
+int wgrad16_groups(const ConvShape& cs) {
+    const int pairs = (cs.c_in / 64) * (cs.c_out / 64);
+    const int n_tiles = wgrad16_geom(cs).n_tiles;
+    int groups = 256 / pairs;
+    if (groups < 1) groups = 1;
+    return groups < n_tiles ? groups : n_tiles;
+}
+
+void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas) {
+    ConvGeom g = wgrad16_geom(cs);
+    W16Geom wg;
+    wg.lwp = cs.taps == 9 ? cs.h_in + 4 : cs.h_in;
+    int plane = g.imgs * g.in_rows * wg.lwp;
+    plane = (plane + 3) & ~3;
+    if (((plane >> 2) & 1) == 0) plane += 4;
+    wg.xp = plane;
+    wg.dp = W16_TILE_PX + 4;
+    const int groups = wgrad16_groups(cs);
+    const int tiles_per_group = (g.n_tiles + groups - 1) / groups;
+    const size_t lds = (size_t)64 * (wg.xp + wg.dp) * sizeof(bf16_t);
+    dim3 grid(groups, (cs.c_in / 64) * (cs.c_out / 64));
+    if (cs.taps == 9) {
+        if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_kernel<9>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(wgrad16_kernel<9>, grid, dim3(256), lds, s, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg, tiles_per_group, cs.c_in,
+                           cs.c_out, replicas);
+    } else {
+        if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(wgrad16_kernel<1>, grid, dim3(256), lds, s, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg, tiles_per_group, cs.c_in,
+                           cs.c_out, replicas);
+    }
+}
