@@ -3,7 +3,6 @@
 #include "act.h"
 
 #define HEAD_MAX_C 128   // two classes per lane
-#define HEAD_MAX_F_PER_LANE 16
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -11,49 +10,50 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// PER_LANE = ceil(F / 64) is a template parameter so that the feature slice stays in registers.
-__device__ __forceinline__ float act_value(float v) { return v; }
-__device__ __forceinline__ float act_value(bf16_t v) { return bf16_to_f32(v); }
-
-template <int PER_LANE, typename T>
+// Lane l owns the channel quads l, l + 64, ... (channels 4q .. 4q+3): PQ = ceil(F / 256) of them, a template parameter
+// so that the pooled features stay in registers.  Pooling reads 8 or 16 bytes per lane and position; F % 4 == 0.
+template <int PQ, typename T>
 __global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ act, int positions, int F,
                                                           const float* __restrict__ W, const float* __restrict__ bias,
                                                           int C, const int32_t* __restrict__ y, float* __restrict__ loss,
                                                           float* __restrict__ feat, float* __restrict__ dlogits,
                                                           float* __restrict__ dfeat, float grad_scale, int relu_mask) {
     const int b = blockIdx.x, lane = threadIdx.x;
-    constexpr int per_lane = PER_LANE;
-    float f[PER_LANE];
+    f32x4 f[PQ];
     const float inv_pos = 1.f / (float)positions;
     const T* a = act + (int64_t)b * positions * F;
 #pragma unroll
-    for (int i = 0; i < per_lane; ++i) {
-        int c = lane + 64 * i;
-        float acc = 0.f;
+    for (int i = 0; i < PQ; ++i) {
+        const int c = 4 * (lane + 64 * i);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if (c < F) {
             // four independent partial sums keep several loads in flight; they are combined in a fixed order
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            f32x4 s0 = acc, s1 = acc, s2 = acc, s3 = acc;
             int p = 0;
             for (; p + 3 < positions; p += 4) {
-                s0 += act_value(a[(int64_t)p * F + c]);
-                s1 += act_value(a[(int64_t)(p + 1) * F + c]);
-                s2 += act_value(a[(int64_t)(p + 2) * F + c]);
-                s3 += act_value(a[(int64_t)(p + 3) * F + c]);
+                s0 += Act<T>::load4(a + (int64_t)p * F + c);
+                s1 += Act<T>::load4(a + (int64_t)(p + 1) * F + c);
+                s2 += Act<T>::load4(a + (int64_t)(p + 2) * F + c);
+                s3 += Act<T>::load4(a + (int64_t)(p + 3) * F + c);
             }
-            for (; p < positions; ++p) s0 += act_value(a[(int64_t)p * F + c]);
+            for (; p < positions; ++p) s0 += Act<T>::load4(a + (int64_t)p * F + c);
             acc = (s0 + s1) + (s2 + s3);
         }
         f[i] = acc * inv_pos;
-        if (feat && c < F) feat[(int64_t)b * F + c] = f[i];
+        if (feat && c < F) *reinterpret_cast<f32x4*>(feat + (int64_t)b * F + c) = f[i];
     }
     // logits: lane l keeps those of classes l and l + 64
     float z_mine[2] = {-INFINITY, -INFINITY};
     for (int c = 0; c < C; ++c) {
         float part = 0.f;
 #pragma unroll
-        for (int i = 0; i < per_lane; ++i) {
-            int k = lane + 64 * i;
-            if (k < F) part = __fmaf_rn(f[i], W[(int64_t)c * F + k], part);
+        for (int i = 0; i < PQ; ++i) {
+            const int k = 4 * (lane + 64 * i);
+            if (k < F) {
+                const f32x4 w = *reinterpret_cast<const f32x4*>(W + (int64_t)c * F + k);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) part = __fmaf_rn(f[i][j], w[j], part);
+            }
         }
         float z = wave_sum(part) + bias[c];
         if (lane == (c & 63)) z_mine[c >> 6] = z;
@@ -78,17 +78,24 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ 
     }
     if (!dfeat) return;
 #pragma unroll
-    for (int i = 0; i < per_lane; ++i) {
-        int k = lane + 64 * i;
-        float acc = 0.f;
+    for (int i = 0; i < PQ; ++i) {
+        const int k = 4 * (lane + 64 * i);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int c = 0; c < C; ++c) {
-            float d = __shfl(c < 64 ? dz[0] : dz[1], c & 63, 64);
-            if (k < F) acc = __fmaf_rn(d, W[(int64_t)c * F + k], acc);
+            const float d = __shfl(c < 64 ? dz[0] : dz[1], c & 63, 64);
+            if (k < F) {
+                const f32x4 w = *reinterpret_cast<const f32x4*>(W + (int64_t)c * F + k);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = __fmaf_rn(d, w[j], acc[j]);
+            }
         }
         if (k < F) {
             acc *= inv_pos;
-            if (relu_mask && !(f[i] > 0.f)) acc = 0.f;
-            dfeat[(int64_t)b * F + k] = acc;
+            if (relu_mask)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (!(f[i][j] > 0.f)) acc[j] = 0.f;
+            *reinterpret_cast<f32x4*>(dfeat + (int64_t)b * F + k) = acc;
         }
     }
 }
@@ -96,15 +103,13 @@ __global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ 
 void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
                          float grad_scale, bool relu_mask) {
-#define HEAD_LAUNCH(PL)                                                                                                          \
-    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PL, T>), dim3(B), dim3(64), 0, s, (const T*)act, positions, F, W, \
+#define HEAD_LAUNCH(PQ)                                                                                                          \
+    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PQ, T>), dim3(B), dim3(64), 0, s, (const T*)act, positions, F, W, \
                                               bias, C, y, loss, feat, dlogits, dfeat, grad_scale, relu_mask ? 1 : 0))
-    const int per_lane = (F + 63) / 64;
-    if (per_lane <= 1) HEAD_LAUNCH(1);
-    else if (per_lane <= 2) HEAD_LAUNCH(2);
-    else if (per_lane <= 4) HEAD_LAUNCH(4);
-    else if (per_lane <= 8) HEAD_LAUNCH(8);
-    else HEAD_LAUNCH(16);
+    const int quads = (F / 4 + 63) / 64;   // F is a multiple of 16, at most 1024
+    if (quads <= 1) HEAD_LAUNCH(1);
+    else if (quads <= 2) HEAD_LAUNCH(2);
+    else HEAD_LAUNCH(4);
 #undef HEAD_LAUNCH
 }
 
