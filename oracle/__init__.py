@@ -13,6 +13,7 @@ from .selection import topk_by_loss, total_order_key            # noqa: F401
 from .aggregation import weighted_aggregate, weights_from_tau   # noqa: F401
 from .optim import sgd_update                                   # noqa: F401
 from .models import MLP, ResNetCifar, WideResNet                            # noqa: F401
+from .transformer import TransformerLM                          # noqa: F401
 from .precision import round_bf16                               # noqa: F401
 from .sampling import allocation, deal, sample_epoch                 # noqa: F401
 from .local_sgd import score_losses, local_step, loss_and_grads, GradientProbe  # noqa: F401

@@ -14,19 +14,26 @@ from .losses import softmax_cross_entropy
 from .optim import sgd_update
 
 
+def _sample_losses(model, logits, y):
+    """(per-sample loss, d loss_b / d logits): models with several predictions per sample average them themselves."""
+    if hasattr(model, "sample_losses"):
+        return model.sample_losses(logits, y)
+    return softmax_cross_entropy(logits, y)
+
+
 def score_losses(model, params, buffers, x, y, chunk=64):
     """Per-sample loss float64 [N] of every pool item under the current parameters."""
     out = np.empty(x.shape[0], dtype=np.float64)
     for s in range(0, x.shape[0], chunk):
         logits, _, _ = model.forward(params, buffers, x[s:s + chunk], train=False)
-        out[s:s + chunk], _ = softmax_cross_entropy(logits, y[s:s + chunk])
+        out[s:s + chunk], _ = _sample_losses(model, logits, y[s:s + chunk])
     return out
 
 
 def loss_and_grads(model, params, buffers, xb, yb):
     """(per-sample losses [B], grads of the mean batch loss, buffers after the forward pass)."""
     logits, cache, new_bufs = model.forward(params, buffers, xb, train=True)
-    losses, dlogits = softmax_cross_entropy(logits, yb)
+    losses, dlogits = _sample_losses(model, logits, yb)
     grads = model.backward(cache, dlogits / xb.shape[0])
     return losses, grads, new_bufs
 
@@ -41,7 +48,7 @@ class GradientProbe:
 
     def __init__(self, model, params, buffers, xb, yb):
         logits, self.cache, self.new_buffers = model.forward(params, buffers, xb, train=True)
-        self.losses, dlogits = softmax_cross_entropy(logits, yb)
+        self.losses, dlogits = _sample_losses(model, logits, yb)
         self.dlogits = dlogits / xb.shape[0]
         self.model = model
 

@@ -26,6 +26,9 @@ WORKLOADS = {
     # wide residual network WRN-16-8, bf16 activations / fp32 master weights, 100 classes
     "wrn16_8_bf16": dict(id=3, model="wrn16_8", act_dtype="bf16", pool=2048, classes=100, k=512, batch=128, tau=4,
                          lr=0.1, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
+    # encoder language model: 6 layers, d 512, 8 heads, FFN 2048, vocabulary 32000, sequences of 128 tokens
+    "transformer": dict(id=4, model="transformer", pool=1024, classes=32000, seq_len=128, k=256, batch=64, tau=4, lr=0.001,
+                        momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
 }
 
 
@@ -196,6 +199,51 @@ def wrn_init(workload_id, widths=(128, 256, 512), blocks=2, classes=100, stem=16
         else:
             buffers[name] = (1.0 + perturb_bn * rng.uniform01(seed, stream, n)).astype(np.float32)
     return params, buffers
+
+
+def transformer_tensor_specs(vocab=32000, seq_len=128, d_model=512, d_ff=2048, layers=6):
+    """[(name, shape)] of the encoder language model's parameters, in flat-vector order (no buffers)."""
+    specs = [("tok_emb.weight", (vocab, d_model)), ("pos_emb.weight", (seq_len, d_model))]
+    for l in range(layers):
+        n = "l%d." % l
+        for a in ("q", "k", "v", "o"):
+            specs += [(n + "attn.%s.weight" % a, (d_model, d_model)), (n + "attn.%s.bias" % a, (d_model,))]
+        specs += [(n + "ln1.weight", (d_model,)), (n + "ln1.bias", (d_model,)),
+                  (n + "ffn.fc1.weight", (d_ff, d_model)), (n + "ffn.fc1.bias", (d_ff,)),
+                  (n + "ffn.fc2.weight", (d_model, d_ff)), (n + "ffn.fc2.bias", (d_model,)),
+                  (n + "ln2.weight", (d_model,)), (n + "ln2.bias", (d_model,))]
+    specs.append(("head.weight", (vocab, d_model)))
+    return specs
+
+
+def transformer_init(workload_id, vocab=32000, seq_len=128, d_model=512, d_ff=2048, layers=6, perturb=0.0):
+    """Parameters dict: embeddings N(0, 0.02), linear weights uniform +-1/sqrt(fan_in) with biases alike,
+    layer-norm scale 1 / shift 0 (moved by `perturb` in tests)."""
+    seed = _seed(workload_id)
+    out = {}
+    for t, (name, shape) in enumerate(transformer_tensor_specs(vocab, seq_len, d_model, d_ff, layers)):
+        n = int(np.prod(shape))
+        stream = 20000 + 4 * t
+        if name.endswith("emb.weight"):
+            out[name] = (0.02 * rng.normal(seed, stream, n)).reshape(shape).astype(np.float32)
+        elif ".ln" in name:
+            base = 1.0 if name.endswith("weight") else 0.0
+            out[name] = (base + perturb * (2.0 * rng.uniform01(seed, stream, n) - 1.0)).astype(np.float32)
+        else:
+            fan_in = shape[1] if len(shape) == 2 else {"fc2": d_ff}.get(name.split(".")[-2], d_model)
+            out[name] = ((2.0 * rng.uniform01(seed, stream, n) - 1.0) / np.sqrt(fan_in)).reshape(shape).astype(np.float32)
+    return out
+
+
+def token_pool(workload_id, n, seq_len=128, vocab=32000, zipf_s=1.1, stream=0):
+    """(inputs int32 [n, seq_len], targets int32 [n, seq_len]): token ranks drawn from a Zipf(s) law truncated to the
+    vocabulary by inverse CDF, id = rank - 1; seq_len + 1 tokens per sequence, the target of a position is the next token."""
+    seed = _seed(workload_id)
+    w = 1.0 / np.arange(1, vocab + 1, dtype=np.float64) ** zipf_s
+    cdf = np.cumsum(w) / w.sum()
+    u = rng.uniform01(seed, 400 + stream, n * (seq_len + 1))
+    ids = np.minimum(np.searchsorted(cdf, u, side="left"), vocab - 1).astype(np.int32).reshape(n, seq_len + 1)
+    return np.ascontiguousarray(ids[:, :-1]), np.ascontiguousarray(ids[:, 1:])
 
 
 def replicas(base, P, workload_id, scale=0.01):
