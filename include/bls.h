@@ -44,7 +44,7 @@ typedef enum {
 typedef struct bls_ctx bls_ctx;     /* device, stream (borrowed) and library-owned scratch */
 typedef struct bls_model bls_model; /* architecture and flat-parameter layout (host only)  */
 
-enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1, BLS_MODEL_WRN = 2 };
+enum { BLS_MODEL_MLP = 0, BLS_MODEL_RESNET_CIFAR = 1, BLS_MODEL_WRN = 2, BLS_MODEL_ENCODER = 3 };
 
 /* Storage type of the activations (and of the copies of the convolution weights the kernels read).
  * Parameters, momentum, gradients, batch-norm statistics, losses and every reduction stay fp32: with
@@ -64,7 +64,17 @@ enum { BLS_ACT_F32 = 0, BLS_ACT_BF16 = 1 };
  *                  keeps its shape and a 1x1 convolution of relu(bn1(x)) otherwise; batch norm, ReLU, global
  *                  average pooling, linear classifier.  WRN-16-8 is hidden 16, widths 128/256/512, blocks 2,
  *                  image_hw 32, classes 100.  Tensor order: stem.conv; per block bn1, conv1, bn2, conv2,
- *                  [shortcut]; final.bn; fc. */
+ *                  [shortcut]; final.bn; fc.
+ *   ENCODER:       transformer encoder language model standing in for the language workload of Section 5: token and
+ *                  learned position embeddings, `blocks` post-layer-norm layers  h = LN1(h + MHA(h)),
+ *                  h = LN2(h + W2 gelu(W1 h + b1) + b2)  with unmasked self-attention, erf GELU, layer-norm eps 1e-5,
+ *                  and a bias-free projection to the vocabulary.  A sample is one sequence; its loss is the mean of
+ *                  its per-position cross-entropies (Section 4.3 ranks one loss per sample).
+ *                  classes = vocabulary size (2 .. 2^20), image_hw = sequence length (1 .. 1024), hidden = model
+ *                  width (multiple of 4, at most 1024), widths[0] = heads (divides hidden), widths[1] = feed-forward
+ *                  width (multiple of 4), blocks = layers (1 .. 16); in_channels and widths[2] are ignored; fp32 only.
+ *                  Tensor order: tok_emb, pos_emb; per layer attn.q/k/v/o (weight, bias), ln1, ffn.fc1, ffn.fc2,
+ *                  ln2; head.weight. */
 typedef struct {
     int32_t kind;        /* BLS_MODEL_*                                    */
     int32_t classes;     /* 2 .. 64 (WRN: 2 .. 128)                        */
@@ -141,11 +151,12 @@ int bls_model_tensor_layout(const bls_model* model, bls_tensor_info* out, int32_
 /* Loss of every candidate under the current parameters (Section 4.2).
  *   params   device float[d]; buffers device float[num_buffers] (may be NULL for the MLP)
  *   x        device float[N, H, W, C] (channels last); y device int32[N], labels in [0, classes)
- *   losses_out device float[N]: softmax cross-entropy of sample i, natural logarithm
+ *            ENCODER: x device int32[N, L] token ids, y device int32[N, L] target ids, both in [0, classes)
+ *   losses_out device float[N]: softmax cross-entropy of sample i, natural logarithm (ENCODER: mean over positions)
  * Batch-norm layers use their running statistics, so a score does not depend on the rest of the
  * pool.  N == 0 is a no-op.  Labels are not range-checked on the device. */
 int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, const float* buffers,
-                 const float* x, const int32_t* y, int64_t N, float* losses_out);
+                 const void* x, const int32_t* y, int64_t N, float* losses_out);
 
 /* Indices of the k largest losses in rank order (Section 4.2; deterministic).
  *   losses device float[N]; idx_out device int32[k]; val_out device float[k] or NULL
@@ -164,7 +175,7 @@ int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_
  * Requires 1 <= k, 1 <= batch; tau == 0 is a no-op.  A zero momentum vector before the first step
  * gives buf = g there.  Indices are not range-checked on the device. */
 int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffers, float* momentum,
-               const float* x_pool, const int32_t* y_pool, int64_t N, const int32_t* sel_idx, int64_t k,
+               const void* x_pool, const int32_t* y_pool, int64_t N, const int32_t* sel_idx, int64_t k,
                int64_t batch, int64_t tau, const bls_sgd* opt, float* step_losses_out);
 
 /* out[j] = sum_i w_i * replicas[i][j], i ascending, in fp32 (Eq. 4).

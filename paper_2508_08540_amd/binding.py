@@ -6,7 +6,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
-MODEL_MLP, MODEL_RESNET_CIFAR, MODEL_WRN = 0, 1, 2
+MODEL_MLP, MODEL_RESNET_CIFAR, MODEL_WRN, MODEL_ENCODER = 0, 1, 2, 3
 ACT_DTYPES = {"f32": 0, "bf16": 1}
 AGG_NORMALISE, AGG_BROADCAST = 1, 2
 
@@ -171,6 +171,11 @@ class Model:
     def wide_resnet(cls, widths=(128, 256, 512), blocks=2, classes=100, image_hw=32, in_channels=3, stem=16, act_dtype="f32"):
         """Pre-activation wide residual network; the defaults are WRN-16-8."""
         return cls(MODEL_WRN, classes, image_hw, in_channels, stem, widths, blocks, act_dtype)
+
+    @classmethod
+    def transformer(cls, vocab=32000, seq_len=128, d_model=512, heads=8, d_ff=2048, layers=6):
+        """Post-layer-norm transformer encoder language model; samples are int32 token sequences [N, seq_len]."""
+        return cls(MODEL_ENCODER, vocab, seq_len, 0, d_model, (heads, d_ff, 0), layers, "f32")
 
     def pack(self, tensors, buffers=False):
         """dict name -> array  =>  flat float32 numpy vector in the library's layout."""

@@ -157,9 +157,10 @@ static void add_conv_bn(bls_model* m, const std::string& conv, const std::string
 int bls_model_create(const bls_model_desc* desc, bls_model** out) {
     if (!desc || !out) return BLS_EINVAL;
     *out = nullptr;
-    if (desc->classes < 2 || desc->classes > (desc->kind == BLS_MODEL_WRN ? 128 : 64)) return BLS_EINVAL;
+    const int max_classes = desc->kind == BLS_MODEL_ENCODER ? (1 << 20) : desc->kind == BLS_MODEL_WRN ? 128 : 64;
+    if (desc->classes < 2 || desc->classes > max_classes) return BLS_EINVAL;
     if (desc->act_dtype != BLS_ACT_F32 && desc->act_dtype != BLS_ACT_BF16) return BLS_EINVAL;
-    if (desc->kind == BLS_MODEL_MLP && desc->act_dtype != BLS_ACT_F32) return BLS_EUNSUPPORTED;
+    if ((desc->kind == BLS_MODEL_MLP || desc->kind == BLS_MODEL_ENCODER) && desc->act_dtype != BLS_ACT_F32) return BLS_EUNSUPPORTED;
     // a convolution's input width must be 16 or a multiple of 32 in the wide network
     auto wide_ok = [](int c) { return c == 16 || (c >= 32 && c <= 512 && c % 32 == 0); };
     bls_model* m = new (std::nothrow) bls_model();
@@ -261,6 +262,38 @@ int bls_model_create(const bls_model_desc* desc, bls_model** out) {
         m->final_hw = hw;
         m->fc_w = m->num_params; add_tensor(m, "fc.weight", false, 2, desc->classes, c_prev);
         m->fc_b = m->num_params; add_tensor(m, "fc.bias", false, 1, desc->classes);
+    } else if (desc->kind == BLS_MODEL_ENCODER) {
+        const int V = desc->classes, L = desc->image_hw, D = desc->hidden, H = desc->widths[0], F = desc->widths[1];
+        if (L < 1 || L > 1024 || D < 4 || D > 1024 || D % 4 != 0 || H < 1 || D % H != 0 || F < 4 || F % 4 != 0 || F > 8192 ||
+            desc->blocks < 1 || desc->blocks > 16) {
+            delete m;
+            return BLS_EINVAL;
+        }
+        m->enc_V = V; m->enc_L = L; m->enc_D = D; m->enc_H = H; m->enc_F = F;
+        m->enc_tok = m->num_params; add_tensor(m, "tok_emb.weight", false, 2, V, D);
+        m->enc_pos = m->num_params; add_tensor(m, "pos_emb.weight", false, 2, L, D);
+        for (int l = 0; l < desc->blocks; ++l) {
+            char pn[16];
+            snprintf(pn, sizeof pn, "l%d.", l);
+            const std::string p(pn);
+            EncLayer e;
+            auto lin = [&](const std::string& name, int out_f, int in_f, int64_t& w, int64_t& b) {
+                w = m->num_params; add_tensor(m, p + name + ".weight", false, 2, out_f, in_f);
+                b = m->num_params; add_tensor(m, p + name + ".bias", false, 1, out_f);
+            };
+            lin("attn.q", D, D, e.wq, e.bq);
+            lin("attn.k", D, D, e.wk, e.bk);
+            lin("attn.v", D, D, e.wv, e.bv);
+            lin("attn.o", D, D, e.wo, e.bo);
+            e.ln1_g = m->num_params; add_tensor(m, p + "ln1.weight", false, 1, D);
+            e.ln1_b = m->num_params; add_tensor(m, p + "ln1.bias", false, 1, D);
+            lin("ffn.fc1", F, D, e.w1, e.b1);
+            lin("ffn.fc2", D, F, e.w2, e.b2);
+            e.ln2_g = m->num_params; add_tensor(m, p + "ln2.weight", false, 1, D);
+            e.ln2_b = m->num_params; add_tensor(m, p + "ln2.bias", false, 1, D);
+            m->enc_layers.push_back(e);
+        }
+        m->enc_head = m->num_params; add_tensor(m, "head.weight", false, 2, V, D);
     } else {
         delete m;
         return BLS_EINVAL;
@@ -291,15 +324,17 @@ int bls_model_tensor_layout(const bls_model* model, bls_tensor_info* out, int32_
 
 // ---- operations -----------------------------------------------------------------------------------
 
-int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, const float* buffers, const float* x,
+int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, const float* buffers, const void* x_any,
                  const int32_t* y, int64_t N, float* losses_out) {
     if (!ctx) return BLS_EINVAL;
     if (!model || N < 0) return bls_fail(ctx, BLS_EINVAL, "score_losses: model is NULL or N < 0");
     if (N == 0) return BLS_OK;
-    if (!params || !x || !y || !losses_out) return bls_fail(ctx, BLS_EINVAL, "score_losses: NULL pointer");
+    if (!params || !x_any || !y || !losses_out) return bls_fail(ctx, BLS_EINVAL, "score_losses: NULL pointer");
     if (model->num_buffers > 0 && !buffers) return bls_fail(ctx, BLS_EINVAL, "score_losses: this model needs buffers");
     if (N >= (int64_t(1) << 31)) return bls_fail(ctx, BLS_EINVAL, "score_losses: N must be below 2^31");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
+    if (model->desc.kind == BLS_MODEL_ENCODER) return seq_score(ctx, model, params, static_cast<const int32_t*>(x_any), y, N, losses_out);
+    const float* x = static_cast<const float*>(x_any);
     if (model->desc.kind == BLS_MODEL_WRN) return wrn_score(ctx, model, params, buffers, x, y, N, losses_out);
     return net_score(ctx, model, params, buffers, x, y, N, losses_out);
 }
@@ -316,7 +351,7 @@ int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_
 }
 
 int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffers, float* momentum,
-               const float* x_pool, const int32_t* y_pool, int64_t N, const int32_t* sel_idx, int64_t k, int64_t batch,
+               const void* x_any, const int32_t* y_pool, int64_t N, const int32_t* sel_idx, int64_t k, int64_t batch,
                int64_t tau, const bls_sgd* opt, float* step_losses_out) {
     if (!ctx) return BLS_EINVAL;
     if (!model || !opt) return bls_fail(ctx, BLS_EINVAL, "local_step: model or opt is NULL");
@@ -325,11 +360,15 @@ int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffe
     if (!(isfinite(opt->lr) && isfinite(opt->momentum) && isfinite(opt->weight_decay)))
         return bls_fail(ctx, BLS_EINVAL, "local_step: non-finite optimiser setting");
     if (tau == 0) return BLS_OK;
-    if (!params || !momentum || !x_pool || !y_pool || !sel_idx) return bls_fail(ctx, BLS_EINVAL, "local_step: NULL pointer");
+    if (!params || !momentum || !x_any || !y_pool || !sel_idx) return bls_fail(ctx, BLS_EINVAL, "local_step: NULL pointer");
     if (model->num_buffers > 0 && !buffers) return bls_fail(ctx, BLS_EINVAL, "local_step: this model needs buffers");
-    if (model->desc.kind != BLS_MODEL_MLP && batch * model->final_hw * model->final_hw < 2)
+    if (model->desc.kind != BLS_MODEL_MLP && model->desc.kind != BLS_MODEL_ENCODER && batch * model->final_hw * model->final_hw < 2)
         return bls_fail(ctx, BLS_EINVAL, "local_step: batch norm needs more than one value per channel");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
+    if (model->desc.kind == BLS_MODEL_ENCODER)
+        return seq_local_step(ctx, model, params, momentum, static_cast<const int32_t*>(x_any), y_pool, N, sel_idx, k, batch, tau, *opt,
+                              step_losses_out);
+    const float* x_pool = static_cast<const float*>(x_any);
     if (model->desc.kind == BLS_MODEL_WRN)
         return wrn_local_step(ctx, model, params, buffers, momentum, x_pool, y_pool, N, sel_idx, k, batch, tau, *opt, step_losses_out);
     return net_local_step(ctx, model, params, buffers, momentum, x_pool, y_pool, N, sel_idx, k, batch, tau, *opt,

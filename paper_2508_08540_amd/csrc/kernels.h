@@ -171,3 +171,48 @@ void launch_update(hipStream_t s, int act, float* params, float* momentum, const
 // Returns 0, or -1 for a shape the kernel does not cover (nothing is launched).
 int launch_wconv(hipStream_t s, int act, int taps, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const void* x,
                  const void* w, void* y, const void* add, fixsum_t* sums, double scale);
+
+// ---- gemm_tiled.hip -----------------------------------------------------------------------------------
+// C[m][n] = alpha * sum_k A(m,k) B(n,k) [+ bias[n]] [+ R[m][n]]; A(m,k) = a_kmajor ? A[k*lda + m] : A[m*lda + k], same for B.
+// Batched over z = z1 * inner + z2 (z1 < batch / inner): pointer offsets z1*s?1 + z2*s?2 (R uses C's).  splits > 1 splits
+// K into partials in `part` (batch must be 1) that are added in order.  Fields below the line are filled by the launcher.
+struct GemmDesc {
+    const float *A, *B;
+    float* C;
+    const float *bias, *R;
+    float* part;
+    int M, N, K, lda, ldb, ldc;
+    int a_kmajor, b_kmajor;
+    int batch, inner, splits;
+    int64_t sa1, sa2, sb1, sb2, sc1, sc2;
+    float alpha;
+    // ----
+    int k_chunk, a_vec, b_vec;
+    int64_t part_stride;
+};
+size_t gemm_tiled_partial_floats(int M, int N, int splits);
+void launch_gemm_tiled(hipStream_t s, GemmDesc d);
+
+// ---- seq.hip ------------------------------------------------------------------------------------------
+// Accumulator ranges that fix_finalize turns into gradients: grad[grad_off + i] = acc[acc_off + i] / 2^44, acc cleared.
+#define FIX_MAX_RANGES 112
+struct FixRange {
+    int64_t acc_off, grad_off, n;
+};
+struct FixRangeTable {
+    int n;
+    FixRange r[FIX_MAX_RANGES];
+};
+void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h);
+void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok);
+void launch_colsum_fix(hipStream_t s, const float* X, int64_t M, int N, fixsum_t* acc);
+void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad);
+void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, float* stats);
+void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
+                          fixsum_t* acc_g, fixsum_t* acc_b);
+void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n);
+void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale);
+void launch_gelu(hipStream_t s, const float* u, float* g, int64_t n);
+void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n);
+void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale);
+void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss);

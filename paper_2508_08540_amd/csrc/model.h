@@ -41,6 +41,11 @@ struct WrnBlock {
     bool proj;
 };
 
+// One layer of the transformer encoder: offsets into params.
+struct EncLayer {
+    int64_t wq, bq, wk, bk, wv, bv, wo, bo, ln1_g, ln1_b, w1, b1, w2, b2, ln2_g, ln2_b;
+};
+
 struct bls_model {
     bls_model_desc desc;
     int64_t num_params = 0;
@@ -57,4 +62,8 @@ struct bls_model {
     ConvSlot wrn_stem{};
     std::vector<WrnBlock> wrn_blocks;
     BnSlot wrn_final_bn{};
+    // transformer encoder: vocabulary V, sequence length L, width D, heads H, feed-forward width F
+    int enc_V = 0, enc_L = 0, enc_D = 0, enc_H = 0, enc_F = 0;
+    int64_t enc_tok = 0, enc_pos = 0, enc_head = 0;
+    std::vector<EncLayer> enc_layers;
 };

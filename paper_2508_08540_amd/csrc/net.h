@@ -15,3 +15,7 @@ int wrn_score(bls_ctx* ctx, const bls_model* m, const float* params, const float
 int wrn_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffers, float* momentum, const float* x_pool,
                    const int32_t* y_pool, int64_t N, const int32_t* sel, int64_t k, int64_t batch, int64_t tau, const bls_sgd& opt,
                    float* step_losses_out);
+// the same two passes for the transformer encoder (net_seq.hip); x holds int32 token ids [N][L], y the targets [N][L]
+int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32_t* x, const int32_t* y, int64_t N, float* losses_out);
+int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momentum, const int32_t* x_pool, const int32_t* y_pool, int64_t N,
+                   const int32_t* sel, int64_t k, int64_t batch, int64_t tau, const bls_sgd& opt, float* step_losses_out);

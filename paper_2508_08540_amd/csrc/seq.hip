@@ -1,0 +1,312 @@
+// Kernels of the sequence model around the GEMMs: embedding lookup and its gradient, layer norm, row softmax,
+// GELU, per-token cross-entropy over a large vocabulary, and column sums.  All activations are fp32 [tokens][D].
+// Sums that cross workgroups (bias, layer-norm and embedding gradients) go through 64-bit fixed-point integer
+// atomics (scale 2^44), so they do not depend on the order of arrival; fix_finalize_kernel turns them into floats.
+#include "kernels.h"
+
+#define LN_EPS 1e-5f
+
+__device__ __forceinline__ float wsum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wmax(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ void fix_add(fixsum_t* p, float v) { atomicAdd(p, (fixsum_t)__double2ll_rn((double)v * FIX_BWD_SCALE)); }
+
+// h[t][:] = tok_emb[token[t]][:] + pos_emb[t % L][:]; one wave per token, D % 4 == 0
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ tokens, int64_t T, int L, int D, const float* __restrict__ tok,
+                                                    const float* __restrict__ pos, float* __restrict__ h) {
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int lane = threadIdx.x & 63;
+    const float* e = tok + (int64_t)tokens[t] * D;
+    const float* p = pos + (int64_t)(t % L) * D;
+    for (int c = 4 * lane; c < D; c += 256)
+        *reinterpret_cast<f32x4*>(h + t * D + c) = *reinterpret_cast<const f32x4*>(e + c) + *reinterpret_cast<const f32x4*>(p + c);
+}
+
+// acc_tok[token[t]][:] += dh[t][:] (fixed point)
+__global__ __launch_bounds__(256) void embed_grad_kernel(const int32_t* __restrict__ tokens, int64_t T, int D, const float* __restrict__ dh,
+                                                         fixsum_t* __restrict__ acc_tok) {
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int lane = threadIdx.x & 63;
+    fixsum_t* a = acc_tok + (int64_t)tokens[t] * D;
+    for (int c = lane; c < D; c += 64) fix_add(a + c, dh[t * D + c]);
+}
+
+// acc[n] += sum over rows of X[m][n]; a workgroup takes 64 rows, thread = column
+__global__ __launch_bounds__(256) void colsum_fix_kernel(const float* __restrict__ X, int64_t M, int N, fixsum_t* __restrict__ acc) {
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int64_t m0 = (int64_t)blockIdx.y * 64, m1 = m0 + 64 < M ? m0 + 64 : M;
+    float s = 0.f;
+    for (int64_t m = m0; m < m1; ++m) s += X[m * N + n];
+    fix_add(acc + n, s);
+}
+
+// out[i] = acc[i] / 2^44, acc[i] = 0; blockIdx.y selects a range
+__global__ __launch_bounds__(256) void fix_finalize_kernel(FixRangeTable tab, fixsum_t* __restrict__ acc, float* __restrict__ grad) {
+    const FixRange r = tab.r[blockIdx.y];
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < r.n; i += (int64_t)gridDim.x * 256) {
+        grad[r.grad_off + i] = (float)((double)(long long)acc[r.acc_off + i] * (1.0 / FIX_BWD_SCALE));
+        acc[r.acc_off + i] = 0ull;
+    }
+}
+
+// y = (x - mean) * invstd * g + b per row; stats[row] = (mean, invstd); one wave per row, D <= 1024, D % 4 == 0
+__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, int64_t T, int D, const float* __restrict__ g,
+                                                        const float* __restrict__ b, float* __restrict__ y, float* __restrict__ stats) {
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int lane = threadIdx.x & 63;
+    f32x4 v[4];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = 4 * (lane + 64 * i);
+        v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (c < D) v[i] = *reinterpret_cast<const f32x4*>(x + t * D + c);
+        s += (v[i][0] + v[i][1]) + (v[i][2] + v[i][3]);
+    }
+    const float mean = wsum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = 4 * (lane + 64 * i);
+        if (c < D)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q += (v[i][j] - mean) * (v[i][j] - mean);
+    }
+    const float inv = 1.f / sqrtf(wsum(q) / (float)D + LN_EPS);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int c = 4 * (lane + 64 * i);
+        if (c < D) {
+            const f32x4 gg = *reinterpret_cast<const f32x4*>(g + c), bb = *reinterpret_cast<const f32x4*>(b + c);
+            f32x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = (v[i][j] - mean) * inv * gg[j] + bb[j];
+            *reinterpret_cast<f32x4*>(y + t * D + c) = o;
+        }
+    }
+    if (stats && lane == 0) {
+        stats[2 * t] = mean;
+        stats[2 * t + 1] = inv;
+    }
+}
+
+// dx = inv * (dxh - mean(dxh) - xhat * mean(dxh * xhat)), dxh = dy * g; acc_g += dy * xhat, acc_b += dy.
+// A wave walks `rows_per_wave` rows and keeps the two column sums of its channels in registers.
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
+                                                            const float* __restrict__ stats, int64_t T, int D, const float* __restrict__ g,
+                                                            float* __restrict__ dx, fixsum_t* __restrict__ acc_g, fixsum_t* __restrict__ acc_b,
+                                                            int rows_per_wave) {
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t t0 = w * rows_per_wave, t1 = t0 + rows_per_wave < T ? t0 + rows_per_wave : T;
+    f32x4 sg[4], sb[4], gg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        sg[i] = sb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const int c = 4 * (lane + 64 * i);
+        gg[i] = c < D ? *reinterpret_cast<const f32x4*>(g + c) : sg[i];
+    }
+    for (int64_t t = t0; t < t1; ++t) {
+        const float mean = stats[2 * t], inv = stats[2 * t + 1];
+        f32x4 xh[4], dh[4];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = 4 * (lane + 64 * i);
+            xh[i] = dh[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (c < D) {
+                const f32x4 xv = *reinterpret_cast<const f32x4*>(x + t * D + c), dv = *reinterpret_cast<const f32x4*>(dy + t * D + c);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    xh[i][j] = (xv[j] - mean) * inv;
+                    dh[i][j] = dv[j] * gg[i][j];
+                    s1 += dh[i][j];
+                    s2 += dh[i][j] * xh[i][j];
+                    sg[i][j] += dv[j] * xh[i][j];
+                    sb[i][j] += dv[j];
+                }
+            }
+        }
+        const float m1 = wsum(s1) / (float)D, m2 = wsum(s2) / (float)D;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = 4 * (lane + 64 * i);
+            if (c < D) {
+                f32x4 o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] = inv * (dh[i][j] - m1 - xh[i][j] * m2);
+                *reinterpret_cast<f32x4*>(dx + t * D + c) = o;
+            }
+        }
+    }
+    if (t0 < T)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int c = 4 * (lane + 64 * i);
+            if (c < D)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    fix_add(acc_g + c + j, sg[i][j]);
+                    fix_add(acc_b + c + j, sb[i][j]);
+                }
+        }
+}
+
+// in place: row <- softmax(row); one wave per row of length n <= 1024
+__global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ s, int64_t rows, int n) {
+    const int64_t rrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rrow >= rows) return;
+    const int lane = threadIdx.x & 63;
+    float* p = s + rrow * n;
+    float v[16];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = lane + 64 * i;
+        v[i] = c < n ? p[c] : -INFINITY;
+        m = fmaxf(m, v[i]);
+    }
+    m = wmax(m);
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        v[i] = lane + 64 * i < n ? expf(v[i] - m) : 0.f;
+        sum += v[i];
+    }
+    sum = wsum(sum);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (lane + 64 * i < n) p[lane + 64 * i] = v[i] / sum;
+}
+
+// in place on dp: ds = p * (dp - sum_j dp_j p_j) * scale
+__global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(float* __restrict__ dp, const float* __restrict__ p, int64_t rows, int n,
+                                                               float scale) {
+    const int64_t rrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (rrow >= rows) return;
+    const int lane = threadIdx.x & 63;
+    float a[16], d[16];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = lane + 64 * i;
+        a[i] = c < n ? p[rrow * n + c] : 0.f;
+        d[i] = c < n ? dp[rrow * n + c] : 0.f;
+        dot += a[i] * d[i];
+    }
+    dot = wsum(dot);
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        if (lane + 64 * i < n) dp[rrow * n + lane + 64 * i] = a[i] * (d[i] - dot) * scale;
+}
+
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float x) {
+    return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
+}
+__global__ __launch_bounds__(256) void gelu_kernel(const float* __restrict__ u, float* __restrict__ g, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) g[i] = gelu_f(u[i]);
+}
+// in place on dg: du = dg * gelu'(u)
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(float* __restrict__ dg, const float* __restrict__ u, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dg[i] *= gelu_df(u[i]);
+}
+
+// One workgroup per token row of logits [T][V]: tok_loss[t] = logsumexp(z) - z[target]; with grad_scale != 0 the row is
+// overwritten by (softmax(z) - onehot(target)) * grad_scale.  Partial results are combined in a fixed order.
+__global__ __launch_bounds__(256) void token_ce_kernel(float* __restrict__ logits, const int32_t* __restrict__ targets, int V,
+                                                       float* __restrict__ tok_loss, float grad_scale) {
+    __shared__ float red[4];
+    const int64_t t = blockIdx.x;
+    float* z = logits + t * (int64_t)V;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float m = -INFINITY;
+    for (int c = threadIdx.x; c < V; c += 256) m = fmaxf(m, z[c]);
+    m = wmax(m);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float s = 0.f;
+    for (int c = threadIdx.x; c < V; c += 256) s += expf(z[c] - m);
+    s = wsum(s);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    s = (red[0] + red[1]) + (red[2] + red[3]);
+    const int tgt = targets[t];
+    if (threadIdx.x == 0) tok_loss[t] = (m + logf(s)) - z[tgt];
+    if (grad_scale != 0.f) {
+        __syncthreads();  // z[tgt] has been read
+        const float inv = 1.f / s;
+        for (int c = threadIdx.x; c < V; c += 256) z[c] = (expf(z[c] - m) * inv - (c == tgt ? 1.f : 0.f)) * grad_scale;
+    }
+}
+
+// loss[b] = mean of tok_loss[b*L .. b*L + L); one wave per sample, fixed order
+__global__ __launch_bounds__(64) void sample_mean_kernel(const float* __restrict__ tok_loss, int L, float* __restrict__ loss) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    float s = 0.f;
+    for (int l = lane; l < L; l += 64) s += tok_loss[(int64_t)b * L + l];
+    s = wsum(s);
+    if (lane == 0) loss[b] = s / (float)L;
+}
+
+// ---- launchers ---------------------------------------------------------------------------------------
+static unsigned nblk(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
+
+void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h) {
+    hipLaunchKernelGGL(embed_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, L, D, tok, pos, h);
+}
+void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok) {
+    hipLaunchKernelGGL(embed_grad_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, D, dh, acc_tok);
+}
+void launch_colsum_fix(hipStream_t s, const float* X, int64_t M, int N, fixsum_t* acc) {
+    hipLaunchKernelGGL(colsum_fix_kernel, dim3(nblk(N, 256), nblk(M, 64)), dim3(256), 0, s, X, M, N, acc);
+}
+void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad) {
+    int64_t longest = 1;
+    for (int i = 0; i < tab.n; ++i) longest = tab.r[i].n > longest ? tab.r[i].n : longest;
+    unsigned bx = nblk(longest, 256);
+    if (bx > 2048) bx = 2048;
+    hipLaunchKernelGGL(fix_finalize_kernel, dim3(bx, tab.n), dim3(256), 0, s, tab, acc, grad);
+}
+void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, float* stats) {
+    hipLaunchKernelGGL(layernorm_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, x, T, D, g, b, y, stats);
+}
+void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
+                          fixsum_t* acc_g, fixsum_t* acc_b) {
+    const int rows_per_wave = 8;
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(nblk(T, 4 * rows_per_wave)), dim3(256), 0, s, dy, x, stats, T, D, g, dx, acc_g, acc_b,
+                       rows_per_wave);
+}
+void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n) {
+    hipLaunchKernelGGL(softmax_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, sc, rows, n);
+}
+void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale) {
+    hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, dp, p, rows, n, scale);
+}
+void launch_gelu(hipStream_t s, const float* u, float* g, int64_t n) {
+    unsigned b = nblk(n, 256);
+    hipLaunchKernelGGL(gelu_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, u, g, n);
+}
+void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n) {
+    unsigned b = nblk(n, 256);
+    hipLaunchKernelGGL(gelu_bwd_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, dg, u, n);
+}
+void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale) {
+    hipLaunchKernelGGL(token_ce_kernel, dim3((unsigned)T), dim3(256), 0, s, logits, targets, V, tok_loss, grad_scale);
+}
+void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss) {
+    hipLaunchKernelGGL(sample_mean_kernel, dim3(B), dim3(64), 0, s, tok_loss, L, loss);
+}

@@ -46,6 +46,18 @@ def test_layout_matches_generator_order_and_counts():
         bls.Model.resnet_cifar(widths=(16, 24, 64))
 
 
+def test_sequence_model_layout_and_rejected_descriptions():
+    import paper_2508_08540_amd as bls
+    m = bls.Model.transformer()
+    assert m.num_params == 51747840 and m.num_buffers == 0
+    assert [(t["name"], t["shape"]) for t in m.tensors] == [(n, tuple(s)) for n, s in synth.transformer_tensor_specs()]
+    small = bls.Model.transformer(50, 8, 16, 2, 32, 2)
+    assert [(t["name"], t["shape"]) for t in small.tensors] == [(n, tuple(s)) for n, s in synth.transformer_tensor_specs(50, 8, 16, 32, 2)]
+    for bad in [dict(d_model=18), dict(heads=3), dict(seq_len=2048), dict(layers=0), dict(d_ff=30), dict(vocab=1)]:
+        with pytest.raises(bls.BlsError):
+            bls.Model.transformer(**bad)
+
+
 def test_weights_from_tau_host_helper():
     import paper_2508_08540_amd as bls
     w = bls.weights_from_tau([32] * 8 + [16] * 2)

@@ -1,0 +1,97 @@
+"""GPU parity of score_losses / local_step for the transformer encoder language model (fp32)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_helpers import Harness, assert_losses_close, assert_tensors_close
+
+pytestmark = pytest.mark.gpu
+CFG = synth.workload("transformer")
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    yield torch, bls, ctx
+    ctx.close()
+
+
+def _harness(env, vocab, L, D, H, F, layers):
+    torch, bls, ctx = env
+    return Harness(torch, bls, ctx, bls.Model.transformer(vocab, L, D, H, F, layers), oracle.TransformerLM(vocab, L, D, H, F, layers))
+
+
+def _zeros(p):
+    return {k: np.zeros_like(v) for k, v in p.items()}
+
+
+def test_layout_matches_the_generator(env):
+    torch, bls, ctx = env
+    m = bls.Model.transformer()
+    assert m.num_params == 51747840 and m.num_buffers == 0
+    assert [(t["name"], t["shape"]) for t in m.tensors] == [(n, tuple(s)) for n, s in synth.transformer_tensor_specs()]
+
+
+SHAPES = [
+    (50, 8, 16, 2, 32, 2, 3),        # everything inside one tile
+    (301, 20, 24, 4, 40, 1, 5),      # head width 6 and an odd vocabulary: the unaligned load path
+    (1000, 130, 64, 2, 128, 2, 3),   # sequence longer than a tile: two tiles of attention scores, ragged edges
+    (700, 16, 256, 8, 1024, 1, 40),  # 640 tokens: several row tiles, split token contraction in the weight gradients
+]
+
+
+@pytest.mark.parametrize("vocab,L,D,H,F,layers,batch", SHAPES)
+def test_scores_and_gradients(env, vocab, L, D, H, F, layers, batch):
+    h = _harness(env, vocab, L, D, H, F, layers)
+    p = synth.transformer_init(CFG["id"], vocab, L, D, F, layers, perturb=0.2)
+    x, y = synth.token_pool(CFG["id"], batch + 3, L, vocab)
+    sel = (np.arange(batch) * 2) % (batch + 3)
+    assert_losses_close(h.score(p, {}, x, y), oracle.score_losses(h.oracle_model, p, {}, x, y), rtol=2e-5)
+    probe = oracle.GradientProbe(h.oracle_model, p, {}, x[sel], y[sel])
+    newp, _, mom, sl = h.local_step(p, {}, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], probe.losses, rtol=2e-5)
+    ref = probe.grads()
+    # A shift of every key by the same vector leaves the softmax unchanged, so the key bias has an exactly zero gradient:
+    # both sides may only hold rounding noise there, measured against the query bias of the same layer.
+    for name in [n for n in ref if n.endswith("attn.k.bias")]:
+        scale = np.abs(ref[name.replace(".k.", ".q.")]).max()
+        assert np.abs(ref.pop(name)).max() <= 1e-12 * scale and np.abs(mom[name]).max() <= 1e-5 * scale, name
+    assert_tensors_close(mom, ref, 1e-4, "gradients")
+    assert_tensors_close(newp, {k: np.asarray(v, np.float64) for k, v in p.items()}, 0.0, "lr = 0 leaves the parameters alone")
+
+
+def test_steps_follow_the_oracle_and_repeat_bit_for_bit(env):
+    vocab, L, D, H, F, layers = 200, 12, 32, 4, 64, 2
+    h = _harness(env, vocab, L, D, H, F, layers)
+    p = synth.transformer_init(CFG["id"], vocab, L, D, F, layers, perturb=0.1)
+    x, y = synth.token_pool(CFG["id"], 30, L, vocab)
+    sel = oracle.topk_by_loss(oracle.score_losses(h.oracle_model, p, {}, x, y).astype(np.float32), 10)
+    B, tau, lr, mu, wd = 4, 3, 0.05, 0.9, 1e-4
+    rp, _, rm, rl = oracle.local_step(h.oracle_model, p, {}, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    gp, _, gm, gl = h.local_step(p, {}, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    assert_losses_close(gl, rl, rtol=1e-4)
+    kb = [n for n in p if n.endswith("attn.k.bias")]   # zero gradient: only weight decay moves these, see above
+    for n in kb:
+        assert np.abs(gp[n] - rp[n]).max() <= 2e-7 * np.abs(rp[n]).max(), n   # equal up to the rounding of the fp32 value itself
+    rest = [n for n in p if n not in kb]
+    assert_tensors_close(gm, {n: rm[n] for n in rest}, 1e-3, "momentum after tau steps")
+    # the change of a parameter is compared up to the fp32 rounding of the parameter itself (one rounding per step)
+    for n in rest:
+        change = np.linalg.norm(rp[n] - p[n])
+        assert np.linalg.norm(gp[n] - rp[n]) <= 1e-3 * change + tau * 2.0 ** -24 * np.linalg.norm(rp[n]), n
+    gp2, _, gm2, gl2 = h.local_step(p, {}, _zeros(p), x, y, sel, B, tau, lr, mu, wd)
+    assert all(np.array_equal(gp[k], gp2[k]) and np.array_equal(gm[k], gm2[k]) for k in gp) and np.array_equal(gl, gl2)
+
+
+def test_scoring_in_chunks_matches_scoring_alone(env):
+    """More sequences than one scoring chunk, with a ragged last chunk: the loss of a sequence does not depend on its neighbours."""
+    vocab, L, D, H, F, layers = 120, 8, 16, 2, 32, 1
+    h = _harness(env, vocab, L, D, H, F, layers)
+    p = synth.transformer_init(CFG["id"], vocab, L, D, F, layers, perturb=0.1)
+    x, y = synth.token_pool(CFG["id"], 75, L, vocab)
+    full = h.score(p, {}, x, y)
+    assert_losses_close(full, oracle.score_losses(h.oracle_model, p, {}, x, y), rtol=2e-5)
+    assert np.array_equal(full[70:], h.score(p, {}, x[70:], y[70:]))
