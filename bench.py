@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16", "wrn16_8_bf16"])
+    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16", "wrn16_8_bf16", "transformer"])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -83,21 +83,33 @@ def main():
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
     act_dtype = cfg.get("act_dtype", "f32")
     wide = cfg["model"] == "wrn16_8"
-    if wide:
+    seq = cfg["model"] == "transformer"
+    if seq:
+        model = bls.Model.transformer()
+        p, b = synth.transformer_init(cfg["id"]), {}
+        x, y = synth.token_pool(cfg["id"], N, cfg["seq_len"], cfg["classes"])
+    elif wide:
         model = bls.Model.wide_resnet(act_dtype=act_dtype)
         p, b = synth.wrn_init(cfg["id"])
     else:
         model = bls.Model.resnet_cifar(act_dtype=act_dtype)
         p, b = synth.resnet_init(cfg["id"])
     d = model.num_params
-    x, y = synth.image_pool(cfg["id"], N, cfg["classes"])
+    if not seq:
+        x, y = synth.image_pool(cfg["id"], N, cfg["classes"])
     flat = model.pack(p)
     ctx = bls.Context(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    p0, b0 = dev(flat), dev(model.pack(b, buffers=True))
+    p0 = dev(flat)
+    b0 = dev(model.pack(b, buffers=True)) if model.num_buffers else torch.zeros(1, device="cuda")
     dp, db, dm = p0.clone(), b0.clone(), torch.zeros_like(p0)
     dx, dy = dev(x), dev(y)
-    others = [dev(r) for r in synth.replicas(flat, P - 1, cfg["id"])]
+    if seq:
+        # the other workers' replicas only feed the aggregation's bandwidth: seeded perturbations drawn on the device
+        gen = torch.Generator(device="cuda").manual_seed(250808540 + cfg["id"])
+        others = [p0 + 0.01 * torch.randn(p0.shape, device="cuda", generator=gen) for _ in range(P - 1)]
+    else:
+        others = [dev(r) for r in synth.replicas(flat, P - 1, cfg["id"])]
     w = bls.weights_from_tau(cfg["tau_workers"])
     losses = torch.empty(N, dtype=torch.float32, device="cuda")
     idx = torch.empty(k, dtype=torch.int32, device="cuda")
@@ -130,6 +142,12 @@ def main():
         one_step()
     prof = ctx.profile_end()
     phases = {name: round(ms / args.steps, 4) for name, (ms, cnt) in prof.items() if cnt}
+    if seq:
+        line = sequence_line(args, cfg, model, prof, phases, value, ms_per_step, finite)
+        if not args.no_cpu_baseline:
+            line["cpu_baseline"] = cpu_baseline_sequence(cfg, p, x, y)
+        print(json.dumps(line))
+        return
     # forward flops of one local step / one scoring pass; the input gradient skips the stem
     if wide:
         conv_flops_img, no_stem = wrn_conv_flops((128, 256, 512), 2, 32, 3, 16)
@@ -199,6 +217,72 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, p, b, x, y)
     print(json.dumps(line))
+
+
+def sequence_line(args, cfg, model, prof, phases, value, ms_per_step, finite):
+    """JSON line of the transformer workload; the roofline is that of the GEMM launches (fp32 MFMA).
+
+    Algorithmic flops per token: 2 per weight of the linear layers and the vocabulary projection in each of forward,
+    input gradient and weight gradient; the attention products add 4*L*D per layer forward and 8*L*D backward.
+    """
+    N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
+    V, L, D, F, layers = cfg["classes"], cfg["seq_len"], 512, 2048, 6
+    lin = layers * (4 * D * D + 2 * D * F) + V * D
+    tok_train, tok_score = tau * B * L, N * L
+    flops = {
+        "gemm": (2 * lin + 4 * L * D * layers) * (tok_train + tok_score) + (2 * lin + 8 * L * D * layers) * tok_train,
+        "conv_wgrad": 2 * lin * tok_train,
+    }
+    dom = max(flops, key=lambda c: prof[c][0])
+    dom_ms, dom_cnt = prof[dom]
+    achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
+    symbol = {"gemm": "gemm_tiled_kernel (forward, input-gradient and attention launches)",
+              "conv_wgrad": "gemm_tiled_kernel (weight-gradient launches) + gemm_split_reduce_kernel"}[dom]
+    roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None, "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2),
+                "launches_per_step": dom_cnt // args.steps}
+    return {
+        "metric": "selected samples/s per local step (6-layer transformer encoder, sequences of %d tokens)" % L, "value": round(value, 1),
+        "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(model.num_params),
+                   "seq_len": L, "vocab": V},
+        "tokens_per_s": round(value * L, 1), "finite": finite, "phase_ms_per_step": phases, "roofline": roofline,
+    }
+
+
+def cpu_baseline_sequence(cfg, p, x, y):
+    """The oracle on the host cores: 4 sequences scored, one local step on 2 sequences, top-k in full, aggregation on a slice."""
+    import numpy as np
+    import oracle
+    from threadpoolctl import threadpool_info
+    N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
+    m = oracle.TransformerLM(cfg["classes"], cfg["seq_len"])
+    n_score, b_step, d_agg = 4, 2, 4_000_000
+    t = time.perf_counter()
+    ls = oracle.score_losses(m, p, {}, x[:n_score], y[:n_score])
+    t_score = (time.perf_counter() - t) / n_score
+    full = np.resize(np.concatenate([ls, ls[::-1]]), N).astype(np.float32)
+    t = time.perf_counter()
+    sel = oracle.topk_by_loss(full, k)
+    t_topk = time.perf_counter() - t
+    zeros = {n: np.zeros_like(v) for n, v in p.items()}
+    t = time.perf_counter()
+    oracle.local_step(m, p, {}, zeros, x, y, sel, b_step, 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+    t_step = (time.perf_counter() - t) * (B / b_step)
+    d = sum(int(v.size) for v in p.values())
+    rng = np.random.default_rng(cfg["id"])
+    reps = rng.standard_normal((P, d_agg)).astype(np.float32)
+    import synth
+    t = time.perf_counter()
+    oracle.weighted_aggregate(reps, synth.aggregation_weights(cfg))
+    t_agg = (time.perf_counter() - t) * (d / d_agg)
+    total = N * t_score + t_topk + tau * t_step + t_agg
+    threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    return {"value": round(tau * B / total, 3), "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": "scored %d of %d sequences, full top-k, 1 of %d local steps at batch %d (scaled to batch %d), aggregation of "
+                      "%d of %d floats (scaled); per-part times scaled to the whole pass" % (n_score, N, tau, b_step, B, d_agg, d),
+            "host_cpus": os.cpu_count()}
 
 
 def _time_calls(torch, fn, reps):
