@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16", "wrn16_8_bf16", "transformer"])
+    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16", "wrn16_8_bf16", "transformer", "transformer_fp32"])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -85,7 +85,7 @@ def main():
     wide = cfg["model"] == "wrn16_8"
     seq = cfg["model"] == "transformer"
     if seq:
-        model = bls.Model.transformer()
+        model = bls.Model.transformer(act_dtype=act_dtype)
         p, b = synth.transformer_init(cfg["id"]), {}
         x, y = synth.token_pool(cfg["id"], N, cfg["seq_len"], cfg["classes"])
     elif wide:
@@ -238,13 +238,16 @@ def sequence_line(args, cfg, model, prof, phases, value, ms_per_step, finite):
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
     symbol = {"gemm": "gemm_tiled_kernel (forward, input-gradient and attention launches)",
               "conv_wgrad": "gemm_tiled_kernel (weight-gradient launches) + gemm_split_reduce_kernel"}[dom]
-    roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 4), "traffic": None, "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2),
+    bf16 = cfg.get("act_dtype") == "bf16"
+    peak = BF16_MFMA_PEAK_TFLOPS if bf16 else FP32_MFMA_PEAK_TFLOPS
+    symbol = symbol.replace("gemm_tiled_kernel", "gemm_bf16_kernel") if bf16 else symbol
+    roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": None, "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2),
                 "launches_per_step": dom_cnt // args.steps}
     return {
         "metric": "selected samples/s per local step (6-layer transformer encoder, sequences of %d tokens)" % L, "value": round(value, 1),
         "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(model.num_params),
                    "seq_len": L, "vocab": V},
         "tokens_per_s": round(value * L, 1), "finite": finite, "phase_ms_per_step": phases, "roofline": roofline,
@@ -257,7 +260,7 @@ def cpu_baseline_sequence(cfg, p, x, y):
     import oracle
     from threadpoolctl import threadpool_info
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
-    m = oracle.TransformerLM(cfg["classes"], cfg["seq_len"])
+    m = oracle.TransformerLM(cfg["classes"], cfg["seq_len"], operand=oracle.round_bf16 if cfg.get("act_dtype") == "bf16" else None)
     n_score, b_step, d_agg = 4, 2, 4_000_000
     t = time.perf_counter()
     ls = oracle.score_losses(m, p, {}, x[:n_score], y[:n_score])

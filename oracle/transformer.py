@@ -9,6 +9,10 @@ untied, bias-free output projection to the vocabulary.  The target of position t
 it in the generated sequence; the loss of a sample is the mean of its per-position cross-entropies, so that
 the sampler still ranks one float per sample (Section 4.3).
 Linear weights are [out, in]; parameters are a dict keyed by tensor name; there are no buffers.
+
+Mixed precision: with `operand` set (e.g. round_bf16) both operands of every matrix product, forward and backward,
+pass through it before they are multiplied; sums, activations and everything else stay float64.  The default is the
+exact model.
 """
 import math
 
@@ -63,8 +67,17 @@ def token_cross_entropy(logits, targets):
 class TransformerLM:
     has_buffers = False
 
-    def __init__(self, vocab=32000, seq_len=128, d_model=512, heads=8, d_ff=2048, layers=6):
+    def __init__(self, vocab=32000, seq_len=128, d_model=512, heads=8, d_ff=2048, layers=6, operand=None):
         self.vocab, self.seq_len, self.d_model, self.heads, self.d_ff, self.layers = vocab, seq_len, d_model, heads, d_ff, layers
+        self.operand = operand if operand is not None else (lambda a: a)
+
+    def _mm(self, a, b):
+        """a @ b with both operands passed through the operand hook."""
+        return self.operand(a) @ self.operand(b)
+
+    def _outer_sum(self, dy, x):
+        """sum over tokens of dy (outer) x: the weight gradient [out, in] of y = x W^T."""
+        return np.tensordot(self.operand(dy), self.operand(x), axes=([0, 1], [0, 1]))
 
     def sample_losses(self, logits, targets):
         return token_cross_entropy(logits, targets)
@@ -80,14 +93,14 @@ class TransformerLM:
         for l in range(self.layers):
             n = "l%d." % l
             c = {"x": h}
-            lin = lambda name, x: x @ p[n + name + ".weight"].T + p[n + name + ".bias"]
+            lin = lambda name, x: self._mm(x, p[n + name + ".weight"].T) + p[n + name + ".bias"]
             split = lambda t: t.reshape(B, L, H, dh).transpose(0, 2, 1, 3)          # [B, H, L, dh]
             q, k, v = split(lin("attn.q", h)), split(lin("attn.k", h)), split(lin("attn.v", h))
-            s = q @ k.transpose(0, 1, 3, 2) / math.sqrt(dh)
+            s = self._mm(q, k.transpose(0, 1, 3, 2)) / math.sqrt(dh)
             s = s - s.max(axis=-1, keepdims=True)
             a = np.exp(s)
             a = a / a.sum(axis=-1, keepdims=True)
-            ctx = (a @ v).transpose(0, 2, 1, 3).reshape(B, L, D)
+            ctx = self._mm(a, v).transpose(0, 2, 1, 3).reshape(B, L, D)
             c.update(q=q, k=k, v=v, a=a, ctx=ctx)
             h1, c["ln1"] = layernorm(h + lin("attn.o", ctx), p[n + "ln1.weight"], p[n + "ln1.bias"])
             c["h1"] = h1
@@ -97,7 +110,7 @@ class TransformerLM:
             h, c["ln2"] = layernorm(h1 + lin("ffn.fc2", gact), p[n + "ln2.weight"], p[n + "ln2.bias"])
             cache["layers"].append(c)
         cache["final"] = h
-        return h @ p["head.weight"].T, cache, dict(buffers)
+        return self._mm(h, p["head.weight"].T), cache, dict(buffers)
 
     def backward(self, cache, dlogits):
         p, tokens = cache["p"], cache["tokens"]
@@ -106,13 +119,13 @@ class TransformerLM:
         dh = D // H
         g = {}
         hf = cache["final"]
-        g["head.weight"] = np.tensordot(dlogits, hf, axes=([0, 1], [0, 1]))
-        dh_ = dlogits @ p["head.weight"]
+        g["head.weight"] = self._outer_sum(dlogits, hf)
+        dh_ = self._mm(dlogits, p["head.weight"])
 
         def lin_back(name, x, dy):
-            g[name + ".weight"] = np.tensordot(dy, x, axes=([0, 1], [0, 1]))
+            g[name + ".weight"] = self._outer_sum(dy, x)
             g[name + ".bias"] = dy.reshape(-1, dy.shape[-1]).sum(axis=0)
-            return dy @ p[name + ".weight"]
+            return self._mm(dy, p[name + ".weight"])
 
         for l in reversed(range(self.layers)):
             n = "l%d." % l
@@ -123,10 +136,10 @@ class TransformerLM:
             dr1, g[n + "ln1.weight"], g[n + "ln1.bias"] = layernorm_backward(dh1, c["ln1"])
             dctx = lin_back(n + "attn.o", c["ctx"], dr1).reshape(B, L, H, dh).transpose(0, 2, 1, 3)
             a, q, k, v = c["a"], c["q"], c["k"], c["v"]
-            dv = a.transpose(0, 1, 3, 2) @ dctx
-            da = dctx @ v.transpose(0, 1, 3, 2)
+            dv = self._mm(a.transpose(0, 1, 3, 2), dctx)
+            da = self._mm(dctx, v.transpose(0, 1, 3, 2))
             ds = a * (da - (da * a).sum(axis=-1, keepdims=True)) / math.sqrt(dh)
-            dq, dk = ds @ k, ds.transpose(0, 1, 3, 2) @ q
+            dq, dk = self._mm(ds, k), self._mm(ds.transpose(0, 1, 3, 2), q)
             merge = lambda t: t.transpose(0, 2, 1, 3).reshape(B, L, D)
             x = c["x"]
             dh_ = dr1 + lin_back(n + "attn.q", x, merge(dq)) + lin_back(n + "attn.k", x, merge(dk)) + lin_back(n + "attn.v", x, merge(dv))

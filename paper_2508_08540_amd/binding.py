@@ -173,9 +173,10 @@ class Model:
         return cls(MODEL_WRN, classes, image_hw, in_channels, stem, widths, blocks, act_dtype)
 
     @classmethod
-    def transformer(cls, vocab=32000, seq_len=128, d_model=512, heads=8, d_ff=2048, layers=6):
-        """Post-layer-norm transformer encoder language model; samples are int32 token sequences [N, seq_len]."""
-        return cls(MODEL_ENCODER, vocab, seq_len, 0, d_model, (heads, d_ff, 0), layers, "f32")
+    def transformer(cls, vocab=32000, seq_len=128, d_model=512, heads=8, d_ff=2048, layers=6, act_dtype="f32"):
+        """Post-layer-norm transformer encoder language model; samples are int32 token sequences [N, seq_len].
+        act_dtype "bf16": operands of every matrix product rounded to bf16, sums and storage fp32."""
+        return cls(MODEL_ENCODER, vocab, seq_len, 0, d_model, (heads, d_ff, 0), layers, act_dtype)
 
     def pack(self, tensors, buffers=False):
         """dict name -> array  =>  flat float32 numpy vector in the library's layout."""

@@ -160,7 +160,7 @@ int bls_model_create(const bls_model_desc* desc, bls_model** out) {
     const int max_classes = desc->kind == BLS_MODEL_ENCODER ? (1 << 20) : desc->kind == BLS_MODEL_WRN ? 128 : 64;
     if (desc->classes < 2 || desc->classes > max_classes) return BLS_EINVAL;
     if (desc->act_dtype != BLS_ACT_F32 && desc->act_dtype != BLS_ACT_BF16) return BLS_EINVAL;
-    if ((desc->kind == BLS_MODEL_MLP || desc->kind == BLS_MODEL_ENCODER) && desc->act_dtype != BLS_ACT_F32) return BLS_EUNSUPPORTED;
+    if (desc->kind == BLS_MODEL_MLP && desc->act_dtype != BLS_ACT_F32) return BLS_EUNSUPPORTED;
     // a convolution's input width must be 16 or a multiple of 32 in the wide network
     auto wide_ok = [](int c) { return c == 16 || (c >= 32 && c <= 512 && c % 32 == 0); };
     bls_model* m = new (std::nothrow) bls_model();

@@ -62,6 +62,31 @@ __device__ __forceinline__ void gt_put(float* __restrict__ S, const f32x4 (&v)[2
     }
 }
 
+// Writes a wave's 64 x 64 block: lane (r, g) holds C[m = .. + 4g + i][n = .. + r] of every 16 x 16 block.
+__device__ __forceinline__ void gt_store(const GemmDesc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, int z, int z1, int z2, int split,
+                                         int r, int g) {
+    float* C = d.splits > 1 ? d.part + ((int64_t)z * d.splits + split) * d.part_stride : d.C + z1 * d.sc1 + z2 * d.sc2;
+    const int ldc = d.splits > 1 ? d.N : d.ldc;
+    const float* R = (d.splits > 1 || !d.R) ? nullptr : d.R + z1 * d.sc1 + z2 * d.sc2;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = m_base + mt * 16 + 4 * g + i, n = n_base + nt * 16 + r;
+                if (m < d.M && n < d.N) {
+                    float v = acc[mt][nt][i];
+                    if (d.splits == 1) {
+                        v *= d.alpha;
+                        if (d.bias) v += d.bias[n];
+                        if (R) v += R[(int64_t)m * ldc + n];
+                    }
+                    C[(int64_t)m * ldc + n] = v;
+                }
+            }
+}
+
 template <bool AK, bool BK>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmDesc d) {
     __shared__ float As[2][GT_K * GT_LD], Bs[2][GT_K * GT_LD];
@@ -118,27 +143,139 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmDesc d) {
         __syncthreads();
         buf ^= 1;
     }
-    // lane holds C[m = .. + 4g + i][n = .. + r]
-    float* C = d.splits > 1 ? d.part + ((int64_t)z * d.splits + split) * d.part_stride : d.C + z1 * d.sc1 + z2 * d.sc2;
-    const int ldc = d.splits > 1 ? d.N : d.ldc;
-    const float* R = (d.splits > 1 || !d.R) ? nullptr : d.R + z1 * d.sc1 + z2 * d.sc2;
+    gt_store(d, acc, m0 + wm * 64, n0 + wn * 64, z, z1, z2, split, r, g);
+}
+
+// ---- the same product with both operands rounded to bf16 (nearest even) on the way into LDS --------------------
+// v_mfma_f32_16x16x32_bf16: lane (r, g) supplies A[r][8g .. 8g+7] and B[8g .. 8g+7][r] as eight bf16 and holds
+// C[4g + i][r].  K advances 32 at a time; LDS tiles are bf16 [128 rows][32 k] with a row pitch of 80 bytes, for which
+// the 16-byte operand reads of a quarter wave fall into distinct banks.  Accumulation, epilogue and memory stay fp32.
+#define GB_K 32
+#define GB_PITCH 40   // bf16 elements per LDS row
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){lo, hi}, bf16x2_t));
+}
+
+// Global fetch of a 128 x 32 operand tile into four float4 per thread.  Row-major operands: task f = row * 8 + k-quad.
+// K-major operands: task f takes two adjacent k for four adjacent rows (v[2i] at k, v[2i+1] at k + 1).
+template <bool KMAJOR>
+__device__ __forceinline__ void gb_fetch(const float* __restrict__ P, int ld, int rows, int row0, int k0, int k_end, bool vec, f32x4 (&v)[4]) {
+    if (KMAJOR) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+        for (int i = 0; i < 2; ++i) {
+            const int kp = (threadIdx.x & 7) + 8 * i, r = row0 + 4 * (threadIdx.x >> 3);
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+            for (int h = 0; h < 2; ++h) {
+                const int k = k0 + 2 * kp + h;
+                f32x4 t = {0.f, 0.f, 0.f, 0.f};
+                if (k < k_end) {
+                    const float* p = P + (int64_t)k * ld + r;
+                    if (vec && r + 3 < rows) t = *reinterpret_cast<const f32x4*>(p);
+                    else
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = m0 + wm * 64 + mt * 16 + 4 * g + i, n = n0 + wn * 64 + nt * 16 + r;
-                if (m < d.M && n < d.N) {
-                    float v = acc[mt][nt][i];
-                    if (d.splits == 1) {
-                        v *= d.alpha;
-                        if (d.bias) v += d.bias[n];
-                        if (R) v += R[(int64_t)m * ldc + n];
-                    }
-                    C[(int64_t)m * ldc + n] = v;
+                        for (int j = 0; j < 4; ++j)
+                            if (r + j < rows) t[j] = p[j];
                 }
+                v[2 * i + h] = t;
             }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int f = threadIdx.x + 256 * i;
+            const int r = row0 + (f >> 3), k = k0 + 4 * (f & 7);
+            f32x4 t = {0.f, 0.f, 0.f, 0.f};
+            if (r < rows) {
+                const float* p = P + (int64_t)r * ld + k;
+                if (vec && k + 3 < k_end) t = *reinterpret_cast<const f32x4*>(p);
+                else
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (k + j < k_end) t[j] = p[j];
+            }
+            v[i] = t;
+        }
+    }
+}
+
+template <bool KMAJOR>
+__device__ __forceinline__ void gb_put(__bf16* __restrict__ S, const f32x4 (&v)[4]) {
+    if (KMAJOR) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int kp = (threadIdx.x & 7) + 8 * i, r = 4 * (threadIdx.x >> 3);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint32_t*>(S + (r + j) * GB_PITCH + 2 * kp) = pack_bf16(v[2 * i][j], v[2 * i + 1][j]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int f = threadIdx.x + 256 * i;
+            *reinterpret_cast<uint2*>(S + (f >> 3) * GB_PITCH + 4 * (f & 7)) = make_uint2(pack_bf16(v[i][0], v[i][1]), pack_bf16(v[i][2], v[i][3]));
+        }
+    }
+}
+
+template <bool AK, bool BK>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDesc d) {
+    __shared__ __attribute__((aligned(16))) __bf16 As[2][GT_TILE * GB_PITCH], Bs[2][GT_TILE * GB_PITCH];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * GT_TILE, n0 = blockIdx.x * GT_TILE;
+    const int split = blockIdx.z % d.splits, z = blockIdx.z / d.splits;
+    const int z1 = z / d.inner, z2 = z - z1 * d.inner;
+    const float* A = d.A + z1 * d.sa1 + z2 * d.sa2;
+    const float* B = d.B + z1 * d.sb1 + z2 * d.sb2;
+    const int k_begin = split * d.k_chunk;
+    const int k_end = min(d.K, k_begin + d.k_chunk);
+    const bool avec = d.a_vec != 0, bvec = d.b_vec != 0;
+
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    f32x4 pa[4], pb[4];
+    gb_fetch<AK>(A, d.lda, d.M, m0, k_begin, k_end, avec, pa);
+    gb_fetch<BK>(B, d.ldb, d.N, n0, k_begin, k_end, bvec, pb);
+    gb_put<AK>(As[0], pa);
+    gb_put<BK>(Bs[0], pb);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = k_begin; k0 < k_end; k0 += GB_K) {
+        const bool more = k0 + GB_K < k_end;
+        if (more) {
+            gb_fetch<AK>(A, d.lda, d.M, m0, k0 + GB_K, k_end, avec, pa);
+            gb_fetch<BK>(B, d.ldb, d.N, n0, k0 + GB_K, k_end, bvec, pb);
+        }
+        const __bf16* as = As[buf] + (wm * 64 + r) * GB_PITCH + 8 * g;
+        const __bf16* bs = Bs[buf] + (wn * 64 + r) * GB_PITCH + 8 * g;
+        bf16x8_t a[4], b[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            a[t] = *reinterpret_cast<const bf16x8_t*>(as + 16 * t * GB_PITCH);
+            b[t] = *reinterpret_cast<const bf16x8_t*>(bs + 16 * t * GB_PITCH);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+        if (more) {
+            gb_put<AK>(As[buf ^ 1], pa);
+            gb_put<BK>(Bs[buf ^ 1], pb);
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+    gt_store(d, acc, m0 + wm * 64, n0 + wn * 64, z, z1, z2, split, r, g);
 }
 
 // out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order
@@ -166,7 +303,8 @@ void launch_gemm_tiled(hipStream_t s, GemmDesc d) {
     if (d.splits < 1) d.splits = 1;
     if (d.inner < 1) d.inner = 1;
     if (d.batch < 1) d.batch = 1;
-    int k_chunk = ((d.K + d.splits - 1) / d.splits + GT_K - 1) / GT_K * GT_K;
+    const int k_step = d.bf16 ? GB_K : GT_K;
+    int k_chunk = ((d.K + d.splits - 1) / d.splits + k_step - 1) / k_step * k_step;
     d.splits = (d.K + k_chunk - 1) / k_chunk;
     d.k_chunk = k_chunk;
     d.part_stride = (int64_t)d.M * d.N;
@@ -176,7 +314,12 @@ void launch_gemm_tiled(hipStream_t s, GemmDesc d) {
     d.a_vec = aligned(d.A, d.lda, d.sa1, d.sa2) ? 1 : 0;
     d.b_vec = aligned(d.B, d.ldb, d.sb1, d.sb2) ? 1 : 0;
     dim3 grid((d.N + GT_TILE - 1) / GT_TILE, (d.M + GT_TILE - 1) / GT_TILE, d.batch * d.splits);
-    if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, true>), grid, dim3(256), 0, s, d);
+    if (d.bf16) {
+        if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_bf16_kernel<true, true>), grid, dim3(256), 0, s, d);
+        else if (d.a_kmajor) hipLaunchKernelGGL((gemm_bf16_kernel<true, false>), grid, dim3(256), 0, s, d);
+        else if (d.b_kmajor) hipLaunchKernelGGL((gemm_bf16_kernel<false, true>), grid, dim3(256), 0, s, d);
+        else hipLaunchKernelGGL((gemm_bf16_kernel<false, false>), grid, dim3(256), 0, s, d);
+    } else if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, true>), grid, dim3(256), 0, s, d);
     else if (d.a_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, false>), grid, dim3(256), 0, s, d);
     else if (d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<false, true>), grid, dim3(256), 0, s, d);
     else hipLaunchKernelGGL((gemm_tiled_kernel<false, false>), grid, dim3(256), 0, s, d);

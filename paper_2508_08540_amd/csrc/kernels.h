@@ -184,6 +184,7 @@ struct GemmDesc {
     int M, N, K, lda, ldb, ldc;
     int a_kmajor, b_kmajor;
     int batch, inner, splits;
+    int bf16;   // round both operands to bf16 and use the bf16 matrix instruction
     int64_t sa1, sa2, sb1, sb2, sc1, sc2;
     float alpha;
     // ----

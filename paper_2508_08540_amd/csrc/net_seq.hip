@@ -12,7 +12,7 @@
 
 namespace {
 
-constexpr int SCORE_SEQS = 32;   // sequences scored together (the logits of one chunk are chunk * L * V floats)
+constexpr int SCORE_SEQS = 128;  // sequences scored together: 16384 tokens fill the chip in every product (logits: 2 GiB at a 32000-word vocabulary)
 
 struct LayerAct {
     float *q, *k, *v, *p, *ctx, *r1, *st1, *h1, *u, *g, *r2, *st2;
@@ -107,7 +107,7 @@ size_t scratch_bytes(const bls_model* m, int B, bool train) {
 }
 
 // y[T][n_out] = x[T][n_in] W^T + b (+ R)
-void linear(bls_ctx* ctx, hipStream_t st, const float* x, int64_t T, int n_in, const float* W, const float* b, int n_out, float* y,
+void linear(bls_ctx* ctx, hipStream_t st, int bf16, const float* x, int64_t T, int n_in, const float* W, const float* b, int n_out, float* y,
             const float* R = nullptr) {
     GemmDesc d{};
     d.A = x; d.lda = n_in;
@@ -116,11 +116,12 @@ void linear(bls_ctx* ctx, hipStream_t st, const float* x, int64_t T, int n_in, c
     d.bias = b; d.R = R;
     d.M = (int)T; d.N = n_out; d.K = n_in;
     d.alpha = 1.f;
+    d.bf16 = bf16;
     PROF(ctx, PROF_GEMM, launch_gemm_tiled(st, d));
 }
 
 // dx[T][n_in] = dy[T][n_out] W (+ R)
-void linear_dgrad(bls_ctx* ctx, hipStream_t st, const float* dy, int64_t T, int n_out, const float* W, int n_in, float* dx,
+void linear_dgrad(bls_ctx* ctx, hipStream_t st, int bf16, const float* dy, int64_t T, int n_out, const float* W, int n_in, float* dx,
                   const float* R = nullptr) {
     GemmDesc d{};
     d.A = dy; d.lda = n_out;
@@ -129,17 +130,19 @@ void linear_dgrad(bls_ctx* ctx, hipStream_t st, const float* dy, int64_t T, int 
     d.R = R;
     d.M = (int)T; d.N = n_in; d.K = n_out;
     d.alpha = 1.f;
+    d.bf16 = bf16;
     PROF(ctx, PROF_GEMM, launch_gemm_tiled(st, d));
 }
 
 // dW[n_out][n_in] = dy^T x, contraction over the T tokens
-void linear_wgrad(bls_ctx* ctx, hipStream_t st, const float* dy, const float* x, int64_t T, int n_out, int n_in, float* dW, float* part) {
+void linear_wgrad(bls_ctx* ctx, hipStream_t st, int bf16, const float* dy, const float* x, int64_t T, int n_out, int n_in, float* dW, float* part) {
     GemmDesc d{};
     d.A = dy; d.lda = n_out; d.a_kmajor = 1;
     d.B = x; d.ldb = n_in; d.b_kmajor = 1;
     d.C = dW; d.ldc = n_in;
     d.M = n_out; d.N = n_in; d.K = (int)T;
     d.alpha = 1.f;
+    d.bf16 = bf16;
     d.splits = wgrad_splits(n_out, n_in, T);
     d.part = part;
     PROF(ctx, PROF_CONV_WGRAD, launch_gemm_tiled(st, d));
@@ -167,6 +170,7 @@ void attention_gemm(bls_ctx* ctx, hipStream_t st, const bls_model* m, int B, Sli
     d.M = L; d.N = N; d.K = K;
     d.batch = B * H; d.inner = H;
     d.alpha = alpha;
+    d.bf16 = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
     PROF(ctx, PROF_GEMM, launch_gemm_tiled(st, d));
 }
 
@@ -184,23 +188,24 @@ __global__ __launch_bounds__(256) void gather_sequences_kernel(const int32_t* __
 // Encoder output for the tokens in `tok`; with keep the per-layer activations stay for the backward pass.
 void forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, const int32_t* tok, int B, SeqScratch& s, bool keep) {
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, dh = D / H;
+    const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
     const int64_t T = (int64_t)B * L;
     PROF(ctx, PROF_GATHER, launch_embed(st, tok, T, L, D, params + m->enc_tok, params + m->enc_pos, s.x[0]));
     for (size_t l = 0; l < m->enc_layers.size(); ++l) {
         const EncLayer& e = m->enc_layers[l];
         const LayerAct& a = s.act[l];
         const float* x = s.x[l];
-        linear(ctx, st, x, T, D, params + e.wq, params + e.bq, D, a.q);
-        linear(ctx, st, x, T, D, params + e.wk, params + e.bk, D, a.k);
-        linear(ctx, st, x, T, D, params + e.wv, params + e.bv, D, a.v);
+        linear(ctx, st, bf, x, T, D, params + e.wq, params + e.bq, D, a.q);
+        linear(ctx, st, bf, x, T, D, params + e.wk, params + e.bk, D, a.k);
+        linear(ctx, st, bf, x, T, D, params + e.wv, params + e.bv, D, a.v);
         attention_gemm(ctx, st, m, B, {a.q, false, false}, {a.k, false, false}, a.p, true, L, dh, 1.f / sqrtf((float)dh));
         PROF(ctx, PROF_NORM, launch_softmax_rows(st, a.p, (int64_t)B * H * L, L));
         attention_gemm(ctx, st, m, B, {a.p, true, false}, {a.v, false, true}, a.ctx, false, dh, L, 1.f);
-        linear(ctx, st, a.ctx, T, D, params + e.wo, params + e.bo, D, a.r1, x);
+        linear(ctx, st, bf, a.ctx, T, D, params + e.wo, params + e.bo, D, a.r1, x);
         PROF(ctx, PROF_NORM, launch_layernorm(st, a.r1, T, D, params + e.ln1_g, params + e.ln1_b, a.h1, keep ? a.st1 : nullptr));
-        linear(ctx, st, a.h1, T, D, params + e.w1, params + e.b1, F, a.u);
+        linear(ctx, st, bf, a.h1, T, D, params + e.w1, params + e.b1, F, a.u);
         PROF(ctx, PROF_NORM, launch_gelu(st, a.u, a.g, T * F));
-        linear(ctx, st, a.g, T, F, params + e.w2, params + e.b2, D, a.r2, a.h1);
+        linear(ctx, st, bf, a.g, T, F, params + e.w2, params + e.b2, D, a.r2, a.h1);
         PROF(ctx, PROF_NORM, launch_layernorm(st, a.r2, T, D, params + e.ln2_g, params + e.ln2_b, s.x[l + 1], keep ? a.st2 : nullptr));
     }
 }
@@ -215,11 +220,12 @@ int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32
     Carver c(ctx->arena);
     SeqScratch s = carve(c, m, chunk, false);
     const int L = m->enc_L, D = m->enc_D, V = m->enc_V, layers = (int)m->enc_layers.size();
+    const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
     for (int64_t first = 0; first < N; first += chunk) {
         const int B = (int)(N - first < chunk ? N - first : chunk);
         const int64_t T = (int64_t)B * L;
         forward(ctx, st, m, params, x + first * L, B, s, false);
-        linear(ctx, st, s.x[layers], T, D, params + m->enc_head, nullptr, V, s.logits);
+        linear(ctx, st, bf, s.x[layers], T, D, params + m->enc_head, nullptr, V, s.logits);
         PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, y + first * L, T, V, s.tok_loss, 0.f));
         PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, B, L, losses_out + first));
     }
@@ -232,6 +238,7 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     (void)N;
     const int B = (int)batch;
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, V = m->enc_V, dh = D / H, layers = (int)m->enc_layers.size();
+    const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
     const int64_t T = (int64_t)B * L;
     if (T >= (int64_t(1) << 31) / 2 || T * (int64_t)V >= (int64_t(1) << 40))
         return bls_fail(ctx, BLS_EINVAL, "local_step: batch * sequence length too large");
@@ -276,12 +283,12 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
         }
         forward(ctx, st, m, params, s.tok, B, s, true);
         const float* hf = s.x[layers];
-        linear(ctx, st, hf, T, D, params + m->enc_head, nullptr, V, s.logits);
+        linear(ctx, st, bf, hf, T, D, params + m->enc_head, nullptr, V, s.logits);
         PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, s.tgt, T, V, s.tok_loss, gscale));
         PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, B, L, step_losses_out ? step_losses_out + j * B : s.loss));
         // head
-        linear_wgrad(ctx, st, s.logits, hf, T, V, D, s.grad + m->enc_head, s.part);
-        linear_dgrad(ctx, st, s.logits, T, V, params + m->enc_head, D, s.da);
+        linear_wgrad(ctx, st, bf, s.logits, hf, T, V, D, s.grad + m->enc_head, s.part);
+        linear_dgrad(ctx, st, bf, s.logits, T, V, params + m->enc_head, D, s.da);
         for (int l = layers - 1; l >= 0; --l) {
             const EncLayer& e = m->enc_layers[l];
             const LayerAct& a = s.act[l];
@@ -289,20 +296,20 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             // h = LN2(r2): da holds dh, db receives dr2
             PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r2, a.st2, T, D, params + e.ln2_g, s.db, s.acc + sa[l].ln2_g, s.acc + sa[l].ln2_b));
             // r2 = h1 + g W2^T + b2
-            linear_wgrad(ctx, st, s.db, a.g, T, D, F, s.grad + e.w2, s.part);
+            linear_wgrad(ctx, st, bf, s.db, a.g, T, D, F, s.grad + e.w2, s.part);
             PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.db, T, D, s.acc + sa[l].b2));
-            linear_dgrad(ctx, st, s.db, T, D, params + e.w2, F, s.df);
+            linear_dgrad(ctx, st, bf, s.db, T, D, params + e.w2, F, s.df);
             PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df, a.u, T * F));
             // u = h1 W1^T + b1
-            linear_wgrad(ctx, st, s.df, a.h1, T, F, D, s.grad + e.w1, s.part);
+            linear_wgrad(ctx, st, bf, s.df, a.h1, T, F, D, s.grad + e.w1, s.part);
             PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.df, T, F, s.acc + sa[l].b1));
-            linear_dgrad(ctx, st, s.df, T, F, params + e.w1, D, s.da, s.db);   // da = dh1 (both uses of h1)
+            linear_dgrad(ctx, st, bf, s.df, T, F, params + e.w1, D, s.da, s.db);   // da = dh1 (both uses of h1)
             // h1 = LN1(r1): db receives dr1
             PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r1, a.st1, T, D, params + e.ln1_g, s.db, s.acc + sa[l].ln1_g, s.acc + sa[l].ln1_b));
             // r1 = x + ctx Wo^T + bo
-            linear_wgrad(ctx, st, s.db, a.ctx, T, D, D, s.grad + e.wo, s.part);
+            linear_wgrad(ctx, st, bf, s.db, a.ctx, T, D, D, s.grad + e.wo, s.part);
             PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.db, T, D, s.acc + sa[l].bo));
-            linear_dgrad(ctx, st, s.db, T, D, params + e.wo, D, s.dc);          // dc = dctx
+            linear_dgrad(ctx, st, bf, s.db, T, D, params + e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
             attention_gemm(ctx, st, m, B, {a.p, true, true}, {s.dc, false, true}, s.dv, false, dh, L, 1.f);      // dv = P^T dctx
             attention_gemm(ctx, st, m, B, {s.dc, false, false}, {a.v, false, false}, s.ds, true, L, dh, 1.f);    // dP = dctx v^T
@@ -310,15 +317,15 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             attention_gemm(ctx, st, m, B, {s.ds, true, false}, {a.k, false, true}, s.dq, false, dh, L, 1.f);     // dq = dS k
             attention_gemm(ctx, st, m, B, {s.ds, true, true}, {a.q, false, true}, s.dk, false, dh, L, 1.f);      // dk = dS^T q
             // q, k, v projections of x
-            linear_wgrad(ctx, st, s.dq, x, T, D, D, s.grad + e.wq, s.part);
-            linear_wgrad(ctx, st, s.dk, x, T, D, D, s.grad + e.wk, s.part);
-            linear_wgrad(ctx, st, s.dv, x, T, D, D, s.grad + e.wv, s.part);
+            linear_wgrad(ctx, st, bf, s.dq, x, T, D, D, s.grad + e.wq, s.part);
+            linear_wgrad(ctx, st, bf, s.dk, x, T, D, D, s.grad + e.wk, s.part);
+            linear_wgrad(ctx, st, bf, s.dv, x, T, D, D, s.grad + e.wv, s.part);
             PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.dq, T, D, s.acc + sa[l].bq));
             PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.dk, T, D, s.acc + sa[l].bk));
             PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.dv, T, D, s.acc + sa[l].bv));
-            linear_dgrad(ctx, st, s.dq, T, D, params + e.wq, D, s.da, s.db);    // da = dx, starting from the residual path
-            linear_dgrad(ctx, st, s.dk, T, D, params + e.wk, D, s.da, s.da);
-            linear_dgrad(ctx, st, s.dv, T, D, params + e.wv, D, s.da, s.da);
+            linear_dgrad(ctx, st, bf, s.dq, T, D, params + e.wq, D, s.da, s.db);    // da = dx, starting from the residual path
+            linear_dgrad(ctx, st, bf, s.dk, T, D, params + e.wk, D, s.da, s.da);
+            linear_dgrad(ctx, st, bf, s.dv, T, D, params + e.wv, D, s.da, s.da);
         }
         // embeddings: position gradient = sum over samples, token gradient = scatter by id
         PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.da, B, L * D, s.acc + acc_pos));

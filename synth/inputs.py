@@ -27,8 +27,11 @@ WORKLOADS = {
     "wrn16_8_bf16": dict(id=3, model="wrn16_8", act_dtype="bf16", pool=2048, classes=100, k=512, batch=128, tau=4,
                          lr=0.1, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
     # encoder language model: 6 layers, d 512, 8 heads, FFN 2048, vocabulary 32000, sequences of 128 tokens
-    "transformer": dict(id=4, model="transformer", pool=1024, classes=32000, seq_len=128, k=256, batch=64, tau=4, lr=0.001,
-                        momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
+    # (bf16 factors in every matrix product, fp32 sums, storage and master weights; the _fp32 variant multiplies in fp32)
+    "transformer": dict(id=4, model="transformer", act_dtype="bf16", pool=1024, classes=32000, seq_len=128, k=256, batch=64, tau=4,
+                        lr=0.001, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
+    "transformer_fp32": dict(id=4, model="transformer", pool=1024, classes=32000, seq_len=128, k=256, batch=64, tau=4,
+                             lr=0.001, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
 }
 
 

@@ -109,3 +109,33 @@ def test_token_pool_follows_the_zipf_law():
     assert abs((ids == 0).mean() - p0) < 5 * math.sqrt(p0 * (1 - p0) / n)
     p9 = w[:10].sum() / w.sum()
     assert abs((ids < 10).mean() - p9) < 5 * math.sqrt(p9 * (1 - p9) / n)
+
+
+def test_operand_hook_rounds_exactly_the_factors_of_every_product():
+    """Mixed-precision reading: only the two factors of a matrix product are rounded.  Pinned by products worked by hand,
+    by a model whose every factor is already representable (nothing may change), and by counting the hook's calls."""
+    m = T.TransformerLM(20, 4, 8, 2, 8, 1, operand=oracle.round_bf16)
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7 and goes to the even 1; 1 + 3 * 2^-9 is nearest to 1 + 2^-7
+    assert m._mm(np.array([[1.0 + 2.0 ** -8]]), np.array([[3.0]]))[0, 0] == 3.0
+    assert m._mm(np.array([[1.0 + 3 * 2.0 ** -9]]), np.array([[3.0]]))[0, 0] == 3.0 * (1.0 + 2.0 ** -7)
+    assert m._outer_sum(np.full((1, 2, 1), 1.0 + 2.0 ** -8), np.full((1, 2, 1), 0.5))[0, 0] == 1.0
+    # factors that bf16 holds exactly (multiples of 1/8 below 16) are left alone
+    a, b = np.arange(-12, 12).reshape(4, 6) / 8.0, np.arange(30).reshape(6, 5) / 8.0
+    assert np.array_equal(m._mm(a, b), a @ b)
+    # one forward and backward pass calls the hook twice per product: per layer 6 linear + 2 attention products forward,
+    # 6 weight gradients + 6 input gradients + 4 attention products backward; the head adds 1 + 2
+    calls = []
+    counted = T.TransformerLM(20, 4, 8, 2, 8, 2, operand=lambda t: (calls.append(1), t)[1])
+    p = synth.transformer_init(4, 20, 4, 8, 8, 2, perturb=0.1)
+    x, y = synth.token_pool(4, 3, 4, 20)
+    exact = T.TransformerLM(20, 4, 8, 2, 8, 2)
+    l0, g0, _ = oracle.loss_and_grads(exact, p, {}, x, y)
+    l1, g1, _ = oracle.loss_and_grads(counted, p, {}, x, y)
+    assert len(calls) == 2 * (2 * (8 + 16) + 3)
+    assert np.array_equal(l0, l1) and all(np.array_equal(g0[k], g1[k]) for k in g0)   # the identity hook changes nothing
+    # rounding moves losses and gradients by about the bf16 spacing, not more and not zero
+    rounded = T.TransformerLM(20, 4, 8, 2, 8, 2, operand=oracle.round_bf16)
+    l2, g2, _ = oracle.loss_and_grads(rounded, p, {}, x, y)
+    assert 0 < np.abs(l2 - l0).max() < 2e-2 * np.abs(l0).max()
+    err = max(np.linalg.norm(g2[k] - g0[k]) / np.linalg.norm(g0[k]) for k in g0 if not k.endswith("attn.k.bias"))
+    assert 1e-4 < err < 0.15, err
