@@ -1,5 +1,6 @@
 // Tiled fp32 GEMM on the matrix cores for the sequence model: C[m][n] = alpha * sum_k A(m,k) B(n,k) [+ bias[n]] [+ R[m][n]].
 //
+// With G set the epilogue also stores gelu(C) there (erf form); C itself may then be NULL.
 // A(m,k) is A[m*lda + k] or, with a_kmajor, A[k*lda + m]; likewise B(n,k).  With these two flags one kernel serves
 // y = x W^T (both k-contiguous), dx = dy W (B k-major), dW = dy^T x (both k-major, contraction over tokens) and the
 // attention products.  A batch index z = z1 * inner + z2 adds z1*s1 + z2*s2 to each base pointer (heads inside
@@ -62,10 +63,21 @@ __device__ __forceinline__ void gt_put(float* __restrict__ S, const f32x4 (&v)[2
     }
 }
 
+// Workgroups are handed to the eight XCDs (each with its own L2) round-robin in launch order.  When the tile count of
+// one matrix divides by eight, launch slot i takes tile (i % 8) * (tiles / 8) + i / 8, so that an XCD walks a contiguous
+// range of tiles, n fastest: the workgroups that share rows of A run on the same L2, one after the other.
+__device__ __forceinline__ void gt_tile_of_block(int& tile_x, int& tile_y) {
+    const int nx = gridDim.x, tiles = nx * gridDim.y;
+    int id = blockIdx.y * nx + blockIdx.x;
+    if ((tiles & 7) == 0) id = (id & 7) * (tiles >> 3) + (id >> 3);
+    tile_y = id / nx;
+    tile_x = id - tile_y * nx;
+}
+
 // Writes a wave's 64 x 64 block: lane (r, g) holds C[m = .. + 4g + i][n = .. + r] of every 16 x 16 block.
 __device__ __forceinline__ void gt_store(const GemmDesc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, int z, int z1, int z2, int split,
                                          int r, int g) {
-    float* C = d.splits > 1 ? d.part + ((int64_t)z * d.splits + split) * d.part_stride : d.C + z1 * d.sc1 + z2 * d.sc2;
+    float* C = d.splits > 1 ? d.part + ((int64_t)z * d.splits + split) * d.part_stride : d.C ? d.C + z1 * d.sc1 + z2 * d.sc2 : nullptr;
     const int ldc = d.splits > 1 ? d.N : d.ldc;
     const float* R = (d.splits > 1 || !d.R) ? nullptr : d.R + z1 * d.sc1 + z2 * d.sc2;
 #pragma unroll
@@ -81,8 +93,9 @@ __device__ __forceinline__ void gt_store(const GemmDesc& d, const f32x4 (&acc)[4
                         v *= d.alpha;
                         if (d.bias) v += d.bias[n];
                         if (R) v += R[(int64_t)m * ldc + n];
+                        if (d.G) d.G[(int64_t)m * ldc + n] = 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
                     }
-                    C[(int64_t)m * ldc + n] = v;
+                    if (C) C[(int64_t)m * ldc + n] = v;
                 }
             }
 }
@@ -93,7 +106,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmDesc d) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * GT_TILE, n0 = blockIdx.x * GT_TILE;
+    int tile_x, tile_y;
+    gt_tile_of_block(tile_x, tile_y);
+    const int m0 = tile_y * GT_TILE, n0 = tile_x * GT_TILE;
     const int split = blockIdx.z % d.splits, z = blockIdx.z / d.splits;
     const int z1 = z / d.inner, z2 = z - z1 * d.inner;
     const float* A = d.A + z1 * d.sa1 + z2 * d.sa2;
@@ -228,7 +243,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDesc d) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * GT_TILE, n0 = blockIdx.x * GT_TILE;
+    int tile_x, tile_y;
+    gt_tile_of_block(tile_x, tile_y);
+    const int m0 = tile_y * GT_TILE, n0 = tile_x * GT_TILE;
     const int split = blockIdx.z % d.splits, z = blockIdx.z / d.splits;
     const int z1 = z / d.inner, z2 = z - z1 * d.inner;
     const float* A = d.A + z1 * d.sa1 + z2 * d.sa2;

@@ -181,6 +181,7 @@ struct GemmDesc {
     float* C;
     const float *bias, *R;
     float* part;
+    float* G;   // optional second output gelu(C), same layout as C (single matrix, no split)
     int M, N, K, lda, ldb, ldc;
     int a_kmajor, b_kmajor;
     int batch, inner, splits;
@@ -213,7 +214,6 @@ void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const 
                           fixsum_t* acc_g, fixsum_t* acc_b);
 void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale);
-void launch_gelu(hipStream_t s, const float* u, float* g, int64_t n);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n);
 void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale);
 void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss);

@@ -108,12 +108,12 @@ size_t scratch_bytes(const bls_model* m, int B, bool train) {
 
 // y[T][n_out] = x[T][n_in] W^T + b (+ R)
 void linear(bls_ctx* ctx, hipStream_t st, int bf16, const float* x, int64_t T, int n_in, const float* W, const float* b, int n_out, float* y,
-            const float* R = nullptr) {
+            const float* R = nullptr, float* gelu_out = nullptr) {
     GemmDesc d{};
     d.A = x; d.lda = n_in;
     d.B = W; d.ldb = n_in;
     d.C = y; d.ldc = n_out;
-    d.bias = b; d.R = R;
+    d.bias = b; d.R = R; d.G = gelu_out;
     d.M = (int)T; d.N = n_out; d.K = n_in;
     d.alpha = 1.f;
     d.bf16 = bf16;
@@ -203,8 +203,8 @@ void forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* para
         attention_gemm(ctx, st, m, B, {a.p, true, false}, {a.v, false, true}, a.ctx, false, dh, L, 1.f);
         linear(ctx, st, bf, a.ctx, T, D, params + e.wo, params + e.bo, D, a.r1, x);
         PROF(ctx, PROF_NORM, launch_layernorm(st, a.r1, T, D, params + e.ln1_g, params + e.ln1_b, a.h1, keep ? a.st1 : nullptr));
-        linear(ctx, st, bf, a.h1, T, D, params + e.w1, params + e.b1, F, a.u);
-        PROF(ctx, PROF_NORM, launch_gelu(st, a.u, a.g, T * F));
+        // u = h1 W1^T + b1 and g = gelu(u) from one epilogue; scoring does not keep u
+        linear(ctx, st, bf, a.h1, T, D, params + e.w1, params + e.b1, F, keep ? a.u : nullptr, nullptr, a.g);
         linear(ctx, st, bf, a.g, T, F, params + e.w2, params + e.b2, D, a.r2, a.h1);
         PROF(ctx, PROF_NORM, launch_layernorm(st, a.r2, T, D, params + e.ln2_g, params + e.ln2_b, s.x[l + 1], keep ? a.st2 : nullptr));
     }

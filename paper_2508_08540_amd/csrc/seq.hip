@@ -1,5 +1,5 @@
 // Kernels of the sequence model around the GEMMs: embedding lookup and its gradient, layer norm, row softmax,
-// GELU, per-token cross-entropy over a large vocabulary, and column sums.  All activations are fp32 [tokens][D].
+// the GELU derivative (the forward GELU lives in the GEMM epilogue), per-token cross-entropy over a large vocabulary, and column sums.  All activations are fp32 [tokens][D].
 // Sums that cross workgroups (bias, layer-norm and embedding gradients) go through 64-bit fixed-point integer
 // atomics (scale 2^44), so they do not depend on the order of arrival; fix_finalize_kernel turns them into floats.
 #include "kernels.h"
@@ -211,12 +211,8 @@ __global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(float* __restrict
         if (lane + 64 * i < n) dp[rrow * n + lane + 64 * i] = a[i] * (d[i] - dot) * scale;
 }
 
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_df(float x) {
     return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
-}
-__global__ __launch_bounds__(256) void gelu_kernel(const float* __restrict__ u, float* __restrict__ g, int64_t n) {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) g[i] = gelu_f(u[i]);
 }
 // in place on dg: du = dg * gelu'(u)
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(float* __restrict__ dg, const float* __restrict__ u, int64_t n) {
@@ -295,10 +291,6 @@ void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n) {
 }
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale) {
     hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, dp, p, rows, n, scale);
-}
-void launch_gelu(hipStream_t s, const float* u, float* g, int64_t n) {
-    unsigned b = nblk(n, 256);
-    hipLaunchKernelGGL(gelu_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, u, g, n);
 }
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n) {
     unsigned b = nblk(n, 256);
