@@ -207,11 +207,13 @@ struct FixRangeTable {
 };
 void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h);
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok);
-void launch_colsum_fix(hipStream_t s, const float* X, int64_t M, int N, fixsum_t* acc);
+size_t colsum_partial_floats(int64_t M, int N);
+void launch_colsum_tokens(hipStream_t s, const float* X, int64_t M, int N, float* part, float* out);
 void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad);
 void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, float* stats);
+size_t layernorm_bwd_partial_floats(int64_t T, int D);
 void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
-                          fixsum_t* acc_g, fixsum_t* acc_b);
+                          float* part, float* dgb);
 void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n);

@@ -24,7 +24,7 @@ struct SeqScratch {
     std::vector<LayerAct> act;      // one per layer when training, one shared set when scoring
     float *logits, *tok_loss, *loss;
     // training only
-    float *grad, *da, *db, *dc, *dq, *dk, *dv, *df, *ds, *part;
+    float *grad, *da, *db, *dc, *dq, *dk, *dv, *df, *ds, *part, *cpart;
     fixsum_t* acc;
     int64_t acc_count;
     size_t part_floats;
@@ -39,8 +39,6 @@ int wgrad_splits(int M, int N, int64_t K) {
     if (s > 64) s = 64;
     return (int)s;
 }
-
-int64_t small_params_per_layer(const bls_model* m) { return 9 * (int64_t)m->enc_D + m->enc_F; }
 
 SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, V = m->enc_V, layers = (int)m->enc_layers.size();
@@ -95,7 +93,11 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     need(V, D);
     s.part_floats = part;
     s.part = c.take<float>(part ? part : 1);
-    s.acc_count = (int64_t)V * D + (int64_t)L * D + layers * small_params_per_layer(m);
+    size_t cs = colsum_partial_floats(T, F > D ? F : D);
+    const size_t ln = layernorm_bwd_partial_floats(T, D), pos = colsum_partial_floats(B, L * D);
+    cs = cs > ln ? cs : ln;
+    s.cpart = c.take<float>(cs > pos ? cs : pos);
+    s.acc_count = (int64_t)V * D;   // fixed-point accumulators of the token-embedding gradient
     s.acc = c.take<fixsum_t>(s.acc_count);
     return s;
 }
@@ -238,6 +240,8 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     (void)N;
     const int B = (int)batch;
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, V = m->enc_V, dh = D / H, layers = (int)m->enc_layers.size();
+    if (m->enc_layers[0].ln1_b != m->enc_layers[0].ln1_g + D || m->enc_layers[0].ln2_b != m->enc_layers[0].ln2_g + D)
+        return bls_fail(ctx, BLS_EUNSUPPORTED, "local_step: layer-norm scale and shift must be adjacent");
     const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
     const int64_t T = (int64_t)B * L;
     if (T >= (int64_t(1) << 31) / 2 || T * (int64_t)V >= (int64_t(1) << 40))
@@ -248,30 +252,9 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     Carver c(ctx->arena);
     SeqScratch s = carve(c, m, B, true);
 
-    // Accumulator layout: token embedding, position embedding, then per layer bq bk bv bo ln1.g ln1.b b1 b2 ln2.g ln2.b.
-    const int64_t acc_tok = 0, acc_pos = (int64_t)V * D, acc_layers = acc_pos + (int64_t)L * D, per_layer = small_params_per_layer(m);
-    struct SmallAcc {
-        int64_t bq, bk, bv, bo, ln1_g, ln1_b, b1, b2, ln2_g, ln2_b;
-    };
-    std::vector<SmallAcc> sa(layers);
-    FixRangeTable emb_tab{}, small_tab{};
+    FixRangeTable emb_tab{};
     emb_tab.n = 1;
-    emb_tab.r[0] = {acc_tok, m->enc_tok, (int64_t)V * D + (int64_t)L * D};   // the two embeddings are adjacent in both layouts
-    if (m->enc_pos != m->enc_tok + (int64_t)V * D) return bls_fail(ctx, BLS_EUNSUPPORTED, "local_step: embedding layout");
-    if (layers * 10 > FIX_MAX_RANGES) return bls_fail(ctx, BLS_EUNSUPPORTED, "local_step: too many layers");
-    for (int l = 0; l < layers; ++l) {
-        const EncLayer& e = m->enc_layers[l];
-        int64_t o = acc_layers + l * per_layer;
-        auto put = [&](int64_t& slot, int64_t grad_off, int64_t n) {
-            slot = o;
-            small_tab.r[small_tab.n++] = {o, grad_off, n};
-            o += n;
-        };
-        put(sa[l].bq, e.bq, D); put(sa[l].bk, e.bk, D); put(sa[l].bv, e.bv, D); put(sa[l].bo, e.bo, D);
-        put(sa[l].ln1_g, e.ln1_g, D); put(sa[l].ln1_b, e.ln1_b, D);
-        put(sa[l].b1, e.b1, F); put(sa[l].b2, e.b2, D);
-        put(sa[l].ln2_g, e.ln2_g, D); put(sa[l].ln2_b, e.ln2_b, D);
-    }
+    emb_tab.r[0] = {0, m->enc_tok, (int64_t)V * D};
     PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.acc), s.acc_count * 2));
     const float gscale = 1.f / (float)T;   // mean over the batch of per-sample means over positions
     const float att = 1.f / sqrtf((float)dh);
@@ -294,21 +277,21 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             const LayerAct& a = s.act[l];
             const float* x = s.x[l];
             // h = LN2(r2): da holds dh, db receives dr2
-            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r2, a.st2, T, D, params + e.ln2_g, s.db, s.acc + sa[l].ln2_g, s.acc + sa[l].ln2_b));
+            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r2, a.st2, T, D, params + e.ln2_g, s.db, s.cpart, s.grad + e.ln2_g));
             // r2 = h1 + g W2^T + b2
             linear_wgrad(ctx, st, bf, s.db, a.g, T, D, F, s.grad + e.w2, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.db, T, D, s.acc + sa[l].b2));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db, T, D, s.cpart, s.grad + e.b2));
             linear_dgrad(ctx, st, bf, s.db, T, D, params + e.w2, F, s.df);
             PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df, a.u, T * F));
             // u = h1 W1^T + b1
             linear_wgrad(ctx, st, bf, s.df, a.h1, T, F, D, s.grad + e.w1, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.df, T, F, s.acc + sa[l].b1));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.df, T, F, s.cpart, s.grad + e.b1));
             linear_dgrad(ctx, st, bf, s.df, T, F, params + e.w1, D, s.da, s.db);   // da = dh1 (both uses of h1)
             // h1 = LN1(r1): db receives dr1
-            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r1, a.st1, T, D, params + e.ln1_g, s.db, s.acc + sa[l].ln1_g, s.acc + sa[l].ln1_b));
+            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r1, a.st1, T, D, params + e.ln1_g, s.db, s.cpart, s.grad + e.ln1_g));
             // r1 = x + ctx Wo^T + bo
             linear_wgrad(ctx, st, bf, s.db, a.ctx, T, D, D, s.grad + e.wo, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.db, T, D, s.acc + sa[l].bo));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db, T, D, s.cpart, s.grad + e.bo));
             linear_dgrad(ctx, st, bf, s.db, T, D, params + e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
             attention_gemm(ctx, st, m, B, {a.p, true, true}, {s.dc, false, true}, s.dv, false, dh, L, 1.f);      // dv = P^T dctx
@@ -320,18 +303,17 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             linear_wgrad(ctx, st, bf, s.dq, x, T, D, D, s.grad + e.wq, s.part);
             linear_wgrad(ctx, st, bf, s.dk, x, T, D, D, s.grad + e.wk, s.part);
             linear_wgrad(ctx, st, bf, s.dv, x, T, D, D, s.grad + e.wv, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.dq, T, D, s.acc + sa[l].bq));
-            PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.dk, T, D, s.acc + sa[l].bk));
-            PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.dv, T, D, s.acc + sa[l].bv));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dq, T, D, s.cpart, s.grad + e.bq));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dk, T, D, s.cpart, s.grad + e.bk));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dv, T, D, s.cpart, s.grad + e.bv));
             linear_dgrad(ctx, st, bf, s.dq, T, D, params + e.wq, D, s.da, s.db);    // da = dx, starting from the residual path
             linear_dgrad(ctx, st, bf, s.dk, T, D, params + e.wk, D, s.da, s.da);
             linear_dgrad(ctx, st, bf, s.dv, T, D, params + e.wv, D, s.da, s.da);
         }
         // embeddings: position gradient = sum over samples, token gradient = scatter by id
-        PROF(ctx, PROF_NORM, launch_colsum_fix(st, s.da, B, L * D, s.acc + acc_pos));
-        PROF(ctx, PROF_NORM, launch_embed_grad(st, s.tok, T, D, s.da, s.acc + acc_tok));
+        PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.da, B, L * D, s.cpart, s.grad + m->enc_pos));
+        PROF(ctx, PROF_NORM, launch_embed_grad(st, s.tok, T, D, s.da, s.acc));
         PROF(ctx, PROF_UPDATE, launch_fix_finalize(st, emb_tab, s.acc, s.grad));
-        PROF(ctx, PROF_UPDATE, launch_fix_finalize(st, small_tab, s.acc, s.grad));
         PROF(ctx, PROF_UPDATE, launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay));
     }
     BLS_HIP(ctx, hipGetLastError());

@@ -1,7 +1,9 @@
 // Kernels of the sequence model around the GEMMs: embedding lookup and its gradient, layer norm, row softmax,
 // the GELU derivative (the forward GELU lives in the GEMM epilogue), per-token cross-entropy over a large vocabulary, and column sums.  All activations are fp32 [tokens][D].
-// Sums that cross workgroups (bias, layer-norm and embedding gradients) go through 64-bit fixed-point integer
-// atomics (scale 2^44), so they do not depend on the order of arrival; fix_finalize_kernel turns them into floats.
+// Column sums over tokens (bias and layer-norm gradients, the position-embedding gradient) are taken in two stages
+// with a fixed order: per-workgroup partial rows, then one pass over those.  The token-embedding gradient scatters by
+// token id through 64-bit fixed-point integer atomics (scale 2^44), which do not depend on the order of arrival;
+// fix_finalize_kernel turns them into floats.
 #include "kernels.h"
 
 #define LN_EPS 1e-5f
@@ -40,14 +42,39 @@ __global__ __launch_bounds__(256) void embed_grad_kernel(const int32_t* __restri
     for (int c = lane; c < D; c += 64) fix_add(a + c, dh[t * D + c]);
 }
 
-// acc[n] += sum over rows of X[m][n]; a workgroup takes 64 rows, thread = column
-__global__ __launch_bounds__(256) void colsum_fix_kernel(const float* __restrict__ X, int64_t M, int N, fixsum_t* __restrict__ acc) {
+// part[blockIdx.y][n] = sum of X[m][n] over the 64 rows of the block
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const float* __restrict__ X, int64_t M, int N, float* __restrict__ part) {
     const int n = blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     const int64_t m0 = (int64_t)blockIdx.y * 64, m1 = m0 + 64 < M ? m0 + 64 : M;
-    float s = 0.f;
-    for (int64_t m = m0; m < m1; ++m) s += X[m * N + n];
-    fix_add(acc + n, s);
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int64_t m = m0;
+    for (; m + 3 < m1; m += 4) {
+        s0 += X[m * N + n];
+        s1 += X[(m + 1) * N + n];
+        s2 += X[(m + 2) * N + n];
+        s3 += X[(m + 3) * N + n];
+    }
+    for (; m < m1; ++m) s0 += X[m * N + n];
+    part[(int64_t)blockIdx.y * N + n] = (s0 + s1) + (s2 + s3);
+}
+
+// out[n] = sum over rows of X[r][n]: 64 columns per workgroup, four row slices folded through LDS in a fixed order
+__global__ __launch_bounds__(256) void colsum_rows_kernel(const float* __restrict__ X, int rows, int N, float* __restrict__ out) {
+    __shared__ float red[4][64];
+    const int c = threadIdx.x & 63, sl = threadIdx.x >> 6, n = blockIdx.x * 64 + c;
+    float a0 = 0.f, a1 = 0.f;
+    if (n < N) {
+        int r = sl;
+        for (; r + 4 < rows; r += 8) {
+            a0 += X[(int64_t)r * N + n];
+            a1 += X[(int64_t)(r + 4) * N + n];
+        }
+        if (r < rows) a0 += X[(int64_t)r * N + n];
+    }
+    red[sl][c] = a0 + a1;
+    __syncthreads();
+    if (sl == 0 && n < N) out[n] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
 }
 
 // out[i] = acc[i] / 2^44, acc[i] = 0; blockIdx.y selects a range
@@ -101,12 +128,13 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
     }
 }
 
-// dx = inv * (dxh - mean(dxh) - xhat * mean(dxh * xhat)), dxh = dy * g; acc_g += dy * xhat, acc_b += dy.
-// A wave walks `rows_per_wave` rows and keeps the two column sums of its channels in registers.
+// dx = inv * (dxh - mean(dxh) - xhat * mean(dxh * xhat)), dxh = dy * g.  A wave walks `rows_per_wave` rows and keeps
+// the column sums of dy * xhat and dy for its channels in registers; the four waves fold theirs through LDS and the
+// workgroup writes one row part[blockIdx.x][0 .. D) = sum dy * xhat, [D .. 2D) = sum dy.
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
                                                             const float* __restrict__ stats, int64_t T, int D, const float* __restrict__ g,
-                                                            float* __restrict__ dx, fixsum_t* __restrict__ acc_g, fixsum_t* __restrict__ acc_b,
-                                                            int rows_per_wave) {
+                                                            float* __restrict__ dx, float* __restrict__ part, int rows_per_wave) {
+    __shared__ float red[4][2 * 1024];
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t t0 = w * rows_per_wave, t1 = t0 + rows_per_wave < T ? t0 + rows_per_wave : T;
@@ -150,17 +178,19 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restr
             }
         }
     }
-    if (t0 < T)
+    const int wave = threadIdx.x >> 6;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int c = 4 * (lane + 64 * i);
-            if (c < D)
+    for (int i = 0; i < 4; ++i) {
+        const int c = 4 * (lane + 64 * i);
+        if (c < D)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    fix_add(acc_g + c + j, sg[i][j]);
-                    fix_add(acc_b + c + j, sb[i][j]);
-                }
-        }
+            for (int j = 0; j < 4; ++j) {
+                red[wave][c + j] = sg[i][j];
+                red[wave][D + c + j] = sb[i][j];
+            }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < 2 * D; c += 256) part[(int64_t)blockIdx.x * 2 * D + c] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
 }
 
 // in place: row <- softmax(row); one wave per row of length n <= 1024
@@ -219,33 +249,61 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(float* __restrict__ dg, c
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dg[i] *= gelu_df(u[i]);
 }
 
-// One workgroup per token row of logits [T][V]: tok_loss[t] = logsumexp(z) - z[target]; with grad_scale != 0 the row is
-// overwritten by (softmax(z) - onehot(target)) * grad_scale.  Partial results are combined in a fixed order.
+// Running (max, sum of exp(z - max)) pairs: fold one value or another pair in.
+struct MaxSum {
+    float m, s;
+};
+__device__ __forceinline__ MaxSum fold(MaxSum a, MaxSum b) {
+    const float M = fmaxf(a.m, b.m);
+    const float fa = a.m == M ? 1.f : expf(a.m - M), fb = b.m == M ? 1.f : expf(b.m - M);
+    return {M, a.s * fa + b.s * fb};
+}
+
+// One workgroup per token row of logits [T][V]: tok_loss[t] = logsumexp(z) - z[target], with the maximum and the sum
+// taken in one pass over the row (each thread keeps a running pair, pairs are folded in a fixed order).  With
+// grad_scale != 0 the row is then overwritten by (softmax(z) - onehot(target)) * grad_scale.
 __global__ __launch_bounds__(256) void token_ce_kernel(float* __restrict__ logits, const int32_t* __restrict__ targets, int V,
                                                        float* __restrict__ tok_loss, float grad_scale) {
-    __shared__ float red[4];
+    __shared__ MaxSum red[4];
     const int64_t t = blockIdx.x;
     float* z = logits + t * (int64_t)V;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    float m = -INFINITY;
-    for (int c = threadIdx.x; c < V; c += 256) m = fmaxf(m, z[c]);
-    m = wmax(m);
-    if (lane == 0) red[wave] = m;
+    MaxSum acc = {-INFINITY, 0.f};
+    const bool vec = (V & 3) == 0;   // rows then start on 16-byte boundaries
+    if (vec) {
+        for (int c = 4 * threadIdx.x; c < V; c += 1024) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(z + c);
+            const float m4 = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+            if (m4 > acc.m) {
+                acc.s *= expf(acc.m - m4);
+                acc.m = m4;
+            }
+            acc.s += (expf(v[0] - acc.m) + expf(v[1] - acc.m)) + (expf(v[2] - acc.m) + expf(v[3] - acc.m));
+        }
+    } else {
+        for (int c = threadIdx.x; c < V; c += 256) acc = fold(acc, MaxSum{z[c], 1.f});
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) acc = fold(acc, MaxSum{__shfl_xor(acc.m, o, 64), __shfl_xor(acc.s, o, 64)});
+    if (lane == 0) red[wave] = acc;
     __syncthreads();
-    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    float s = 0.f;
-    for (int c = threadIdx.x; c < V; c += 256) s += expf(z[c] - m);
-    s = wsum(s);
-    if (lane == 0) red[wave] = s;
-    __syncthreads();
-    s = (red[0] + red[1]) + (red[2] + red[3]);
+    acc = fold(fold(red[0], red[1]), fold(red[2], red[3]));
+    const float m = acc.m, s = acc.s;
     const int tgt = targets[t];
     if (threadIdx.x == 0) tok_loss[t] = (m + logf(s)) - z[tgt];
     if (grad_scale != 0.f) {
         __syncthreads();  // z[tgt] has been read
         const float inv = 1.f / s;
-        for (int c = threadIdx.x; c < V; c += 256) z[c] = (expf(z[c] - m) * inv - (c == tgt ? 1.f : 0.f)) * grad_scale;
+        if (vec) {
+            for (int c = 4 * threadIdx.x; c < V; c += 1024) {
+                f32x4 v = *reinterpret_cast<const f32x4*>(z + c);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = (expf(v[j] - m) * inv - (c + j == tgt ? 1.f : 0.f)) * grad_scale;
+                *reinterpret_cast<f32x4*>(z + c) = v;
+            }
+        } else {
+            for (int c = threadIdx.x; c < V; c += 256) z[c] = (expf(z[c] - m) * inv - (c == tgt ? 1.f : 0.f)) * grad_scale;
+        }
     }
 }
 
@@ -267,8 +325,15 @@ void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D,
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok) {
     hipLaunchKernelGGL(embed_grad_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, D, dh, acc_tok);
 }
-void launch_colsum_fix(hipStream_t s, const float* X, int64_t M, int N, fixsum_t* acc) {
-    hipLaunchKernelGGL(colsum_fix_kernel, dim3(nblk(N, 256), nblk(M, 64)), dim3(256), 0, s, X, M, N, acc);
+size_t colsum_partial_floats(int64_t M, int N) { return (size_t)nblk(M, 64) * N; }
+// out[n] = sum_m X[m][n]; part holds colsum_partial_floats(M, N) floats
+void launch_colsum_tokens(hipStream_t s, const float* X, int64_t M, int N, float* part, float* out) {
+    if (M <= 64) {
+        hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(N, 64)), dim3(256), 0, s, X, (int)M, N, out);
+        return;
+    }
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(nblk(N, 256), nblk(M, 64)), dim3(256), 0, s, X, M, N, part);
+    hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(N, 64)), dim3(256), 0, s, part, (int)nblk(M, 64), N, out);
 }
 void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad) {
     int64_t longest = 1;
@@ -280,11 +345,14 @@ void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc,
 void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, float* stats) {
     hipLaunchKernelGGL(layernorm_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, x, T, D, g, b, y, stats);
 }
+#define LN_BWD_ROWS_PER_WAVE 4
+size_t layernorm_bwd_partial_floats(int64_t T, int D) { return (size_t)nblk(T, 4 * LN_BWD_ROWS_PER_WAVE) * 2 * D; }
+// dgb[0 .. D) = gradient of the scale, dgb[D .. 2D) = gradient of the shift; part holds layernorm_bwd_partial_floats(T, D)
 void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
-                          fixsum_t* acc_g, fixsum_t* acc_b) {
-    const int rows_per_wave = 8;
-    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(nblk(T, 4 * rows_per_wave)), dim3(256), 0, s, dy, x, stats, T, D, g, dx, acc_g, acc_b,
-                       rows_per_wave);
+                          float* part, float* dgb) {
+    const unsigned wgs = nblk(T, 4 * LN_BWD_ROWS_PER_WAVE);
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, part, LN_BWD_ROWS_PER_WAVE);
+    hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(2 * D, 64)), dim3(256), 0, s, part, (int)wgs, 2 * D, dgb);
 }
 void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n) {
     hipLaunchKernelGGL(softmax_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, sc, rows, n);
