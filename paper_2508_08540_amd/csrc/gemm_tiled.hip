@@ -74,30 +74,41 @@ __device__ __forceinline__ void gt_tile_of_block(int& tile_x, int& tile_y) {
     tile_x = id - tile_y * nx;
 }
 
-// Writes a wave's 64 x 64 block: lane (r, g) holds C[m = .. + 4g + i][n = .. + r] of every 16 x 16 block.
-__device__ __forceinline__ void gt_store(const GemmDesc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, int z, int z1, int z2, int split,
-                                         int r, int g) {
-    float* C = d.splits > 1 ? d.part + ((int64_t)z * d.splits + split) * d.part_stride : d.C ? d.C + z1 * d.sc1 + z2 * d.sc2 : nullptr;
-    const int ldc = d.splits > 1 ? d.N : d.ldc;
-    const float* R = (d.splits > 1 || !d.R) ? nullptr : d.R + z1 * d.sc1 + z2 * d.sc2;
+// Writes a wave's 64 x 64 block: lane (r, g) holds C[m = .. + 4g + i][n = .. + r] of every 16 x 16 block.  Blocks that
+// lie inside C take the path without bounds checks.
+template <bool GUARD>
+__device__ __forceinline__ void gt_store_block(const GemmDesc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, float* C, const float* R,
+                                               int ldc, bool plain, int r, int g) {
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < 4; ++nt) {
+            const int n = n_base + nt * 16 + r;
+            const float bias = (!plain && d.bias && (!GUARD || n < d.N)) ? d.bias[n] : 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int m = m_base + mt * 16 + 4 * g + i, n = n_base + nt * 16 + r;
-                if (m < d.M && n < d.N) {
+                const int m = m_base + mt * 16 + 4 * g + i;
+                if (!GUARD || (m < d.M && n < d.N)) {
                     float v = acc[mt][nt][i];
-                    if (d.splits == 1) {
-                        v *= d.alpha;
-                        if (d.bias) v += d.bias[n];
+                    if (!plain) {
+                        v = v * d.alpha + bias;
                         if (R) v += R[(int64_t)m * ldc + n];
                         if (d.G) d.G[(int64_t)m * ldc + n] = 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
                     }
                     if (C) C[(int64_t)m * ldc + n] = v;
                 }
             }
+        }
+}
+
+__device__ __forceinline__ void gt_store(const GemmDesc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, int z, int z1, int z2, int split,
+                                         int r, int g) {
+    const bool plain = d.splits > 1;   // partial sums go out as they are; the reduction applies the epilogue
+    float* C = plain ? d.part + ((int64_t)z * d.splits + split) * d.part_stride : d.C ? d.C + z1 * d.sc1 + z2 * d.sc2 : nullptr;
+    const int ldc = plain ? d.N : d.ldc;
+    const float* R = (plain || !d.R) ? nullptr : d.R + z1 * d.sc1 + z2 * d.sc2;
+    if (m_base + 64 <= d.M && n_base + 64 <= d.N) gt_store_block<false>(d, acc, m_base, n_base, C, R, ldc, plain, r, g);
+    else gt_store_block<true>(d, acc, m_base, n_base, C, R, ldc, plain, r, g);
 }
 
 template <bool AK, bool BK>
@@ -218,6 +229,34 @@ __device__ __forceinline__ void gb_fetch(const float* __restrict__ P, int ld, in
     }
 }
 
+// The same fetch without any bounds check, for operands whose rows allow 16-byte loads and whose K is a multiple of
+// 32: element offsets of the thread's four loads at k = 0 are fixed before the loop.  Rows past the end of the matrix
+// are clamped to the last valid ones: they only feed rows or columns of C that are never stored.
+template <bool KMAJOR>
+__device__ __forceinline__ void gb_offsets(uint32_t (&off)[4], int ld, int rows, int row0) {
+    if (KMAJOR) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kp = (threadIdx.x & 7) + 8 * i, r = min(row0 + 4 * (int)(threadIdx.x >> 3), rows - 4);
+                off[2 * i + h] = (uint32_t)((2 * kp + h) * ld + r);
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int f = threadIdx.x + 256 * i;
+            off[i] = (uint32_t)(min(row0 + (f >> 3), rows - 1) * ld + 4 * (f & 7));
+        }
+    }
+}
+template <bool KMAJOR>
+__device__ __forceinline__ void gb_fetch_fast(const float* __restrict__ P, const uint32_t (&off)[4], int ld, int k, f32x4 (&v)[4]) {
+    const uint32_t step = KMAJOR ? (uint32_t)k * (uint32_t)ld : (uint32_t)k;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const f32x4*>(P + (off[i] + step));
+}
+
 template <bool KMAJOR>
 __device__ __forceinline__ void gb_put(__bf16* __restrict__ S, const f32x4 (&v)[4]) {
     if (KMAJOR) {
@@ -237,7 +276,7 @@ __device__ __forceinline__ void gb_put(__bf16* __restrict__ S, const f32x4 (&v)[
     }
 }
 
-template <bool AK, bool BK>
+template <bool AK, bool BK, bool FAST>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDesc d) {
     __shared__ __attribute__((aligned(16))) __bf16 As[2][GT_TILE * GB_PITCH], Bs[2][GT_TILE * GB_PITCH];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -260,19 +299,38 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDesc d) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // Rows of a matrix whose pitch is a power of two fall into few memory channels at any one k.  Each tile row of C
+    // therefore starts its walk over K at a different step and wraps around, so that the workgroups in flight read
+    // different k ranges; tiles that share rows of A keep the same order.
+    const int steps = (k_end - k_begin + GB_K - 1) / GB_K;
+    const int rot = steps > 0 ? tile_y % steps : 0;
+    auto k_of = [&](int i) {
+        const int sidx = i + rot < steps ? i + rot : i + rot - steps;
+        return k_begin + sidx * GB_K;
+    };
     f32x4 pa[4], pb[4];
-    gb_fetch<AK>(A, d.lda, d.M, m0, k_begin, k_end, avec, pa);
-    gb_fetch<BK>(B, d.ldb, d.N, n0, k_begin, k_end, bvec, pb);
+    uint32_t offa[4], offb[4];
+    if (FAST) {
+        gb_offsets<AK>(offa, d.lda, d.M, m0);
+        gb_offsets<BK>(offb, d.ldb, d.N, n0);
+    }
+    auto fetch = [&](int k) {
+        if (FAST) {
+            gb_fetch_fast<AK>(A, offa, d.lda, k, pa);
+            gb_fetch_fast<BK>(B, offb, d.ldb, k, pb);
+        } else {
+            gb_fetch<AK>(A, d.lda, d.M, m0, k, k_end, avec, pa);
+            gb_fetch<BK>(B, d.ldb, d.N, n0, k, k_end, bvec, pb);
+        }
+    };
+    fetch(k_of(0));
     gb_put<AK>(As[0], pa);
     gb_put<BK>(Bs[0], pb);
     __syncthreads();
     int buf = 0;
-    for (int k0 = k_begin; k0 < k_end; k0 += GB_K) {
-        const bool more = k0 + GB_K < k_end;
-        if (more) {
-            gb_fetch<AK>(A, d.lda, d.M, m0, k0 + GB_K, k_end, avec, pa);
-            gb_fetch<BK>(B, d.ldb, d.N, n0, k0 + GB_K, k_end, bvec, pb);
-        }
+    for (int i = 0; i < steps; ++i) {
+        const bool more = i + 1 < steps;
+        if (more) fetch(k_of(i + 1));
         const __bf16* as = As[buf] + (wm * 64 + r) * GB_PITCH + 8 * g;
         const __bf16* bs = Bs[buf] + (wn * 64 + r) * GB_PITCH + 8 * g;
         bf16x8_t a[4], b[4];
@@ -332,10 +390,20 @@ void launch_gemm_tiled(hipStream_t s, GemmDesc d) {
     d.b_vec = aligned(d.B, d.ldb, d.sb1, d.sb2) ? 1 : 0;
     dim3 grid((d.N + GT_TILE - 1) / GT_TILE, (d.M + GT_TILE - 1) / GT_TILE, d.batch * d.splits);
     if (d.bf16) {
-        if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_bf16_kernel<true, true>), grid, dim3(256), 0, s, d);
-        else if (d.a_kmajor) hipLaunchKernelGGL((gemm_bf16_kernel<true, false>), grid, dim3(256), 0, s, d);
-        else if (d.b_kmajor) hipLaunchKernelGGL((gemm_bf16_kernel<false, true>), grid, dim3(256), 0, s, d);
-        else hipLaunchKernelGGL((gemm_bf16_kernel<false, false>), grid, dim3(256), 0, s, d);
+        // the unchecked fetch needs 16-byte loads on both operands, whole K steps and 32-bit element offsets
+        const int64_t span_a = (int64_t)(d.a_kmajor ? d.K : d.M) * d.lda, span_b = (int64_t)(d.b_kmajor ? d.K : d.N) * d.ldb;
+        const bool fast = d.a_vec && d.b_vec && d.K % GB_K == 0 && (!d.a_kmajor || d.M % 4 == 0) && (!d.b_kmajor || d.N % 4 == 0) &&
+                          d.M >= 4 && d.N >= 4 && span_a < (int64_t(1) << 30) && span_b < (int64_t(1) << 30);
+#define GB_LAUNCH(AKM, BKM)                                                                                   \
+    do {                                                                                                      \
+        if (fast) hipLaunchKernelGGL((gemm_bf16_kernel<AKM, BKM, true>), grid, dim3(256), 0, s, d);            \
+        else hipLaunchKernelGGL((gemm_bf16_kernel<AKM, BKM, false>), grid, dim3(256), 0, s, d);                \
+    } while (0)
+        if (d.a_kmajor && d.b_kmajor) GB_LAUNCH(true, true);
+        else if (d.a_kmajor) GB_LAUNCH(true, false);
+        else if (d.b_kmajor) GB_LAUNCH(false, true);
+        else GB_LAUNCH(false, false);
+#undef GB_LAUNCH
     } else if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, true>), grid, dim3(256), 0, s, d);
     else if (d.a_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, false>), grid, dim3(256), 0, s, d);
     else if (d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<false, true>), grid, dim3(256), 0, s, d);
