@@ -73,9 +73,11 @@ enum { BLS_ACT_F32 = 0, BLS_ACT_BF16 = 1 };
  *                  classes = vocabulary size (2 .. 2^20), image_hw = sequence length (1 .. 1024), hidden = model
  *                  width (multiple of 4, at most 1024), widths[0] = heads (divides hidden), widths[1] = feed-forward
  *                  width (multiple of 4), blocks = layers (1 .. 16); in_channels and widths[2] are ignored.
- *                  Activations are stored in fp32; with BLS_ACT_BF16 both operands of every matrix product
- *                  (linear layers, attention scores and values, and all their gradients) are rounded to bf16,
- *                  nearest even, as they are read, and multiplied on the bf16 matrix cores with fp32 sums.
+ *                  With BLS_ACT_BF16 both factors of every matrix product (linear layers, attention scores and
+ *                  values, and all their gradients) are bf16, rounded to nearest even by the kernel that produces
+ *                  them, and multiplied on the bf16 matrix cores with fp32 sums; tensors that are only ever factors
+ *                  are stored in bf16 alone.  Everything else (residual sums, layer norm, softmax, the GELU
+ *                  derivative, bias and layer-norm gradients, losses, parameters, momentum, the update) is fp32.
  *                  Tensor order: tok_emb, pos_emb; per layer attn.q/k/v/o (weight, bias), ln1, ffn.fc1, ffn.fc2,
  *                  ln2; head.weight. */
 typedef struct {

@@ -172,187 +172,6 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmDesc d) {
     gt_store(d, acc, m0 + wm * 64, n0 + wn * 64, z, z1, z2, split, r, g);
 }
 
-// ---- the same product with both operands rounded to bf16 (nearest even) on the way into LDS --------------------
-// v_mfma_f32_16x16x32_bf16: lane (r, g) supplies A[r][8g .. 8g+7] and B[8g .. 8g+7][r] as eight bf16 and holds
-// C[4g + i][r].  K advances 32 at a time; LDS tiles are bf16 [128 rows][32 k] with a row pitch of 80 bytes, for which
-// the 16-byte operand reads of a quarter wave fall into distinct banks.  Accumulation, epilogue and memory stay fp32.
-#define GB_K 32
-#define GB_PITCH 40   // bf16 elements per LDS row
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){lo, hi}, bf16x2_t));
-}
-
-// Global fetch of a 128 x 32 operand tile into four float4 per thread.  Row-major operands: task f = row * 8 + k-quad.
-// K-major operands: task f takes two adjacent k for four adjacent rows (v[2i] at k, v[2i+1] at k + 1).
-template <bool KMAJOR>
-__device__ __forceinline__ void gb_fetch(const float* __restrict__ P, int ld, int rows, int row0, int k0, int k_end, bool vec, f32x4 (&v)[4]) {
-    if (KMAJOR) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int kp = (threadIdx.x & 7) + 8 * i, r = row0 + 4 * (threadIdx.x >> 3);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int k = k0 + 2 * kp + h;
-                f32x4 t = {0.f, 0.f, 0.f, 0.f};
-                if (k < k_end) {
-                    const float* p = P + (int64_t)k * ld + r;
-                    if (vec && r + 3 < rows) t = *reinterpret_cast<const f32x4*>(p);
-                    else
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (r + j < rows) t[j] = p[j];
-                }
-                v[2 * i + h] = t;
-            }
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = threadIdx.x + 256 * i;
-            const int r = row0 + (f >> 3), k = k0 + 4 * (f & 7);
-            f32x4 t = {0.f, 0.f, 0.f, 0.f};
-            if (r < rows) {
-                const float* p = P + (int64_t)r * ld + k;
-                if (vec && k + 3 < k_end) t = *reinterpret_cast<const f32x4*>(p);
-                else
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (k + j < k_end) t[j] = p[j];
-            }
-            v[i] = t;
-        }
-    }
-}
-
-// The same fetch without any bounds check, for operands whose rows allow 16-byte loads and whose K is a multiple of
-// 32: element offsets of the thread's four loads at k = 0 are fixed before the loop.  Rows past the end of the matrix
-// are clamped to the last valid ones: they only feed rows or columns of C that are never stored.
-template <bool KMAJOR>
-__device__ __forceinline__ void gb_offsets(uint32_t (&off)[4], int ld, int rows, int row0) {
-    if (KMAJOR) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int kp = (threadIdx.x & 7) + 8 * i, r = min(row0 + 4 * (int)(threadIdx.x >> 3), rows - 4);
-                off[2 * i + h] = (uint32_t)((2 * kp + h) * ld + r);
-            }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = threadIdx.x + 256 * i;
-            off[i] = (uint32_t)(min(row0 + (f >> 3), rows - 1) * ld + 4 * (f & 7));
-        }
-    }
-}
-template <bool KMAJOR>
-__device__ __forceinline__ void gb_fetch_fast(const float* __restrict__ P, const uint32_t (&off)[4], int ld, int k, f32x4 (&v)[4]) {
-    const uint32_t step = KMAJOR ? (uint32_t)k * (uint32_t)ld : (uint32_t)k;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const f32x4*>(P + (off[i] + step));
-}
-
-template <bool KMAJOR>
-__device__ __forceinline__ void gb_put(__bf16* __restrict__ S, const f32x4 (&v)[4]) {
-    if (KMAJOR) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int kp = (threadIdx.x & 7) + 8 * i, r = 4 * (threadIdx.x >> 3);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<uint32_t*>(S + (r + j) * GB_PITCH + 2 * kp) = pack_bf16(v[2 * i][j], v[2 * i + 1][j]);
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int f = threadIdx.x + 256 * i;
-            *reinterpret_cast<uint2*>(S + (f >> 3) * GB_PITCH + 4 * (f & 7)) = make_uint2(pack_bf16(v[i][0], v[i][1]), pack_bf16(v[i][2], v[i][3]));
-        }
-    }
-}
-
-template <bool AK, bool BK, bool FAST>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDesc d) {
-    __shared__ __attribute__((aligned(16))) __bf16 As[2][GT_TILE * GB_PITCH], Bs[2][GT_TILE * GB_PITCH];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 15, g = lane >> 4;
-    const int wm = wave >> 1, wn = wave & 1;
-    int tile_x, tile_y;
-    gt_tile_of_block(tile_x, tile_y);
-    const int m0 = tile_y * GT_TILE, n0 = tile_x * GT_TILE;
-    const int split = blockIdx.z % d.splits, z = blockIdx.z / d.splits;
-    const int z1 = z / d.inner, z2 = z - z1 * d.inner;
-    const float* A = d.A + z1 * d.sa1 + z2 * d.sa2;
-    const float* B = d.B + z1 * d.sb1 + z2 * d.sb2;
-    const int k_begin = split * d.k_chunk;
-    const int k_end = min(d.K, k_begin + d.k_chunk);
-    const bool avec = d.a_vec != 0, bvec = d.b_vec != 0;
-
-    f32x4 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Rows of a matrix whose pitch is a power of two fall into few memory channels at any one k.  Each tile row of C
-    // therefore starts its walk over K at a different step and wraps around, so that the workgroups in flight read
-    // different k ranges; tiles that share rows of A keep the same order.
-    const int steps = (k_end - k_begin + GB_K - 1) / GB_K;
-    const int rot = steps > 0 ? tile_y % steps : 0;
-    auto k_of = [&](int i) {
-        const int sidx = i + rot < steps ? i + rot : i + rot - steps;
-        return k_begin + sidx * GB_K;
-    };
-    f32x4 pa[4], pb[4];
-    uint32_t offa[4], offb[4];
-    if (FAST) {
-        gb_offsets<AK>(offa, d.lda, d.M, m0);
-        gb_offsets<BK>(offb, d.ldb, d.N, n0);
-    }
-    auto fetch = [&](int k) {
-        if (FAST) {
-            gb_fetch_fast<AK>(A, offa, d.lda, k, pa);
-            gb_fetch_fast<BK>(B, offb, d.ldb, k, pb);
-        } else {
-            gb_fetch<AK>(A, d.lda, d.M, m0, k, k_end, avec, pa);
-            gb_fetch<BK>(B, d.ldb, d.N, n0, k, k_end, bvec, pb);
-        }
-    };
-    fetch(k_of(0));
-    gb_put<AK>(As[0], pa);
-    gb_put<BK>(Bs[0], pb);
-    __syncthreads();
-    int buf = 0;
-    for (int i = 0; i < steps; ++i) {
-        const bool more = i + 1 < steps;
-        if (more) fetch(k_of(i + 1));
-        const __bf16* as = As[buf] + (wm * 64 + r) * GB_PITCH + 8 * g;
-        const __bf16* bs = Bs[buf] + (wn * 64 + r) * GB_PITCH + 8 * g;
-        bf16x8_t a[4], b[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            a[t] = *reinterpret_cast<const bf16x8_t*>(as + 16 * t * GB_PITCH);
-            b[t] = *reinterpret_cast<const bf16x8_t*>(bs + 16 * t * GB_PITCH);
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
-        if (more) {
-            gb_put<AK>(As[buf ^ 1], pa);
-            gb_put<BK>(Bs[buf ^ 1], pb);
-        }
-        __syncthreads();
-        buf ^= 1;
-    }
-    gt_store(d, acc, m0 + wm * 64, n0 + wn * 64, z, z1, z2, split, r, g);
-}
-
 // out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order
 __global__ __launch_bounds__(256) void gemm_split_reduce_kernel(const float* __restrict__ part, int splits, int M, int N, float alpha,
                                                                 const float* __restrict__ bias, const float* __restrict__ R, int ldc,
@@ -378,7 +197,7 @@ void launch_gemm_tiled(hipStream_t s, GemmDesc d) {
     if (d.splits < 1) d.splits = 1;
     if (d.inner < 1) d.inner = 1;
     if (d.batch < 1) d.batch = 1;
-    const int k_step = d.bf16 ? GB_K : GT_K;
+    const int k_step = GT_K;
     int k_chunk = ((d.K + d.splits - 1) / d.splits + k_step - 1) / k_step * k_step;
     d.splits = (d.K + k_chunk - 1) / k_chunk;
     d.k_chunk = k_chunk;
@@ -389,22 +208,7 @@ void launch_gemm_tiled(hipStream_t s, GemmDesc d) {
     d.a_vec = aligned(d.A, d.lda, d.sa1, d.sa2) ? 1 : 0;
     d.b_vec = aligned(d.B, d.ldb, d.sb1, d.sb2) ? 1 : 0;
     dim3 grid((d.N + GT_TILE - 1) / GT_TILE, (d.M + GT_TILE - 1) / GT_TILE, d.batch * d.splits);
-    if (d.bf16) {
-        // the unchecked fetch needs 16-byte loads on both operands, whole K steps and 32-bit element offsets
-        const int64_t span_a = (int64_t)(d.a_kmajor ? d.K : d.M) * d.lda, span_b = (int64_t)(d.b_kmajor ? d.K : d.N) * d.ldb;
-        const bool fast = d.a_vec && d.b_vec && d.K % GB_K == 0 && (!d.a_kmajor || d.M % 4 == 0) && (!d.b_kmajor || d.N % 4 == 0) &&
-                          d.M >= 4 && d.N >= 4 && span_a < (int64_t(1) << 30) && span_b < (int64_t(1) << 30);
-#define GB_LAUNCH(AKM, BKM)                                                                                   \
-    do {                                                                                                      \
-        if (fast) hipLaunchKernelGGL((gemm_bf16_kernel<AKM, BKM, true>), grid, dim3(256), 0, s, d);            \
-        else hipLaunchKernelGGL((gemm_bf16_kernel<AKM, BKM, false>), grid, dim3(256), 0, s, d);                \
-    } while (0)
-        if (d.a_kmajor && d.b_kmajor) GB_LAUNCH(true, true);
-        else if (d.a_kmajor) GB_LAUNCH(true, false);
-        else if (d.b_kmajor) GB_LAUNCH(false, true);
-        else GB_LAUNCH(false, false);
-#undef GB_LAUNCH
-    } else if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, true>), grid, dim3(256), 0, s, d);
+    if (d.a_kmajor && d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, true>), grid, dim3(256), 0, s, d);
     else if (d.a_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<true, false>), grid, dim3(256), 0, s, d);
     else if (d.b_kmajor) hipLaunchKernelGGL((gemm_tiled_kernel<false, true>), grid, dim3(256), 0, s, d);
     else hipLaunchKernelGGL((gemm_tiled_kernel<false, false>), grid, dim3(256), 0, s, d);

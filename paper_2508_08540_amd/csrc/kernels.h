@@ -185,7 +185,6 @@ struct GemmDesc {
     int M, N, K, lda, ldb, ldc;
     int a_kmajor, b_kmajor;
     int batch, inner, splits;
-    int bf16;   // round both operands to bf16 and use the bf16 matrix instruction
     int64_t sa1, sa2, sb1, sb2, sc1, sc2;
     float alpha;
     // ----
@@ -194,6 +193,27 @@ struct GemmDesc {
 };
 size_t gemm_tiled_partial_floats(int M, int N, int splits);
 void launch_gemm_tiled(hipStream_t s, GemmDesc d);
+
+// ---- gemm16.hip --------------------------------------------------------------------------------------
+// The same product with both operands stored in bf16 (uint16_t bit patterns).  Outputs: C fp32, C16 bf16, G16 = gelu(C)
+// in bf16, any of them NULL; ldc and the batch strides sc1/sc2 apply to all of them and to R.  splits > 1 needs
+// batch == 1 and writes C only.  Fields below the line are filled by the launcher.
+struct Gemm16Desc {
+    const uint16_t *A, *B;
+    float* C;
+    uint16_t *C16, *G16;
+    const float *bias, *R;
+    float* part;
+    int M, N, K, lda, ldb, ldc;
+    int a_kmajor, b_kmajor;
+    int batch, inner, splits;
+    int64_t sa1, sa2, sb1, sb2, sc1, sc2;
+    float alpha;
+    // ----
+    int k_chunk, a_vec, b_vec, c_vec;
+    int64_t part_stride;
+};
+void launch_gemm16(hipStream_t s, Gemm16Desc d);
 
 // ---- seq.hip ------------------------------------------------------------------------------------------
 // Accumulator ranges that fix_finalize turns into gradients: grad[grad_off + i] = acc[acc_off + i] / 2^44, acc cleared.
@@ -205,17 +225,18 @@ struct FixRangeTable {
     int n;
     FixRange r[FIX_MAX_RANGES];
 };
-void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h);
+void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h, uint16_t* h16);
+void launch_to_bf16(hipStream_t s, const float* in, uint16_t* out, int64_t n);
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok);
 size_t colsum_partial_floats(int64_t M, int N);
 void launch_colsum_tokens(hipStream_t s, const float* X, int64_t M, int N, float* part, float* out);
 void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad);
-void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, float* stats);
+void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, uint16_t* y16, float* stats);
 size_t layernorm_bwd_partial_floats(int64_t T, int D);
 void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
-                          float* part, float* dgb);
-void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n);
-void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale);
-void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n);
-void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale);
+                          uint16_t* dx16, float* part, float* dgb);
+void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n);
+void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale);
+void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n);
+void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale, uint16_t* d16);
 void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss);

@@ -1,6 +1,13 @@
 // Transformer encoder language model: scoring and local SGD steps.  Every matrix product (linear layers, attention
-// scores, attention-weighted values, their gradients and the weight gradients) is one launch of the tiled MFMA GEMM;
-// the kernels of seq.hip do the rest.  Activations are fp32 [tokens][width], heads are column slices of width D/H.
+// scores, attention-weighted values, their gradients and the weight gradients) is one launch of a tiled MFMA GEMM;
+// the kernels of seq.hip do the rest.  Activations are [tokens][width], heads are column slices of width D/H.
+//
+// Two modes.  fp32: every tensor is fp32 and the products run on the fp32 matrix instruction.  bf16 factors: every
+// tensor that is a factor of some product also (or only) exists as a bf16 copy, written by the kernel that produces
+// it, and the products read those copies (bf16 matrix instruction, fp32 sums); everything that is not a product -
+// residual sums, layer norm, softmax, GELU derivative, bias and layer-norm gradients, the loss, the parameters and
+// their update - reads and writes fp32.  Tensors that are only ever factors (q, k, v, the attention output, GELU
+// output, the gradients of the attention output, of the scores and of the logits) exist in bf16 alone.
 #include "kernels.h"
 #include "net.h"
 
@@ -14,20 +21,30 @@ namespace {
 
 constexpr int SCORE_SEQS = 128;  // sequences scored together: 16384 tokens fill the chip in every product (logits: 2 GiB at a 32000-word vocabulary)
 
+// A tensor as fp32 (f), as bf16 (h), or both; a NULL member does not exist in this mode.
+struct Mat {
+    float* f = nullptr;
+    uint16_t* h = nullptr;
+};
+
 struct LayerAct {
-    float *q, *k, *v, *p, *ctx, *r1, *st1, *h1, *u, *g, *r2, *st2;
+    Mat q, k, v, p, ctx, h1, g;
+    float *r1, *st1, *u, *r2, *st2;
 };
 
 struct SeqScratch {
+    bool bf = false;
     int32_t *tok, *tgt;
-    std::vector<float*> x;          // x[l] is the input of layer l, x[layers] the encoder output
+    uint16_t* w16;                  // bf16 copy of the parameter vector (bf16 mode)
+    std::vector<Mat> x;             // x[l] is the input of layer l, x[layers] the encoder output
     std::vector<LayerAct> act;      // one per layer when training, one shared set when scoring
     float *logits, *tok_loss, *loss;
     // training only
-    float *grad, *da, *db, *dc, *dq, *dk, *dv, *df, *ds, *part, *cpart;
+    Mat dlogits;                    // fp32 mode: the logits buffer itself
+    Mat db, dc, dq, dk, dv, df, ds;
+    float *grad, *da, *part, *cpart;
     fixsum_t* acc;
     int64_t acc_count;
-    size_t part_floats;
 };
 
 // Splits of the token contraction of a weight gradient so that about two waves of workgroups are in flight.
@@ -40,15 +57,26 @@ int wgrad_splits(int M, int N, int64_t K) {
     return (int)s;
 }
 
+enum Kind { F32_ONLY, BOTH, FACTOR_ONLY };   // FACTOR_ONLY: fp32 in fp32 mode, bf16 alone in bf16 mode
+
+Mat take(Carver& c, bool bf, Kind kind, int64_t n) {
+    Mat m;
+    if (!bf || kind != FACTOR_ONLY) m.f = c.take<float>(n);
+    if (bf && kind != F32_ONLY) m.h = c.take<uint16_t>(n);
+    return m;
+}
+
 SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, V = m->enc_V, layers = (int)m->enc_layers.size();
-    const int64_t T = (int64_t)B * L;
+    const int64_t T = (int64_t)B * L, PP = (int64_t)B * H * L * L;
     SeqScratch s{};
+    const bool bf = s.bf = m->desc.act_dtype == BLS_ACT_BF16;
     s.tok = c.take<int32_t>(T);
     s.tgt = c.take<int32_t>(T);
+    s.w16 = bf ? c.take<uint16_t>(m->num_params) : nullptr;
     const int sets = train ? layers : 1;
     s.x.resize(layers + 1);
-    for (int l = 0; l <= layers; ++l) s.x[l] = (train || l < 2) ? c.take<float>(T * D) : s.x[l - 2];
+    for (int l = 0; l <= layers; ++l) s.x[l] = (train || l < 2) ? take(c, bf, BOTH, T * D) : s.x[l - 2];
     s.act.resize(layers);
     for (int l = 0; l < layers; ++l) {
         if (l >= sets) {
@@ -56,16 +84,16 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
             continue;
         }
         LayerAct& a = s.act[l];
-        a.q = c.take<float>(T * D);
-        a.k = c.take<float>(T * D);
-        a.v = c.take<float>(T * D);
-        a.p = c.take<float>((int64_t)B * H * L * L);
-        a.ctx = c.take<float>(T * D);
+        a.q = take(c, bf, FACTOR_ONLY, T * D);
+        a.k = take(c, bf, FACTOR_ONLY, T * D);
+        a.v = take(c, bf, FACTOR_ONLY, T * D);
+        a.p = take(c, bf, BOTH, PP);
+        a.ctx = take(c, bf, FACTOR_ONLY, T * D);
         a.r1 = c.take<float>(T * D);
         a.st1 = c.take<float>(2 * T);
-        a.h1 = c.take<float>(T * D);
+        a.h1 = take(c, bf, BOTH, T * D);
         a.u = c.take<float>(T * F);
-        a.g = c.take<float>(T * F);
+        a.g = take(c, bf, FACTOR_ONLY, T * F);
         a.r2 = c.take<float>(T * D);
         a.st2 = c.take<float>(2 * T);
     }
@@ -73,15 +101,17 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     s.tok_loss = c.take<float>(T);
     s.loss = c.take<float>(B);
     if (!train) return s;
+    if (bf) s.dlogits.h = c.take<uint16_t>(T * V);
+    else s.dlogits.f = s.logits;
     s.grad = c.take<float>(m->num_params);
     s.da = c.take<float>(T * D);
-    s.db = c.take<float>(T * D);
-    s.dc = c.take<float>(T * D);
-    s.dq = c.take<float>(T * D);
-    s.dk = c.take<float>(T * D);
-    s.dv = c.take<float>(T * D);
-    s.df = c.take<float>(T * F);
-    s.ds = c.take<float>((int64_t)B * H * L * L);
+    s.db = take(c, bf, BOTH, T * D);
+    s.dc = take(c, bf, FACTOR_ONLY, T * D);
+    s.dq = take(c, bf, BOTH, T * D);
+    s.dk = take(c, bf, BOTH, T * D);
+    s.dv = take(c, bf, BOTH, T * D);
+    s.df = take(c, bf, BOTH, T * F);
+    s.ds = take(c, bf, BOTH, PP);
     size_t part = 0;
     auto need = [&](int M, int N) {
         const size_t f = gemm_tiled_partial_floats(M, N, wgrad_splits(M, N, T));
@@ -91,7 +121,6 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     need(F, D);
     need(D, F);
     need(V, D);
-    s.part_floats = part;
     s.part = c.take<float>(part ? part : 1);
     size_t cs = colsum_partial_floats(T, F > D ? F : D);
     const size_t ln = layernorm_bwd_partial_floats(T, D), pos = colsum_partial_floats(B, L * D);
@@ -108,73 +137,137 @@ size_t scratch_bytes(const bls_model* m, int B, bool train) {
     return c.off;
 }
 
-// y[T][n_out] = x[T][n_in] W^T + b (+ R)
-void linear(bls_ctx* ctx, hipStream_t st, int bf16, const float* x, int64_t T, int n_in, const float* W, const float* b, int n_out, float* y,
-            const float* R = nullptr, float* gelu_out = nullptr) {
-    GemmDesc d{};
-    d.A = x; d.lda = n_in;
-    d.B = W; d.ldb = n_in;
-    d.C = y; d.ldc = n_out;
-    d.bias = b; d.R = R; d.G = gelu_out;
-    d.M = (int)T; d.N = n_out; d.K = n_in;
-    d.alpha = 1.f;
-    d.bf16 = bf16;
-    PROF(ctx, PROF_GEMM, launch_gemm_tiled(st, d));
-}
-
-// dx[T][n_in] = dy[T][n_out] W (+ R)
-void linear_dgrad(bls_ctx* ctx, hipStream_t st, int bf16, const float* dy, int64_t T, int n_out, const float* W, int n_in, float* dx,
-                  const float* R = nullptr) {
-    GemmDesc d{};
-    d.A = dy; d.lda = n_out;
-    d.B = W; d.ldb = n_in; d.b_kmajor = 1;
-    d.C = dx; d.ldc = n_in;
-    d.R = R;
-    d.M = (int)T; d.N = n_in; d.K = n_out;
-    d.alpha = 1.f;
-    d.bf16 = bf16;
-    PROF(ctx, PROF_GEMM, launch_gemm_tiled(st, d));
-}
-
-// dW[n_out][n_in] = dy^T x, contraction over the T tokens
-void linear_wgrad(bls_ctx* ctx, hipStream_t st, int bf16, const float* dy, const float* x, int64_t T, int n_out, int n_in, float* dW, float* part) {
-    GemmDesc d{};
-    d.A = dy; d.lda = n_out; d.a_kmajor = 1;
-    d.B = x; d.ldb = n_in; d.b_kmajor = 1;
-    d.C = dW; d.ldc = n_in;
-    d.M = n_out; d.N = n_in; d.K = (int)T;
-    d.alpha = 1.f;
-    d.bf16 = bf16;
-    d.splits = wgrad_splits(n_out, n_in, T);
-    d.part = part;
-    PROF(ctx, PROF_CONV_WGRAD, launch_gemm_tiled(st, d));
-}
-
-// Batched product over (sample, head): matrices are slices of [T][D] activations (row pitch D, head offset D/H) or of
-// the [B][H][L][L] probability tensor.
-struct Slice {
-    const float* p;
-    bool probs;    // [B][H][L][L] tensor, otherwise [T][D] activation
-    bool kmajor;
+// One product C = alpha * A B^T (+ bias) (+ R) in the mode of the scratch: fp32 members and the fp32 GEMM, or bf16
+// members and the bf16 GEMM.  out takes the result in every form it has; gelu (optional) takes gelu(result).
+struct Product {
+    Mat A, B, out, gelu;
+    const float *bias = nullptr, *R = nullptr;
+    float* part = nullptr;
+    int M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
+    bool a_kmajor = false, b_kmajor = false;
+    int batch = 1, inner = 1, splits = 1;
+    int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0;
+    float alpha = 1.f;
 };
-void attention_gemm(bls_ctx* ctx, hipStream_t st, const bls_model* m, int B, Slice a, Slice b, float* c, bool c_probs, int N, int K,
-                    float alpha) {
-    const int L = m->enc_L, D = m->enc_D, H = m->enc_H, dh = D / H;
-    GemmDesc d{};
-    auto strides = [&](bool probs, int& ld, int64_t& s1, int64_t& s2) {
-        ld = probs ? L : D;
-        s1 = probs ? (int64_t)H * L * L : (int64_t)L * D;
-        s2 = probs ? (int64_t)L * L : dh;
-    };
-    d.A = a.p; d.a_kmajor = a.kmajor ? 1 : 0; strides(a.probs, d.lda, d.sa1, d.sa2);
-    d.B = b.p; d.b_kmajor = b.kmajor ? 1 : 0; strides(b.probs, d.ldb, d.sb1, d.sb2);
-    d.C = c; strides(c_probs, d.ldc, d.sc1, d.sc2);
-    d.M = L; d.N = N; d.K = K;
-    d.batch = B * H; d.inner = H;
-    d.alpha = alpha;
-    d.bf16 = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
-    PROF(ctx, PROF_GEMM, launch_gemm_tiled(st, d));
+
+void multiply(bls_ctx* ctx, hipStream_t st, bool bf, const Product& p, int prof_class) {
+    ProfScope prof(ctx, prof_class);
+    if (bf) {
+        Gemm16Desc d{};
+        d.A = p.A.h; d.B = p.B.h; d.C = p.out.f; d.C16 = p.out.h; d.G16 = p.gelu.h;
+        d.bias = p.bias; d.R = p.R; d.part = p.part;
+        d.M = p.M; d.N = p.N; d.K = p.K; d.lda = p.lda; d.ldb = p.ldb; d.ldc = p.ldc;
+        d.a_kmajor = p.a_kmajor; d.b_kmajor = p.b_kmajor;
+        d.batch = p.batch; d.inner = p.inner; d.splits = p.splits;
+        d.sa1 = p.sa1; d.sa2 = p.sa2; d.sb1 = p.sb1; d.sb2 = p.sb2; d.sc1 = p.sc1; d.sc2 = p.sc2;
+        d.alpha = p.alpha;
+        launch_gemm16(st, d);
+    } else {
+        GemmDesc d{};
+        d.A = p.A.f; d.B = p.B.f; d.C = p.out.f; d.G = p.gelu.f;
+        d.bias = p.bias; d.R = p.R; d.part = p.part;
+        d.M = p.M; d.N = p.N; d.K = p.K; d.lda = p.lda; d.ldb = p.ldb; d.ldc = p.ldc;
+        d.a_kmajor = p.a_kmajor; d.b_kmajor = p.b_kmajor;
+        d.batch = p.batch; d.inner = p.inner; d.splits = p.splits;
+        d.sa1 = p.sa1; d.sa2 = p.sa2; d.sb1 = p.sb1; d.sb2 = p.sb2; d.sc1 = p.sc1; d.sc2 = p.sc2;
+        d.alpha = p.alpha;
+        launch_gemm_tiled(st, d);
+    }
 }
+
+struct Net {
+    bls_ctx* ctx;
+    hipStream_t st;
+    const bls_model* m;
+    const float* params;
+    SeqScratch* s;
+    int B;
+
+    Mat weight(int64_t off) const { return Mat{const_cast<float*>(params) + off, s->bf ? s->w16 + off : nullptr}; }
+
+    // y[T][n_out] = x[T][n_in] W^T + b (+ R); gelu (optional) takes gelu(y)
+    void linear(Mat x, int64_t T, int n_in, int64_t w_off, int64_t b_off, int n_out, Mat y, const float* R = nullptr, Mat gelu = Mat{}) const {
+        Product p;
+        p.A = x; p.lda = n_in;
+        p.B = weight(w_off); p.ldb = n_in;
+        p.out = y; p.gelu = gelu; p.ldc = n_out;
+        p.bias = b_off >= 0 ? params + b_off : nullptr;
+        p.R = R;
+        p.M = (int)T; p.N = n_out; p.K = n_in;
+        multiply(ctx, st, s->bf, p, PROF_GEMM);
+    }
+    // dx[T][n_in] = dy[T][n_out] W (+ R)
+    void linear_dgrad(Mat dy, int64_t T, int n_out, int64_t w_off, int n_in, Mat dx, const float* R = nullptr) const {
+        Product p;
+        p.A = dy; p.lda = n_out;
+        p.B = weight(w_off); p.ldb = n_in; p.b_kmajor = true;
+        p.out = dx; p.ldc = n_in;
+        p.R = R;
+        p.M = (int)T; p.N = n_in; p.K = n_out;
+        multiply(ctx, st, s->bf, p, PROF_GEMM);
+    }
+    // dW[n_out][n_in] = dy^T x, contraction over the T tokens
+    void linear_wgrad(Mat dy, Mat x, int64_t T, int n_out, int n_in, int64_t w_off) const {
+        Product p;
+        p.A = dy; p.lda = n_out; p.a_kmajor = true;
+        p.B = x; p.ldb = n_in; p.b_kmajor = true;
+        p.out.f = s->grad + w_off; p.ldc = n_in;
+        p.M = n_out; p.N = n_in; p.K = (int)T;
+        p.splits = wgrad_splits(n_out, n_in, T);
+        p.part = s->part;
+        multiply(ctx, st, s->bf, p, PROF_CONV_WGRAD);
+    }
+    // Batched product over (sample, head): factors and result are slices of [T][D] activations (row pitch D, head
+    // offset D/H) or of a [B][H][L][L] tensor (probs).
+    void attention(Mat a, bool a_probs, bool a_kmajor, Mat b, bool b_probs, bool b_kmajor, Mat c, bool c_probs, int N, int K, float alpha) const {
+        const int L = m->enc_L, D = m->enc_D, H = m->enc_H, dh = D / H;
+        Product p;
+        auto strides = [&](bool probs, int& ld, int64_t& s1, int64_t& s2) {
+            ld = probs ? L : D;
+            s1 = probs ? (int64_t)H * L * L : (int64_t)L * D;
+            s2 = probs ? (int64_t)L * L : dh;
+        };
+        p.A = a; p.a_kmajor = a_kmajor; strides(a_probs, p.lda, p.sa1, p.sa2);
+        p.B = b; p.b_kmajor = b_kmajor; strides(b_probs, p.ldb, p.sb1, p.sb2);
+        p.out = c; strides(c_probs, p.ldc, p.sc1, p.sc2);
+        p.M = L; p.N = N; p.K = K;
+        p.batch = B * H; p.inner = H;
+        p.alpha = alpha;
+        multiply(ctx, st, s->bf, p, PROF_GEMM);
+    }
+
+    // Encoder output for the tokens in `tok`; with keep the per-layer activations stay for the backward pass.
+    void forward(const int32_t* tok, bool keep) const {
+        const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, dh = D / H;
+        const int64_t T = (int64_t)B * L;
+        PROF(ctx, PROF_GATHER, launch_embed(st, tok, T, L, D, params + m->enc_tok, params + m->enc_pos, s->x[0].f, s->x[0].h));
+        for (size_t l = 0; l < m->enc_layers.size(); ++l) {
+            const EncLayer& e = m->enc_layers[l];
+            const LayerAct& a = s->act[l];
+            const Mat x = s->x[l];
+            linear(x, T, D, e.wq, e.bq, D, a.q);
+            linear(x, T, D, e.wk, e.bk, D, a.k);
+            linear(x, T, D, e.wv, e.bv, D, a.v);
+            // scores into the fp32 probability buffer, softmax in place (kept in fp32 only where something reads it)
+            attention(a.q, false, false, a.k, false, false, Mat{a.p.f, nullptr}, true, L, dh, 1.f / sqrtf((float)dh));
+            PROF(ctx, PROF_NORM, launch_softmax_rows(st, a.p.f, a.p.h, keep || !s->bf, (int64_t)B * H * L, L));
+            attention(a.p, true, false, a.v, false, true, a.ctx, false, dh, L, 1.f);
+            linear(a.ctx, T, D, e.wo, e.bo, D, Mat{a.r1, nullptr}, x.f);
+            PROF(ctx, PROF_NORM, launch_layernorm(st, a.r1, T, D, params + e.ln1_g, params + e.ln1_b, a.h1.f, a.h1.h, keep ? a.st1 : nullptr));
+            // u = h1 W1^T + b1 and g = gelu(u) from one epilogue; scoring does not keep u
+            linear(a.h1, T, D, e.w1, e.b1, F, Mat{keep ? a.u : nullptr, nullptr}, nullptr, a.g);
+            linear(a.g, T, F, e.w2, e.b2, D, Mat{a.r2, nullptr}, a.h1.f);
+            PROF(ctx, PROF_NORM, launch_layernorm(st, a.r2, T, D, params + e.ln2_g, params + e.ln2_b, s->x[l + 1].f, s->x[l + 1].h, keep ? a.st2 : nullptr));
+        }
+    }
+
+    // bf16 copies of everything after the embeddings (the embeddings are only ever looked up)
+    void refresh_weight_copies() const {
+        if (!s->bf) return;
+        const int64_t first = m->enc_layers[0].wq;
+        PROF(ctx, PROF_UPDATE, launch_to_bf16(st, params + first, s->w16 + first, m->num_params - first));
+    }
+};
 
 __global__ __launch_bounds__(256) void gather_sequences_kernel(const int32_t* __restrict__ x, const int32_t* __restrict__ y,
                                                                const int32_t* __restrict__ sel, int64_t k, int64_t start, int L,
@@ -184,31 +277,6 @@ __global__ __launch_bounds__(256) void gather_sequences_kernel(const int32_t* __
     for (int l = threadIdx.x; l < L; l += 256) {
         tok[(int64_t)b * L + l] = x[src * L + l];
         tgt[(int64_t)b * L + l] = y[src * L + l];
-    }
-}
-
-// Encoder output for the tokens in `tok`; with keep the per-layer activations stay for the backward pass.
-void forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, const int32_t* tok, int B, SeqScratch& s, bool keep) {
-    const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, dh = D / H;
-    const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
-    const int64_t T = (int64_t)B * L;
-    PROF(ctx, PROF_GATHER, launch_embed(st, tok, T, L, D, params + m->enc_tok, params + m->enc_pos, s.x[0]));
-    for (size_t l = 0; l < m->enc_layers.size(); ++l) {
-        const EncLayer& e = m->enc_layers[l];
-        const LayerAct& a = s.act[l];
-        const float* x = s.x[l];
-        linear(ctx, st, bf, x, T, D, params + e.wq, params + e.bq, D, a.q);
-        linear(ctx, st, bf, x, T, D, params + e.wk, params + e.bk, D, a.k);
-        linear(ctx, st, bf, x, T, D, params + e.wv, params + e.bv, D, a.v);
-        attention_gemm(ctx, st, m, B, {a.q, false, false}, {a.k, false, false}, a.p, true, L, dh, 1.f / sqrtf((float)dh));
-        PROF(ctx, PROF_NORM, launch_softmax_rows(st, a.p, (int64_t)B * H * L, L));
-        attention_gemm(ctx, st, m, B, {a.p, true, false}, {a.v, false, true}, a.ctx, false, dh, L, 1.f);
-        linear(ctx, st, bf, a.ctx, T, D, params + e.wo, params + e.bo, D, a.r1, x);
-        PROF(ctx, PROF_NORM, launch_layernorm(st, a.r1, T, D, params + e.ln1_g, params + e.ln1_b, a.h1, keep ? a.st1 : nullptr));
-        // u = h1 W1^T + b1 and g = gelu(u) from one epilogue; scoring does not keep u
-        linear(ctx, st, bf, a.h1, T, D, params + e.w1, params + e.b1, F, keep ? a.u : nullptr, nullptr, a.g);
-        linear(ctx, st, bf, a.g, T, F, params + e.w2, params + e.b2, D, a.r2, a.h1);
-        PROF(ctx, PROF_NORM, launch_layernorm(st, a.r2, T, D, params + e.ln2_g, params + e.ln2_b, s.x[l + 1], keep ? a.st2 : nullptr));
     }
 }
 
@@ -222,14 +290,15 @@ int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32
     Carver c(ctx->arena);
     SeqScratch s = carve(c, m, chunk, false);
     const int L = m->enc_L, D = m->enc_D, V = m->enc_V, layers = (int)m->enc_layers.size();
-    const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
+    Net net{ctx, st, m, params, &s, chunk};
+    net.refresh_weight_copies();
     for (int64_t first = 0; first < N; first += chunk) {
-        const int B = (int)(N - first < chunk ? N - first : chunk);
-        const int64_t T = (int64_t)B * L;
-        forward(ctx, st, m, params, x + first * L, B, s, false);
-        linear(ctx, st, bf, s.x[layers], T, D, params + m->enc_head, nullptr, V, s.logits);
-        PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, y + first * L, T, V, s.tok_loss, 0.f));
-        PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, B, L, losses_out + first));
+        net.B = (int)(N - first < chunk ? N - first : chunk);
+        const int64_t T = (int64_t)net.B * L;
+        net.forward(x + first * L, false);
+        net.linear(s.x[layers], T, D, m->enc_head, -1, V, Mat{s.logits, nullptr});
+        PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, y + first * L, T, V, s.tok_loss, 0.f, nullptr));
+        PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, net.B, L, losses_out + first));
     }
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
@@ -242,7 +311,6 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, V = m->enc_V, dh = D / H, layers = (int)m->enc_layers.size();
     if (m->enc_layers[0].ln1_b != m->enc_layers[0].ln1_g + D || m->enc_layers[0].ln2_b != m->enc_layers[0].ln2_g + D)
         return bls_fail(ctx, BLS_EUNSUPPORTED, "local_step: layer-norm scale and shift must be adjacent");
-    const int bf = m->desc.act_dtype == BLS_ACT_BF16 ? 1 : 0;
     const int64_t T = (int64_t)B * L;
     if (T >= (int64_t(1) << 31) / 2 || T * (int64_t)V >= (int64_t(1) << 40))
         return bls_fail(ctx, BLS_EINVAL, "local_step: batch * sequence length too large");
@@ -251,6 +319,7 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     hipStream_t st = ctx->stream;
     Carver c(ctx->arena);
     SeqScratch s = carve(c, m, B, true);
+    Net net{ctx, st, m, params, &s, B};
 
     FixRangeTable emb_tab{};
     emb_tab.n = 1;
@@ -258,57 +327,59 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.acc), s.acc_count * 2));
     const float gscale = 1.f / (float)T;   // mean over the batch of per-sample means over positions
     const float att = 1.f / sqrtf((float)dh);
+    const Mat da{s.da, nullptr};
 
     for (int64_t j = 0; j < tau; ++j) {
+        net.refresh_weight_copies();
         {
             ProfScope prof(ctx, PROF_GATHER);
             hipLaunchKernelGGL(gather_sequences_kernel, dim3(B), dim3(256), 0, st, x_pool, y_pool, sel, k, j * B, L, s.tok, s.tgt);
         }
-        forward(ctx, st, m, params, s.tok, B, s, true);
-        const float* hf = s.x[layers];
-        linear(ctx, st, bf, hf, T, D, params + m->enc_head, nullptr, V, s.logits);
-        PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, s.tgt, T, V, s.tok_loss, gscale));
+        net.forward(s.tok, true);
+        const Mat hf = s.x[layers];
+        net.linear(hf, T, D, m->enc_head, -1, V, Mat{s.logits, nullptr});
+        PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, s.tgt, T, V, s.tok_loss, gscale, s.dlogits.h));
         PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, B, L, step_losses_out ? step_losses_out + j * B : s.loss));
         // head
-        linear_wgrad(ctx, st, bf, s.logits, hf, T, V, D, s.grad + m->enc_head, s.part);
-        linear_dgrad(ctx, st, bf, s.logits, T, V, params + m->enc_head, D, s.da);
+        net.linear_wgrad(s.dlogits, hf, T, V, D, m->enc_head);
+        net.linear_dgrad(s.dlogits, T, V, m->enc_head, D, da);
         for (int l = layers - 1; l >= 0; --l) {
             const EncLayer& e = m->enc_layers[l];
             const LayerAct& a = s.act[l];
-            const float* x = s.x[l];
+            const Mat x = s.x[l];
             // h = LN2(r2): da holds dh, db receives dr2
-            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r2, a.st2, T, D, params + e.ln2_g, s.db, s.cpart, s.grad + e.ln2_g));
+            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r2, a.st2, T, D, params + e.ln2_g, s.db.f, s.db.h, s.cpart, s.grad + e.ln2_g));
             // r2 = h1 + g W2^T + b2
-            linear_wgrad(ctx, st, bf, s.db, a.g, T, D, F, s.grad + e.w2, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db, T, D, s.cpart, s.grad + e.b2));
-            linear_dgrad(ctx, st, bf, s.db, T, D, params + e.w2, F, s.df);
-            PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df, a.u, T * F));
+            net.linear_wgrad(s.db, a.g, T, D, F, e.w2);
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db.f, T, D, s.cpart, s.grad + e.b2));
+            net.linear_dgrad(s.db, T, D, e.w2, F, Mat{s.df.f, nullptr});
+            PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df.f, a.u, s.df.h, T * F));
             // u = h1 W1^T + b1
-            linear_wgrad(ctx, st, bf, s.df, a.h1, T, F, D, s.grad + e.w1, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.df, T, F, s.cpart, s.grad + e.b1));
-            linear_dgrad(ctx, st, bf, s.df, T, F, params + e.w1, D, s.da, s.db);   // da = dh1 (both uses of h1)
+            net.linear_wgrad(s.df, a.h1, T, F, D, e.w1);
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.df.f, T, F, s.cpart, s.grad + e.b1));
+            net.linear_dgrad(s.df, T, F, e.w1, D, da, s.db.f);   // da = dh1 (both uses of h1)
             // h1 = LN1(r1): db receives dr1
-            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r1, a.st1, T, D, params + e.ln1_g, s.db, s.cpart, s.grad + e.ln1_g));
+            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r1, a.st1, T, D, params + e.ln1_g, s.db.f, s.db.h, s.cpart, s.grad + e.ln1_g));
             // r1 = x + ctx Wo^T + bo
-            linear_wgrad(ctx, st, bf, s.db, a.ctx, T, D, D, s.grad + e.wo, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db, T, D, s.cpart, s.grad + e.bo));
-            linear_dgrad(ctx, st, bf, s.db, T, D, params + e.wo, D, s.dc);          // dc = dctx
+            net.linear_wgrad(s.db, a.ctx, T, D, D, e.wo);
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db.f, T, D, s.cpart, s.grad + e.bo));
+            net.linear_dgrad(s.db, T, D, e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
-            attention_gemm(ctx, st, m, B, {a.p, true, true}, {s.dc, false, true}, s.dv, false, dh, L, 1.f);      // dv = P^T dctx
-            attention_gemm(ctx, st, m, B, {s.dc, false, false}, {a.v, false, false}, s.ds, true, L, dh, 1.f);    // dP = dctx v^T
-            PROF(ctx, PROF_NORM, launch_softmax_bwd_rows(st, s.ds, a.p, (int64_t)B * H * L, L, att));
-            attention_gemm(ctx, st, m, B, {s.ds, true, false}, {a.k, false, true}, s.dq, false, dh, L, 1.f);     // dq = dS k
-            attention_gemm(ctx, st, m, B, {s.ds, true, true}, {a.q, false, true}, s.dk, false, dh, L, 1.f);      // dk = dS^T q
+            net.attention(a.p, true, true, s.dc, false, true, s.dv, false, dh, L, 1.f);                      // dv = P^T dctx
+            net.attention(s.dc, false, false, a.v, false, false, Mat{s.ds.f, nullptr}, true, L, dh, 1.f);    // dP = dctx v^T
+            PROF(ctx, PROF_NORM, launch_softmax_bwd_rows(st, s.ds.f, a.p.f, s.ds.h, (int64_t)B * H * L, L, att));
+            net.attention(s.ds, true, false, a.k, false, true, s.dq, false, dh, L, 1.f);                     // dq = dS k
+            net.attention(s.ds, true, true, a.q, false, true, s.dk, false, dh, L, 1.f);                      // dk = dS^T q
             // q, k, v projections of x
-            linear_wgrad(ctx, st, bf, s.dq, x, T, D, D, s.grad + e.wq, s.part);
-            linear_wgrad(ctx, st, bf, s.dk, x, T, D, D, s.grad + e.wk, s.part);
-            linear_wgrad(ctx, st, bf, s.dv, x, T, D, D, s.grad + e.wv, s.part);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dq, T, D, s.cpart, s.grad + e.bq));
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dk, T, D, s.cpart, s.grad + e.bk));
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dv, T, D, s.cpart, s.grad + e.bv));
-            linear_dgrad(ctx, st, bf, s.dq, T, D, params + e.wq, D, s.da, s.db);    // da = dx, starting from the residual path
-            linear_dgrad(ctx, st, bf, s.dk, T, D, params + e.wk, D, s.da, s.da);
-            linear_dgrad(ctx, st, bf, s.dv, T, D, params + e.wv, D, s.da, s.da);
+            net.linear_wgrad(s.dq, x, T, D, D, e.wq);
+            net.linear_wgrad(s.dk, x, T, D, D, e.wk);
+            net.linear_wgrad(s.dv, x, T, D, D, e.wv);
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dq.f, T, D, s.cpart, s.grad + e.bq));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dk.f, T, D, s.cpart, s.grad + e.bk));
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dv.f, T, D, s.cpart, s.grad + e.bv));
+            net.linear_dgrad(s.dq, T, D, e.wq, D, da, s.db.f);    // da = dx, starting from the residual path
+            net.linear_dgrad(s.dk, T, D, e.wk, D, da, s.da);
+            net.linear_dgrad(s.dv, T, D, e.wv, D, da, s.da);
         }
         // embeddings: position gradient = sum over samples, token gradient = scatter by id
         PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.da, B, L * D, s.cpart, s.grad + m->enc_pos));

@@ -18,18 +18,32 @@ __device__ __forceinline__ float wmax(float v) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
     return v;
 }
+typedef __bf16 sq_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float sq_f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t sq_u32x2 __attribute__((ext_vector_type(2)));
+// two floats -> two bf16 (nearest even) in one word, the first in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((sq_f32x2){lo, hi}, sq_bf16x2));
+}
+__device__ __forceinline__ uint16_t to_bf16(float v) { return (uint16_t)(pack_bf16x2(v, 0.f) & 0xffffu); }
+__device__ __forceinline__ void store_bf16x4(uint16_t* p, f32x4 v) {
+    *reinterpret_cast<sq_u32x2*>(p) = sq_u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+}
 __device__ __forceinline__ void fix_add(fixsum_t* p, float v) { atomicAdd(p, (fixsum_t)__double2ll_rn((double)v * FIX_BWD_SCALE)); }
 
 // h[t][:] = tok_emb[token[t]][:] + pos_emb[t % L][:]; one wave per token, D % 4 == 0
 __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ tokens, int64_t T, int L, int D, const float* __restrict__ tok,
-                                                    const float* __restrict__ pos, float* __restrict__ h) {
+                                                    const float* __restrict__ pos, float* __restrict__ h, uint16_t* __restrict__ h16) {
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     const int lane = threadIdx.x & 63;
     const float* e = tok + (int64_t)tokens[t] * D;
     const float* p = pos + (int64_t)(t % L) * D;
-    for (int c = 4 * lane; c < D; c += 256)
-        *reinterpret_cast<f32x4*>(h + t * D + c) = *reinterpret_cast<const f32x4*>(e + c) + *reinterpret_cast<const f32x4*>(p + c);
+    for (int c = 4 * lane; c < D; c += 256) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(e + c) + *reinterpret_cast<const f32x4*>(p + c);
+        *reinterpret_cast<f32x4*>(h + t * D + c) = v;
+        if (h16) store_bf16x4(h16 + t * D + c, v);
+    }
 }
 
 // acc_tok[token[t]][:] += dh[t][:] (fixed point)
@@ -88,7 +102,8 @@ __global__ __launch_bounds__(256) void fix_finalize_kernel(FixRangeTable tab, fi
 
 // y = (x - mean) * invstd * g + b per row; stats[row] = (mean, invstd); one wave per row, D <= 1024, D % 4 == 0
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, int64_t T, int D, const float* __restrict__ g,
-                                                        const float* __restrict__ b, float* __restrict__ y, float* __restrict__ stats) {
+                                                        const float* __restrict__ b, float* __restrict__ y, uint16_t* __restrict__ y16,
+                                                        float* __restrict__ stats) {
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     const int lane = threadIdx.x & 63;
@@ -120,6 +135,7 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] = (v[i][j] - mean) * inv * gg[j] + bb[j];
             *reinterpret_cast<f32x4*>(y + t * D + c) = o;
+            if (y16) store_bf16x4(y16 + t * D + c, o);
         }
     }
     if (stats && lane == 0) {
@@ -133,7 +149,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 // workgroup writes one row part[blockIdx.x][0 .. D) = sum dy * xhat, [D .. 2D) = sum dy.
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
                                                             const float* __restrict__ stats, int64_t T, int D, const float* __restrict__ g,
-                                                            float* __restrict__ dx, float* __restrict__ part, int rows_per_wave) {
+                                                            float* __restrict__ dx, uint16_t* __restrict__ dx16, float* __restrict__ part,
+                                                            int rows_per_wave) {
     __shared__ float red[4][2 * 1024];
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -175,6 +192,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restr
 #pragma unroll
                 for (int j = 0; j < 4; ++j) o[j] = inv * (dh[i][j] - m1 - xh[i][j] * m2);
                 *reinterpret_cast<f32x4*>(dx + t * D + c) = o;
+                if (dx16) store_bf16x4(dx16 + t * D + c, o);
             }
         }
     }
@@ -193,8 +211,9 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restr
     for (int c = threadIdx.x; c < 2 * D; c += 256) part[(int64_t)blockIdx.x * 2 * D + c] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
 }
 
-// in place: row <- softmax(row); one wave per row of length n <= 1024
-__global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ s, int64_t rows, int n) {
+// row <- softmax(row), in place when store_f32 is set, and/or as bf16 into p16; one wave per row of length n <= 1024
+__global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ s, uint16_t* __restrict__ p16, int store_f32, int64_t rows,
+                                                           int n) {
     const int64_t rrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (rrow >= rows) return;
     const int lane = threadIdx.x & 63;
@@ -217,12 +236,16 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ s
     sum = wsum(sum);
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-        if (lane + 64 * i < n) p[lane + 64 * i] = v[i] / sum;
+        if (lane + 64 * i < n) {
+            const float q = v[i] / sum;
+            if (store_f32) p[lane + 64 * i] = q;
+            if (p16) p16[rrow * n + lane + 64 * i] = to_bf16(q);
+        }
 }
 
-// in place on dp: ds = p * (dp - sum_j dp_j p_j) * scale
-__global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(float* __restrict__ dp, const float* __restrict__ p, int64_t rows, int n,
-                                                               float scale) {
+// ds = p * (dp - sum_j dp_j p_j) * scale, in place on dp, or as bf16 into ds16 when that is given
+__global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(float* __restrict__ dp, const float* __restrict__ p, uint16_t* __restrict__ ds16,
+                                                               int64_t rows, int n, float scale) {
     const int64_t rrow = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (rrow >= rows) return;
     const int lane = threadIdx.x & 63;
@@ -238,15 +261,24 @@ __global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(float* __restrict
     dot = wsum(dot);
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-        if (lane + 64 * i < n) dp[rrow * n + lane + 64 * i] = a[i] * (d[i] - dot) * scale;
+        if (lane + 64 * i < n) {
+            const float q = a[i] * (d[i] - dot) * scale;
+            if (ds16) ds16[rrow * n + lane + 64 * i] = to_bf16(q);
+            else dp[rrow * n + lane + 64 * i] = q;
+        }
 }
 
 __device__ __forceinline__ float gelu_df(float x) {
     return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
 }
 // in place on dg: du = dg * gelu'(u)
-__global__ __launch_bounds__(256) void gelu_bwd_kernel(float* __restrict__ dg, const float* __restrict__ u, int64_t n) {
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dg[i] *= gelu_df(u[i]);
+__global__ __launch_bounds__(256) void gelu_bwd_kernel(float* __restrict__ dg, const float* __restrict__ u, uint16_t* __restrict__ du16,
+                                                       int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const float q = dg[i] * gelu_df(u[i]);
+        dg[i] = q;
+        if (du16) du16[i] = to_bf16(q);
+    }
 }
 
 // Running (max, sum of exp(z - max)) pairs: fold one value or another pair in.
@@ -261,9 +293,10 @@ __device__ __forceinline__ MaxSum fold(MaxSum a, MaxSum b) {
 
 // One workgroup per token row of logits [T][V]: tok_loss[t] = logsumexp(z) - z[target], with the maximum and the sum
 // taken in one pass over the row (each thread keeps a running pair, pairs are folded in a fixed order).  With
-// grad_scale != 0 the row is then overwritten by (softmax(z) - onehot(target)) * grad_scale.
+// grad_scale != 0 the gradient (softmax(z) - onehot(target)) * grad_scale then overwrites the row, or goes to d16 as bf16
+// when that is given (the logits stay).
 __global__ __launch_bounds__(256) void token_ce_kernel(float* __restrict__ logits, const int32_t* __restrict__ targets, int V,
-                                                       float* __restrict__ tok_loss, float grad_scale) {
+                                                       float* __restrict__ tok_loss, float grad_scale, uint16_t* __restrict__ d16) {
     __shared__ MaxSum red[4];
     const int64_t t = blockIdx.x;
     float* z = logits + t * (int64_t)V;
@@ -299,10 +332,15 @@ __global__ __launch_bounds__(256) void token_ce_kernel(float* __restrict__ logit
                 f32x4 v = *reinterpret_cast<const f32x4*>(z + c);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) v[j] = (expf(v[j] - m) * inv - (c + j == tgt ? 1.f : 0.f)) * grad_scale;
-                *reinterpret_cast<f32x4*>(z + c) = v;
+                if (d16) store_bf16x4(d16 + t * (int64_t)V + c, v);
+                else *reinterpret_cast<f32x4*>(z + c) = v;
             }
         } else {
-            for (int c = threadIdx.x; c < V; c += 256) z[c] = (expf(z[c] - m) * inv - (c == tgt ? 1.f : 0.f)) * grad_scale;
+            for (int c = threadIdx.x; c < V; c += 256) {
+                const float q = (expf(z[c] - m) * inv - (c == tgt ? 1.f : 0.f)) * grad_scale;
+                if (d16) d16[t * (int64_t)V + c] = to_bf16(q);
+                else z[c] = q;
+            }
         }
     }
 }
@@ -316,11 +354,22 @@ __global__ __launch_bounds__(64) void sample_mean_kernel(const float* __restrict
     if (lane == 0) loss[b] = s / (float)L;
 }
 
+// out[i] = bf16(in[i]), nearest even: the bf16 copies of the weights
+__global__ __launch_bounds__(256) void to_bf16_kernel(const float* __restrict__ in, uint16_t* __restrict__ out, int64_t n4) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256)
+        store_bf16x4(out + 4 * i, *reinterpret_cast<const f32x4*>(in + 4 * i));
+}
+
 // ---- launchers ---------------------------------------------------------------------------------------
 static unsigned nblk(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
 
-void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h) {
-    hipLaunchKernelGGL(embed_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, L, D, tok, pos, h);
+void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h, uint16_t* h16) {
+    hipLaunchKernelGGL(embed_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, L, D, tok, pos, h, h16);
+}
+// n must be a multiple of 4 and both pointers 16- / 8-byte aligned
+void launch_to_bf16(hipStream_t s, const float* in, uint16_t* out, int64_t n) {
+    unsigned b = nblk(n / 4, 256);
+    hipLaunchKernelGGL(to_bf16_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, in, out, n / 4);
 }
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok) {
     hipLaunchKernelGGL(embed_grad_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, D, dh, acc_tok);
@@ -342,30 +391,30 @@ void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc,
     if (bx > 2048) bx = 2048;
     hipLaunchKernelGGL(fix_finalize_kernel, dim3(bx, tab.n), dim3(256), 0, s, tab, acc, grad);
 }
-void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, float* stats) {
-    hipLaunchKernelGGL(layernorm_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, x, T, D, g, b, y, stats);
+void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const float* g, const float* b, float* y, uint16_t* y16, float* stats) {
+    hipLaunchKernelGGL(layernorm_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, x, T, D, g, b, y, y16, stats);
 }
 #define LN_BWD_ROWS_PER_WAVE 4
 size_t layernorm_bwd_partial_floats(int64_t T, int D) { return (size_t)nblk(T, 4 * LN_BWD_ROWS_PER_WAVE) * 2 * D; }
 // dgb[0 .. D) = gradient of the scale, dgb[D .. 2D) = gradient of the shift; part holds layernorm_bwd_partial_floats(T, D)
 void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
-                          float* part, float* dgb) {
+                          uint16_t* dx16, float* part, float* dgb) {
     const unsigned wgs = nblk(T, 4 * LN_BWD_ROWS_PER_WAVE);
-    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, part, LN_BWD_ROWS_PER_WAVE);
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE);
     hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(2 * D, 64)), dim3(256), 0, s, part, (int)wgs, 2 * D, dgb);
 }
-void launch_softmax_rows(hipStream_t s, float* sc, int64_t rows, int n) {
-    hipLaunchKernelGGL(softmax_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, sc, rows, n);
+void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n) {
+    hipLaunchKernelGGL(softmax_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, sc, p16, store_f32 ? 1 : 0, rows, n);
 }
-void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, int64_t rows, int n, float scale) {
-    hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, dp, p, rows, n, scale);
+void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale) {
+    hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, dp, p, ds16, rows, n, scale);
 }
-void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, int64_t n) {
+void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n) {
     unsigned b = nblk(n, 256);
-    hipLaunchKernelGGL(gelu_bwd_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, dg, u, n);
+    hipLaunchKernelGGL(gelu_bwd_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, dg, u, du16, n);
 }
-void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale) {
-    hipLaunchKernelGGL(token_ce_kernel, dim3((unsigned)T), dim3(256), 0, s, logits, targets, V, tok_loss, grad_scale);
+void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale, uint16_t* d16) {
+    hipLaunchKernelGGL(token_ce_kernel, dim3((unsigned)T), dim3(256), 0, s, logits, targets, V, tok_loss, grad_scale, d16);
 }
 void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss) {
     hipLaunchKernelGGL(sample_mean_kernel, dim3(B), dim3(64), 0, s, tok_loss, L, loss);
