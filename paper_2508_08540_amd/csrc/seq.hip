@@ -243,6 +243,33 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(float* __restrict__ s
         }
 }
 
+// The same for rows of n <= 4 * LPR values with n % 4 == 0: LPR lanes per row, one 16-byte load each, 64 / LPR rows per wave.
+template <int LPR>
+__global__ __launch_bounds__(256) void softmax_short_rows_kernel(float* __restrict__ s, uint16_t* __restrict__ p16, int store_f32, int64_t rows,
+                                                                 int n) {
+    const int lane = threadIdx.x & 63, sub = lane % LPR;
+    const int64_t rrow = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * (64 / LPR) + lane / LPR;
+    const bool live = rrow < rows && 4 * sub < n;
+    f32x4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (live) v = *reinterpret_cast<const f32x4*>(s + rrow * n + 4 * sub);
+    float m = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v[j] = live ? expf(v[j] - m) : 0.f;
+        sum += v[j];
+    }
+#pragma unroll
+    for (int o = LPR / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (!live) return;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = v[j] / sum;
+    if (store_f32) *reinterpret_cast<f32x4*>(s + rrow * n + 4 * sub) = v;
+    if (p16) store_bf16x4(p16 + rrow * n + 4 * sub, v);
+}
+
 // ds = p * (dp - sum_j dp_j p_j) * scale, in place on dp, or as bf16 into ds16 when that is given
 __global__ __launch_bounds__(256) void softmax_bwd_rows_kernel(float* __restrict__ dp, const float* __restrict__ p, uint16_t* __restrict__ ds16,
                                                                int64_t rows, int n, float scale) {
@@ -304,15 +331,25 @@ __global__ __launch_bounds__(256) void token_ce_kernel(float* __restrict__ logit
     MaxSum acc = {-INFINITY, 0.f};
     const bool vec = (V & 3) == 0;   // rows then start on 16-byte boundaries
     if (vec) {
-        for (int c = 4 * threadIdx.x; c < V; c += 1024) {
-            const f32x4 v = *reinterpret_cast<const f32x4*>(z + c);
+        // four loads in flight per thread; the running pair takes them in order
+        auto take = [&](f32x4 v) {
             const float m4 = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
             if (m4 > acc.m) {
                 acc.s *= expf(acc.m - m4);
                 acc.m = m4;
             }
             acc.s += (expf(v[0] - acc.m) + expf(v[1] - acc.m)) + (expf(v[2] - acc.m) + expf(v[3] - acc.m));
+        };
+        int c = 4 * threadIdx.x;
+        for (; c + 3072 < V; c += 4096) {
+            const f32x4 v0 = *reinterpret_cast<const f32x4*>(z + c), v1 = *reinterpret_cast<const f32x4*>(z + c + 1024),
+                        v2 = *reinterpret_cast<const f32x4*>(z + c + 2048), v3 = *reinterpret_cast<const f32x4*>(z + c + 3072);
+            take(v0);
+            take(v1);
+            take(v2);
+            take(v3);
         }
+        for (; c < V; c += 1024) take(*reinterpret_cast<const f32x4*>(z + c));
     } else {
         for (int c = threadIdx.x; c < V; c += 256) acc = fold(acc, MaxSum{z[c], 1.f});
     }
@@ -404,7 +441,13 @@ void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const 
     hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(2 * D, 64)), dim3(256), 0, s, part, (int)wgs, 2 * D, dgb);
 }
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n) {
-    hipLaunchKernelGGL(softmax_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, sc, p16, store_f32 ? 1 : 0, rows, n);
+    const int f = store_f32 ? 1 : 0;
+    if (n % 4 == 0 && n <= 128 && n > 64)
+        hipLaunchKernelGGL(softmax_short_rows_kernel<32>, dim3(nblk(rows, 8)), dim3(256), 0, s, sc, p16, f, rows, n);
+    else if (n % 4 == 0 && n <= 64)
+        hipLaunchKernelGGL(softmax_short_rows_kernel<16>, dim3(nblk(rows, 16)), dim3(256), 0, s, sc, p16, f, rows, n);
+    else
+        hipLaunchKernelGGL(softmax_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, sc, p16, f, rows, n);
 }
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale) {
     hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3(nblk(rows, 4)), dim3(256), 0, s, dp, p, ds16, rows, n, scale);

@@ -42,6 +42,8 @@ SHAPES = [
     (301, 20, 24, 4, 40, 1, 5),      # head width 6 and an odd vocabulary: the unaligned load path
     (1000, 130, 64, 2, 128, 2, 3),   # sequence longer than a tile: two tiles of attention scores, ragged edges
     (700, 16, 256, 8, 1024, 1, 40),  # 640 tokens: several row tiles, split token contraction in the weight gradients
+    (90, 128, 64, 2, 64, 1, 2),      # the measured sequence length: attention rows of 128, two rows per wave in the softmax
+    (64, 72, 32, 4, 48, 1, 3),       # rows of 72: the short-row softmax with idle lanes, head width 8
 ]
 
 
