@@ -614,7 +614,7 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
 // wgrad16.hip: the bf16 matrix-instruction kernel for wide stride-1 layers
 bool wgrad16_covers(int act, const ConvShape& cs);
 int wgrad16_groups(const ConvShape& cs);
-void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas);
+void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt);
 
 // Accumulator replicas of a layer: as many as there are pixel groups, at most WGRAD_REPLICAS.
 int conv_wgrad_replicas(int act, const ConvShape& cs) {
@@ -642,7 +642,7 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
                        const KernelTiming* kt) {
     if (wgrad16_covers(act, cs)) {
-        launch_wgrad16(s, cs, x, dy, gacc, conv_wgrad_replicas(act, cs));
+        launch_wgrad16(s, cs, x, dy, gacc, conv_wgrad_replicas(act, cs), kt);
         return;
     }
     ACT_DISPATCH(act, {

@@ -165,7 +165,8 @@ int wgrad16_groups(const ConvShape& cs) {
     return groups < n_tiles ? groups : n_tiles;
 }
 
-void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas) {
+void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt) {
+    hipEvent_t ev0 = kt ? kt->start : nullptr, ev1 = kt ? kt->stop : nullptr;   // timing events ride on the dispatch itself
     ConvGeom g = wgrad16_geom(cs);
     W16Geom wg;
     wg.lwp = cs.taps == 9 ? cs.h_in + 4 : cs.h_in;
@@ -180,11 +181,11 @@ void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const voi
     dim3 grid(groups, (cs.c_in / 64) * (cs.c_out / 64));
     if (cs.taps == 9) {
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_kernel<9>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL(wgrad16_kernel<9>, grid, dim3(256), lds, s, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg, tiles_per_group, cs.c_in,
-                           cs.c_out, replicas);
+        hipExtLaunchKernelGGL(wgrad16_kernel<9>, grid, dim3(256), lds, s, ev0, ev1, 0, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg,
+                              tiles_per_group, cs.c_in, cs.c_out, replicas);
     } else {
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL(wgrad16_kernel<1>, grid, dim3(256), lds, s, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg, tiles_per_group, cs.c_in,
-                           cs.c_out, replicas);
+        hipExtLaunchKernelGGL(wgrad16_kernel<1>, grid, dim3(256), lds, s, ev0, ev1, 0, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg,
+                              tiles_per_group, cs.c_in, cs.c_out, replicas);
     }
 }

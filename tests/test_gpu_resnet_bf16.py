@@ -184,3 +184,19 @@ def test_mlp_rejects_bf16(env):
     torch, bls, ctx = env
     with pytest.raises(bls.BlsError):
         bls.Model(0, act_dtype="bf16")
+
+
+def test_event_timing_covers_every_dispatch_and_leaves_results_alone(env):
+    """The per-class event timing brackets every launch of a step, also the bf16 weight-gradient kernel of the
+    64-channel layers, and a timed step gives the bits of an untimed one."""
+    torch, bls, ctx = env
+    h = _harness(env, widths=(16, 32, 64), blocks=1, hw=16)
+    p, b, x, y, sel = _case((16, 32, 64), 1, 16, 8)
+    plain = h.local_step(p, b, _zeros(p), x, y, sel, 8, 2, lr=0.05, mu=0.9)
+    ctx.profile_begin()
+    timed = h.local_step(p, b, _zeros(p), x, y, sel, 8, 2, lr=0.05, mu=0.9)
+    prof = ctx.profile_end()
+    assert prof["conv_wgrad"][1] > 0 and prof["conv_wgrad"][0] > 0.0 and prof["conv_fwd"][1] > 0
+    assert all(ms >= 0.0 for ms, _ in prof.values())
+    assert all(np.array_equal(plain[0][k], timed[0][k]) for k in plain[0]) and np.array_equal(plain[3], timed[3])
+    torch.cuda.synchronize()   # an error left behind by the timing would surface here
