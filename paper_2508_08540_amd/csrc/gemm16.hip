@@ -178,7 +178,42 @@ __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4
     }
 }
 
-template <bool AK, bool BK, bool FAST>
+// Softmax statistics of a wave's 64 columns for each of its 64 rows: ce_part[2 * tile_x + wn][m] = (max, sum of
+// exp(v - max)) over the columns that exist, and the value in column ce_targets[m] goes to ce_tlogit[m] when this wave
+// holds it.  A later pass folds the pairs of a row in index order.  The product is taken without bias.
+__device__ __forceinline__ void g16_ce_block(const Gemm16Desc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, int part_idx, int r, int g) {
+    const bool full = n_base + 64 <= d.N;   // uniform: every column of the block exists
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        const int m = m_base + 16 * mt + r;
+        const int tgt = m < d.M ? d.ce_targets[m] : -1;
+        const int t_local = tgt - n_base - 4 * g;   // column of the target among this lane's 16, as 16 nt + i
+        float v[16];
+        float mx = -INFINITY, at_target = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float q = acc[mt][nt][i] * d.alpha;
+                if (!full && n_base + 16 * nt + 4 * g + i >= d.N) q = -INFINITY;
+                v[4 * nt + i] = q;
+                mx = fmaxf(mx, q);
+                at_target = t_local == 16 * nt + i ? q : at_target;
+            }
+        if (t_local >= 0 && t_local < 64 && (t_local & 12) == 0) d.ce_tlogit[m] = at_target;
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        float sum = 0.f;
+        if (mx > -INFINITY)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sum += __expf(v[j] - mx);   // hardware exponential: 64 per lane, the accurate one would double the tile time
+        sum += __shfl_xor(sum, 16, 64);
+        sum += __shfl_xor(sum, 32, 64);
+        if (g == 0 && m < d.M) *reinterpret_cast<f32x2_v*>(d.ce_part + 2 * ((int64_t)part_idx * d.M + m)) = f32x2_v{mx, sum};
+    }
+}
+
+template <bool AK, bool BK, bool FAST, bool CE>
 __global__ __launch_bounds__(256) void gemm16_kernel(Gemm16Desc d) {
     __shared__ __attribute__((aligned(16))) bf16_t As[2][G16_TILE * G16_PITCH], Bs[2][G16_TILE * G16_PITCH];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -262,6 +297,7 @@ __global__ __launch_bounds__(256) void gemm16_kernel(Gemm16Desc d) {
     const float* R = (plain || !d.R) ? nullptr : d.R + zoff;
     const int ldc = plain ? d.N : d.ldc;
     const int m_base = m0 + wm * 64, n_base = n0 + wn * 64;
+    if (CE) g16_ce_block(d, acc, m_base, n_base, 2 * tile_x + wn, r, g);   // its own instantiation: the statistics cost registers
     const bool vec = (plain ? (d.N & 3) == 0 : d.c_vec != 0) && m_base + 64 <= d.M && n_base + 64 <= d.N;
     if (vec) g16_store_block<true>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
     else g16_store_block<false>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
@@ -305,10 +341,14 @@ void launch_gemm16(hipStream_t s, Gemm16Desc d) {
     dim3 grid((d.N + G16_TILE - 1) / G16_TILE, (d.M + G16_TILE - 1) / G16_TILE, d.batch * d.splits);
 #define G16_LAUNCH(AKM, BKM)                                                                             \
     do {                                                                                                 \
-        if (fast) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true>), grid, dim3(256), 0, s, d);          \
-        else hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, false>), grid, dim3(256), 0, s, d);              \
+        if (fast) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, false>), grid, dim3(256), 0, s, d);   \
+        else hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, false, false>), grid, dim3(256), 0, s, d);       \
     } while (0)
-    if (d.a_kmajor && d.b_kmajor) G16_LAUNCH(true, true);
+    if (d.ce_part) {
+        // row statistics: row-major factors, one matrix, no split (the vocabulary projection)
+        if (fast) hipLaunchKernelGGL((gemm16_kernel<false, false, true, true>), grid, dim3(256), 0, s, d);
+        else hipLaunchKernelGGL((gemm16_kernel<false, false, false, true>), grid, dim3(256), 0, s, d);
+    } else if (d.a_kmajor && d.b_kmajor) G16_LAUNCH(true, true);
     else if (d.a_kmajor) G16_LAUNCH(true, false);
     else if (d.b_kmajor) G16_LAUNCH(false, true);
     else G16_LAUNCH(false, false);

@@ -209,6 +209,11 @@ struct Gemm16Desc {
     int batch, inner, splits;
     int64_t sa1, sa2, sb1, sb2, sc1, sc2;
     float alpha;
+    // optional softmax statistics of the rows of C (single matrix, no split): per row and per 64-column block the pair
+    // (max, sum exp(C - max)) into ce_part[2 * ceil(N / 128)][M][2], and C[m][ce_targets[m]] into ce_tlogit[m]
+    float* ce_part;
+    const int32_t* ce_targets;
+    float* ce_tlogit;
     // ----
     int k_chunk, a_vec, b_vec, c_vec;
     int64_t part_stride;
@@ -238,5 +243,11 @@ void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const 
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n);
+// Cross-entropy from the statistics the vocabulary projection left behind: folds the n_parts pairs of a row in index
+// order; tok_loss[t] = max + log(sum) - tlogit[t]; row_stats[t] = (max, sum) if given.
+void launch_ce_combine(hipStream_t s, const float* ce_part, int n_parts, const float* tlogit, int64_t T, float* tok_loss, float* row_stats);
+// d16[t][c] = bf16((exp(logits[t][c] - max_t) / sum_t - [c == target_t]) * grad_scale)
+void launch_ce_grad(hipStream_t s, const float* logits, const int32_t* targets, const float* row_stats, int64_t T, int V, float grad_scale,
+                    uint16_t* d16);
 void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale, uint16_t* d16);
 void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss);

@@ -39,6 +39,8 @@ struct SeqScratch {
     std::vector<Mat> x;             // x[l] is the input of layer l, x[layers] the encoder output
     std::vector<LayerAct> act;      // one per layer when training, one shared set when scoring
     float *logits, *tok_loss, *loss;
+    float *ce_part, *ce_tlogit, *ce_rows;   // bf16 mode: softmax statistics left by the vocabulary projection
+    int ce_parts;
     // training only
     Mat dlogits;                    // fp32 mode: the logits buffer itself
     Mat db, dc, dq, dk, dv, df, ds;
@@ -97,7 +99,12 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         a.r2 = c.take<float>(T * D);
         a.st2 = c.take<float>(2 * T);
     }
-    s.logits = c.take<float>(T * V);
+    // bf16 mode: the vocabulary projection leaves row statistics behind and scoring never stores the logits
+    s.logits = (bf && !train) ? nullptr : c.take<float>(T * V);
+    s.ce_parts = 2 * (int)ceil_div(V, 128);
+    s.ce_part = bf ? c.take<float>(T * s.ce_parts * 2) : nullptr;
+    s.ce_tlogit = bf ? c.take<float>(T) : nullptr;
+    s.ce_rows = bf ? c.take<float>(2 * T) : nullptr;
     s.tok_loss = c.take<float>(T);
     s.loss = c.take<float>(B);
     if (!train) return s;
@@ -148,6 +155,8 @@ struct Product {
     int batch = 1, inner = 1, splits = 1;
     int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0;
     float alpha = 1.f;
+    const int32_t* ce_targets = nullptr;   // bf16 mode only: leave softmax statistics of the rows behind
+    float *ce_part = nullptr, *ce_tlogit = nullptr;
 };
 
 void multiply(bls_ctx* ctx, hipStream_t st, bool bf, const Product& p, int prof_class) {
@@ -161,6 +170,7 @@ void multiply(bls_ctx* ctx, hipStream_t st, bool bf, const Product& p, int prof_
         d.batch = p.batch; d.inner = p.inner; d.splits = p.splits;
         d.sa1 = p.sa1; d.sa2 = p.sa2; d.sb1 = p.sb1; d.sb2 = p.sb2; d.sc1 = p.sc1; d.sc2 = p.sc2;
         d.alpha = p.alpha;
+        d.ce_part = p.ce_part; d.ce_targets = p.ce_targets; d.ce_tlogit = p.ce_tlogit;
         launch_gemm16(st, d);
     } else {
         GemmDesc d{};
@@ -195,6 +205,25 @@ struct Net {
         p.R = R;
         p.M = (int)T; p.N = n_out; p.K = n_in;
         multiply(ctx, st, s->bf, p, PROF_GEMM);
+    }
+    // Per-token losses of the encoder output hf against `targets`; with keep_logits the logits stay in s->logits (and,
+    // in bf16 mode, the row statistics in s->ce_rows) for the gradient.
+    void token_losses(Mat hf, const int32_t* targets, int64_t T, bool keep_logits) const {
+        const int D = m->enc_D, V = m->enc_V;
+        Product p;
+        p.A = hf; p.lda = D;
+        p.B = weight(m->enc_head); p.ldb = D;
+        p.ldc = V;
+        p.M = (int)T; p.N = V; p.K = D;
+        if (s->bf) {
+            p.out.f = keep_logits ? s->logits : nullptr;
+            p.ce_part = s->ce_part; p.ce_targets = targets; p.ce_tlogit = s->ce_tlogit;
+            multiply(ctx, st, true, p, PROF_GEMM);
+            PROF(ctx, PROF_HEAD, launch_ce_combine(st, s->ce_part, s->ce_parts, s->ce_tlogit, T, s->tok_loss, keep_logits ? s->ce_rows : nullptr));
+        } else {
+            p.out.f = s->logits;
+            multiply(ctx, st, false, p, PROF_GEMM);
+        }
     }
     // dx[T][n_in] = dy[T][n_out] W (+ R)
     void linear_dgrad(Mat dy, int64_t T, int n_out, int64_t w_off, int n_in, Mat dx, const float* R = nullptr) const {
@@ -289,15 +318,15 @@ int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32
     hipStream_t st = ctx->stream;
     Carver c(ctx->arena);
     SeqScratch s = carve(c, m, chunk, false);
-    const int L = m->enc_L, D = m->enc_D, V = m->enc_V, layers = (int)m->enc_layers.size();
+    const int L = m->enc_L, V = m->enc_V, layers = (int)m->enc_layers.size();
     Net net{ctx, st, m, params, &s, chunk};
     net.refresh_weight_copies();
     for (int64_t first = 0; first < N; first += chunk) {
         net.B = (int)(N - first < chunk ? N - first : chunk);
         const int64_t T = (int64_t)net.B * L;
         net.forward(x + first * L, false);
-        net.linear(s.x[layers], T, D, m->enc_head, -1, V, Mat{s.logits, nullptr});
-        PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, y + first * L, T, V, s.tok_loss, 0.f, nullptr));
+        net.token_losses(s.x[layers], y + first * L, T, false);
+        if (!s.bf) PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, y + first * L, T, V, s.tok_loss, 0.f, nullptr));
         PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, net.B, L, losses_out + first));
     }
     BLS_HIP(ctx, hipGetLastError());
@@ -337,8 +366,9 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
         }
         net.forward(s.tok, true);
         const Mat hf = s.x[layers];
-        net.linear(hf, T, D, m->enc_head, -1, V, Mat{s.logits, nullptr});
-        PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, s.tgt, T, V, s.tok_loss, gscale, s.dlogits.h));
+        net.token_losses(hf, s.tgt, T, true);
+        if (s.bf) PROF(ctx, PROF_HEAD, launch_ce_grad(st, s.logits, s.tgt, s.ce_rows, T, V, gscale, s.dlogits.h));
+        else PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, s.tgt, T, V, s.tok_loss, gscale, nullptr));
         PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, B, L, step_losses_out ? step_losses_out + j * B : s.loss));
         // head
         net.linear_wgrad(s.dlogits, hf, T, V, D, m->enc_head);

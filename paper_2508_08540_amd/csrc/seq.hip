@@ -382,6 +382,49 @@ __global__ __launch_bounds__(256) void token_ce_kernel(float* __restrict__ logit
     }
 }
 
+// Folds the n_parts (max, sum) pairs part[i][t] of every row t: a workgroup takes 64 rows, thread (row, slice) folds the
+// pairs slice, slice + 4, ... in order, and the four slices are folded in order through LDS.
+__global__ __launch_bounds__(256) void ce_combine_kernel(const float* __restrict__ part, int n_parts, const float* __restrict__ tlogit, int64_t T,
+                                                         float* __restrict__ tok_loss, float* __restrict__ row_stats) {
+    __shared__ MaxSum red[4][64];
+    const int row = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int64_t t = (int64_t)blockIdx.x * 64 + row;
+    MaxSum acc = {-INFINITY, 0.f};
+    if (t < T)
+        for (int i = slice; i < n_parts; i += 4) {
+            const sq_f32x2 p = *reinterpret_cast<const sq_f32x2*>(part + 2 * ((int64_t)i * T + t));
+            acc = fold(acc, MaxSum{p[0], p[1]});
+        }
+    red[slice][row] = acc;
+    __syncthreads();
+    if (slice == 0 && t < T) {
+        acc = fold(fold(red[0][row], red[1][row]), fold(red[2][row], red[3][row]));
+        tok_loss[t] = (acc.m + logf(acc.s)) - tlogit[t];
+        if (row_stats) {
+            row_stats[2 * t] = acc.m;
+            row_stats[2 * t + 1] = acc.s;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void ce_grad_kernel(const float* __restrict__ logits, const int32_t* __restrict__ targets,
+                                                      const float* __restrict__ row_stats, int V, float grad_scale, uint16_t* __restrict__ d16) {
+    const int64_t t = blockIdx.x;
+    const float* z = logits + t * (int64_t)V;
+    const float m = row_stats[2 * t], inv = 1.f / row_stats[2 * t + 1];
+    const int tgt = targets[t];
+    if ((V & 3) == 0) {
+        for (int c = 4 * threadIdx.x; c < V; c += 1024) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(z + c);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (expf(v[j] - m) * inv - (c + j == tgt ? 1.f : 0.f)) * grad_scale;
+            store_bf16x4(d16 + t * (int64_t)V + c, v);
+        }
+    } else {
+        for (int c = threadIdx.x; c < V; c += 256) d16[t * (int64_t)V + c] = to_bf16((expf(z[c] - m) * inv - (c == tgt ? 1.f : 0.f)) * grad_scale);
+    }
+}
+
 // loss[b] = mean of tok_loss[b*L .. b*L + L); one wave per sample, fixed order
 __global__ __launch_bounds__(64) void sample_mean_kernel(const float* __restrict__ tok_loss, int L, float* __restrict__ loss) {
     const int b = blockIdx.x, lane = threadIdx.x;
@@ -458,6 +501,13 @@ void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, i
 }
 void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale, uint16_t* d16) {
     hipLaunchKernelGGL(token_ce_kernel, dim3((unsigned)T), dim3(256), 0, s, logits, targets, V, tok_loss, grad_scale, d16);
+}
+void launch_ce_combine(hipStream_t s, const float* ce_part, int n_parts, const float* tlogit, int64_t T, float* tok_loss, float* row_stats) {
+    hipLaunchKernelGGL(ce_combine_kernel, dim3(nblk(T, 64)), dim3(256), 0, s, ce_part, n_parts, tlogit, T, tok_loss, row_stats);
+}
+void launch_ce_grad(hipStream_t s, const float* logits, const int32_t* targets, const float* row_stats, int64_t T, int V, float grad_scale,
+                    uint16_t* d16) {
+    hipLaunchKernelGGL(ce_grad_kernel, dim3((unsigned)T), dim3(256), 0, s, logits, targets, row_stats, V, grad_scale, d16);
 }
 void launch_sample_mean(hipStream_t s, const float* tok_loss, int B, int L, float* loss) {
     hipLaunchKernelGGL(sample_mean_kernel, dim3(B), dim3(64), 0, s, tok_loss, L, loss);
