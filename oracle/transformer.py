@@ -20,7 +20,10 @@ import numpy as np
 
 LN_EPS = 1e-5
 _SQRT2 = math.sqrt(2.0)
-_erf = np.vectorize(math.erf, otypes=[np.float64])
+try:
+    from scipy.special import erf as _erf          # the same function, evaluated array-wise
+except ImportError:                                 # pragma: no cover
+    _erf = np.vectorize(math.erf, otypes=[np.float64])
 
 
 def gelu(x):

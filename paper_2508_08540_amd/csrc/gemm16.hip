@@ -28,27 +28,30 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_v){lo, hi}, bf16x2_v));
 }
 
-// ---- operand fetch: two 16-byte pieces per thread and operand ---------------------------------------------------------
-// Row-major operand: piece f = tid + 256 i covers row f >> 2, k = 8 (f & 3) .. + 7.
-// K-major operand: the thread takes k = 2 kp and 2 kp + 1 for the eight rows of chunk c, kp = (tid >> 2) & 15,
-// c = 4 (tid >> 6) + (tid & 3); the two pieces are interleaved into (k, k+1) pairs on the way into LDS.
+// ---- operand fetch: two 16-byte pieces per thread for every 128 rows of an operand tile ------------------------------
+// An operand tile has NP * 128 rows (NP = 1 or 2); piece i = 2 * group + sub belongs to rows 128 * group ...
+// Row-major operand: f = tid + 256 sub covers row f >> 2, k = 8 (f & 3) .. + 7.
+// K-major operand: the thread takes k = 2 kp + sub for the eight rows of chunk c, kp = (tid >> 2) & 15,
+// c = 4 (tid >> 6) + (tid & 3); the two pieces of a group are interleaved into (k, k+1) pairs on the way into LDS.
 template <bool KMAJOR>
 __device__ __forceinline__ void g16_piece(int i, int& row, int& k) {
+    const int group = i >> 1, sub = i & 1;
     if (KMAJOR) {
-        row = 8 * (4 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 3));
-        k = 2 * (int)((threadIdx.x >> 2) & 15) + i;
+        row = 128 * group + 8 * (4 * (int)(threadIdx.x >> 6) + (int)(threadIdx.x & 3));
+        k = 2 * (int)((threadIdx.x >> 2) & 15) + sub;
     } else {
-        const int f = threadIdx.x + 256 * i;
-        row = f >> 2;
+        const int f = threadIdx.x + 256 * sub;
+        row = 128 * group + (f >> 2);
         k = 8 * (f & 3);
     }
 }
 
 // Checked fetch: any shape and alignment, element by element where a 16-byte load is not possible.
-template <bool KMAJOR>
-__device__ __forceinline__ void g16_fetch(const bf16_t* __restrict__ P, int ld, int rows, int row0, int k0, int k_end, bool vec, u32x4 (&v)[2]) {
+template <bool KMAJOR, int NP>
+__device__ __forceinline__ void g16_fetch(const bf16_t* __restrict__ P, int ld, int rows, int row0, int k0, int k_end, bool vec,
+                                          u32x4 (&v)[2 * NP]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2 * NP; ++i) {
         int row, k;
         g16_piece<KMAJOR>(i, row, k);
         row += row0;
@@ -83,37 +86,40 @@ __device__ __forceinline__ void g16_fetch(const bf16_t* __restrict__ P, int ld, 
 
 // Unchecked fetch: element offsets of the two pieces at k = 0 are fixed before the loop.  Rows past the end of the
 // matrix are clamped to valid ones; they only feed rows or columns of C that are never stored.
-template <bool KMAJOR>
-__device__ __forceinline__ void g16_offsets(uint32_t (&off)[2], int ld, int rows, int row0) {
+template <bool KMAJOR, int NP>
+__device__ __forceinline__ void g16_offsets(uint32_t (&off)[2 * NP], int ld, int rows, int row0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 2 * NP; ++i) {
         int row, k;
         g16_piece<KMAJOR>(i, row, k);
         if (KMAJOR) off[i] = (uint32_t)(k * ld + min(row0 + row, rows - 8));
         else off[i] = (uint32_t)(min(row0 + row, rows - 1) * ld + k);
     }
 }
-template <bool KMAJOR>
-__device__ __forceinline__ void g16_fetch_fast(const bf16_t* __restrict__ P, const uint32_t (&off)[2], int ld, int k, u32x4 (&v)[2]) {
+template <bool KMAJOR, int NP>
+__device__ __forceinline__ void g16_fetch_fast(const bf16_t* __restrict__ P, const uint32_t (&off)[2 * NP], int ld, int k, u32x4 (&v)[2 * NP]) {
     const uint32_t step = KMAJOR ? (uint32_t)k * (uint32_t)ld : (uint32_t)k;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) v[i] = *reinterpret_cast<const u32x4*>(P + (off[i] + step));
+    for (int i = 0; i < 2 * NP; ++i) v[i] = *reinterpret_cast<const u32x4*>(P + (off[i] + step));
 }
 
-template <bool KMAJOR>
-__device__ __forceinline__ void g16_put(bf16_t* __restrict__ S, const u32x4 (&v)[2]) {
+template <bool KMAJOR, int NP>
+__device__ __forceinline__ void g16_put(bf16_t* __restrict__ S, const u32x4 (&v)[2 * NP]) {
     if (KMAJOR) {
-        int row, k;
-        g16_piece<true>(0, row, k);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            // rows row + 2j and row + 2j + 1: the low and the high halves of word j of both pieces
-            *reinterpret_cast<uint32_t*>(S + (row + 2 * j) * G16_PITCH + k) = __builtin_amdgcn_perm(v[1][j], v[0][j], 0x05040100u);
-            *reinterpret_cast<uint32_t*>(S + (row + 2 * j + 1) * G16_PITCH + k) = __builtin_amdgcn_perm(v[1][j], v[0][j], 0x07060302u);
+        for (int grp = 0; grp < NP; ++grp) {
+            int row, k;
+            g16_piece<true>(2 * grp, row, k);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // rows row + 2j and row + 2j + 1: the low and the high halves of word j of both pieces
+                *reinterpret_cast<uint32_t*>(S + (row + 2 * j) * G16_PITCH + k) = __builtin_amdgcn_perm(v[2 * grp + 1][j], v[2 * grp][j], 0x05040100u);
+                *reinterpret_cast<uint32_t*>(S + (row + 2 * j + 1) * G16_PITCH + k) = __builtin_amdgcn_perm(v[2 * grp + 1][j], v[2 * grp][j], 0x07060302u);
+            }
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2 * NP; ++i) {
             int row, k;
             g16_piece<false>(i, row, k);
             *reinterpret_cast<u32x4*>(S + row * G16_PITCH + k) = v[i];
@@ -131,11 +137,11 @@ __device__ __forceinline__ void g16_tile_of_block(int& tile_x, int& tile_y) {
 }
 
 // Stores a wave's 64 x 64 block; lane (r, g) holds acc[mt][nt][i] = C[m_base + 16 mt + r][n_base + 16 nt + 4 g + i].
-template <bool VEC>
-__device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, float* C, bf16_t* C16,
+template <bool VEC, int MB>
+__device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4 (&acc)[MB][4], int m_base, int n_base, float* C, bf16_t* C16,
                                                 bf16_t* G16, const float* R, int ldc, bool plain, int r, int g) {
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < MB; ++mt) {
         const int m = m_base + 16 * mt + r;
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
@@ -181,10 +187,11 @@ __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4
 // Softmax statistics of a wave's 64 columns for each of its 64 rows: ce_part[2 * tile_x + wn][m] = (max, sum of
 // exp(v - max)) over the columns that exist, and the value in column ce_targets[m] goes to ce_tlogit[m] when this wave
 // holds it.  A later pass folds the pairs of a row in index order.  The product is taken without bias.
-__device__ __forceinline__ void g16_ce_block(const Gemm16Desc& d, const f32x4 (&acc)[4][4], int m_base, int n_base, int part_idx, int r, int g) {
+template <int MB>
+__device__ __forceinline__ void g16_ce_block(const Gemm16Desc& d, const f32x4 (&acc)[MB][4], int m_base, int n_base, int part_idx, int r, int g) {
     const bool full = n_base + 64 <= d.N;   // uniform: every column of the block exists
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < MB; ++mt) {
         const int m = m_base + 16 * mt + r;
         const int tgt = m < d.M ? d.ce_targets[m] : -1;
         const int t_local = tgt - n_base - 4 * g;   // column of the target among this lane's 16, as 16 nt + i
@@ -213,15 +220,18 @@ __device__ __forceinline__ void g16_ce_block(const Gemm16Desc& d, const f32x4 (&
     }
 }
 
-template <bool AK, bool BK, bool FAST, bool CE>
-__global__ __launch_bounds__(256) void gemm16_kernel(Gemm16Desc d) {
-    __shared__ __attribute__((aligned(16))) bf16_t As[2][G16_TILE * G16_PITCH], Bs[2][G16_TILE * G16_PITCH];
+// MB = 16-row blocks per wave in m: 4 (128 x 128 tile per workgroup) or 8 (256 x 128: a third less operand traffic
+// per flop, for products with enough tiles to fill the chip that way).
+template <bool AK, bool BK, bool FAST, bool CE, int MB>
+__global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc d) {
+    constexpr int NPA = MB / 4, TILE_M = 32 * MB;
+    __shared__ __attribute__((aligned(16))) bf16_t As[2][TILE_M * G16_PITCH], Bs[2][G16_TILE * G16_PITCH];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 15, g = lane >> 4;
     const int wm = wave >> 1, wn = wave & 1;
     int tile_x, tile_y;
     g16_tile_of_block(tile_x, tile_y);
-    const int m0 = tile_y * G16_TILE, n0 = tile_x * G16_TILE;
+    const int m0 = tile_y * TILE_M, n0 = tile_x * G16_TILE;
     const int split = blockIdx.z % d.splits, z = blockIdx.z / d.splits;
     const int z1 = z / d.inner, z2 = z - z1 * d.inner;
     const bf16_t* A = d.A + z1 * d.sa1 + z2 * d.sa2;
@@ -230,9 +240,9 @@ __global__ __launch_bounds__(256) void gemm16_kernel(Gemm16Desc d) {
     const int k_end = min(d.K, k_begin + d.k_chunk);
     const bool avec = d.a_vec != 0, bvec = d.b_vec != 0;
 
-    f32x4 acc[4][4];
+    f32x4 acc[MB][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -244,46 +254,45 @@ __global__ __launch_bounds__(256) void gemm16_kernel(Gemm16Desc d) {
         const int sidx = i + rot < steps ? i + rot : i + rot - steps;
         return k_begin + sidx * G16_K;
     };
-    u32x4 pa[2], pb[2];
-    uint32_t offa[2], offb[2];
+    u32x4 pa[2 * NPA], pb[2];
+    uint32_t offa[2 * NPA], offb[2];
     if (FAST) {
-        g16_offsets<AK>(offa, d.lda, d.M, m0);
-        g16_offsets<BK>(offb, d.ldb, d.N, n0);
+        g16_offsets<AK, NPA>(offa, d.lda, d.M, m0);
+        g16_offsets<BK, 1>(offb, d.ldb, d.N, n0);
     }
     auto fetch = [&](int k) {
         if (FAST) {
-            g16_fetch_fast<AK>(A, offa, d.lda, k, pa);
-            g16_fetch_fast<BK>(B, offb, d.ldb, k, pb);
+            g16_fetch_fast<AK, NPA>(A, offa, d.lda, k, pa);
+            g16_fetch_fast<BK, 1>(B, offb, d.ldb, k, pb);
         } else {
-            g16_fetch<AK>(A, d.lda, d.M, m0, k, k_end, avec, pa);
-            g16_fetch<BK>(B, d.ldb, d.N, n0, k, k_end, bvec, pb);
+            g16_fetch<AK, NPA>(A, d.lda, d.M, m0, k, k_end, avec, pa);
+            g16_fetch<BK, 1>(B, d.ldb, d.N, n0, k, k_end, bvec, pb);
         }
     };
     if (steps > 0) {
         fetch(k_of(0));
-        g16_put<AK>(As[0], pa);
-        g16_put<BK>(Bs[0], pb);
+        g16_put<AK, NPA>(As[0], pa);
+        g16_put<BK, 1>(Bs[0], pb);
     }
     __syncthreads();
     int buf = 0;
     for (int i = 0; i < steps; ++i) {
         const bool more = i + 1 < steps;
         if (more) fetch(k_of(i + 1));
-        const bf16_t* as = As[buf] + (wm * 64 + r) * G16_PITCH + 8 * g;
+        const bf16_t* as = As[buf] + (wm * 16 * MB + r) * G16_PITCH + 8 * g;
         const bf16_t* bs = Bs[buf] + (wn * 64 + r) * G16_PITCH + 8 * g;
-        bf16x8_v a[4], b[4];
+        bf16x8_v a[MB], b[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            a[t] = *reinterpret_cast<const bf16x8_v*>(as + 16 * t * G16_PITCH);
-            b[t] = *reinterpret_cast<const bf16x8_v*>(bs + 16 * t * G16_PITCH);
-        }
+        for (int t = 0; t < MB; ++t) a[t] = *reinterpret_cast<const bf16x8_v*>(as + 16 * t * G16_PITCH);
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int t = 0; t < 4; ++t) b[t] = *reinterpret_cast<const bf16x8_v*>(bs + 16 * t * G16_PITCH);
+#pragma unroll
+        for (int mt = 0; mt < MB; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[nt], a[mt], acc[mt][nt], 0, 0, 0);
         if (more) {
-            g16_put<AK>(As[buf ^ 1], pa);
-            g16_put<BK>(Bs[buf ^ 1], pb);
+            g16_put<AK, NPA>(As[buf ^ 1], pa);
+            g16_put<BK, 1>(Bs[buf ^ 1], pb);
         }
         __syncthreads();
         buf ^= 1;
@@ -296,11 +305,11 @@ __global__ __launch_bounds__(256) void gemm16_kernel(Gemm16Desc d) {
     bf16_t* G16 = (plain || !d.G16) ? nullptr : d.G16 + zoff;
     const float* R = (plain || !d.R) ? nullptr : d.R + zoff;
     const int ldc = plain ? d.N : d.ldc;
-    const int m_base = m0 + wm * 64, n_base = n0 + wn * 64;
-    if (CE) g16_ce_block(d, acc, m_base, n_base, 2 * tile_x + wn, r, g);   // its own instantiation: the statistics cost registers
-    const bool vec = (plain ? (d.N & 3) == 0 : d.c_vec != 0) && m_base + 64 <= d.M && n_base + 64 <= d.N;
-    if (vec) g16_store_block<true>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
-    else g16_store_block<false>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
+    const int m_base = m0 + wm * 16 * MB, n_base = n0 + wn * 64;
+    if (CE) g16_ce_block<MB>(d, acc, m_base, n_base, 2 * tile_x + wn, r, g);   // its own instantiation: the statistics cost registers
+    const bool vec = (plain ? (d.N & 3) == 0 : d.c_vec != 0) && m_base + 16 * MB <= d.M && n_base + 64 <= d.N;
+    if (vec) g16_store_block<true, MB>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
+    else g16_store_block<false, MB>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
 }
 
 // out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order (weight gradients: fp32 output only)
@@ -338,20 +347,21 @@ void launch_gemm16(hipStream_t s, Gemm16Desc d) {
     const int64_t span_a = (int64_t)(d.a_kmajor ? d.K : d.M) * d.lda, span_b = (int64_t)(d.b_kmajor ? d.K : d.N) * d.ldb;
     const bool fast = d.a_vec && d.b_vec && d.K % G16_K == 0 && (!d.a_kmajor || d.M % 8 == 0) && (!d.b_kmajor || d.N % 8 == 0) && d.M >= 8 &&
                       d.N >= 8 && span_a < (int64_t(1) << 31) && span_b < (int64_t(1) << 31);
-    dim3 grid((d.N + G16_TILE - 1) / G16_TILE, (d.M + G16_TILE - 1) / G16_TILE, d.batch * d.splits);
-#define G16_LAUNCH(AKM, BKM)                                                                             \
-    do {                                                                                                 \
-        if (fast) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, false>), grid, dim3(256), 0, s, d);   \
-        else hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, false, false>), grid, dim3(256), 0, s, d);       \
+    // 256-row tiles where the product still has at least 512 of them (two per compute unit); they need the unchecked fetch
+    const bool tall = fast && !d.a_kmajor && (int64_t)((d.M + 255) / 256) * ((d.N + G16_TILE - 1) / G16_TILE) * d.batch * d.splits >= 512 && d.M >= 256;
+    const int tile_m = tall ? 256 : G16_TILE;
+    dim3 grid((d.N + G16_TILE - 1) / G16_TILE, (d.M + tile_m - 1) / tile_m, d.batch * d.splits);
+#define G16_LAUNCH(AKM, BKM, CEM, TALL_OK)                                                                     \
+    do {                                                                                                       \
+        if (TALL_OK && tall) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, CEM, TALL_OK ? 8 : 4>), grid, dim3(256), 0, s, d); \
+        else if (fast) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, CEM, 4>), grid, dim3(256), 0, s, d);   \
+        else hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, false, CEM, 4>), grid, dim3(256), 0, s, d);            \
     } while (0)
-    if (d.ce_part) {
-        // row statistics: row-major factors, one matrix, no split (the vocabulary projection)
-        if (fast) hipLaunchKernelGGL((gemm16_kernel<false, false, true, true>), grid, dim3(256), 0, s, d);
-        else hipLaunchKernelGGL((gemm16_kernel<false, false, false, true>), grid, dim3(256), 0, s, d);
-    } else if (d.a_kmajor && d.b_kmajor) G16_LAUNCH(true, true);
-    else if (d.a_kmajor) G16_LAUNCH(true, false);
-    else if (d.b_kmajor) G16_LAUNCH(false, true);
-    else G16_LAUNCH(false, false);
+    if (d.ce_part) G16_LAUNCH(false, false, true, true);   // row statistics: row-major factors, one matrix, no split
+    else if (d.a_kmajor && d.b_kmajor) G16_LAUNCH(true, true, false, false);
+    else if (d.a_kmajor) G16_LAUNCH(true, false, false, false);
+    else if (d.b_kmajor) G16_LAUNCH(false, true, false, true);
+    else G16_LAUNCH(false, false, false, true);
 #undef G16_LAUNCH
     if (d.splits > 1) {
         int64_t total = (int64_t)d.M * d.N;

@@ -133,6 +133,25 @@ def test_bf16_products_scores_and_gradients(env, vocab, L, D, H, F, layers, batc
     assert not {n: e for n, e in worst.items() if e[0] > max(2e-3, 0.5 * e[1])}, worst
 
 
+def test_bf16_products_with_256_row_tiles(env):
+    """4096 tokens against 4096-wide layers: the vocabulary projection, fc1 and the input gradient of fc2 have 512 tiles
+    of 256 x 128 and take that kernel variant; same criteria as above."""
+    vocab, L, D, H, F, layers, batch = 4096, 128, 32, 2, 4096, 1, 32
+    h = _harness(env, vocab, L, D, H, F, layers, "bf16")
+    p = synth.transformer_init(CFG["id"], vocab, L, D, F, layers, perturb=0.2)
+    x, y = synth.token_pool(CFG["id"], batch, L, vocab)
+    sel = np.arange(batch)
+    probe = oracle.GradientProbe(h.oracle_model, p, {}, x, y)
+    assert_losses_close(h.score(p, {}, x, y), probe.losses, rtol=2e-4)
+    _, _, mom, sl = h.local_step(p, {}, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], probe.losses, rtol=2e-4)
+    ref = probe.grads()
+    exact = oracle.GradientProbe(oracle.TransformerLM(vocab, L, D, H, F, layers), p, {}, x, y).grads()
+    ref.pop("l0.attn.k.bias")
+    worst = {n: (rel_err(mom[n], ref[n]), rel_err(exact[n], ref[n])) for n in ref}
+    assert not {n: e for n, e in worst.items() if e[0] > max(2e-3, 0.5 * e[1])}, worst
+
+
 def test_bf16_products_steps_follow_the_oracle(env):
     vocab, L, D, H, F, layers = 200, 12, 32, 4, 64, 2
     h = _harness(env, vocab, L, D, H, F, layers, "bf16")
