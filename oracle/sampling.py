@@ -14,6 +14,14 @@ k = floor(lambda * N_F) in double precision, N_S = N - N_F (the epoch covers N s
 replacement of m items = the m items with the largest random key, equal keys by lower index, where
 the keys (one float per sample and per group) are an input, so that both implementations consume the
 same random numbers.
+
+Variants compared in the appendix (sampling-scheme comparison and its table).  scheme "separated" is the
+method above.  scheme "unified": the group that samples by loss goes first and the other group trains on
+the remaining data, i.e. on exactly the N - N_biased samples the first group did not take, in the order of
+its random keys.  high_loss_to "slow" hands the high-loss samples to the slow workers instead: the slow
+allocation is the floor(lambda N_S) highest losses plus a uniform fill from the rest, and the fast workers
+draw uniformly (from all N, or from the remainder under "unified").  The unbiased baseline of that table is
+uniform sampling for both groups and needs no loss at all.
 """
 import math
 
@@ -36,20 +44,38 @@ def deal(ranked, P):
     return [np.asarray(ranked[p::P]) for p in range(P)]
 
 
-def sample_epoch(losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam):
-    """Returns dict(fast=[P_f index arrays], slow=[P_s index arrays], n_fast, k, n_slow, fast_ranked, slow_ranked)."""
+def _by_loss_then_uniform(losses, keys, n, k):
+    """n ranked indices: the k highest losses, then the n - k largest keys among the rest."""
+    high = topk_by_loss(losses, k)                                   # highest loss first, ties by lower index
+    unselected = np.ones(losses.shape[0], dtype=bool)
+    unselected[high] = False
+    rest = np.flatnonzero(unselected)
+    # uniform without replacement from the rest: largest random key first
+    fill = rest[topk_by_loss(keys[rest], n - k)] if n > k else np.zeros(0, dtype=np.int64)
+    return np.concatenate([high.astype(np.int64), fill.astype(np.int64)])
+
+
+def sample_epoch(losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, scheme="separated", high_loss_to="fast"):
+    """Returns dict(fast=[P_f index arrays], slow=[P_s index arrays], n_fast, k, n_slow, fast_ranked, slow_ranked);
+    k is the size of the by-loss part of the group named by high_loss_to."""
+    if scheme not in ("separated", "unified") or high_loss_to not in ("fast", "slow"):
+        raise ValueError("unknown sampling variant")
     losses = np.asarray(losses, dtype=np.float32)
     u_fast = np.asarray(u_fast, dtype=np.float32)
     u_slow = np.asarray(u_slow, dtype=np.float32)
     N = losses.shape[0]
     n_fast, k, n_slow = allocation(N, tau_f, P_f, tau_s, P_s, lam)
-    high = topk_by_loss(losses, k)                                   # highest loss first, ties by lower index
-    unselected = np.ones(N, dtype=bool)
-    unselected[high] = False
-    rest = np.flatnonzero(unselected)
-    # uniform without replacement from the rest: largest random key first
-    fill = rest[topk_by_loss(u_fast[rest], n_fast - k)] if n_fast > k else np.zeros(0, dtype=np.int64)
-    fast_ranked = np.concatenate([high.astype(np.int64), fill.astype(np.int64)])
-    slow_ranked = topk_by_loss(u_slow, n_slow).astype(np.int64)
+    if high_loss_to == "slow":
+        k = int(math.floor(float(lam) * float(n_slow)))
+    n_biased, u_biased, n_other, u_other = (n_fast, u_fast, n_slow, u_slow) if high_loss_to == "fast" else (n_slow, u_slow, n_fast, u_fast)
+    biased = _by_loss_then_uniform(losses, u_biased, n_biased, k)
+    if scheme == "separated":
+        other = topk_by_loss(u_other, n_other).astype(np.int64)      # from all N, independent of the other group
+    else:
+        left = np.ones(N, dtype=bool)
+        left[biased] = False
+        left = np.flatnonzero(left)                                  # what the first group did not take
+        other = left[topk_by_loss(u_other[left], n_other)].astype(np.int64)
+    fast_ranked, slow_ranked = (biased, other) if high_loss_to == "fast" else (other, biased)
     return dict(fast=deal(fast_ranked, P_f), slow=deal(slow_ranked, P_s), n_fast=n_fast, k=k, n_slow=n_slow,
                 fast_ranked=fast_ranked, slow_ranked=slow_ranked)

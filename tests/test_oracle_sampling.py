@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
+import synth
 from oracle.sampling import allocation, deal, sample_epoch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -108,3 +109,42 @@ def test_inclusion_frequencies_are_uniform():
             assert abs(fill_hits[i] / draws - p_fill) < 5 * np.sqrt(p_fill * (1 - p_fill) / draws)
     p_slow = ns / N
     assert np.all(np.abs(slow_hits / draws - p_slow) < 5 * np.sqrt(p_slow * (1 - p_slow) / draws))
+
+
+def test_appendix_variants_on_a_case_worked_by_hand():
+    """Eight samples, tau_F P_F : tau_S P_S = 3 : 1, so N_F = 6 and N_S = 2; lambda = 1/2.  Worked on paper from the
+    appendix's description of unified sampling and of handing the high-loss samples to the slow workers."""
+    losses = [5, 1, 7, 3, 8, 2, 6, 4]
+    u_fast = [.1, .9, .5, .8, .2, .3, .4, .7]
+    u_slow = [.6, .5, .4, .3, .2, .9, .1, .8]
+    run = lambda **kw: oracle.sample_epoch(losses, u_fast, u_slow, 3, 1, 1, 1, 0.5, **kw)
+    # losses 8, 7, 6 sit at 4, 2, 6; of the rest {0, 1, 3, 5, 7} the largest fast keys are .9, .8, .7 at 1, 3, 7
+    sep = run()
+    assert sep["fast_ranked"].tolist() == [4, 2, 6, 1, 3, 7] and sep["slow_ranked"].tolist() == [5, 7] and sep["k"] == 3
+    # unified: the slow workers get what is left, {0, 5}, larger slow key (.9 at 5) first
+    uni = run(scheme="unified")
+    assert uni["fast_ranked"].tolist() == [4, 2, 6, 1, 3, 7] and uni["slow_ranked"].tolist() == [5, 0]
+    # high loss to the slow workers: k = floor(2 / 2) = 1 -> sample 4, then the largest slow key among the rest (.9 at 5);
+    # the fast workers draw six by fast key from all eight: .9 .8 .7 .5 .4 .3 at 1 3 7 2 6 5
+    hs = run(high_loss_to="slow")
+    assert hs["slow_ranked"].tolist() == [4, 5] and hs["fast_ranked"].tolist() == [1, 3, 7, 2, 6, 5] and hs["k"] == 1
+    # ... or, unified, from the six that are left: {0, 1, 2, 3, 6, 7} by fast key .9 .8 .7 .5 .4 .1
+    hu = run(scheme="unified", high_loss_to="slow")
+    assert hu["slow_ranked"].tolist() == [4, 5] and hu["fast_ranked"].tolist() == [1, 3, 7, 2, 6, 0]
+
+
+@pytest.mark.parametrize("high_loss_to", ["fast", "slow"])
+def test_unified_sampling_covers_every_sample_exactly_once(high_loss_to):
+    N = 1000
+    losses = synth.loss_array("ties16", N)
+    uf, us = (synth.rng.uniform01(synth.inputs.BASE_SEED, 600 + g, N).astype(np.float32) for g in (0, 1))
+    r = oracle.sample_epoch(losses, uf, us, 32, 8, 4, 2, 0.3, scheme="unified", high_loss_to=high_loss_to)
+    both = np.concatenate([r["fast_ranked"], r["slow_ranked"]])
+    assert np.array_equal(np.sort(both), np.arange(N))
+    # the group that does not sample by loss holds its share in descending order of its own keys
+    other, keys = (r["slow_ranked"], us) if high_loss_to == "fast" else (r["fast_ranked"], uf)
+    assert np.all(np.diff(np.asarray(keys)[other]) <= 0)
+    # the by-loss group is what the separated scheme gives it
+    sep = oracle.sample_epoch(losses, uf, us, 32, 8, 4, 2, 0.3, high_loss_to=high_loss_to)
+    name = "fast_ranked" if high_loss_to == "fast" else "slow_ranked"
+    assert np.array_equal(r[name], sep[name])
