@@ -216,6 +216,20 @@ int bls_worker_share(int64_t n, int P, int p, int64_t* offset, int64_t* count);
 int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
                  int P_f, int64_t tau_s, int P_s, double lambda, int32_t* fast_idx_out, int32_t* slow_idx_out);
 
+/* The sampling schemes compared in the appendix (sampling-scheme comparison and its table of data-allocation rows).
+ *   scheme        BLS_SAMPLING_SEPARATED: as sample_epoch.  BLS_SAMPLING_UNIFIED: the group that samples by loss goes
+ *                 first and the other group trains on the remaining data: it receives exactly the samples the first
+ *                 group did not take (N - N_F resp. N - N_S of them), in descending order of its own keys.
+ *   high_loss_to  BLS_HIGH_LOSS_TO_FAST: as sample_epoch.  BLS_HIGH_LOSS_TO_SLOW: the slow workers receive the
+ *                 floor(lambda N_S) highest losses and a uniform fill from the rest (keys u_slow); the fast workers draw
+ *                 uniformly by u_fast, from all N or, unified, from what the slow workers left.
+ * Sizes, layout of the outputs, ties and errors as for sample_epoch, which is the (SEPARATED, TO_FAST) case. */
+enum { BLS_SAMPLING_SEPARATED = 0, BLS_SAMPLING_UNIFIED = 1 };
+enum { BLS_HIGH_LOSS_TO_FAST = 0, BLS_HIGH_LOSS_TO_SLOW = 1 };
+int sample_epoch_variant(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
+                         int P_f, int64_t tau_s, int P_s, double lambda, int scheme, int high_loss_to, int32_t* fast_idx_out,
+                         int32_t* slow_idx_out);
+
 /* w_i = tau_i / sum_j tau_j (Eq. 4), computed in double and rounded once.  Host only. */
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out);
 

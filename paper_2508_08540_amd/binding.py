@@ -15,8 +15,10 @@ DECLARED_SYMBOLS = (
     "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
-    "sample_epoch",
+    "sample_epoch", "sample_epoch_variant",
 )
+SAMPLING_SCHEMES = {"separated": 0, "unified": 1}
+HIGH_LOSS_TO = {"fast": 0, "slow": 1}
 PROFILE_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "norm", "head", "gemm", "update", "gather", "topk",
                    "aggregate", "wgrad_reduce")
 
@@ -73,6 +75,7 @@ def _load():
                                        C.POINTER(i64)]
     L.bls_worker_share.argtypes = [i64, C.c_int, C.c_int, C.POINTER(i64), C.POINTER(i64)]
     L.sample_epoch.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, vp, vp]
+    L.sample_epoch_variant.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, C.c_int, C.c_int, vp, vp]
     L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
     L.bls_weights_from_tau.argtypes = [C.POINTER(i64), C.c_int, C.POINTER(C.c_float)]
     L.bls_profile_begin.argtypes = [vp]
@@ -248,9 +251,16 @@ def worker_share(n, P, p):
     return off.value, cnt.value
 
 
-def sample_epoch(ctx, losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, fast_idx_out, slow_idx_out):
-    ctx.check(lib.sample_epoch(ctx.handle, _ptr(losses), _ptr(u_fast), _ptr(u_slow), losses.shape[0], tau_f, P_f, tau_s,
-                               P_s, lam, _ptr(fast_idx_out), _ptr(slow_idx_out)))
+def sample_epoch(ctx, losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, fast_idx_out, slow_idx_out, scheme=None,
+                 high_loss_to=None):
+    """scheme / high_loss_to given: the appendix's variants through sample_epoch_variant."""
+    if scheme is None and high_loss_to is None:
+        ctx.check(lib.sample_epoch(ctx.handle, _ptr(losses), _ptr(u_fast), _ptr(u_slow), losses.shape[0], tau_f, P_f, tau_s,
+                                   P_s, lam, _ptr(fast_idx_out), _ptr(slow_idx_out)))
+    else:
+        ctx.check(lib.sample_epoch_variant(ctx.handle, _ptr(losses), _ptr(u_fast), _ptr(u_slow), losses.shape[0], tau_f, P_f,
+                                           tau_s, P_s, lam, SAMPLING_SCHEMES[scheme or "separated"],
+                                           HIGH_LOSS_TO[high_loss_to or "fast"], _ptr(fast_idx_out), _ptr(slow_idx_out)))
 
 
 def weights_from_tau(tau):

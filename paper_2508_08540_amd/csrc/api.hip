@@ -425,19 +425,32 @@ int bls_worker_share(int64_t n, int P, int p, int64_t* offset, int64_t* count) {
     return BLS_OK;
 }
 
-int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
-                 int P_f, int64_t tau_s, int P_s, double lambda, int32_t* fast_idx_out, int32_t* slow_idx_out) {
+int sample_epoch_variant(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f, int P_f,
+                         int64_t tau_s, int P_s, double lambda, int scheme, int high_loss_to, int32_t* fast_idx_out, int32_t* slow_idx_out) {
     if (!ctx) return BLS_EINVAL;
+    if ((scheme != BLS_SAMPLING_SEPARATED && scheme != BLS_SAMPLING_UNIFIED) || (high_loss_to != BLS_HIGH_LOSS_TO_FAST && high_loss_to != BLS_HIGH_LOSS_TO_SLOW))
+        return bls_fail(ctx, BLS_EINVAL, "sample_epoch_variant: unknown scheme or group");
     int64_t nf, k, ns;
     if (bls_epoch_allocation(N, tau_f, P_f, tau_s, P_s, lambda, &nf, &k, &ns) != BLS_OK)
         return bls_fail(ctx, BLS_EINVAL, "sample_epoch: need 0 <= N < 2^31, 1 <= tau_F, 0 <= tau_S, 1 <= P_F, 0 <= P_S, 0 < lambda <= 1");
     if (ns > 0 && P_s < 1) return bls_fail(ctx, BLS_EINVAL, "sample_epoch: slow samples but no slow worker");
     if (N == 0) return BLS_OK;
-    if (!losses || (nf > k && !u_fast) || (ns > 0 && !u_slow) || (nf > 0 && !fast_idx_out) || (ns > 0 && !slow_idx_out))
+    const bool to_fast = high_loss_to == BLS_HIGH_LOSS_TO_FAST;
+    if (!to_fast) k = (int64_t)floor(lambda * (double)ns);   // the by-loss part of the slow allocation
+    const int64_t n_biased = to_fast ? nf : ns, n_other = to_fast ? ns : nf;
+    const float *u_biased = to_fast ? u_fast : u_slow, *u_other = to_fast ? u_slow : u_fast;
+    if (!losses || (n_biased > k && !u_biased) || (n_other > 0 && !u_other) || (nf > 0 && !fast_idx_out) || (ns > 0 && !slow_idx_out))
         return bls_fail(ctx, BLS_EINVAL, "sample_epoch: NULL pointer");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
     ProfScope prof(ctx, PROF_TOPK);
-    return launch_sample_epoch(ctx, losses, u_fast, u_slow, N, nf, k, ns, P_f, P_s, fast_idx_out, slow_idx_out);
+    return launch_sample_epoch(ctx, losses, u_biased, u_other, N, n_biased, k, n_other, to_fast ? P_f : P_s, to_fast ? P_s : P_f,
+                               scheme == BLS_SAMPLING_UNIFIED, to_fast ? fast_idx_out : slow_idx_out, to_fast ? slow_idx_out : fast_idx_out);
+}
+
+int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
+                 int P_f, int64_t tau_s, int P_s, double lambda, int32_t* fast_idx_out, int32_t* slow_idx_out) {
+    return sample_epoch_variant(ctx, losses, u_fast, u_slow, N, tau_f, P_f, tau_s, P_s, lambda, BLS_SAMPLING_SEPARATED, BLS_HIGH_LOSS_TO_FAST,
+                                fast_idx_out, slow_idx_out);
 }
 
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out) {

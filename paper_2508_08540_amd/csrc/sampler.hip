@@ -30,36 +30,47 @@ static unsigned blocks_for(int64_t n) {
     return (unsigned)(b < 1 ? 1 : (b > 4096 ? 4096 : b));
 }
 
-int launch_sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t n_fast,
-                        int64_t k, int64_t n_slow, int P_f, int P_s, int32_t* fast_out, int32_t* slow_out) {
+// The by-loss group takes the k highest losses, then n_biased - k by its own key from the rest; the other group takes
+// n_other by its key from all N (separated) or from what the first group left (unified: the first group's picks are
+// struck from the other group's keys as well).
+int launch_sample_epoch(bls_ctx* ctx, const float* losses, const float* u_biased, const float* u_other, int64_t N, int64_t n_biased,
+                        int64_t k, int64_t n_other, int P_biased, int P_other, bool unified, int32_t* biased_out, int32_t* other_out) {
     // scratch: the selection's own region first (it carves from the arena base), then the masked keys and the ranking
     const size_t topk_bytes = (topk_scratch_bytes(N, N) + 255) & ~size_t(255);
     Carver sizes(nullptr);
     sizes.take<float>(N);
+    sizes.take<int32_t>(N);
     sizes.take<int32_t>(N);
     int rc = bls_arena_reserve(ctx, topk_bytes + sizes.off);
     if (rc != BLS_OK) return rc;
     Carver c(ctx->arena + topk_bytes);
     float* keys = c.take<float>(N);
     int32_t* ranked = c.take<int32_t>(N);
+    int32_t* ranked_other = c.take<int32_t>(N);
     hipStream_t s = ctx->stream;
-    if (n_fast > 0) {
+    if (n_biased > 0) {
         if (k > 0) {
             rc = launch_topk(ctx, losses, N, k, ranked, nullptr);
             if (rc != BLS_OK) return rc;
         }
-        if (n_fast > k) {
-            hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_fast, keys, N);
+        if (n_biased > k) {
+            hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_biased, keys, N);
             if (k > 0) hipLaunchKernelGGL(exclude_selected_kernel, dim3(blocks_for(k)), dim3(256), 0, s, ranked, k, keys);
-            rc = launch_topk(ctx, keys, N, n_fast - k, ranked + k, nullptr);
+            rc = launch_topk(ctx, keys, N, n_biased - k, ranked + k, nullptr);
             if (rc != BLS_OK) return rc;
         }
-        hipLaunchKernelGGL(deal_kernel, dim3(blocks_for(n_fast)), dim3(256), 0, s, ranked, n_fast, P_f, fast_out);
+        hipLaunchKernelGGL(deal_kernel, dim3(blocks_for(n_biased)), dim3(256), 0, s, ranked, n_biased, P_biased, biased_out);
     }
-    if (n_slow > 0) {
-        rc = launch_topk(ctx, u_slow, N, n_slow, ranked, nullptr);
+    if (n_other > 0) {
+        const float* from = u_other;
+        if (unified && n_biased > 0) {
+            hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_other, keys, N);
+            hipLaunchKernelGGL(exclude_selected_kernel, dim3(blocks_for(n_biased)), dim3(256), 0, s, ranked, n_biased, keys);
+            from = keys;
+        }
+        rc = launch_topk(ctx, from, N, n_other, ranked_other, nullptr);
         if (rc != BLS_OK) return rc;
-        hipLaunchKernelGGL(deal_kernel, dim3(blocks_for(n_slow)), dim3(256), 0, s, ranked, n_slow, P_s, slow_out);
+        hipLaunchKernelGGL(deal_kernel, dim3(blocks_for(n_other)), dim3(256), 0, s, ranked_other, n_other, P_other, other_out);
     }
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;

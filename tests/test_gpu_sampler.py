@@ -92,3 +92,53 @@ def test_errors(env):
             bls.sample_epoch(ctx, z, z, z, args[0], args[1], args[2], args[3], args[4], out, out)
     with pytest.raises(bls.BlsError):
         bls.sample_epoch(ctx, z, z, z, 1, 1, 1, 1, 0.5, None, out)
+
+
+# ---- the appendix's sampling variants ---------------------------------------------------------------------------------
+
+def _check_variant(env, losses, uf, us, tf, pf, ts, ps, lam, scheme, to):
+    torch, bls, ctx = env
+    N = losses.shape[0]
+    nf, _, ns = bls.epoch_allocation(N, tf, pf, ts, ps, lam)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    fast = torch.full((max(nf, 1),), -7, dtype=torch.int32, device="cuda")
+    slow = torch.full((max(ns, 1),), -7, dtype=torch.int32, device="cuda")
+    bls.sample_epoch(ctx, dev(losses), dev(uf), dev(us), tf, pf, ts, ps, lam, fast, slow, scheme=scheme, high_loss_to=to)
+    ctx.synchronize()
+    ref = oracle.sample_epoch(losses, uf, us, tf, pf, ts, ps, lam, scheme=scheme, high_loss_to=to)
+    assert (nf, ns) == (ref["n_fast"], ref["n_slow"])
+    for got, group, n, P in ((fast.cpu().numpy()[:nf], ref["fast"], nf, pf), (slow.cpu().numpy()[:ns], ref["slow"], ns, ps)):
+        for p in range(P if n else 0):
+            off, cnt = bls.worker_share(n, P, p)
+            np.testing.assert_array_equal(got[off:off + cnt], group[p].astype(np.int32))
+    return fast.cpu().numpy()[:nf], slow.cpu().numpy()[:ns]
+
+
+@pytest.mark.parametrize("scheme,to", [("separated", "fast"), ("unified", "fast"), ("separated", "slow"), ("unified", "slow")])
+@pytest.mark.parametrize("N,tf,pf,ts,ps,lam", [
+    (8, 3, 1, 1, 1, 0.5), (257, 32, 8, 1, 2, 0.25), (5000, 3, 7, 2, 5, 1.0), (5000, 3, 7, 2, 5, 0.001), (16385, 32, 8, 16, 2, 0.3),
+    (50000, 32, 8, 1, 2, 0.5), (40000, 2, 2, 0, 0, 0.5),
+])
+def test_variants_match_the_oracle(env, scheme, to, N, tf, pf, ts, ps, lam):
+    seed = synth.inputs.BASE_SEED + 3 * N
+    for kind in ("halfnormal", "ties16"):
+        losses = synth.loss_array(kind, N, seed=seed)
+        fast, slow = _check_variant(env, losses, _keys(seed, 21, N), _keys(seed, 22, N), tf, pf, ts, ps, lam, scheme, to)
+        if scheme == "unified":
+            assert np.array_equal(np.sort(np.concatenate([fast, slow])), np.arange(N))   # every sample exactly once
+
+
+def test_variants_with_special_losses_tied_keys_and_bad_arguments(env):
+    torch, bls, ctx = env
+    N = 20000
+    losses = synth.loss_array("specials", N)
+    uf = np.round(_keys(5, 1, N) * 8).astype(np.float32) / 8
+    us = np.zeros(N, dtype=np.float32)
+    for scheme in ("separated", "unified"):
+        for to in ("fast", "slow"):
+            _check_variant(env, losses, uf, us, 32, 8, 4, 2, 0.5, scheme, to)
+    z = torch.zeros(4, dtype=torch.float32, device="cuda")
+    o = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(bls.BlsError):
+        ctx.check(bls.binding.lib.sample_epoch_variant(ctx.handle, z.data_ptr(), z.data_ptr(), z.data_ptr(), 4, 1, 1, 1, 1, 0.5, 2, 0,
+                                                       o.data_ptr(), o.data_ptr()))          # an unknown scheme is rejected
