@@ -17,3 +17,4 @@ from .transformer import TransformerLM                          # noqa: F401
 from .precision import round_bf16                               # noqa: F401
 from .sampling import allocation, deal, sample_epoch                 # noqa: F401
 from .local_sgd import score_losses, local_step, loss_and_grads, GradientProbe  # noqa: F401
+from .round import communication_round                            # noqa: F401
