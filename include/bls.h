@@ -191,6 +191,35 @@ int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffe
 int weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const float* weights, int P, int64_t d,
                        float* out, int flags);
 
+/* ---- one communication round (Algorithm 1: local steps of every worker, loss recording, aggregation) ---- */
+
+/* One worker of a round.  All pointers are device pointers.
+ *   tau        local steps this round (0: the worker neither trains nor counts)
+ *   idx, n_idx the samples assigned to it (a segment of sample_epoch's output); entries distinct
+ *   params, buffers  storage for its replica, float[d] / float[num_buffers]; overwritten with the global model when the
+ *              round starts, they hold the trained replica afterwards
+ *   momentum   float[d], the worker's own optimiser state, kept from round to round by the caller */
+typedef struct {
+    int64_t tau;
+    const int32_t* idx;
+    int64_t n_idx;
+    float* params;
+    float* buffers;
+    float* momentum;
+} bls_worker;
+
+/* Every worker with tau > 0, in the order given: replica <- global model; tau local steps on its samples as in
+ * local_step (batches walk idx cyclically); then  global_params <- sum_i (tau_i / sum_j tau_j) * params_i  (Eq. 4), and
+ * the same for the batch-norm running statistics in global_buffers.
+ *   workers     host array of P descriptions, 1 <= P <= 64
+ *   loss_table  device float[N] or NULL: the loss of every processed sample is stored at its index (the loss-recording
+ *               step of Algorithm 1); a sample processed more than once keeps the loss recorded last, in the order
+ *               workers, steps, positions; other entries are left alone
+ * The workers run one after the other on the context's stream.  Errors as for local_step and weighted_aggregate. */
+int communication_round(bls_ctx* ctx, const bls_model* model, float* global_params, float* global_buffers,
+                        const bls_worker* workers, int P, const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch,
+                        const bls_sgd* opt, float* loss_table);
+
 /* ---- epoch sampler (Section 4.2; sampling steps at the top of every epoch of Algorithm 1) ------- */
 
 /* Sizes of one epoch's allocation.  N_F = floor(N tau_F P_F / (tau_F P_F + tau_S P_S)) samples go to the

@@ -15,7 +15,7 @@ DECLARED_SYMBOLS = (
     "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
-    "sample_epoch", "sample_epoch_variant",
+    "sample_epoch", "sample_epoch_variant", "communication_round",
 )
 SAMPLING_SCHEMES = {"separated": 0, "unified": 1}
 HIGH_LOSS_TO = {"fast": 0, "slow": 1}
@@ -75,6 +75,7 @@ def _load():
                                        C.POINTER(i64)]
     L.bls_worker_share.argtypes = [i64, C.c_int, C.c_int, C.POINTER(i64), C.POINTER(i64)]
     L.sample_epoch.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, vp, vp]
+    L.communication_round.argtypes = [vp, vp, vp, vp, vp, C.c_int, vp, vp, i64, i64, vp, vp]
     L.sample_epoch_variant.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, C.c_int, C.c_int, vp, vp]
     L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
     L.bls_weights_from_tau.argtypes = [C.POINTER(i64), C.c_int, C.POINTER(C.c_float)]
@@ -261,6 +262,23 @@ def sample_epoch(ctx, losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, fast_
         ctx.check(lib.sample_epoch_variant(ctx.handle, _ptr(losses), _ptr(u_fast), _ptr(u_slow), losses.shape[0], tau_f, P_f,
                                            tau_s, P_s, lam, SAMPLING_SCHEMES[scheme or "separated"],
                                            HIGH_LOSS_TO[high_loss_to or "fast"], _ptr(fast_idx_out), _ptr(slow_idx_out)))
+
+
+class _Worker(C.Structure):
+    _fields_ = [("tau", C.c_int64), ("idx", C.c_void_p), ("n_idx", C.c_int64), ("params", C.c_void_p), ("buffers", C.c_void_p),
+                ("momentum", C.c_void_p)]
+
+
+def communication_round(ctx, model, global_params, global_buffers, workers, x_pool, y_pool, batch, lr, mu=0.0, weight_decay=0.0,
+                        loss_table=None):
+    """workers: list of dict(tau, idx, params, buffers, momentum) of device tensors (buffers may be None)."""
+    arr = (_Worker * len(workers))()
+    for i, w in enumerate(workers):
+        addr = lambda t: None if t is None else _ptr(t).value
+        arr[i] = _Worker(int(w["tau"]), addr(w["idx"]), w["idx"].shape[0], addr(w["params"]), addr(w.get("buffers")), addr(w["momentum"]))
+    opt = _Sgd(lr, mu, weight_decay)
+    ctx.check(lib.communication_round(ctx.handle, model.handle, _ptr(global_params), _ptr(global_buffers), arr, len(workers),
+                                      _ptr(x_pool), _ptr(y_pool), x_pool.shape[0], batch, C.byref(opt), _ptr(loss_table)))
 
 
 def weights_from_tau(tau):

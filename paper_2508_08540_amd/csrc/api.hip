@@ -84,6 +84,7 @@ void bls_ctx_destroy(bls_ctx* ctx) {
     for (hipEvent_t e : ctx->fork_events) (void)hipEventDestroy(e);
     if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
     if (ctx->arena) (void)hipFree(ctx->arena);
+    if (ctx->round_losses) (void)hipFree(ctx->round_losses);
     delete ctx;
 }
 
@@ -451,6 +452,75 @@ int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const f
                  int P_f, int64_t tau_s, int P_s, double lambda, int32_t* fast_idx_out, int32_t* slow_idx_out) {
     return sample_epoch_variant(ctx, losses, u_fast, u_slow, N, tau_f, P_f, tau_s, P_s, lambda, BLS_SAMPLING_SEPARATED, BLS_HIGH_LOSS_TO_FAST,
                                 fast_idx_out, slow_idx_out);
+}
+
+// table[idx[e mod n_idx]] = losses[e] for the last entry e of every cyclic position: the local steps walk idx cyclically,
+// so entry e is overwritten later exactly when e + n_idx < n.
+__global__ __launch_bounds__(256) void record_losses_kernel(const int32_t* __restrict__ idx, int64_t n_idx, int64_t n,
+                                                            const float* __restrict__ losses, float* __restrict__ table) {
+    const int64_t first = n > n_idx ? n - n_idx : 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) table[idx[e % n_idx]] = losses[e];
+}
+
+int communication_round(bls_ctx* ctx, const bls_model* model, float* global_params, float* global_buffers, const bls_worker* workers, int P,
+                        const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch, const bls_sgd* opt, float* loss_table) {
+    if (!ctx) return BLS_EINVAL;
+    if (!model || !opt || !workers || !global_params) return bls_fail(ctx, BLS_EINVAL, "communication_round: NULL pointer");
+    if (P < 1 || P > 64 || batch < 1 || batch > 65536) return bls_fail(ctx, BLS_EINVAL, "communication_round: need 1 <= P <= 64, 1 <= batch <= 65536");
+    if (model->num_buffers > 0 && !global_buffers) return bls_fail(ctx, BLS_EINVAL, "communication_round: this model needs buffers");
+    double tau_sum = 0.0;
+    int64_t most = 0;
+    for (int i = 0; i < P; ++i) {
+        const bls_worker& w = workers[i];
+        if (w.tau < 0 || w.tau > (int64_t(1) << 20)) return bls_fail(ctx, BLS_EINVAL, "communication_round: tau of worker %d out of range", i);
+        if (w.tau == 0) continue;
+        if (!w.idx || w.n_idx < 1 || !w.params || !w.momentum || (model->num_buffers > 0 && !w.buffers))
+            return bls_fail(ctx, BLS_EINVAL, "communication_round: worker %d lacks samples or storage", i);
+        if (w.params == global_params) return bls_fail(ctx, BLS_EINVAL, "communication_round: worker %d trains in the global vector", i);
+        tau_sum += (double)w.tau;
+        most = w.tau * batch > most ? w.tau * batch : most;
+    }
+    if (!(tau_sum > 0.0)) return bls_fail(ctx, BLS_EINVAL, "communication_round: no worker takes a step");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    if (loss_table && (size_t)most > ctx->round_losses_count) {
+        BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (ctx->round_losses) BLS_HIP(ctx, hipFree(ctx->round_losses));
+        ctx->round_losses = nullptr;
+        ctx->round_losses_count = 0;
+        BLS_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->round_losses), (size_t)most * sizeof(float)));
+        ctx->round_losses_count = (size_t)most;
+    }
+    const float* trained[64];
+    const float* trained_buffers[64];
+    float weights[64];
+    int n_trained = 0;
+    for (int i = 0; i < P; ++i) {
+        const bls_worker& w = workers[i];
+        if (w.tau == 0) continue;
+        // every worker starts the round from the global model (the aggregate of the previous round)
+        BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)model->num_params * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+        if (model->num_buffers > 0)
+            BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)model->num_buffers * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+        int rc = local_step(ctx, model, w.params, w.buffers, w.momentum, x_pool, y_pool, N, w.idx, w.n_idx, batch, w.tau, opt,
+                            loss_table ? ctx->round_losses : nullptr);
+        if (rc != BLS_OK) return rc;
+        if (loss_table) {
+            const int64_t n = w.tau * batch, live = n < w.n_idx ? n : w.n_idx;
+            hipLaunchKernelGGL(record_losses_kernel, dim3((unsigned)((live + 255) / 256)), dim3(256), 0, ctx->stream, w.idx, w.n_idx, n,
+                               ctx->round_losses, loss_table);
+        }
+        trained[n_trained] = w.params;
+        trained_buffers[n_trained] = w.buffers;
+        weights[n_trained] = (float)((double)w.tau / tau_sum);
+        ++n_trained;
+    }
+    int rc = weighted_aggregate(ctx, trained, weights, n_trained, model->num_params, global_params, BLS_AGG_NORMALISE);
+    if (rc != BLS_OK) return rc;
+    if (model->num_buffers > 0) rc = weighted_aggregate(ctx, trained_buffers, weights, n_trained, model->num_buffers, global_buffers, BLS_AGG_NORMALISE);
+    if (rc != BLS_OK) return rc;
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
 }
 
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out) {

@@ -1,0 +1,103 @@
+"""GPU parity of communication_round (one round of Algorithm 1 on one GPU) against the oracle's round."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_helpers import assert_losses_close, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    yield torch, bls, ctx
+    ctx.close()
+
+
+def _zeros(p):
+    return {k: np.zeros_like(v, dtype=np.float64) for k, v in p.items()}
+
+
+def _round(env, model, omodel, p, b, x, y, workers, batch, lr, mu, wd, N):
+    """Runs the round on both sides; workers: list of (tau, idx, momentum dict)."""
+    torch, bls, ctx = env
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    gp = dev(model.pack(p))
+    gb = dev(model.pack(b, buffers=True)) if model.num_buffers else None
+    table0 = np.full(N, -3.0, dtype=np.float32)
+    table = dev(table0)
+    dws = []
+    for tau, idx, mom in workers:
+        dws.append(dict(tau=tau, idx=dev(np.asarray(idx, np.int32)), params=torch.full_like(gp, 7.0),
+                        buffers=torch.full_like(gb, 7.0) if gb is not None else None, momentum=dev(model.pack(mom))))
+    bls.communication_round(ctx, model, gp, gb, dws, dev(x), dev(y), batch, lr, mu, wd, table)
+    ctx.synchronize()
+    ref_p, ref_b, ref_m, ref_t = oracle.communication_round(omodel, p, b, [dict(tau=t, idx=i, momentum=m) for t, i, m in workers], x, y,
+                                                            batch, lr, mu, wd, loss_table=table0)
+    got_p = model.unpack(gp.cpu().numpy())
+    got_b = model.unpack(gb.cpu().numpy(), buffers=True) if gb is not None else {}
+    got_m = [model.unpack(w["momentum"].cpu().numpy()) for w in dws]
+    return got_p, got_b, got_m, table.cpu().numpy(), ref_p, ref_b, ref_m, ref_t, table0
+
+
+def _compare(p, got_p, got_b, got_m, got_t, ref_p, ref_b, ref_m, ref_t, table0, workers, tol):
+    for k in ref_p:   # the change of the global model, up to the fp32 rounding of the parameter itself
+        change = np.linalg.norm(ref_p[k] - p[k])
+        assert np.linalg.norm(got_p[k] - ref_p[k]) <= tol * change + 4 * 2.0 ** -24 * np.linalg.norm(ref_p[k]), k
+    for k in ref_b:
+        assert rel_err(got_b[k], ref_b[k]) <= tol, k
+    for (tau, _, mom), gm, rm in zip(workers, got_m, ref_m):
+        for k in rm:
+            if tau == 0:
+                assert np.array_equal(gm[k], np.asarray(mom[k], np.float32)), k     # an idle worker's state is not touched
+            else:
+                assert rel_err(gm[k], rm[k]) <= tol, k
+    touched = ref_t != table0.astype(np.float64)
+    assert np.array_equal(got_t[~touched], table0[~touched])                        # other entries are left alone
+    assert_losses_close(got_t[touched], ref_t[touched], rtol=1e-4)
+
+
+def test_mlp_round_with_wraparound_overlap_and_an_idle_worker(env):
+    torch, bls, ctx = env
+    cfg = synth.workload("mlp")
+    N = 40
+    model, omodel = bls.Model.mlp(hidden=32), oracle.MLP()
+    p = synth.mlp_init(cfg["id"], hidden=32)
+    x, y = synth.image_pool(cfg["id"], N, 10)
+    workers = [(3, np.arange(0, 10), _zeros(p)),                       # 12 positions over 10 samples: two are seen twice
+               (1, np.array([8, 9, 20, 21, 22, 23]), _zeros(p)),       # overlaps the first worker: its losses win in the table
+               (0, np.arange(30, 34), {k: np.ones_like(v, dtype=np.float64) for k, v in p.items()}),
+               (2, np.arange(24, 32), _zeros(p))]
+    out = _round(env, model, omodel, p, {}, x, y, workers, 4, 0.05, 0.9, 1e-4, N)
+    _compare(p, *out, workers, 1e-4)
+
+
+def test_resnet_round_aggregates_running_statistics_too(env):
+    torch, bls, ctx = env
+    cfg = synth.workload("resnet20_fp32")
+    widths, blocks, hw, N = (16, 16, 32), 1, 8, 24
+    model, omodel = bls.Model.resnet_cifar(widths, blocks, 10, hw), oracle.ResNetCifar(widths, blocks)
+    p, b = synth.resnet_init(cfg["id"], widths, blocks, 10, perturb_bn=0.1)
+    x, y = synth.image_pool(cfg["id"], N, 10, hw=hw)
+    workers = [(2, np.arange(0, 8), _zeros(p)), (1, np.arange(8, 16), _zeros(p)), (3, np.arange(12, 24), _zeros(p))]
+    out = _round(env, model, omodel, p, b, x, y, workers, 4, 0.05, 0.9, 0.0, N)
+    _compare(p, *out, workers, 2e-3)
+
+
+def test_rejected_arguments(env):
+    torch, bls, ctx = env
+    model = bls.Model.mlp(hidden=32)
+    gp = torch.zeros(model.num_params, device="cuda")
+    x, y = torch.zeros(4, 32, 32, 3, device="cuda"), torch.zeros(4, dtype=torch.int32, device="cuda")
+    idx = torch.arange(4, dtype=torch.int32, device="cuda")
+    w = dict(tau=1, idx=idx, params=torch.zeros_like(gp), buffers=None, momentum=torch.zeros_like(gp))
+    with pytest.raises(bls.BlsError):
+        bls.communication_round(ctx, model, gp, None, [dict(w, tau=0)], x, y, 2, 0.1)          # nobody takes a step
+    with pytest.raises(bls.BlsError):
+        bls.communication_round(ctx, model, gp, None, [dict(w, params=gp)], x, y, 2, 0.1)      # would train in the global vector
+    with pytest.raises(bls.BlsError):
+        bls.communication_round(ctx, model, gp, None, [w] * 65, x, y, 2, 0.1)                  # more workers than the aggregation takes
