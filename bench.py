@@ -68,11 +68,16 @@ def main():
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the workload step, time top-k and aggregation stand-alone over a range of sizes")
+    ap.add_argument("--round", action="store_true",
+                    help="instead of the workload step, time communication_round (8 ResNet20 workers, 20 steps of 128 each) "
+                         "with 1, 2, 4 and 8 workers side by side")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part in this build (run with --gpus 1)")
     if args.sweep:
         return sweep()
+    if args.round:
+        return round_lanes()
 
     import numpy as np
     import torch
@@ -344,6 +349,50 @@ def sweep():
         gbs = (P + 1) * 4 * d / t / 1e9
         out["aggregate"].append({"P": P, "d": d, "us": round(t * 1e6, 2), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
         del reps_sets
+    print(json.dumps(out))
+
+
+def round_lanes():
+    """One communication round of 8 fast workers (ResNet20 fp32, tau = 20, batch 128, 2560 samples each, loss table kept),
+    timed with the workers one after the other and 2, 4, 8 side by side; one JSON line, samples/s over all workers."""
+    import numpy as np
+    import torch
+    import synth
+    import paper_2508_08540_amd as bls
+    cfg = synth.workload("resnet20_fp32")
+    P, tau, B = 8, cfg["tau"], cfg["batch"]
+    per = tau * B
+    N = P * per
+    model = bls.Model.resnet_cifar()
+    p, b = synth.resnet_init(cfg["id"])
+    x, y = synth.image_pool(cfg["id"], 2048, cfg["classes"])
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dx, dy = dev(x).repeat(N // 2048, 1, 1, 1).contiguous(), dev(y).repeat(N // 2048).contiguous()
+    ctx = bls.Context(0)
+    gp0, gb0 = dev(model.pack(p)), dev(model.pack(b, buffers=True))
+    table = torch.zeros(N, device="cuda")
+    ws = [dict(tau=tau, idx=torch.arange(i * per, (i + 1) * per, dtype=torch.int32, device="cuda"), params=torch.empty_like(gp0),
+               buffers=torch.empty_like(gb0), momentum=torch.zeros_like(gp0)) for i in range(P)]
+    out = {"metric": "communication round, samples/s over 8 ResNet20 workers", "unit": "samples/s", "tau": tau, "batch": B, "workers": P,
+           "lanes": []}
+    ref = None
+    for lanes in (1, 2, 4, 8):
+        ctx.set_lanes(lanes)
+        times = []
+        for rep in range(4):
+            gp, gb = gp0.clone(), gb0.clone()
+            for w in ws:
+                w["momentum"].zero_()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            bls.communication_round(ctx, model, gp, gb, ws, dx, dy, B, cfg["lr"], cfg["momentum"], cfg["weight_decay"], table)
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+        t = min(times[1:])
+        same = True if ref is None else bool(torch.equal(ref, gp))
+        ref = gp.clone() if ref is None else ref
+        out["lanes"].append({"lanes": lanes, "ms": round(1e3 * t, 2), "samples/s": round(P * per / t, 1), "same_bits_as_one_lane": same})
+    ctx.set_lanes(1)
     print(json.dumps(out))
 
 

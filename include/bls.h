@@ -120,6 +120,11 @@ enum {
 /* Creates a context on HIP device `device`.  `hip_stream` is a hipStream_t owned by the caller
  * (NULL = the default stream); all work of this context is enqueued there. */
 int bls_ctx_create(bls_ctx** out, int device, void* hip_stream);
+/* Number of workers communication_round runs side by side (1 .. 16, default 1).  With more than one lane the library
+ * owns that many extra streams (default priority), each with its own scratch memory; the workers of a round are dealt
+ * to them in turn and the context's stream waits for all of them before it aggregates.  Results do not depend on the
+ * number of lanes.  Waits for the context's stream. */
+int bls_ctx_set_lanes(bls_ctx* ctx, int lanes);
 /* Waits for the stream, frees the scratch memory and the context.  NULL is allowed. */
 void bls_ctx_destroy(bls_ctx* ctx);
 /* Text of the most recent error on this context ("" if none).  Owned by the context. */
@@ -215,7 +220,8 @@ typedef struct {
  *   loss_table  device float[N] or NULL: the loss of every processed sample is stored at its index (the loss-recording
  *               step of Algorithm 1); a sample processed more than once keeps the loss recorded last, in the order
  *               workers, steps, positions; other entries are left alone
- * The workers run one after the other on the context's stream.  Errors as for local_step and weighted_aggregate. */
+ * The workers run one after the other on the context's stream, or side by side on the lanes set with bls_ctx_set_lanes
+ * (the recorded losses and the aggregate are the same either way).  Errors as for local_step and weighted_aggregate. */
 int communication_round(bls_ctx* ctx, const bls_model* model, float* global_params, float* global_buffers,
                         const bls_worker* workers, int P, const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch,
                         const bls_sgd* opt, float* loss_table);

@@ -15,7 +15,7 @@ DECLARED_SYMBOLS = (
     "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
-    "sample_epoch", "sample_epoch_variant", "communication_round",
+    "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes",
 )
 SAMPLING_SCHEMES = {"separated": 0, "unified": 1}
 HIGH_LOSS_TO = {"fast": 0, "slow": 1}
@@ -75,6 +75,7 @@ def _load():
                                        C.POINTER(i64)]
     L.bls_worker_share.argtypes = [i64, C.c_int, C.c_int, C.POINTER(i64), C.POINTER(i64)]
     L.sample_epoch.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, vp, vp]
+    L.bls_ctx_set_lanes.argtypes = [vp, C.c_int]
     L.communication_round.argtypes = [vp, vp, vp, vp, vp, C.c_int, vp, vp, i64, i64, vp, vp]
     L.sample_epoch_variant.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, C.c_int, C.c_int, vp, vp]
     L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
@@ -118,6 +119,10 @@ class Context:
 
     def profile_begin(self):
         self.check(lib.bls_profile_begin(self.handle))
+
+    def set_lanes(self, lanes):
+        """Workers that communication_round runs side by side (library-owned streams and scratch)."""
+        self.check(lib.bls_ctx_set_lanes(self.handle, lanes))
 
     def profile_end(self):
         """{class: (milliseconds, bracketed launch groups)} since profile_begin."""

@@ -76,6 +76,10 @@ void bls_ctx_destroy(bls_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    for (bls_ctx* lane : ctx->lanes) bls_ctx_destroy(lane);
+    ctx->lanes.clear();
+    for (hipEvent_t e : ctx->lane_events) (void)hipEventDestroy(e);
+    if (ctx->round_start) (void)hipEventDestroy(ctx->round_start);
     net_release(ctx);
     if (ctx->aux) {
         (void)hipStreamSynchronize(ctx->aux);
@@ -85,7 +89,34 @@ void bls_ctx_destroy(bls_ctx* ctx) {
     if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
     if (ctx->arena) (void)hipFree(ctx->arena);
     if (ctx->round_losses) (void)hipFree(ctx->round_losses);
+    if (ctx->owns_stream) (void)hipStreamDestroy(ctx->stream);
     delete ctx;
+}
+
+int bls_ctx_set_lanes(bls_ctx* ctx, int lanes) {
+    if (!ctx) return BLS_EINVAL;
+    if (lanes < 1 || lanes > 16) return bls_fail(ctx, BLS_EINVAL, "bls_ctx_set_lanes: need 1 <= lanes <= 16");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const int want = lanes == 1 ? 0 : lanes;   // one lane = the context's own stream
+    while ((int)ctx->lanes.size() > want) {
+        bls_ctx_destroy(ctx->lanes.back());
+        ctx->lanes.pop_back();
+    }
+    while ((int)ctx->lanes.size() < want) {
+        hipStream_t st = nullptr;
+        BLS_HIP(ctx, hipStreamCreateWithFlags(&st, hipStreamNonBlocking));   // default priority
+        bls_ctx* lane = nullptr;
+        int rc = bls_ctx_create(&lane, ctx->device, st);
+        if (rc != BLS_OK) {
+            (void)hipStreamDestroy(st);
+            return bls_fail(ctx, rc, "bls_ctx_set_lanes: could not create lane %d", (int)ctx->lanes.size());
+        }
+        lane->owns_stream = true;
+        ctx->lanes.push_back(lane);
+    }
+    if (!ctx->round_start) BLS_HIP(ctx, hipEventCreateWithFlags(&ctx->round_start, hipEventDisableTiming));
+    return BLS_OK;
 }
 
 const char* bls_last_error(const bls_ctx* ctx) { return ctx ? ctx->error.c_str() : ""; }
@@ -470,7 +501,7 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
     if (P < 1 || P > 64 || batch < 1 || batch > 65536) return bls_fail(ctx, BLS_EINVAL, "communication_round: need 1 <= P <= 64, 1 <= batch <= 65536");
     if (model->num_buffers > 0 && !global_buffers) return bls_fail(ctx, BLS_EINVAL, "communication_round: this model needs buffers");
     double tau_sum = 0.0;
-    int64_t most = 0;
+    int64_t total = 0;
     for (int i = 0; i < P; ++i) {
         const bls_worker& w = workers[i];
         if (w.tau < 0 || w.tau > (int64_t(1) << 20)) return bls_fail(ctx, BLS_EINVAL, "communication_round: tau of worker %d out of range", i);
@@ -479,41 +510,65 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
             return bls_fail(ctx, BLS_EINVAL, "communication_round: worker %d lacks samples or storage", i);
         if (w.params == global_params) return bls_fail(ctx, BLS_EINVAL, "communication_round: worker %d trains in the global vector", i);
         tau_sum += (double)w.tau;
-        most = w.tau * batch > most ? w.tau * batch : most;
+        total += w.tau * batch;
     }
     if (!(tau_sum > 0.0)) return bls_fail(ctx, BLS_EINVAL, "communication_round: no worker takes a step");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
-    if (loss_table && (size_t)most > ctx->round_losses_count) {
+    if (loss_table && (size_t)total > ctx->round_losses_count) {
         BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        for (bls_ctx* lane : ctx->lanes) BLS_HIP(ctx, hipStreamSynchronize(lane->stream));
         if (ctx->round_losses) BLS_HIP(ctx, hipFree(ctx->round_losses));
         ctx->round_losses = nullptr;
         ctx->round_losses_count = 0;
-        BLS_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->round_losses), (size_t)most * sizeof(float)));
-        ctx->round_losses_count = (size_t)most;
+        BLS_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->round_losses), (size_t)total * sizeof(float)));
+        ctx->round_losses_count = (size_t)total;
     }
+    const int n_lanes = (int)ctx->lanes.size();
+    while ((int)ctx->lane_events.size() < P) {
+        hipEvent_t e;
+        BLS_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        ctx->lane_events.push_back(e);
+    }
+    if (n_lanes > 0) BLS_HIP(ctx, hipEventRecord(ctx->round_start, ctx->stream));   // the global model is ready
     const float* trained[64];
     const float* trained_buffers[64];
     float weights[64];
+    int64_t loss_off[64];
     int n_trained = 0;
+    int64_t off = 0;
     for (int i = 0; i < P; ++i) {
         const bls_worker& w = workers[i];
         if (w.tau == 0) continue;
+        bls_ctx* lane = n_lanes > 0 ? ctx->lanes[n_trained % n_lanes] : ctx;
+        if (lane != ctx) BLS_HIP(ctx, hipStreamWaitEvent(lane->stream, ctx->round_start, 0));
         // every worker starts the round from the global model (the aggregate of the previous round)
-        BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)model->num_params * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
+        BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)model->num_params * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
         if (model->num_buffers > 0)
-            BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)model->num_buffers * sizeof(float), hipMemcpyDeviceToDevice, ctx->stream));
-        int rc = local_step(ctx, model, w.params, w.buffers, w.momentum, x_pool, y_pool, N, w.idx, w.n_idx, batch, w.tau, opt,
-                            loss_table ? ctx->round_losses : nullptr);
-        if (rc != BLS_OK) return rc;
-        if (loss_table) {
-            const int64_t n = w.tau * batch, live = n < w.n_idx ? n : w.n_idx;
-            hipLaunchKernelGGL(record_losses_kernel, dim3((unsigned)((live + 255) / 256)), dim3(256), 0, ctx->stream, w.idx, w.n_idx, n,
-                               ctx->round_losses, loss_table);
-        }
+            BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)model->num_buffers * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
+        int rc = local_step(lane, model, w.params, w.buffers, w.momentum, x_pool, y_pool, N, w.idx, w.n_idx, batch, w.tau, opt,
+                            loss_table ? ctx->round_losses + off : nullptr);
+        if (rc != BLS_OK) return lane == ctx ? rc : bls_fail(ctx, rc, "communication_round: worker %d: %s", i, lane->error.c_str());
+        if (lane != ctx) BLS_HIP(ctx, hipEventRecord(ctx->lane_events[n_trained], lane->stream));
         trained[n_trained] = w.params;
         trained_buffers[n_trained] = w.buffers;
         weights[n_trained] = (float)((double)w.tau / tau_sum);
+        loss_off[n_trained] = off;
+        off += w.tau * batch;
         ++n_trained;
+    }
+    if (n_lanes > 0)
+        for (int t = 0; t < n_trained; ++t) BLS_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->lane_events[t], 0));
+    if (loss_table) {
+        // in worker order on the one stream, so that of two workers that processed the same sample the later one wins
+        int t = 0;
+        for (int i = 0; i < P; ++i) {
+            const bls_worker& w = workers[i];
+            if (w.tau == 0) continue;
+            const int64_t n = w.tau * batch, live = n < w.n_idx ? n : w.n_idx;
+            hipLaunchKernelGGL(record_losses_kernel, dim3((unsigned)((live + 255) / 256)), dim3(256), 0, ctx->stream, w.idx, w.n_idx, n,
+                               ctx->round_losses + loss_off[t], loss_table);
+            ++t;
+        }
     }
     int rc = weighted_aggregate(ctx, trained, weights, n_trained, model->num_params, global_params, BLS_AGG_NORMALISE);
     if (rc != BLS_OK) return rc;

@@ -25,8 +25,12 @@ struct bls_ctx {
     hipStream_t aux = nullptr;             // library-owned side stream for work off the critical path
     std::vector<hipEvent_t> fork_events;   // main -> aux dependencies, one per use inside a call
     hipEvent_t join_event = nullptr;       // aux -> main
-    float* round_losses = nullptr;   // per-sample losses of one worker's local steps (communication_round), grown on demand
+    float* round_losses = nullptr;   // per-sample losses of the workers' local steps (communication_round), grown on demand
     size_t round_losses_count = 0;
+    std::vector<bls_ctx*> lanes;     // library-owned contexts (own stream, side stream and scratch) for concurrent workers
+    std::vector<hipEvent_t> lane_events;   // one per worker of a round: its local steps are done
+    hipEvent_t round_start = nullptr;      // main stream -> lanes
+    bool owns_stream = false;
     char* arena = nullptr;      // one scratch allocation, grown on demand
     size_t arena_bytes = 0;
     int num_cus = 0;

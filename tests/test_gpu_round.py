@@ -101,3 +101,41 @@ def test_rejected_arguments(env):
         bls.communication_round(ctx, model, gp, None, [dict(w, params=gp)], x, y, 2, 0.1)      # would train in the global vector
     with pytest.raises(bls.BlsError):
         bls.communication_round(ctx, model, gp, None, [w] * 65, x, y, 2, 0.1)                  # more workers than the aggregation takes
+
+
+def test_workers_side_by_side_give_the_same_bits(env):
+    """Three lanes against one: same global model, momenta, running statistics and loss table, bit for bit, twice in a row
+    (the second round starts from the first round's aggregate while the lanes are still warm)."""
+    torch, bls, ctx = env
+    cfg = synth.workload("resnet20_fp32")
+    widths, blocks, hw, N = (16, 16, 32), 1, 8, 40
+    model = bls.Model.resnet_cifar(widths, blocks, 10, hw)
+    p, b = synth.resnet_init(cfg["id"], widths, blocks, 10, perturb_bn=0.1)
+    x, y = synth.image_pool(cfg["id"], N, 10, hw=hw)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dx, dy = dev(x), dev(y)
+    segments = [np.arange(0, 8), np.arange(6, 16), np.arange(16, 24), np.arange(20, 36), np.arange(30, 40)]
+    taus = [2, 1, 3, 2, 1]
+
+    def run(lanes):
+        ctx.set_lanes(lanes)
+        gp, gb = dev(model.pack(p)), dev(model.pack(b, buffers=True))
+        table = torch.full((N,), -3.0, device="cuda")
+        ws = [dict(tau=t, idx=dev(s.astype(np.int32)), params=torch.empty_like(gp), buffers=torch.empty_like(gb), momentum=torch.zeros_like(gp))
+              for t, s in zip(taus, segments)]
+        for _ in range(2):
+            bls.communication_round(ctx, model, gp, gb, ws, dx, dy, 4, 0.05, 0.9, 1e-4, table)
+        ctx.synchronize()
+        torch.cuda.synchronize()
+        return [gp.cpu().numpy(), gb.cpu().numpy(), table.cpu().numpy()] + [w["momentum"].cpu().numpy() for w in ws]
+
+    try:
+        one, three, five = run(1), run(3), run(5)
+    finally:
+        ctx.set_lanes(1)
+    for a, c, e in zip(one, three, five):
+        assert np.array_equal(a, c) and np.array_equal(a, e)
+    seen = set()
+    for t, seg in zip(taus, segments):
+        seen.update(seg[:min(len(seg), 4 * t)].tolist())
+    assert np.isfinite(one[0]).all() and (one[2] != -3.0).sum() == len(seen)
