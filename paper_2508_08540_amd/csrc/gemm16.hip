@@ -137,7 +137,7 @@ __device__ __forceinline__ void g16_tile_of_block(int& tile_x, int& tile_y) {
 }
 
 // Stores a wave's 64 x 64 block; lane (r, g) holds acc[mt][nt][i] = C[m_base + 16 mt + r][n_base + 16 nt + 4 g + i].
-template <bool VEC, int MB>
+template <bool VEC, int MB, bool GELU>
 __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4 (&acc)[MB][4], int m_base, int n_base, float* C, bf16_t* C16,
                                                 bf16_t* G16, const float* R, int ldc, bool plain, int r, int g) {
 #pragma unroll
@@ -157,7 +157,7 @@ __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4
                 }
                 if (C) *reinterpret_cast<f32x4*>(C + at) = v;
                 if (C16) *reinterpret_cast<u32x2*>(C16 + at) = u32x2{pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3])};
-                if (G16) {
+                if (GELU && G16) {
                     f32x4 q;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) q[i] = 0.5f * v[i] * (1.f + erff(v[i] * 0.70710678118654752f));
@@ -176,7 +176,7 @@ __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4
                         }
                         if (C) C[at] = v;
                         if (C16) C16[at] = (bf16_t)(pack2_bf16(v, 0.f) & 0xffffu);
-                        if (G16) G16[at] = (bf16_t)(pack2_bf16(0.5f * v * (1.f + erff(v * 0.70710678118654752f)), 0.f) & 0xffffu);
+                        if (GELU && G16) G16[at] = (bf16_t)(pack2_bf16(0.5f * v * (1.f + erff(v * 0.70710678118654752f)), 0.f) & 0xffffu);
                     }
                 }
             }
@@ -222,7 +222,8 @@ __device__ __forceinline__ void g16_ce_block(const Gemm16Desc& d, const f32x4 (&
 
 // MB = 16-row blocks per wave in m: 4 (128 x 128 tile per workgroup) or 8 (256 x 128: a third less operand traffic
 // per flop, for products with enough tiles to fill the chip that way).
-template <bool AK, bool BK, bool FAST, bool CE, int MB>
+// EPI: 0 plain epilogue, 1 also writes gelu(C) (its erf code stays out of the other instantiations), 2 softmax statistics
+template <bool AK, bool BK, bool FAST, int EPI, int MB>
 __global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc d) {
     constexpr int NPA = MB / 4, TILE_M = 32 * MB;
     __shared__ __attribute__((aligned(16))) bf16_t As[2][TILE_M * G16_PITCH], Bs[2][G16_TILE * G16_PITCH];
@@ -306,10 +307,10 @@ __global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc
     const float* R = (plain || !d.R) ? nullptr : d.R + zoff;
     const int ldc = plain ? d.N : d.ldc;
     const int m_base = m0 + wm * 16 * MB, n_base = n0 + wn * 64;
-    if (CE) g16_ce_block<MB>(d, acc, m_base, n_base, 2 * tile_x + wn, r, g);   // its own instantiation: the statistics cost registers
+    if (EPI == 2) g16_ce_block<MB>(d, acc, m_base, n_base, 2 * tile_x + wn, r, g);   // its own instantiation: the statistics cost registers
     const bool vec = (plain ? (d.N & 3) == 0 : d.c_vec != 0) && m_base + 16 * MB <= d.M && n_base + 64 <= d.N;
-    if (vec) g16_store_block<true, MB>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
-    else g16_store_block<false, MB>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
+    if (vec) g16_store_block<true, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
+    else g16_store_block<false, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
 }
 
 // out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order (weight gradients: fp32 output only)
@@ -351,17 +352,18 @@ void launch_gemm16(hipStream_t s, Gemm16Desc d) {
     const bool tall = fast && !d.a_kmajor && (int64_t)((d.M + 255) / 256) * ((d.N + G16_TILE - 1) / G16_TILE) * d.batch * d.splits >= 512 && d.M >= 256;
     const int tile_m = tall ? 256 : G16_TILE;
     dim3 grid((d.N + G16_TILE - 1) / G16_TILE, (d.M + tile_m - 1) / tile_m, d.batch * d.splits);
-#define G16_LAUNCH(AKM, BKM, CEM, TALL_OK)                                                                     \
+#define G16_LAUNCH(AKM, BKM, EPI, TALL_OK)                                                                     \
     do {                                                                                                       \
-        if (TALL_OK && tall) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, CEM, TALL_OK ? 8 : 4>), grid, dim3(256), 0, s, d); \
-        else if (fast) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, CEM, 4>), grid, dim3(256), 0, s, d);   \
-        else hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, false, CEM, 4>), grid, dim3(256), 0, s, d);            \
+        if (TALL_OK && tall) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, EPI, TALL_OK ? 8 : 4>), grid, dim3(256), 0, s, d); \
+        else if (fast) hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, true, EPI, 4>), grid, dim3(256), 0, s, d);   \
+        else hipLaunchKernelGGL((gemm16_kernel<AKM, BKM, false, EPI, 4>), grid, dim3(256), 0, s, d);            \
     } while (0)
-    if (d.ce_part) G16_LAUNCH(false, false, true, true);   // row statistics: row-major factors, one matrix, no split
-    else if (d.a_kmajor && d.b_kmajor) G16_LAUNCH(true, true, false, false);
-    else if (d.a_kmajor) G16_LAUNCH(true, false, false, false);
-    else if (d.b_kmajor) G16_LAUNCH(false, true, false, true);
-    else G16_LAUNCH(false, false, false, true);
+    if (d.ce_part) G16_LAUNCH(false, false, 2, true);   // row statistics: row-major factors, one matrix, no split
+    else if (d.G16 && !d.a_kmajor && !d.b_kmajor) G16_LAUNCH(false, false, 1, true);
+    else if (d.a_kmajor && d.b_kmajor) G16_LAUNCH(true, true, 0, false);
+    else if (d.a_kmajor) G16_LAUNCH(true, false, 0, false);
+    else if (d.b_kmajor) G16_LAUNCH(false, true, 0, true);
+    else G16_LAUNCH(false, false, 0, true);
 #undef G16_LAUNCH
     if (d.splits > 1) {
         int64_t total = (int64_t)d.M * d.N;
