@@ -519,7 +519,8 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
 // packed copies that the next forward and input-gradient kernels read.  The gradient of a convolution weight
 // dw[16*ob + o][t][16*ib + i] is the sum over the replicas of accumulator (ob, ib)[(t*4 + o%4)*64 + 16*(o/4) + i]
 // (blocks of 16 * taps * 16 values),
-// converted back to float; the accumulators are cleared for the next step.  All other gradients come from grad[].
+// converted back to float; the accumulators are cleared for the next step.  All other gradients, and those of layers
+// with replicas == 0, come from grad[].
 // The kernel also clears the batch-norm accumulators of the next step.
 template <typename T>
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params, float* __restrict__ momentum,
@@ -547,13 +548,17 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
             const int block_floats = 16 * e.taps * 16;
             const int64_t src = (int64_t)((co >> 4) * (NI >> 4) + (ci >> 4)) * block_floats + (t * 4 + (o & 3)) * 64 + 16 * (o >> 2) + (ci & 15);
             const int64_t pitch = (int64_t)blocks * block_floats;
-            fixsum_t* acc_l = gacc + e.acc_off;
-            long long acc = 0;
-            for (int rep = 0; rep < e.replicas; ++rep) {
-                acc += (long long)acc_l[rep * pitch + src];
-                acc_l[rep * pitch + src] = 0ull;
+            if (e.replicas > 0) {
+                fixsum_t* acc_l = gacc + e.acc_off;
+                long long acc = 0;
+                for (int rep = 0; rep < e.replicas; ++rep) {
+                    acc += (long long)acc_l[rep * pitch + src];
+                    acc_l[rep * pitch + src] = 0ull;
+                }
+                g = (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));
+            } else {
+                g = grad[i];   // this layer's weight gradient was written as floats (replicas == 0)
             }
-            g = (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));
         } else {
             g = grad[i];
         }

@@ -46,7 +46,21 @@ struct WrnScratch {
     int64_t n_sums, wacc_count;
     float *grad, *loss, *feat, *dlogits, *dfeat;
     int32_t* yb;
+    // bf16: weight gradients of the 1x1 shortcuts as one GEMM dW = dy^T x over the pixels
+    uint16_t* xs16;     // the shortcut's input sampled at its stride, [pixels_out][c_in]
+    float* gpart;       // partial sums of the split contraction
 };
+
+// The 1x1 shortcut's weight gradient is a plain matrix product over the output pixels; in bf16 it runs on the bf16 GEMM
+// (split over the pixels, partial sums added in order) instead of the convolution weight-gradient kernel.
+bool shortcut_wgrad_by_gemm(int act, const ConvSlot& c) { return act == ACT_BF16 && c.taps == 1 && c.c_in >= 16 && c.c_in % 8 == 0 && c.c_out % 8 == 0; }
+int shortcut_splits(const ConvSlot& c, int B) {
+    const int64_t tiles = ceil_div(c.c_out, 128) * ceil_div(c.c_in, 128), K = (int64_t)B * c.h_out * c.h_out;
+    int64_t sp = ceil_div(512, tiles);
+    const int64_t most = K / 256 > 1 ? K / 256 : 1;
+    sp = sp > most ? most : sp;
+    return (int)(sp > 64 ? 64 : sp);
+}
 
 ConvShape shape_of(const ConvSlot& c, int B) {
     ConvShape cs;
@@ -98,8 +112,12 @@ WrnScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         ue.fwd_quad = s.convs[i].fwd_off / (4 * (int64_t)esz);
         ue.dgrad_quad = s.convs[i].dgrad_off >= 0 ? s.convs[i].dgrad_off / (4 * (int64_t)esz) : -1;
         ue.c_in = cs.c_in; ue.c_out = cs.c_out; ue.c_in_real = cs.c_in_real; ue.taps = cv.taps;
-        ue.replicas = conv_wgrad_replicas(s.act, cs); ue.pad_ = 0;
-        acc += conv_wgrad_accumulators(s.act, cs);
+        if (shortcut_wgrad_by_gemm(s.act, cv)) {
+            ue.replicas = 0; ue.pad_ = 0;   // gradient arrives as floats in grad[]
+        } else {
+            ue.replicas = conv_wgrad_replicas(s.act, cs); ue.pad_ = 0;
+            acc += conv_wgrad_accumulators(s.act, cs);
+        }
     }
     // batch norms
     std::vector<const BnSlot*> bslots;
@@ -158,6 +176,17 @@ WrnScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         s.feat = c.take<float>((size_t)B * m->final_c);
         s.dlogits = c.take<float>((size_t)B * m->desc.classes);
         s.dfeat = c.take<float>((size_t)B * m->final_c);
+        size_t xs = 0, gp = 0;
+        for (const WrnBlock& b : m->wrn_blocks)
+            if (b.proj && shortcut_wgrad_by_gemm(s.act, b.shortcut)) {
+                const ConvSlot& cv = b.shortcut;
+                const size_t sampled = cv.stride != 1 ? (size_t)B * cv.h_out * cv.h_out * cv.c_in : 0;
+                const size_t part = (size_t)cv.c_out * cv.c_in * shortcut_splits(cv, B);
+                xs = sampled > xs ? sampled : xs;
+                gp = part > gp ? part : gp;
+            }
+        s.xs16 = c.take<uint16_t>(xs ? xs : 1);
+        s.gpart = c.take<float>(gp ? gp : 1);
     }
     return s;
 }
@@ -192,9 +221,47 @@ int conv_dgrad(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const ConvRef&
     return BLS_OK;
 }
 
+// xs[b][oy][ox][:] = x[b][stride * oy][stride * ox][:], 16 bytes per thread
+__global__ __launch_bounds__(256) void sample_pixels_kernel(const uint16_t* __restrict__ x, int h_in, int h_out, int stride, int c8, int64_t n16,
+                                                            uint16_t* __restrict__ xs) {
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) {
+        const int64_t pix = i / c8;
+        const int c = (int)(i - pix * c8);
+        const int ox = (int)(pix % h_out);
+        const int64_t t = pix / h_out;
+        const int oy = (int)(t % h_out);
+        const int64_t b = t / h_out;
+        const int64_t src = ((b * h_in + (int64_t)stride * oy) * h_in + (int64_t)stride * ox) * c8 + c;
+        reinterpret_cast<uint4*>(xs)[i] = reinterpret_cast<const uint4*>(x)[src];
+    }
+}
+
 void conv_wgrad(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const ConvRef& cr, int B, const act_t* x, const act_t* dy) {
     ProfScope prof_(ctx, PROF_CONV_WGRAD);
-    launch_conv_wgrad(st, s.act, shape_of(*cr.slot, B), x, dy, s.wacc + cr.acc_off);
+    const ConvSlot& c = *cr.slot;
+    if (shortcut_wgrad_by_gemm(s.act, c)) {
+        const int64_t pixels = (int64_t)B * c.h_out * c.h_out;
+        const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
+        if (c.stride != 1) {
+            const int64_t n16 = pixels * (c.c_in / 8);
+            int64_t blocks = (n16 + 255) / 256;
+            hipLaunchKernelGGL(sample_pixels_kernel, dim3((unsigned)(blocks > 4096 ? 4096 : blocks)), dim3(256), 0, st, xs, c.h_in, c.h_out, c.stride,
+                               c.c_in / 8, n16, s.xs16);
+            xs = s.xs16;
+        }
+        Gemm16Desc d{};
+        d.A = reinterpret_cast<const uint16_t*>(dy); d.lda = c.c_out; d.a_kmajor = 1;
+        d.B = xs; d.ldb = c.c_in; d.b_kmajor = 1;
+        d.C = s.grad + c.w_off; d.ldc = c.c_in;
+        d.M = c.c_out; d.N = c.c_in; d.K = (int)pixels;
+        d.alpha = 1.f;
+        d.splits = shortcut_splits(c, B);
+        d.part = s.gpart;
+        launch_gemm16(st, d);
+        return;
+    }
+    launch_conv_wgrad(st, s.act, shape_of(c, B), x, dy, s.wacc + cr.acc_off);
 }
 
 void bn_forward(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const BnRef& bn, const float* params, float* buffers, int64_t pixels,
