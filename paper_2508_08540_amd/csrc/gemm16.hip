@@ -313,12 +313,16 @@ __global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc
     else g16_store_block<false, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
 }
 
-// out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order (weight gradients: fp32 output only)
+// out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order (weight gradients: fp32 output only); blockIdx.y is the
+// matrix of a batch (outer batch index only), whose output starts sc1 floats after the previous one
 __global__ __launch_bounds__(256) void gemm16_split_reduce_kernel(const float* __restrict__ part, int splits, int M, int N, float alpha,
                                                                   const float* __restrict__ bias, const float* __restrict__ R, int ldc,
-                                                                  float* __restrict__ out) {
+                                                                  float* __restrict__ out, int64_t sc1) {
     const int64_t total = (int64_t)M * N;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    part += (int64_t)blockIdx.y * splits * total;
+    out += (int64_t)blockIdx.y * sc1;
+    if (R) R += (int64_t)blockIdx.y * sc1;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         float acc = part[i];
         for (int zz = 1; zz < splits; ++zz) acc += part[(int64_t)zz * total + i];
@@ -331,7 +335,8 @@ __global__ __launch_bounds__(256) void gemm16_split_reduce_kernel(const float* _
     }
 }
 
-// Launch.  Split-K needs batch == 1 and an fp32 output only; d.part must then hold M*N*splits floats.
+// Launch.  Split-K writes an fp32 output only and, with a batch, needs inner == 1; d.part must then hold
+// batch*M*N*splits floats.
 void launch_gemm16(hipStream_t s, Gemm16Desc d) {
     if (d.splits < 1) d.splits = 1;
     if (d.inner < 1) d.inner = 1;
@@ -369,7 +374,7 @@ void launch_gemm16(hipStream_t s, Gemm16Desc d) {
         int64_t total = (int64_t)d.M * d.N;
         int64_t blocks = (total + 255) / 256;
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(gemm16_split_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, d.part, d.splits, d.M, d.N, d.alpha, d.bias, d.R,
-                           d.ldc, d.C);
+        hipLaunchKernelGGL(gemm16_split_reduce_kernel, dim3((unsigned)blocks, (unsigned)d.batch), dim3(256), 0, s, d.part, d.splits, d.M, d.N, d.alpha,
+                           d.bias, d.R, d.ldc, d.C, d.sc1);
     }
 }

@@ -194,6 +194,9 @@ struct GemmDesc {
 size_t gemm_tiled_partial_floats(int M, int N, int splits);
 void launch_gemm_tiled(hipStream_t s, GemmDesc d);
 
+// true where the bf16 weight-gradient kernel (wgrad16.hip) takes the layer
+bool wgrad16_covers(int act, const ConvShape& cs);
+
 // ---- gemm16.hip --------------------------------------------------------------------------------------
 // The same product with both operands stored in bf16 (uint16_t bit patterns).  Outputs: C fp32, C16 bf16, G16 = gelu(C)
 // in bf16, any of them NULL; ldc and the batch strides sc1/sc2 apply to all of them and to R.  splits > 1 needs

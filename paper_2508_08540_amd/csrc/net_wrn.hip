@@ -53,9 +53,17 @@ struct WrnScratch {
 
 // The 1x1 shortcut's weight gradient is a plain matrix product over the output pixels; in bf16 it runs on the bf16 GEMM
 // (split over the pixels, partial sums added in order) instead of the convolution weight-gradient kernel.
-bool shortcut_wgrad_by_gemm(int act, const ConvSlot& c) { return act == ACT_BF16 && c.taps == 1 && c.c_in >= 16 && c.c_in % 8 == 0 && c.c_out % 8 == 0; }
+// The same holds tap by tap for a 3x3 layer (one product per tap over inputs gathered at that tap's offset, zero outside
+// the map); the layers the bf16 weight-gradient kernel does not cover (stride 2, fewer than 64 input channels) go this way.
+bool shortcut_wgrad_by_gemm(int act, const ConvSlot& c, int B = 2) {
+    if (act != ACT_BF16 || c.c_in < 16 || c.c_in % 8 != 0 || c.c_out % 8 != 0) return false;
+    if (c.taps == 1) return true;
+    ConvShape cs;
+    cs.B = B; cs.h_in = c.h_in; cs.c_in = c.c_in; cs.c_out = c.c_out; cs.stride = c.stride; cs.c_in_real = c.c_in; cs.taps = c.taps;
+    return !wgrad16_covers(act, cs);
+}
 int shortcut_splits(const ConvSlot& c, int B) {
-    const int64_t tiles = ceil_div(c.c_out, 128) * ceil_div(c.c_in, 128), K = (int64_t)B * c.h_out * c.h_out;
+    const int64_t tiles = ceil_div(c.c_out, 128) * ceil_div(c.c_in, 128) * c.taps, K = (int64_t)B * c.h_out * c.h_out;
     int64_t sp = ceil_div(512, tiles);
     const int64_t most = K / 256 > 1 ? K / 256 : 1;
     sp = sp > most ? most : sp;
@@ -185,6 +193,14 @@ WrnScratch carve(Carver& c, const bls_model* m, int B, bool train) {
                 xs = sampled > xs ? sampled : xs;
                 gp = part > gp ? part : gp;
             }
+        for (const WrnBlock& b : m->wrn_blocks)
+            for (const ConvSlot* cv : {&b.conv1, &b.conv2})
+                if (shortcut_wgrad_by_gemm(s.act, *cv)) {
+                    const size_t gathered = (size_t)9 * B * cv->h_out * cv->h_out * cv->c_in;
+                    const size_t part = (size_t)9 * cv->c_out * cv->c_in * shortcut_splits(*cv, B);
+                    xs = gathered > xs ? gathered : xs;
+                    gp = part > gp ? part : gp;
+                }
         s.xs16 = c.take<uint16_t>(xs ? xs : 1);
         s.gpart = c.take<float>(gp ? gp : 1);
     }
@@ -237,10 +253,46 @@ __global__ __launch_bounds__(256) void sample_pixels_kernel(const uint16_t* __re
     }
 }
 
+// xs[t][b][oy][ox][:] = x[b][stride * oy + ky - 1][stride * ox + kx - 1][:] for tap t = 3 ky + kx, zero outside the map
+__global__ __launch_bounds__(256) void gather_taps_kernel(const uint16_t* __restrict__ x, int h_in, int h_out, int stride, int c8, int64_t n16,
+                                                          uint16_t* __restrict__ xs) {
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < 9 * n16; i += step) {
+        const int t = (int)(i / n16);
+        const int64_t j = i - (int64_t)t * n16, pix = j / c8;
+        const int c = (int)(j - pix * c8);
+        const int ox = (int)(pix % h_out);
+        const int64_t q = pix / h_out;
+        const int oy = (int)(q % h_out);
+        const int64_t b = q / h_out;
+        const int iy = stride * oy + t / 3 - 1, ix = stride * ox + t % 3 - 1;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (iy >= 0 && iy < h_in && ix >= 0 && ix < h_in) v = reinterpret_cast<const uint4*>(x)[((b * h_in + iy) * h_in + ix) * c8 + c];
+        reinterpret_cast<uint4*>(xs)[i] = v;
+    }
+}
+
 void conv_wgrad(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const ConvRef& cr, int B, const act_t* x, const act_t* dy) {
     ProfScope prof_(ctx, PROF_CONV_WGRAD);
     const ConvSlot& c = *cr.slot;
-    if (shortcut_wgrad_by_gemm(s.act, c)) {
+    if (c.taps == 9 && shortcut_wgrad_by_gemm(s.act, c)) {
+        const int64_t pixels = (int64_t)B * c.h_out * c.h_out, n16 = pixels * (c.c_in / 8);
+        int64_t blocks = (9 * n16 + 255) / 256;
+        hipLaunchKernelGGL(gather_taps_kernel, dim3((unsigned)(blocks > 8192 ? 8192 : blocks)), dim3(256), 0, st, reinterpret_cast<const uint16_t*>(x),
+                           c.h_in, c.h_out, c.stride, c.c_in / 8, n16, s.xs16);
+        Gemm16Desc d{};
+        d.A = reinterpret_cast<const uint16_t*>(dy); d.lda = c.c_out; d.a_kmajor = 1;            // the same dy for every tap
+        d.B = s.xs16; d.ldb = c.c_in; d.b_kmajor = 1; d.sb1 = pixels * c.c_in;
+        d.C = s.grad + c.w_off; d.ldc = 9 * c.c_in; d.sc1 = c.c_in;                              // w[c_out][tap][c_in]
+        d.M = c.c_out; d.N = c.c_in; d.K = (int)pixels;
+        d.batch = 9; d.inner = 1;
+        d.alpha = 1.f;
+        d.splits = shortcut_splits(c, B);
+        d.part = s.gpart;
+        launch_gemm16(st, d);
+        return;
+    }
+    if (c.taps == 1 && shortcut_wgrad_by_gemm(s.act, c)) {
         const int64_t pixels = (int64_t)B * c.h_out * c.h_out;
         const uint16_t* xs = reinterpret_cast<const uint16_t*>(x);
         if (c.stride != 1) {
