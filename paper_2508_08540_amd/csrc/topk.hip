@@ -122,19 +122,23 @@ __global__ __launch_bounds__(256) void sel_threshold_kernel(const uint32_t* __re
 }
 
 __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* total) {
-    __shared__ uint32_t sc[256];
-    sc[threadIdx.x] = v;
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
-        uint32_t add = threadIdx.x >= (unsigned)o ? sc[threadIdx.x - o] : 0u;
-        __syncthreads();
-        sc[threadIdx.x] += add;
-        __syncthreads();
+    // inclusive scan inside each wave by shuffles, then the four wave totals through LDS
+    __shared__ uint32_t wave_total[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t below = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += below;
     }
-    uint32_t incl = sc[threadIdx.x];
-    if (total) *total = sc[255];
+    if (lane == 63) wave_total[wave] = incl;
     __syncthreads();
-    return incl - v;
+    uint32_t before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_total[w];
+    const uint32_t all = (wave_total[0] + wave_total[1]) + (wave_total[2] + wave_total[3]);
+    __syncthreads();   // wave_total may be written again by the next call
+    if (total) *total = all;
+    return before + incl - v;
 }
 
 __global__ __launch_bounds__(256) void sel_count_kernel(const float* __restrict__ losses, int64_t N, const SelInfo* __restrict__ info,
@@ -207,7 +211,32 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ 
         }
 }
 
+// The same in one launch for arrays of up to 8192 entries (pools of up to about 65 000 losses; above that the strided
+// per-thread loads cost more than the two launches saved): thread t of the one workgroup owns entries
+// [t * per, (t + 1) * per), all loaded before anything else so that the loads overlap.
+#define SCAN_ONE_LAUNCH_MAX 8192
+__global__ __launch_bounds__(256) void scan_small_kernel(uint32_t* __restrict__ data, int n, int per) {
+    uint32_t v[32];
+    const int base = threadIdx.x * per;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) v[j] = (j < per && base + j < n) ? data[base + j] : 0u;
+    uint32_t c = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) c += v[j];
+    uint32_t run = block_exclusive_scan_256(c, nullptr);
+#pragma unroll
+    for (int j = 0; j < 32; ++j)
+        if (j < per && base + j < n) {
+            data[base + j] = run;
+            run += v[j];
+        }
+}
+
 static void exclusive_scan_u32(hipStream_t s, uint32_t* data, int64_t n, uint32_t* sums) {
+    if (n <= SCAN_ONE_LAUNCH_MAX) {
+        hipLaunchKernelGGL(scan_small_kernel, dim3(1), dim3(256), 0, s, data, (int)n, (int)((n + 255) / 256));
+        return;
+    }
     int n_chunks = (int)((n + SCAN_CHUNK - 1) / SCAN_CHUNK);
     hipLaunchKernelGGL(scan_chunk_sums_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums);
     hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sums, n_chunks);
