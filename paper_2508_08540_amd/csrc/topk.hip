@@ -266,15 +266,21 @@ __global__ __launch_bounds__(256) void radix_count_kernel(const uint32_t* __rest
 
 // table has been exclusive-scanned: table[d * n_blocks + b] = first output slot of digit d in block b.
 // Each wave owns RTILE/4 consecutive elements of the tile and ranks them 64 at a time with ballots, so the
-// order of equal digits is the input order (stable).
+// order of equal digits is the input order (stable).  The ranked pairs are first put in digit order in LDS;
+// the tile is then written out position by position, so that neighbouring lanes write neighbouring slots of a
+// digit's run instead of 64 unrelated addresses per instruction.  Small sorts (RITER = 8, launch-bound) skip the staging
+// and write from the ranking loop.
 template <int RITER>
 __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ idx_in,
                                                             uint32_t* __restrict__ keys_out, uint32_t* __restrict__ idx_out,
                                                             const SelInfo* __restrict__ info, int shift,
                                                             const uint32_t* __restrict__ table, int n_blocks) {
-    __shared__ uint32_t cnt[4][256];
-    const uint32_t M = info->M;
     constexpr int RTILE = RITER * 256;
+    constexpr bool STAGED = RITER >= 16;
+    __shared__ uint32_t cnt[4][256];
+    __shared__ uint32_t to_global[256];   // global slot of a digit's first element minus its slot in the tile
+    __shared__ uint32_t kbuf[STAGED ? RTILE : 1], ibuf[STAGED ? RTILE : 1];
+    const uint32_t M = info->M;
     const int64_t base = (int64_t)blockIdx.x * RTILE;
     if (base >= M) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -291,12 +297,21 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __re
         if (valid) atomicAdd(&cnt[wave][(key[it] >> shift) & 255u], 1u);
     }
     __syncthreads();
-    {   // per digit: turn wave counts into starting slots (global start + counts of lower waves)
-        uint32_t run = table[(int64_t)threadIdx.x * n_blocks + blockIdx.x];
+    {   // per digit: slots of the tile in digit order, waves in order inside a digit
+        uint32_t c[4], tile_count = 0;
         for (int w = 0; w < 4; ++w) {
-            uint32_t c = cnt[w][threadIdx.x];
+            c[w] = cnt[w][threadIdx.x];
+            tile_count += c[w];
+        }
+        uint32_t run = table[(int64_t)threadIdx.x * n_blocks + blockIdx.x];   // direct: global slots
+        if (STAGED) {
+            const uint32_t in_tile = block_exclusive_scan_256(tile_count, nullptr);
+            to_global[threadIdx.x] = run - in_tile;
+            run = in_tile;
+        }
+        for (int w = 0; w < 4; ++w) {
             cnt[w][threadIdx.x] = run;
-            run += c;
+            run += c[w];
         }
     }
     __syncthreads();
@@ -315,12 +330,26 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __re
         if (valid) {
             uint32_t rank = __popcll(peers & lt);
             uint32_t pos = cnt[wave][d] + rank;
-            keys_out[pos] = key[it];
-            idx_out[pos] = id[it];
+            if (STAGED) {
+                kbuf[pos] = key[it];
+                ibuf[pos] = id[it];
+            } else {
+                keys_out[pos] = key[it];
+                idx_out[pos] = id[it];
+            }
         }
         __builtin_amdgcn_wave_barrier();
         if (valid && (peers & lt) == 0ull) cnt[wave][d] += (uint32_t)__popcll(peers);  // lowest peer advances the slot
         __builtin_amdgcn_wave_barrier();
+    }
+    if (!STAGED) return;
+    __syncthreads();
+    const int n_valid = (int)(M - base < (uint32_t)RTILE ? M - base : (uint32_t)RTILE);
+    for (int j = threadIdx.x; j < n_valid; j += 256) {
+        const uint32_t k = kbuf[j];
+        const uint32_t pos = to_global[(k >> shift) & 255u] + (uint32_t)j;
+        keys_out[pos] = k;
+        idx_out[pos] = ibuf[j];
     }
 }
 
