@@ -139,3 +139,23 @@ def test_workers_side_by_side_give_the_same_bits(env):
     for t, seg in zip(taus, segments):
         seen.update(seg[:min(len(seg), 4 * t)].tolist())
     assert np.isfinite(one[0]).all() and (one[2] != -3.0).sum() == len(seen)
+
+
+def test_transformer_round_with_token_sequences(env):
+    """The round with the sequence model (int32 token pool, no buffers, bf16 factors): against the oracle's round."""
+    torch, bls, ctx = env
+    cfg = synth.workload("transformer")
+    vocab, L, D, H, F, layers, N = 120, 12, 32, 4, 64, 1, 20
+    model = bls.Model.transformer(vocab, L, D, H, F, layers, "bf16")
+    omodel = oracle.TransformerLM(vocab, L, D, H, F, layers, operand=oracle.round_bf16)
+    p = synth.transformer_init(cfg["id"], vocab, L, D, F, layers, perturb=0.1)
+    x, y = synth.token_pool(cfg["id"], N, L, vocab)
+    workers = [(2, np.arange(0, 8), _zeros(p)), (1, np.arange(6, 12), _zeros(p)), (2, np.arange(12, 20), _zeros(p))]
+    got_p, got_b, got_m, got_t, ref_p, ref_b, ref_m, ref_t, table0 = _round(env, model, omodel, p, {}, x, y, workers, 4, 0.05, 0.9, 0.0, N)
+    keep = [k for k in ref_p if not k.endswith("attn.k.bias")]     # zero gradient up to rounding, see the transformer tests
+    for k in keep:
+        change = np.linalg.norm(ref_p[k] - p[k])
+        assert np.linalg.norm(got_p[k] - ref_p[k]) <= 1e-2 * change + 4 * 2.0 ** -24 * np.linalg.norm(ref_p[k]), k
+    touched = ref_t != table0.astype(np.float64)
+    assert touched.sum() == 18 and np.array_equal(got_t[~touched], table0[~touched])
+    assert_losses_close(got_t[touched], ref_t[touched], rtol=1e-3)

@@ -62,3 +62,21 @@ def test_zero_learning_rate_leaves_the_global_model_alone_and_equal_steps_averag
     singles = [oracle.local_step(m, p, {}, _zeros(p), x, y, w["idx"], 4, 2, 0.05)[0] for w in workers]
     for k in p:
         np.testing.assert_allclose(gp[k], sum(s[k] for s in singles) / 3.0, rtol=0, atol=1e-15)
+
+
+def test_running_statistics_are_aggregated_with_the_same_weights():
+    cfg = synth.workload("resnet20_fp32")
+    widths, blocks, hw = (16, 16, 16), 1, 8
+    m = oracle.ResNetCifar(widths, blocks)
+    p, b = synth.resnet_init(cfg["id"], widths, blocks, 10, perturb_bn=0.1)
+    x, y = synth.image_pool(cfg["id"], 16, 10, hw=hw)
+    ia, ib = np.arange(0, 8), np.arange(8, 16)
+    pa, ba, _, _ = oracle.local_step(m, p, b, _zeros(p), x, y, ia, 4, 2, 0.05, 0.9)
+    pb, bb, _, _ = oracle.local_step(m, p, b, _zeros(p), x, y, ib, 4, 1, 0.05, 0.9)
+    workers = [dict(tau=2, idx=ia, momentum=_zeros(p)), dict(tau=1, idx=ib, momentum=_zeros(p))]
+    gp, gb, _, _ = oracle.communication_round(m, p, b, workers, x, y, 4, 0.05, 0.9)
+    for k in b:
+        np.testing.assert_allclose(gb[k], (2.0 * ba[k] + 1.0 * bb[k]) / 3.0, rtol=0, atol=1e-14)
+        assert not np.allclose(ba[k], bb[k])          # the two workers really saw different batches
+    for k in p:
+        np.testing.assert_allclose(gp[k], (2.0 * pa[k] + 1.0 * pb[k]) / 3.0, rtol=0, atol=1e-14)
