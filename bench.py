@@ -246,6 +246,8 @@ def sequence_line(args, cfg, model, prof, phases, value, ms_per_step, finite):
     bf16 = cfg.get("act_dtype") == "bf16"
     peak = BF16_MFMA_PEAK_TFLOPS if bf16 else FP32_MFMA_PEAK_TFLOPS
     symbol = symbol.replace("gemm_tiled_kernel", "gemm16_kernel").replace("gemm_split_reduce_kernel", "gemm16_split_reduce_kernel") if bf16 else symbol
+    if bf16 and dom == "gemm":
+        symbol = "gemm16_kernel + attention16_kernel (forward, input-gradient and attention launches)"
     roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4), "traffic": None, "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2),
                 "launches_per_step": dom_cnt // args.steps}

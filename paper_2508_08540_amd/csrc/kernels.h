@@ -243,6 +243,11 @@ void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const flo
 size_t layernorm_bwd_partial_floats(int64_t T, int D);
 void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
                           uint16_t* dx16, float* part, float* dgb);
+// Fused self-attention with bf16 factors for short sequences (L <= 128, L % 8 == 0, dh 32 or 64): ctx = softmax(alpha q k^T) v per
+// (sample, head); P / P16 (nullable) keep the probabilities as [B][H][L][L].  Returns false, having launched nothing, for
+// anything else.
+bool launch_attention16(hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v, int ld, int B, int H, int L, int dh, float alpha,
+                        uint16_t* ctx, int ldc, float* P, uint16_t* P16);
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n);

@@ -19,7 +19,7 @@
 
 namespace {
 
-constexpr int SCORE_SEQS = 128;  // sequences scored together: 16384 tokens fill the chip in every product (logits: 2 GiB at a 32000-word vocabulary)
+constexpr int SCORE_SEQS = 256;  // sequences scored together: 32768 tokens give every product three workgroups per compute unit (fp32 logits: 4 GiB at a 32000-word vocabulary, element offsets below 2^31)
 
 // A tensor as fp32 (f), as bf16 (h), or both; a NULL member does not exist in this mode.
 struct Mat {
@@ -57,6 +57,17 @@ int wgrad_splits(int M, int N, int64_t K) {
     if (s > max_s) s = max_s;
     if (s > 64) s = 64;
     return (int)s;
+}
+
+// Splits of a long contraction whose output has too few tiles to keep three workgroups on every compute unit (what
+// hides the load latency of the K loop); only for fp32 outputs, since the partial sums are added by a second kernel.
+#define DGRAD_SPLIT_MIN_K 4096
+int dgrad_splits(int64_t M, int N, int K) {
+    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
+    if (K < DGRAD_SPLIT_MIN_K || tiles >= 512) return 1;
+    int64_t s = ceil_div(768, tiles);
+    if (s > K / 1024) s = K / 1024;
+    return (int)(s > 1 ? s : 1);
 }
 
 enum Kind { F32_ONLY, BOTH, FACTOR_ONLY };   // FACTOR_ONLY: fp32 in fp32 mode, bf16 alone in bf16 mode
@@ -128,6 +139,11 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     need(F, D);
     need(D, F);
     need(V, D);
+    for (int n_out : {D, F, V})
+        for (int n_in : {D, F}) {
+            const size_t f = gemm_tiled_partial_floats((int)T, n_in, dgrad_splits(T, n_in, n_out));
+            part = f > part ? f : part;
+        }
     s.part = c.take<float>(part ? part : 1);
     size_t cs = colsum_partial_floats(T, F > D ? F : D);
     const size_t ln = layernorm_bwd_partial_floats(T, D), pos = colsum_partial_floats(B, L * D);
@@ -233,6 +249,10 @@ struct Net {
         p.out = dx; p.ldc = n_in;
         p.R = R;
         p.M = (int)T; p.N = n_in; p.K = n_out;
+        if (s->bf && !dx.h) {
+            p.splits = dgrad_splits(T, n_in, n_out);
+            p.part = s->part;
+        }
         multiply(ctx, st, s->bf, p, PROF_GEMM);
     }
     // dW[n_out][n_in] = dy^T x, contraction over the T tokens
@@ -277,10 +297,19 @@ struct Net {
             linear(x, T, D, e.wq, e.bq, D, a.q);
             linear(x, T, D, e.wk, e.bk, D, a.k);
             linear(x, T, D, e.wv, e.bv, D, a.v);
-            // scores into the fp32 probability buffer, softmax in place (kept in fp32 only where something reads it)
-            attention(a.q, false, false, a.k, false, false, Mat{a.p.f, nullptr}, true, L, dh, 1.f / sqrtf((float)dh));
-            PROF(ctx, PROF_NORM, launch_softmax_rows(st, a.p.f, a.p.h, keep || !s->bf, (int64_t)B * H * L, L));
-            attention(a.p, true, false, a.v, false, true, a.ctx, false, dh, L, 1.f);
+            const float att = 1.f / sqrtf((float)dh);
+            bool fused = false;
+            if (s->bf) {
+                // short sequences: scores, softmax and weighted values of a (sample, head) in one workgroup
+                ProfScope prof_(ctx, PROF_GEMM);
+                fused = launch_attention16(st, a.q.h, a.k.h, a.v.h, D, B, H, L, dh, att, a.ctx.h, D, keep ? a.p.f : nullptr, keep ? a.p.h : nullptr);
+            }
+            if (!fused) {
+                // scores into the fp32 probability buffer, softmax in place (kept in fp32 only where something reads it)
+                attention(a.q, false, false, a.k, false, false, Mat{a.p.f, nullptr}, true, L, dh, att);
+                PROF(ctx, PROF_NORM, launch_softmax_rows(st, a.p.f, a.p.h, keep || !s->bf, (int64_t)B * H * L, L));
+                attention(a.p, true, false, a.v, false, true, a.ctx, false, dh, L, 1.f);
+            }
             linear(a.ctx, T, D, e.wo, e.bo, D, Mat{a.r1, nullptr}, x.f);
             PROF(ctx, PROF_NORM, launch_layernorm(st, a.r1, T, D, params + e.ln1_g, params + e.ln1_b, a.h1.f, a.h1.h, keep ? a.st1 : nullptr));
             // u = h1 W1^T + b1 and g = gelu(u) from one epilogue; scoring does not keep u
