@@ -224,7 +224,7 @@ __device__ __forceinline__ void g16_ce_block(const Gemm16Desc& d, const f32x4 (&
 // per flop, for products with enough tiles to fill the chip that way).
 // EPI: 0 plain epilogue, 1 also writes gelu(C) (its erf code stays out of the other instantiations), 2 softmax statistics
 template <bool AK, bool BK, bool FAST, int EPI, int MB>
-__global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc d) {
+__global__ __launch_bounds__(256, MB == 8 ? 2 : 3) void gemm16_kernel(Gemm16Desc d) {
     constexpr int NPA = MB / 4, TILE_M = 32 * MB;
     __shared__ __attribute__((aligned(16))) bf16_t As[2][TILE_M * G16_PITCH], Bs[2][G16_TILE * G16_PITCH];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -255,13 +255,15 @@ __global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc
         const int sidx = i + rot < steps ? i + rot : i + rot - steps;
         return k_begin + sidx * G16_K;
     };
-    u32x4 pa[2 * NPA], pb[2];
+    // Two K steps of global loads are in flight (register sets 0 and 1, used in turn) while a third is multiplied
+    // out of LDS: with one to three workgroups per compute unit it is the bytes in flight that bound the rate.
+    u32x4 pa0[2 * NPA], pb0[2], pa1[2 * NPA], pb1[2];
     uint32_t offa[2 * NPA], offb[2];
     if (FAST) {
         g16_offsets<AK, NPA>(offa, d.lda, d.M, m0);
         g16_offsets<BK, 1>(offb, d.ldb, d.N, n0);
     }
-    auto fetch = [&](int k) {
+    auto fetch = [&](int k, u32x4 (&pa)[2 * NPA], u32x4 (&pb)[2]) {
         if (FAST) {
             g16_fetch_fast<AK, NPA>(A, offa, d.lda, k, pa);
             g16_fetch_fast<BK, 1>(B, offb, d.ldb, k, pb);
@@ -270,16 +272,7 @@ __global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc
             g16_fetch<BK, 1>(B, d.ldb, d.N, n0, k, k_end, bvec, pb);
         }
     };
-    if (steps > 0) {
-        fetch(k_of(0));
-        g16_put<AK, NPA>(As[0], pa);
-        g16_put<BK, 1>(Bs[0], pb);
-    }
-    __syncthreads();
-    int buf = 0;
-    for (int i = 0; i < steps; ++i) {
-        const bool more = i + 1 < steps;
-        if (more) fetch(k_of(i + 1));
+    auto compute = [&](int buf) {
         const bf16_t* as = As[buf] + (wm * 16 * MB + r) * G16_PITCH + 8 * g;
         const bf16_t* bs = Bs[buf] + (wn * 64 + r) * G16_PITCH + 8 * g;
         bf16x8_v a[MB], b[4];
@@ -291,12 +284,49 @@ __global__ __launch_bounds__(256, MB == 8 ? 2 : 1) void gemm16_kernel(Gemm16Desc
         for (int mt = 0; mt < MB; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[nt], a[mt], acc[mt][nt], 0, 0, 0);
-        if (more) {
-            g16_put<AK, NPA>(As[buf ^ 1], pa);
-            g16_put<BK, 1>(Bs[buf ^ 1], pb);
+    };
+    if (steps > 0) {
+        fetch(k_of(0), pa0, pb0);
+        g16_put<AK, NPA>(As[0], pa0);
+        g16_put<BK, 1>(Bs[0], pb0);
+    }
+    if (steps > 1) fetch(k_of(1), pa0, pb0);
+    __syncthreads();
+    int i = 0;
+    // steady state, two steps per turn: every fetch and store is unconditional here, so that the wait before a store
+    // into LDS counts the younger set's loads as still in flight
+    for (; i + 3 < steps; i += 2) {
+        fetch(k_of(i + 2), pa1, pb1);
+        compute(0);
+        g16_put<AK, NPA>(As[1], pa0);
+        g16_put<BK, 1>(Bs[1], pb0);
+        __syncthreads();
+        fetch(k_of(i + 3), pa0, pb0);
+        compute(1);
+        g16_put<AK, NPA>(As[0], pa1);
+        g16_put<BK, 1>(Bs[0], pb1);
+        __syncthreads();
+    }
+    // the last (up to three) steps
+    while (i < steps) {
+        // LDS buffer 0 holds step i, register set 0 step i + 1
+        if (i + 2 < steps) fetch(k_of(i + 2), pa1, pb1);
+        compute(0);
+        if (i + 1 < steps) {
+            g16_put<AK, NPA>(As[1], pa0);
+            g16_put<BK, 1>(Bs[1], pb0);
         }
         __syncthreads();
-        buf ^= 1;
+        if (++i >= steps) break;
+        // LDS buffer 1 holds step i, register set 1 step i + 1
+        if (i + 2 < steps) fetch(k_of(i + 2), pa0, pb0);
+        compute(1);
+        if (i + 1 < steps) {
+            g16_put<AK, NPA>(As[0], pa1);
+            g16_put<BK, 1>(Bs[0], pb1);
+        }
+        __syncthreads();
+        ++i;
     }
 
     const bool plain = d.splits > 1;   // partial sums go out as they are; the reduction applies the epilogue

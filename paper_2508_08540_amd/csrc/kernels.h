@@ -248,6 +248,9 @@ void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const 
 // anything else.
 bool launch_attention16(hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v, int ld, int B, int H, int L, int dh, float alpha,
                         uint16_t* ctx, int ldc, float* P, uint16_t* P16);
+// Its backward pass from dctx (bf16) and the fp32 probabilities: dq, dk, dv as fp32 and bf16, same shapes and limits.
+bool launch_attention16_bwd(hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dctx, const float* P, int ld, int B,
+                            int H, int L, int dh, float alpha, float* dq, float* dk, float* dv, uint16_t* dq16, uint16_t* dk16, uint16_t* dv16);
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n);

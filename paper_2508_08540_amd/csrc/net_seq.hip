@@ -424,11 +424,18 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db.f, T, D, s.cpart, s.grad + e.bo));
             net.linear_dgrad(s.db, T, D, e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
-            net.attention(a.p, true, true, s.dc, false, true, s.dv, false, dh, L, 1.f);                      // dv = P^T dctx
-            net.attention(s.dc, false, false, a.v, false, false, Mat{s.ds.f, nullptr}, true, L, dh, 1.f);    // dP = dctx v^T
-            PROF(ctx, PROF_NORM, launch_softmax_bwd_rows(st, s.ds.f, a.p.f, s.ds.h, (int64_t)B * H * L, L, att));
-            net.attention(s.ds, true, false, a.k, false, true, s.dq, false, dh, L, 1.f);                     // dq = dS k
-            net.attention(s.ds, true, true, a.q, false, true, s.dk, false, dh, L, 1.f);                      // dk = dS^T q
+            bool fused = false;
+            if (s.bf) {
+                ProfScope prof_(ctx, PROF_GEMM);
+                fused = launch_attention16_bwd(st, a.q.h, a.k.h, a.v.h, s.dc.h, a.p.f, D, B, H, L, dh, att, s.dq.f, s.dk.f, s.dv.f, s.dq.h, s.dk.h, s.dv.h);
+            }
+            if (!fused) {
+                net.attention(a.p, true, true, s.dc, false, true, s.dv, false, dh, L, 1.f);                      // dv = P^T dctx
+                net.attention(s.dc, false, false, a.v, false, false, Mat{s.ds.f, nullptr}, true, L, dh, 1.f);    // dP = dctx v^T
+                PROF(ctx, PROF_NORM, launch_softmax_bwd_rows(st, s.ds.f, a.p.f, s.ds.h, (int64_t)B * H * L, L, att));
+                net.attention(s.ds, true, false, a.k, false, true, s.dq, false, dh, L, 1.f);                     // dq = dS k
+                net.attention(s.ds, true, true, a.q, false, true, s.dk, false, dh, L, 1.f);                      // dk = dS^T q
+            }
             // q, k, v projections of x
             net.linear_wgrad(s.dq, x, T, D, D, e.wq);
             net.linear_wgrad(s.dk, x, T, D, D, e.wk);

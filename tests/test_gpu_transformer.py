@@ -44,6 +44,8 @@ SHAPES = [
     (700, 16, 256, 8, 1024, 1, 40),  # 640 tokens: several row tiles, split token contraction in the weight gradients
     (90, 128, 64, 2, 64, 1, 2),      # the measured sequence length: attention rows of 128, two rows per wave in the softmax
     (64, 72, 32, 4, 48, 1, 3),       # rows of 72: the short-row softmax with idle lanes, head width 8
+    (120, 72, 128, 2, 64, 1, 3),     # head width 64, 72 tokens: the one-workgroup attention (bf16 factors) with a ragged row block
+    (80, 40, 64, 2, 48, 2, 2),       # head width 32, 40 tokens: the same with more than half of the score tile empty
 ]
 
 
