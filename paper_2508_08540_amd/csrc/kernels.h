@@ -236,6 +236,21 @@ struct FixRangeTable {
 void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D, const float* tok, const float* pos, float* h, uint16_t* h16);
 void launch_to_bf16(hipStream_t s, const float* in, uint16_t* out, int64_t n);
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok);
+// Column sums in two halves, the second half of many of them in one launch: partial sums of row chunks land in one
+// buffer (part_off), the table kernel folds each job's rows in index order into out[out_off ..].
+#define COLSUM_TABLE_MAX 64
+struct ColsumJob {
+    int64_t part_off, out_off;
+    int rows, N;
+};
+struct ColsumTable {
+    ColsumJob j[COLSUM_TABLE_MAX];
+    int n;
+};
+int launch_colsum_partial(hipStream_t s, const float* X, int64_t M, int N, float* part);
+void launch_colsum_table(hipStream_t s, const ColsumTable& tab, const float* part, float* out);
+int launch_layernorm_bwd_partial(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
+                                 uint16_t* dx16, float* part);
 size_t colsum_partial_floats(int64_t M, int N);
 void launch_colsum_tokens(hipStream_t s, const float* X, int64_t M, int N, float* part, float* out);
 void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad);

@@ -45,6 +45,7 @@ struct SeqScratch {
     Mat dlogits;                    // fp32 mode: the logits buffer itself
     Mat db, dc, dq, dk, dv, df, ds;
     float *grad, *da, *part, *cpart;
+    size_t cpart_floats;
     fixsum_t* acc;
     int64_t acc_count;
 };
@@ -145,10 +146,11 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
             part = f > part ? f : part;
         }
     s.part = c.take<float>(part ? part : 1);
-    size_t cs = colsum_partial_floats(T, F > D ? F : D);
-    const size_t ln = layernorm_bwd_partial_floats(T, D), pos = colsum_partial_floats(B, L * D);
-    cs = cs > ln ? cs : ln;
-    s.cpart = c.take<float>(cs > pos ? cs : pos);
+    // partial column sums of one backward pass: per layer five D-wide and one F-wide bias gradient and two layer norms
+    const size_t per_layer = 5 * colsum_partial_floats(T, D) + colsum_partial_floats(T, F) + 2 * layernorm_bwd_partial_floats(T, D);
+    const size_t pos = colsum_partial_floats(B, L * D);
+    s.cpart_floats = per_layer * layers > pos ? per_layer * layers : pos;
+    s.cpart = c.take<float>(s.cpart_floats);
     s.acc_count = (int64_t)V * D;   // fixed-point accumulators of the token-embedding gradient
     s.acc = c.take<fixsum_t>(s.acc_count);
     return s;
@@ -383,6 +385,39 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     emb_tab.n = 1;
     emb_tab.r[0] = {0, m->enc_tok, (int64_t)V * D};
     PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.acc), s.acc_count * 2));
+    // Column sums (bias and layer-norm gradients) leave their partial sums in s.cpart; one launch at the end of the
+    // backward pass, or when the table or the buffer is full, folds them all into the gradient.
+    ColsumTable sums{};
+    size_t sums_used = 0;
+    auto flush_sums = [&]() {
+        if (sums.n > 0) PROF(ctx, PROF_NORM, launch_colsum_table(st, sums, s.cpart, s.grad));
+        sums.n = 0;
+        sums_used = 0;
+    };
+    auto reserve_sums = [&](size_t floats) {
+        if (sums.n == COLSUM_TABLE_MAX || sums_used + floats > s.cpart_floats) flush_sums();
+        return s.cpart + sums_used;
+    };
+    auto push_sums = [&](int rows, int N, int64_t out_off) {
+        sums.j[sums.n++] = ColsumJob{(int64_t)sums_used, out_off, rows, N};
+        sums_used += (size_t)rows * N;
+    };
+    auto bias_grad = [&](const float* dy, int N, int64_t out_off) {
+        if (T <= 64) {
+            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, dy, T, N, nullptr, s.grad + out_off));
+            return;
+        }
+        float* part = reserve_sums(colsum_partial_floats(T, N));
+        int rows = 0;
+        PROF(ctx, PROF_NORM, rows = launch_colsum_partial(st, dy, T, N, part));
+        push_sums(rows, N, out_off);
+    };
+    auto layernorm_bwd = [&](const float* dy, const float* xin, const float* stats, int64_t g_off, float* dx, uint16_t* dx16) {
+        float* part = reserve_sums(layernorm_bwd_partial_floats(T, D));
+        int rows = 0;
+        PROF(ctx, PROF_NORM, rows = launch_layernorm_bwd_partial(st, dy, xin, stats, T, D, params + g_off, dx, dx16, part));
+        push_sums(rows, 2 * D, g_off);
+    };
     const float gscale = 1.f / (float)T;   // mean over the batch of per-sample means over positions
     const float att = 1.f / sqrtf((float)dh);
     const Mat da{s.da, nullptr};
@@ -407,21 +442,21 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             const LayerAct& a = s.act[l];
             const Mat x = s.x[l];
             // h = LN2(r2): da holds dh, db receives dr2
-            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r2, a.st2, T, D, params + e.ln2_g, s.db.f, s.db.h, s.cpart, s.grad + e.ln2_g));
+            layernorm_bwd(s.da, a.r2, a.st2, e.ln2_g, s.db.f, s.db.h);
             // r2 = h1 + g W2^T + b2
             net.linear_wgrad(s.db, a.g, T, D, F, e.w2);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db.f, T, D, s.cpart, s.grad + e.b2));
+            bias_grad(s.db.f, D, e.b2);
             net.linear_dgrad(s.db, T, D, e.w2, F, Mat{s.df.f, nullptr});
             PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df.f, a.u, s.df.h, T * F));
             // u = h1 W1^T + b1
             net.linear_wgrad(s.df, a.h1, T, F, D, e.w1);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.df.f, T, F, s.cpart, s.grad + e.b1));
+            bias_grad(s.df.f, F, e.b1);
             net.linear_dgrad(s.df, T, F, e.w1, D, da, s.db.f);   // da = dh1 (both uses of h1)
             // h1 = LN1(r1): db receives dr1
-            PROF(ctx, PROF_NORM, launch_layernorm_bwd(st, s.da, a.r1, a.st1, T, D, params + e.ln1_g, s.db.f, s.db.h, s.cpart, s.grad + e.ln1_g));
+            layernorm_bwd(s.da, a.r1, a.st1, e.ln1_g, s.db.f, s.db.h);
             // r1 = x + ctx Wo^T + bo
             net.linear_wgrad(s.db, a.ctx, T, D, D, e.wo);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.db.f, T, D, s.cpart, s.grad + e.bo));
+            bias_grad(s.db.f, D, e.bo);
             net.linear_dgrad(s.db, T, D, e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
             bool fused = false;
@@ -440,14 +475,15 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             net.linear_wgrad(s.dq, x, T, D, D, e.wq);
             net.linear_wgrad(s.dk, x, T, D, D, e.wk);
             net.linear_wgrad(s.dv, x, T, D, D, e.wv);
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dq.f, T, D, s.cpart, s.grad + e.bq));
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dk.f, T, D, s.cpart, s.grad + e.bk));
-            PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.dv.f, T, D, s.cpart, s.grad + e.bv));
+            bias_grad(s.dq.f, D, e.bq);
+            bias_grad(s.dk.f, D, e.bk);
+            bias_grad(s.dv.f, D, e.bv);
             net.linear_dgrad(s.dq, T, D, e.wq, D, da, s.db.f);    // da = dx, starting from the residual path
             net.linear_dgrad(s.dk, T, D, e.wk, D, da, s.da);
             net.linear_dgrad(s.dv, T, D, e.wv, D, da, s.da);
         }
         // embeddings: position gradient = sum over samples, token gradient = scatter by id
+        flush_sums();
         PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.da, B, L * D, s.cpart, s.grad + m->enc_pos));
         PROF(ctx, PROF_NORM, launch_embed_grad(st, s.tok, T, D, s.da, s.acc));
         PROF(ctx, PROF_UPDATE, launch_fix_finalize(st, emb_tab, s.acc, s.grad));

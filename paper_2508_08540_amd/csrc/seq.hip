@@ -91,6 +91,27 @@ __global__ __launch_bounds__(256) void colsum_rows_kernel(const float* __restric
     if (sl == 0 && n < N) out[n] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
 }
 
+// The same for a table of jobs (blockIdx.y): out[out_off + n] = sum over the job's rows of part[part_off + r * N + n]
+__global__ __launch_bounds__(256) void colsum_table_kernel(ColsumTable tab, const float* __restrict__ part, float* __restrict__ out) {
+    __shared__ float red[4][64];
+    const ColsumJob job = tab.j[blockIdx.y];
+    const int c = threadIdx.x & 63, sl = threadIdx.x >> 6, n = blockIdx.x * 64 + c;
+    if (blockIdx.x * 64 >= job.N) return;
+    const float* X = part + job.part_off;
+    float a0 = 0.f, a1 = 0.f;
+    if (n < job.N) {
+        int r = sl;
+        for (; r + 4 < job.rows; r += 8) {
+            a0 += X[(int64_t)r * job.N + n];
+            a1 += X[(int64_t)(r + 4) * job.N + n];
+        }
+        if (r < job.rows) a0 += X[(int64_t)r * job.N + n];
+    }
+    red[sl][c] = a0 + a1;
+    __syncthreads();
+    if (sl == 0 && n < job.N) out[job.out_off + n] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+}
+
 // out[i] = acc[i] / 2^44, acc[i] = 0; blockIdx.y selects a range
 __global__ __launch_bounds__(256) void fix_finalize_kernel(FixRangeTable tab, fixsum_t* __restrict__ acc, float* __restrict__ grad) {
     const FixRange r = tab.r[blockIdx.y];
@@ -464,6 +485,17 @@ void launch_colsum_tokens(hipStream_t s, const float* X, int64_t M, int N, float
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(nblk(N, 256), nblk(M, 64)), dim3(256), 0, s, X, M, N, part);
     hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(N, 64)), dim3(256), 0, s, part, (int)nblk(M, 64), N, out);
 }
+// First half only: part[r][n] = sum over the 64 rows of chunk r; returns the number of chunks
+int launch_colsum_partial(hipStream_t s, const float* X, int64_t M, int N, float* part) {
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(nblk(N, 256), nblk(M, 64)), dim3(256), 0, s, X, M, N, part);
+    return (int)nblk(M, 64);
+}
+// Second half of up to COLSUM_TABLE_MAX column sums in one launch
+void launch_colsum_table(hipStream_t s, const ColsumTable& tab, const float* part, float* out) {
+    int widest = 1;
+    for (int i = 0; i < tab.n; ++i) widest = tab.j[i].N > widest ? tab.j[i].N : widest;
+    if (tab.n > 0) hipLaunchKernelGGL(colsum_table_kernel, dim3(nblk(widest, 64), tab.n), dim3(256), 0, s, tab, part, out);
+}
 void launch_fix_finalize(hipStream_t s, const FixRangeTable& tab, fixsum_t* acc, float* grad) {
     int64_t longest = 1;
     for (int i = 0; i < tab.n; ++i) longest = tab.r[i].n > longest ? tab.r[i].n : longest;
@@ -482,6 +514,13 @@ void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const 
     const unsigned wgs = nblk(T, 4 * LN_BWD_ROWS_PER_WAVE);
     hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE);
     hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(2 * D, 64)), dim3(256), 0, s, part, (int)wgs, 2 * D, dgb);
+}
+// Without the final sum: part takes one row of (scale, shift) gradient partials per workgroup; returns the number of rows
+int launch_layernorm_bwd_partial(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
+                                 uint16_t* dx16, float* part) {
+    const unsigned wgs = nblk(T, 4 * LN_BWD_ROWS_PER_WAVE);
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE);
+    return (int)wgs;
 }
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n) {
     const int f = store_f32 ? 1 : 0;
