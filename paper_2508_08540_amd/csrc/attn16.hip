@@ -205,7 +205,7 @@ struct AtT {   // a transposed [dh][128 + 8] operand: pieces of two rows per thr
 // out[row][16 nt + 4 g + i] = sum_k X[row][k] Yt[16 nt + ..][k] over the 128 (padded) k, rows 32 wave + 16 mt + r; stored as fp32 and bf16
 template <int DH>
 __device__ __forceinline__ void at_product_store(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yt, int wave, int r, int g, int L,
-                                                 float* __restrict__ out, bf16_t* __restrict__ out16, int ldo) {
+                                                 float* __restrict__ out, bf16_t* __restrict__ out16, int ldo, float* __restrict__ colsum) {
     f32x4 o[2][DH / 16];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -234,13 +234,26 @@ __device__ __forceinline__ void at_product_store(const bf16_t* __restrict__ X, c
                 *reinterpret_cast<at_u32x2*>(out16 + at) = at_u32x2{at_pack(o[mt][nt][0], o[mt][nt][1]), at_pack(o[mt][nt][2], o[mt][nt][3])};
             }
     }
+    if (colsum) {
+        // sum over the wave's 32 rows (rows past L are exact zeros): the two row blocks, then the 16 lanes of a column quad
+#pragma unroll
+        for (int nt = 0; nt < DH / 16; ++nt) {
+            f32x4 c = o[0][nt] + o[1][nt];
+#pragma unroll
+            for (int sh = 1; sh < 16; sh <<= 1)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) c[i] += __shfl_xor(c[i], sh, 64);
+            if (r == 0) *reinterpret_cast<f32x4*>(colsum + 16 * nt + 4 * g) = c;
+        }
+    }
 }
 
 template <int DH>
 __global__ __launch_bounds__(256, 2) void attention16_bwd_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                               const bf16_t* __restrict__ dctx, const float* __restrict__ P, int ld, int H, int L,
                                                               float alpha, float* __restrict__ dq, float* __restrict__ dk, float* __restrict__ dv,
-                                                              bf16_t* __restrict__ dq16, bf16_t* __restrict__ dk16, bf16_t* __restrict__ dv16) {
+                                                              bf16_t* __restrict__ dq16, bf16_t* __restrict__ dk16, bf16_t* __restrict__ dv16,
+                                                              float* __restrict__ colsum) {
     constexpr int PQ = DH + 8;
     constexpr int RC_ELEMS = 2 * AT_L * PQ, P_ELEMS = AT_L * AT_PP;
     constexpr int R0 = RC_ELEMS > P_ELEMS ? RC_ELEMS : P_ELEMS;
@@ -254,6 +267,9 @@ __global__ __launch_bounds__(256, 2) void attention16_bwd_kernel(const bf16_t* _
     const int b = blockIdx.x / H, h = blockIdx.x - b * H;
     const int64_t head = ((int64_t)b * L) * ld + h * DH;   // first element of the head's slice in a [tokens][ld] tensor
     const float* Ph = P + (int64_t)blockIdx.x * L * L;
+    // partial column sums: [3][4 B][H DH], this wave's row and this head's columns
+    const int64_t cs_plane = (int64_t)4 * (gridDim.x / H) * H * DH;
+    float* cs = colsum ? colsum + ((int64_t)4 * b + wave) * H * DH + h * DH : nullptr;
 
     constexpr int CH = DH / 8;
     for (int i = threadIdx.x; i < AT_L * CH; i += 256) {
@@ -333,7 +349,7 @@ __global__ __launch_bounds__(256, 2) void attention16_bwd_kernel(const bf16_t* _
     // ---- dv[n][d] = sum_m P[m][n] dctx[m][d] -------------------------------------------------------------------------------
     put_transposed(p16);
     __syncthreads();
-    at_product_store<DH>(X, Yt, wave, r, g, L, dv + head, dv16 + head, ld);
+    at_product_store<DH>(X, Yt, wave, r, g, L, dv + head, dv16 + head, ld, cs ? cs + 2 * cs_plane : nullptr);
     __syncthreads();
     // ---- dq[m][d] = sum_n dS[m][n] k[n][d] ---------------------------------------------------------------------------------
     yt.put(Yt);
@@ -343,13 +359,13 @@ __global__ __launch_bounds__(256, 2) void attention16_bwd_kernel(const bf16_t* _
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) *reinterpret_cast<at_u32x2*>(X + (32 * wave + 16 * mt + r) * AT_PP + 16 * nt + 4 * g) = ds16[mt][nt];
     __syncthreads();
-    at_product_store<DH>(X, Yt, wave, r, g, L, dq + head, dq16 + head, ld);
+    at_product_store<DH>(X, Yt, wave, r, g, L, dq + head, dq16 + head, ld, cs);
     __syncthreads();
     // ---- dk[n][d] = sum_m dS[m][n] q[m][d] ---------------------------------------------------------------------------------
     yt.put(Yt);
     put_transposed(ds16);
     __syncthreads();
-    at_product_store<DH>(X, Yt, wave, r, g, L, dk + head, dk16 + head, ld);
+    at_product_store<DH>(X, Yt, wave, r, g, L, dk + head, dk16 + head, ld, cs ? cs + cs_plane : nullptr);
 }
 
 // Returns false (and launches nothing) for shapes or alignments the kernel does not take.
@@ -364,15 +380,16 @@ bool launch_attention16(hipStream_t s, const uint16_t* q, const uint16_t* k, con
 }
 
 bool launch_attention16_bwd(hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dctx, const float* P, int ld, int B,
-                            int H, int L, int dh, float alpha, float* dq, float* dk, float* dv, uint16_t* dq16, uint16_t* dk16, uint16_t* dv16) {
+                            int H, int L, int dh, float alpha, float* dq, float* dk, float* dv, uint16_t* dq16, uint16_t* dk16, uint16_t* dv16,
+                            float* colsum) {
     auto al = [](const void* p, int bytes) { return p != nullptr && (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; };
     if (L < 8 || L > AT_L || L % 8 != 0 || (dh != 32 && dh != 64) || ld % 8 != 0) return false;
     if (!al(q, 16) || !al(k, 16) || !al(v, 16) || !al(dctx, 16) || !al(P, 16) || !al(dq, 16) || !al(dk, 16) || !al(dv, 16) || !al(dq16, 8) ||
-        !al(dk16, 8) || !al(dv16, 8))
+        !al(dk16, 8) || !al(dv16, 8) || (reinterpret_cast<uintptr_t>(colsum) & 15) != 0)
         return false;
     if (dh == 64)
-        hipLaunchKernelGGL(attention16_bwd_kernel<64>, dim3(B * H), dim3(256), 0, s, q, k, v, dctx, P, ld, H, L, alpha, dq, dk, dv, dq16, dk16, dv16);
+        hipLaunchKernelGGL(attention16_bwd_kernel<64>, dim3(B * H), dim3(256), 0, s, q, k, v, dctx, P, ld, H, L, alpha, dq, dk, dv, dq16, dk16, dv16, colsum);
     else
-        hipLaunchKernelGGL(attention16_bwd_kernel<32>, dim3(B * H), dim3(256), 0, s, q, k, v, dctx, P, ld, H, L, alpha, dq, dk, dv, dq16, dk16, dv16);
+        hipLaunchKernelGGL(attention16_bwd_kernel<32>, dim3(B * H), dim3(256), 0, s, q, k, v, dctx, P, ld, H, L, alpha, dq, dk, dv, dq16, dk16, dv16, colsum);
     return true;
 }

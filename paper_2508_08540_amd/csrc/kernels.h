@@ -237,11 +237,11 @@ void launch_embed(hipStream_t s, const int32_t* tokens, int64_t T, int L, int D,
 void launch_to_bf16(hipStream_t s, const float* in, uint16_t* out, int64_t n);
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok);
 // Column sums in two halves, the second half of many of them in one launch: partial sums of row chunks land in one
-// buffer (part_off), the table kernel folds each job's rows in index order into out[out_off ..].
+// buffer (part_off), the table kernel folds each job's rows in a fixed order into out[out_off ..].
 #define COLSUM_TABLE_MAX 64
 struct ColsumJob {
     int64_t part_off, out_off;
-    int rows, N;
+    int rows, N, pitch;   // pitch = floats between the rows of the partial sums
 };
 struct ColsumTable {
     ColsumJob j[COLSUM_TABLE_MAX];
@@ -264,8 +264,11 @@ void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const 
 bool launch_attention16(hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v, int ld, int B, int H, int L, int dh, float alpha,
                         uint16_t* ctx, int ldc, float* P, uint16_t* P16);
 // Its backward pass from dctx (bf16) and the fp32 probabilities: dq, dk, dv as fp32 and bf16, same shapes and limits.
+// colsum (optional) takes partial column sums for the bias gradients: three [4 B][H dh] arrays (dq, dk, dv in that order), row
+// 4 b + w = the sum over the rows of sample b that wave w of its workgroups owned.
 bool launch_attention16_bwd(hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* dctx, const float* P, int ld, int B,
-                            int H, int L, int dh, float alpha, float* dq, float* dk, float* dv, uint16_t* dq16, uint16_t* dk16, uint16_t* dv16);
+                            int H, int L, int dh, float alpha, float* dq, float* dk, float* dv, uint16_t* dq16, uint16_t* dk16, uint16_t* dv16,
+                            float* colsum);
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n);

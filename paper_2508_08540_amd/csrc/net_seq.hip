@@ -147,7 +147,7 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         }
     s.part = c.take<float>(part ? part : 1);
     // partial column sums of one backward pass: per layer five D-wide and one F-wide bias gradient and two layer norms
-    const size_t per_layer = 5 * colsum_partial_floats(T, D) + colsum_partial_floats(T, F) + 2 * layernorm_bwd_partial_floats(T, D);
+    const size_t per_layer = 3 * colsum_partial_floats(T, D) + colsum_partial_floats(T, F) + 2 * layernorm_bwd_partial_floats(T, D) + (size_t)12 * B * D;
     const size_t pos = colsum_partial_floats(B, L * D);
     s.cpart_floats = per_layer * layers > pos ? per_layer * layers : pos;
     s.cpart = c.take<float>(s.cpart_floats);
@@ -395,12 +395,15 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
         sums_used = 0;
     };
     auto reserve_sums = [&](size_t floats) {
-        if (sums.n == COLSUM_TABLE_MAX || sums_used + floats > s.cpart_floats) flush_sums();
-        return s.cpart + sums_used;
+        if (sums.n + 3 > COLSUM_TABLE_MAX || sums_used + floats > s.cpart_floats) flush_sums();
+        float* part = s.cpart + sums_used;
+        sums_used += floats;
+        return part;
     };
-    auto push_sums = [&](int rows, int N, int64_t out_off) {
-        sums.j[sums.n++] = ColsumJob{(int64_t)sums_used, out_off, rows, N};
-        sums_used += (size_t)rows * N;
+    auto push_sums = [&](size_t part_off, int rows, int N, int pitch, int64_t out_off) {
+        if (sums.n == COLSUM_TABLE_MAX) return false;   // callers reserve first, which leaves room for three jobs
+        sums.j[sums.n++] = ColsumJob{(int64_t)part_off, out_off, rows, N, pitch};
+        return true;
     };
     auto bias_grad = [&](const float* dy, int N, int64_t out_off) {
         if (T <= 64) {
@@ -410,13 +413,15 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
         float* part = reserve_sums(colsum_partial_floats(T, N));
         int rows = 0;
         PROF(ctx, PROF_NORM, rows = launch_colsum_partial(st, dy, T, N, part));
-        push_sums(rows, N, out_off);
+        push_sums(part - s.cpart, rows, N, N, out_off);
     };
-    auto layernorm_bwd = [&](const float* dy, const float* xin, const float* stats, int64_t g_off, float* dx, uint16_t* dx16) {
+    // layer norm backward; the column sums of its result are the gradient of the bias at bias_off
+    auto layernorm_bwd = [&](const float* dy, const float* xin, const float* stats, int64_t g_off, float* dx, uint16_t* dx16, int64_t bias_off) {
         float* part = reserve_sums(layernorm_bwd_partial_floats(T, D));
         int rows = 0;
         PROF(ctx, PROF_NORM, rows = launch_layernorm_bwd_partial(st, dy, xin, stats, T, D, params + g_off, dx, dx16, part));
-        push_sums(rows, 2 * D, g_off);
+        push_sums(part - s.cpart, rows, 2 * D, 3 * D, g_off);
+        push_sums(part - s.cpart + 2 * D, rows, D, 3 * D, bias_off);
     };
     const float gscale = 1.f / (float)T;   // mean over the batch of per-sample means over positions
     const float att = 1.f / sqrtf((float)dh);
@@ -442,10 +447,9 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             const LayerAct& a = s.act[l];
             const Mat x = s.x[l];
             // h = LN2(r2): da holds dh, db receives dr2
-            layernorm_bwd(s.da, a.r2, a.st2, e.ln2_g, s.db.f, s.db.h);
+            layernorm_bwd(s.da, a.r2, a.st2, e.ln2_g, s.db.f, s.db.h, e.b2);
             // r2 = h1 + g W2^T + b2
             net.linear_wgrad(s.db, a.g, T, D, F, e.w2);
-            bias_grad(s.db.f, D, e.b2);
             net.linear_dgrad(s.db, T, D, e.w2, F, Mat{s.df.f, nullptr});
             PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df.f, a.u, s.df.h, T * F));
             // u = h1 W1^T + b1
@@ -453,16 +457,18 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             bias_grad(s.df.f, F, e.b1);
             net.linear_dgrad(s.df, T, F, e.w1, D, da, s.db.f);   // da = dh1 (both uses of h1)
             // h1 = LN1(r1): db receives dr1
-            layernorm_bwd(s.da, a.r1, a.st1, e.ln1_g, s.db.f, s.db.h);
+            layernorm_bwd(s.da, a.r1, a.st1, e.ln1_g, s.db.f, s.db.h, e.bo);
             // r1 = x + ctx Wo^T + bo
             net.linear_wgrad(s.db, a.ctx, T, D, D, e.wo);
-            bias_grad(s.db.f, D, e.bo);
             net.linear_dgrad(s.db, T, D, e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
             bool fused = false;
             if (s.bf) {
+                float* part = reserve_sums((size_t)3 * 4 * B * D);
                 ProfScope prof_(ctx, PROF_GEMM);
-                fused = launch_attention16_bwd(st, a.q.h, a.k.h, a.v.h, s.dc.h, a.p.f, D, B, H, L, dh, att, s.dq.f, s.dk.f, s.dv.f, s.dq.h, s.dk.h, s.dv.h);
+                fused = launch_attention16_bwd(st, a.q.h, a.k.h, a.v.h, s.dc.h, a.p.f, D, B, H, L, dh, att, s.dq.f, s.dk.f, s.dv.f, s.dq.h, s.dk.h, s.dv.h, part);
+                const int64_t offs[3] = {e.bq, e.bk, e.bv};
+                for (int i = 0; fused && i < 3; ++i) push_sums(part - s.cpart + (size_t)i * 4 * B * D, 4 * B, D, D, offs[i]);
             }
             if (!fused) {
                 net.attention(a.p, true, true, s.dc, false, true, s.dv, false, dh, L, 1.f);                      // dv = P^T dctx
@@ -475,9 +481,11 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             net.linear_wgrad(s.dq, x, T, D, D, e.wq);
             net.linear_wgrad(s.dk, x, T, D, D, e.wk);
             net.linear_wgrad(s.dv, x, T, D, D, e.wv);
-            bias_grad(s.dq.f, D, e.bq);
-            bias_grad(s.dk.f, D, e.bk);
-            bias_grad(s.dv.f, D, e.bv);
+            if (!fused) {
+                bias_grad(s.dq.f, D, e.bq);
+                bias_grad(s.dk.f, D, e.bk);
+                bias_grad(s.dv.f, D, e.bv);
+            }
             net.linear_dgrad(s.dq, T, D, e.wq, D, da, s.db.f);    // da = dx, starting from the residual path
             net.linear_dgrad(s.dk, T, D, e.wk, D, da, s.da);
             net.linear_dgrad(s.dv, T, D, e.wv, D, da, s.da);

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void colsum_rows_kernel(const float* __restric
     if (sl == 0 && n < N) out[n] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
 }
 
-// The same for a table of jobs (blockIdx.y): out[out_off + n] = sum over the job's rows of part[part_off + r * N + n]
+// The same for a table of jobs (blockIdx.y): out[out_off + n] = sum over the job's rows of part[part_off + r * pitch + n]
 __global__ __launch_bounds__(256) void colsum_table_kernel(ColsumTable tab, const float* __restrict__ part, float* __restrict__ out) {
     __shared__ float red[4][64];
     const ColsumJob job = tab.j[blockIdx.y];
@@ -102,10 +102,10 @@ __global__ __launch_bounds__(256) void colsum_table_kernel(ColsumTable tab, cons
     if (n < job.N) {
         int r = sl;
         for (; r + 4 < job.rows; r += 8) {
-            a0 += X[(int64_t)r * job.N + n];
-            a1 += X[(int64_t)(r + 4) * job.N + n];
+            a0 += X[(int64_t)r * job.pitch + n];
+            a1 += X[(int64_t)(r + 4) * job.pitch + n];
         }
-        if (r < job.rows) a0 += X[(int64_t)r * job.N + n];
+        if (r < job.rows) a0 += X[(int64_t)r * job.pitch + n];
     }
     red[sl][c] = a0 + a1;
     __syncthreads();
@@ -167,19 +167,20 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict_
 
 // dx = inv * (dxh - mean(dxh) - xhat * mean(dxh * xhat)), dxh = dy * g.  A wave walks `rows_per_wave` rows and keeps
 // the column sums of dy * xhat and dy for its channels in registers; the four waves fold theirs through LDS and the
-// workgroup writes one row part[blockIdx.x][0 .. D) = sum dy * xhat, [D .. 2D) = sum dy.
+// workgroup writes one row part[blockIdx.x][0 .. D) = sum dy * xhat, [D .. 2D) = sum dy and, with sum_dx, [2D .. 3D) = sum dx
+// (the gradient of a bias added just before the normalised tensor).
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restrict__ dy, const float* __restrict__ x,
                                                             const float* __restrict__ stats, int64_t T, int D, const float* __restrict__ g,
                                                             float* __restrict__ dx, uint16_t* __restrict__ dx16, float* __restrict__ part,
-                                                            int rows_per_wave) {
-    __shared__ float red[4][2 * 1024];
+                                                            int rows_per_wave, int sum_dx) {
+    __shared__ float red[4][3 * 1024];
     const int lane = threadIdx.x & 63;
     const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     const int64_t t0 = w * rows_per_wave, t1 = t0 + rows_per_wave < T ? t0 + rows_per_wave : T;
-    f32x4 sg[4], sb[4], gg[4];
+    f32x4 sg[4], sb[4], sx[4], gg[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        sg[i] = sb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        sg[i] = sb[i] = sx[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         const int c = 4 * (lane + 64 * i);
         gg[i] = c < D ? *reinterpret_cast<const f32x4*>(g + c) : sg[i];
     }
@@ -212,6 +213,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restr
                 f32x4 o;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) o[j] = inv * (dh[i][j] - m1 - xh[i][j] * m2);
+                sx[i] += o;
                 *reinterpret_cast<f32x4*>(dx + t * D + c) = o;
                 if (dx16) store_bf16x4(dx16 + t * D + c, o);
             }
@@ -226,10 +228,12 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const float* __restr
             for (int j = 0; j < 4; ++j) {
                 red[wave][c + j] = sg[i][j];
                 red[wave][D + c + j] = sb[i][j];
+                red[wave][2 * D + c + j] = sx[i][j];
             }
     }
     __syncthreads();
-    for (int c = threadIdx.x; c < 2 * D; c += 256) part[(int64_t)blockIdx.x * 2 * D + c] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+    const int width = (sum_dx ? 3 : 2) * D;
+    for (int c = threadIdx.x; c < width; c += 256) part[(int64_t)blockIdx.x * width + c] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
 }
 
 // row <- softmax(row), in place when store_f32 is set, and/or as bf16 into p16; one wave per row of length n <= 1024
@@ -507,19 +511,20 @@ void launch_layernorm(hipStream_t s, const float* x, int64_t T, int D, const flo
     hipLaunchKernelGGL(layernorm_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, x, T, D, g, b, y, y16, stats);
 }
 #define LN_BWD_ROWS_PER_WAVE 4
-size_t layernorm_bwd_partial_floats(int64_t T, int D) { return (size_t)nblk(T, 4 * LN_BWD_ROWS_PER_WAVE) * 2 * D; }
+size_t layernorm_bwd_partial_floats(int64_t T, int D) { return (size_t)nblk(T, 4 * LN_BWD_ROWS_PER_WAVE) * 3 * D; }
 // dgb[0 .. D) = gradient of the scale, dgb[D .. 2D) = gradient of the shift; part holds layernorm_bwd_partial_floats(T, D)
 void launch_layernorm_bwd(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
                           uint16_t* dx16, float* part, float* dgb) {
     const unsigned wgs = nblk(T, 4 * LN_BWD_ROWS_PER_WAVE);
-    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE);
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE, 0);
     hipLaunchKernelGGL(colsum_rows_kernel, dim3(nblk(2 * D, 64)), dim3(256), 0, s, part, (int)wgs, 2 * D, dgb);
 }
-// Without the final sum: part takes one row of (scale, shift) gradient partials per workgroup; returns the number of rows
+// Without the final sum: part takes one row of (scale, shift, column sum of dx) partials, 3 D floats, per workgroup;
+// returns the number of rows
 int launch_layernorm_bwd_partial(hipStream_t s, const float* dy, const float* x, const float* stats, int64_t T, int D, const float* g, float* dx,
                                  uint16_t* dx16, float* part) {
     const unsigned wgs = nblk(T, 4 * LN_BWD_ROWS_PER_WAVE);
-    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE);
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(wgs), dim3(256), 0, s, dy, x, stats, T, D, g, dx, dx16, part, LN_BWD_ROWS_PER_WAVE, 1);
     return (int)wgs;
 }
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n) {
