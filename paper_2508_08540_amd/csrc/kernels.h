@@ -272,6 +272,10 @@ bool launch_attention16_bwd(hipStream_t s, const uint16_t* q, const uint16_t* k,
 void launch_softmax_rows(hipStream_t s, float* sc, uint16_t* p16, bool store_f32, int64_t rows, int n);
 void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t* ds16, int64_t rows, int n, float scale);
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n);
+// The same on a [M][N] tensor, leaving partial column sums of the result (returned number of rows x N floats) in part;
+// returns 0 and launches nothing where its vector accesses do not fit
+size_t gelu_bwd_colsum_floats(int64_t M, int N);
+int launch_gelu_bwd_colsum(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t M, int N, float* part);
 // Cross-entropy from the statistics the vocabulary projection left behind: folds the n_parts pairs of a row in index
 // order; tok_loss[t] = max + log(sum) - tlogit[t]; row_stats[t] = (max, sum) if given.
 void launch_ce_combine(hipStream_t s, const float* ce_part, int n_parts, const float* tlogit, int64_t T, float* tok_loss, float* row_stats);

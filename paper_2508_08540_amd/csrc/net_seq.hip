@@ -147,7 +147,7 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         }
     s.part = c.take<float>(part ? part : 1);
     // partial column sums of one backward pass: per layer five D-wide and one F-wide bias gradient and two layer norms
-    const size_t per_layer = 3 * colsum_partial_floats(T, D) + colsum_partial_floats(T, F) + 2 * layernorm_bwd_partial_floats(T, D) + (size_t)12 * B * D;
+    const size_t per_layer = 3 * colsum_partial_floats(T, D) + colsum_partial_floats(T, F) + gelu_bwd_colsum_floats(T, F) + 2 * layernorm_bwd_partial_floats(T, D) + (size_t)12 * B * D;
     const size_t pos = colsum_partial_floats(B, L * D);
     s.cpart_floats = per_layer * layers > pos ? per_layer * layers : pos;
     s.cpart = c.take<float>(s.cpart_floats);
@@ -451,10 +451,20 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
             // r2 = h1 + g W2^T + b2
             net.linear_wgrad(s.db, a.g, T, D, F, e.w2);
             net.linear_dgrad(s.db, T, D, e.w2, F, Mat{s.df.f, nullptr});
-            PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df.f, a.u, s.df.h, T * F));
+            {
+                // du = dg * gelu'(u) with the partial sums of the bias gradient
+                float* part = reserve_sums(gelu_bwd_colsum_floats(T, F));
+                int rows = 0;
+                PROF(ctx, PROF_NORM, rows = launch_gelu_bwd_colsum(st, s.df.f, a.u, s.df.h, T, F, part));
+                if (rows > 0) {
+                    push_sums(part - s.cpart, rows, F, F, e.b1);
+                } else {
+                    PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df.f, a.u, s.df.h, T * F));
+                    bias_grad(s.df.f, F, e.b1);
+                }
+            }
             // u = h1 W1^T + b1
             net.linear_wgrad(s.df, a.h1, T, F, D, e.w1);
-            bias_grad(s.df.f, F, e.b1);
             net.linear_dgrad(s.df, T, F, e.w1, D, da, s.db.f);   // da = dh1 (both uses of h1)
             // h1 = LN1(r1): db receives dr1
             layernorm_bwd(s.da, a.r1, a.st1, e.ln1_g, s.db.f, s.db.h, e.bo);

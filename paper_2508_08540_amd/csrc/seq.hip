@@ -333,6 +333,28 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(float* __restrict__ dg, c
     }
 }
 
+// The same with the column sums of du on the way (the gradient of the bias added before the activation): a workgroup
+// owns GB_ROWS rows of 1024 adjacent columns, a thread four of those columns; part[blockIdx.y][n] = its rows' sum.
+#define GB_ROWS 32
+__global__ __launch_bounds__(256) void gelu_bwd_colsum_kernel(float* __restrict__ dg, const float* __restrict__ u, uint16_t* __restrict__ du16,
+                                                              int64_t M, int N, float* __restrict__ part) {
+    const int n = 4 * (blockIdx.x * 256 + threadIdx.x);
+    if (n >= N) return;
+    const int64_t m0 = (int64_t)blockIdx.y * GB_ROWS, m1 = m0 + GB_ROWS < M ? m0 + GB_ROWS : M;
+    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int64_t m = m0; m < m1; ++m) {
+        const f32x4 d = *reinterpret_cast<const f32x4*>(dg + m * N + n), uu = *reinterpret_cast<const f32x4*>(u + m * N + n);
+        f32x4 q;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) q[j] = d[j] * gelu_df(uu[j]);
+        *reinterpret_cast<f32x4*>(dg + m * N + n) = q;
+        if (du16) store_bf16x4(du16 + m * N + n, q);
+        sum += q;
+    }
+    *reinterpret_cast<f32x4*>(part + (int64_t)blockIdx.y * N + n) = sum;
+}
+
 // Running (max, sum of exp(z - max)) pairs: fold one value or another pair in.
 struct MaxSum {
     float m, s;
@@ -542,6 +564,15 @@ void launch_softmax_bwd_rows(hipStream_t s, float* dp, const float* p, uint16_t*
 void launch_gelu_bwd(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t n) {
     unsigned b = nblk(n, 256);
     hipLaunchKernelGGL(gelu_bwd_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, dg, u, du16, n);
+}
+size_t gelu_bwd_colsum_floats(int64_t M, int N) { return (size_t)nblk(M, GB_ROWS) * N; }
+// dg[M][N] in place and the partial column sums of the result, gelu_bwd_colsum_floats(M, N) floats; N % 4 == 0 and 16-byte
+// aligned pointers (8 for du16) or nothing is launched and 0 comes back; otherwise the number of rows of part
+int launch_gelu_bwd_colsum(hipStream_t s, float* dg, const float* u, uint16_t* du16, int64_t M, int N, float* part) {
+    auto al = [](const void* p, int bytes) { return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; };
+    if (N % 4 != 0 || !al(dg, 16) || !al(u, 16) || !al(du16, 8) || !al(part, 16)) return 0;
+    hipLaunchKernelGGL(gelu_bwd_colsum_kernel, dim3(nblk(N, 1024), nblk(M, GB_ROWS)), dim3(256), 0, s, dg, u, du16, M, N, part);
+    return (int)nblk(M, GB_ROWS);
 }
 void launch_token_ce(hipStream_t s, float* logits, const int32_t* targets, int64_t T, int V, float* tok_loss, float grad_scale, uint16_t* d16) {
     hipLaunchKernelGGL(token_ce_kernel, dim3((unsigned)T), dim3(256), 0, s, logits, targets, V, tok_loss, grad_scale, d16);
