@@ -139,7 +139,7 @@ __device__ __forceinline__ void g16_tile_of_block(int& tile_x, int& tile_y) {
 // Stores a wave's 64 x 64 block; lane (r, g) holds acc[mt][nt][i] = C[m_base + 16 mt + r][n_base + 16 nt + 4 g + i].
 template <bool VEC, int MB, bool GELU>
 __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4 (&acc)[MB][4], int m_base, int n_base, float* C, bf16_t* C16,
-                                                bf16_t* G16, const float* R, int ldc, bool plain, int r, int g) {
+                                                bf16_t* G16, const float* R, const float* bias, int ldc, bool plain, int r, int g) {
 #pragma unroll
     for (int mt = 0; mt < MB; ++mt) {
         const int m = m_base + 16 * mt + r;
@@ -152,7 +152,7 @@ __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4
                 const int64_t at = (int64_t)m * ldc + n;
                 if (!plain) {
                     v *= d.alpha;
-                    if (d.bias) v += *reinterpret_cast<const f32x4*>(d.bias + n);
+                    if (bias) v += *reinterpret_cast<const f32x4*>(bias + n);
                     if (R) v += *reinterpret_cast<const f32x4*>(R + at);
                 }
                 if (C) *reinterpret_cast<f32x4*>(C + at) = v;
@@ -171,7 +171,7 @@ __device__ __forceinline__ void g16_store_block(const Gemm16Desc& d, const f32x4
                         const int64_t at = (int64_t)m * ldc + n + i;
                         if (!plain) {
                             v *= d.alpha;
-                            if (d.bias) v += d.bias[n + i];
+                            if (bias) v += bias[n + i];
                             if (R) v += R[at];
                         }
                         if (C) C[at] = v;
@@ -335,12 +335,13 @@ __global__ __launch_bounds__(256, MB == 8 ? 2 : 3) void gemm16_kernel(Gemm16Desc
     bf16_t* C16 = (plain || !d.C16) ? nullptr : d.C16 + zoff;
     bf16_t* G16 = (plain || !d.G16) ? nullptr : d.G16 + zoff;
     const float* R = (plain || !d.R) ? nullptr : d.R + zoff;
+    const float* bias = (plain || !d.bias) ? nullptr : d.bias + z1 * d.sbias1;
     const int ldc = plain ? d.N : d.ldc;
     const int m_base = m0 + wm * 16 * MB, n_base = n0 + wn * 64;
     if (EPI == 2) g16_ce_block<MB>(d, acc, m_base, n_base, 2 * tile_x + wn, r, g);   // its own instantiation: the statistics cost registers
     const bool vec = (plain ? (d.N & 3) == 0 : d.c_vec != 0) && m_base + 16 * MB <= d.M && n_base + 64 <= d.N;
-    if (vec) g16_store_block<true, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
-    else g16_store_block<false, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, ldc, plain, r, g);
+    if (vec) g16_store_block<true, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, bias, ldc, plain, r, g);
+    else g16_store_block<false, MB, EPI == 1>(d, acc, m_base, n_base, C, C16, G16, R, bias, ldc, plain, r, g);
 }
 
 // out[i] = alpha * sum_z part[z][i] (+ bias) (+ R), in split order (weight gradients: fp32 output only); blockIdx.y is the
@@ -378,7 +379,7 @@ void launch_gemm16(hipStream_t s, Gemm16Desc d) {
     auto al = [](const void* p, int bytes) { return p == nullptr || (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; };
     d.a_vec = (al(d.A, 16) && d.lda % 8 == 0 && d.sa1 % 8 == 0 && d.sa2 % 8 == 0) ? 1 : 0;
     d.b_vec = (al(d.B, 16) && d.ldb % 8 == 0 && d.sb1 % 8 == 0 && d.sb2 % 8 == 0) ? 1 : 0;
-    d.c_vec = (al(d.C, 16) && al(d.R, 16) && al(d.bias, 16) && al(d.C16, 8) && al(d.G16, 8) && d.ldc % 4 == 0 && d.sc1 % 4 == 0 && d.sc2 % 4 == 0) ? 1 : 0;
+    d.c_vec = (al(d.C, 16) && al(d.R, 16) && al(d.bias, 16) && al(d.C16, 8) && al(d.G16, 8) && d.ldc % 4 == 0 && d.sc1 % 4 == 0 && d.sc2 % 4 == 0 && d.sbias1 % 4 == 0) ? 1 : 0;
     // the unchecked fetch needs 16-byte loads on both operands, whole K steps and 32-bit element offsets
     const int64_t span_a = (int64_t)(d.a_kmajor ? d.K : d.M) * d.lda, span_b = (int64_t)(d.b_kmajor ? d.K : d.N) * d.ldb;
     const bool fast = d.a_vec && d.b_vec && d.K % G16_K == 0 && (!d.a_kmajor || d.M % 8 == 0) && (!d.b_kmajor || d.N % 8 == 0) && d.M >= 8 &&

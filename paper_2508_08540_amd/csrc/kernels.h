@@ -211,6 +211,7 @@ struct Gemm16Desc {
     int a_kmajor, b_kmajor;
     int batch, inner, splits;
     int64_t sa1, sa2, sb1, sb2, sc1, sc2;
+    int64_t sbias1;   // floats between the bias vectors of consecutive z1 (unsplit products only)
     float alpha;
     // optional softmax statistics of the rows of C (single matrix, no split): per row and per 64-column block the pair
     // (max, sum exp(C - max)) into ce_part[2 * ceil(N / 128)][M][2], and C[m][ce_targets[m]] into ce_tlogit[m]

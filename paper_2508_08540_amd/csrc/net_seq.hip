@@ -51,8 +51,8 @@ struct SeqScratch {
 };
 
 // Splits of the token contraction of a weight gradient so that about two waves of workgroups are in flight.
-int wgrad_splits(int M, int N, int64_t K) {
-    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128);
+int wgrad_splits(int M, int N, int64_t K, int batch = 1) {
+    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 128) * batch;
     int64_t s = ceil_div(512, tiles);
     const int64_t max_s = K / 256 > 1 ? K / 256 : 1;
     if (s > max_s) s = max_s;
@@ -80,6 +80,14 @@ Mat take(Carver& c, bool bf, Kind kind, int64_t n) {
     return m;
 }
 
+// Three tensors of n elements each, exactly n apart (one product can then run over all three as a batch)
+void take3(Carver& c, bool bf, Kind kind, int64_t n, Mat& a, Mat& b, Mat& d) {
+    const Mat all = take(c, bf, kind, 3 * n);
+    a = all;
+    b = Mat{all.f ? all.f + n : nullptr, all.h ? all.h + n : nullptr};
+    d = Mat{all.f ? all.f + 2 * n : nullptr, all.h ? all.h + 2 * n : nullptr};
+}
+
 SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     const int L = m->enc_L, D = m->enc_D, H = m->enc_H, F = m->enc_F, V = m->enc_V, layers = (int)m->enc_layers.size();
     const int64_t T = (int64_t)B * L, PP = (int64_t)B * H * L * L;
@@ -98,9 +106,7 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
             continue;
         }
         LayerAct& a = s.act[l];
-        a.q = take(c, bf, FACTOR_ONLY, T * D);
-        a.k = take(c, bf, FACTOR_ONLY, T * D);
-        a.v = take(c, bf, FACTOR_ONLY, T * D);
+        take3(c, bf, FACTOR_ONLY, T * D, a.q, a.k, a.v);
         a.p = take(c, bf, BOTH, PP);
         a.ctx = take(c, bf, FACTOR_ONLY, T * D);
         a.r1 = c.take<float>(T * D);
@@ -126,9 +132,7 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     s.da = c.take<float>(T * D);
     s.db = take(c, bf, BOTH, T * D);
     s.dc = take(c, bf, FACTOR_ONLY, T * D);
-    s.dq = take(c, bf, BOTH, T * D);
-    s.dk = take(c, bf, BOTH, T * D);
-    s.dv = take(c, bf, BOTH, T * D);
+    take3(c, bf, BOTH, T * D, s.dq, s.dk, s.dv);
     s.df = take(c, bf, BOTH, T * F);
     s.ds = take(c, bf, BOTH, PP);
     size_t part = 0;
@@ -137,6 +141,10 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
         part = f > part ? f : part;
     };
     need(D, D);
+    {
+        const size_t f = 3 * gemm_tiled_partial_floats(D, D, wgrad_splits(D, D, T, 3));
+        part = f > part ? f : part;
+    }
     need(F, D);
     need(D, F);
     need(V, D);
@@ -171,7 +179,7 @@ struct Product {
     int M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
     bool a_kmajor = false, b_kmajor = false;
     int batch = 1, inner = 1, splits = 1;
-    int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0;
+    int64_t sa1 = 0, sa2 = 0, sb1 = 0, sb2 = 0, sc1 = 0, sc2 = 0, sbias1 = 0;
     float alpha = 1.f;
     const int32_t* ce_targets = nullptr;   // bf16 mode only: leave softmax statistics of the rows behind
     float *ce_part = nullptr, *ce_tlogit = nullptr;
@@ -187,6 +195,7 @@ void multiply(bls_ctx* ctx, hipStream_t st, bool bf, const Product& p, int prof_
         d.a_kmajor = p.a_kmajor; d.b_kmajor = p.b_kmajor;
         d.batch = p.batch; d.inner = p.inner; d.splits = p.splits;
         d.sa1 = p.sa1; d.sa2 = p.sa2; d.sb1 = p.sb1; d.sb2 = p.sb2; d.sc1 = p.sc1; d.sc2 = p.sc2;
+        d.sbias1 = p.sbias1;
         d.alpha = p.alpha;
         d.ce_part = p.ce_part; d.ce_targets = p.ce_targets; d.ce_tlogit = p.ce_tlogit;
         launch_gemm16(st, d);
@@ -268,6 +277,46 @@ struct Net {
         p.part = s->part;
         multiply(ctx, st, s->bf, p, PROF_CONV_WGRAD);
     }
+    // q, k, v = x Wq^T + bq, ... as one batch of three products where the three weights (and biases, and outputs) are
+    // equally spaced; three products otherwise
+    void qkv(Mat x, int64_t T, const EncLayer& e, const LayerAct& a) const {
+        const int D = m->enc_D;
+        const int64_t sw = e.wk - e.wq, so = a.k.h - a.q.h;
+        if (s->bf && e.wv - e.wk == sw && e.bk - e.bq == sw && e.bv - e.bk == sw && a.v.h - a.k.h == so) {
+            Product p;
+            p.A = x; p.lda = D;
+            p.B = weight(e.wq); p.ldb = D; p.sb1 = sw;
+            p.out = a.q; p.ldc = D; p.sc1 = so;
+            p.bias = params + e.bq; p.sbias1 = sw;
+            p.M = (int)T; p.N = D; p.K = D;
+            p.batch = 3;
+            multiply(ctx, st, true, p, PROF_GEMM);
+            return;
+        }
+        linear(x, T, D, e.wq, e.bq, D, a.q);
+        linear(x, T, D, e.wk, e.bk, D, a.k);
+        linear(x, T, D, e.wv, e.bv, D, a.v);
+    }
+    // Weight gradients of the same three projections from dq, dk, dv
+    void qkv_wgrad(Mat dq, Mat dk, Mat dv, Mat x, int64_t T, const EncLayer& e) const {
+        const int D = m->enc_D;
+        const int64_t sw = e.wk - e.wq, sd = dk.h - dq.h;
+        if (s->bf && e.wv - e.wk == sw && dv.h - dk.h == sd) {
+            Product p;
+            p.A = dq; p.lda = D; p.a_kmajor = true; p.sa1 = sd;
+            p.B = x; p.ldb = D; p.b_kmajor = true;
+            p.out.f = s->grad + e.wq; p.ldc = D; p.sc1 = sw;
+            p.M = D; p.N = D; p.K = (int)T;
+            p.batch = 3;
+            p.splits = wgrad_splits(D, D, T, 3);
+            p.part = s->part;
+            multiply(ctx, st, true, p, PROF_CONV_WGRAD);
+            return;
+        }
+        linear_wgrad(dq, x, T, D, D, e.wq);
+        linear_wgrad(dk, x, T, D, D, e.wk);
+        linear_wgrad(dv, x, T, D, D, e.wv);
+    }
     // Batched product over (sample, head): factors and result are slices of [T][D] activations (row pitch D, head
     // offset D/H) or of a [B][H][L][L] tensor (probs).
     void attention(Mat a, bool a_probs, bool a_kmajor, Mat b, bool b_probs, bool b_kmajor, Mat c, bool c_probs, int N, int K, float alpha) const {
@@ -296,9 +345,7 @@ struct Net {
             const EncLayer& e = m->enc_layers[l];
             const LayerAct& a = s->act[l];
             const Mat x = s->x[l];
-            linear(x, T, D, e.wq, e.bq, D, a.q);
-            linear(x, T, D, e.wk, e.bk, D, a.k);
-            linear(x, T, D, e.wv, e.bv, D, a.v);
+            qkv(x, T, e, a);
             const float att = 1.f / sqrtf((float)dh);
             bool fused = false;
             if (s->bf) {
@@ -488,9 +535,7 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
                 net.attention(s.ds, true, true, a.q, false, true, s.dk, false, dh, L, 1.f);                      // dk = dS^T q
             }
             // q, k, v projections of x
-            net.linear_wgrad(s.dq, x, T, D, D, e.wq);
-            net.linear_wgrad(s.dk, x, T, D, D, e.wk);
-            net.linear_wgrad(s.dv, x, T, D, D, e.wv);
+            net.qkv_wgrad(s.dq, s.dk, s.dv, x, T, e);
             if (!fused) {
                 bias_grad(s.dq.f, D, e.bq);
                 bias_grad(s.dk.f, D, e.bk);
