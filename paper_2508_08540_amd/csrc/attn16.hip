@@ -6,9 +6,9 @@
 //
 // Four waves; wave w owns rows 32 w .. 32 w + 31.  v_mfma_f32_16x16x32_bf16 with the key (value) tile as first operand,
 // so that lane (r, g) holds row r, columns 4 g .. 4 g + 3 of a 16 x 16 block: a row of S lives in four lanes and its
-// softmax needs two shuffles.  LDS: Q and K as [row][dh + 8] (the padding spreads the 16-byte operand reads over the
-// banks), V transposed to [d][128 + 8] (pairs of rows interleaved on the way in), and P as [row][128 + 8] in the space
-// Q and K occupied.
+// softmax needs two shuffles.  LDS: Q and K as [row][dh + 16] (row pitches of 32 bytes more than a multiple of 64 let the
+// 16-byte operand reads run at the full LDS rate), V transposed to [d][128 + 16] (pairs of rows interleaved on the way
+// in), and P as [row][128 + 16] in the space Q and K occupied.
 #include "act.h"
 #include "kernels.h"
 
@@ -19,7 +19,7 @@ typedef uint32_t at_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t at_u32x2 __attribute__((ext_vector_type(2)));
 
 #define AT_L 128          // rows and columns of the padded score tile
-#define AT_PP (AT_L + 8)  // pitch of P and of the transposed V, in bf16 elements
+#define AT_PP (AT_L + 16) // pitch of P and of the transposed V, in bf16 elements: 288 bytes
 
 __device__ __forceinline__ uint32_t at_pack(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((at_f32x2){lo, hi}, at_bf16x2));
@@ -29,7 +29,7 @@ template <int DH>
 __global__ __launch_bounds__(256) void attention16_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                           int ld, int H, int L, float alpha, bf16_t* __restrict__ ctx, int ldc,
                                                           float* __restrict__ P, bf16_t* __restrict__ P16) {
-    constexpr int PQ = DH + 8;                                    // pitch of Q and K
+    constexpr int PQ = DH + 16;                                   // pitch of Q and K
     constexpr int QK_ELEMS = 2 * AT_L * PQ, P_ELEMS = AT_L * AT_PP;
     constexpr int R0 = QK_ELEMS > P_ELEMS ? QK_ELEMS : P_ELEMS;
     __shared__ __attribute__((aligned(16))) bf16_t lds[R0 + DH * AT_PP];
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void attention16_kernel(const bf16_t* __restri
 // one product ahead).
 
 template <int DH>
-struct AtT {   // a transposed [dh][128 + 8] operand: pieces of two rows per thread
+struct AtT {   // a transposed [dh][128 + 16] operand: pieces of two rows per thread
     static constexpr int CH = DH / 8, TASKS = (AT_L / 2) * CH / 256;
     at_u32x4 lo[TASKS], hi[TASKS];
     __device__ __forceinline__ void load(const bf16_t* __restrict__ src, int ld, int L) {
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void attention16_bwd_kernel(const bf16_t* _
                                                               float alpha, float* __restrict__ dq, float* __restrict__ dk, float* __restrict__ dv,
                                                               bf16_t* __restrict__ dq16, bf16_t* __restrict__ dk16, bf16_t* __restrict__ dv16,
                                                               float* __restrict__ colsum) {
-    constexpr int PQ = DH + 8;
+    constexpr int PQ = DH + 16;
     constexpr int RC_ELEMS = 2 * AT_L * PQ, P_ELEMS = AT_L * AT_PP;
     constexpr int R0 = RC_ELEMS > P_ELEMS ? RC_ELEMS : P_ELEMS;
     __shared__ __attribute__((aligned(16))) bf16_t lds[R0 + DH * AT_PP];

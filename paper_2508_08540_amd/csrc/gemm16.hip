@@ -6,9 +6,10 @@
 // gemm16_split_reduce_kernel adds in split order.
 //
 // Workgroup = 128 x 128 tile of C, four waves as 2 x 2, each 64 x 64 = 4 x 4 blocks of v_mfma_f32_16x16x32_bf16.
-// K advances 32 at a time through two LDS buffers [128 rows][32 k] with a row pitch of 80 bytes (the 16-byte operand
-// reads of a quarter wave then fall into distinct banks); the next step's global loads (16 bytes = 8 bf16 per lane)
-// are in flight in registers while the matrix instructions run.  The B tile is passed as the first MFMA operand, so
+// K advances 32 at a time through two LDS buffers [128 rows][32 k] with a row pitch of 96 bytes (measured: the 16-byte
+// operand reads, 16 rows x 4 k groups per instruction, run at the full LDS rate when the pitch is 32 bytes more than a
+// multiple of 64, at half of it with an odd number of 16-byte units such as 80 or 144 bytes); the next two steps'
+// global loads (16 bytes = 8 bf16 per lane) are in flight in registers while the matrix instructions run.  The B tile is passed as the first MFMA operand, so
 // that lane (r, g) holds C[m = r][n = 4g .. 4g+3] of a block: four adjacent outputs, stored with one 16-byte (fp32)
 // or 8-byte (bf16) store.
 #include "act.h"
@@ -16,7 +17,7 @@
 
 #define G16_TILE 128
 #define G16_K 32
-#define G16_PITCH 40   // bf16 elements per LDS row
+#define G16_PITCH 48   // bf16 elements per LDS row (96 bytes)
 
 typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_v __attribute__((ext_vector_type(8)));

@@ -21,7 +21,8 @@ struct WEpi {
 };
 
 // bf16 chunks of 32 channels run on v_mfma_f32_16x16x32_bf16: lane group g supplies channels 8g .. 8g+7 of both
-// operands, the pixel pitch in LDS is 80 bytes so that the 16-byte reads are aligned and spread over all banks, and
+// operands, the pixel pitch in LDS is 96 bytes (16-byte reads of 16 pixels x 4 channel groups run at the full LDS rate
+// when the pitch is 32 bytes more than a multiple of 64; measured at half of it with 80 bytes), and
 // the weights of a lane are two neighbouring quads of the packed copy.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 #define WC_NV 7   // 16-byte vectors of a chunk tile per thread in the prefetching path
@@ -29,7 +30,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 template <typename T, int TAPS, int CK>
 struct WcTraits {
     static constexpr bool K32 = sizeof(T) == 2 && CK == 32;
-    static constexpr int PADE = K32 ? 8 : 4;          // padding elements per pixel
+    static constexpr int PADE = K32 ? 16 : sizeof(T) == 4 ? 8 : 4;   // padding elements per pixel
     static constexpr int CPQ = (CK + PADE) / 4;       // pixel pitch in quads
     static constexpr int S = CK / 16;
     static constexpr int CV = CK / 4 / Tile<T>::VQ;   // 16-byte vectors per pixel and chunk
