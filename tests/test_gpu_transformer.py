@@ -46,6 +46,7 @@ SHAPES = [
     (64, 72, 32, 4, 48, 1, 3),       # rows of 72: the short-row softmax with idle lanes, head width 8
     (120, 72, 128, 2, 64, 1, 3),     # head width 64, 72 tokens: the one-workgroup attention (bf16 factors) with a ragged row block
     (80, 40, 64, 2, 48, 2, 2),       # head width 32, 40 tokens: the same with more than half of the score tile empty
+    (50, 8, 16, 2, 32, 9, 9),        # nine layers, 72 tokens: more column sums per backward pass than one table launch takes
 ]
 
 
@@ -127,9 +128,11 @@ def test_bf16_products_scores_and_gradients(env, vocab, L, D, H, F, layers, batc
     assert_losses_close(sl[0], probe.losses, rtol=2e-4)
     ref = probe.grads()
     for name in [n for n in ref if n.endswith("attn.k.bias")]:
-        # with rounded factors the key-bias gradient is no longer an exact zero, only small against the query bias
+        # with rounded factors the key-bias gradient is no longer an exact zero: what is left on either side is rounding noise
+        # of the softmax gradient (one bf16 step, 2^-8, of terms of the size of the query-bias gradient), so two
+        # implementations agree only to a few 2^-8 of that scale
         scale = np.abs(ref[name.replace(".k.", ".q.")]).max()
-        assert np.abs(mom[name] - ref.pop(name)).max() <= 2e-3 * scale, name
+        assert np.abs(mom[name] - ref.pop(name)).max() <= 1e-2 * scale, name
     exact = oracle.GradientProbe(oracle.TransformerLM(vocab, L, D, H, F, layers), p, {}, x[sel], y[sel]).grads()
     worst = {n: (rel_err(mom[n], ref[n]), rel_err(exact[n], ref[n])) for n in ref}
     assert not {n: e for n, e in worst.items() if e[0] > max(2e-3, 0.5 * e[1])}, worst
