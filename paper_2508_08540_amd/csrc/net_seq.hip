@@ -19,7 +19,18 @@
 
 namespace {
 
-constexpr int SCORE_SEQS = 256;  // sequences scored together: 32768 tokens give every product three workgroups per compute unit (fp32 logits: 4 GiB at a 32000-word vocabulary, element offsets below 2^31)
+// Tokens scored together.  65536 give every product of the bf16 mode at least two rounds of workgroups, so that the first
+// loads and the epilogue of one tile overlap the K loop of another; the fp32 mode stores the logits of a chunk
+// (4 GiB at 32768 tokens and a 32000-word vocabulary) and keeps their element offsets below 2^31.
+constexpr int64_t SCORE_TOKENS_BF16 = 65536, SCORE_TOKENS_F32 = 32768;
+int score_chunk(const bls_model* m, int64_t N) {
+    const bool bf = m->desc.act_dtype == BLS_ACT_BF16;
+    int64_t tokens = bf ? SCORE_TOKENS_BF16 : SCORE_TOKENS_F32;
+    if (!bf && tokens * m->enc_V >= (int64_t(1) << 31)) tokens = ((int64_t(1) << 31) - 1) / m->enc_V;
+    int64_t seqs = tokens / m->enc_L;
+    if (seqs < 1) seqs = 1;
+    return (int)(N < seqs ? N : seqs);
+}
 
 // A tensor as fp32 (f), as bf16 (h), or both; a NULL member does not exist in this mode.
 struct Mat {
@@ -390,7 +401,7 @@ __global__ __launch_bounds__(256) void gather_sequences_kernel(const int32_t* __
 }  // namespace
 
 int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32_t* x, const int32_t* y, int64_t N, float* losses_out) {
-    const int chunk = (int)(N < SCORE_SEQS ? N : SCORE_SEQS);
+    const int chunk = score_chunk(m, N);
     int rc = bls_arena_reserve(ctx, scratch_bytes(m, chunk, false));
     if (rc != BLS_OK) return rc;
     hipStream_t st = ctx->stream;

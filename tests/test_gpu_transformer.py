@@ -93,15 +93,18 @@ def test_steps_follow_the_oracle_and_repeat_bit_for_bit(env):
     assert all(np.array_equal(gp[k], gp2[k]) and np.array_equal(gm[k], gm2[k]) for k in gp) and np.array_equal(gl, gl2)
 
 
-def test_scoring_in_chunks_matches_scoring_alone(env):
-    """More sequences than one scoring chunk, with a ragged last chunk: the loss of a sequence does not depend on its neighbours."""
+@pytest.mark.parametrize("act,chunk_tokens,rtol", [("f32", 32768, 2e-5), ("bf16", 65536, 2e-4)])
+def test_scoring_in_chunks_matches_scoring_alone(env, act, chunk_tokens, rtol):
+    """More sequences than the library scores at once (32768 tokens in fp32, 65536 with bf16 factors), with a ragged last
+    chunk: the loss of a sequence does not depend on its neighbours or on the chunk it falls into."""
     vocab, L, D, H, F, layers = 120, 8, 16, 2, 32, 1
-    h = _harness(env, vocab, L, D, H, F, layers)
+    h = _harness(env, vocab, L, D, H, F, layers, act)
     p = synth.transformer_init(CFG["id"], vocab, L, D, F, layers, perturb=0.1)
-    x, y = synth.token_pool(CFG["id"], 75, L, vocab)
+    n = chunk_tokens // L + 37
+    x, y = synth.token_pool(CFG["id"], n, L, vocab)
     full = h.score(p, {}, x, y)
-    assert_losses_close(full, oracle.score_losses(h.oracle_model, p, {}, x, y), rtol=2e-5)
-    assert np.array_equal(full[70:], h.score(p, {}, x[70:], y[70:]))
+    assert_losses_close(full, oracle.score_losses(h.oracle_model, p, {}, x, y), rtol=rtol)
+    assert np.array_equal(full[n - 50:], h.score(p, {}, x[n - 50:], y[n - 50:]))   # the tail spans the chunk boundary
 
 
 # ---- products with bf16 factors ---------------------------------------------------------------------------------------
