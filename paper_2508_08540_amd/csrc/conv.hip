@@ -229,6 +229,7 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
 template <typename T, int CIN, int MT, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
                                                             T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
+    __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     typedef typename Tile<T>::quad quad;
     extern __shared__ f32x4 lds_raw[];  // vector-typed so that tile reads and writes are single 16- or 8-byte LDS accesses
     quad* lds4 = reinterpret_cast<quad*>(lds_raw);

@@ -19,6 +19,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const T* __restrict__ res, int c_res, int res_stride, int h_out,
                                                        T* __restrict__ out) {
+    __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     constexpr bool WIDE = MAXC > 64;
     __shared__ float s_mean[MAXC], s_invstd[MAXC];
     for (int c0 = 0; c0 < (WIDE ? C : 1); c0 += 256) {
@@ -175,6 +176,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
                                                            const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
                                                            float* __restrict__ dbeta, float inv_count, T* __restrict__ dy,
                                                            T* __restrict__ g_out, const T* __restrict__ add) {
+    __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     constexpr bool WIDE = MAXC > 64;
     __shared__ float s_dg[MAXC], s_db[MAXC];
     auto channel_sums = [&](int c) {
