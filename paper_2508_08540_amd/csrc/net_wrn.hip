@@ -42,6 +42,10 @@ struct WrnScratch {
     act_t *xpad, *y0, *a_final;
     std::vector<act_t*> o1, y1, o2, sc, out;  // per block
     act_t *g1, *g2, *g3, *g4;    // backward temporaries; in inference g1..g4 rotate as activations
+    // gradients that the weight-gradient kernels of the side stream read: they keep a buffer of their own for the whole
+    // backward pass.  dblk[i] = gradient of the input of block i (dblk[blocks] = of the last block's output),
+    // dy1[i] = gradient of the first convolution's output in block i
+    std::vector<act_t*> dblk, dy1;
     fixsum_t *sums, *wacc;
     int64_t n_sums, wacc_count;
     float *grad, *loss, *feat, *dlogits, *dfeat;
@@ -161,6 +165,7 @@ WrnScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     }
     const size_t nb = m->wrn_blocks.size();
     s.o1.assign(nb, nullptr); s.y1.assign(nb, nullptr); s.o2.assign(nb, nullptr); s.sc.assign(nb, nullptr); s.out.assign(nb, nullptr);
+    s.dblk.assign(nb + 1, nullptr); s.dy1.assign(nb, nullptr);
     s.g1 = c.take<act_t>(max_act * esz);
     s.g2 = c.take<act_t>(max_act * esz);
     s.g3 = c.take<act_t>(max_act * esz);
@@ -173,6 +178,9 @@ WrnScratch carve(Carver& c, const bls_model* m, int B, bool train) {
             const size_t out_elems = (size_t)B * b.conv1.h_out * b.conv1.h_out * b.conv1.c_out;
             s.o1[i] = c.take<act_t>(in_elems * esz);
             s.y1[i] = c.take<act_t>(out_elems * esz);
+            s.dblk[i] = c.take<act_t>(in_elems * esz);
+            s.dy1[i] = c.take<act_t>(out_elems * esz);
+            if (i + 1 == nb) s.dblk[nb] = c.take<act_t>(out_elems * esz);
             s.o2[i] = c.take<act_t>(out_elems * esz);
             if (b.proj) s.sc[i] = c.take<act_t>(out_elems * esz);
             s.out[i] = c.take<act_t>(out_elems * esz);
@@ -273,7 +281,7 @@ __global__ __launch_bounds__(256) void gather_taps_kernel(const uint16_t* __rest
 }
 
 void conv_wgrad(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const ConvRef& cr, int B, const act_t* x, const act_t* dy) {
-    ProfScope prof_(ctx, PROF_CONV_WGRAD);
+    ProfScope prof_(ctx, PROF_CONV_WGRAD, st);
     const ConvSlot& c = *cr.slot;
     if (c.taps == 9 && shortcut_wgrad_by_gemm(s.act, c)) {
         const int64_t pixels = (int64_t)B * c.h_out * c.h_out, n16 = pixels * (c.c_in / 8);
@@ -403,11 +411,25 @@ int backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* para
         ci += m->wrn_blocks[i].proj ? 3 : 2;
     }
     const int64_t px_f = (int64_t)B * m->final_hw * m->final_hw;
-    // dcur holds the gradient of the current block output; it trades places with g4 after every block (local rotation only)
-    act_t* dcur = s.g1;
-    act_t* dnext = s.g2;
-    act_t* g3 = s.g3;
-    act_t* g4 = s.g4;
+    // The weight gradients are off the critical path (only the update needs them): each runs on the context's side
+    // stream after an event that marks its dy as written; nothing they read is overwritten before the streams join at
+    // the end of the pass (activations are per block, the gradients they read have buffers of their own).
+    size_t n_forks = 0;
+    auto wgrad_aside = [&](const ConvRef& cr, const act_t* x, const act_t* dy) -> int {
+        if (n_forks == ctx->fork_events.size()) {
+            hipEvent_t e;
+            BLS_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+            ctx->fork_events.push_back(e);
+        }
+        hipEvent_t ev = ctx->fork_events[n_forks++];
+        BLS_HIP(ctx, hipEventRecord(ev, st));
+        BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ev, 0));
+        conv_wgrad(ctx, ctx->aux, s, cr, B, x, dy);
+        return BLS_OK;
+    };
+    act_t* dnext = s.g2;   // main stream only
+    act_t* g3 = s.g3;      // main stream only
+    act_t* dcur = s.dblk[nb];
     bn_backward(ctx, st, s, s.bns[2 * nb], params, px_f, s.dfeat, m->final_hw * m->final_hw, s.a_final, s.out[nb - 1], dcur, nullptr);
     int rc;
     for (size_t ii = nb; ii-- > 0;) {
@@ -416,29 +438,29 @@ int backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* para
         const ConvRef& c1 = s.convs[first[ii]];
         const ConvRef& c2 = s.convs[first[ii] + 1];
         const act_t* block_in = ii == 0 ? s.y0 : s.out[ii - 1];
-        conv_wgrad(ctx, st, s, c2, B, s.o2[ii], dcur);
+        act_t* dy1 = s.dy1[ii];
+        if ((rc = wgrad_aside(c2, s.o2[ii], dcur)) != BLS_OK) return rc;
         rc = conv_dgrad(ctx, st, s, c2, B, dcur, g3, nullptr);                                   // g3 = d o2
         if (rc != BLS_OK) return rc;
-        bn_backward(ctx, st, s, s.bns[2 * ii + 1], params, px_out, g3, 0, s.o2[ii], s.y1[ii], g4, nullptr);  // g4 = d y1
-        conv_wgrad(ctx, st, s, c1, B, s.o1[ii], g4);
+        bn_backward(ctx, st, s, s.bns[2 * ii + 1], params, px_out, g3, 0, s.o2[ii], s.y1[ii], dy1, nullptr);
+        if ((rc = wgrad_aside(c1, s.o1[ii], dy1)) != BLS_OK) return rc;
         const act_t* branch = nullptr;
         if (b.proj) {
             const ConvRef& cs = s.convs[first[ii] + 2];
-            conv_wgrad(ctx, st, s, cs, B, s.o1[ii], dcur);
+            if ((rc = wgrad_aside(cs, s.o1[ii], dcur)) != BLS_OK) return rc;
             rc = conv_dgrad(ctx, st, s, cs, B, dcur, g3, nullptr);                               // g3 = gradient through the projection
             if (rc != BLS_OK) return rc;
             branch = g3;
         }
-        rc = conv_dgrad(ctx, st, s, c1, B, g4, dnext, branch);                                   // dnext = d o1
+        rc = conv_dgrad(ctx, st, s, c1, B, dy1, dnext, branch);                                  // dnext = d o1
         if (rc != BLS_OK) return rc;
-        // d block_in = bn1 backward of d o1, plus the gradient through an identity shortcut; written over g4
-        bn_backward(ctx, st, s, s.bns[2 * ii], params, px_in, dnext, 0, s.o1[ii], block_in, g4, b.proj ? nullptr : dcur);
-        // rotate: g4 holds the new dcur
-        act_t* t = dcur;
-        dcur = g4;
-        g4 = t;
+        // d block_in = bn1 backward of d o1, plus the gradient through an identity shortcut
+        bn_backward(ctx, st, s, s.bns[2 * ii], params, px_in, dnext, 0, s.o1[ii], block_in, s.dblk[ii], b.proj ? nullptr : dcur);
+        dcur = s.dblk[ii];
     }
-    conv_wgrad(ctx, st, s, s.convs[0], B, s.xpad, dcur);
+    if ((rc = wgrad_aside(s.convs[0], s.xpad, dcur)) != BLS_OK) return rc;
+    BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
+    BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
     return BLS_OK;
 }
 

@@ -45,6 +45,7 @@ static size_t wconv_lds_bytes(const ConvGeom& g) {
 template <typename T, int TAPS, int CK, int NPT>
 __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, const void* __restrict__ wpk, T* __restrict__ y, WEpi e,
                                                     ConvGeom g, int c_in, int pipelined) {
+    __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     typedef typename Tile<T>::quad quad;
     typedef typename Tile<T>::vec16 vec16;
     typedef WcTraits<T, TAPS, CK> TR;
