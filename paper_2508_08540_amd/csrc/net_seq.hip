@@ -54,8 +54,11 @@ struct SeqScratch {
     int ce_parts;
     // training only
     Mat dlogits;                    // fp32 mode: the logits buffer itself
-    Mat db, dc, dq, dk, dv, df, ds;
-    float *grad, *da, *part, *cpart;
+    Mat dc, ds;                     // gradient of the attention output, of the scores (unfused attention only)
+    // gradients that weight-gradient products read on the side stream: one buffer per layer, so that nothing they read is
+    // overwritten before the streams join.  db2 / db1 = gradient of the input of the second / first layer norm
+    std::vector<Mat> db2, db1, df, dq, dk, dv;
+    float *grad, *da, *part, *part_main, *cpart;   // part: split-K partial sums of the side stream, part_main: of the main stream
     size_t cpart_floats;
     fixsum_t* acc;
     int64_t acc_count;
@@ -141,11 +144,15 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     else s.dlogits.f = s.logits;
     s.grad = c.take<float>(m->num_params);
     s.da = c.take<float>(T * D);
-    s.db = take(c, bf, BOTH, T * D);
     s.dc = take(c, bf, FACTOR_ONLY, T * D);
-    take3(c, bf, BOTH, T * D, s.dq, s.dk, s.dv);
-    s.df = take(c, bf, BOTH, T * F);
     s.ds = take(c, bf, BOTH, PP);
+    s.db2.resize(layers); s.db1.resize(layers); s.df.resize(layers); s.dq.resize(layers); s.dk.resize(layers); s.dv.resize(layers);
+    for (int l = 0; l < layers; ++l) {
+        s.db2[l] = take(c, bf, BOTH, T * D);
+        s.db1[l] = take(c, bf, BOTH, T * D);
+        s.df[l] = take(c, bf, BOTH, T * F);
+        take3(c, bf, BOTH, T * D, s.dq[l], s.dk[l], s.dv[l]);
+    }
     size_t part = 0;
     auto need = [&](int M, int N) {
         const size_t f = gemm_tiled_partial_floats(M, N, wgrad_splits(M, N, T));
@@ -159,12 +166,14 @@ SeqScratch carve(Carver& c, const bls_model* m, int B, bool train) {
     need(F, D);
     need(D, F);
     need(V, D);
+    s.part = c.take<float>(part ? part : 1);
+    part = 0;
     for (int n_out : {D, F, V})
         for (int n_in : {D, F}) {
             const size_t f = gemm_tiled_partial_floats((int)T, n_in, dgrad_splits(T, n_in, n_out));
             part = f > part ? f : part;
         }
-    s.part = c.take<float>(part ? part : 1);
+    s.part_main = c.take<float>(part ? part : 1);
     // partial column sums of one backward pass: per layer five D-wide and one F-wide bias gradient and two layer norms
     const size_t per_layer = 3 * colsum_partial_floats(T, D) + colsum_partial_floats(T, F) + gelu_bwd_colsum_floats(T, F) + 2 * layernorm_bwd_partial_floats(T, D) + (size_t)12 * B * D;
     const size_t pos = colsum_partial_floats(B, L * D);
@@ -197,7 +206,7 @@ struct Product {
 };
 
 void multiply(bls_ctx* ctx, hipStream_t st, bool bf, const Product& p, int prof_class) {
-    ProfScope prof(ctx, prof_class);
+    ProfScope prof(ctx, prof_class, st);
     if (bf) {
         Gemm16Desc d{};
         d.A = p.A.h; d.B = p.B.h; d.C = p.out.f; d.C16 = p.out.h; d.G16 = p.gelu.h;
@@ -273,7 +282,7 @@ struct Net {
         p.M = (int)T; p.N = n_in; p.K = n_out;
         if (s->bf && !dx.h) {
             p.splits = dgrad_splits(T, n_in, n_out);
-            p.part = s->part;
+            p.part = s->part_main;
         }
         multiply(ctx, st, s->bf, p, PROF_GEMM);
     }
@@ -438,6 +447,8 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
     Carver c(ctx->arena);
     SeqScratch s = carve(c, m, B, true);
     Net net{ctx, st, m, params, &s, B};
+    Net side = net;   // the same products on the side stream
+    side.st = ctx->aux;
 
     FixRangeTable emb_tab{};
     emb_tab.n = 1;
@@ -497,70 +508,93 @@ int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momen
         if (s.bf) PROF(ctx, PROF_HEAD, launch_ce_grad(st, s.logits, s.tgt, s.ce_rows, T, V, gscale, s.dlogits.h));
         else PROF(ctx, PROF_HEAD, launch_token_ce(st, s.logits, s.tgt, T, V, s.tok_loss, gscale, nullptr));
         PROF(ctx, PROF_HEAD, launch_sample_mean(st, s.tok_loss, B, L, step_losses_out ? step_losses_out + j * B : s.loss));
+        // Weight gradients are off the critical path (only the update needs them): each product runs on the side stream
+        // after an event that marks its gradient factor as written.
+        size_t n_forks = 0;
+        auto aside = [&]() -> int {
+            if (n_forks == ctx->fork_events.size()) {
+                hipEvent_t ev;
+                BLS_HIP(ctx, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+                ctx->fork_events.push_back(ev);
+            }
+            hipEvent_t ev = ctx->fork_events[n_forks++];
+            BLS_HIP(ctx, hipEventRecord(ev, st));
+            BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ev, 0));
+            return BLS_OK;
+        };
+        int rc2;
         // head
-        net.linear_wgrad(s.dlogits, hf, T, V, D, m->enc_head);
+        if ((rc2 = aside()) != BLS_OK) return rc2;
+        side.linear_wgrad(s.dlogits, hf, T, V, D, m->enc_head);
         net.linear_dgrad(s.dlogits, T, V, m->enc_head, D, da);
         for (int l = layers - 1; l >= 0; --l) {
             const EncLayer& e = m->enc_layers[l];
             const LayerAct& a = s.act[l];
             const Mat x = s.x[l];
-            // h = LN2(r2): da holds dh, db receives dr2
-            layernorm_bwd(s.da, a.r2, a.st2, e.ln2_g, s.db.f, s.db.h, e.b2);
+            const Mat db2 = s.db2[l], db1 = s.db1[l], df = s.df[l], dq = s.dq[l], dk = s.dk[l], dv = s.dv[l];
+            // h = LN2(r2): da holds dh, db2 receives dr2
+            layernorm_bwd(s.da, a.r2, a.st2, e.ln2_g, db2.f, db2.h, e.b2);
             // r2 = h1 + g W2^T + b2
-            net.linear_wgrad(s.db, a.g, T, D, F, e.w2);
-            net.linear_dgrad(s.db, T, D, e.w2, F, Mat{s.df.f, nullptr});
+            if ((rc2 = aside()) != BLS_OK) return rc2;
+            side.linear_wgrad(db2, a.g, T, D, F, e.w2);
+            net.linear_dgrad(db2, T, D, e.w2, F, Mat{df.f, nullptr});
             {
                 // du = dg * gelu'(u) with the partial sums of the bias gradient
                 float* part = reserve_sums(gelu_bwd_colsum_floats(T, F));
                 int rows = 0;
-                PROF(ctx, PROF_NORM, rows = launch_gelu_bwd_colsum(st, s.df.f, a.u, s.df.h, T, F, part));
+                PROF(ctx, PROF_NORM, rows = launch_gelu_bwd_colsum(st, df.f, a.u, df.h, T, F, part));
                 if (rows > 0) {
                     push_sums(part - s.cpart, rows, F, F, e.b1);
                 } else {
-                    PROF(ctx, PROF_NORM, launch_gelu_bwd(st, s.df.f, a.u, s.df.h, T * F));
-                    bias_grad(s.df.f, F, e.b1);
+                    PROF(ctx, PROF_NORM, launch_gelu_bwd(st, df.f, a.u, df.h, T * F));
+                    bias_grad(df.f, F, e.b1);
                 }
             }
             // u = h1 W1^T + b1
-            net.linear_wgrad(s.df, a.h1, T, F, D, e.w1);
-            net.linear_dgrad(s.df, T, F, e.w1, D, da, s.db.f);   // da = dh1 (both uses of h1)
-            // h1 = LN1(r1): db receives dr1
-            layernorm_bwd(s.da, a.r1, a.st1, e.ln1_g, s.db.f, s.db.h, e.bo);
+            if ((rc2 = aside()) != BLS_OK) return rc2;
+            side.linear_wgrad(df, a.h1, T, F, D, e.w1);
+            net.linear_dgrad(df, T, F, e.w1, D, da, db2.f);   // da = dh1 (both uses of h1)
+            // h1 = LN1(r1): db1 receives dr1
+            layernorm_bwd(s.da, a.r1, a.st1, e.ln1_g, db1.f, db1.h, e.bo);
             // r1 = x + ctx Wo^T + bo
-            net.linear_wgrad(s.db, a.ctx, T, D, D, e.wo);
-            net.linear_dgrad(s.db, T, D, e.wo, D, s.dc);          // dc = dctx
+            if ((rc2 = aside()) != BLS_OK) return rc2;
+            side.linear_wgrad(db1, a.ctx, T, D, D, e.wo);
+            net.linear_dgrad(db1, T, D, e.wo, D, s.dc);          // dc = dctx
             // ctx = P v;  P = softmax(att * q k^T)
             bool fused = false;
             if (s.bf) {
                 float* part = reserve_sums((size_t)3 * 4 * B * D);
                 ProfScope prof_(ctx, PROF_GEMM);
-                fused = launch_attention16_bwd(st, a.q.h, a.k.h, a.v.h, s.dc.h, a.p.f, D, B, H, L, dh, att, s.dq.f, s.dk.f, s.dv.f, s.dq.h, s.dk.h, s.dv.h, part);
+                fused = launch_attention16_bwd(st, a.q.h, a.k.h, a.v.h, s.dc.h, a.p.f, D, B, H, L, dh, att, dq.f, dk.f, dv.f, dq.h, dk.h, dv.h, part);
                 const int64_t offs[3] = {e.bq, e.bk, e.bv};
                 for (int i = 0; fused && i < 3; ++i) push_sums(part - s.cpart + (size_t)i * 4 * B * D, 4 * B, D, D, offs[i]);
             }
             if (!fused) {
-                net.attention(a.p, true, true, s.dc, false, true, s.dv, false, dh, L, 1.f);                      // dv = P^T dctx
-                net.attention(s.dc, false, false, a.v, false, false, Mat{s.ds.f, nullptr}, true, L, dh, 1.f);    // dP = dctx v^T
+                net.attention(a.p, true, true, s.dc, false, true, dv, false, dh, L, 1.f);                      // dv = P^T dctx
+                net.attention(s.dc, false, false, a.v, false, false, Mat{s.ds.f, nullptr}, true, L, dh, 1.f);  // dP = dctx v^T
                 PROF(ctx, PROF_NORM, launch_softmax_bwd_rows(st, s.ds.f, a.p.f, s.ds.h, (int64_t)B * H * L, L, att));
-                net.attention(s.ds, true, false, a.k, false, true, s.dq, false, dh, L, 1.f);                     // dq = dS k
-                net.attention(s.ds, true, true, a.q, false, true, s.dk, false, dh, L, 1.f);                      // dk = dS^T q
+                net.attention(s.ds, true, false, a.k, false, true, dq, false, dh, L, 1.f);                     // dq = dS k
+                net.attention(s.ds, true, true, a.q, false, true, dk, false, dh, L, 1.f);                      // dk = dS^T q
             }
             // q, k, v projections of x
-            net.qkv_wgrad(s.dq, s.dk, s.dv, x, T, e);
+            if ((rc2 = aside()) != BLS_OK) return rc2;
+            side.qkv_wgrad(dq, dk, dv, x, T, e);
             if (!fused) {
-                bias_grad(s.dq.f, D, e.bq);
-                bias_grad(s.dk.f, D, e.bk);
-                bias_grad(s.dv.f, D, e.bv);
+                bias_grad(dq.f, D, e.bq);
+                bias_grad(dk.f, D, e.bk);
+                bias_grad(dv.f, D, e.bv);
             }
-            net.linear_dgrad(s.dq, T, D, e.wq, D, da, s.db.f);    // da = dx, starting from the residual path
-            net.linear_dgrad(s.dk, T, D, e.wk, D, da, s.da);
-            net.linear_dgrad(s.dv, T, D, e.wv, D, da, s.da);
+            net.linear_dgrad(dq, T, D, e.wq, D, da, db1.f);    // da = dx, starting from the residual path
+            net.linear_dgrad(dk, T, D, e.wk, D, da, s.da);
+            net.linear_dgrad(dv, T, D, e.wv, D, da, s.da);
         }
         // embeddings: position gradient = sum over samples, token gradient = scatter by id
         flush_sums();
         PROF(ctx, PROF_NORM, launch_colsum_tokens(st, s.da, B, L * D, s.cpart, s.grad + m->enc_pos));
         PROF(ctx, PROF_NORM, launch_embed_grad(st, s.tok, T, D, s.da, s.acc));
         PROF(ctx, PROF_UPDATE, launch_fix_finalize(st, emb_tab, s.acc, s.grad));
+        BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));   // every weight gradient is in
+        BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
         PROF(ctx, PROF_UPDATE, launch_sgd(st, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay));
     }
     BLS_HIP(ctx, hipGetLastError());
