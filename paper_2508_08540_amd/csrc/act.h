@@ -41,9 +41,12 @@ struct Act<bf16_t> {
                      __uint_as_float(r.y & 0xffff0000u)};
     }
     static __device__ __forceinline__ f32x4 load4(const bf16_t* p) { return widen(load_raw(p)); }
+    // round to nearest even by the hardware's packed conversion (the same values as f32_to_bf16)
     static __device__ __forceinline__ raw4 narrow(f32x4 v) {
-        return make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
-                          (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16));
+        typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+        typedef float f32x2_hw __attribute__((ext_vector_type(2)));
+        return make_uint2(__builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_hw){v[0], v[1]}, bf16x2_hw)),
+                          __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_hw){v[2], v[3]}, bf16x2_hw)));
     }
     static __device__ __forceinline__ void store4(bf16_t* p, f32x4 v) { *reinterpret_cast<uint2*>(p) = narrow(v); }
     static __device__ __forceinline__ f32x4 rounded(f32x4 v) { return widen(narrow(v)); }

@@ -14,11 +14,20 @@
 // running statistics are used.
 // MAXC: 64 (narrow layers: thread c handles channel c, the form the compiler schedules best: a loop there, even
 // with one trip, costs microseconds per launch) or BN_MAX_C (the per-channel prologue loops over 256-channel passes).
+// log2 of the number of channel quads when that is a power of two, else -1
+static int quads_log2(int C) {
+    const int cq = C >> 2;
+    if (cq <= 0 || (cq & (cq - 1)) != 0) return -1;
+    int l = 0;
+    while ((1 << l) < cq) ++l;
+    return l;
+}
+
 template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, int64_t pixels, int C, BnStats st,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const T* __restrict__ res, int c_res, int res_stride, int h_out,
-                                                       T* __restrict__ out) {
+                                                       T* __restrict__ out, int cq_log2) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     constexpr bool WIDE = MAXC > 64;
     __shared__ float s_mean[MAXC], s_invstd[MAXC];
@@ -51,7 +60,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int lo = (C - c_res) >> 1;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        int64_t p = i / cq;
+        const int64_t p = cq_log2 >= 0 ? i >> cq_log2 : i / cq;   // (a 64-bit division costs as much as the rest of the body)
         int c = (int)(i - p * cq) << 2;
         f32x4 v = Act<T>::load4(y + p * C + c);
         f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
@@ -84,13 +93,14 @@ void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int 
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
+    const int cq_log2 = quads_log2(C);
     ACT_DISPATCH(act, {
         if (C > 64)
             hipLaunchKernelGGL((bn_apply_kernel<T, BN_MAX_C>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
-                               (const T*)res, c_res, res_stride, h_out, (T*)out);
+                               (const T*)res, c_res, res_stride, h_out, (T*)out, cq_log2);
         else
             hipLaunchKernelGGL((bn_apply_kernel<T, 64>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
-                               (const T*)res, c_res, res_stride, h_out, (T*)out);
+                               (const T*)res, c_res, res_stride, h_out, (T*)out, cq_log2);
     });
 }
 
@@ -175,7 +185,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
                                                            const float* __restrict__ invstd, const float* __restrict__ gamma,
                                                            const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
                                                            float* __restrict__ dbeta, float inv_count, T* __restrict__ dy,
-                                                           T* __restrict__ g_out, const T* __restrict__ add) {
+                                                           T* __restrict__ g_out, const T* __restrict__ add, int cq_log2) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     constexpr bool WIDE = MAXC > 64;
     __shared__ float s_dg[MAXC], s_db[MAXC];
@@ -197,7 +207,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
     int64_t total = pixels * cq;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        int64_t p = i / cq;
+        const int64_t p = cq_log2 >= 0 ? i >> cq_log2 : i / cq;
         int c = (int)(i - p * cq) << 2;
         f32x4 d = load_dout<T>(dout, shared, p, C, c);
         f32x4 o = Act<T>::load4(out + p * C + c);
@@ -228,7 +238,8 @@ void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_posi
 #define BN_BWD_APPLY(MAXC, HAS_ADD)                                                                                                   \
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MAXC, HAS_ADD>), dim3((unsigned)blocks), dim3(256), 0, s, dout, dout_positions_shared,   \
                        (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums, dgamma, dbeta, 1.f / (float)pixels, (T*)dy,  \
-                       (T*)g_out, (const T*)add)
+                       (T*)g_out, (const T*)add, cq_log2)
+    const int cq_log2 = quads_log2(C);
     ACT_DISPATCH(act, {
         if (C > 64 || add) {
             if (add) BN_BWD_APPLY(BN_MAX_C, true);
