@@ -1,5 +1,5 @@
 // Classifier head: (average pooling) + linear layer + per-sample softmax cross-entropy, one
-// wavefront per sample with shuffle reductions; and the head's weight gradient.
+// workgroup of four wavefronts per sample with shuffle reductions; and the head's weight gradient.
 #include "act.h"
 
 #define HEAD_MAX_C 128   // two classes per lane
@@ -10,102 +10,13 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Lane l owns the channel quads l, l + 64, ... (channels 4q .. 4q+3): PQ = ceil(F / 256) of them, a template parameter
-// so that the pooled features stay in registers.  Pooling reads 8 or 16 bytes per lane and position; F % 4 == 0.
+// Average pool, linear layer, softmax cross-entropy and their gradients for one sample per workgroup.  Lane l owns the
+// channel quads l, l + 64, ... (channels 4q .. 4q+3): PQ = ceil(F / 256) of them, a template parameter so that the pooled
+// features stay in registers; F % 4 == 0.  Four waves per sample (a single one leaves the compute unit nearly empty and
+// spends its time waiting for one load after another): wave w pools positions w, w + 4, ..., takes classes w, w + 4, ...
+// and, for the feature gradient, sums over those classes; the partial results meet in LDS and are added in wave order.
 template <int PQ, typename T>
-__global__ __launch_bounds__(64) void head_forward_kernel(const T* __restrict__ act, int positions, int F,
-                                                          const float* __restrict__ W, const float* __restrict__ bias,
-                                                          int C, const int32_t* __restrict__ y, float* __restrict__ loss,
-                                                          float* __restrict__ feat, float* __restrict__ dlogits,
-                                                          float* __restrict__ dfeat, float grad_scale, int relu_mask) {
-    const int b = blockIdx.x, lane = threadIdx.x;
-    f32x4 f[PQ];
-    const float inv_pos = 1.f / (float)positions;
-    const T* a = act + (int64_t)b * positions * F;
-#pragma unroll
-    for (int i = 0; i < PQ; ++i) {
-        const int c = 4 * (lane + 64 * i);
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (c < F) {
-            // four independent partial sums keep several loads in flight; they are combined in a fixed order
-            f32x4 s0 = acc, s1 = acc, s2 = acc, s3 = acc;
-            int p = 0;
-            for (; p + 3 < positions; p += 4) {
-                s0 += Act<T>::load4(a + (int64_t)p * F + c);
-                s1 += Act<T>::load4(a + (int64_t)(p + 1) * F + c);
-                s2 += Act<T>::load4(a + (int64_t)(p + 2) * F + c);
-                s3 += Act<T>::load4(a + (int64_t)(p + 3) * F + c);
-            }
-            for (; p < positions; ++p) s0 += Act<T>::load4(a + (int64_t)p * F + c);
-            acc = (s0 + s1) + (s2 + s3);
-        }
-        f[i] = acc * inv_pos;
-        if (feat && c < F) *reinterpret_cast<f32x4*>(feat + (int64_t)b * F + c) = f[i];
-    }
-    // logits: lane l keeps those of classes l and l + 64
-    float z_mine[2] = {-INFINITY, -INFINITY};
-    for (int c = 0; c < C; ++c) {
-        float part = 0.f;
-#pragma unroll
-        for (int i = 0; i < PQ; ++i) {
-            const int k = 4 * (lane + 64 * i);
-            if (k < F) {
-                const f32x4 w = *reinterpret_cast<const f32x4*>(W + (int64_t)c * F + k);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) part = __fmaf_rn(f[i][j], w[j], part);
-            }
-        }
-        float z = wave_sum(part) + bias[c];
-        if (lane == (c & 63)) z_mine[c >> 6] = z;
-    }
-    float m = fmaxf(z_mine[0], z_mine[1]);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    float ex[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) ex[h] = lane + 64 * h < C ? expf(z_mine[h] - m) : 0.f;
-    float sum = wave_sum(ex[0]) + wave_sum(ex[1]);
-    const int label = y[b];
-    float z_label = __shfl(label < 64 ? z_mine[0] : z_mine[1], label & 63, 64);
-    if (lane == 0) loss[b] = (m + logf(sum)) - z_label;
-    if (!dlogits) return;
-    float dz[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int c = lane + 64 * h;
-        dz[h] = c < C ? (ex[h] / sum - (c == label ? 1.f : 0.f)) * grad_scale : 0.f;
-        if (c < C) dlogits[(int64_t)b * C + c] = dz[h];
-    }
-    if (!dfeat) return;
-#pragma unroll
-    for (int i = 0; i < PQ; ++i) {
-        const int k = 4 * (lane + 64 * i);
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < C; ++c) {
-            const float d = __shfl(c < 64 ? dz[0] : dz[1], c & 63, 64);
-            if (k < F) {
-                const f32x4 w = *reinterpret_cast<const f32x4*>(W + (int64_t)c * F + k);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[j] = __fmaf_rn(d, w[j], acc[j]);
-            }
-        }
-        if (k < F) {
-            acc *= inv_pos;
-            if (relu_mask)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (!(f[i][j] > 0.f)) acc[j] = 0.f;
-            *reinterpret_cast<f32x4*>(dfeat + (int64_t)b * F + k) = acc;
-        }
-    }
-}
-
-// The same for wide feature vectors (F > 256), four waves per sample: a single wave per sample leaves the compute unit
-// nearly empty and spends its time waiting for one load after another.  Wave w pools positions w, w + 4, ..., takes
-// classes w, w + 4, ... and, for the feature gradient, sums over those classes; the partial results meet in LDS and are
-// added in wave order.
-template <int PQ, typename T>
-__global__ __launch_bounds__(256) void head_forward_wide_kernel(const T* __restrict__ act, int positions, int F,
+__global__ __launch_bounds__(256) void head_forward_kernel(const T* __restrict__ act, int positions, int F,
                                                                const float* __restrict__ W, const float* __restrict__ bias,
                                                                int C, const int32_t* __restrict__ y, float* __restrict__ loss,
                                                                float* __restrict__ feat, float* __restrict__ dlogits,
@@ -213,17 +124,13 @@ __global__ __launch_bounds__(256) void head_forward_wide_kernel(const T* __restr
 void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
                          float grad_scale, bool relu_mask) {
-#define HEAD_LAUNCH(PQ)                                                                                                          \
-    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PQ, T>), dim3(B), dim3(64), 0, s, (const T*)act, positions, F, W, \
-                                              bias, C, y, loss, feat, dlogits, dfeat, grad_scale, relu_mask ? 1 : 0))
-#define HEAD_LAUNCH_WIDE(PQ)                                                                                                     \
-    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_wide_kernel<PQ, T>), dim3(B), dim3(256), 0, s, (const T*)act, positions, F, W, \
+#define HEAD_LAUNCH(PQ)                                                                                                     \
+    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PQ, T>), dim3(B), dim3(256), 0, s, (const T*)act, positions, F, W, \
                                               bias, C, y, loss, feat, dlogits, dfeat, grad_scale, relu_mask ? 1 : 0))
     const int quads = (F / 4 + 63) / 64;   // F is a multiple of 16, at most 1024
     if (quads <= 1) HEAD_LAUNCH(1);
-    else if (quads <= 2) HEAD_LAUNCH_WIDE(2);
-    else HEAD_LAUNCH_WIDE(4);
-#undef HEAD_LAUNCH_WIDE
+    else if (quads <= 2) HEAD_LAUNCH(2);
+    else HEAD_LAUNCH(4);
 #undef HEAD_LAUNCH
 }
 
