@@ -64,7 +64,8 @@ int bls_ctx_create(bls_ctx** out, int device, void* hip_stream) {
         ctx->max_lds = (size_t)optin;
     (void)hipGetLastError();
     if (hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&ctx->join_event, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&ctx->join_event, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->head_event, hipEventDisableTiming) != hipSuccess) {
         delete ctx;
         return BLS_EHIP;
     }
@@ -87,6 +88,7 @@ void bls_ctx_destroy(bls_ctx* ctx) {
     }
     for (hipEvent_t e : ctx->fork_events) (void)hipEventDestroy(e);
     if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
+    if (ctx->head_event) (void)hipEventDestroy(ctx->head_event);
     if (ctx->arena) (void)hipFree(ctx->arena);
     if (ctx->round_losses) (void)hipFree(ctx->round_losses);
     if (ctx->owns_stream) (void)hipStreamDestroy(ctx->stream);

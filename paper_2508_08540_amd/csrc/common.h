@@ -25,6 +25,7 @@ struct bls_ctx {
     hipStream_t aux = nullptr;             // library-owned side stream for work off the critical path
     std::vector<hipEvent_t> fork_events;   // main -> aux dependencies, one per use inside a call
     hipEvent_t join_event = nullptr;       // aux -> main
+    hipEvent_t head_event = nullptr;       // main -> aux: the classifier head's gradients are written
     float* round_losses = nullptr;   // per-sample losses of the workers' local steps (communication_round), grown on demand
     size_t round_losses_count = 0;
     std::vector<bls_ctx*> lanes;     // library-owned contexts (own stream, side stream and scratch) for concurrent workers

@@ -509,7 +509,13 @@ int wrn_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         if (rc != BLS_OK) return rc;
         PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C,
                                                  s.yb, loss, s.feat, s.dlogits, s.dfeat, inv_b, false));
-        PROF(ctx, PROF_HEAD, launch_head_wgrad(st, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b));
+        // the head's weight gradient is only needed by the update: side stream, joined at the end of the backward pass
+        BLS_HIP(ctx, hipEventRecord(ctx->head_event, st));
+        BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->head_event, 0));
+        {
+            ProfScope prof_(ctx, PROF_HEAD, ctx->aux);
+            launch_head_wgrad(ctx->aux, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b);
+        }
         rc = backward(ctx, st, m, params, B, s);
         if (rc != BLS_OK) return rc;
         PROF(ctx, PROF_UPDATE, launch_update(st, s.act, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay, s.wacc,
