@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_bf16", "wrn16_8_bf16", "transformer", "transformer_fp32"])
+    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_b32", "resnet20_bf16", "wrn16_8_bf16", "transformer", "transformer_fp32"])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -176,7 +176,7 @@ def main():
     # gradient always multiplies in fp32
     peak = BF16_MFMA_PEAK_TFLOPS if (act_dtype == "bf16" and dom != "conv_wgrad") else FP32_MFMA_PEAK_TFLOPS
     traffic = None
-    rec = MEASURED_TRAFFIC.get(symbol) if act_dtype == "f32" else None
+    rec = MEASURED_TRAFFIC.get(symbol) if args.workload == "resnet20_fp32" else None   # the counters were taken on that workload
     if rec:
         import hashlib
         with open(os.path.join(ROOT, rec["source"]), "rb") as fh:

@@ -20,6 +20,10 @@ WORKLOADS = {
                 weight_decay=0.0, P=4, weights=(0.35, 0.35, 0.15, 0.15)),
     "resnet20_fp32": dict(id=1, model="resnet20", pool=512, classes=10, k=128, batch=128, tau=20, lr=0.1,
                           momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
+    # the same pool and selection with the batch size and local step count of the paper's own ResNet20 runs (batch 32,
+    # tau_F = 32; hyper-parameter table of the appendix, Section 5.1): 1024 samples per pass, the selection walked cyclically
+    "resnet20_b32": dict(id=1, model="resnet20", pool=512, classes=10, k=128, batch=32, tau=32, lr=0.1,
+                         momentum=0.9, weight_decay=1e-4, P=10, tau_workers=(32,) * 8 + (16,) * 2),
     # the same network with bf16 activations and fp32 master weights, larger pool and selection
     "resnet20_bf16": dict(id=2, model="resnet20", act_dtype="bf16", pool=4096, classes=10, k=1024, batch=128, tau=50,
                           lr=0.1, momentum=0.9, weight_decay=0.0, P=10, tau_workers=(32,) * 8 + (16,) * 2),
