@@ -22,7 +22,7 @@
 namespace {
 
 constexpr int PAD_C = 16;       // the stem's input is zero-padded to 16 channels so it runs on the same kernels
-constexpr int SCORE_CHUNK = 512;
+constexpr int SCORE_CHUNK = 2048;
 constexpr int MLP_SPLITS = 8;
 
 int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }

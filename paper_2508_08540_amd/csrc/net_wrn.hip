@@ -14,7 +14,7 @@
 namespace {
 
 constexpr int PAD_C = 16;        // the stem's input is zero-padded to 16 channels
-constexpr int SCORE_CHUNK = 256;
+constexpr int SCORE_CHUNK = 1024;   // images scored together
 typedef uint8_t act_t;
 
 int padded(int c) { return c < PAD_C ? PAD_C : c; }

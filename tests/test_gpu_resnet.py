@@ -153,10 +153,12 @@ def test_full_workload_configuration(env):
 
 
 def test_scoring_in_several_chunks_and_wide_images(env):
-    # pools larger than the library's scoring chunk (512) are processed in pieces; 64x64 images take the
-    # non-prefetching staging path of the convolution kernel
+    # pools larger than the library's scoring chunk (2048) are processed in pieces, the last one ragged; 64x64 images take
+    # the non-prefetching staging path of the convolution kernel
     h = _harness(env, (16, 32, 64), 1, 8)
     p, b = synth.resnet_init(CFG["id"], (16, 32, 64), 1, 10, perturb_bn=0.2)
-    x, y = synth.image_pool(CFG["id"], 1100, 10, hw=8)
-    assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y))
+    x, y = synth.image_pool(CFG["id"], 2100, 10, hw=8)
+    full = h.score(p, b, x, y)
+    assert_losses_close(full[1990:], oracle.score_losses(h.oracle_model, p, b, x[1990:], y[1990:]))   # across the chunk boundary
+    assert np.array_equal(full[1990:], h.score(p, b, x[1990:], y[1990:]))    # a loss does not depend on the chunk it falls into
     _grad_case(env, (16, 16, 32), 1, 64, 2)

@@ -64,6 +64,18 @@ def test_fp32_gradients_and_scores(env, widths, blocks, hw, batch, classes, stem
     assert_tensors_close(gb, probe.new_buffers, 1e-5, "running statistics")
 
 
+def test_scoring_in_several_chunks(env):
+    """More images than the library scores at once (1024), the last chunk ragged: losses match the oracle across the chunk
+    boundary and do not depend on the chunk an image falls into."""
+    widths, blocks, hw, classes, stem = (32, 32, 64), 1, 8, 10, 16
+    h = _harness(env, widths, blocks, hw, classes, stem)
+    p, b = synth.wrn_init(CFG["id"], widths, blocks, classes, stem, perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], 1060, classes, hw=hw)
+    full = h.score(p, b, x, y)
+    assert_losses_close(full[990:], oracle.score_losses(h.oracle_model, p, b, x[990:], y[990:]))
+    assert np.array_equal(full[990:], h.score(p, b, x[990:], y[990:]))
+
+
 def test_fp32_steps_follow_the_oracle(env):
     widths, blocks, hw, classes, stem = (32, 64, 64), 1, 8, 10, 16
     h = _harness(env, widths, blocks, hw, classes, stem)
