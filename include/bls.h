@@ -151,6 +151,12 @@ void bls_model_destroy(bls_model* model);
 /* d: number of trainable floats.  Buffers: batch-norm running statistics (0 for the MLP). */
 int64_t bls_model_num_params(const bls_model* model);
 int64_t bls_model_num_buffers(const bls_model* model);
+/* Device scratch memory the context grows to (once; it is kept until the context is destroyed): with training != 0 for
+ * local_step at batch size n, otherwise for score_losses over a pool of n samples (large pools are scored in chunks, so
+ * the figure stops growing).  Activations kept for the backward pass, gradients, partial sums and the kernels' weight
+ * copies live there (Algorithm 1's worker holds its model, momentum and data; everything else is this scratch).
+ * Host only.  BLS_EINVAL for a NULL model or n outside [1, 2^24]. */
+int64_t bls_model_workspace_bytes(const bls_model* model, int64_t n, int training);
 /* Number of tensors (parameters and buffers together). */
 int32_t bls_model_num_tensors(const bls_model* model);
 /* Fills out[0 .. capacity-1]; returns the number of tensors written or BLS_EINVAL. */

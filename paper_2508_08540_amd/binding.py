@@ -12,7 +12,7 @@ AGG_NORMALISE, AGG_BROADCAST = 1, 2
 
 DECLARED_SYMBOLS = (
     "bls_ctx_create", "bls_ctx_destroy", "bls_last_error", "bls_ctx_synchronize", "bls_model_create",
-    "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_num_tensors",
+    "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_workspace_bytes", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
     "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes",
@@ -65,6 +65,8 @@ def _load():
     for f in (L.bls_model_num_params, L.bls_model_num_buffers):
         f.argtypes = [vp]
         f.restype = i64
+    L.bls_model_workspace_bytes.argtypes = [vp, i64, C.c_int]
+    L.bls_model_workspace_bytes.restype = i64
     L.bls_model_num_tensors.argtypes = [vp]
     L.bls_model_num_tensors.restype = i32
     L.bls_model_tensor_layout.argtypes = [vp, C.POINTER(_TensorInfo), i32]
@@ -166,6 +168,13 @@ class Model:
         assert got == n
         self.tensors = [dict(name=t.name.decode(), offset=t.offset, shape=tuple(t.shape[:t.ndim]),
                              is_buffer=bool(t.is_buffer)) for t in arr]
+
+    def workspace_bytes(self, n, training):
+        """Device scratch the context grows to for local_step at batch size n (training) or score_losses over n samples."""
+        got = lib.bls_model_workspace_bytes(self.handle, int(n), 1 if training else 0)
+        if got < 0:
+            raise BlsError(int(got), "bls_model_workspace_bytes rejected the arguments")
+        return int(got)
 
     @classmethod
     def mlp(cls, d_hw=32, in_channels=3, hidden=128, classes=10):

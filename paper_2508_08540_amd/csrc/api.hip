@@ -341,6 +341,17 @@ int64_t bls_model_num_params(const bls_model* model) { return model ? model->num
 int64_t bls_model_num_buffers(const bls_model* model) { return model ? model->num_buffers : BLS_EINVAL; }
 int32_t bls_model_num_tensors(const bls_model* model) { return model ? (int32_t)model->tensors.size() : BLS_EINVAL; }
 
+int64_t bls_model_workspace_bytes(const bls_model* model, int64_t n, int training) {
+    if (!model || n < 1 || n > (int64_t(1) << 24)) return BLS_EINVAL;
+    const bool train = training != 0;
+    if (model->desc.kind == BLS_MODEL_ENCODER) {
+        if (train && n * model->enc_L >= (int64_t(1) << 31) / 8) return BLS_EINVAL;
+        return (int64_t)seq_workspace_bytes(model, n, train);
+    }
+    if (model->desc.kind == BLS_MODEL_WRN) return (int64_t)wrn_workspace_bytes(model, n, train);
+    return (int64_t)net_workspace_bytes(model, n, train);
+}
+
 int bls_model_tensor_layout(const bls_model* model, bls_tensor_info* out, int32_t capacity) {
     if (!model || !out || capacity < 0) return BLS_EINVAL;
     int n = (int)model->tensors.size() < capacity ? (int)model->tensors.size() : capacity;

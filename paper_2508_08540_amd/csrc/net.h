@@ -19,3 +19,7 @@ int wrn_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
 int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32_t* x, const int32_t* y, int64_t N, float* losses_out);
 int seq_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* momentum, const int32_t* x_pool, const int32_t* y_pool, int64_t N,
                    const int32_t* sel, int64_t k, int64_t batch, int64_t tau, const bls_sgd& opt, float* step_losses_out);
+// Scratch the context grows to for local_step at batch size n (train) or for score_losses over a pool of n samples
+size_t net_workspace_bytes(const bls_model* m, int64_t n, bool train);
+size_t wrn_workspace_bytes(const bls_model* m, int64_t n, bool train);
+size_t seq_workspace_bytes(const bls_model* m, int64_t n, bool train);

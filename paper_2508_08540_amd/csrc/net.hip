@@ -298,6 +298,10 @@ size_t scratch_bytes(const bls_model* m, int B, bool train) {
 
 }  // namespace
 
+size_t net_workspace_bytes(const bls_model* m, int64_t n, bool train) {
+    return scratch_bytes(m, (int)(train || n < SCORE_CHUNK ? n : SCORE_CHUNK), train);
+}
+
 int net_score(bls_ctx* ctx, const bls_model* m, const float* params, const float* buffers, const float* x,
               const int32_t* y, int64_t N, float* losses_out) {
     const int chunk = (int)(N < SCORE_CHUNK ? N : SCORE_CHUNK);

@@ -409,6 +409,8 @@ __global__ __launch_bounds__(256) void gather_sequences_kernel(const int32_t* __
 
 }  // namespace
 
+size_t seq_workspace_bytes(const bls_model* m, int64_t n, bool train) { return scratch_bytes(m, train ? (int)n : score_chunk(m, n), train); }
+
 int seq_score(bls_ctx* ctx, const bls_model* m, const float* params, const int32_t* x, const int32_t* y, int64_t N, float* losses_out) {
     const int chunk = score_chunk(m, N);
     int rc = bls_arena_reserve(ctx, scratch_bytes(m, chunk, false));

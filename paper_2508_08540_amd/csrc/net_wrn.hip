@@ -466,6 +466,10 @@ int backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* para
 
 }  // namespace
 
+size_t wrn_workspace_bytes(const bls_model* m, int64_t n, bool train) {
+    return scratch_bytes(m, (int)(train || n < SCORE_CHUNK ? n : SCORE_CHUNK), train);
+}
+
 int wrn_score(bls_ctx* ctx, const bls_model* m, const float* params, const float* buffers, const float* x, const int32_t* y, int64_t N,
               float* losses_out) {
     const int chunk = (int)(N < SCORE_CHUNK ? N : SCORE_CHUNK);

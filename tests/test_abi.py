@@ -58,6 +58,20 @@ def test_sequence_model_layout_and_rejected_descriptions():
             bls.Model.transformer(**bad)
 
 
+def test_workspace_query():
+    """Scratch sizes are a host-side function of the model and the batch: they grow with the training batch, stop growing
+    once a pool is scored in chunks, and bad arguments are refused."""
+    import paper_2508_08540_amd as bls
+    for m, chunk in ((bls.Model.mlp(), 2048), (bls.Model.resnet_cifar(), 2048), (bls.Model.wide_resnet(act_dtype="bf16"), 1024),
+                     (bls.Model.transformer(act_dtype="bf16"), 512), (bls.Model.transformer(), 256)):
+        train = [m.workspace_bytes(n, True) for n in (16, 32, 64)]
+        assert 0 < train[0] < train[1] < train[2]
+        assert m.workspace_bytes(chunk // 2, False) < m.workspace_bytes(chunk, False) == m.workspace_bytes(4 * chunk, False)
+        for bad in (0, -3, 1 << 25):
+            with pytest.raises(bls.BlsError):
+                m.workspace_bytes(bad, True)
+
+
 def test_weights_from_tau_host_helper():
     import paper_2508_08540_amd as bls
     w = bls.weights_from_tau([32] * 8 + [16] * 2)
