@@ -21,8 +21,8 @@ sys.path.insert(0, ROOT)
 # dispatch averaged over all launches of a bench run), each scaled by what the same counter reads for a plain
 # 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
 MEASURED_TRAFFIC = {
-    "wgrad_kernel": {"fetch_kib": 5460.7, "fetch_scale": 2.0, "write_kib": 9216.0, "write_scale": 1.0,
-                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "44ef3a0d3093f305"},
+    "wgrad_kernel": {"fetch_kib": 5461.7, "fetch_scale": 2.0, "write_kib": 9216.0, "write_scale": 1.0,
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "cc526ea2bf776c72"},
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3

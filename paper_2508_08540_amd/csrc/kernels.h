@@ -75,6 +75,8 @@ void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, i
 // (sum, sum of squares) of y over `count` values; every workgroup derives mean and invstd from them, and
 // workgroup 0 also stores them into mean/invstd and moves the running statistics.  Inference: sums == nullptr
 // and the running statistics are used.  At most 512 channels.
+#define BN_EPS 1e-5        // variance offset of the batch norm (Section 5.1: PyTorch defaults)
+#define BN_MOMENTUM 0.1    // weight of the batch statistics in the running ones
 struct BnStats {
     const fixsum_t* sums;
     double count;
@@ -126,6 +128,15 @@ struct ConvEpi {
     // inference forward (gamma != nullptr): out = relu(bn(y) + shortcut) with mean_prev = running mean, invstd_prev =
     // running variance, sc_g = shortcut source (c channels sc_c, first output channel sc_lo, spatial stride sc_stride)
     const float *gamma, *beta;
+    // training forward with in_sums != nullptr: the input x is the raw convolution output of the layer below.  The kernel
+    // turns that layer's sums into statistics (workgroup 0 stores them and updates the running statistics, as bn_apply
+    // does), applies its batch norm and ReLU while staging, and writes the activation to a_out for the backward pass.
+    // Stride-1 3x3 layers only; the values are those bn_apply would have stored.
+    const fixsum_t* in_sums;
+    double in_count;
+    float *in_mean, *in_invstd, *in_rmean, *in_rvar;
+    const float *in_gamma, *in_beta;
+    void* a_out;
 };
 int conv_fwd_tiles(const ConvShape& cs);
 // x, y, dy, dx are activations of storage type `act`.  In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).

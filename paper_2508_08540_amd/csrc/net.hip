@@ -190,6 +190,10 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
     }
     const act_t* block_in = nullptr;
     const act_t* cur = s.xpad;
+    // Training: the batch norm + ReLU of a layer without a shortcut (the stem and the first convolution of every block)
+    // is applied by the next convolution while it stages its input, which also stores the activation for the backward
+    // pass; `pending` is that layer, whose raw convolution output the next launch reads.
+    int pending = -1;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
@@ -202,7 +206,19 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             ConvEpi e{};
             e.sums = s.sums + (size_t)l * 2 * FIX_SET;
             e.scale = FIX_FWD_SCALE;
-            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
+            const act_t* x_in = cur;
+            if (pending >= 0) {
+                const ConvBn& pb = m->layers[pending];
+                e.in_sums = s.sums + (size_t)pending * 2 * FIX_SET;
+                e.in_count = (double)((int64_t)B * pb.h_out * pb.h_out);
+                e.in_mean = s.mean[pending]; e.in_invstd = s.invstd[pending];
+                e.in_rmean = buffers + pb.rmean_off; e.in_rvar = buffers + pb.rvar_off;
+                e.in_gamma = params + pb.gamma_off; e.in_beta = params + pb.beta_off;
+                e.a_out = s.a[pending];
+                x_in = s.y[pending];
+                pending = -1;
+            }
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, x_in, s.wpack + s.fwd_off[l], y, &e, kt));
         } else {
             // inference: one kernel per layer, batch norm (running statistics), shortcut and ReLU in the epilogue
             ConvEpi e{};
@@ -214,6 +230,11 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             }
             PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, cur, s.wpack + s.fwd_off[l], y, &e, kt));
             cur = y;
+            continue;
+        }
+        if (!is_conv2 && l + 1 < L && m->layers[l + 1].stride == 1 && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
+            pending = l;      // no shortcut to add here: the next convolution normalises on load and writes s.a[l]
+            cur = s.a[l];
             continue;
         }
         BnStats bs{};

@@ -4,8 +4,6 @@
 // All kernels are templates on the storage type of the activations; arithmetic is fp32.
 #include "act.h"
 
-#define BN_EPS 1e-5
-#define BN_MOMENTUM 0.1
 #define BN_MAX_C 512
 
 // out = relu(gamma*(y-mean)*invstd + beta + shortcut(res)).  In training the statistics come from the
