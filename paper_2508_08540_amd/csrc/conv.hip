@@ -84,31 +84,33 @@ __device__ __forceinline__ void tile_store(const typename Tile<T>::vec16 (&v)[PR
 // ---- batch norm + ReLU of the layer below applied while staging (training forward) ------------------------------------
 // s_bn[0..3][c] = mean, 1/std, scale, shift of input channel c.  The arithmetic is bn_apply_kernel's, so the staged and
 // the stored values are the ones that kernel would have written.
-__device__ __forceinline__ f32x4 bn_relu4(f32x4 v, const float (*s_bn)[64], int c) {
+__device__ __forceinline__ f32x4 bn_relu4(f32x4 v, f32x4 res, const float (*s_bn)[64], int c) {
     f32x4 o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float t = __fmaf_rn((v[j] - s_bn[0][c + j]) * s_bn[1][c + j], s_bn[2][c + j], s_bn[3][c + j]) + 0.f;
+        const float t = __fmaf_rn((v[j] - s_bn[0][c + j]) * s_bn[1][c + j], s_bn[2][c + j], s_bn[3][c + j]) + res[j];
         o[j] = fmaxf(t, 0.f);
     }
     return o;
 }
+// v and res (the shortcut, zeros where there is none) as loaded: 4 fp32 or 8 bf16 channels from c on
 template <typename T>
-__device__ __forceinline__ typename Tile<T>::vec16 bn_relu16(typename Tile<T>::vec16 v, const float (*s_bn)[64], int c) {
+__device__ __forceinline__ typename Tile<T>::vec16 bn_relu16(typename Tile<T>::vec16 v, typename Tile<T>::vec16 res, const float (*s_bn)[64], int c) {
     if constexpr (sizeof(T) == 4) {
-        return bn_relu4(v, s_bn, c);
+        return bn_relu4(v, res, s_bn, c);
     } else {
-        const uint2 lo = Act<T>::narrow(bn_relu4(Act<T>::widen(make_uint2(v.x, v.y)), s_bn, c));
-        const uint2 hi = Act<T>::narrow(bn_relu4(Act<T>::widen(make_uint2(v.z, v.w)), s_bn, c + 4));
+        const uint2 lo = Act<T>::narrow(bn_relu4(Act<T>::widen(make_uint2(v.x, v.y)), Act<T>::widen(make_uint2(res.x, res.y)), s_bn, c));
+        const uint2 hi = Act<T>::narrow(bn_relu4(Act<T>::widen(make_uint2(v.z, v.w)), Act<T>::widen(make_uint2(res.z, res.w)), s_bn, c + 4));
         return make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
 }
 
 // tile_store with that transform: rows and columns outside the image stay zero; the rows the tile's own output rows
 // sit on (everything but the halo) also go to a_out, so that every pixel of the activation is written exactly once.
-template <typename T, int CIN>
-__device__ __forceinline__ void tile_store_bn(const typename Tile<T>::vec16 (&v)[PRE_ROWS], typename Tile<T>::quad* __restrict__ ldsq,
-                                              const ConvGeom& g, int tile, const float (*s_bn)[64], T* __restrict__ a_out) {
+template <typename T, int CIN, bool RES>
+__device__ __forceinline__ void tile_store_bn(const typename Tile<T>::vec16 (&v)[PRE_ROWS], const typename Tile<T>::vec16 (&vr)[RES ? PRE_ROWS : 1],
+                                              typename Tile<T>::quad* __restrict__ ldsq, const ConvGeom& g, int tile, const float (*s_bn)[64],
+                                              T* __restrict__ a_out) {
     constexpr int CPQ = CIN / 4 + 1, CQ = CIN / 4 / Tile<T>::VQ;
     constexpr int CQ_LOG2 = clog2(CQ);
     const int col = threadIdx.x;
@@ -131,7 +133,7 @@ __device__ __forceinline__ void tile_store_bn(const typename Tile<T>::vec16 (&v)
         if (r < rows_total) {
             typename Tile<T>::vec16 o = v[r];
             if (ok) {
-                o = bn_relu16<T>(o, s_bn, c0);
+                o = bn_relu16<T>(o, RES ? vr[RES ? r : 0] : Tile<T>::zero16(), s_bn, c0);
                 if (li >= g.pad && li < g.pad + rpi)
                     *reinterpret_cast<typename Tile<T>::vec16*>(a_out + (((int64_t)n * g.h_in + hi) * g.h_in + wi) * CIN + c0) = o;
             }
@@ -141,9 +143,9 @@ __device__ __forceinline__ void tile_store_bn(const typename Tile<T>::vec16 (&v)
 }
 
 // stage_input with the same transform (tiles that do not fit the prefetching path)
-template <typename T, int CIN, int THREADS>
-__device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ x, const ConvGeom& g, int tile,
-                                               const float (*s_bn)[64], T* __restrict__ a_out) {
+template <typename T, int CIN, int THREADS, bool RES>
+__device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ x, const T* __restrict__ res,
+                                               const ConvGeom& g, int tile, const float (*s_bn)[64], T* __restrict__ a_out) {
     typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = clog2(CQ);
@@ -159,7 +161,7 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
         const int64_t colo = (int64_t)(wok ? wi : 0) * CIN + cq * 4;
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
         for (int r0 = 0; r0 < rows_total; r0 += R) {
-            raw4 v[R];
+            raw4 v[R], vr[R];
             int64_t at[R];
             bool ok[R], inner[R];
 #pragma unroll
@@ -172,15 +174,18 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
                 ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
                 inner[r] = li >= g.pad && li < g.pad + rpi;
                 at[r] = ((int64_t)n * g.h_in + hi) * g.h_in * CIN + colo;
-                v[r] = Act<T>::zero();
-                if (ok[r]) v[r] = Act<T>::load_raw(x + at[r]);
+                v[r] = vr[r] = Act<T>::zero();
+                if (ok[r]) {
+                    v[r] = Act<T>::load_raw(x + at[r]);
+                    if (RES) vr[r] = Act<T>::load_raw(res + at[r]);
+                }
             }
 #pragma unroll
             for (int r = 0; r < R; ++r)
                 if (r0 + r < rows_total) {
                     raw4 o = v[r];
                     if (ok[r]) {
-                        const f32x4 t = bn_relu4(Act<T>::widen(o), s_bn, cq * 4);
+                        const f32x4 t = bn_relu4(Act<T>::widen(o), Act<T>::widen(vr[r]), s_bn, cq * 4);
                         if constexpr (sizeof(T) == 4) o = t;
                         else o = Act<T>::narrow(t);
                         if (inner[r]) *reinterpret_cast<raw4*>(a_out + at[r]) = o;
@@ -336,15 +341,15 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
 // The grid is persistent: workgroup b handles tiles b, b + gridDim.x, ...  While the MFMAs of one tile
 // run from one LDS buffer, the global loads of the next tile are in flight into registers and are then
 // written to the other buffer (one barrier per tile).
-// XF: the input is the raw convolution output of the layer below; its batch norm and ReLU are applied while staging
-// (ConvEpi::in_sums and the fields after it).
-template <typename T, int CIN, int MT, int NW, int EPI, bool XF>
+// XF > 0: the input is the raw convolution output of the layer below; its batch norm (XF == 2: plus an identity
+// shortcut) and ReLU are applied while staging (ConvEpi::in_sums and the fields after it).
+template <typename T, int CIN, int MT, int NW, int EPI, int XF>
 __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
                                                             T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     typedef typename Tile<T>::quad quad;
     __shared__ float s_bn[XF ? 4 : 1][64];
-    if constexpr (XF) {
+    if constexpr (XF != 0) {
         // statistics of the input's batch norm, exactly as bn_apply_kernel derives them
         const int c = threadIdx.x;
         if (c < CIN) {
@@ -368,6 +373,8 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
         __syncthreads();
     }
     T* a_out = static_cast<T*>(e.a_out);
+    const T* in_res = static_cast<const T*>(e.in_res);
+    constexpr bool RES = XF == 2;
     extern __shared__ f32x4 lds_raw[];  // vector-typed so that tile reads and writes are single 16- or 8-byte LDS accesses
     quad* lds4 = reinterpret_cast<quad*>(lds_raw);
     float* lds = reinterpret_cast<float*>(lds_raw);
@@ -392,24 +399,29 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
     if (pipelined) {
         const int buf_f4 = g.imgs * g.in_rows * g.lw * ((CIN + 4) / 4);
         typename Tile<T>::vec16 pre[PRE_ROWS];
+        typename Tile<T>::vec16 pre_r[RES ? PRE_ROWS : 1];
         int tile = blockIdx.x;
         tile_load<T, CIN>(pre, x, g, tile);
-        if constexpr (XF) tile_store_bn<T, CIN>(pre, lds4, g, tile, s_bn, a_out);
+        if constexpr (RES) tile_load<T, CIN>(pre_r, in_res, g, tile);
+        if constexpr (XF != 0) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4, g, tile, s_bn, a_out);
         else tile_store<T, CIN>(pre, lds4, g);
         __syncthreads();
         for (int it = 0; tile < g.n_tiles; ++it, tile += gridDim.x) {
             const int next = tile + gridDim.x;
-            if (next < g.n_tiles) tile_load<T, CIN>(pre, x, g, next);
+            if (next < g.n_tiles) {
+                tile_load<T, CIN>(pre, x, g, next);
+                if constexpr (RES) tile_load<T, CIN>(pre_r, in_res, g, next);
+            }
             conv_tile<T, CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
             if (next < g.n_tiles) {
-                if constexpr (XF) tile_store_bn<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g, next, s_bn, a_out);
+                if constexpr (XF != 0) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4 + ((it + 1) & 1) * buf_f4, g, next, s_bn, a_out);
                 else tile_store<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
             }
             __syncthreads();
         }
     } else {
         for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
-            if constexpr (XF) stage_input_bn<T, CIN, NW * 64>(lds4, x, g, tile, s_bn, a_out);
+            if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out);
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();
             conv_tile<T, CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
@@ -462,9 +474,9 @@ static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const vo
     const int pipelined = (g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
     size_t lds = input_lds_bytes<T, CIN>(g) * (pipelined ? 2 : 1);
     if ((EPI == 1 || EPI == 2) && lds < 1024) lds = 1024;  // per-wave partial sums
-    auto kern = conv_kernel<T, CIN, MT, NW, EPI, false>;
+    auto kern = conv_kernel<T, CIN, MT, NW, EPI, 0>;
     if constexpr (EPI == 1) {
-        if (e.in_sums) kern = conv_kernel<T, CIN, MT, NW, EPI, true>;
+        if (e.in_sums) kern = e.in_res ? conv_kernel<T, CIN, MT, NW, EPI, 2> : conv_kernel<T, CIN, MT, NW, EPI, 1>;
     }
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)

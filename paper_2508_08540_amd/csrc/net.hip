@@ -194,6 +194,7 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
     // is applied by the next convolution while it stages its input, which also stores the activation for the backward
     // pass; `pending` is that layer, whose raw convolution output the next launch reads.
     int pending = -1;
+    const act_t* pending_res = nullptr;   // identity shortcut that goes with it (the end of a block), or nullptr
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
@@ -214,6 +215,7 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
                 e.in_mean = s.mean[pending]; e.in_invstd = s.invstd[pending];
                 e.in_rmean = buffers + pb.rmean_off; e.in_rvar = buffers + pb.rvar_off;
                 e.in_gamma = params + pb.gamma_off; e.in_beta = params + pb.beta_off;
+                e.in_res = pending_res;
                 e.a_out = s.a[pending];
                 x_in = s.y[pending];
                 pending = -1;
@@ -232,8 +234,12 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             cur = y;
             continue;
         }
-        if (!is_conv2 && l + 1 < L && m->layers[l + 1].stride == 1 && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
-            pending = l;      // no shortcut to add here: the next convolution normalises on load and writes s.a[l]
+        // the next convolution can normalise on load when it keeps the shape (stride 1, same channels) and the shortcut to
+        // add, if any, is the identity (a block that keeps the shape)
+        const bool identity_res = is_conv2 && m->layers[l - 1].stride == 1 && m->layers[l - 1].c_in == cb.c_out;
+        if ((!is_conv2 || identity_res) && l + 1 < L && m->layers[l + 1].stride == 1 && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
+            pending = l;      // the next convolution writes s.a[l]
+            pending_res = is_conv2 ? block_in : nullptr;
             cur = s.a[l];
             continue;
         }
