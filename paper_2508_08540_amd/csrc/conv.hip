@@ -196,6 +196,81 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
     }
 }
 
+// ---- batch-norm backward of the layer applied while its input gradient stages dy -----------------------------------------
+// s_bw[0..4][c] = sum of g, sum of g * xhat, mean, 1/std, scale of channel c; the expression is bn_bwd_apply_kernel's.
+__device__ __forceinline__ f32x4 bn_bwd4(f32x4 d, f32x4 o, f32x4 v, const float (*s_bw)[64], int c, float inv_count, f32x4& gq) {
+    f32x4 r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float g = o[j] > 0.f ? d[j] : 0.f;
+        float xhat = (v[j] - s_bw[2][c + j]) * s_bw[3][c + j];
+        gq[j] = g;
+        r[j] = s_bw[4][c + j] * s_bw[3][c + j] * (g - s_bw[0][c + j] * inv_count - xhat * (s_bw[1][c + j] * inv_count));
+    }
+    return r;
+}
+
+// Stages dy = batch-norm backward of (dout, out, y) for the tile, zero outside the image; the rows that are not halo are
+// stored to dy_out (and the masked gradient to g_out), every pixel exactly once.
+template <typename T, int CIN, int THREADS>
+__device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ dout, const T* __restrict__ out,
+                                                const T* __restrict__ y, const ConvGeom& g, int tile, const float (*s_bw)[64], float inv_count,
+                                                T* __restrict__ dy_out, T* __restrict__ g_out) {
+    typedef typename Act<T>::raw4 raw4;
+    constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
+    constexpr int CQ_LOG2 = clog2(CQ);
+    constexpr int R = 3;
+    const int rpi = 1 << g.rpi_log2;
+    const int row0 = tile * g.rows_tile;
+    const int n_cols = g.lw * CQ;
+    const int rows_total = g.imgs * g.in_rows;
+    for (int col = threadIdx.x; col < n_cols; col += THREADS) {
+        const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
+        const int wi = lc - g.pad;
+        const bool wok = (unsigned)wi < (unsigned)g.h_in;
+        const int64_t colo = (int64_t)(wok ? wi : 0) * CIN + cq * 4;
+        typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
+        for (int r0 = 0; r0 < rows_total; r0 += R) {
+            raw4 vd[R], vo[R], vy[R];
+            int64_t at[R];
+            bool ok[R], inner[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int lr = r0 + r;                               // wave-uniform
+                const int part = lr / g.in_rows, li = lr - part * g.in_rows;
+                const int grow = row0 + part * rpi;
+                const int n = grow >> g.wout_log2;
+                const int hi = (grow & (g.h_out - 1)) - g.pad + li;
+                ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
+                inner[r] = li >= g.pad && li < g.pad + rpi;
+                at[r] = ((int64_t)n * g.h_in + hi) * g.h_in * CIN + colo;
+                vd[r] = vo[r] = vy[r] = Act<T>::zero();
+                if (ok[r]) {
+                    vd[r] = Act<T>::load_raw(dout + at[r]);
+                    vo[r] = Act<T>::load_raw(out + at[r]);
+                    vy[r] = Act<T>::load_raw(y + at[r]);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (r0 + r < rows_total) {
+                    raw4 o = Act<T>::zero();
+                    if (ok[r]) {
+                        f32x4 gq;
+                        const f32x4 t = bn_bwd4(Act<T>::widen(vd[r]), Act<T>::widen(vo[r]), Act<T>::widen(vy[r]), s_bw, cq * 4, inv_count, gq);
+                        if constexpr (sizeof(T) == 4) o = t;
+                        else o = Act<T>::narrow(t);
+                        if (inner[r]) {
+                            *reinterpret_cast<raw4*>(dy_out + at[r]) = o;
+                            if (g_out) Act<T>::store4(g_out + at[r], gq);
+                        }
+                    }
+                    dst[(r0 + r) * g.lw * CP4] = o;
+                }
+        }
+    }
+}
+
 template <typename T, int CIN, int MT, int NW, int EPI>
 __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restrict__ lds4, const typename Tile<T>::quad (&wr)[9][CIN / 16],
                                           T* __restrict__ y, const ConvEpi& e, const ConvGeom& g, int tile, f32x4& ssum, f32x4& ssq) {
@@ -341,15 +416,30 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
 // The grid is persistent: workgroup b handles tiles b, b + gridDim.x, ...  While the MFMAs of one tile
 // run from one LDS buffer, the global loads of the next tile are in flight into registers and are then
 // written to the other buffer (one barrier per tile).
-// XF > 0: the input is the raw convolution output of the layer below; its batch norm (XF == 2: plus an identity
-// shortcut) and ReLU are applied while staging (ConvEpi::in_sums and the fields after it).
+// XF 1, 2: the input is the raw convolution output of the layer below; its batch norm (XF == 2: plus an identity
+// shortcut) and ReLU are applied while staging (ConvEpi::in_sums and the fields after it).  XF 3 (input gradient): the
+// input dy is computed while staging, by the layer's batch-norm backward (ConvEpi::bw_dout and the fields after it).
 template <typename T, int CIN, int MT, int NW, int EPI, int XF>
 __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
                                                             T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     typedef typename Tile<T>::quad quad;
-    __shared__ float s_bn[XF ? 4 : 1][64];
-    if constexpr (XF != 0) {
+    __shared__ float s_bn[XF == 3 ? 5 : XF ? 4 : 1][64];
+    if constexpr (XF == 3) {
+        const int c = threadIdx.x;
+        if (c < CIN) {
+            s_bn[0][c] = (float)((double)fixsum_read(e.bw_sums, CIN, 0, c) * (1.0 / FIX_BWD_SCALE));
+            s_bn[1][c] = (float)((double)fixsum_read(e.bw_sums, CIN, 1, c) * (1.0 / FIX_BWD_SCALE));
+            s_bn[2][c] = e.bw_mean[c];
+            s_bn[3][c] = e.bw_invstd[c];
+            s_bn[4][c] = e.bw_gamma[c];
+            if (blockIdx.x == 0) {
+                e.bw_dbeta[c] = s_bn[0][c];
+                e.bw_dgamma[c] = s_bn[1][c];
+            }
+        }
+        __syncthreads();
+    } else if constexpr (XF != 0) {
         // statistics of the input's batch norm, exactly as bn_apply_kernel derives them
         const int c = threadIdx.x;
         if (c < CIN) {
@@ -403,7 +493,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
         int tile = blockIdx.x;
         tile_load<T, CIN>(pre, x, g, tile);
         if constexpr (RES) tile_load<T, CIN>(pre_r, in_res, g, tile);
-        if constexpr (XF != 0) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4, g, tile, s_bn, a_out);
+        if constexpr (XF == 1 || XF == 2) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4, g, tile, s_bn, a_out);
         else tile_store<T, CIN>(pre, lds4, g);
         __syncthreads();
         for (int it = 0; tile < g.n_tiles; ++it, tile += gridDim.x) {
@@ -414,14 +504,17 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             }
             conv_tile<T, CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
             if (next < g.n_tiles) {
-                if constexpr (XF != 0) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4 + ((it + 1) & 1) * buf_f4, g, next, s_bn, a_out);
+                if constexpr (XF == 1 || XF == 2) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4 + ((it + 1) & 1) * buf_f4, g, next, s_bn, a_out);
                 else tile_store<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
             }
             __syncthreads();
         }
     } else {
         for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
-            if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out);
+            if constexpr (XF == 3)
+                stage_input_bwd<T, CIN, NW * 64>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_out), static_cast<const T*>(e.bw_y), g,
+                                                 tile, s_bn, e.bw_inv_count, static_cast<T*>(e.bw_dy_out), static_cast<T*>(e.bw_g_out));
+            else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out);
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();
             conv_tile<T, CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
@@ -471,12 +564,17 @@ static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const vo
     const int grid = conv_grid(g);
     // prefetching needs the whole tile in PRE_ROWS registers per thread, one column per thread, and more
     // than one tile per workgroup to pay off
-    const int pipelined = (g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
+    bool fused_bwd = false;
+    if constexpr (EPI == 2) fused_bwd = e.bw_dout != nullptr;   // three tensors per element do not fit the prefetching path's registers
+    const int pipelined = (!fused_bwd && g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
     size_t lds = input_lds_bytes<T, CIN>(g) * (pipelined ? 2 : 1);
     if ((EPI == 1 || EPI == 2) && lds < 1024) lds = 1024;  // per-wave partial sums
     auto kern = conv_kernel<T, CIN, MT, NW, EPI, 0>;
     if constexpr (EPI == 1) {
         if (e.in_sums) kern = e.in_res ? conv_kernel<T, CIN, MT, NW, EPI, 2> : conv_kernel<T, CIN, MT, NW, EPI, 1>;
+    }
+    if constexpr (EPI == 2) {
+        if (fused_bwd) kern = conv_kernel<T, CIN, MT, NW, EPI, 3>;
     }
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)

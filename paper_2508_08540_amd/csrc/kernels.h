@@ -138,6 +138,16 @@ struct ConvEpi {
     const float *in_gamma, *in_beta;
     const void* in_res;   // optional identity shortcut of x's shape, added before the ReLU (the end of a block)
     void* a_out;
+    // input gradient with bw_dout != nullptr (stride-1 layers): the launch's input dy does not exist yet.  The kernel computes
+    // it while staging, as bn_bwd_apply does, from the gradient bw_dout of the layer's activation bw_out, the layer's
+    // convolution output bw_y, its statistics and the backward sums bw_sums [2][C] (workgroup 0 stores the scale and shift
+    // gradients), and stores it to bw_dy_out for the weight gradient; bw_g_out (optional) takes dout * (out > 0).
+    const void *bw_dout, *bw_out, *bw_y;
+    const float *bw_mean, *bw_invstd, *bw_gamma;
+    const fixsum_t* bw_sums;
+    float *bw_dgamma, *bw_dbeta;
+    float bw_inv_count;
+    void *bw_dy_out, *bw_g_out;
 };
 int conv_fwd_tiles(const ConvShape& cs);
 // x, y, dy, dx are activations of storage type `act`.  In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).

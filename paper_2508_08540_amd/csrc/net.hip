@@ -23,6 +23,7 @@ namespace {
 
 constexpr int PAD_C = 16;       // the stem's input is zero-padded to 16 channels so it runs on the same kernels
 constexpr int SCORE_CHUNK = 2048;
+constexpr int FUSED_BWD_MIN_C = 32;   // channel count from which the batch-norm backward rides in the input gradient's staging
 constexpr int MLP_SPLITS = 8;
 
 int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
@@ -289,12 +290,23 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l],
                                                       s.sums + ((size_t)l * 2 + 1) * FIX_SET));
         }
-        PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
-                            s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
-        BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
-        BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
-        PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt));
+        // Layers in the narrower stages (their tiles take the non-prefetching staging anyway) with stride 1 and a tensor as
+        // upstream gradient: the input-gradient convolution computes dy itself while staging, the element-wise kernel goes
+        const bool fused_bwd = l > 0 && !shared && cb.stride == 1 && cb.c_out <= 64 && cb.c_out >= FUSED_BWD_MIN_C;
+        auto weight_gradient = [&]() -> int {
+            BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
+            BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
+            PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(ctx->aux, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt));
+            return BLS_OK;
+        };
+        if (!fused_bwd) {
+            PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
+                                s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
+            int rcw = weight_gradient();
+            if (rcw != BLS_OK) return rcw;
+        }
         if (l == 0) break;
+        act_t* dx = dout == s.d2 ? s.d1 : s.d2;   // never the tensor the fused staging reads
         {
             // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
             // batch-norm backward sums of layer l-1
@@ -306,9 +318,21 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                 const ConvBn& c2 = m->layers[l + 1];
                 e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
             }
-            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, s.act, cs, s.dy[l], s.wpack + s.dgrad_off[l], s.d2, &e, kt));
+            if (fused_bwd) {
+                e.bw_dout = dout; e.bw_out = s.a[l]; e.bw_y = s.y[l];
+                e.bw_mean = s.mean[l]; e.bw_invstd = s.invstd[l]; e.bw_gamma = params + cb.gamma_off;
+                e.bw_sums = s.sums + ((size_t)l * 2 + 1) * FIX_SET;
+                e.bw_dgamma = s.grad + cb.gamma_off; e.bw_dbeta = s.grad + cb.beta_off;
+                e.bw_inv_count = 1.f / (float)pixels;
+                e.bw_dy_out = s.dy[l]; e.bw_g_out = is_conv2 ? s.g : nullptr;
+            }
+            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, s.act, cs, s.dy[l], s.wpack + s.dgrad_off[l], dx, &e, kt));
         }
-        dout = s.d2;
+        if (fused_bwd) {
+            int rcw = weight_gradient();   // dy[l] exists once the input gradient has run
+            if (rcw != BLS_OK) return rcw;
+        }
+        dout = dx;
         shared = 0;
     }
     BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
