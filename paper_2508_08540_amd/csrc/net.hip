@@ -23,7 +23,7 @@ namespace {
 
 constexpr int PAD_C = 16;       // the stem's input is zero-padded to 16 channels so it runs on the same kernels
 constexpr int SCORE_CHUNK = 2048;
-constexpr int FUSED_BWD_MIN_C = 32;   // channel count from which the batch-norm backward rides in the input gradient's staging
+constexpr int FUSED_BWD_MIN_C = 16;   // channel count from which the batch-norm backward rides in the input gradient's staging
 constexpr int MLP_SPLITS = 8;
 
 int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
