@@ -128,13 +128,13 @@ __device__ __forceinline__ void tile_store_bn(const typename Tile<T>::vec16 (&v)
         const int part = r / g.in_rows, li = r - part * g.in_rows;  // wave-uniform
         const int grow = row0 + part * rpi;
         const int n = grow >> g.wout_log2;
-        const int hi = (grow & (g.h_out - 1)) - g.pad + li;
+        const int hi = (grow & (g.h_out - 1)) * g.stride - g.pad + li;
         const bool ok = r < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
         if (r < rows_total) {
             typename Tile<T>::vec16 o = v[r];
             if (ok) {
                 o = bn_relu16<T>(o, RES ? vr[RES ? r : 0] : Tile<T>::zero16(), s_bn, c0);
-                if (li >= g.pad && li < g.pad + rpi)
+                if (li >= g.pad && li < g.pad + rpi * g.stride)
                     *reinterpret_cast<typename Tile<T>::vec16*>(a_out + (((int64_t)n * g.h_in + hi) * g.h_in + wi) * CIN + c0) = o;
             }
             Tile<T>::store16(dst + r * g.lw * CPQ, o);
@@ -170,9 +170,9 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
                 const int part = lr / g.in_rows, li = lr - part * g.in_rows;
                 const int grow = row0 + part * rpi;
                 const int n = grow >> g.wout_log2;
-                const int hi = (grow & (g.h_out - 1)) - g.pad + li;
+                const int hi = (grow & (g.h_out - 1)) * g.stride - g.pad + li;
                 ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
-                inner[r] = li >= g.pad && li < g.pad + rpi;
+                inner[r] = li >= g.pad && li < g.pad + rpi * g.stride;
                 at[r] = ((int64_t)n * g.h_in + hi) * g.h_in * CIN + colo;
                 v[r] = vr[r] = Act<T>::zero();
                 if (ok[r]) {
@@ -227,8 +227,10 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
     for (int col = threadIdx.x; col < n_cols; col += THREADS) {
         const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
         const int wi = lc - g.pad;
-        const bool wok = (unsigned)wi < (unsigned)g.h_in;
-        const int64_t colo = (int64_t)(wok ? wi : 0) * CIN + cq * 4;
+        // stride-2 layers: dy is read with zeros inserted (g.ups), only even virtual coordinates hold a pixel
+        const bool wok = (unsigned)wi < (unsigned)g.h_in && !(g.ups && (wi & 1));
+        const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
+        const int64_t colo = (int64_t)(wok ? (g.ups ? wi >> 1 : wi) : 0) * CIN + cq * 4;
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
         for (int r0 = 0; r0 < rows_total; r0 += R) {
             raw4 vd[R], vo[R], vy[R];
@@ -241,9 +243,9 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
                 const int grow = row0 + part * rpi;
                 const int n = grow >> g.wout_log2;
                 const int hi = (grow & (g.h_out - 1)) - g.pad + li;
-                ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
+                ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok && !(g.ups && (hi & 1));
                 inner[r] = li >= g.pad && li < g.pad + rpi;
-                at[r] = ((int64_t)n * g.h_in + hi) * g.h_in * CIN + colo;
+                at[r] = ((int64_t)n * src_h + (g.ups ? hi >> 1 : hi)) * src_h * CIN + colo;
                 vd[r] = vo[r] = vy[r] = Act<T>::zero();
                 if (ok[r]) {
                     vd[r] = Act<T>::load_raw(dout + at[r]);

@@ -131,7 +131,7 @@ struct ConvEpi {
     // training forward with in_sums != nullptr: the input x is the raw convolution output of the layer below.  The kernel
     // turns that layer's sums into statistics (workgroup 0 stores them and updates the running statistics, as bn_apply
     // does), applies its batch norm (+ shortcut) and ReLU while staging, and writes the activation to a_out for the backward pass.
-    // Stride-1 3x3 layers only; the values are those bn_apply would have stored.
+    // 3x3 layers of either stride; the values are those bn_apply would have stored.
     const fixsum_t* in_sums;
     double in_count;
     float *in_mean, *in_invstd, *in_rmean, *in_rvar;

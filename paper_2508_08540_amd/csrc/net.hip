@@ -235,10 +235,10 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             cur = y;
             continue;
         }
-        // the next convolution can normalise on load when it keeps the shape (stride 1, same channels) and the shortcut to
-        // add, if any, is the identity (a block that keeps the shape)
+        // the next convolution can normalise on load when the shortcut to add, if any, is the identity (a block that keeps
+        // the shape)
         const bool identity_res = is_conv2 && m->layers[l - 1].stride == 1 && m->layers[l - 1].c_in == cb.c_out;
-        if ((!is_conv2 || identity_res) && l + 1 < L && m->layers[l + 1].stride == 1 && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
+        if ((!is_conv2 || identity_res) && l + 1 < L && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
             pending = l;      // the next convolution writes s.a[l]
             pending_res = is_conv2 ? block_in : nullptr;
             cur = s.a[l];
@@ -290,9 +290,9 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l],
                                                       s.sums + ((size_t)l * 2 + 1) * FIX_SET));
         }
-        // Layers in the narrower stages (their tiles take the non-prefetching staging anyway) with stride 1 and a tensor as
-        // upstream gradient: the input-gradient convolution computes dy itself while staging, the element-wise kernel goes
-        const bool fused_bwd = l > 0 && !shared && cb.stride == 1 && cb.c_out <= 64 && cb.c_out >= FUSED_BWD_MIN_C;
+        // Layers whose upstream gradient is a tensor (all but the top one): the input-gradient convolution computes dy itself
+        // while staging (for a stride-2 layer at the even positions of the zero-inserted image), the element-wise kernel goes
+        const bool fused_bwd = l > 0 && !shared && cb.c_out <= 64 && cb.c_out >= FUSED_BWD_MIN_C;
         auto weight_gradient = [&]() -> int {
             BLS_HIP(ctx, hipEventRecord(ctx->fork_events[l], st));
             BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->fork_events[l], 0));
