@@ -21,8 +21,11 @@ sys.path.insert(0, ROOT)
 # dispatch averaged over all launches of a bench run), each scaled by what the same counter reads for a plain
 # 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
 MEASURED_TRAFFIC = {
-    "wgrad_kernel": {"fetch_kib": 5461.7, "fetch_scale": 2.0, "write_kib": 9216.0, "write_scale": 1.0,
-                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "cc526ea2bf776c72"},
+    "wgrad_kernel": {"fetch_kib": 5459.7, "fetch_scale": 2.0, "write_kib": 9216.0, "write_scale": 1.0,
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "e53c7889bbd4ac42"},
+    # launch-weighted mean over the 18 input-gradient launches of a local step
+    "conv_kernel (input-gradient launches)": {"fetch_kib": 16554.7, "fetch_scale": 2.0, "write_kib": 12267.0, "write_scale": 1.0,
+                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "e53c7889bbd4ac42"},
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
@@ -38,6 +41,31 @@ def resnet_conv_flops(widths, blocks, hw, in_ch):
             h = h // stride
             total += 2 * 9 * c_prev * c * h * h + 2 * 9 * c * c * h * h
             c_prev = c
+    return total
+
+
+def resnet_dgrad_bytes(widths, blocks, hw, batch, elt):
+    """Algorithmic bytes of the input-gradient launches of one local step (layers 1 .. L-1), each tensor counted once.
+
+    The launch of layer l reads its upstream gradient, activation and convolution output (it applies the layer's
+    batch-norm backward itself; the top layer reads a finished dy instead), the packed weights, the activation and
+    convolution output of layer l-1 (batch-norm backward sums of that layer) and, for the first layer of a block,
+    the shortcut gradient; it writes dy (plus the masked gradient for the last layer of a block) and dx."""
+    layers, c_prev, h = [], widths[0], hw      # (c_in, c_out, h_in, h_out) of layers 1 .. L-1
+    for s, c in enumerate(widths):
+        for b in range(blocks):
+            stride = 2 if (b == 0 and s > 0) else 1
+            layers.append((c_prev, c, h, h // stride))
+            layers.append((c, c, h // stride, h // stride))
+            c_prev, h = c, h // stride
+    total = 0
+    for i, (c_in, c_out, h_in, h_out) in enumerate(layers):
+        out, inn = batch * h_out * h_out * c_out, batch * h_in * h_in * c_in
+        conv2, top = i % 2 == 1, i == len(layers) - 1
+        elems = (out if top else 3 * out + out + (out if conv2 else 0)) + 2 * inn + inn + 9 * c_in * c_out
+        if not conv2:
+            elems += batch * h_out * h_out * c_in    # shortcut gradient: the block's output positions, this layer's input channels
+        total += elems * elt
     return total
 
 
@@ -185,6 +213,15 @@ def main():
     roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2), "launches_per_step": dom_cnt // args.steps}
+    if dom == "conv_dgrad" and not wide:
+        # These launches also carry the batch-norm backward (eight tensors per layer against 2*9*C_in*C_out flop per
+        # pixel): the roof that binds is the one with the larger minimum time.
+        nbytes = resnet_dgrad_bytes((16, 32, 64), 3, 32, B, 2 if act_dtype == "bf16" else 4) * tau
+        if nbytes / (HBM_PEAK_GBS * 1e9) > flops[dom] / (peak * 1e12):
+            gbs = nbytes * args.steps / (dom_ms * 1e-3) / 1e9
+            roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_tflops": round(achieved, 3),
+                             "algorithmic_bytes_per_launch": nbytes * args.steps // dom_cnt})
 
     # Aggregation bandwidth on a vector large enough to leave the caches (WRN-16-8 sized, P = 10),
     # rotating three buffer sets; algorithmic bytes = (P + 1) * d * 4.

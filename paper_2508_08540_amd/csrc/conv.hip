@@ -662,12 +662,18 @@ void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x,
     else launch_conv_c<0>(s, act, cs.c_in, g, x, w, y, ConvEpi{}, kt);
 }
 
+#ifndef DGRAD_TALL_MIN_H
+#define DGRAD_TALL_MIN_H 32
+#endif
 void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt) {
     // The gradient with respect to the input is a stride-1 convolution whose input channels are the
     // layer's output channels and whose output channels are the layer's input channels.
     int ups = cs.stride == 2 ? 1 : 0;
-    ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in);
+    // with the batch-norm backward in the staging three tensors are read per tile: taller tiles on the large images
+    // (halo rows 2 in 10 instead of 2 in 6)
+    const int rows = (bn_below && bn_below->bw_dout && cs.h_in >= DGRAD_TALL_MIN_H) ? 8 : 0;
+    ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in, rows);
     if (bn_below) launch_conv_c<2>(s, act, cs.c_out, g, dy, w, dx, *bn_below, kt);
     else launch_conv_c<0>(s, act, cs.c_out, g, dy, w, dx, ConvEpi{}, kt);
 }
