@@ -653,17 +653,22 @@ int conv_fwd_tiles(const ConvShape& cs) {
     return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
 }
 
+#ifndef FWD_TALL_MIN_H
+#define FWD_TALL_MIN_H 32
+#endif
 void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
                      const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
-    ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real);
+    // normalise-on-load launches on the large images: taller tiles, fewer halo rows of the raw tensor (and its shortcut)
+    const int rows = (stats && stats->in_sums && cs.stride == 1 && h_out >= FWD_TALL_MIN_H) ? 8 : 0;
+    ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows);
     if (stats && stats->gamma) launch_conv_c<3>(s, act, cs.c_in, g, x, w, y, *stats, kt);
     else if (stats) launch_conv_c<1>(s, act, cs.c_in, g, x, w, y, *stats, kt);
     else launch_conv_c<0>(s, act, cs.c_in, g, x, w, y, ConvEpi{}, kt);
 }
 
 #ifndef DGRAD_TALL_MIN_H
-#define DGRAD_TALL_MIN_H 32
+#define DGRAD_TALL_MIN_H 16
 #endif
 void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt) {
