@@ -698,7 +698,13 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 
 #define WGRAD_THREADS 256
 
-template <typename T, int TAPS>
+// PIPE: a thread owns up to WG_XK fixed 4-channel slots of the x tile and WG_DK of the dy tile; the next tile's slots are
+// loaded into registers while the current tile multiplies (tiles small enough for that, see wgrad_geom).
+#define WG_XK 4
+#define WG_DK 2
+#define WG_PIPE_PIXELS 128
+
+template <typename T, int TAPS, bool PIPE>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
                                                               int NI, int NO, int replicas) {
@@ -724,17 +730,72 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
 
     const int tile_begin = blockIdx.x * tiles_per_group;
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
+    typedef typename Act<T>::raw4 raw4;
+    // slot k of this thread: element threadIdx.x + k * WGRAD_THREADS of the tile (rows x columns x 4 channel quads)
+    int x_dst[WG_XK], x_part[WG_XK], x_li[WG_XK], x_off[WG_XK];
+    raw4 xv[WG_XK], dv[WG_DK];
+    if constexpr (PIPE) {
+        const int n_cols = g.lw * 4, slots = g.imgs * g.in_rows * n_cols;
+#pragma unroll
+        for (int k = 0; k < WG_XK; ++k) {
+            const int e = threadIdx.x + k * WGRAD_THREADS;
+            const int lr = e / n_cols, col = e - lr * n_cols;
+            const int lc = col >> 2, cq = col & 3, wi = lc - g.pad;
+            x_dst[k] = e < slots ? (lr * g.lw + lc) * (CP / 4) + cq : -1;
+            x_part[k] = lr / g.in_rows;
+            x_li[k] = lr - x_part[k] * g.in_rows;
+            x_off[k] = (e < slots && (unsigned)wi < (unsigned)g.h_in) ? wi * NI + ib * 16 + cq * 4 : -1;
+        }
+    }
+    auto load_tile = [&](int tile) {
+        const int rpi = 1 << g.rpi_log2;
+        const int row0 = tile * g.rows_tile;
+#pragma unroll
+        for (int k = 0; k < WG_XK; ++k) {
+            xv[k] = Act<T>::zero();
+            if (x_off[k] >= 0) {
+                const int grow = row0 + x_part[k] * rpi;
+                const int n = grow >> g.wout_log2;
+                const int hi = (grow & (g.h_out - 1)) * g.stride - g.pad + x_li[k];
+                if (n < g.B && (unsigned)hi < (unsigned)g.h_in) xv[k] = Act<T>::load_raw(x + ((int64_t)n * g.h_in + hi) * g.h_in * NI + x_off[k]);
+            }
+        }
+        const int64_t pix0 = (int64_t)tile * tile_pixels;
+#pragma unroll
+        for (int k = 0; k < WG_DK; ++k) {
+            const int i = threadIdx.x + k * WGRAD_THREADS;
+            const int q = i >> 2, c4 = i & 3;
+            dv[k] = Act<T>::zero();
+            if (i < tile_pixels * 4 && pix0 + q < total_pixels) dv[k] = Act<T>::load_raw(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
+        }
+    };
+    if constexpr (PIPE) {
+        if (tile_begin < tile_end) load_tile(tile_begin);
+    }
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         __syncthreads();  // previous tile fully consumed
-        stage_input<T, f32x4, 16, WGRAD_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
-        const int64_t pix0 = (int64_t)tile * tile_pixels;
-        for (int i = threadIdx.x; i < tile_pixels * 4; i += WGRAD_THREADS) {
-            int q = i >> 2, c4 = i & 3;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (pix0 + q < total_pixels) v = Act<T>::load4(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
-            reinterpret_cast<f32x4*>(lds_dy)[q * (DP / 4) + c4] = v;
+        if constexpr (PIPE) {
+#pragma unroll
+            for (int k = 0; k < WG_XK; ++k)
+                if (x_dst[k] >= 0) lds4[x_dst[k]] = Act<T>::widen(xv[k]);
+#pragma unroll
+            for (int k = 0; k < WG_DK; ++k) {
+                const int i = threadIdx.x + k * WGRAD_THREADS;
+                if (i < tile_pixels * 4) reinterpret_cast<f32x4*>(lds_dy)[i] = Act<T>::widen(dv[k]);
+            }
+            __syncthreads();
+            if (tile + 1 < tile_end) load_tile(tile + 1);
+        } else {
+            stage_input<T, f32x4, 16, WGRAD_THREADS, 0>(lds4, x, g, tile, NI, ib * 16);
+            const int64_t pix0 = (int64_t)tile * tile_pixels;
+            for (int i = threadIdx.x; i < tile_pixels * 4; i += WGRAD_THREADS) {
+                int q = i >> 2, c4 = i & 3;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (pix0 + q < total_pixels) v = Act<T>::load4(dy + (pix0 + q) * NO + ob * 16 + c4 * 4);
+                reinterpret_cast<f32x4*>(lds_dy)[q * (DP / 4) + c4] = v;
+            }
+            __syncthreads();
         }
-        __syncthreads();
         // One MFMA consumes 4 pixels (one per lane group).
         if (w_out >= 4) {
             // a quad lies inside one output row: the waves take rows in turn and the row base is wave-uniform
@@ -867,8 +928,20 @@ void launch_update(hipStream_t s, int act, float* params, float* momentum, const
 
 // Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller
 // when the staged 16-channel input slice would exceed 40 KB of LDS.
+static bool wgrad_fits_pipe(const ConvGeom& g) {
+    return g.imgs * g.in_rows * g.lw * 4 <= WG_XK * WGRAD_THREADS && (g.rows_tile << g.wout_log2) * 4 <= WG_DK * WGRAD_THREADS;
+}
+
 static ConvGeom wgrad_geom(const ConvShape& cs) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
+    {
+        // preferred: tiles of WG_PIPE_PIXELS pixels whose slots fit the prefetch registers, two or more per workgroup
+        int rows = WG_PIPE_PIXELS / h_out;
+        if (rows >= 1 && h_out >= 4) {
+            ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows, cs.taps == 9 ? 1 : 0);
+            if (wgrad_fits_pipe(g)) return g;
+        }
+    }
     int rows = 256 / h_out;
     if (rows < 4) rows = 4;
     for (;;) {
@@ -906,10 +979,12 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
-    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<T, TAPS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const bool pipe = wgrad_fits_pipe(g) && tiles_per_group > 1;
+    auto kern = pipe ? wgrad_kernel<T, TAPS, true> : wgrad_kernel<T, TAPS, false>;
+    if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (lds < 4 * 16 * TAPS * 16 * sizeof(float)) lds = 4 * 16 * TAPS * 16 * sizeof(float);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipExtLaunchKernelGGL((wgrad_kernel<T, TAPS>), dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
+    hipExtLaunchKernelGGL(kern, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
                           kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out, groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS);
 }
 
