@@ -697,6 +697,9 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40: |dW| < 2^23, resolution 2^-40
 
 #define WGRAD_THREADS 256
+#ifndef WGRAD_GROUP_CAP
+#define WGRAD_GROUP_CAP 512
+#endif
 
 // PIPE: a thread owns up to WG_XK fixed 4-channel slots of the x tile and WG_DK of the dy tile; the next tile's slots are
 // loaded into registers while the current tile multiplies (tiles small enough for that, see wgrad_geom).
@@ -953,7 +956,7 @@ static ConvGeom wgrad_geom(const ConvShape& cs) {
 
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    int cap = 512 / blocks;
+    int cap = WGRAD_GROUP_CAP / blocks;
     if (cap < 1) cap = 1;
     return n_tiles < cap ? n_tiles : cap;
 }
