@@ -105,44 +105,8 @@ __device__ __forceinline__ typename Tile<T>::vec16 bn_relu16(typename Tile<T>::v
     }
 }
 
-// tile_store with that transform: rows and columns outside the image stay zero; the rows the tile's own output rows
+// stage_input with that transform: rows and columns outside the image stay zero; the rows the tile's own output rows
 // sit on (everything but the halo) also go to a_out, so that every pixel of the activation is written exactly once.
-template <typename T, int CIN, bool RES>
-__device__ __forceinline__ void tile_store_bn(const typename Tile<T>::vec16 (&v)[PRE_ROWS], const typename Tile<T>::vec16 (&vr)[RES ? PRE_ROWS : 1],
-                                              typename Tile<T>::quad* __restrict__ ldsq, const ConvGeom& g, int tile, const float (*s_bn)[64],
-                                              T* __restrict__ a_out) {
-    constexpr int CPQ = CIN / 4 + 1, CQ = CIN / 4 / Tile<T>::VQ;
-    constexpr int CQ_LOG2 = clog2(CQ);
-    const int col = threadIdx.x;
-    if (col >= g.lw * CQ) return;
-    const int rpi = 1 << g.rpi_log2;
-    const int row0 = tile * g.rows_tile;
-    const int rows_total = g.imgs * g.in_rows;
-    const int cq = col & (CQ - 1), lc = col >> CQ_LOG2;
-    const int c0 = cq * (4 * Tile<T>::VQ);
-    const int wi = lc - g.pad;
-    const bool wok = (unsigned)wi < (unsigned)g.h_in;
-    typename Tile<T>::quad* dst = ldsq + lc * CPQ + cq * Tile<T>::VQ;
-#pragma unroll
-    for (int r = 0; r < PRE_ROWS; ++r) {
-        const int part = r / g.in_rows, li = r - part * g.in_rows;  // wave-uniform
-        const int grow = row0 + part * rpi;
-        const int n = grow >> g.wout_log2;
-        const int hi = (grow & (g.h_out - 1)) * g.stride - g.pad + li;
-        const bool ok = r < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
-        if (r < rows_total) {
-            typename Tile<T>::vec16 o = v[r];
-            if (ok) {
-                o = bn_relu16<T>(o, RES ? vr[RES ? r : 0] : Tile<T>::zero16(), s_bn, c0);
-                if (li >= g.pad && li < g.pad + rpi * g.stride)
-                    *reinterpret_cast<typename Tile<T>::vec16*>(a_out + (((int64_t)n * g.h_in + hi) * g.h_in + wi) * CIN + c0) = o;
-            }
-            Tile<T>::store16(dst + r * g.lw * CPQ, o);
-        }
-    }
-}
-
-// stage_input with the same transform (tiles that do not fit the prefetching path)
 template <typename T, int CIN, int THREADS, bool RES>
 __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ x, const T* __restrict__ res,
                                                const ConvGeom& g, int tile, const float (*s_bn)[64], T* __restrict__ a_out) {
@@ -488,27 +452,20 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
     }
     f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
 
-    if (pipelined) {
+    // the transforming variants stage without prefetching: their launches have at most one or two tiles per workgroup
+    // at the batch sizes of a local step, and the prefetch registers would cost them a wave of occupancy
+    if (XF == 0 && pipelined) {
         const int buf_f4 = g.imgs * g.in_rows * g.lw * ((CIN + 4) / 4);
         typename Tile<T>::vec16 pre[PRE_ROWS];
-        typename Tile<T>::vec16 pre_r[RES ? PRE_ROWS : 1];
         int tile = blockIdx.x;
         tile_load<T, CIN>(pre, x, g, tile);
-        if constexpr (RES) tile_load<T, CIN>(pre_r, in_res, g, tile);
-        if constexpr (XF == 1 || XF == 2) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4, g, tile, s_bn, a_out);
-        else tile_store<T, CIN>(pre, lds4, g);
+        tile_store<T, CIN>(pre, lds4, g);
         __syncthreads();
         for (int it = 0; tile < g.n_tiles; ++it, tile += gridDim.x) {
             const int next = tile + gridDim.x;
-            if (next < g.n_tiles) {
-                tile_load<T, CIN>(pre, x, g, next);
-                if constexpr (RES) tile_load<T, CIN>(pre_r, in_res, g, next);
-            }
+            if (next < g.n_tiles) tile_load<T, CIN>(pre, x, g, next);
             conv_tile<T, CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
-            if (next < g.n_tiles) {
-                if constexpr (XF == 1 || XF == 2) tile_store_bn<T, CIN, RES>(pre, pre_r, lds4 + ((it + 1) & 1) * buf_f4, g, next, s_bn, a_out);
-                else tile_store<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
-            }
+            if (next < g.n_tiles) tile_store<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
             __syncthreads();
         }
     } else {
@@ -566,9 +523,11 @@ static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const vo
     const int grid = conv_grid(g);
     // prefetching needs the whole tile in PRE_ROWS registers per thread, one column per thread, and more
     // than one tile per workgroup to pay off
-    bool fused_bwd = false;
-    if constexpr (EPI == 2) fused_bwd = e.bw_dout != nullptr;   // three tensors per element do not fit the prefetching path's registers
-    const int pipelined = (!fused_bwd && g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
+    bool transforming = false;   // batch norm applied while staging: no prefetching path
+    if constexpr (EPI == 1) transforming = e.in_sums != nullptr;
+    if constexpr (EPI == 2) transforming = e.bw_dout != nullptr;
+    const bool fused_bwd = EPI == 2 && transforming;
+    const int pipelined = (!transforming && g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
     size_t lds = input_lds_bytes<T, CIN>(g) * (pipelined ? 2 : 1);
     if ((EPI == 1 || EPI == 2) && lds < 1024) lds = 1024;  // per-wave partial sums
     auto kern = conv_kernel<T, CIN, MT, NW, EPI, 0>;
