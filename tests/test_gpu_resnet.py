@@ -47,6 +47,8 @@ def _grad_case(env, widths, blocks, hw, batch, classes=10, tol=1e-4):
     ((32, 32, 64), 1, 32, 2),
     ((16, 64, 64), 1, 16, 5),     # 16 -> 64 shortcut
     ((64, 64, 64), 1, 8, 9),
+    ((64, 64, 64), 1, 8, 67),     # weight gradient walks two tiles per workgroup (register prefetch), odd last tile
+    ((16, 32, 64), 1, 32, 67),    # the same on 32x32 images: 536 tiles of 128 pixels over 512 workgroups
 ])
 def test_gradients_small_nets(env, widths, blocks, hw, batch):
     _grad_case(env, widths, blocks, hw, batch)
