@@ -109,11 +109,13 @@ __device__ __forceinline__ typename Tile<T>::vec16 bn_relu16(typename Tile<T>::v
 // sit on (everything but the halo) also go to a_out, so that every pixel of the activation is written exactly once.
 template <typename T, int CIN, int THREADS, bool RES>
 __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ x, const T* __restrict__ res,
-                                               const ConvGeom& g, int tile, const float (*s_bn)[64], T* __restrict__ a_out) {
+                                               const ConvGeom& g, int tile, const float (*s_bn)[64], T* __restrict__ a_out,
+                                               int res_c, int res_lo, int res_stride) {
     typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = clog2(CQ);
     constexpr int R = 6;
+    const int res_h = g.h_in * res_stride;
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
     const int n_cols = g.lw * CQ;
@@ -123,6 +125,9 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
         const int wi = lc - g.pad;
         const bool wok = (unsigned)wi < (unsigned)g.h_in;
         const int64_t colo = (int64_t)(wok ? wi : 0) * CIN + cq * 4;
+        // the shortcut covers channels res_lo .. res_lo + res_c of x and is read at every res_stride-th pixel
+        const bool rch = RES && cq * 4 >= res_lo && cq * 4 < res_lo + res_c;
+        const int64_t rcolo = (int64_t)(wok ? wi : 0) * res_stride * res_c + (cq * 4 - res_lo);
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
         for (int r0 = 0; r0 < rows_total; r0 += R) {
             raw4 v[R], vr[R];
@@ -141,7 +146,7 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
                 v[r] = vr[r] = Act<T>::zero();
                 if (ok[r]) {
                     v[r] = Act<T>::load_raw(x + at[r]);
-                    if (RES) vr[r] = Act<T>::load_raw(res + at[r]);
+                    if (rch) vr[r] = Act<T>::load_raw(res + ((int64_t)n * res_h + (int64_t)hi * res_stride) * res_h * res_c + rcolo);
                 }
             }
 #pragma unroll
@@ -473,7 +478,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             if constexpr (XF == 3)
                 stage_input_bwd<T, CIN, NW * 64>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_out), static_cast<const T*>(e.bw_y), g,
                                                  tile, s_bn, e.bw_inv_count, static_cast<T*>(e.bw_dy_out), static_cast<T*>(e.bw_g_out));
-            else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out);
+            else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out, e.in_res_c, e.in_res_lo, e.in_res_stride);
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();
             conv_tile<T, CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);

@@ -136,7 +136,8 @@ struct ConvEpi {
     double in_count;
     float *in_mean, *in_invstd, *in_rmean, *in_rvar;
     const float *in_gamma, *in_beta;
-    const void* in_res;   // optional identity shortcut of x's shape, added before the ReLU (the end of a block)
+    const void* in_res;   // optional shortcut added before the ReLU (the end of a block): in_res_c channels that go to
+    int in_res_c, in_res_lo, in_res_stride;   // x's channels in_res_lo .. (zeros elsewhere), read at every in_res_stride-th pixel
     void* a_out;
     // input gradient with bw_dout != nullptr (stride-1 layers): the launch's input dy does not exist yet.  The kernel computes
     // it while staging, as bn_bwd_apply does, from the gradient bw_dout of the layer's activation bw_out, the layer's

@@ -195,7 +195,8 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
     // is applied by the next convolution while it stages its input, which also stores the activation for the backward
     // pass; `pending` is that layer, whose raw convolution output the next launch reads.
     int pending = -1;
-    const act_t* pending_res = nullptr;   // identity shortcut that goes with it (the end of a block), or nullptr
+    const act_t* pending_res = nullptr;   // shortcut that goes with it (the end of a block), or nullptr; its channels and stride
+    int pending_res_c = 0, pending_res_stride = 1;
     for (int l = 0; l < L; ++l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
@@ -217,6 +218,7 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
                 e.in_rmean = buffers + pb.rmean_off; e.in_rvar = buffers + pb.rvar_off;
                 e.in_gamma = params + pb.gamma_off; e.in_beta = params + pb.beta_off;
                 e.in_res = pending_res;
+                e.in_res_c = pending_res_c; e.in_res_lo = (pb.c_out - pending_res_c) / 2; e.in_res_stride = pending_res_stride;
                 e.a_out = s.a[pending];
                 x_in = s.y[pending];
                 pending = -1;
@@ -235,12 +237,13 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             cur = y;
             continue;
         }
-        // the next convolution can normalise on load when the shortcut to add, if any, is the identity (a block that keeps
-        // the shape)
-        const bool identity_res = is_conv2 && m->layers[l - 1].stride == 1 && m->layers[l - 1].c_in == cb.c_out;
-        if ((!is_conv2 || identity_res) && l + 1 < L && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
+        // the next convolution can normalise on load (adding the block's shortcut, identity or subsampled and zero-padded)
+        // when it reads all of this layer's channels
+        if (l + 1 < L && m->layers[l + 1].c_in == cb.c_out && cb.c_out <= 64) {
             pending = l;      // the next convolution writes s.a[l]
             pending_res = is_conv2 ? block_in : nullptr;
+            pending_res_c = is_conv2 ? m->layers[l - 1].c_in : 0;
+            pending_res_stride = is_conv2 ? m->layers[l - 1].stride : 1;
             cur = s.a[l];
             continue;
         }
