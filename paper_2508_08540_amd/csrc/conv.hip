@@ -623,8 +623,8 @@ int conv_fwd_tiles(const ConvShape& cs) {
 void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
                      const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
-    // normalise-on-load launches on the large images: taller tiles, fewer halo rows of the raw tensor (and its shortcut)
-    const int rows = (stats && stats->in_sums && cs.stride == 1 && h_out >= FWD_TALL_MIN_H) ? 8 : 0;
+    // normalise-on-load and inference launches on the large images: taller tiles, fewer halo rows re-read
+    const int rows = (stats && (stats->in_sums || stats->gamma) && cs.stride == 1 && h_out >= FWD_TALL_MIN_H) ? 8 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows);
     if (stats && stats->gamma) launch_conv_c<3>(s, act, cs.c_in, g, x, w, y, *stats, kt);
     else if (stats) launch_conv_c<1>(s, act, cs.c_in, g, x, w, y, *stats, kt);
