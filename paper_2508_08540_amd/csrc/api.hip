@@ -25,6 +25,7 @@ int bls_arena_reserve(bls_ctx* ctx, size_t bytes) {
     if (bytes <= ctx->arena_bytes) return BLS_OK;
     BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->aux) BLS_HIP(ctx, hipStreamSynchronize(ctx->aux));
+    if (ctx->aux2) BLS_HIP(ctx, hipStreamSynchronize(ctx->aux2));
     if (ctx->arena) BLS_HIP(ctx, hipFree(ctx->arena));
     ctx->arena = nullptr;
     ctx->arena_bytes = 0;
@@ -64,7 +65,9 @@ int bls_ctx_create(bls_ctx** out, int device, void* hip_stream) {
         ctx->max_lds = (size_t)optin;
     (void)hipGetLastError();
     if (hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess ||
+        hipStreamCreateWithFlags(&ctx->aux2, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->join_event, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->join_event2, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->head_event, hipEventDisableTiming) != hipSuccess) {
         delete ctx;
         return BLS_EHIP;
@@ -86,8 +89,13 @@ void bls_ctx_destroy(bls_ctx* ctx) {
         (void)hipStreamSynchronize(ctx->aux);
         (void)hipStreamDestroy(ctx->aux);
     }
+    if (ctx->aux2) {
+        (void)hipStreamSynchronize(ctx->aux2);
+        (void)hipStreamDestroy(ctx->aux2);
+    }
     for (hipEvent_t e : ctx->fork_events) (void)hipEventDestroy(e);
     if (ctx->join_event) (void)hipEventDestroy(ctx->join_event);
+    if (ctx->join_event2) (void)hipEventDestroy(ctx->join_event2);
     if (ctx->head_event) (void)hipEventDestroy(ctx->head_event);
     if (ctx->arena) (void)hipFree(ctx->arena);
     if (ctx->round_losses) (void)hipFree(ctx->round_losses);
