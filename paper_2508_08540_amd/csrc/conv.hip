@@ -660,7 +660,10 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 #define WGRAD_REPLICAS 8
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40: |dW| < 2^23, resolution 2^-40
 
-#define WGRAD_THREADS 256
+#ifndef WGRAD_THREADS
+#define WGRAD_THREADS 512
+#endif
+#define WG_WAVES (WGRAD_THREADS / 64)
 #ifndef WGRAD_GROUP_CAP
 #define WGRAD_GROUP_CAP 512
 #endif
@@ -669,7 +672,7 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 // loaded into registers while the current tile multiplies (tiles small enough for that, see wgrad_geom).
 #define WG_XK 4
 #define WG_DK 2
-#define WG_PIPE_PIXELS 128
+#define WG_PIPE_PIXELS (WGRAD_THREADS / 2)
 
 template <typename T, int TAPS, bool PIPE>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
@@ -767,7 +770,7 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
         if (w_out >= 4) {
             // a quad lies inside one output row: the waves take rows in turn and the row base is wave-uniform
             const int lane_x = grp * g.stride * CP + r16, lane_dy = grp * DP + r16;
-            for (int row = wave; row < g.rows_tile; row += 4) {
+            for (int row = wave; row < g.rows_tile; row += WG_WAVES) {
                 const int part = row >> g.rpi_log2, r = row & ((1 << g.rpi_log2) - 1);
                 const float* xr = lds_x + (part * g.in_rows + r * g.stride) * g.lw * CP + lane_x;
                 const float* dr = lds_dy + (row << g.wout_log2) * DP + lane_dy;
@@ -783,7 +786,7 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
                 }
             }
         } else {
-            for (int qd = wave; qd < tile_pixels / 4; qd += 4) {
+            for (int qd = wave; qd < tile_pixels / 4; qd += WG_WAVES) {
                 const int q = 4 * qd + grp;
                 const float a = lds_dy[q * DP + r16];
                 const int xb = pixel_lds_base<16, 0>(g, q) + r16;
@@ -806,7 +809,9 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
     // order-independent accumulation across pixel groups: replicated 64-bit fixed point, integer atomic add
     fixsum_t* out = gacc + ((int64_t)(blockIdx.x % replicas) * gridDim.y + blockIdx.y) * BLOCK_FLOATS;
     for (int e = threadIdx.x; e < BLOCK_FLOATS; e += WGRAD_THREADS) {
-        const float v = ((lds[e] + lds[BLOCK_FLOATS + e]) + lds[2 * BLOCK_FLOATS + e]) + lds[3 * BLOCK_FLOATS + e];
+        float v = lds[e];
+#pragma unroll
+        for (int wv = 1; wv < WG_WAVES; ++wv) v += lds[wv * BLOCK_FLOATS + e];
         atomicAdd(out + e, (fixsum_t)__double2ll_rn((double)v * FIX_WGRAD_SCALE));
     }
 }
@@ -920,7 +925,7 @@ static ConvGeom wgrad_geom(const ConvShape& cs) {
 
 static int wgrad_groups(const ConvShape& cs, int n_tiles) {
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    int cap = WGRAD_GROUP_CAP / blocks;
+    int cap = WGRAD_GROUP_CAP / blocks / (WG_WAVES / 4);
     if (cap < 1) cap = 1;
     return n_tiles < cap ? n_tiles : cap;
 }
@@ -948,8 +953,8 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
     const bool pipe = wgrad_fits_pipe(g) && tiles_per_group > 1;
     auto kern = pipe ? wgrad_kernel<T, TAPS, true> : wgrad_kernel<T, TAPS, false>;
+    if (lds < WG_WAVES * 16 * TAPS * 16 * sizeof(float)) lds = WG_WAVES * 16 * TAPS * 16 * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (lds < 4 * 16 * TAPS * 16 * sizeof(float)) lds = 4 * 16 * TAPS * 16 * sizeof(float);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
     hipExtLaunchKernelGGL(kern, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
                           kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out, groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS);
