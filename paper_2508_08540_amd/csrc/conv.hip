@@ -188,7 +188,7 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
     typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = clog2(CQ);
-    constexpr int R = 3;
+    constexpr int R = 5;   // the 10 rows of an 8-row tile in two rounds of loads
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
     const int n_cols = g.lw * CQ;
