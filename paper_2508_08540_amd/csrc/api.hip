@@ -65,7 +65,6 @@ int bls_ctx_create(bls_ctx** out, int device, void* hip_stream) {
         ctx->max_lds = (size_t)optin;
     (void)hipGetLastError();
     if (hipStreamCreateWithFlags(&ctx->aux, hipStreamNonBlocking) != hipSuccess ||
-        hipStreamCreateWithFlags(&ctx->aux2, hipStreamNonBlocking) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->join_event, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->join_event2, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->head_event, hipEventDisableTiming) != hipSuccess) {

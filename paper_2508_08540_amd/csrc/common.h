@@ -23,7 +23,7 @@ struct bls_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
     hipStream_t aux = nullptr;             // library-owned side stream for work off the critical path
-    hipStream_t aux2 = nullptr;            // a second one: ResNet weight gradients alternate between the two
+    hipStream_t aux2 = nullptr;            // a second one, created on first use: bf16 ResNet weight gradients alternate between the two
     std::vector<hipEvent_t> fork_events;   // main -> aux dependencies, one per use inside a call
     hipEvent_t join_event = nullptr;       // aux -> main
     hipEvent_t join_event2 = nullptr;      // aux2 -> main

@@ -278,6 +278,10 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         BLS_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
         ctx->fork_events.push_back(e);
     }
+    // the second side stream exists only where it is used: idle streams still take part in the mapping of streams to
+    // hardware queues and cost concurrent workers (lanes) 15 % of their throughput
+    const bool two_sides = s.act == ACT_BF16;
+    if (two_sides && !ctx->aux2) BLS_HIP(ctx, hipStreamCreateWithFlags(&ctx->aux2, hipStreamNonBlocking));
     const ConvBn& last = m->layers[L - 1];
     const void* dout = s.dfeat;
     int shared = last.h_out * last.h_out;
@@ -301,7 +305,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             // With bf16 storage the main stream's kernels are shorter than the weight gradients (which multiply in fp32), the
             // side stream is the long pole and neighbouring layers' weight gradients alternate between two streams; with
             // fp32 storage a third queue only slows the critical path (measured: +1.7 % per pass).
-            hipStream_t side = (s.act == ACT_BF16 && (l & 1)) ? ctx->aux2 : ctx->aux;
+            hipStream_t side = (two_sides && (l & 1)) ? ctx->aux2 : ctx->aux;
             BLS_HIP(ctx, hipStreamWaitEvent(side, ctx->fork_events[l], 0));
             PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(side, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt));
             return BLS_OK;
@@ -344,8 +348,10 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
     }
     BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
     BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
-    BLS_HIP(ctx, hipEventRecord(ctx->join_event2, ctx->aux2));
-    BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event2, 0));
+    if (two_sides) {
+        BLS_HIP(ctx, hipEventRecord(ctx->join_event2, ctx->aux2));
+        BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event2, 0));
+    }
     return BLS_OK;
 }
 
