@@ -661,7 +661,7 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40: |dW| < 2^23, resolution 2^-40
 
 #ifndef WGRAD_THREADS
-#define WGRAD_THREADS 256
+#define WGRAD_THREADS 512
 #endif
 #define WG_WAVES (WGRAD_THREADS / 64)
 #ifndef WGRAD_GROUP_CAP
