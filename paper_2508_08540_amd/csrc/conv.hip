@@ -617,6 +617,9 @@ int conv_fwd_tiles(const ConvShape& cs) {
     return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
 }
 
+#ifndef TALL_MIN_TILES
+#define TALL_MIN_TILES 256
+#endif
 #ifndef FWD_TALL_MIN_H
 #define FWD_TALL_MIN_H 32
 #endif
@@ -624,7 +627,8 @@ void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x,
                      const KernelTiming* kt) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     // normalise-on-load and inference launches on the large images: taller tiles, fewer halo rows re-read
-    const int rows = (stats && (stats->in_sums || stats->gamma) && cs.stride == 1 && h_out >= FWD_TALL_MIN_H) ? 8 : 0;
+    // (only while the launch keeps at least TALL_MIN_TILES workgroups)
+    const int rows = (stats && (stats->in_sums || stats->gamma) && cs.stride == 1 && h_out >= FWD_TALL_MIN_H && cs.B * h_out >= 8 * TALL_MIN_TILES) ? 8 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows);
     if (stats && stats->gamma) launch_conv_c<3>(s, act, cs.c_in, g, x, w, y, *stats, kt);
     else if (stats) launch_conv_c<1>(s, act, cs.c_in, g, x, w, y, *stats, kt);
@@ -641,7 +645,7 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
     int ups = cs.stride == 2 ? 1 : 0;
     // with the batch-norm backward in the staging three tensors are read per tile: taller tiles on the large images
     // (halo rows 2 in 10 instead of 2 in 6)
-    const int rows = (bn_below && bn_below->bw_dout && cs.h_in >= DGRAD_TALL_MIN_H) ? 8 : 0;
+    const int rows = (bn_below && bn_below->bw_dout && cs.h_in >= DGRAD_TALL_MIN_H && cs.B * cs.h_in >= 8 * TALL_MIN_TILES) ? 8 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in, rows);
     if (bn_below) launch_conv_c<2>(s, act, cs.c_out, g, dy, w, dx, *bn_below, kt);
     else launch_conv_c<0>(s, act, cs.c_out, g, dy, w, dx, ConvEpi{}, kt);
