@@ -22,10 +22,10 @@ sys.path.insert(0, ROOT)
 # 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
 MEASURED_TRAFFIC = {
     "wgrad_kernel": {"fetch_kib": 5266.7, "fetch_scale": 2.0, "write_kib": 4608.0, "write_scale": 1.0,
-                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "9632e4da09678b8d"},
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "8b326a228c1421c2"},
     # launch-weighted mean over the 18 input-gradient launches of a local step
     "conv_kernel (input-gradient launches)": {"fetch_kib": 14979.3, "fetch_scale": 2.0, "write_kib": 12224.2, "write_scale": 1.0,
-                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "9632e4da09678b8d"},
+                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "8b326a228c1421c2"},
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
