@@ -180,6 +180,16 @@ int score_losses(bls_ctx* ctx, const bls_model* model, const float* params, cons
  * 0 <= k <= N < 2^31; k == 0 is a no-op.  val_out[r] = losses[idx_out[r]] bit for bit. */
 int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out);
 
+/* topk_by_loss for callers that cannot allocate device memory (code under HIP graph capture, serving loops and harnesses
+ * that forbid hipMalloc): same arguments, same result bit for bit, and no allocation of any kind on the device.  Pools
+ * above 16384 losses work in a fixed array of 18 MiB that is part of the library's device image (every GPU the library
+ * runs on holds it until the process ends), which limits N to BLS_TOPK_STATIC_MAX_N; a larger N is BLS_EINVAL.  All calls
+ * on one GPU share that array: calls that overlap in time on one GPU (two contexts, two streams) race; calls in stream
+ * order on one stream do not.  Nothing in the array has to survive between calls, and the launches clear what they count
+ * in.  Its device address is looked up when a context is created on the GPU. */
+enum { BLS_TOPK_STATIC_MAX_N = 1 << 20 };
+int topk_by_loss_static(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out);
+
 /* tau mini-batch SGD updates on the selected samples (Algorithm 1, fast-worker branch).
  *   params, momentum  device float[d], updated in place; buffers device float[num_buffers],
  *                     updated in place (batch norm trains with batch statistics)

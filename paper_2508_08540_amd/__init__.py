@@ -6,6 +6,6 @@ package loads the library and fails loudly if it has not been built
 (`python -m paper_2508_08540_amd.build`).
 """
 from .binding import (  # noqa: F401
-    BlsError, Context, Model, lib, library_path, local_step, score_losses, topk_by_loss, weighted_aggregate,
+    BlsError, Context, Model, lib, library_path, local_step, score_losses, topk_by_loss, topk_by_loss_static, TOPK_STATIC_MAX_N, weighted_aggregate,
     weights_from_tau, sample_epoch, communication_round, epoch_allocation, worker_share, MODEL_MLP, MODEL_RESNET_CIFAR, MODEL_WRN, MODEL_ENCODER, AGG_NORMALISE, AGG_BROADCAST, DECLARED_SYMBOLS, PROFILE_CLASSES,
 )

@@ -15,8 +15,9 @@ DECLARED_SYMBOLS = (
     "bls_model_destroy", "bls_model_num_params", "bls_model_num_buffers", "bls_model_workspace_bytes", "bls_model_num_tensors",
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
-    "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes",
+    "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes", "topk_by_loss_static",
 )
+TOPK_STATIC_MAX_N = 1 << 20
 SAMPLING_SCHEMES = {"separated": 0, "unified": 1}
 HIGH_LOSS_TO = {"fast": 0, "slow": 1}
 PROFILE_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "norm", "head", "gemm", "update", "gather", "topk",
@@ -72,6 +73,7 @@ def _load():
     L.bls_model_tensor_layout.argtypes = [vp, C.POINTER(_TensorInfo), i32]
     L.score_losses.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
     L.topk_by_loss.argtypes = [vp, vp, i64, i64, vp, vp]
+    L.topk_by_loss_static.argtypes = [vp, vp, i64, i64, vp, vp]
     L.local_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i64, C.POINTER(_Sgd), vp]
     L.bls_epoch_allocation.argtypes = [i64, i64, C.c_int, i64, C.c_int, C.c_double, C.POINTER(i64), C.POINTER(i64),
                                        C.POINTER(i64)]
@@ -228,6 +230,12 @@ def score_losses(ctx, model, params, buffers, x, y, losses_out):
 
 def topk_by_loss(ctx, losses, k, idx_out, val_out=None):
     ctx.check(lib.topk_by_loss(ctx.handle, _ptr(losses), losses.shape[0], k, _ptr(idx_out), _ptr(val_out)))
+    return idx_out
+
+
+def topk_by_loss_static(ctx, losses, k, idx_out, val_out=None):
+    """topk_by_loss on the library's fixed device array: no allocation, N <= TOPK_STATIC_MAX_N."""
+    ctx.check(lib.topk_by_loss_static(ctx.handle, _ptr(losses), losses.shape[0], k, _ptr(idx_out), _ptr(val_out)))
     return idx_out
 
 

@@ -71,6 +71,10 @@ int bls_ctx_create(bls_ctx** out, int device, void* hip_stream) {
         delete ctx;
         return BLS_EHIP;
     }
+    if (topk_static_init(ctx) != BLS_OK) {
+        bls_ctx_destroy(ctx);
+        return BLS_EHIP;
+    }
     *out = ctx;
     return BLS_OK;
 }
@@ -400,6 +404,16 @@ int topk_by_loss(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_
     BLS_HIP(ctx, hipSetDevice(ctx->device));
     ProfScope prof(ctx, PROF_TOPK);
     return launch_topk(ctx, losses, N, k, idx_out, val_out);
+}
+
+int topk_by_loss_static(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
+    if (!ctx) return BLS_EINVAL;
+    if (N < 0 || k < 0 || k > N) return bls_fail(ctx, BLS_EINVAL, "topk_by_loss_static: need 0 <= k <= N (N=%lld, k=%lld)", (long long)N, (long long)k);
+    if (k == 0) return BLS_OK;
+    if (!losses || !idx_out) return bls_fail(ctx, BLS_EINVAL, "topk_by_loss_static: NULL pointer");
+    BLS_HIP(ctx, hipSetDevice(ctx->device));
+    ProfScope prof(ctx, PROF_TOPK);
+    return launch_topk_static(ctx, losses, N, k, idx_out, val_out);
 }
 
 int local_step(bls_ctx* ctx, const bls_model* model, float* params, float* buffers, float* momentum,

@@ -110,5 +110,8 @@ int launch_weighted_aggregate(bls_ctx* ctx, const float* const* replicas, const 
                               float* out, bool broadcast);
 size_t topk_scratch_bytes(int64_t N, int64_t k);
 int launch_topk(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out);
+// The same on the library's fixed device array (no allocation); topk_static_init looks its address up for ctx's device.
+int topk_static_init(bls_ctx* ctx);
+int launch_topk_static(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out);
 int launch_sample_epoch(bls_ctx* ctx, const float* losses, const float* u_biased, const float* u_other, int64_t N, int64_t n_biased,
                         int64_t k, int64_t n_other, int P_biased, int P_other, bool unified, int32_t* biased_out, int32_t* other_out);

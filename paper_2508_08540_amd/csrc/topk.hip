@@ -9,6 +9,8 @@
 // Small pools (N <= TOPK_LDS_MAX) are sorted by one workgroup entirely in LDS with a bitonic
 // network.  Larger pools take a multi-workgroup path: radix-select of the k-th word, ordered
 // compaction of the selected words, and an LSD radix sort of those k words.
+#include <mutex>
+
 #include "common.h"
 
 #define TOPK_LDS_MAX 16384
@@ -410,10 +412,9 @@ size_t topk_scratch_bytes(int64_t N, int64_t k) {
     return c.off;
 }
 
-static int launch_topk_large(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
-    int rc = bls_arena_reserve(ctx, topk_scratch_bytes(N, k));
-    if (rc != BLS_OK) return rc;
-    Carver c(ctx->arena);
+// `scratch_base`: topk_scratch_bytes(N, k) bytes of device memory, 256-byte aligned; nothing in it needs to be cleared.
+static int launch_topk_large(bls_ctx* ctx, char* scratch_base, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
+    Carver c(scratch_base);
     TopkScratch t = carve_topk(c, N);
     hipStream_t s = ctx->stream;
     const int nb = t.n_blocks, rb = t.r_blocks;
@@ -443,19 +444,58 @@ static int launch_topk_large(bls_ctx* ctx, const float* losses, int64_t N, int64
     return BLS_OK;
 }
 
+static int launch_topk_small(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
+    int M = 2;
+    while (M < N) M <<= 1;
+    size_t lds = (size_t)M * sizeof(uint64_t);
+    if (lds > ctx->max_lds) return bls_fail(ctx, BLS_EUNSUPPORTED, "top-k needs %zu bytes of LDS, device allows %zu", lds, ctx->max_lds);
+    if (lds > 65536)
+        BLS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(topk_lds_bitonic_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(topk_lds_bitonic_kernel, dim3(1), dim3(TOPK_THREADS), lds, ctx->stream, losses, (int)N, (int)k, M, idx_out,
+                       val_out);
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}
+
 int launch_topk(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
-    if (N <= TOPK_LDS_MAX) {
-        int M = 2;
-        while (M < N) M <<= 1;
-        size_t lds = (size_t)M * sizeof(uint64_t);
-        if (lds > ctx->max_lds) return bls_fail(ctx, BLS_EUNSUPPORTED, "top-k needs %zu bytes of LDS, device allows %zu", lds, ctx->max_lds);
-        if (lds > 65536)
-            BLS_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(topk_lds_bitonic_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(topk_lds_bitonic_kernel, dim3(1), dim3(TOPK_THREADS), lds, ctx->stream, losses, (int)N, (int)k,
-                           M, idx_out, val_out);
-        BLS_HIP(ctx, hipGetLastError());
-        return BLS_OK;
-    }
-    return launch_topk_large(ctx, losses, N, k, idx_out, val_out);
+    if (N <= TOPK_LDS_MAX) return launch_topk_small(ctx, losses, N, k, idx_out, val_out);
+    int rc = bls_arena_reserve(ctx, topk_scratch_bytes(N, k));
+    if (rc != BLS_OK) return rc;
+    return launch_topk_large(ctx, ctx->arena, losses, N, k, idx_out, val_out);
+}
+
+// ---- selection without any allocation -----------------------------------------------------------------
+//
+// The large-pool path above needs device scratch (histogram, block counts, digit tables and two pairs of key / index
+// arrays).  For callers that must not allocate, the same launches run on a fixed array in the library's device image.
+// Every GPU the library is loaded on holds its own copy of the array at its own address, for the life of the process.
+
+#define TOPK_STATIC_BYTES (size_t(18) << 20)   // >= topk_scratch_bytes(BLS_TOPK_STATIC_MAX_N, .), checked on every call
+#define TOPK_STATIC_MAX_DEVICES 64
+
+static __device__ __align__(256) unsigned char scratch[TOPK_STATIC_BYTES];
+
+// Device address of `scratch` per GPU (the array's name in host code is only a handle for the symbol lookup).
+static char* g_static_scratch[TOPK_STATIC_MAX_DEVICES];
+static std::mutex g_static_scratch_lock;
+
+int topk_static_init(bls_ctx* ctx) {
+    if (ctx->device < 0 || ctx->device >= TOPK_STATIC_MAX_DEVICES) return BLS_OK;   // topk_by_loss_static refuses such a device
+    std::lock_guard<std::mutex> hold(g_static_scratch_lock);
+    if (g_static_scratch[ctx->device]) return BLS_OK;
+    void* ptr = nullptr;
+    BLS_HIP(ctx, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));   // the context's device is current
+    if (!ptr) return bls_fail(ctx, BLS_EHIP, "no device address for the static top-k scratch");
+    g_static_scratch[ctx->device] = static_cast<char*>(ptr);
+    return BLS_OK;
+}
+
+int launch_topk_static(bls_ctx* ctx, const float* losses, int64_t N, int64_t k, int32_t* idx_out, float* val_out) {
+    if (N > BLS_TOPK_STATIC_MAX_N || topk_scratch_bytes(N, k) > TOPK_STATIC_BYTES)
+        return bls_fail(ctx, BLS_EINVAL, "topk_by_loss_static: N = %lld exceeds the limit of %d", (long long)N, BLS_TOPK_STATIC_MAX_N);
+    if (N <= TOPK_LDS_MAX) return launch_topk_small(ctx, losses, N, k, idx_out, val_out);
+    char* base = (ctx->device >= 0 && ctx->device < TOPK_STATIC_MAX_DEVICES) ? g_static_scratch[ctx->device] : nullptr;
+    if (!base) return bls_fail(ctx, BLS_EUNSUPPORTED, "topk_by_loss_static: no static scratch on device %d", ctx->device);
+    return launch_topk_large(ctx, base, losses, N, k, idx_out, val_out);
 }
