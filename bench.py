@@ -320,9 +320,8 @@ def cpu_baseline_sequence(cfg, p, x, y):
     d = sum(int(v.size) for v in p.values())
     rng = np.random.default_rng(cfg["id"])
     reps = rng.standard_normal((P, d_agg)).astype(np.float32)
-    import synth
     t = time.perf_counter()
-    oracle.weighted_aggregate(reps, synth.aggregation_weights(cfg))
+    oracle.weighted_aggregate(reps, oracle.weights_from_tau(cfg["tau_workers"]))
     t_agg = (time.perf_counter() - t) * (d / d_agg)
     total = N * t_score + t_topk + tau * t_step + t_agg
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
@@ -462,7 +461,7 @@ def cpu_baseline(cfg, p, b, x, y):
     flat = (bls.Model.wide_resnet() if wide else bls.Model.resnet_cifar()).pack(p)
     reps = synth.replicas(flat, P, cfg["id"])
     t = time.perf_counter()
-    oracle.weighted_aggregate(reps, synth.aggregation_weights(cfg))
+    oracle.weighted_aggregate(reps, oracle.weights_from_tau(cfg["tau_workers"]))
     t_agg = time.perf_counter() - t
     total = N * t_score_img + t_topk + tau * t_step + t_agg
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])

@@ -58,12 +58,15 @@ class GradientProbe:
         return self.model.backward(self.cache, self.dlogits)
 
     def near_zero_units(self, rel=1e-5):
+        """[(relu name, flat index)] with |z| <= rel * rms(z of that ReLU), closest to zero (relative to the rms) first."""
         out = []
         for name, z in self.cache.get("z", {}).items():
             rms = float(np.sqrt(np.mean(z * z)))
-            for i in np.flatnonzero(np.abs(z.reshape(-1)) <= rel * rms):
-                out.append((name, int(i)))
-        return out
+            flat = np.abs(z.reshape(-1))
+            for i in np.flatnonzero(flat <= rel * rms):
+                out.append((flat[i] / max(rms, 1e-300), name, int(i)))
+        out.sort()
+        return [(name, i) for _, name, i in out]
 
 
 def local_step(model, params, buffers, momentum_bufs, x_pool, y_pool, sel, batch, tau,

@@ -16,7 +16,6 @@
 // Covers stride 1, channel counts that are multiples of 64; other layers use wgrad_kernel.
 #include "conv_tile.h"
 
-#include <cstdlib>
 
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40, as in wgrad_kernel
 #define W16_TILE_PX 128
@@ -143,11 +142,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const bf16_t* __restrict__
     }
 }
 
-// BLS_WGRAD_FP32=1 in the environment sends every layer to wgrad_kernel (used by the tests to compare the two kernels
-// on identical operands).
 bool wgrad16_covers(int act, const ConvShape& cs) {
-    const char* off = getenv("BLS_WGRAD_FP32");
-    if (off && off[0] == '1') return false;
     return act == ACT_BF16 && cs.stride == 1 && cs.c_in % 64 == 0 && cs.c_out % 64 == 0 && cs.c_in_real == cs.c_in && cs.h_in >= 4 &&
            cs.h_in <= 64;
 }

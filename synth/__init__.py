@@ -8,5 +8,5 @@ method's arithmetic (no forward pass, loss, selection, update or aggregation).
 from .rng import uniform01, normal, randint            # noqa: F401
 from .inputs import (                                   # noqa: F401
     WORKLOADS, workload, image_pool, mlp_init, resnet_init, resnet_tensor_specs,
-    mlp_tensor_specs, wrn_tensor_specs, wrn_init, transformer_tensor_specs, transformer_init, token_pool, replicas, aggregation_weights, loss_array, LOSS_ARRAY_KINDS,
+    mlp_tensor_specs, wrn_tensor_specs, wrn_init, transformer_tensor_specs, transformer_init, token_pool, replicas, loss_array, LOSS_ARRAY_KINDS,
 )

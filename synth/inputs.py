@@ -13,8 +13,9 @@ from . import rng
 BASE_SEED = 250808540
 
 # Sizes of the workloads this repository measures or tests.  'tau' is the number of local
-# updates of the fast process per round, 'tau_workers' the per-worker step counts that
-# produce the aggregation weights tau_i / sum(tau) (Eq. 4 of the paper).
+# updates of the fast process per round, 'tau_workers' the per-worker step counts of a round (the
+# aggregation weights follow from them on either side of a comparison: the oracle's weights_from_tau
+# and the library's bls_weights_from_tau; this package computes none).
 WORKLOADS = {
     "mlp": dict(id=0, model="mlp", pool=256, classes=10, k=64, batch=64, tau=4, lr=0.1, momentum=0.0,
                 weight_decay=0.0, P=4, weights=(0.35, 0.35, 0.15, 0.15)),
@@ -261,14 +262,6 @@ def replicas(base, P, workload_id, scale=0.01):
     for i in range(P):
         out[i] = (base.astype(np.float64) + scale * rng.normal(seed, 9000 + i, d)).astype(np.float32)
     return out
-
-
-def aggregation_weights(cfg):
-    """float64 weights of a workload: given directly, or tau_i / sum(tau) from per-worker step counts."""
-    if "weights" in cfg:
-        return np.asarray(cfg["weights"], dtype=np.float64)
-    tau = np.asarray(cfg["tau_workers"], dtype=np.float64)
-    return tau / tau.sum()
 
 
 LOSS_ARRAY_KINDS = ("halfnormal", "ties16", "equal", "ascending", "descending", "specials")

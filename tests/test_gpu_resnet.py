@@ -40,6 +40,14 @@ def _grad_case(env, widths, blocks, hw, batch, classes=10, tol=1e-4):
     assert_tensors_close(gb, probe.new_buffers, 1e-5, "running statistics")
 
 
+@pytest.mark.parametrize("widths,hw", [((16, 16, 16), 32), ((32, 32, 32), 16), ((64, 64, 64), 8), ((16, 32, 64), 32)])
+def test_gradients_at_the_benchmarked_launch_geometry(env, widths, hw):
+    """Batch 128 on one-block nets of a single width: every convolution, batch-norm and weight-gradient launch has the grid,
+    tile height and tiles per workgroup of the corresponding ResNet20 stage at the benchmarked batch size (the last case:
+    the two widening stride-2 transitions as well), and every gradient tensor is held to the single-step tolerance."""
+    _grad_case(env, widths, 1, hw, 128)
+
+
 @pytest.mark.parametrize("widths,blocks,hw,batch", [
     ((16, 32, 64), 1, 8, 4),      # tiles spanning several images, ragged last tile
     ((16, 32, 64), 1, 16, 6),
@@ -130,13 +138,11 @@ def test_full_workload_configuration(env):
     _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, B, 1, lr=0.0, mu=0.9)
     assert_losses_close(sl[0], probe.losses)
     assert_tensors_close(gb, probe.new_buffers, 1e-5, "running statistics")
-    # At this size about two hundred ReLU units sit within rounding of zero, too many to search.  The
-    # tensors above the last two ReLUs depend on few of them and are held to the single-step tolerance;
-    # the rest were checked at that tolerance on smaller batches above and are bounded loosely here.
-    top = ["fc.weight", "fc.bias", "s3.b2.bn2.weight", "s3.b2.bn2.bias", "s3.b2.conv2.weight", "s3.b2.bn1.weight",
-           "s3.b2.bn1.bias", "s3.b2.conv1.weight"]
-    assert_grads_match_up_to_relu_ties(probe, mom, 1e-4, max_units=48, tensors=top, relus=["s3.b2.out", "s3.b2.h1"])
-    assert_tensors_close(mom, probe.grads(), 2e-2, "all gradients, ReLU ties not resolved")
+    # Every gradient tensor at the single-step tolerance.  At this size about two hundred of the 24 million ReLU units sit
+    # within 1e-5 rms of zero and a handful of them land on the other side of the kink in fp32; the helper identifies those
+    # by a least-squares fit over the per-unit effects and requires a match once the oracle takes the same decisions.
+    n_inverted = assert_grads_match_up_to_relu_ties(probe, mom, 1e-4)
+    assert n_inverted <= 16, n_inverted
     # tau steps at lr = 0: batch norm trains (statistics move) but the weights do not
     p2, b2, m2, sl2 = h.local_step(p, b, _zeros(p), x, y, sel, B, tau, lr=0.0, mu=0.0)
     assert np.isfinite(sl2).all()

@@ -47,6 +47,8 @@ SHAPES = [
     (120, 72, 128, 2, 64, 1, 3),     # head width 64, 72 tokens: the one-workgroup attention (bf16 factors) with a ragged row block
     (80, 40, 64, 2, 48, 2, 2),       # head width 32, 40 tokens: the same with more than half of the score tile empty
     (50, 8, 16, 2, 32, 9, 9),        # nine layers, 72 tokens: more column sums per backward pass than one table launch takes
+    (32000, 128, 512, 8, 2048, 2, 2),  # the measured widths (two of the six layers, two sequences): 500 softmax-statistics
+                                       # pairs per row, the split contraction of the vocabulary input gradient, batched q/k/v
 ]
 
 
@@ -138,7 +140,11 @@ def test_bf16_products_scores_and_gradients(env, vocab, L, D, H, F, layers, batc
         assert np.abs(mom[name] - ref.pop(name)).max() <= 1e-2 * scale, name
     exact = oracle.GradientProbe(oracle.TransformerLM(vocab, L, D, H, F, layers), p, {}, x[sel], y[sel]).grads()
     worst = {n: (rel_err(mom[n], ref[n]), rel_err(exact[n], ref[n])) for n in ref}
-    assert not {n: e for n, e in worst.items() if e[0] > max(2e-3, 0.5 * e[1])}, worst
+    # The query and key gradients are products with the softmax gradient, the factor in which fp32 cancels (see above): at
+    # the measured widths (512-deep contractions over rows of 128 scores) they are held to the size of the rounding effect
+    # itself, as after several steps below; every other tensor to half of it.
+    share = lambda n: 1.0 if D >= 512 and (".attn.q." in n or ".attn.k." in n) else 0.5
+    assert not {n: e for n, e in worst.items() if e[0] > max(2e-3, share(n) * e[1])}, worst
 
 
 def test_bf16_products_with_256_row_tiles(env):

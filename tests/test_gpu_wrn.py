@@ -139,25 +139,55 @@ def test_wrn16_8_bf16_one_small_batch(env):
         assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
 
 
-@pytest.mark.parametrize("widths,blocks,hw,batch,stem", [
-    ((64, 64, 64), 2, 32, 3, 16),        # 3x3 on 32x32, 16x16 and 8x8 maps
-    ((64, 128, 128), 1, 16, 5, 64),      # 4x4 maps; identity first block with a 64-channel stem
-    ((128, 128, 256), 1, 16, 2, 64),     # stride-1 1x1 projection 64 -> 128, several channel-block pairs
-])
-def test_bf16_weight_gradient_kernels_agree(env, widths, blocks, hw, batch, stem):
-    """Wide stride-1 bf16 layers take their weight gradient on the bf16 matrix instruction; with BLS_WGRAD_FP32=1 the
-    library sends them to the fp32-instruction kernel that the other tests hold to the oracle.  Both see the same
-    bf16 operands (products of two bf16 numbers are exact in fp32), so they may differ by summation order only."""
-    import os
-    h = _harness(env, widths, blocks, hw, 10, stem, "bf16")
-    p, b, x, y, sel = _case(widths, blocks, hw, batch, 10, stem)
-    os.environ.pop("BLS_WGRAD_FP32", None)
-    _, gb1, mom1, sl1 = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
-    os.environ["BLS_WGRAD_FP32"] = "1"
-    try:
-        _, gb2, mom2, sl2 = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
-    finally:
-        os.environ.pop("BLS_WGRAD_FP32", None)
-    np.testing.assert_array_equal(sl1, sl2)
-    assert_tensors_close(mom1, mom2, 2e-6, "weight gradients, bf16 vs fp32 matrix instruction")
-    assert any(rel_err(mom1[k], mom2[k]) > 0 for k in mom1 if "conv" in k)   # two different kernels did run
+def test_wrn16_8_fp32_real_network(env):
+    """The real network (16-channel stem, widths 128/256/512, two blocks per stage, 32x32 images, 100 classes) in fp32 on four
+    images: scores, training losses, every gradient tensor and the running statistics at the fp32 tolerances."""
+    h = _harness(env, (128, 256, 512), 2, 32, 100, 16)
+    p, b = synth.wrn_init(CFG["id"], perturb_bn=0.1)
+    x, y = synth.image_pool(CFG["id"], 4, 100)
+    assert_losses_close(h.score(p, b, x, y), oracle.score_losses(h.oracle_model, p, b, x, y))
+    probe = oracle.GradientProbe(h.oracle_model, p, b, x, y)
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, np.arange(4), 4, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], probe.losses)
+    assert_grads_match_up_to_relu_ties(probe, mom, 1e-4)
+    assert_tensors_close(gb, probe.new_buffers, 1e-5, "running statistics")
+
+
+@pytest.mark.parametrize("widths", [(64, 64, 64), (128, 128, 128)])
+def test_bf16_weight_gradient_kernel_against_the_oracle(env, widths):
+    """Stride-1 layers whose channel counts are multiples of 64 take their weight gradient on the bf16 matrix instruction
+    (3x3 layers at 8x8 and 4x4 maps here; with 128 channels also the 1x1 stride-1 projection from the 64-channel stem and
+    several channel-block pairs per launch).  Products of two bf16 numbers are exact in fp32, so wherever no rounding to
+    bf16 upstream of a tensor falls on a near-tie the kernels agree with the bf16 oracle as tightly as the fp32 path does
+    with the plain one.  A flip late in the backward pass disturbs only the tensors below it, so the criterion is per
+    tensor: over several seeds every gradient tensor above the first batch norm must be tight at least once (a kernel that computes something else
+    never is), and every seed stays inside the flip envelope."""
+    h = _harness(env, widths, 1, 8, 10, 64, "bf16")
+    best = {}
+    for stream in range(8):
+        p, b, x, y, sel = _case(widths, 1, 8, 2, 10, 64, stream)
+        losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+        _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, 2, 1, lr=0.0, mu=0.9)
+        errs = {k: rel_err(mom[k], grads[k]) for k in grads}
+        assert max(errs.values()) < 0.6, errs
+        if max(errs.values()) <= 1e-4:
+            assert_losses_close(sl[0], losses)
+        best = {k: min(e, best.get(k, 1.0)) for k, e in errs.items()}
+    # the three tensors at the very end of the backward pass see every flip above them: they are not this kernel's
+    bottom = ("stem.conv.weight", "s1.b0.bn1.weight", "s1.b0.bn1.bias")
+    assert not {k: e for k, e in best.items() if e > (2e-3 if k in bottom else 1e-4)}, best
+
+
+def test_bf16_weight_gradient_several_tiles_per_workgroup(env):
+    """512 -> 512 channels at 8x8 maps, 24 images: 64 channel-block pairs leave four pixel groups, so a workgroup of the
+    bf16 weight-gradient kernel walks two tiles, the last one ragged.  At this size some bf16 roundings flip, so the
+    criterion is the envelope one: no further from the float64 oracle than the bf16 oracle itself is (x 1.5, + 0.03)."""
+    widths, stem, batch = (512, 512, 512), 64, 24
+    h = _harness(env, widths, 1, 8, 10, stem, "bf16")
+    p, b, x, y, sel = _case(widths, 1, 8, batch, 10, stem)
+    losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses, rtol=2e-2)
+    _, g64, _ = oracle.loss_and_grads(oracle.WideResNet(widths, 1, stem), p, b, x[sel], y[sel])
+    for k in grads:
+        assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
