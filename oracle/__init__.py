@@ -18,3 +18,4 @@ from .precision import round_bf16                               # noqa: F401
 from .sampling import allocation, deal, sample_epoch                 # noqa: F401
 from .local_sgd import score_losses, local_step, loss_and_grads, GradientProbe  # noqa: F401
 from .round import communication_round                            # noqa: F401
+from .epoch import multistep_lr, rounds_per_epoch, train_epochs   # noqa: F401

@@ -8,6 +8,9 @@ Readings where the paper is silent: a worker keeps its own momentum buffers from
 and an output here); batch-norm running statistics are aggregated with the same weights as the parameters; a sample
 processed more than once in a round keeps the loss recorded last, in the order workers (as listed), steps, positions
 in the batch; a worker with tau_i = 0 neither trains nor counts.
+
+uniform_weights=True replaces Eq. (4) by the balanced average x_{t+1} = (1/m) sum_i x^i of Section 4.3 over the m
+workers that took part (the settings of the feature-wise evaluation without the aggregation bias).
 """
 import numpy as np
 
@@ -16,13 +19,13 @@ from .local_sgd import local_step
 
 
 def communication_round(model, global_params, global_buffers, workers, x_pool, y_pool, batch, lr, momentum=0.0,
-                        weight_decay=0.0, loss_table=None):
+                        weight_decay=0.0, loss_table=None, uniform_weights=False):
     """workers: list of dict(tau=int, idx=int array, momentum=dict of arrays).
 
     Returns (global_params, global_buffers, [momentum dict per worker], loss_table); inputs are not modified.
     """
     taus = [int(w["tau"]) for w in workers]
-    weights = weights_from_tau(taus)
+    weights = weights_from_tau([1 if t > 0 else 0 for t in taus]) if uniform_weights else weights_from_tau(taus)
     table = None if loss_table is None else np.array(loss_table, dtype=np.float64)
     new_p = {k: np.zeros_like(np.asarray(v, dtype=np.float64)) for k, v in global_params.items()}
     new_b = {k: np.zeros_like(np.asarray(v, dtype=np.float64)) for k, v in global_buffers.items()}

@@ -20,8 +20,10 @@ method above.  scheme "unified": the group that samples by loss goes first and t
 the remaining data, i.e. on exactly the N - N_biased samples the first group did not take, in the order of
 its random keys.  high_loss_to "slow" hands the high-loss samples to the slow workers instead: the slow
 allocation is the floor(lambda N_S) highest losses plus a uniform fill from the rest, and the fast workers
-draw uniformly (from all N, or from the remainder under "unified").  The unbiased baseline of that table is
-uniform sampling for both groups and needs no loss at all.
+draw uniformly (from all N, or from the remainder under "unified").  The unbiased baseline of that table (and the
+settings of the feature-wise evaluation that switch the sampling bias off) is uniform sampling for both groups and
+needs no loss at all: high_loss_to "none" has no by-loss part (k = 0), the fast workers draw their N_F samples by
+their keys and the slow workers theirs, independently ("separated") or from what the fast workers left ("unified").
 """
 import math
 
@@ -58,7 +60,7 @@ def _by_loss_then_uniform(losses, keys, n, k):
 def sample_epoch(losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, scheme="separated", high_loss_to="fast"):
     """Returns dict(fast=[P_f index arrays], slow=[P_s index arrays], n_fast, k, n_slow, fast_ranked, slow_ranked);
     k is the size of the by-loss part of the group named by high_loss_to."""
-    if scheme not in ("separated", "unified") or high_loss_to not in ("fast", "slow"):
+    if scheme not in ("separated", "unified") or high_loss_to not in ("fast", "slow", "none"):
         raise ValueError("unknown sampling variant")
     losses = np.asarray(losses, dtype=np.float32)
     u_fast = np.asarray(u_fast, dtype=np.float32)
@@ -67,7 +69,9 @@ def sample_epoch(losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, scheme="se
     n_fast, k, n_slow = allocation(N, tau_f, P_f, tau_s, P_s, lam)
     if high_loss_to == "slow":
         k = int(math.floor(float(lam) * float(n_slow)))
-    n_biased, u_biased, n_other, u_other = (n_fast, u_fast, n_slow, u_slow) if high_loss_to == "fast" else (n_slow, u_slow, n_fast, u_fast)
+    if high_loss_to == "none":
+        k = 0                                                        # nobody samples by loss; the fast group draws first
+    n_biased, u_biased, n_other, u_other = (n_slow, u_slow, n_fast, u_fast) if high_loss_to == "slow" else (n_fast, u_fast, n_slow, u_slow)
     biased = _by_loss_then_uniform(losses, u_biased, n_biased, k)
     if scheme == "separated":
         other = topk_by_loss(u_other, n_other).astype(np.int64)      # from all N, independent of the other group
@@ -76,6 +80,6 @@ def sample_epoch(losses, u_fast, u_slow, tau_f, P_f, tau_s, P_s, lam, scheme="se
         left[biased] = False
         left = np.flatnonzero(left)                                  # what the first group did not take
         other = left[topk_by_loss(u_other[left], n_other)].astype(np.int64)
-    fast_ranked, slow_ranked = (biased, other) if high_loss_to == "fast" else (other, biased)
+    fast_ranked, slow_ranked = (other, biased) if high_loss_to == "slow" else (biased, other)
     return dict(fast=deal(fast_ranked, P_f), slow=deal(slow_ranked, P_s), n_fast=n_fast, k=k, n_slow=n_slow,
                 fast_ranked=fast_ranked, slow_ranked=slow_ranked)
