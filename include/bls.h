@@ -236,11 +236,19 @@ typedef struct {
  *   loss_table  device float[N] or NULL: the loss of every processed sample is stored at its index (the loss-recording
  *               step of Algorithm 1); a sample processed more than once keeps the loss recorded last, in the order
  *               workers, steps, positions; other entries are left alone
+ * The weights are computed in double from the step counts and rounded once, as by bls_weights_from_tau.
  * The workers run one after the other on the context's stream, or side by side on the lanes set with bls_ctx_set_lanes
- * (the recorded losses and the aggregate are the same either way).  Errors as for local_step and weighted_aggregate. */
+ * (the recorded losses and the aggregate are the same either way).  Errors as for local_step and weighted_aggregate;
+ * workers that take a step must not share params, buffers or momentum storage with each other or with the global
+ * vectors (BLS_EINVAL).  flags: 0 or BLS_ROUND_UNIFORM_WEIGHTS. */
+enum {
+    BLS_ROUND_UNIFORM_WEIGHTS = 1 /* aggregate with the balanced average (1/m) sum_i x^i of Section 4.3 over the m workers
+                                     that took part instead of Eq. 4: the setting without the aggregation bias of the
+                                     appendix's feature-wise evaluation */
+};
 int communication_round(bls_ctx* ctx, const bls_model* model, float* global_params, float* global_buffers,
                         const bls_worker* workers, int P, const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch,
-                        const bls_sgd* opt, float* loss_table);
+                        const bls_sgd* opt, float* loss_table, int flags);
 
 /* ---- epoch sampler (Section 4.2; sampling steps at the top of every epoch of Algorithm 1) ------- */
 
@@ -274,12 +282,61 @@ int sample_epoch(bls_ctx* ctx, const float* losses, const float* u_fast, const f
  *   high_loss_to  BLS_HIGH_LOSS_TO_FAST: as sample_epoch.  BLS_HIGH_LOSS_TO_SLOW: the slow workers receive the
  *                 floor(lambda N_S) highest losses and a uniform fill from the rest (keys u_slow); the fast workers draw
  *                 uniformly by u_fast, from all N or, unified, from what the slow workers left.
- * Sizes, layout of the outputs, ties and errors as for sample_epoch, which is the (SEPARATED, TO_FAST) case. */
+ *                 BLS_HIGH_LOSS_TO_NONE: nobody samples by loss (the unbiased column of that table; the settings of the
+ *                 feature-wise evaluation without the sampling bias): the fast workers draw their N_F samples uniformly
+ *                 by u_fast, the slow workers their N_S by u_slow from all N or, unified, from what the fast workers
+ *                 left; losses may be NULL and lambda only has to be valid.
+ * Sizes, layout of the outputs, ties and errors as for sample_epoch, which is the (SEPARATED, TO_FAST) case.  Keys are
+ * finite; a key of -inf is treated as the lowest finite float (a sample already drawn is never drawn again). */
 enum { BLS_SAMPLING_SEPARATED = 0, BLS_SAMPLING_UNIFIED = 1 };
-enum { BLS_HIGH_LOSS_TO_FAST = 0, BLS_HIGH_LOSS_TO_SLOW = 1 };
+enum { BLS_HIGH_LOSS_TO_FAST = 0, BLS_HIGH_LOSS_TO_SLOW = 1, BLS_HIGH_LOSS_TO_NONE = 2 };
 int sample_epoch_variant(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f,
                          int P_f, int64_t tau_s, int P_s, double lambda, int scheme, int high_loss_to, int32_t* fast_idx_out,
                          int32_t* slow_idx_out);
+
+/* ---- the outer loop of Algorithm 1 on one GPU: E epochs of sampling and communication rounds ---------------------- */
+
+/* Settings of a run (the inputs of Algorithm 1 and the optimiser settings of Appendix A.1).
+ *   epochs      E >= 0
+ *   tau_f, P_f, tau_s, P_s, lambda, scheme, high_loss_to   as for sample_epoch_variant; the P_f fast workers come first
+ *   round_flags as for communication_round
+ *   batch       mini-batch size B
+ *   opt         opt.lr is the initial learning rate; momentum and weight decay are constant
+ *   milestones  host array of n_milestones epoch numbers (counted from 0); during epoch t the learning rate is
+ *               opt.lr * lr_gamma^(number of milestones <= t)  (the MultiStepLR schedule named in Appendix A.1) */
+typedef struct {
+    int64_t epochs;
+    int64_t tau_f;
+    int64_t tau_s;
+    int32_t P_f;
+    int32_t P_s;
+    double lambda;
+    int32_t scheme;
+    int32_t high_loss_to;
+    int32_t round_flags;
+    int32_t n_milestones;
+    int64_t batch;
+    bls_sgd opt;
+    float lr_gamma;
+    const int64_t* milestones;
+} bls_epoch_plan;
+
+/* Runs the epochs: at the top of epoch t the sampler assigns the fast and the slow workers their samples from the current
+ * loss table and the keys u_fast[t], u_slow[t]; round r then hands worker i the next tau_i * B samples of its share, the
+ * workers with a non-empty hand run communication_round (a shorter last hand still takes tau_i steps, its batches wrap
+ * around the hand; a worker whose share is used up sits the round out), and the epoch ends when every share is consumed.
+ *   global_params, global_buffers  device, in/out: the global model
+ *   worker_params  device float[P, d], worker_buffers device float[P, num_buffers] (NULL without buffers): replica storage
+ *   worker_momentum device float[P, d], in/out: every worker keeps its optimiser state across rounds and epochs
+ *   u_fast, u_slow device float[E, N]: the random keys of every epoch (finite; drawn by the caller)
+ *   loss_table     device float[N], in/out: the loss the sampler ranks (fill it before the first epoch, e.g. with
+ *                  score_losses); processed samples get their recorded loss
+ *   idx_work       device int32[N]: holds the epoch's assignment while its rounds run
+ *   rounds_out     host, may be NULL: number of communication rounds that were run
+ * P = P_f + P_s <= 64.  Everything is enqueued on the context's stream; errors as for the calls it is made of. */
+int train_epochs(bls_ctx* ctx, const bls_model* model, const bls_epoch_plan* plan, float* global_params, float* global_buffers,
+                 float* worker_params, float* worker_buffers, float* worker_momentum, const void* x_pool, const int32_t* y_pool,
+                 int64_t N, const float* u_fast, const float* u_slow, float* loss_table, int32_t* idx_work, int64_t* rounds_out);
 
 /* w_i = tau_i / sum_j tau_j (Eq. 4), computed in double and rounded once.  Host only. */
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out);

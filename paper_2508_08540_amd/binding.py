@@ -16,10 +16,12 @@ DECLARED_SYMBOLS = (
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
     "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes", "topk_by_loss_static",
+    "train_epochs",
 )
+ROUND_UNIFORM_WEIGHTS = 1
 TOPK_STATIC_MAX_N = 1 << 20
 SAMPLING_SCHEMES = {"separated": 0, "unified": 1}
-HIGH_LOSS_TO = {"fast": 0, "slow": 1}
+HIGH_LOSS_TO = {"fast": 0, "slow": 1, "none": 2}
 PROFILE_CLASSES = ("conv_fwd", "conv_dgrad", "conv_wgrad", "norm", "head", "gemm", "update", "gather", "topk",
                    "aggregate", "wgrad_reduce")
 
@@ -42,6 +44,13 @@ class _TensorInfo(C.Structure):
 
 class _Sgd(C.Structure):
     _fields_ = [("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float)]
+
+
+class _EpochPlan(C.Structure):
+    _fields_ = [("epochs", C.c_int64), ("tau_f", C.c_int64), ("tau_s", C.c_int64), ("P_f", C.c_int32), ("P_s", C.c_int32),
+                ("lam", C.c_double), ("scheme", C.c_int32), ("high_loss_to", C.c_int32), ("round_flags", C.c_int32),
+                ("n_milestones", C.c_int32), ("batch", C.c_int64), ("opt", _Sgd), ("lr_gamma", C.c_float),
+                ("milestones", C.POINTER(C.c_int64))]
 
 
 def library_path():
@@ -80,7 +89,8 @@ def _load():
     L.bls_worker_share.argtypes = [i64, C.c_int, C.c_int, C.POINTER(i64), C.POINTER(i64)]
     L.sample_epoch.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, vp, vp]
     L.bls_ctx_set_lanes.argtypes = [vp, C.c_int]
-    L.communication_round.argtypes = [vp, vp, vp, vp, vp, C.c_int, vp, vp, i64, i64, vp, vp]
+    L.communication_round.argtypes = [vp, vp, vp, vp, vp, C.c_int, vp, vp, i64, i64, vp, vp, C.c_int]
+    L.train_epochs.argtypes = [vp, vp, C.POINTER(_EpochPlan), vp, vp, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp, C.POINTER(i64)]
     L.sample_epoch_variant.argtypes = [vp, vp, vp, vp, i64, i64, C.c_int, i64, C.c_int, C.c_double, C.c_int, C.c_int, vp, vp]
     L.weighted_aggregate.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_float), C.c_int, i64, vp, C.c_int]
     L.bls_weights_from_tau.argtypes = [C.POINTER(i64), C.c_int, C.POINTER(C.c_float)]
@@ -292,7 +302,7 @@ class _Worker(C.Structure):
 
 
 def communication_round(ctx, model, global_params, global_buffers, workers, x_pool, y_pool, batch, lr, mu=0.0, weight_decay=0.0,
-                        loss_table=None):
+                        loss_table=None, flags=0):
     """workers: list of dict(tau, idx, params, buffers, momentum) of device tensors (buffers may be None)."""
     arr = (_Worker * len(workers))()
     for i, w in enumerate(workers):
@@ -300,7 +310,21 @@ def communication_round(ctx, model, global_params, global_buffers, workers, x_po
         arr[i] = _Worker(int(w["tau"]), addr(w["idx"]), w["idx"].shape[0], addr(w["params"]), addr(w.get("buffers")), addr(w["momentum"]))
     opt = _Sgd(lr, mu, weight_decay)
     ctx.check(lib.communication_round(ctx.handle, model.handle, _ptr(global_params), _ptr(global_buffers), arr, len(workers),
-                                      _ptr(x_pool), _ptr(y_pool), x_pool.shape[0], batch, C.byref(opt), _ptr(loss_table)))
+                                      _ptr(x_pool), _ptr(y_pool), x_pool.shape[0], batch, C.byref(opt), _ptr(loss_table), flags))
+
+
+def train_epochs(ctx, model, global_params, global_buffers, worker_params, worker_buffers, worker_momentum, x_pool, y_pool, u_fast, u_slow,
+                 loss_table, idx_work, epochs, tau_f, P_f, tau_s, P_s, lam, batch, lr, mu=0.0, weight_decay=0.0, milestones=(), lr_gamma=0.1,
+                 scheme="separated", high_loss_to="fast", round_flags=0):
+    """The outer loop of Algorithm 1 on device tensors; returns the number of communication rounds that were run."""
+    ms = (C.c_int64 * max(len(milestones), 1))(*[int(m) for m in milestones])
+    plan = _EpochPlan(int(epochs), int(tau_f), int(tau_s), int(P_f), int(P_s), float(lam), SAMPLING_SCHEMES[scheme], HIGH_LOSS_TO[high_loss_to],
+                      int(round_flags), len(milestones), int(batch), _Sgd(lr, mu, weight_decay), float(lr_gamma), ms)
+    rounds = C.c_int64()
+    ctx.check(lib.train_epochs(ctx.handle, model.handle, C.byref(plan), _ptr(global_params), _ptr(global_buffers), _ptr(worker_params),
+                               _ptr(worker_buffers), _ptr(worker_momentum), _ptr(x_pool), _ptr(y_pool), x_pool.shape[0], _ptr(u_fast),
+                               _ptr(u_slow), _ptr(loss_table), _ptr(idx_work), C.byref(rounds)))
+    return rounds.value
 
 
 def weights_from_tau(tau):

@@ -494,18 +494,20 @@ int bls_worker_share(int64_t n, int P, int p, int64_t* offset, int64_t* count) {
 int sample_epoch_variant(bls_ctx* ctx, const float* losses, const float* u_fast, const float* u_slow, int64_t N, int64_t tau_f, int P_f,
                          int64_t tau_s, int P_s, double lambda, int scheme, int high_loss_to, int32_t* fast_idx_out, int32_t* slow_idx_out) {
     if (!ctx) return BLS_EINVAL;
-    if ((scheme != BLS_SAMPLING_SEPARATED && scheme != BLS_SAMPLING_UNIFIED) || (high_loss_to != BLS_HIGH_LOSS_TO_FAST && high_loss_to != BLS_HIGH_LOSS_TO_SLOW))
+    if ((scheme != BLS_SAMPLING_SEPARATED && scheme != BLS_SAMPLING_UNIFIED) ||
+        (high_loss_to != BLS_HIGH_LOSS_TO_FAST && high_loss_to != BLS_HIGH_LOSS_TO_SLOW && high_loss_to != BLS_HIGH_LOSS_TO_NONE))
         return bls_fail(ctx, BLS_EINVAL, "sample_epoch_variant: unknown scheme or group");
     int64_t nf, k, ns;
     if (bls_epoch_allocation(N, tau_f, P_f, tau_s, P_s, lambda, &nf, &k, &ns) != BLS_OK)
         return bls_fail(ctx, BLS_EINVAL, "sample_epoch: need 0 <= N < 2^31, 1 <= tau_F, 0 <= tau_S, 1 <= P_F, 0 <= P_S, 0 < lambda <= 1");
     if (ns > 0 && P_s < 1) return bls_fail(ctx, BLS_EINVAL, "sample_epoch: slow samples but no slow worker");
     if (N == 0) return BLS_OK;
-    const bool to_fast = high_loss_to == BLS_HIGH_LOSS_TO_FAST;
+    const bool to_fast = high_loss_to != BLS_HIGH_LOSS_TO_SLOW;   // without a by-loss part the fast group still draws first
     if (!to_fast) k = (int64_t)floor(lambda * (double)ns);   // the by-loss part of the slow allocation
+    if (high_loss_to == BLS_HIGH_LOSS_TO_NONE) k = 0;
     const int64_t n_biased = to_fast ? nf : ns, n_other = to_fast ? ns : nf;
     const float *u_biased = to_fast ? u_fast : u_slow, *u_other = to_fast ? u_slow : u_fast;
-    if (!losses || (n_biased > k && !u_biased) || (n_other > 0 && !u_other) || (nf > 0 && !fast_idx_out) || (ns > 0 && !slow_idx_out))
+    if ((k > 0 && !losses) || (n_biased > k && !u_biased) || (n_other > 0 && !u_other) || (nf > 0 && !fast_idx_out) || (ns > 0 && !slow_idx_out))
         return bls_fail(ctx, BLS_EINVAL, "sample_epoch: NULL pointer");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
     ProfScope prof(ctx, PROF_TOPK);
@@ -528,25 +530,43 @@ __global__ __launch_bounds__(256) void record_losses_kernel(const int32_t* __res
     for (int64_t e = first + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) table[idx[e % n_idx]] = losses[e];
 }
 
+// True when [a, a + na) and [b, b + nb) floats share an address.
+static bool ranges_overlap(const float* a, int64_t na, const float* b, int64_t nb) {
+    if (!a || !b || na <= 0 || nb <= 0) return false;
+    return a < b + nb && b < a + na;
+}
+
 int communication_round(bls_ctx* ctx, const bls_model* model, float* global_params, float* global_buffers, const bls_worker* workers, int P,
-                        const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch, const bls_sgd* opt, float* loss_table) {
+                        const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch, const bls_sgd* opt, float* loss_table, int flags) {
     if (!ctx) return BLS_EINVAL;
     if (!model || !opt || !workers || !global_params) return bls_fail(ctx, BLS_EINVAL, "communication_round: NULL pointer");
     if (P < 1 || P > 64 || batch < 1 || batch > 65536) return bls_fail(ctx, BLS_EINVAL, "communication_round: need 1 <= P <= 64, 1 <= batch <= 65536");
+    if (flags & ~BLS_ROUND_UNIFORM_WEIGHTS) return bls_fail(ctx, BLS_EINVAL, "communication_round: unknown flag");
     if (model->num_buffers > 0 && !global_buffers) return bls_fail(ctx, BLS_EINVAL, "communication_round: this model needs buffers");
-    double tau_sum = 0.0;
+    const bool uniform = (flags & BLS_ROUND_UNIFORM_WEIGHTS) != 0;
+    const int64_t d = model->num_params, nb = model->num_buffers;
+    double weight_sum = 0.0;
     int64_t total = 0;
     for (int i = 0; i < P; ++i) {
         const bls_worker& w = workers[i];
         if (w.tau < 0 || w.tau > (int64_t(1) << 20)) return bls_fail(ctx, BLS_EINVAL, "communication_round: tau of worker %d out of range", i);
         if (w.tau == 0) continue;
-        if (!w.idx || w.n_idx < 1 || !w.params || !w.momentum || (model->num_buffers > 0 && !w.buffers))
+        if (!w.idx || w.n_idx < 1 || !w.params || !w.momentum || (nb > 0 && !w.buffers))
             return bls_fail(ctx, BLS_EINVAL, "communication_round: worker %d lacks samples or storage", i);
-        if (w.params == global_params) return bls_fail(ctx, BLS_EINVAL, "communication_round: worker %d trains in the global vector", i);
-        tau_sum += (double)w.tau;
+        if (ranges_overlap(w.params, d, global_params, d) || ranges_overlap(w.momentum, d, global_params, d) ||
+            ranges_overlap(w.params, d, w.momentum, d) || ranges_overlap(w.buffers, nb, global_buffers, nb))
+            return bls_fail(ctx, BLS_EINVAL, "communication_round: storage of worker %d overlaps the global model or itself", i);
+        for (int j = 0; j < i; ++j) {
+            const bls_worker& v = workers[j];
+            if (v.tau == 0) continue;
+            if (ranges_overlap(w.params, d, v.params, d) || ranges_overlap(w.params, d, v.momentum, d) || ranges_overlap(w.momentum, d, v.params, d) ||
+                ranges_overlap(w.momentum, d, v.momentum, d) || ranges_overlap(w.buffers, nb, v.buffers, nb))
+                return bls_fail(ctx, BLS_EINVAL, "communication_round: workers %d and %d share storage", j, i);
+        }
+        weight_sum += uniform ? 1.0 : (double)w.tau;
         total += w.tau * batch;
     }
-    if (!(tau_sum > 0.0)) return bls_fail(ctx, BLS_EINVAL, "communication_round: no worker takes a step");
+    if (!(weight_sum > 0.0)) return bls_fail(ctx, BLS_EINVAL, "communication_round: no worker takes a step");
     BLS_HIP(ctx, hipSetDevice(ctx->device));
     if (loss_table && (size_t)total > ctx->round_losses_count) {
         BLS_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -576,16 +596,15 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
         bls_ctx* lane = n_lanes > 0 ? ctx->lanes[n_trained % n_lanes] : ctx;
         if (lane != ctx) BLS_HIP(ctx, hipStreamWaitEvent(lane->stream, ctx->round_start, 0));
         // every worker starts the round from the global model (the aggregate of the previous round)
-        BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)model->num_params * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
-        if (model->num_buffers > 0)
-            BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)model->num_buffers * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
+        BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
+        if (nb > 0) BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)nb * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
         int rc = local_step(lane, model, w.params, w.buffers, w.momentum, x_pool, y_pool, N, w.idx, w.n_idx, batch, w.tau, opt,
                             loss_table ? ctx->round_losses + off : nullptr);
         if (rc != BLS_OK) return lane == ctx ? rc : bls_fail(ctx, rc, "communication_round: worker %d: %s", i, lane->error.c_str());
         if (lane != ctx) BLS_HIP(ctx, hipEventRecord(ctx->lane_events[n_trained], lane->stream));
         trained[n_trained] = w.params;
         trained_buffers[n_trained] = w.buffers;
-        weights[n_trained] = (float)((double)w.tau / tau_sum);
+        weights[n_trained] = (float)((uniform ? 1.0 : (double)w.tau) / weight_sum);   // Eq. 4 in double, rounded once
         loss_off[n_trained] = off;
         off += w.tau * batch;
         ++n_trained;
@@ -604,11 +623,75 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
             ++t;
         }
     }
-    int rc = weighted_aggregate(ctx, trained, weights, n_trained, model->num_params, global_params, BLS_AGG_NORMALISE);
+    int rc = weighted_aggregate(ctx, trained, weights, n_trained, d, global_params, 0);
     if (rc != BLS_OK) return rc;
-    if (model->num_buffers > 0) rc = weighted_aggregate(ctx, trained_buffers, weights, n_trained, model->num_buffers, global_buffers, BLS_AGG_NORMALISE);
+    if (nb > 0) rc = weighted_aggregate(ctx, trained_buffers, weights, n_trained, nb, global_buffers, 0);
     if (rc != BLS_OK) return rc;
     BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}
+
+int train_epochs(bls_ctx* ctx, const bls_model* model, const bls_epoch_plan* plan, float* global_params, float* global_buffers,
+                 float* worker_params, float* worker_buffers, float* worker_momentum, const void* x_pool, const int32_t* y_pool, int64_t N,
+                 const float* u_fast, const float* u_slow, float* loss_table, int32_t* idx_work, int64_t* rounds_out) {
+    if (!ctx) return BLS_EINVAL;
+    if (rounds_out) *rounds_out = 0;
+    if (!model || !plan) return bls_fail(ctx, BLS_EINVAL, "train_epochs: model or plan is NULL");
+    const int P = plan->P_f + plan->P_s;
+    if (plan->epochs < 0 || plan->P_f < 1 || plan->P_s < 0 || P > 64 || plan->batch < 1 || plan->n_milestones < 0 ||
+        (plan->n_milestones > 0 && !plan->milestones) || !isfinite(plan->lr_gamma) || !isfinite(plan->opt.lr))
+        return bls_fail(ctx, BLS_EINVAL, "train_epochs: need epochs >= 0, 1 <= P_f, 0 <= P_s, P_f + P_s <= 64, batch >= 1 and a finite schedule");
+    int64_t nf = 0, k = 0, ns = 0;
+    if (bls_epoch_allocation(N, plan->tau_f, plan->P_f, plan->tau_s, plan->P_s, plan->lambda, &nf, &k, &ns) != BLS_OK)
+        return bls_fail(ctx, BLS_EINVAL, "train_epochs: allocation arguments out of range (see bls_epoch_allocation)");
+    if (plan->epochs == 0 || N == 0) return BLS_OK;
+    if (!global_params || !worker_params || !worker_momentum || !x_pool || !y_pool || !loss_table || !idx_work ||
+        (model->num_buffers > 0 && (!global_buffers || !worker_buffers)))
+        return bls_fail(ctx, BLS_EINVAL, "train_epochs: NULL pointer");
+    const int64_t d = model->num_params, nb = model->num_buffers;
+    // worker p's share of its group's list and the rounds needed to consume it at tau * batch samples per round
+    int64_t share_off[64], share_len[64], tau[64], rounds = 0;
+    for (int p = 0; p < P; ++p) {
+        const bool fast = p < plan->P_f;
+        int64_t off = 0, cnt = 0;
+        bls_worker_share(fast ? nf : ns, fast ? plan->P_f : plan->P_s, fast ? p : p - plan->P_f, &off, &cnt);
+        share_off[p] = (fast ? 0 : nf) + off;
+        share_len[p] = cnt;
+        tau[p] = fast ? plan->tau_f : plan->tau_s;
+        if (tau[p] > 0 && cnt > 0) {
+            const int64_t per_round = tau[p] * plan->batch, need = (cnt + per_round - 1) / per_round;
+            if (need > rounds) rounds = need;
+        }
+    }
+    int64_t rounds_run = 0;
+    for (int64_t e = 0; e < plan->epochs; ++e) {
+        int reached = 0;
+        for (int m = 0; m < plan->n_milestones; ++m)
+            if (plan->milestones[m] <= e) ++reached;
+        bls_sgd opt = plan->opt;
+        opt.lr = (float)((double)plan->opt.lr * pow((double)plan->lr_gamma, (double)reached));
+        int rc = sample_epoch_variant(ctx, loss_table, u_fast ? u_fast + e * N : nullptr, u_slow ? u_slow + e * N : nullptr, N, plan->tau_f, plan->P_f,
+                                      plan->tau_s, plan->P_s, plan->lambda, plan->scheme, plan->high_loss_to, idx_work, idx_work + nf);
+        if (rc != BLS_OK) return rc;
+        for (int64_t r = 0; r < rounds; ++r) {
+            bls_worker ws[64];
+            for (int p = 0; p < P; ++p) {
+                const int64_t per_round = tau[p] * plan->batch, start = r * per_round;
+                const int64_t hand = tau[p] > 0 && start < share_len[p] ? (share_len[p] - start < per_round ? share_len[p] - start : per_round) : 0;
+                ws[p].tau = hand > 0 ? tau[p] : 0;
+                ws[p].idx = idx_work + share_off[p] + start;
+                ws[p].n_idx = hand;
+                ws[p].params = worker_params + (int64_t)p * d;
+                ws[p].buffers = nb > 0 ? worker_buffers + (int64_t)p * nb : nullptr;
+                ws[p].momentum = worker_momentum + (int64_t)p * d;
+            }
+            rc = communication_round(ctx, model, global_params, global_buffers, ws, P, x_pool, y_pool, N, plan->batch, &opt, loss_table,
+                                     plan->round_flags);
+            if (rc != BLS_OK) return rc;
+            ++rounds_run;
+        }
+    }
+    if (rounds_out) *rounds_out = rounds_run;
     return BLS_OK;
 }
 

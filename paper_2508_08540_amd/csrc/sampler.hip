@@ -4,9 +4,14 @@
 // expressed by overwriting the keys of the already selected samples with -inf before that top-m.
 #include "common.h"
 
-__global__ __launch_bounds__(256) void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+// Copy of the caller's keys that the exclusion below writes into.  Keys are finite by contract; a key of -inf is lifted
+// to the lowest finite value so that it still ranks above the struck entries and a struck sample is never drawn again.
+__global__ __launch_bounds__(256) void copy_keys_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float v = src[i];
+        dst[i] = v == -INFINITY ? -3.402823466e38f : v;
+    }
 }
 
 __global__ __launch_bounds__(256) void exclude_selected_kernel(const int32_t* __restrict__ sel, int64_t k, float* __restrict__ keys) {
@@ -54,9 +59,13 @@ int launch_sample_epoch(bls_ctx* ctx, const float* losses, const float* u_biased
             if (rc != BLS_OK) return rc;
         }
         if (n_biased > k) {
-            hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_biased, keys, N);
-            if (k > 0) hipLaunchKernelGGL(exclude_selected_kernel, dim3(blocks_for(k)), dim3(256), 0, s, ranked, k, keys);
-            rc = launch_topk(ctx, keys, N, n_biased - k, ranked + k, nullptr);
+            const float* from = u_biased;   // nothing to strike when no sample was taken by loss
+            if (k > 0) {
+                hipLaunchKernelGGL(copy_keys_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_biased, keys, N);
+                hipLaunchKernelGGL(exclude_selected_kernel, dim3(blocks_for(k)), dim3(256), 0, s, ranked, k, keys);
+                from = keys;
+            }
+            rc = launch_topk(ctx, from, N, n_biased - k, ranked + k, nullptr);
             if (rc != BLS_OK) return rc;
         }
         hipLaunchKernelGGL(deal_kernel, dim3(blocks_for(n_biased)), dim3(256), 0, s, ranked, n_biased, P_biased, biased_out);
@@ -64,7 +73,7 @@ int launch_sample_epoch(bls_ctx* ctx, const float* losses, const float* u_biased
     if (n_other > 0) {
         const float* from = u_other;
         if (unified && n_biased > 0) {
-            hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_other, keys, N);
+            hipLaunchKernelGGL(copy_keys_kernel, dim3(blocks_for(N)), dim3(256), 0, s, u_other, keys, N);
             hipLaunchKernelGGL(exclude_selected_kernel, dim3(blocks_for(n_biased)), dim3(256), 0, s, ranked, n_biased, keys);
             from = keys;
         }

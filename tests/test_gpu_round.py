@@ -22,7 +22,7 @@ def _zeros(p):
     return {k: np.zeros_like(v, dtype=np.float64) for k, v in p.items()}
 
 
-def _round(env, model, omodel, p, b, x, y, workers, batch, lr, mu, wd, N):
+def _round(env, model, omodel, p, b, x, y, workers, batch, lr, mu, wd, N, uniform=False):
     """Runs the round on both sides; workers: list of (tau, idx, momentum dict)."""
     torch, bls, ctx = env
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -34,10 +34,10 @@ def _round(env, model, omodel, p, b, x, y, workers, batch, lr, mu, wd, N):
     for tau, idx, mom in workers:
         dws.append(dict(tau=tau, idx=dev(np.asarray(idx, np.int32)), params=torch.full_like(gp, 7.0),
                         buffers=torch.full_like(gb, 7.0) if gb is not None else None, momentum=dev(model.pack(mom))))
-    bls.communication_round(ctx, model, gp, gb, dws, dev(x), dev(y), batch, lr, mu, wd, table)
+    bls.communication_round(ctx, model, gp, gb, dws, dev(x), dev(y), batch, lr, mu, wd, table, flags=bls.ROUND_UNIFORM_WEIGHTS if uniform else 0)
     ctx.synchronize()
     ref_p, ref_b, ref_m, ref_t = oracle.communication_round(omodel, p, b, [dict(tau=t, idx=i, momentum=m) for t, i, m in workers], x, y,
-                                                            batch, lr, mu, wd, loss_table=table0)
+                                                            batch, lr, mu, wd, loss_table=table0, uniform_weights=uniform)
     got_p = model.unpack(gp.cpu().numpy())
     got_b = model.unpack(gb.cpu().numpy(), buffers=True) if gb is not None else {}
     got_m = [model.unpack(w["momentum"].cpu().numpy()) for w in dws]
@@ -76,7 +76,9 @@ def test_mlp_round_with_wraparound_overlap_and_an_idle_worker(env):
     _compare(p, *out, workers, 1e-4)
 
 
-def test_resnet_round_aggregates_running_statistics_too(env):
+@pytest.mark.parametrize("uniform", [False, True])
+def test_resnet_round_aggregates_running_statistics_too(env, uniform):
+    # uniform: the balanced average of Section 4.3 instead of Eq. (4) (unequal step counts, so the two differ)
     torch, bls, ctx = env
     cfg = synth.workload("resnet20_fp32")
     widths, blocks, hw, N = (16, 16, 32), 1, 8, 24
@@ -84,7 +86,7 @@ def test_resnet_round_aggregates_running_statistics_too(env):
     p, b = synth.resnet_init(cfg["id"], widths, blocks, 10, perturb_bn=0.1)
     x, y = synth.image_pool(cfg["id"], N, 10, hw=hw)
     workers = [(2, np.arange(0, 8), _zeros(p)), (1, np.arange(8, 16), _zeros(p)), (3, np.arange(12, 24), _zeros(p))]
-    out = _round(env, model, omodel, p, b, x, y, workers, 4, 0.05, 0.9, 0.0, N)
+    out = _round(env, model, omodel, p, b, x, y, workers, 4, 0.05, 0.9, 0.0, N, uniform)
     _compare(p, *out, workers, 2e-3)
 
 
@@ -101,6 +103,12 @@ def test_rejected_arguments(env):
         bls.communication_round(ctx, model, gp, None, [dict(w, params=gp)], x, y, 2, 0.1)      # would train in the global vector
     with pytest.raises(bls.BlsError):
         bls.communication_round(ctx, model, gp, None, [w] * 65, x, y, 2, 0.1)                  # more workers than the aggregation takes
+    with pytest.raises(bls.BlsError):
+        bls.communication_round(ctx, model, gp, None, [w, dict(w)], x, y, 2, 0.1)              # two workers in the same storage
+    with pytest.raises(bls.BlsError):
+        bls.communication_round(ctx, model, gp, None, [dict(w, momentum=w["params"])], x, y, 2, 0.1)   # momentum inside the replica
+    with pytest.raises(bls.BlsError):
+        bls.communication_round(ctx, model, gp, None, [w], x, y, 2, 0.1, flags=8)              # unknown flag
 
 
 def test_workers_side_by_side_give_the_same_bits(env):

@@ -114,7 +114,8 @@ def _check_variant(env, losses, uf, us, tf, pf, ts, ps, lam, scheme, to):
     return fast.cpu().numpy()[:nf], slow.cpu().numpy()[:ns]
 
 
-@pytest.mark.parametrize("scheme,to", [("separated", "fast"), ("unified", "fast"), ("separated", "slow"), ("unified", "slow")])
+@pytest.mark.parametrize("scheme,to", [("separated", "fast"), ("unified", "fast"), ("separated", "slow"), ("unified", "slow"),
+                                       ("separated", "none"), ("unified", "none")])
 @pytest.mark.parametrize("N,tf,pf,ts,ps,lam", [
     (8, 3, 1, 1, 1, 0.5), (257, 32, 8, 1, 2, 0.25), (5000, 3, 7, 2, 5, 1.0), (5000, 3, 7, 2, 5, 0.001), (16385, 32, 8, 16, 2, 0.3),
     (50000, 32, 8, 1, 2, 0.5), (40000, 2, 2, 0, 0, 0.5),
@@ -135,8 +136,17 @@ def test_variants_with_special_losses_tied_keys_and_bad_arguments(env):
     uf = np.round(_keys(5, 1, N) * 8).astype(np.float32) / 8
     us = np.zeros(N, dtype=np.float32)
     for scheme in ("separated", "unified"):
-        for to in ("fast", "slow"):
+        for to in ("fast", "slow", "none"):
             _check_variant(env, losses, uf, us, 32, 8, 4, 2, 0.5, scheme, to)
+    # a key of -inf (outside the contract) still never lets a struck sample be drawn twice
+    bad = _keys(6, 1, N).copy()
+    bad[::3] = -np.inf
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    nf, _, ns = bls.epoch_allocation(N, 32, 8, 4, 2, 0.5)
+    fast, slow = torch.empty(nf, dtype=torch.int32, device="cuda"), torch.empty(ns, dtype=torch.int32, device="cuda")
+    bls.sample_epoch(ctx, dev(losses), dev(bad), dev(bad), 32, 8, 4, 2, 0.5, fast, slow, scheme="unified", high_loss_to="fast")
+    ctx.synchronize()
+    assert np.array_equal(np.sort(np.concatenate([fast.cpu().numpy(), slow.cpu().numpy()])), np.arange(N))
     z = torch.zeros(4, dtype=torch.float32, device="cuda")
     o = torch.zeros(4, dtype=torch.int32, device="cuda")
     with pytest.raises(bls.BlsError):
