@@ -96,6 +96,8 @@ def main():
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the workload step, time top-k and aggregation stand-alone over a range of sizes")
+    ap.add_argument("--round-mode", default=None, choices=["sequential", "2 lanes", "4 lanes", "8 lanes", "batched"],
+                    help="with --round: time only this way of running the workers (for profiles)")
     ap.add_argument("--round", action="store_true",
                     help="instead of the workload step, time communication_round (8 ResNet20 workers, 20 steps of 128 each) "
                          "with 1, 2, 4 and 8 workers side by side")
@@ -105,7 +107,7 @@ def main():
     if args.sweep:
         return sweep()
     if args.round:
-        return round_lanes()
+        return round_lanes(args.round_mode)
 
     import numpy as np
     import torch
@@ -390,7 +392,7 @@ def sweep():
     print(json.dumps(out))
 
 
-def round_lanes():
+def round_lanes(only=None):
     """One communication round of 8 fast workers (ResNet20 fp32, tau = 20, batch 128, 2560 samples each, loss table kept),
     timed with the workers one after the other and 2, 4, 8 side by side; one JSON line, samples/s over all workers."""
     import numpy as np
@@ -412,9 +414,12 @@ def round_lanes():
     ws = [dict(tau=tau, idx=torch.arange(i * per, (i + 1) * per, dtype=torch.int32, device="cuda"), params=torch.empty_like(gp0),
                buffers=torch.empty_like(gb0), momentum=torch.zeros_like(gp0)) for i in range(P)]
     out = {"metric": "communication round, samples/s over 8 ResNet20 workers", "unit": "samples/s", "tau": tau, "batch": B, "workers": P,
-           "lanes": []}
+           "modes": []}
     ref = None
-    for lanes in (1, 2, 4, 8):
+    # the workers one after the other, side by side on 2 / 4 / 8 streams, and side by side inside the kernels (the default)
+    for name, lanes, flags in (("sequential", 1, bls.ROUND_SEQUENTIAL), ("2 lanes", 2, 0), ("4 lanes", 4, 0), ("8 lanes", 8, 0), ("batched", 1, 0)):
+        if only is not None and name != only:
+            continue
         ctx.set_lanes(lanes)
         times = []
         for rep in range(4):
@@ -423,13 +428,13 @@ def round_lanes():
                 w["momentum"].zero_()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            bls.communication_round(ctx, model, gp, gb, ws, dx, dy, B, cfg["lr"], cfg["momentum"], cfg["weight_decay"], table)
+            bls.communication_round(ctx, model, gp, gb, ws, dx, dy, B, cfg["lr"], cfg["momentum"], cfg["weight_decay"], table, flags=flags)
             torch.cuda.synchronize()
             times.append(time.perf_counter() - t0)
         t = min(times[1:])
         same = True if ref is None else bool(torch.equal(ref, gp))
         ref = gp.clone() if ref is None else ref
-        out["lanes"].append({"lanes": lanes, "ms": round(1e3 * t, 2), "samples/s": round(P * per / t, 1), "same_bits_as_one_lane": same})
+        out["modes"].append({"mode": name, "ms": round(1e3 * t, 2), "samples/s": round(P * per / t, 1), "same_bits_as_sequential": same})
     ctx.set_lanes(1)
     print(json.dumps(out))
 

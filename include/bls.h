@@ -237,14 +237,19 @@ typedef struct {
  *               step of Algorithm 1); a sample processed more than once keeps the loss recorded last, in the order
  *               workers, steps, positions; other entries are left alone
  * The weights are computed in double from the step counts and rounded once, as by bls_weights_from_tau.
- * The workers run one after the other on the context's stream, or side by side on the lanes set with bls_ctx_set_lanes
- * (the recorded losses and the aggregate are the same either way).  Errors as for local_step and weighted_aggregate;
+ * The workers are the parallel loop of Algorithm 1.  For RESNET_CIFAR models (and no lanes set) they run side by side
+ * inside the kernels: one launch per layer covers every worker that still has steps to take, each worker in a scratch
+ * slot of its own (bls_model_workspace_bytes(model, batch, 1) plus two parameter vectors per worker).  Otherwise they run
+ * one after the other on the context's stream, or on the lanes set with bls_ctx_set_lanes.  The recorded losses, the
+ * replicas and the aggregate are the same bits on every path.  Errors as for local_step and weighted_aggregate;
  * workers that take a step must not share params, buffers or momentum storage with each other or with the global
- * vectors (BLS_EINVAL).  flags: 0 or BLS_ROUND_UNIFORM_WEIGHTS. */
+ * vectors (BLS_EINVAL).  flags: 0 or a sum of BLS_ROUND_* values. */
 enum {
-    BLS_ROUND_UNIFORM_WEIGHTS = 1 /* aggregate with the balanced average (1/m) sum_i x^i of Section 4.3 over the m workers
-                                     that took part instead of Eq. 4: the setting without the aggregation bias of the
-                                     appendix's feature-wise evaluation */
+    BLS_ROUND_UNIFORM_WEIGHTS = 1, /* aggregate with the balanced average (1/m) sum_i x^i of Section 4.3 over the m workers
+                                      that took part instead of Eq. 4: the setting without the aggregation bias of the
+                                      appendix's feature-wise evaluation */
+    BLS_ROUND_SEQUENTIAL = 2       /* run the workers one after the other even where the library could run them side by side
+                                      in one launch per layer (one scratch slot instead of one per worker; same results) */
 };
 int communication_round(bls_ctx* ctx, const bls_model* model, float* global_params, float* global_buffers,
                         const bls_worker* workers, int P, const void* x_pool, const int32_t* y_pool, int64_t N, int64_t batch,

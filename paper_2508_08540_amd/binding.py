@@ -18,7 +18,7 @@ DECLARED_SYMBOLS = (
     "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes", "topk_by_loss_static",
     "train_epochs",
 )
-ROUND_UNIFORM_WEIGHTS = 1
+ROUND_UNIFORM_WEIGHTS, ROUND_SEQUENTIAL = 1, 2
 TOPK_STATIC_MAX_N = 1 << 20
 SAMPLING_SCHEMES = {"separated": 0, "unified": 1}
 HIGH_LOSS_TO = {"fast": 0, "slow": 1, "none": 2}

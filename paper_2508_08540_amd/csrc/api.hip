@@ -541,7 +541,14 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
     if (!ctx) return BLS_EINVAL;
     if (!model || !opt || !workers || !global_params) return bls_fail(ctx, BLS_EINVAL, "communication_round: NULL pointer");
     if (P < 1 || P > 64 || batch < 1 || batch > 65536) return bls_fail(ctx, BLS_EINVAL, "communication_round: need 1 <= P <= 64, 1 <= batch <= 65536");
-    if (flags & ~BLS_ROUND_UNIFORM_WEIGHTS) return bls_fail(ctx, BLS_EINVAL, "communication_round: unknown flag");
+    if (flags & ~(BLS_ROUND_UNIFORM_WEIGHTS | BLS_ROUND_SEQUENTIAL)) return bls_fail(ctx, BLS_EINVAL, "communication_round: unknown flag");
+    for (int i = 0; i < P; ++i)   // local_step's own checks, made here once for every path
+        if (workers[i].tau > 0 && (N < 1 || N >= (int64_t(1) << 31) || !x_pool || !y_pool))
+            return bls_fail(ctx, BLS_EINVAL, "communication_round: need a pool of 1 <= N < 2^31 samples");
+    if (!(isfinite(opt->lr) && isfinite(opt->momentum) && isfinite(opt->weight_decay)))
+        return bls_fail(ctx, BLS_EINVAL, "communication_round: non-finite optimiser setting");
+    if (model->desc.kind != BLS_MODEL_MLP && model->desc.kind != BLS_MODEL_ENCODER && batch * model->final_hw * model->final_hw < 2)
+        return bls_fail(ctx, BLS_EINVAL, "communication_round: batch norm needs more than one value per channel");
     if (model->num_buffers > 0 && !global_buffers) return bls_fail(ctx, BLS_EINVAL, "communication_round: this model needs buffers");
     const bool uniform = (flags & BLS_ROUND_UNIFORM_WEIGHTS) != 0;
     const int64_t d = model->num_params, nb = model->num_buffers;
@@ -583,7 +590,6 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
         BLS_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
         ctx->lane_events.push_back(e);
     }
-    if (n_lanes > 0) BLS_HIP(ctx, hipEventRecord(ctx->round_start, ctx->stream));   // the global model is ready
     const float* trained[64];
     const float* trained_buffers[64];
     float weights[64];
@@ -593,21 +599,37 @@ int communication_round(bls_ctx* ctx, const bls_model* model, float* global_para
     for (int i = 0; i < P; ++i) {
         const bls_worker& w = workers[i];
         if (w.tau == 0) continue;
-        bls_ctx* lane = n_lanes > 0 ? ctx->lanes[n_trained % n_lanes] : ctx;
-        if (lane != ctx) BLS_HIP(ctx, hipStreamWaitEvent(lane->stream, ctx->round_start, 0));
-        // every worker starts the round from the global model (the aggregate of the previous round)
-        BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
-        if (nb > 0) BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)nb * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
-        int rc = local_step(lane, model, w.params, w.buffers, w.momentum, x_pool, y_pool, N, w.idx, w.n_idx, batch, w.tau, opt,
-                            loss_table ? ctx->round_losses + off : nullptr);
-        if (rc != BLS_OK) return lane == ctx ? rc : bls_fail(ctx, rc, "communication_round: worker %d: %s", i, lane->error.c_str());
-        if (lane != ctx) BLS_HIP(ctx, hipEventRecord(ctx->lane_events[n_trained], lane->stream));
         trained[n_trained] = w.params;
         trained_buffers[n_trained] = w.buffers;
         weights[n_trained] = (float)((uniform ? 1.0 : (double)w.tau) / weight_sum);   // Eq. 4 in double, rounded once
         loss_off[n_trained] = off;
         off += w.tau * batch;
         ++n_trained;
+    }
+    // Networks with a batched path run all workers in one launch per layer (the same kernels on the same data per worker,
+    // hence the same bits as one after the other); it needs one scratch slot per worker.
+    const bool batched = n_lanes == 0 && !(flags & BLS_ROUND_SEQUENTIAL) && n_trained >= 2 && net_round_batched_covers(model);
+    if (batched) {
+        int rc = net_round_batched(ctx, model, global_params, global_buffers, workers, P, static_cast<const float*>(x_pool), y_pool, batch, *opt,
+                                   loss_table ? ctx->round_losses : nullptr, loss_off);
+        if (rc != BLS_OK) return rc;
+    } else {
+        if (n_lanes > 0) BLS_HIP(ctx, hipEventRecord(ctx->round_start, ctx->stream));   // the global model is ready
+        int t = 0;
+        for (int i = 0; i < P; ++i) {
+            const bls_worker& w = workers[i];
+            if (w.tau == 0) continue;
+            bls_ctx* lane = n_lanes > 0 ? ctx->lanes[t % n_lanes] : ctx;
+            if (lane != ctx) BLS_HIP(ctx, hipStreamWaitEvent(lane->stream, ctx->round_start, 0));
+            // every worker starts the round from the global model (the aggregate of the previous round)
+            BLS_HIP(ctx, hipMemcpyAsync(w.params, global_params, (size_t)d * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
+            if (nb > 0) BLS_HIP(ctx, hipMemcpyAsync(w.buffers, global_buffers, (size_t)nb * sizeof(float), hipMemcpyDeviceToDevice, lane->stream));
+            int rc = local_step(lane, model, w.params, w.buffers, w.momentum, x_pool, y_pool, N, w.idx, w.n_idx, batch, w.tau, opt,
+                                loss_table ? ctx->round_losses + loss_off[t] : nullptr);
+            if (rc != BLS_OK) return lane == ctx ? rc : bls_fail(ctx, rc, "communication_round: worker %d: %s", i, lane->error.c_str());
+            if (lane != ctx) BLS_HIP(ctx, hipEventRecord(ctx->lane_events[t], lane->stream));
+            ++t;
+        }
     }
     if (n_lanes > 0)
         for (int t = 0; t < n_trained; ++t) BLS_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->lane_events[t], 0));

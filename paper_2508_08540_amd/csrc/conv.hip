@@ -242,6 +242,19 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
     }
 }
 
+// The epilogue's pointers as replica blockIdx.z sees them (`ro` bytes further).
+__device__ __forceinline__ void epi_at(ConvEpi& e, int64_t ro) {
+    e.sums = rep_at(e.sums, ro); e.sc_g = rep_at(e.sc_g, ro); e.a_prev = rep_at(e.a_prev, ro); e.y_prev = rep_at(e.y_prev, ro);
+    e.mean_prev = rep_at(e.mean_prev, ro); e.invstd_prev = rep_at(e.invstd_prev, ro); e.gamma = rep_at(e.gamma, ro); e.beta = rep_at(e.beta, ro);
+    e.in_sums = rep_at(e.in_sums, ro); e.in_mean = rep_at(e.in_mean, ro); e.in_invstd = rep_at(e.in_invstd, ro);
+    e.in_rmean = rep_at(e.in_rmean, ro); e.in_rvar = rep_at(e.in_rvar, ro); e.in_gamma = rep_at(e.in_gamma, ro); e.in_beta = rep_at(e.in_beta, ro);
+    e.in_res = rep_at(e.in_res, ro); e.a_out = rep_at(e.a_out, ro);
+    e.bw_dout = rep_at(e.bw_dout, ro); e.bw_out = rep_at(e.bw_out, ro); e.bw_y = rep_at(e.bw_y, ro); e.bw_mean = rep_at(e.bw_mean, ro);
+    e.bw_invstd = rep_at(e.bw_invstd, ro); e.bw_gamma = rep_at(e.bw_gamma, ro); e.bw_sums = rep_at(e.bw_sums, ro);
+    e.bw_dgamma = rep_at(e.bw_dgamma, ro); e.bw_dbeta = rep_at(e.bw_dbeta, ro); e.bw_dy_out = rep_at(e.bw_dy_out, ro);
+    e.bw_g_out = rep_at(e.bw_g_out, ro);
+}
+
 template <typename T, int CIN, int MT, int NW, int EPI>
 __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restrict__ lds4, const typename Tile<T>::quad (&wr)[9][CIN / 16],
                                           T* __restrict__ y, const ConvEpi& e, const ConvGeom& g, int tile, f32x4& ssum, f32x4& ssq) {
@@ -392,8 +405,13 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
 // input dy is computed while staging, by the layer's batch-norm backward (ConvEpi::bw_dout and the fields after it).
 template <typename T, int CIN, int MT, int NW, int EPI, int XF>
 __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
-                                                            T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined) {
+                                                            T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined, int64_t rstride) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        x = rep_at(x, ro); w = rep_at(w, ro); y = rep_at(y, ro);
+        epi_at(e, ro);
+    }
     typedef typename Tile<T>::quad quad;
     __shared__ float s_bn[XF == 3 ? 5 : XF ? 4 : 1][64];
     if constexpr (XF == 3) {
@@ -523,7 +541,7 @@ static int conv_grid(const ConvGeom& g) { return g.n_tiles < CONV_GRID_CAP ? g.n
 
 template <typename T, int CIN, int EPI>
 static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const void* w, T* y, const ConvEpi& e,
-                          const KernelTiming* kt) {
+                          const KernelTiming* kt, Reps reps) {
     constexpr int MT = CONV_MT, NW = CONV_NW;
     const int grid = conv_grid(g);
     // prefetching needs the whole tile in PRE_ROWS registers per thread, one column per thread, and more
@@ -544,25 +562,25 @@ static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const vo
     }
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)
-    hipExtLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), lds, s, kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, w, y, e, g,
-                          pipelined);
+    hipExtLaunchKernelGGL(kern, dim3(grid, 1, reps.n), dim3(NW * 64), lds, s, kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, w, y, e, g,
+                          pipelined, reps.stride);
 }
 
 template <typename T, int EPI>
 static void launch_conv_ct(hipStream_t s, int c_in, const ConvGeom& g, const void* x, const void* w, void* y, const ConvEpi& e,
-                           const KernelTiming* kt) {
+                           const KernelTiming* kt, Reps reps) {
     switch (c_in) {
-        case 16: launch_conv_t<T, 16, EPI>(s, g, (const T*)x, w, (T*)y, e, kt); break;
-        case 32: launch_conv_t<T, 32, EPI>(s, g, (const T*)x, w, (T*)y, e, kt); break;
-        default: launch_conv_t<T, 64, EPI>(s, g, (const T*)x, w, (T*)y, e, kt); break;
+        case 16: launch_conv_t<T, 16, EPI>(s, g, (const T*)x, w, (T*)y, e, kt, reps); break;
+        case 32: launch_conv_t<T, 32, EPI>(s, g, (const T*)x, w, (T*)y, e, kt, reps); break;
+        default: launch_conv_t<T, 64, EPI>(s, g, (const T*)x, w, (T*)y, e, kt, reps); break;
     }
 }
 
 template <int EPI>
 static void launch_conv_c(hipStream_t s, int act, int c_in, const ConvGeom& g, const void* x, const void* w, void* y, const ConvEpi& e,
-                          const KernelTiming* kt) {
-    if (act == ACT_BF16) launch_conv_ct<bf16_t, EPI>(s, c_in, g, x, w, y, e, kt);
-    else launch_conv_ct<float, EPI>(s, c_in, g, x, w, y, e, kt);
+                          const KernelTiming* kt, Reps reps) {
+    if (act == ACT_BF16) launch_conv_ct<bf16_t, EPI>(s, c_in, g, x, w, y, e, kt, reps);
+    else launch_conv_ct<float, EPI>(s, c_in, g, x, w, y, e, kt, reps);
 }
 
 // ---- weight packing -----------------------------------------------------------------------------------
@@ -576,7 +594,9 @@ static void launch_conv_c(hipStream_t s, int act, int c_in, const ConvGeom& g, c
 
 template <typename T>
 __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restrict__ params, typename Tile<T>::quad* __restrict__ packed,
-                                                           PackTable tab) {
+                                                           PackTable tab, int64_t rstride) {
+    params = rep_at(params, (int64_t)blockIdx.z * rstride);
+    packed = rep_at(packed, (int64_t)blockIdx.z * rstride);
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // quad index
     if (i >= tab.total_vec4) return;
     int l = 0;
@@ -606,10 +626,10 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const float* __restri
     Act<T>::store4(reinterpret_cast<T*>(packed + i), v);
 }
 
-void launch_pack_weights(hipStream_t s, int act, const float* params, void* packed, const PackTable& tab) {
+void launch_pack_weights(hipStream_t s, int act, const float* params, void* packed, const PackTable& tab, Reps reps) {
     int64_t blocks = (tab.total_vec4 + 255) / 256;
-    ACT_DISPATCH(act, hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, params,
-                                         (typename Tile<T>::quad*)packed, tab));
+    ACT_DISPATCH(act, hipLaunchKernelGGL(pack_weights_kernel<T>, dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, params,
+                                         (typename Tile<T>::quad*)packed, tab, reps.stride));
 }
 
 int conv_fwd_tiles(const ConvShape& cs) {
@@ -624,22 +644,22 @@ int conv_fwd_tiles(const ConvShape& cs) {
 #define FWD_TALL_MIN_H 32
 #endif
 void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
-                     const KernelTiming* kt) {
+                     const KernelTiming* kt, Reps reps) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
     // normalise-on-load and inference launches on the large images: taller tiles, fewer halo rows re-read
     // (only while the launch keeps at least TALL_MIN_TILES workgroups)
     const int rows = (stats && (stats->in_sums || stats->gamma) && cs.stride == 1 && h_out >= FWD_TALL_MIN_H && cs.B * h_out >= 8 * TALL_MIN_TILES) ? 8 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows);
-    if (stats && stats->gamma) launch_conv_c<3>(s, act, cs.c_in, g, x, w, y, *stats, kt);
-    else if (stats) launch_conv_c<1>(s, act, cs.c_in, g, x, w, y, *stats, kt);
-    else launch_conv_c<0>(s, act, cs.c_in, g, x, w, y, ConvEpi{}, kt);
+    if (stats && stats->gamma) launch_conv_c<3>(s, act, cs.c_in, g, x, w, y, *stats, kt, reps);
+    else if (stats) launch_conv_c<1>(s, act, cs.c_in, g, x, w, y, *stats, kt, reps);
+    else launch_conv_c<0>(s, act, cs.c_in, g, x, w, y, ConvEpi{}, kt, reps);
 }
 
 #ifndef DGRAD_TALL_MIN_H
 #define DGRAD_TALL_MIN_H 16
 #endif
 void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
-                       const KernelTiming* kt) {
+                       const KernelTiming* kt, Reps reps) {
     // The gradient with respect to the input is a stride-1 convolution whose input channels are the
     // layer's output channels and whose output channels are the layer's input channels.
     int ups = cs.stride == 2 ? 1 : 0;
@@ -647,8 +667,8 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
     // (halo rows 2 in 10 instead of 2 in 6)
     const int rows = (bn_below && bn_below->bw_dout && cs.h_in >= DGRAD_TALL_MIN_H && cs.B * cs.h_in >= 8 * TALL_MIN_TILES) ? 8 : 0;
     ConvGeom g = make_geom(cs.B, cs.h_in, cs.h_in, cs.c_in, 1, ups, cs.c_in, rows);
-    if (bn_below) launch_conv_c<2>(s, act, cs.c_out, g, dy, w, dx, *bn_below, kt);
-    else launch_conv_c<0>(s, act, cs.c_out, g, dy, w, dx, ConvEpi{}, kt);
+    if (bn_below) launch_conv_c<2>(s, act, cs.c_out, g, dy, w, dx, *bn_below, kt, reps);
+    else launch_conv_c<0>(s, act, cs.c_out, g, dy, w, dx, ConvEpi{}, kt, reps);
 }
 
 // ---- weight gradient ------------------------------------------------------------------------------
@@ -681,7 +701,11 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 template <typename T, int TAPS, bool PIPE>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
-                                                              int NI, int NO, int replicas) {
+                                                              int NI, int NO, int replicas, int64_t rstride) {
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        x = rep_at(x, ro); dy = rep_at(dy, ro); gacc = rep_at(gacc, ro);
+    }
     extern __shared__ f32x4 lds4[];
     float* lds = reinterpret_cast<float*>(lds4);
     // pixel pitch 16 floats: the four lane groups of a read (4 consecutive pixels x 16 channels) cover the
@@ -832,7 +856,12 @@ template <typename T>
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const float* __restrict__ grad, int64_t d, float lr, float mu, float wd,
                                                      fixsum_t* __restrict__ gacc, T* __restrict__ packed, UpdateTable tab,
-                                                     fixsum_t* __restrict__ sums, int64_t n_sums) {
+                                                     fixsum_t* __restrict__ sums, int64_t n_sums, int64_t rstride) {
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        params = rep_at(params, ro); momentum = rep_at(momentum, ro); grad = rep_at(grad, ro); gacc = rep_at(gacc, ro); packed = rep_at(packed, ro);
+        sums = rep_at(sums, ro);
+    }
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = first; i < n_sums; i += stride) sums[i] = 0ull;
@@ -895,11 +924,11 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
 }
 
 void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
-                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums) {
+                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums, Reps reps) {
     int64_t blocks = (d + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    ACT_DISPATCH(act, hipLaunchKernelGGL(update_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, params, momentum, grad, d, lr, mu,
-                                         wd, gacc, (T*)packed, tab, sums, n_sums));
+    ACT_DISPATCH(act, hipLaunchKernelGGL(update_kernel<T>, dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, params, momentum, grad, d, lr, mu,
+                                         wd, gacc, (T*)packed, tab, sums, n_sums, reps.stride));
 }
 
 // Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller
@@ -937,7 +966,8 @@ static int wgrad_groups(const ConvShape& cs, int n_tiles) {
 // wgrad16.hip: the bf16 matrix-instruction kernel for wide stride-1 layers
 bool wgrad16_covers(int act, const ConvShape& cs);
 int wgrad16_groups(const ConvShape& cs);
-void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt);
+void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt,
+                    Reps reps);
 
 // Accumulator replicas of a layer: as many as there are pixel groups, at most WGRAD_REPLICAS.
 int conv_wgrad_replicas(int act, const ConvShape& cs) {
@@ -950,7 +980,7 @@ int64_t conv_wgrad_accumulators(int act, const ConvShape& cs) {
 }
 
 template <typename T, int TAPS>
-static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, const T* dy, fixsum_t* gacc, const KernelTiming* kt) {
+static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, const T* dy, fixsum_t* gacc, const KernelTiming* kt, Reps reps) {
     ConvGeom g = wgrad_geom(cs);
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
@@ -960,19 +990,20 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
     if (lds < WG_WAVES * 16 * TAPS * 16 * sizeof(float)) lds = WG_WAVES * 16 * TAPS * 16 * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipExtLaunchKernelGGL(kern, dim3(groups, blocks), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
-                          kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out, groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS);
+    hipExtLaunchKernelGGL(kern, dim3(groups, blocks, reps.n), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
+                          kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out, groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS,
+                          reps.stride);
 }
 
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
-                       const KernelTiming* kt) {
+                       const KernelTiming* kt, Reps reps) {
     if (wgrad16_covers(act, cs)) {
-        launch_wgrad16(s, cs, x, dy, gacc, conv_wgrad_replicas(act, cs), kt);
+        launch_wgrad16(s, cs, x, dy, gacc, conv_wgrad_replicas(act, cs), kt, reps);
         return;
     }
     ACT_DISPATCH(act, {
-        if (cs.taps == 9) launch_conv_wgrad_t<T, 9>(s, cs, (const T*)x, (const T*)dy, gacc, kt);
-        else launch_conv_wgrad_t<T, 1>(s, cs, (const T*)x, (const T*)dy, gacc, kt);
+        if (cs.taps == 9) launch_conv_wgrad_t<T, 9>(s, cs, (const T*)x, (const T*)dy, gacc, kt, reps);
+        else launch_conv_wgrad_t<T, 1>(s, cs, (const T*)x, (const T*)dy, gacc, kt, reps);
     });
 }
 

@@ -20,7 +20,12 @@ __global__ __launch_bounds__(256) void head_forward_kernel(const T* __restrict__
                                                                const float* __restrict__ W, const float* __restrict__ bias,
                                                                int C, const int32_t* __restrict__ y, float* __restrict__ loss,
                                                                float* __restrict__ feat, float* __restrict__ dlogits,
-                                                               float* __restrict__ dfeat, float grad_scale, int relu_mask) {
+                                                               float* __restrict__ dfeat, float grad_scale, int relu_mask, int64_t rstride) {
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        act = rep_at(act, ro); W = rep_at(W, ro); bias = rep_at(bias, ro); y = rep_at(y, ro); loss = rep_at(loss, ro); feat = rep_at(feat, ro);
+        dlogits = rep_at(dlogits, ro); dfeat = rep_at(dfeat, ro);
+    }
     __shared__ __attribute__((aligned(16))) float part[4][256 * PQ];   // per wave: pooled sums, later feature-gradient sums
     __shared__ __attribute__((aligned(16))) float fs[256 * PQ];        // pooled features
     __shared__ float zs[HEAD_MAX_C];
@@ -123,10 +128,10 @@ __global__ __launch_bounds__(256) void head_forward_kernel(const T* __restrict__
 
 void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
-                         float grad_scale, bool relu_mask) {
+                         float grad_scale, bool relu_mask, Reps reps) {
 #define HEAD_LAUNCH(PQ)                                                                                                     \
-    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PQ, T>), dim3(B), dim3(256), 0, s, (const T*)act, positions, F, W, \
-                                              bias, C, y, loss, feat, dlogits, dfeat, grad_scale, relu_mask ? 1 : 0))
+    ACT_DISPATCH(act_type, hipLaunchKernelGGL((head_forward_kernel<PQ, T>), dim3(B, 1, reps.n), dim3(256), 0, s, (const T*)act, positions, F, W, \
+                                              bias, C, y, loss, feat, dlogits, dfeat, grad_scale, relu_mask ? 1 : 0, reps.stride))
     const int quads = (F / 4 + 63) / 64;   // F is a multiple of 16, at most 1024
     if (quads <= 1) HEAD_LAUNCH(1);
     else if (quads <= 2) HEAD_LAUNCH(2);
@@ -137,7 +142,11 @@ void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, in
 // One workgroup per class c: thread (f mod 64, slice) adds every 4th sample for its features, the four
 // slices are folded through LDS in order.  db[c] comes from the same workgroup.
 __global__ __launch_bounds__(256) void head_wgrad_kernel(const float* __restrict__ dlogits, const float* __restrict__ feat,
-                                                         int B, int C, int F, float* __restrict__ dW, float* __restrict__ db) {
+                                                         int B, int C, int F, float* __restrict__ dW, float* __restrict__ db, int64_t rstride) {
+    if (rstride) {
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        dlogits = rep_at(dlogits, ro); feat = rep_at(feat, ro); dW = rep_at(dW, ro); db = rep_at(db, ro);
+    }
     __shared__ float red[4][64];
     const int c = blockIdx.x, fl = threadIdx.x & 63, sl = threadIdx.x >> 6;
     for (int f0 = 0; f0 < F; f0 += 64) {
@@ -160,6 +169,6 @@ __global__ __launch_bounds__(256) void head_wgrad_kernel(const float* __restrict
     if (threadIdx.x == 0) db[c] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
 }
 
-void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db) {
-    hipLaunchKernelGGL(head_wgrad_kernel, dim3(C), dim3(256), 0, s, dlogits, feat, B, C, F, dW, db);
+void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db, Reps reps) {
+    hipLaunchKernelGGL(head_wgrad_kernel, dim3(C, 1, reps.n), dim3(256), 0, s, dlogits, feat, B, C, F, dW, db, reps.stride);
 }

@@ -30,6 +30,27 @@ __device__ __forceinline__ long long fixsum_read(const fixsum_t* sums, int C, in
 #define FIX_FWD_SCALE 4294967296.0
 #define FIX_BWD_SCALE 17592186044416.0
 
+// Several replicas of a network in one launch (the workers of a communication round side by side): every buffer of
+// replica r sits `stride` bytes after the same buffer of replica r - 1 (parameters, statistics, activations, sums:
+// one slot per replica, all laid out alike), the launchers below take the pointers of replica 0 and add a grid
+// dimension (blockIdx.z = replica); a kernel shifts its pointers by blockIdx.z * stride before anything else.
+// The default is one replica and no shift.
+struct Reps {
+    int n = 1;
+    int64_t stride = 0;
+};
+// Pointer p of replica 0 as replica r sees it (`ro` = r * stride bytes); null stays null.
+template <typename P>
+__device__ __forceinline__ P rep_at(P p, int64_t ro) {
+    return p ? (P)((const char*)p + ro) : p;
+}
+// Per-replica selection lists of a batched gather (the only per-replica arguments that are not slot-relative).
+#define GATHER_MAX_REPS 64
+struct GatherReps {
+    const int32_t* sel[GATHER_MAX_REPS];
+    int64_t k[GATHER_MAX_REPS];
+};
+
 // Optional pair of events that a launcher attaches to its kernel dispatch (start and end of that kernel).
 struct KernelTiming {
     hipEvent_t start, stop;
@@ -45,11 +66,14 @@ void launch_gather_rows(hipStream_t s, const float* src, const int32_t* y_src, c
 void launch_gather_images(hipStream_t s, const float* src, const int32_t* y_src, const int32_t* sel, int64_t k,
                           int64_t start, int64_t first, int batch, int pixels, int c_src, int c_dst, int act, void* dst,
                           int32_t* y_dst);
+// The same for several replicas at once: replica r gathers by lists.sel[r] / lists.k[r] into its own dst / y_dst.
+void launch_gather_images_reps(hipStream_t s, const float* src, const int32_t* y_src, const GatherReps& lists, int64_t start, int batch,
+                               int pixels, int c_src, int c_dst, int act, void* dst, int32_t* y_dst, Reps reps);
 void launch_sgd(hipStream_t s, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
                 float wd);
 // out[n] = sum_b in[b][n]
 void launch_colsum(hipStream_t s, const float* in, int rows, int cols, float* out);
-void launch_fill_zero(hipStream_t s, float* p, int64_t n);
+void launch_fill_zero(hipStream_t s, float* p, int64_t n, Reps reps = Reps{});
 
 // ---- gemm.hip ---------------------------------------------------------------------------------------
 // C[m][n] = sum_k A(m,k) * B(n,k); A(m,k) = a_kmajor ? A[k*lda+m] : A[m*lda+k], likewise B.
@@ -66,9 +90,9 @@ void launch_gemm(hipStream_t s, const float* A, int lda, bool a_kmajor, const fl
 // when relu_mask is set.
 void launch_head_forward(hipStream_t s, int act_type, const void* act, int B, int positions, int F, const float* W, const float* bias,
                          int C, const int32_t* y, float* loss, float* feat, float* dlogits, float* dfeat,
-                         float grad_scale, bool relu_mask);
+                         float grad_scale, bool relu_mask, Reps reps = Reps{});
 // dW[c][f] = sum_b dlogits[b][c] feat[b][f]; db[c] = sum_b dlogits[b][c]
-void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db);
+void launch_head_wgrad(hipStream_t s, const float* dlogits, const float* feat, int B, int C, int F, float* dW, float* db, Reps reps = Reps{});
 
 // ---- norm.hip ---------------------------------------------------------------------------------------
 // Where the normalisation statistics of bn_apply come from.  Training: `sums` holds the fixed-point
@@ -84,17 +108,17 @@ struct BnStats {
 };
 // a = relu(gamma * (y - mean) * invstd + beta [+ shortcut(res)]); res has c_res channels at res_stride x resolution
 void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
-                     const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out);
+                     const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out, Reps reps = Reps{});
 // Backward of relu(bn(y) [+ shortcut]) for a layer whose upstream gradient does not come from an input-gradient
 // kernel: g = dout * (out > 0); dout is a tensor of the storage type, or, with dout_positions_shared > 0, an fp32
 // [samples][C] matrix whose rows are shared by that many positions; adds (sum g, sum g*xhat) into the fixed-point accumulators `sums` [2][C].
 void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
-                          int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums);
+                          int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums, Reps reps = Reps{});
 // dy = gamma*invstd*(g - dbeta/M - xhat*dgamma/M) with g = dout * (out > 0) and (dbeta, dgamma) read from `sums`;
 // workgroup 0 stores dgamma and dbeta; g_out (optional) receives g; `add` (optional, shape of dy) is added to dy.
 void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add = nullptr);
+                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add = nullptr, Reps reps = Reps{});
 // ---- conv.hip ---------------------------------------------------------------------------------------
 struct ConvShape {
     int B, h_in, c_in, c_out, stride;  // square maps; 3x3, padding 1; c_in, c_out in {16, 32, 64}
@@ -114,7 +138,7 @@ struct PackTable {
     int64_t total_vec4;
     PackEntry e[PACK_MAX_ENTRIES];
 };
-void launch_pack_weights(hipStream_t s, int act, const float* params, void* packed, const PackTable& tab);
+void launch_pack_weights(hipStream_t s, int act, const float* params, void* packed, const PackTable& tab, Reps reps = Reps{});
 // Fused epilogue of the convolution kernels (see conv_kernel).  `sums` points at [replica][2][channels] accumulators:
 // forward (sum, sum of squares) of the output; input gradient (sum g, sum g*xhat) of the layer below.
 struct ConvEpi {
@@ -155,17 +179,17 @@ int conv_fwd_tiles(const ConvShape& cs);
 // y = conv(x, w); with `stats` the kernel also accumulates (sum, sum of squares) of y per channel, or, when
 // stats->gamma is set, applies inference batch norm + shortcut + ReLU before storing.
 void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
-                     const KernelTiming* kt = nullptr);
+                     const KernelTiming* kt = nullptr, Reps reps = Reps{});
 // dx = conv_transpose(dy, w) [+ shortcut gradient]; with `bn_below` also the batch-norm backward sums of the layer
 // that produced x.
 void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
-                       const KernelTiming* kt = nullptr);
+                       const KernelTiming* kt = nullptr, Reps reps = Reps{});
 // Adds dy (x) shifted x over all pixels into gacc: [replica][c_out/16][c_in/16][2304] fixed-point accumulators
 // (conv_wgrad_accumulators entries, zero before the call) ...
 int64_t conv_wgrad_accumulators(int act, const ConvShape& cs);
 int conv_wgrad_replicas(int act, const ConvShape& cs);
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
-                       const KernelTiming* kt = nullptr);
+                       const KernelTiming* kt = nullptr, Reps reps = Reps{});
 // End of a local step in one launch (see update_kernel): gradient of every parameter (convolution weights from the
 // accumulators, which are cleared; the rest from grad[]), SGD update, refresh of the packed weight copies, and
 // clearing of the n_sums batch-norm accumulators.
@@ -183,7 +207,7 @@ struct UpdateTable {
     UpdateEntry e[WGRAD_MAX_ENTRIES];
 };
 void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
-                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums);
+                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums, Reps reps = Reps{});
 
 // ---- wconv.hip --------------------------------------------------------------------------------------
 // Convolution for wide layers: y = conv(x, w) [+ add] with a 3x3 (taps 9, padding 1) or 1x1 (taps 1) filter;

@@ -71,6 +71,7 @@ void mlp_hidden(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* p
 // ---- residual network ---------------------------------------------------------------------------------
 
 struct ResScratch {
+    Reps reps;                         // replicas that every launch covers (one, or the workers of a batched round)
     int act;                           // storage type of activations and packed weights
     act_t* wpack;                      // packed weights: forward copies of all layers, then input-gradient copies
     std::vector<int64_t> fwd_off, dgrad_off;  // byte offsets into wpack per layer
@@ -186,8 +187,8 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
         }
     };
     if (prepare) {
-        PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab));
-        if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), (int64_t)m->layers.size() * 2 * FIX_SET * 2));
+        PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab, s.reps));
+        if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), (int64_t)m->layers.size() * 2 * FIX_SET * 2, s.reps));
     }
     const act_t* block_in = nullptr;
     const act_t* cur = s.xpad;
@@ -223,7 +224,7 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
                 x_in = s.y[pending];
                 pending = -1;
             }
-            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, x_in, s.wpack + s.fwd_off[l], y, &e, kt));
+            PROF_KERNEL(ctx, PROF_CONV_FWD, launch_conv_fwd(st, s.act, cs, x_in, s.wpack + s.fwd_off[l], y, &e, kt, s.reps));
         } else {
             // inference: one kernel per layer, batch norm (running statistics), shortcut and ReLU in the epilogue
             ConvEpi e{};
@@ -262,7 +263,7 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
             res_stride = c1.stride;
         }
         PROF(ctx, PROF_NORM, launch_bn_apply(st, s.act, y, pixels, cb.c_out, bs, params + cb.gamma_off, params + cb.beta_off, res,
-                        c_res, res_stride, cb.h_out, a));
+                        c_res, res_stride, cb.h_out, a, s.reps));
         cur = a;
     }
     return cur;
@@ -295,7 +296,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             // top layer: its upstream gradient comes from the head; lower layers get these sums from the
             // input-gradient kernel of the layer above
             PROF(ctx, PROF_NORM, launch_bn_bwd_reduce(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l],
-                                                      s.sums + ((size_t)l * 2 + 1) * FIX_SET));
+                                                      s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.reps));
         }
         // Layers whose upstream gradient is a tensor (all but the top one): the input-gradient convolution computes dy itself
         // while staging (for a stride-2 layer at the even positions of the zero-inserted image), the element-wise kernel goes
@@ -307,12 +308,13 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             // fp32 storage a third queue only slows the critical path (measured: +1.7 % per pass).
             hipStream_t side = (two_sides && (l & 1)) ? ctx->aux2 : ctx->aux;
             BLS_HIP(ctx, hipStreamWaitEvent(side, ctx->fork_events[l], 0));
-            PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(side, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt));
+            PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(side, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt, s.reps));
             return BLS_OK;
         };
         if (!fused_bwd) {
             PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
-                                s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr));
+                                s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr,
+                                nullptr, s.reps));
             int rcw = weight_gradient();
             if (rcw != BLS_OK) return rcw;
         }
@@ -337,7 +339,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
                 e.bw_inv_count = 1.f / (float)pixels;
                 e.bw_dy_out = s.dy[l]; e.bw_g_out = is_conv2 ? s.g : nullptr;
             }
-            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, s.act, cs, s.dy[l], s.wpack + s.dgrad_off[l], dx, &e, kt));
+            PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, s.act, cs, s.dy[l], s.wpack + s.dgrad_off[l], dx, &e, kt, s.reps));
         }
         if (fused_bwd) {
             int rcw = weight_gradient();   // dy[l] exists once the input gradient has run
@@ -353,6 +355,94 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event2, 0));
     }
     return BLS_OK;
+}
+
+// One training step on the batch already gathered into s.xpad / s.yb: forward, head, backward, update.  All launches cover
+// s.reps replicas (params, buffers, momentum, loss and the scratch are replica 0's).
+int resnet_train_step(bls_ctx* ctx, hipStream_t st, const bls_model* m, float* params, float* buffers, float* momentum, int B, ResScratch& s,
+                      float* loss, const bls_sgd& opt, bool first) {
+    const int C = m->desc.classes;
+    const float inv_b = 1.f / (float)B;
+    const act_t* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true, first);
+    PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
+                        loss, s.feat, s.dlogits, s.dfeat, inv_b, false, s.reps));
+    // the head's weight gradient is only needed by the update: side stream, joined at the end of the backward pass
+    BLS_HIP(ctx, hipEventRecord(ctx->head_event, st));
+    BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->head_event, 0));
+    {
+        ProfScope prof_(ctx, PROF_HEAD, ctx->aux);
+        launch_head_wgrad(ctx->aux, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b, s.reps);
+    }
+    int rc = resnet_backward(ctx, st, m, params, B, s);
+    if (rc != BLS_OK) return rc;
+    // gradients of the convolution weights are still in the accumulators: the update reads them there
+    PROF(ctx, PROF_UPDATE, launch_update(st, s.act, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay,
+                                         s.wacc, s.wpack, s.utab, s.sums, (int64_t)m->layers.size() * 2 * FIX_SET, s.reps));
+    return BLS_OK;
+}
+
+// ---- the workers of a communication round side by side ----------------------------------------------------------------
+// Worker r lives in slot r of the arena: its parameters, running statistics, momentum, recorded losses and the whole
+// training scratch, every slot laid out alike, so that one launch per layer covers all workers (Reps).
+struct SlotHead {
+    float *params, *buffers, *momentum, *losses;
+};
+
+SlotHead carve_slot_head(Carver& c, const bls_model* m, int B, int64_t tau_max) {
+    SlotHead h{};
+    h.params = c.take<float>(m->num_params);
+    h.buffers = c.take<float>(m->num_buffers > 0 ? m->num_buffers : 1);
+    h.momentum = c.take<float>(m->num_params);
+    h.losses = c.take<float>((size_t)tau_max * B);
+    return h;
+}
+
+#define ROUND_MAX_REPS 64
+struct RoundIO {   // the workers' own storage, by slot
+    float* params[ROUND_MAX_REPS];
+    float* buffers[ROUND_MAX_REPS];
+    float* momentum[ROUND_MAX_REPS];
+    float* losses[ROUND_MAX_REPS];     // where the recorded losses of the slot go (or nullptr)
+    int64_t n_losses[ROUND_MAX_REPS];
+};
+
+// Start of a round: every slot takes the global model and its worker's momentum.
+__global__ __launch_bounds__(256) void round_copy_in_kernel(const float* __restrict__ gparams, const float* __restrict__ gbuffers, RoundIO io,
+                                                            SlotHead h, int64_t d, int64_t nb, int64_t rstride) {
+    const int r = blockIdx.z;
+    const int64_t ro = (int64_t)r * rstride;
+    float *sp = rep_at(h.params, ro), *sb = rep_at(h.buffers, ro), *sm = rep_at(h.momentum, ro);
+    const float* wm = io.momentum[r];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = first; i < d; i += stride) {
+        sp[i] = gparams[i];
+        sm[i] = wm[i];
+    }
+    for (int64_t i = first; i < nb; i += stride) sb[i] = gbuffers[i];
+}
+
+// End of a round: the trained replica, its running statistics, momentum and recorded losses go to the worker's storage.
+__global__ __launch_bounds__(256) void round_copy_out_kernel(RoundIO io, SlotHead h, int64_t d, int64_t nb, int64_t rstride) {
+    const int r = blockIdx.z;
+    const int64_t ro = (int64_t)r * rstride;
+    const float *sp = rep_at(h.params, ro), *sb = rep_at(h.buffers, ro), *sm = rep_at(h.momentum, ro), *sl = rep_at(h.losses, ro);
+    float *wp = io.params[r], *wb = io.buffers[r], *wm = io.momentum[r], *wl = io.losses[r];
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x, first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (int64_t i = first; i < d; i += stride) {
+        wp[i] = sp[i];
+        wm[i] = sm[i];
+    }
+    if (wb)
+        for (int64_t i = first; i < nb; i += stride) wb[i] = sb[i];
+    if (wl)
+        for (int64_t i = first; i < io.n_losses[r]; i += stride) wl[i] = sl[i];
+}
+
+size_t round_slot_bytes(const bls_model* m, int B, int64_t tau_max) {
+    Carver c(nullptr);
+    carve_slot_head(c, m, B, tau_max);
+    carve_resnet(c, m, B, true);
+    return (c.off + 255) & ~size_t(255);
 }
 
 size_t scratch_bytes(const bls_model* m, int B, bool train) {
@@ -407,8 +497,8 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
     if (rc != BLS_OK) return rc;
     hipStream_t st = ctx->stream;
     Carver c(ctx->arena);
-    const float inv_b = 1.f / (float)B;
     if (m->desc.kind == BLS_MODEL_MLP) {
+        const float inv_b = 1.f / (float)B;
         MlpScratch s = carve_mlp(c, m, B, true);
         const int hid = m->desc.hidden, C = m->desc.classes;
         for (int64_t j = 0; j < tau; ++j) {
@@ -425,29 +515,80 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         }
     } else {
         ResScratch s = carve_resnet(c, m, B, true);
-        const int hw = m->desc.image_hw, C = m->desc.classes;
+        const int hw = m->desc.image_hw;
         // the weight-gradient accumulators start at zero; every reduction leaves them at zero again
         PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.wacc), s.wacc_count * 2));
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
             PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
-            const act_t* fin = resnet_forward(ctx, st, m, params, buffers, B, s, true, j == 0);
-            PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C, s.yb,
-                                loss, s.feat, s.dlogits, s.dfeat, inv_b, false));
-            // the head's weight gradient is only needed by the update: side stream, joined at the end of the backward pass
-            BLS_HIP(ctx, hipEventRecord(ctx->head_event, st));
-            BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->head_event, 0));
-            {
-                ProfScope prof_(ctx, PROF_HEAD, ctx->aux);
-                launch_head_wgrad(ctx->aux, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b);
-            }
-            rc = resnet_backward(ctx, st, m, params, B, s);
+            rc = resnet_train_step(ctx, st, m, params, buffers, momentum, B, s, loss, opt, j == 0);
             if (rc != BLS_OK) return rc;
-            // gradients of the convolution weights are still in the accumulators: the update reads them there
-            PROF(ctx, PROF_UPDATE, launch_update(st, s.act, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay,
-                                                 s.wacc, s.wpack, s.utab, s.sums, (int64_t)m->layers.size() * 2 * FIX_SET));
         }
     }
+    BLS_HIP(ctx, hipGetLastError());
+    return BLS_OK;
+}
+
+bool net_round_batched_covers(const bls_model* m) { return m->desc.kind == BLS_MODEL_RESNET_CIFAR; }
+
+int net_round_batched(bls_ctx* ctx, const bls_model* m, const float* global_params, const float* global_buffers, const bls_worker* workers, int P,
+                      const float* x_pool, const int32_t* y_pool, int64_t batch, const bls_sgd& opt, float* losses_out, const int64_t* loss_off) {
+    // slots in order of decreasing step count: the workers still training after step j are then the first R_j slots
+    int order[ROUND_MAX_REPS], R = 0;
+    for (int i = 0; i < P; ++i)
+        if (workers[i].tau > 0) order[R++] = i;
+    if (R < 1 || R > ROUND_MAX_REPS) return bls_fail(ctx, BLS_EINVAL, "batched round: %d workers take a step, 1 .. %d supported", R, ROUND_MAX_REPS);
+    for (int a = 1; a < R; ++a)   // stable insertion sort by tau, descending
+        for (int b = a; b > 0 && workers[order[b]].tau > workers[order[b - 1]].tau; --b) {
+            const int t = order[b]; order[b] = order[b - 1]; order[b - 1] = t;
+        }
+    const int B = (int)batch;
+    const int64_t tau_max = workers[order[0]].tau;
+    const size_t slot = round_slot_bytes(m, B, tau_max);
+    int rc = bls_arena_reserve(ctx, slot * R);
+    if (rc != BLS_OK) return rc;
+    hipStream_t st = ctx->stream;
+    Carver c(ctx->arena);
+    SlotHead h = carve_slot_head(c, m, B, tau_max);
+    ResScratch s = carve_resnet(c, m, B, true);
+    s.reps.n = R;
+    s.reps.stride = (int64_t)slot;
+    RoundIO io{};
+    GatherReps lists{};
+    int t_seen = 0;
+    for (int i = 0; i < P; ++i) {   // loss_off counts the workers that take a step, in the caller's order
+        if (workers[i].tau == 0) continue;
+        for (int r = 0; r < R; ++r)
+            if (order[r] == i) {
+                io.losses[r] = losses_out ? losses_out + loss_off[t_seen] : nullptr;
+                io.n_losses[r] = workers[i].tau * batch;
+            }
+        ++t_seen;
+    }
+    for (int r = 0; r < R; ++r) {
+        const bls_worker& w = workers[order[r]];
+        io.params[r] = w.params; io.buffers[r] = w.buffers; io.momentum[r] = w.momentum;
+        lists.sel[r] = w.idx; lists.k[r] = w.n_idx;
+    }
+    const int64_t d = m->num_params, nb = m->num_buffers;
+    int64_t blocks = (d + 255) / 256;
+    if (blocks > 256) blocks = 256;
+    PROF(ctx, PROF_UPDATE, hipLaunchKernelGGL(round_copy_in_kernel, dim3((unsigned)blocks, 1, R), dim3(256), 0, st, global_params, global_buffers, io, h,
+                                              d, nb, s.reps.stride));
+    // the weight-gradient accumulators start at zero; every update leaves them at zero again
+    PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.wacc), s.wacc_count * 2, s.reps));
+    const int hw = m->desc.image_hw;
+    for (int64_t j = 0; j < tau_max; ++j) {
+        int rj = 0;
+        while (rj < R && workers[order[rj]].tau > j) ++rj;
+        s.reps.n = rj;
+        PROF(ctx, PROF_GATHER, launch_gather_images_reps(st, x_pool, y_pool, lists, j * B, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb,
+                                                         s.reps));
+        rc = resnet_train_step(ctx, st, m, h.params, h.buffers, h.momentum, B, s, h.losses + j * B, opt, j == 0);
+        if (rc != BLS_OK) return rc;
+    }
+    s.reps.n = R;
+    PROF(ctx, PROF_UPDATE, hipLaunchKernelGGL(round_copy_out_kernel, dim3((unsigned)blocks, 1, R), dim3(256), 0, st, io, h, d, nb, s.reps.stride));
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }

@@ -25,8 +25,14 @@ template <typename T, int MAXC>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, int64_t pixels, int C, BnStats st,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        const T* __restrict__ res, int c_res, int res_stride, int h_out,
-                                                       T* __restrict__ out, int cq_log2) {
+                                                       T* __restrict__ out, int cq_log2, int64_t rstride) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        y = rep_at(y, ro); gamma = rep_at(gamma, ro); beta = rep_at(beta, ro); res = rep_at(res, ro); out = rep_at(out, ro);
+        st.sums = rep_at(st.sums, ro); st.mean = rep_at(st.mean, ro); st.invstd = rep_at(st.invstd, ro);
+        st.running_mean = rep_at(st.running_mean, ro); st.running_var = rep_at(st.running_var, ro);
+    }
     constexpr bool WIDE = MAXC > 64;
     __shared__ float s_mean[MAXC], s_invstd[MAXC];
     for (int c0 = 0; c0 < (WIDE ? C : 1); c0 += 256) {
@@ -87,18 +93,19 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
 }
 
 void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
-                     const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out) {
+                     const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out, Reps reps) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     const int cq_log2 = quads_log2(C);
+    const dim3 grid((unsigned)blocks, 1, reps.n);
     ACT_DISPATCH(act, {
         if (C > 64)
-            hipLaunchKernelGGL((bn_apply_kernel<T, BN_MAX_C>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
-                               (const T*)res, c_res, res_stride, h_out, (T*)out, cq_log2);
+            hipLaunchKernelGGL((bn_apply_kernel<T, BN_MAX_C>), grid, dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
+                               (const T*)res, c_res, res_stride, h_out, (T*)out, cq_log2, reps.stride);
         else
-            hipLaunchKernelGGL((bn_apply_kernel<T, 64>), dim3((unsigned)blocks), dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
-                               (const T*)res, c_res, res_stride, h_out, (T*)out, cq_log2);
+            hipLaunchKernelGGL((bn_apply_kernel<T, 64>), grid, dim3(256), 0, s, (const T*)y, pixels, C, st, gamma, beta,
+                               (const T*)res, c_res, res_stride, h_out, (T*)out, cq_log2, reps.stride);
     });
 }
 
@@ -124,7 +131,12 @@ template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restrict__ dout, int shared,
                                                             const T* __restrict__ out, const T* __restrict__ y,
                                                             int64_t pixels, int C, const float* __restrict__ mean,
-                                                            const float* __restrict__ invstd, fixsum_t* __restrict__ sums) {
+                                                            const float* __restrict__ invstd, fixsum_t* __restrict__ sums, int64_t rstride) {
+    if (rstride) {
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        dout = rep_at(dout, ro); out = rep_at(out, ro); y = rep_at(y, ro); mean = rep_at(mean, ro); invstd = rep_at(invstd, ro);
+        sums = rep_at(sums, ro);
+    }
     __shared__ float red[2][256][4];
     const int cq = C >> 2;              // threads per pixel (C <= BN_MAX_C: at most 128)
     const int lanes_p = 256 / cq;       // pixels in flight per block; threads beyond lanes_p * cq idle
@@ -164,15 +176,16 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
 }
 
 void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
-                          int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums) {
+                          int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums, Reps reps) {
     int n = bn_bwd_partials(pixels);
+    const dim3 grid(n, 1, reps.n);
     ACT_DISPATCH(act, {
         if (2 * C > 256)
-            hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, true>), dim3(n), dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
-                               (const T*)y, pixels, C, mean, invstd, sums);
+            hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, true>), grid, dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
+                               (const T*)y, pixels, C, mean, invstd, sums, reps.stride);
         else
-            hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, false>), dim3(n), dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
-                               (const T*)y, pixels, C, mean, invstd, sums);
+            hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, false>), grid, dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
+                               (const T*)y, pixels, C, mean, invstd, sums, reps.stride);
     });
 }
 
@@ -183,8 +196,14 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
                                                            const float* __restrict__ invstd, const float* __restrict__ gamma,
                                                            const fixsum_t* __restrict__ sums, float* __restrict__ dgamma,
                                                            float* __restrict__ dbeta, float inv_count, T* __restrict__ dy,
-                                                           T* __restrict__ g_out, const T* __restrict__ add, int cq_log2) {
+                                                           T* __restrict__ g_out, const T* __restrict__ add, int cq_log2, int64_t rstride) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
+    if (rstride) {
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        dout = rep_at(dout, ro); out = rep_at(out, ro); y = rep_at(y, ro); mean = rep_at(mean, ro); invstd = rep_at(invstd, ro);
+        gamma = rep_at(gamma, ro); sums = rep_at(sums, ro); dgamma = rep_at(dgamma, ro); dbeta = rep_at(dbeta, ro); dy = rep_at(dy, ro);
+        g_out = rep_at(g_out, ro); add = rep_at(add, ro);
+    }
     constexpr bool WIDE = MAXC > 64;
     __shared__ float s_dg[MAXC], s_db[MAXC];
     auto channel_sums = [&](int c) {
@@ -229,14 +248,14 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
 
 void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                          int64_t pixels, int C, const float* mean, const float* invstd, const float* gamma,
-                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add) {
+                         const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add, Reps reps) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 4096) blocks = 4096;
 #define BN_BWD_APPLY(MAXC, HAS_ADD)                                                                                                   \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MAXC, HAS_ADD>), dim3((unsigned)blocks), dim3(256), 0, s, dout, dout_positions_shared,   \
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MAXC, HAS_ADD>), dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, dout, dout_positions_shared,   \
                        (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums, dgamma, dbeta, 1.f / (float)pixels, (T*)dy,  \
-                       (T*)g_out, (const T*)add, cq_log2)
+                       (T*)g_out, (const T*)add, cq_log2, reps.stride)
     const int cq_log2 = quads_log2(C);
     ACT_DISPATCH(act, {
         if (C > 64 || add) {

@@ -28,7 +28,11 @@ struct W16Geom {
 
 template <int TAPS>
 __global__ __launch_bounds__(256) void wgrad16_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, fixsum_t* __restrict__ gacc,
-                                                      ConvGeom g, W16Geom wg, int tiles_per_group, int NI, int NO, int replicas) {
+                                                      ConvGeom g, W16Geom wg, int tiles_per_group, int NI, int NO, int replicas, int64_t rstride) {
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        x = rep_at(x, ro); dy = rep_at(dy, ro); gacc = rep_at(gacc, ro);
+    }
     extern __shared__ uint2 lds2[];
     uint2* xT = lds2;                       // [64][xp / 4] quads
     uint2* dyT = lds2 + 64 * (wg.xp / 4);   // [64][dp / 4] quads
@@ -160,7 +164,8 @@ int wgrad16_groups(const ConvShape& cs) {
     return groups < n_tiles ? groups : n_tiles;
 }
 
-void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt) {
+void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt,
+                    Reps reps) {
     hipEvent_t ev0 = kt ? kt->start : nullptr, ev1 = kt ? kt->stop : nullptr;   // timing events ride on the dispatch itself
     ConvGeom g = wgrad16_geom(cs);
     W16Geom wg;
@@ -173,14 +178,14 @@ void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const voi
     const int groups = wgrad16_groups(cs);
     const int tiles_per_group = (g.n_tiles + groups - 1) / groups;
     const size_t lds = (size_t)64 * (wg.xp + wg.dp) * sizeof(bf16_t);
-    dim3 grid(groups, (cs.c_in / 64) * (cs.c_out / 64));
+    dim3 grid(groups, (cs.c_in / 64) * (cs.c_out / 64), reps.n);
     if (cs.taps == 9) {
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_kernel<9>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         hipExtLaunchKernelGGL(wgrad16_kernel<9>, grid, dim3(256), lds, s, ev0, ev1, 0, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg,
-                              tiles_per_group, cs.c_in, cs.c_out, replicas);
+                              tiles_per_group, cs.c_in, cs.c_out, replicas, reps.stride);
     } else {
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         hipExtLaunchKernelGGL(wgrad16_kernel<1>, grid, dim3(256), lds, s, ev0, ev1, 0, (const bf16_t*)x, (const bf16_t*)dy, gacc, g, wg,
-                              tiles_per_group, cs.c_in, cs.c_out, replicas);
+                              tiles_per_group, cs.c_in, cs.c_out, replicas, reps.stride);
     }
 }

@@ -149,6 +149,42 @@ def test_workers_side_by_side_give_the_same_bits(env):
     assert np.isfinite(one[0]).all() and (one[2] != -3.0).sum() == len(seen)
 
 
+@pytest.mark.parametrize("act", ["f32", "bf16"])
+def test_workers_inside_one_launch_give_the_same_bits_as_one_after_the_other(env, act):
+    """Residual networks run the workers of a round side by side inside the kernels (one launch per layer for all workers
+    that still have steps to take; unequal step counts, an idle worker, overlapping samples, selections of different
+    lengths): replicas, momenta, running statistics, loss table and aggregate are the same bits as with
+    BLS_ROUND_SEQUENTIAL, twice in a row."""
+    torch, bls, ctx = env
+    cfg = synth.workload("resnet20_fp32")
+    widths, blocks, hw, N = (16, 32, 64), 1, 16, 64
+    model = bls.Model.resnet_cifar(widths, blocks, 10, hw, act_dtype=act)
+    p, b = synth.resnet_init(cfg["id"], widths, blocks, 10, perturb_bn=0.1)
+    x, y = synth.image_pool(cfg["id"], N, 10, hw=hw)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dx, dy = dev(x), dev(y)
+    segments = [np.arange(0, 12), np.arange(6, 16), np.arange(16, 24), np.arange(3, 9), np.arange(20, 50), np.arange(40, 64)]
+    taus = [2, 1, 3, 0, 2, 3]
+
+    def run(flags):
+        gp, gb = dev(model.pack(p)), dev(model.pack(b, buffers=True))
+        table = torch.full((N,), -3.0, device="cuda")
+        ws = [dict(tau=t, idx=dev(s.astype(np.int32)), params=torch.full_like(gp, 5.0), buffers=torch.full_like(gb, 5.0),
+                   momentum=torch.full_like(gp, 0.01 * (i + 1))) for i, (t, s) in enumerate(zip(taus, segments))]
+        for _ in range(2):
+            bls.communication_round(ctx, model, gp, gb, ws, dx, dy, 6, 0.05, 0.9, 1e-4, table, flags=flags)
+        ctx.synchronize()
+        out = [gp.cpu().numpy(), gb.cpu().numpy(), table.cpu().numpy()]
+        for w in ws:
+            out += [w["params"].cpu().numpy(), w["buffers"].cpu().numpy(), w["momentum"].cpu().numpy()]
+        return out
+
+    side_by_side, in_turn = run(0), run(bls.ROUND_SEQUENTIAL)
+    for a, c in zip(side_by_side, in_turn):
+        assert np.array_equal(a, c)
+    assert np.isfinite(side_by_side[0]).all() and (side_by_side[3 + 3 * 3] == 5.0).all()    # the idle worker's storage is not touched
+
+
 def test_transformer_round_with_token_sequences(env):
     """The round with the sequence model (int32 token pool, no buffers, bf16 factors): against the oracle's round."""
     torch, bls, ctx = env
