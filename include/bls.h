@@ -21,7 +21,15 @@
  *   - Return value: BLS_OK (0) or a negative bls_status.  Argument errors are detected on the
  *     host before anything is enqueued and leave all outputs untouched; bls_last_error() then
  *     describes the problem.  Nothing is printed and nothing aborts.
- *   - Results are bit-reproducible run to run (no floating-point atomics).
+ *   - Results are bit-reproducible run to run (no floating-point atomics).  Sums over a whole batch that many
+ *     workgroups contribute to (batch-norm statistics, the two sums of the batch-norm backward pass, convolution
+ *     weight gradients, token-embedding gradients) are accumulated as 64-bit fixed-point integers, which bounds what one
+ *     workgroup may contribute (bls_sum_limits): 2^24 to a forward sum (the sum of squares of 256 convolution outputs,
+ *     i.e. an rms below 256 per tile), 2^9 to a backward sum, 2^13 to a weight-gradient sum.  A contribution beyond its
+ *     limit, or one that is not finite, does not wrap around and is not dropped: the sum becomes NaN, and with it the
+ *     statistics, gradients, parameters and every later loss, as an overflow in floating point would end.  Inputs
+ *     normalised to unit scale (the convention of the paper's image pipelines) stay four orders of magnitude below
+ *     the limits; raw 8-bit pixel values (0 .. 255) are within them.
  *   - One context must not be used from two threads at once.
  */
 #ifndef BLS_H
@@ -342,6 +350,11 @@ typedef struct {
 int train_epochs(bls_ctx* ctx, const bls_model* model, const bls_epoch_plan* plan, float* global_params, float* global_buffers,
                  float* worker_params, float* worker_buffers, float* worker_momentum, const void* x_pool, const int32_t* y_pool,
                  int64_t N, const float* u_fast, const float* u_slow, float* loss_table, int32_t* idx_work, int64_t* rounds_out);
+
+/* Largest magnitude one workgroup may add to a forward statistic (sum or sum of squares of its tile of a convolution
+ * output), to a batch-norm backward sum, and to a weight-gradient sum (see the conventions at the top); any pointer may
+ * be NULL.  Host only. */
+int bls_sum_limits(double* forward_partial, double* backward_partial, double* weight_gradient_partial);
 
 /* w_i = tau_i / sum_j tau_j (Eq. 4), computed in double and rounded once.  Host only. */
 int bls_weights_from_tau(const int64_t* tau, int P, float* weights_out);

@@ -7,5 +7,5 @@ package loads the library and fails loudly if it has not been built
 """
 from .binding import (  # noqa: F401
     BlsError, Context, Model, lib, library_path, local_step, score_losses, topk_by_loss, topk_by_loss_static, TOPK_STATIC_MAX_N, weighted_aggregate,
-    weights_from_tau, sample_epoch, communication_round, train_epochs, ROUND_UNIFORM_WEIGHTS, ROUND_SEQUENTIAL, epoch_allocation, worker_share, MODEL_MLP, MODEL_RESNET_CIFAR, MODEL_WRN, MODEL_ENCODER, AGG_NORMALISE, AGG_BROADCAST, DECLARED_SYMBOLS, PROFILE_CLASSES,
+    weights_from_tau, sum_limits, sample_epoch, communication_round, train_epochs, ROUND_UNIFORM_WEIGHTS, ROUND_SEQUENTIAL, epoch_allocation, worker_share, MODEL_MLP, MODEL_RESNET_CIFAR, MODEL_WRN, MODEL_ENCODER, AGG_NORMALISE, AGG_BROADCAST, DECLARED_SYMBOLS, PROFILE_CLASSES,
 )

@@ -16,7 +16,7 @@ DECLARED_SYMBOLS = (
     "bls_model_tensor_layout", "score_losses", "topk_by_loss", "local_step", "weighted_aggregate",
     "bls_weights_from_tau", "bls_profile_begin", "bls_profile_end", "bls_epoch_allocation", "bls_worker_share",
     "sample_epoch", "sample_epoch_variant", "communication_round", "bls_ctx_set_lanes", "topk_by_loss_static",
-    "train_epochs",
+    "train_epochs", "bls_sum_limits",
 )
 ROUND_UNIFORM_WEIGHTS, ROUND_SEQUENTIAL = 1, 2
 TOPK_STATIC_MAX_N = 1 << 20
@@ -325,6 +325,14 @@ def train_epochs(ctx, model, global_params, global_buffers, worker_params, worke
                                _ptr(worker_buffers), _ptr(worker_momentum), _ptr(x_pool), _ptr(y_pool), x_pool.shape[0], _ptr(u_fast),
                                _ptr(u_slow), _ptr(loss_table), _ptr(idx_work), C.byref(rounds)))
     return rounds.value
+
+
+def sum_limits():
+    """(forward, backward, weight-gradient) bound of one workgroup's contribution to a fixed-point batch sum."""
+    f, b, w = C.c_double(), C.c_double(), C.c_double()
+    lib.bls_sum_limits.argtypes = [C.POINTER(C.c_double)] * 3
+    lib.bls_sum_limits(C.byref(f), C.byref(b), C.byref(w))
+    return f.value, b.value, w.value
 
 
 def weights_from_tau(tau):

@@ -8,6 +8,7 @@
 #include "common.h"
 #include "model.h"
 #include "net.h"
+#include "kernels.h"
 
 int bls_fail(bls_ctx* ctx, int code, const char* fmt, ...) {
     if (ctx) {
@@ -714,6 +715,13 @@ int train_epochs(bls_ctx* ctx, const bls_model* model, const bls_epoch_plan* pla
         }
     }
     if (rounds_out) *rounds_out = rounds_run;
+    return BLS_OK;
+}
+
+int bls_sum_limits(double* forward_partial, double* backward_partial, double* weight_gradient_partial) {
+    if (forward_partial) *forward_partial = 2.0 * FIX_PARTIAL_LIMIT / FIX_FWD_SCALE;   // the convolution's epilogue (half as many workgroups per word)
+    if (backward_partial) *backward_partial = FIX_PARTIAL_LIMIT / FIX_BWD_SCALE;
+    if (weight_gradient_partial) *weight_gradient_partial = FIX_PARTIAL_LIMIT / 1099511627776.0;   // the weight-gradient kernels' 2^40
     return BLS_OK;
 }
 

@@ -89,7 +89,7 @@ __device__ __forceinline__ f32x4 bn_relu4(f32x4 v, f32x4 res, const float (*s_bn
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const float t = __fmaf_rn((v[j] - s_bn[0][c + j]) * s_bn[1][c + j], s_bn[2][c + j], s_bn[3][c + j]) + res[j];
-        o[j] = fmaxf(t, 0.f);
+        o[j] = relu_keep_nan(t);
     }
     return o;
 }
@@ -377,7 +377,7 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
                     }
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        v[j] = fmaxf(__fmaf_rn((v[j] - ch_mu[j]) * ch_is[j], ch_ga[j], ch_be[j]) + r[j], 0.f);
+                        v[j] = relu_keep_nan(__fmaf_rn((v[j] - ch_mu[j]) * ch_is[j], ch_ga[j], ch_be[j]) + r[j]);
                     Act<T>::store4(y + p * NO + c0, v);
                 } else {
                     v = Act<T>::rounded(v);
@@ -423,8 +423,9 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             s_bn[3][c] = e.bw_invstd[c];
             s_bn[4][c] = e.bw_gamma[c];
             if (blockIdx.x == 0) {
-                e.bw_dbeta[c] = s_bn[0][c];
-                e.bw_dgamma[c] = s_bn[1][c];
+                const bool bad = fixsum_poisoned(e.bw_sums, CIN, c);   // out of range or not finite: NaN, as a float sum would end
+                e.bw_dbeta[c] = bad ? FIX_NAN : s_bn[0][c];
+                e.bw_dgamma[c] = bad ? FIX_NAN : s_bn[1][c];
             }
         }
         __syncthreads();
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
         if (c < CIN) {
             const double s1 = (double)fixsum_read(e.in_sums, CIN, 0, c) * (1.0 / FIX_FWD_SCALE);
             const double s2 = (double)fixsum_read(e.in_sums, CIN, 1, c) * (1.0 / FIX_FWD_SCALE);
-            const double mu = s1 / e.in_count;
+            double mu = s1 / e.in_count;
             double var = s2 / e.in_count - mu * mu;
             if (var < 0.0) var = 0.0;
             s_bn[0][c] = (float)mu;
@@ -442,6 +443,10 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             s_bn[2][c] = e.in_gamma[c];
             s_bn[3][c] = e.in_beta[c];
             if (blockIdx.x == 0) {
+                if (fixsum_poisoned(e.in_sums, CIN, c)) {   // out of range or not finite: NaN, as a float sum would end
+                    s_bn[0][c] = s_bn[1][c] = FIX_NAN;
+                    mu = var = (double)FIX_NAN;
+                }
                 e.in_mean[c] = s_bn[0][c];
                 e.in_invstd[c] = s_bn[1][c];
                 const double unbiased = e.in_count > 1.0 ? var * e.in_count / (e.in_count - 1.0) : var;
@@ -528,15 +533,15 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             float acc = 0.f;
             for (int wv = cb; wv < NW; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
             // order-independent accumulation across workgroups: 64-bit fixed point, integer atomic add
-            atomicAdd(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + c, (fixsum_t)__double2ll_rn((double)acc * e.scale));
+            // at most CONV_GRID_CAP / FIX_REPLICAS = 32 workgroups add to one word
+            fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + c, (double)acc * e.scale, 2.0 * FIX_PARTIAL_LIMIT);
         }
     }
 }
 
-// Workgroups per launch: at most CONV_GRID_CAP (two per compute unit on a 256-CU part).
-#ifndef CONV_GRID_CAP
+// Workgroups per launch: at most CONV_GRID_CAP (two per compute unit on a 256-CU part; the range of the epilogue's
+// fixed-point sums counts on this cap).
 #define CONV_GRID_CAP 512
-#endif
 static int conv_grid(const ConvGeom& g) { return g.n_tiles < CONV_GRID_CAP ? g.n_tiles : CONV_GRID_CAP; }
 
 template <typename T, int CIN, int EPI>
@@ -637,12 +642,8 @@ int conv_fwd_tiles(const ConvShape& cs) {
     return make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real).n_tiles;
 }
 
-#ifndef TALL_MIN_TILES
 #define TALL_MIN_TILES 256
-#endif
-#ifndef FWD_TALL_MIN_H
 #define FWD_TALL_MIN_H 32
-#endif
 void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* w, void* y, const ConvEpi* stats,
                      const KernelTiming* kt, Reps reps) {
     int h_out = (cs.h_in - 1) / cs.stride + 1;
@@ -655,9 +656,7 @@ void launch_conv_fwd(hipStream_t s, int act, const ConvShape& cs, const void* x,
     else launch_conv_c<0>(s, act, cs.c_in, g, x, w, y, ConvEpi{}, kt, reps);
 }
 
-#ifndef DGRAD_TALL_MIN_H
 #define DGRAD_TALL_MIN_H 16
-#endif
 void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* dy, const void* w, void* dx, const ConvEpi* bn_below,
                        const KernelTiming* kt, Reps reps) {
     // The gradient with respect to the input is a stride-1 convolution whose input channels are the
@@ -684,13 +683,9 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 #define WGRAD_REPLICAS 8
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40: |dW| < 2^23, resolution 2^-40
 
-#ifndef WGRAD_THREADS
 #define WGRAD_THREADS 512
-#endif
 #define WG_WAVES (WGRAD_THREADS / 64)
-#ifndef WGRAD_GROUP_CAP
 #define WGRAD_GROUP_CAP 512
-#endif
 
 // PIPE: a thread owns up to WG_XK fixed 4-channel slots of the x tile and WG_DK of the dy tile; the next tile's slots are
 // loaded into registers while the current tile multiplies (tiles small enough for that, see wgrad_geom).
@@ -840,7 +835,7 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
         float v = lds[e];
 #pragma unroll
         for (int wv = 1; wv < WG_WAVES; ++wv) v += lds[wv * BLOCK_FLOATS + e];
-        atomicAdd(out + e, (fixsum_t)__double2ll_rn((double)v * FIX_WGRAD_SCALE));
+        fixsum_add(out + e, (double)v * FIX_WGRAD_SCALE);
     }
 }
 
@@ -886,11 +881,14 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
             if (e.replicas > 0) {
                 fixsum_t* acc_l = gacc + e.acc_off;
                 long long acc = 0;
+                bool poisoned = false;
                 for (int rep = 0; rep < e.replicas; ++rep) {
-                    acc += (long long)acc_l[rep * pitch + src];
+                    const long long w = (long long)acc_l[rep * pitch + src];
+                    poisoned |= w >= FIX_POISON_MIN;
+                    acc += w;
                     acc_l[rep * pitch + src] = 0ull;
                 }
-                g = (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));
+                g = poisoned ? FIX_NAN : (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));   // out of range: NaN, as a float sum would end
             } else {
                 g = grad[i];   // this layer's weight gradient was written as floats (replicas == 0)
             }

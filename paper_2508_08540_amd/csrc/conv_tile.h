@@ -30,10 +30,8 @@ struct Tile<bf16_t> {
 constexpr int clog2(int v) { return v <= 1 ? 0 : 1 + clog2(v >> 1); }
 
 #define CONV_THREADS 256
-#ifndef CONV_MT
 #define CONV_MT 2   // 16-pixel tiles a wave accumulates at once
 #define CONV_NW 4   // waves per workgroup of the forward / input-gradient kernel
-#endif
 
 struct ConvGeom {
     int B, h_in, h_out, c_out, stride, ups;  // ups: input is read with zeros inserted (h_in is the virtual size)

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
         float acc = part[i];
         for (int z = 1; z < splits; ++z) acc += part[(int64_t)z * total + i];
         if (bias) acc += bias[i % N];
-        if (relu) acc = fmaxf(acc, 0.f);
+        if (relu) acc = relu_keep_nan(acc);
         if (mask) acc = mask[i] > 0.f ? acc : 0.f;
         out[i] = acc;
     }

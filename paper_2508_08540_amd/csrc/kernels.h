@@ -14,9 +14,31 @@ static inline size_t act_bytes(int act) { return act == ACT_BF16 ? 2 : 4; }
 // Per-channel sums that cross workgroups are accumulated as 64-bit fixed-point integers with atomic adds:
 // integer addition is associative, so the result does not depend on the order in which workgroups arrive
 // (bit-reproducible), and no partial-sum rows or finalisation kernels are needed.  A float partial p
-// contributes llrint(p * scale); forward statistics use 2^32 (|sum| < 2^31, resolution 2^-32), backward
-// sums 2^44 (|sum| < 2^19, resolution 2^-44).  The accumulators must be zero before the producing kernel.
+// contributes llrint(p * scale); forward statistics use 2^30 (resolution 2^-30), backward sums 2^44, weight
+// gradients 2^40.  The accumulators must be zero before the producing kernel.
+//
+// Range.  A word takes at most FIX_WORD_CONTRIBUTIONS partials (the launchers cap their grids accordingly; the
+// convolution's epilogue, whose grid is capped at 512 workgroups over 16 replicas, half as many), each below
+// FIX_PARTIAL_LIMIT (there: twice that) in scaled units, so a word stays below 2^59 in magnitude: neither a word nor
+// the sum of its 16 replicas can wrap.  A partial that is not finite or not below the limit does not add: it raises
+// the word to FIX_POISON with a signed atomic maximum (later additions cannot bring it back below FIX_POISON_MIN).
+// Workgroup 0 of every consumer, the one that stores the statistics, checks for poisoned words and stores NaN then; the
+// update turns a poisoned weight-gradient word into a NaN gradient.  An overflow or a non-finite value therefore ends,
+// as in floating point, in NaN statistics, gradients, parameters and losses instead of in finite garbage.  Limits of a
+// partial in real units: 2^24 for forward sums (the sum of squares of one tile of 256 outputs: rms below 256), 2^9 for
+// backward sums (2^10 from a convolution's epilogue), 2^13 for weight-gradient sums.
 typedef unsigned long long fixsum_t;
+#define FIX_WORD_CONTRIBUTIONS 64
+#define FIX_PARTIAL_LIMIT 9007199254740992.0   // 2^53 = 2^59 / FIX_WORD_CONTRIBUTIONS
+#define FIX_POISON (1ll << 62)
+#define FIX_POISON_MIN (1ll << 61)
+__device__ __forceinline__ void fixsum_add(fixsum_t* dst, double scaled, double limit = FIX_PARTIAL_LIMIT) {
+    if (fabs(scaled) < limit) atomicAdd(dst, (fixsum_t)__double2ll_rn(scaled));
+    else atomicMax(reinterpret_cast<long long*>(dst), FIX_POISON);   // also taken by NaN
+}
+// ReLU that keeps NaN (the hardware maximum returns the other operand): a poisoned statistic or a diverged weight has to
+// reach the losses instead of being clamped to zero on the way.
+__device__ __forceinline__ float relu_keep_nan(float t) { return t < 0.f ? 0.f : t; }
 // Each accumulator is replicated FIX_REPLICAS times (workgroup b adds into replica b % FIX_REPLICAS) to
 // spread the atomic traffic; readers add the replicas (integer, exact).  One set = FIX_SET entries.
 #define FIX_REPLICAS 16
@@ -27,7 +49,18 @@ __device__ __forceinline__ long long fixsum_read(const fixsum_t* sums, int C, in
     for (int r = 0; r < FIX_REPLICAS; ++r) t += (long long)sums[(r * 2 + which) * C + c];
     return t;
 }
-#define FIX_FWD_SCALE 4294967296.0
+// True if either sum of channel c holds a poisoned word (checked by the one workgroup that stores the statistics).
+__device__ __forceinline__ bool fixsum_poisoned(const fixsum_t* sums, int C, int c) {
+    long long top = 0;   // all loads in flight at once: the words are in cache, the other workgroups have just read them
+#pragma unroll
+    for (int r = 0; r < 2 * FIX_REPLICAS; ++r) {
+        const long long w = (long long)sums[r * C + c];
+        top |= w & ~(w >> 63);   // bits of the non-negative words (a poisoned word is positive)
+    }
+    return top >= FIX_POISON_MIN;
+}
+#define FIX_NAN __int_as_float(0x7fc00000)
+#define FIX_FWD_SCALE 1073741824.0
 #define FIX_BWD_SCALE 17592186044416.0
 
 // Several replicas of a network in one launch (the workers of a communication round side by side): every buffer of

@@ -41,12 +41,16 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
         if (st.sums) {
             const double s1 = (double)fixsum_read(st.sums, C, 0, c) * (1.0 / FIX_FWD_SCALE);
             const double s2 = (double)fixsum_read(st.sums, C, 1, c) * (1.0 / FIX_FWD_SCALE);
-            const double mu = s1 / st.count;
+            double mu = s1 / st.count;
             double var = s2 / st.count - mu * mu;
             if (var < 0.0) var = 0.0;
             s_mean[c] = (float)mu;
             s_invstd[c] = (float)(1.0 / sqrt(var + BN_EPS));
             if (blockIdx.x == 0) {
+                if (fixsum_poisoned(st.sums, C, c)) {   // out of range or not finite: NaN, as a float sum would end
+                    s_mean[c] = s_invstd[c] = FIX_NAN;
+                    mu = var = (double)FIX_NAN;
+                }
                 st.mean[c] = s_mean[c];
                 st.invstd[c] = s_invstd[c];
                 const double unbiased = st.count > 1.0 ? var * st.count / (st.count - 1.0) : var;
@@ -86,7 +90,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float t = __fmaf_rn((v[j] - s_mean[c + j]) * s_invstd[c + j], ga[j], be[j]) + r[j];
-            o[j] = fmaxf(t, 0.f);
+            o[j] = relu_keep_nan(t);
         }
         Act<T>::store4(out + p * C + c, o);
     }
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
         int which = t / C, ch = t % C;
         float acc = 0.f;
         for (int l = 0; l < lanes_p; ++l) acc += red[which][l * cq + (ch >> 2)][ch & 3];
-        atomicAdd(sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * C + ch, (fixsum_t)__double2ll_rn((double)acc * FIX_BWD_SCALE));
+        fixsum_add(sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * C + ch, (double)acc * FIX_BWD_SCALE);
     }
 }
 
@@ -210,8 +214,9 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
         s_db[c] = (float)((double)fixsum_read(sums, C, 0, c) * (1.0 / FIX_BWD_SCALE));
         s_dg[c] = (float)((double)fixsum_read(sums, C, 1, c) * (1.0 / FIX_BWD_SCALE));
         if (blockIdx.x == 0) {
-            dbeta[c] = s_db[c];
-            dgamma[c] = s_dg[c];
+            const bool bad = fixsum_poisoned(sums, C, c);   // out of range or not finite: NaN, as a float sum would end
+            dbeta[c] = bad ? FIX_NAN : s_db[c];
+            dgamma[c] = bad ? FIX_NAN : s_dg[c];
         }
     };
     if constexpr (WIDE) {

@@ -29,7 +29,6 @@ __device__ __forceinline__ uint16_t to_bf16(float v) { return (uint16_t)(pack_bf
 __device__ __forceinline__ void store_bf16x4(uint16_t* p, f32x4 v) {
     *reinterpret_cast<sq_u32x2*>(p) = sq_u32x2{pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
 }
-__device__ __forceinline__ void fix_add(fixsum_t* p, float v) { atomicAdd(p, (fixsum_t)__double2ll_rn((double)v * FIX_BWD_SCALE)); }
 
 // h[t][:] = tok_emb[token[t]][:] + pos_emb[t % L][:]; one wave per token, D % 4 == 0
 __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ tokens, int64_t T, int L, int D, const float* __restrict__ tok,
@@ -46,14 +45,17 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
     }
 }
 
-// acc_tok[token[t]][:] += dh[t][:] (fixed point)
+// acc_tok[token[t]][:] += dh[t][:] (fixed point, 2^-44).  Every token of the batch may hit the same row, so a single
+// contribution must stay below `limit` = 2^61 / T in scaled units (16 in real units for 8192 tokens; the single word
+// of a row is read on its own, so it may use the whole range below the poison value); beyond that, or
+// for a value that is not finite, the word is poisoned and the gradient comes out as NaN.
 __global__ __launch_bounds__(256) void embed_grad_kernel(const int32_t* __restrict__ tokens, int64_t T, int D, const float* __restrict__ dh,
-                                                         fixsum_t* __restrict__ acc_tok) {
+                                                         fixsum_t* __restrict__ acc_tok, double limit) {
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
     const int lane = threadIdx.x & 63;
     fixsum_t* a = acc_tok + (int64_t)tokens[t] * D;
-    for (int c = lane; c < D; c += 64) fix_add(a + c, dh[t * D + c]);
+    for (int c = lane; c < D; c += 64) fixsum_add(a + c, (double)dh[t * D + c] * FIX_BWD_SCALE, limit);
 }
 
 // part[blockIdx.y][n] = sum of X[m][n] over the 64 rows of the block
@@ -116,7 +118,8 @@ __global__ __launch_bounds__(256) void colsum_table_kernel(ColsumTable tab, cons
 __global__ __launch_bounds__(256) void fix_finalize_kernel(FixRangeTable tab, fixsum_t* __restrict__ acc, float* __restrict__ grad) {
     const FixRange r = tab.r[blockIdx.y];
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < r.n; i += (int64_t)gridDim.x * 256) {
-        grad[r.grad_off + i] = (float)((double)(long long)acc[r.acc_off + i] * (1.0 / FIX_BWD_SCALE));
+        const long long w = (long long)acc[r.acc_off + i];
+        grad[r.grad_off + i] = w >= FIX_POISON_MIN ? FIX_NAN : (float)((double)w * (1.0 / FIX_BWD_SCALE));
         acc[r.acc_off + i] = 0ull;
     }
 }
@@ -499,7 +502,9 @@ void launch_to_bf16(hipStream_t s, const float* in, uint16_t* out, int64_t n) {
     hipLaunchKernelGGL(to_bf16_kernel, dim3(b > 8192 ? 8192 : b), dim3(256), 0, s, in, out, n / 4);
 }
 void launch_embed_grad(hipStream_t s, const int32_t* tokens, int64_t T, int D, const float* dh, fixsum_t* acc_tok) {
-    hipLaunchKernelGGL(embed_grad_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, D, dh, acc_tok);
+    double limit = 2305843009213693952.0;   // 2^61
+    for (int64_t n = 1; n < T; n <<= 1) limit *= 0.5;
+    hipLaunchKernelGGL(embed_grad_kernel, dim3(nblk(T, 4)), dim3(256), 0, s, tokens, T, D, dh, acc_tok, limit);
 }
 size_t colsum_partial_floats(int64_t M, int N) { return (size_t)nblk(M, 64) * N; }
 // out[n] = sum_m X[m][n]; part holds colsum_partial_floats(M, N) floats

@@ -18,6 +18,7 @@ struct WEpi {
     const void* add;   // tensor of the output's shape added before the store, or nullptr
     fixsum_t* sums;    // [replica][2][c_out] accumulators for (sum, sum of squares) of the stored values, or nullptr
     double scale;
+    double limit;      // bound of one workgroup's partial in scaled units (the grid is not capped here: 2^61 / contributions per word)
 };
 
 // bf16 chunks of 32 channels run on v_mfma_f32_16x16x32_bf16: lane group g supplies channels 8g .. 8g+7 of both
@@ -238,8 +239,7 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
             const int which = threadIdx.x >> 6, c = threadIdx.x & 63;  // channel c of this group: wave c/16 holds it
             const int ch = blockIdx.y * 64 + c;
             if (ch < NO)
-                atomicAdd(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + ch,
-                          (fixsum_t)__double2ll_rn((double)red[((c >> 4) * 2 + which) * 16 + (c & 15)] * e.scale));
+                fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + ch, (double)red[((c >> 4) * 2 + which) * 16 + (c & 15)] * e.scale, e.limit);
         }
     }
 }
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
 // path needs the chunk tile to fit WC_NV vectors per thread and two buffers to fit 80 KB.
 template <typename T, int TAPS, int CK>
 static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const T* x, const void* w,
-                          T* y, const WEpi& e) {
+                          T* y, const WEpi& e_in) {
     typedef WcTraits<T, TAPS, CK> TR;
     const int pad = TAPS == 9 ? 1 : 0;
     auto geom = [&](int npt) { return make_geom(B, h_in, h_out, c_out, stride, ups, c_in, (npt * 16) / h_out, pad); };
@@ -267,6 +267,8 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
     if (pipelined) lds *= 2;
     if (lds < 1024) lds = 1024;
     dim3 grid(g.n_tiles, (c_out / 16 + 3) / 4);
+    WEpi e = e_in;
+    e.limit = 576460752303423488.0 / (double)((g.n_tiles + FIX_REPLICAS - 1) / FIX_REPLICAS);   // 2^59 over the partials one word takes
     if (npt == 16) {
         auto kern = wconv_kernel<T, TAPS, CK, 16>;
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -284,7 +286,7 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
 int launch_wconv(hipStream_t s, int act, int taps, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const void* x,
                  const void* w, void* y, const void* add, fixsum_t* sums, double scale) {
     if (!(c_in == 16 || c_in % 32 == 0) || c_out % 16 != 0 || (taps != 9 && taps != 1)) return -1;
-    WEpi e{add, sums, scale};
+    WEpi e{add, sums, scale, 0.0};
     int rc = -1;
     ACT_DISPATCH(act, {
         if (taps == 9) rc = c_in == 16 ? launch_wconv_t<T, 9, 16>(s, B, h_in, h_out, c_in, c_out, stride, ups, (const T*)x, w, (T*)y, e)

@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const bf16_t* __restrict__
 #pragma unroll
         for (int t = 0; t < TAPS; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) atomicAdd(out + (t * 4 + j) * 64, (fixsum_t)__double2ll_rn((double)acc[t][b][j] * FIX_WGRAD_SCALE));
+            for (int j = 0; j < 4; ++j) fixsum_add(out + (t * 4 + j) * 64, (double)acc[t][b][j] * FIX_WGRAD_SCALE);
     }
 }
 
