@@ -1,5 +1,7 @@
 """Throughput of the fast-process local step on one MI355X.
 
+--workload mlp runs configs[0] (the small MLP the oracle finishes in seconds: pool 256, k 64, batch 64, 4 steps).
+
 One "step" is one pass of the whole hot path on the ResNet20 fp32 workload: score the 512-image
 pool, select the 128 highest-loss samples, run 20 local SGD steps of batch 128 on them, and aggregate
 10 parameter replicas with step-count weights.  Prints one JSON line.
@@ -90,7 +92,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_b32", "resnet20_bf16", "wrn16_8_bf16", "transformer", "transformer_fp32"])
+    ap.add_argument("--workload", default="resnet20_fp32", choices=["resnet20_fp32", "resnet20_b32", "resnet20_bf16", "wrn16_8_bf16", "transformer", "transformer_fp32", "mlp"])
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the run, launch a plain copy of known size (aggregation of one replica with weight 1, "
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -119,7 +121,11 @@ def main():
     act_dtype = cfg.get("act_dtype", "f32")
     wide = cfg["model"] == "wrn16_8"
     seq = cfg["model"] == "transformer"
-    if seq:
+    mlp = cfg["model"] == "mlp"
+    if mlp:
+        model = bls.Model.mlp()
+        p, b = synth.mlp_init(cfg["id"]), {}
+    elif seq:
         model = bls.Model.transformer(act_dtype=act_dtype)
         p, b = synth.transformer_init(cfg["id"]), {}
         x, y = synth.token_pool(cfg["id"], N, cfg["seq_len"], cfg["classes"])
@@ -145,7 +151,7 @@ def main():
         others = [p0 + 0.01 * torch.randn(p0.shape, device="cuda", generator=gen) for _ in range(P - 1)]
     else:
         others = [dev(r) for r in synth.replicas(flat, P - 1, cfg["id"])]
-    w = bls.weights_from_tau(cfg["tau_workers"])
+    w = bls.weights_from_tau(cfg["tau_workers"]) if "tau_workers" in cfg else np.asarray(cfg["weights"], dtype=np.float32)
     losses = torch.empty(N, dtype=torch.float32, device="cuda")
     idx = torch.empty(k, dtype=torch.int32, device="cuda")
     sl = torch.empty(tau * B, dtype=torch.float32, device="cuda")
@@ -153,9 +159,9 @@ def main():
 
     def one_step():
         dp.copy_(p0); db.copy_(b0); dm.zero_()          # every step starts the round from the same global model
-        bls.score_losses(ctx, model, dp, db, dx, dy, losses)
+        bls.score_losses(ctx, model, dp, db if model.num_buffers else None, dx, dy, losses)
         bls.topk_by_loss(ctx, losses, k, idx)
-        bls.local_step(ctx, model, dp, db, dm, dx, dy, idx, B, tau, cfg["lr"], cfg["momentum"], cfg["weight_decay"], sl)
+        bls.local_step(ctx, model, dp, db if model.num_buffers else None, dm, dx, dy, idx, B, tau, cfg["lr"], cfg["momentum"], cfg["weight_decay"], sl)
         bls.weighted_aggregate(ctx, [dp] + others, w, agg)
 
     for _ in range(args.warmup):
@@ -177,6 +183,25 @@ def main():
         one_step()
     prof = ctx.profile_end()
     phases = {name: round(ms / args.steps, 4) for name, (ms, cnt) in prof.items() if cnt}
+    if mlp:
+        # the two products with the 3072 x 128 weight matrix: forward over scored and trained samples, weight gradient
+        flop = 2 * 3072 * 128 * ((N + tau * B) + tau * B) * args.steps
+        ms, cnt = prof["gemm"]
+        achieved = flop / (ms * 1e-3) / 1e12
+        line = {"metric": "selected samples/s per local step (MLP 3072-128-10)", "value": round(value, 1), "unit": "samples/s", "n_gpus": 1,
+                "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+                "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                "config": {"workload": args.workload, "pool": N, "k": k, "batch": B, "tau": tau, "P": P, "d": int(d)}, "finite": finite,
+                "phase_ms_per_step": phases,
+                "roofline": {"bound": "mfma", "kernel": "gemm16_kernel (fully connected layer: forward and weight gradient)",
+                             "achieved": round(achieved, 3), "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": round(achieved / FP32_MFMA_PEAK_TFLOPS, 5), "traffic": None, "avg_launch_us": round(1e3 * ms / cnt, 2),
+                             "launches_per_step": cnt // args.steps,
+                             "note": "products of 64 .. 256 rows: launch latency, not the matrix pipe, bounds this workload"}}
+        if not args.no_cpu_baseline:
+            line["cpu_baseline"] = cpu_baseline(cfg, p, b, x, y)
+        print(json.dumps(line))
+        return
     if seq:
         line = sequence_line(args, cfg, model, prof, phases, value, ms_per_step, finite)
         if not args.no_cpu_baseline:
@@ -215,6 +240,9 @@ def main():
     roofline = {"bound": "mfma", "kernel": symbol, "achieved": round(achieved, 3), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_launch_us": round(1e3 * dom_ms / dom_cnt, 2), "launches_per_step": dom_cnt // args.steps}
+    if traffic is not None:
+        # not measured by this run: FETCH_SIZE / WRITE_SIZE of an earlier rocprofv3 run of this same kernel source
+        roofline["traffic_source"] = "stored counter run (profiles/bench_resnet20_fp32_hbm_traffic.txt), valid for the current %s" % rec["source"]
     if dom == "conv_dgrad" and not wide:
         # These launches also carry the batch-norm backward (eight tensors per layer against 2*9*C_in*C_out flop per
         # pixel): the roof that binds is the one with the larger minimum time.
@@ -440,40 +468,51 @@ def round_lanes(only=None):
 
 
 def cpu_baseline(cfg, p, b, x, y):
-    """The oracle timed on the host cores on a bounded sample of the same workload."""
+    """The oracle timed on the host cores on a bounded sample of the same workload: once with the threads the numerical
+    library takes by itself, once limited to a single thread (a smaller sample, scaled per image)."""
     import numpy as np
     import oracle
     import synth
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_info, threadpool_limits
+    import paper_2508_08540_amd as bls
     N, k, B, tau, P = cfg["pool"], cfg["k"], cfg["batch"], cfg["tau"], cfg["P"]
     storage = oracle.round_bf16 if cfg.get("act_dtype") == "bf16" else None
-    wide = cfg["model"] == "wrn16_8"
-    m = oracle.WideResNet(storage=storage) if wide else oracle.ResNetCifar(storage=storage)
+    kind = cfg["model"]
+    wide, mlp = kind == "wrn16_8", kind == "mlp"
+    m = oracle.MLP() if mlp else oracle.WideResNet(storage=storage) if wide else oracle.ResNetCifar(storage=storage)
+    flat = (bls.Model.mlp() if mlp else bls.Model.wide_resnet() if wide else bls.Model.resnet_cifar()).pack(p)
+    reps = synth.replicas(flat, P, cfg["id"])
+    weights = oracle.weights_from_tau(cfg["tau_workers"]) if "tau_workers" in cfg else np.asarray(cfg["weights"], np.float64)
+    zeros = {n: np.zeros_like(v) for n, v in p.items()}
+
+    def timed(n_score, b_step):
+        t = time.perf_counter()
+        ls = oracle.score_losses(m, p, b, x[:n_score], y[:n_score])
+        t_score_img = (time.perf_counter() - t) / n_score
+        full = np.resize(np.concatenate([ls, ls[::-1]]), N).astype(np.float32)
+        t = time.perf_counter()
+        sel = oracle.topk_by_loss(full, k)
+        t_topk = time.perf_counter() - t
+        t = time.perf_counter()
+        oracle.local_step(m, p, b, zeros, x, y, sel, b_step, 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
+        t_step = (time.perf_counter() - t) * (B / b_step)
+        t = time.perf_counter()
+        oracle.weighted_aggregate(reps, weights)
+        t_agg = time.perf_counter() - t
+        return tau * B / (N * t_score_img + t_topk + tau * t_step + t_agg)
+
     n_score = 16 if wide else 64
     b_step = 8 if wide else B        # the wide network's step is timed on a smaller batch and scaled per sample
-    t = time.perf_counter()
-    ls = oracle.score_losses(m, p, b, x[:n_score], y[:n_score])
-    t_score_img = (time.perf_counter() - t) / n_score
-    full = np.resize(np.concatenate([ls, ls[::-1]]), N).astype(np.float32)
-    t = time.perf_counter()
-    sel = oracle.topk_by_loss(full, k)
-    t_topk = time.perf_counter() - t
-    zeros = {n: np.zeros_like(v) for n, v in p.items()}
-    t = time.perf_counter()
-    oracle.local_step(m, p, b, zeros, x, y, sel, b_step, 1, cfg["lr"], cfg["momentum"], cfg["weight_decay"])
-    t_step = (time.perf_counter() - t) * (B / b_step)
-    import paper_2508_08540_amd as bls
-    flat = (bls.Model.wide_resnet() if wide else bls.Model.resnet_cifar()).pack(p)
-    reps = synth.replicas(flat, P, cfg["id"])
-    t = time.perf_counter()
-    oracle.weighted_aggregate(reps, oracle.weights_from_tau(cfg["tau_workers"]))
-    t_agg = time.perf_counter() - t
-    total = N * t_score_img + t_topk + tau * t_step + t_agg
+    value = timed(n_score, b_step)
     threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
-    return {"value": round(tau * B / total, 2), "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": "scored %d of %d pool images, full top-k, 1 of %d local steps at batch %d%s, full aggregation; "
-                      "per-part times scaled to the whole pass" % (n_score, N, tau, b_step,
-                                                                   " (scaled to batch %d)" % B if b_step != B else ""),
+    n1, b1 = (4, 2) if wide else (N, B) if mlp else (16, 16)
+    with threadpool_limits(limits=1):
+        single = timed(n1, b1)
+    note = lambda ns, bs: "scored %d of %d pool images, full top-k, 1 of %d local steps at batch %d%s, full aggregation" % (
+        ns, N, tau, bs, " (scaled to batch %d)" % B if bs != B else "")
+    return {"value": round(value, 2), "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": note(n_score, b_step) + "; per-part times scaled to the whole pass",
+            "single_thread": {"value": round(single, 2), "unit": "samples/s", "cores": 1, "sample": note(n1, b1)},
             "host_cpus": os.cpu_count()}
 
 
