@@ -59,11 +59,14 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_lds_bitonic_kernel(const fl
 
 // ---- large pools ----------------------------------------------------------------------------------
 //
-// 1. 2048-bin histogram of the top 11 key bits; the bin b* that contains the k-th largest key follows.
-// 2. Every element with bin >= b* (M of them, M >= k, usually M is close to k) is compacted, in index
-//    order, into (sort key, index) arrays; the sort key is ~key so that ascending order is rank order.
-// 3. Stable LSD radix sort of the M pairs by the 32-bit sort key, 8 bits per pass.  Stability keeps
-//    equal losses in ascending index order, which is the tie rule.
+// 1. Two-level radix select of the k-th largest key: a 2048-bin histogram of the top 11 key bits gives the bin b1 that
+//    holds it, a second histogram of the next 11 bits over the members of b1 gives the 22-bit prefix `thr`: the M
+//    elements with key >> 10 >= thr are selected (M >= k; the excess is at most the members of one 22-bit prefix).
+//    Histograms are aggregated per wave before they touch LDS (losses crowd into a few exponent bins).
+// 2. The selected elements are compacted, in index order, into (sort key, index) arrays; the sort key is hi - key
+//    (hi bounds every key), so that ascending order is rank order and the keys only span the range that occurs.
+// 3. Stable LSD radix sort of the M pairs, 8 bits per pass, with as many passes as that range needs (the later passes
+//    exit at once).  Stability keeps equal losses in ascending index order, which is the tie rule.
 // 4. The first k pairs are the result.
 // Nothing is read back to the host: grids are sized for the worst case M == N and blocks past M exit.
 
@@ -74,8 +77,12 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_lds_bitonic_kernel(const fl
 // rounds of 64); 8 rounds for moderate pools, 16 for very large ones (longer runs per digit when scattering).
 
 struct SelInfo {
-    uint32_t bin;    // b*
-    uint32_t M;      // elements with bin >= b*
+    uint32_t bin;        // b1
+    uint32_t above;      // elements in bins above b1
+    uint32_t thr;        // selected: key >> 10 >= thr
+    uint32_t M;          // number of selected elements
+    uint32_t hi;         // no key is larger; sort key = hi - key
+    uint32_t n_passes;   // 8-bit passes that cover hi - (thr << 10)
 };
 
 __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* p, int64_t n) {
@@ -83,28 +90,79 @@ __global__ __launch_bounds__(256) void zero_u32_kernel(uint32_t* p, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
 }
 
-__global__ __launch_bounds__(256) void sel_hist_kernel(const float* __restrict__ losses, int64_t N, uint32_t* __restrict__ hist) {
-    __shared__ uint32_t h[SEL_BINS];
-    for (int i = threadIdx.x; i < SEL_BINS; i += 256) h[i] = 0u;
-    __syncthreads();
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride)
-        atomicAdd(&h[loss_key(losses[i]) >> 21], 1u);
-    __syncthreads();
-    for (int i = threadIdx.x; i < SEL_BINS; i += 256)
-        if (h[i]) atomicAdd(&hist[i], h[i]);
+// Elements 4 q .. 4 q + 3 (zero key, invalid, past N); VEC: the array allows 16-byte loads.
+template <bool VEC>
+__device__ __forceinline__ void load_keys4(const float* __restrict__ losses, int64_t N, int64_t q, uint32_t (&key)[4], bool (&ok)[4]) {
+    const int64_t i0 = q * 4;
+    if (VEC && i0 + 3 < N) {
+        const float4 v = *reinterpret_cast<const float4*>(losses + i0);
+        key[0] = loss_key(v.x); key[1] = loss_key(v.y); key[2] = loss_key(v.z); key[3] = loss_key(v.w);
+        ok[0] = ok[1] = ok[2] = ok[3] = true;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ok[j] = i0 + j < N;
+            key[j] = ok[j] ? loss_key(losses[i0 + j]) : 0u;
+        }
+    }
 }
 
-// One block: suffix counts over the bins; b* is the largest bin whose suffix count reaches k.
+// LEVEL 1: bins of key >> 21 over all elements.  Losses crowd into a handful of exponent bins, so every bin has
+// SUB counters in LDS and a lane adds to counter lane % SUB: the lanes of a wave that meet in one bin spread over SUB
+// addresses.  LEVEL 2: bins of (key >> 10) & 2047 over the members of info->bin only (those bits are spread evenly).
+template <int LEVEL, bool VEC>
+__global__ __launch_bounds__(256) void sel_hist_kernel(const float* __restrict__ losses, int64_t N, const SelInfo* __restrict__ info,
+                                                       uint32_t* __restrict__ hist) {
+    constexpr int SUB = LEVEL == 1 ? 8 : 1;
+    __shared__ uint32_t h[SEL_BINS * SUB];
+    for (int i = threadIdx.x; i < SEL_BINS * SUB; i += 256) h[i] = 0u;
+    __syncthreads();
+    const uint32_t b1 = LEVEL == 2 ? info->bin : 0u;
+    const uint32_t sub = threadIdx.x & (SUB - 1);
+    const int64_t quads = (N + 3) >> 2, stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < quads; q += 2 * stride) {
+        uint32_t key[2][4];
+        bool ok[2][4] = {{false, false, false, false}, {false, false, false, false}};
+        load_keys4<VEC>(losses, N, q, key[0], ok[0]);
+        if (q + stride < quads) load_keys4<VEC>(losses, N, q + stride, key[1], ok[1]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (LEVEL == 1) {
+                    if (ok[u][j]) atomicAdd(&h[(key[u][j] >> 21) * SUB + sub], 1u);
+                } else {
+                    if (ok[u][j] && (key[u][j] >> 21) == b1) atomicAdd(&h[(key[u][j] >> 10) & (SEL_BINS - 1)], 1u);
+                }
+            }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < SEL_BINS; i += 256) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) c += h[i * SUB + u];
+        if (c) atomicAdd(&hist[i], c);
+    }
+}
+
+// One block: suffix counts over the bins; the bin sought is the largest one whose suffix count reaches `want`.
+// LEVEL 1: want = k; stores bin, above and hi.  LEVEL 2: want = k - above over the sub-bins of b1; stores thr, M, n_passes.
+template <int LEVEL>
 __global__ __launch_bounds__(256) void sel_threshold_kernel(const uint32_t* __restrict__ hist, uint32_t k, SelInfo* __restrict__ info) {
     __shared__ uint32_t part[256];
+    __shared__ uint32_t top_bin;
+    const uint32_t want = LEVEL == 1 ? k : k - info->above;
     uint32_t mine[8], tot = 0;
+    if (threadIdx.x == 0) top_bin = 0u;
     for (int j = 0; j < 8; ++j) {
         mine[j] = hist[threadIdx.x * 8 + j];
         tot += mine[j];
     }
     part[threadIdx.x] = tot;
     __syncthreads();
+    if (LEVEL == 1)
+        for (int j = 0; j < 8; ++j)
+            if (mine[j]) atomicMax(&top_bin, threadIdx.x * 8 + j);
     // inclusive suffix sum over threads (thread t: bins 8t .. 8t+7)
     for (int o = 1; o < 256; o <<= 1) {
         uint32_t add = (threadIdx.x + o < 256) ? part[threadIdx.x + o] : 0u;
@@ -115,9 +173,19 @@ __global__ __launch_bounds__(256) void sel_threshold_kernel(const uint32_t* __re
     uint32_t above = part[threadIdx.x] - tot;  // elements in bins of higher threads
     for (int j = 7; j >= 0; --j) {
         uint32_t with = above + mine[j];
-        if (above < k && with >= k) {
-            info->bin = threadIdx.x * 8 + j;
-            info->M = with;
+        if (above < want && with >= want) {
+            const uint32_t b = threadIdx.x * 8 + j;
+            if (LEVEL == 1) {
+                info->bin = b;
+                info->above = above;
+                info->hi = top_bin == SEL_BINS - 1 ? 0xffffffffu : ((top_bin + 1u) << 21) - 1u;
+            } else {
+                const uint32_t thr = (info->bin << 11) | b;
+                const uint32_t range = info->hi - (thr << 10);   // sort keys lie in [0, range]
+                info->thr = thr;
+                info->M = info->above + with;
+                info->n_passes = range == 0u ? 0u : (32u - (uint32_t)__clz(range) + 7u) / 8u;
+            }
         }
         above = with;
     }
@@ -143,33 +211,52 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
     return before + incl - v;
 }
 
+// The 8 consecutive elements of a thread (two quads)
+template <bool VEC>
+__device__ __forceinline__ uint32_t load_tile_keys(const float* __restrict__ losses, int64_t N, uint32_t thr, uint32_t (&key)[8], bool (&sel)[8]) {
+    const int64_t q0 = ((int64_t)blockIdx.x * TILE + threadIdx.x * 8) >> 2;
+    uint32_t c = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t kq[4];
+        bool ok[4];
+        load_keys4<VEC>(losses, N, q0 + h, kq, ok);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            key[4 * h + j] = kq[j];
+            sel[4 * h + j] = ok[j] && (kq[j] >> 10) >= thr;
+            c += sel[4 * h + j] ? 1u : 0u;
+        }
+    }
+    return c;
+}
+
+template <bool VEC>
 __global__ __launch_bounds__(256) void sel_count_kernel(const float* __restrict__ losses, int64_t N, const SelInfo* __restrict__ info,
                                                         uint32_t* __restrict__ counts) {
-    const uint32_t bin = info->bin;
-    int64_t base = (int64_t)blockIdx.x * TILE + threadIdx.x * 8;
-    uint32_t c = 0;
-    for (int j = 0; j < 8; ++j)
-        if (base + j < N && (loss_key(losses[base + j]) >> 21) >= bin) ++c;
+    uint32_t key[8];
+    bool sel[8];
+    const uint32_t c = load_tile_keys<VEC>(losses, N, info->thr, key, sel);
     uint32_t total;
     block_exclusive_scan_256(c, &total);
     if (threadIdx.x == 0) counts[blockIdx.x] = total;
 }
 
 // counts has been exclusive-scanned into offsets
+template <bool VEC>
 __global__ __launch_bounds__(256) void sel_compact_kernel(const float* __restrict__ losses, int64_t N, const SelInfo* __restrict__ info,
                                                           const uint32_t* __restrict__ offsets, uint32_t* __restrict__ keys,
                                                           uint32_t* __restrict__ idx) {
-    const uint32_t bin = info->bin;
-    int64_t base = (int64_t)blockIdx.x * TILE + threadIdx.x * 8;
-    uint32_t key[8], c = 0;
-    for (int j = 0; j < 8; ++j) {
-        key[j] = base + j < N ? loss_key(losses[base + j]) : 0u;
-        if (base + j < N && (key[j] >> 21) >= bin) ++c;
-    }
+    const uint32_t hi = info->hi;
+    const int64_t base = (int64_t)blockIdx.x * TILE + threadIdx.x * 8;
+    uint32_t key[8];
+    bool sel[8];
+    const uint32_t c = load_tile_keys<VEC>(losses, N, info->thr, key, sel);
     uint32_t pos = offsets[blockIdx.x] + block_exclusive_scan_256(c, nullptr);
+#pragma unroll
     for (int j = 0; j < 8; ++j)
-        if (base + j < N && (key[j] >> 21) >= bin) {
-            keys[pos] = ~key[j];
+        if (sel[j]) {
+            keys[pos] = hi - key[j];
             idx[pos] = (uint32_t)(base + j);
             ++pos;
         }
@@ -177,7 +264,25 @@ __global__ __launch_bounds__(256) void sel_compact_kernel(const float* __restric
 
 // ---- exclusive scan of a uint32 array (three kernels) -------------------------------------------------
 
-__global__ __launch_bounds__(256) void scan_chunk_sums_kernel(const uint32_t* __restrict__ data, int64_t n, uint32_t* __restrict__ sums) {
+// The scans take an optional (info, pass): a radix pass the key range does not need is skipped by all its kernels.
+__device__ __forceinline__ bool pass_skipped(const SelInfo* info, int pass) { return info && (uint32_t)pass >= info->n_passes; }
+// Radix tiles that hold selected pairs (the grids and tables are sized for M == N on the host) and the length of a
+// pass's digit table, 256 entries per such tile; with rtile == 0 the scan takes the length it was given.
+__device__ __forceinline__ int active_tiles(const SelInfo* info, int rtile, int n_blocks) {
+    const int64_t a = ((int64_t)info->M + rtile - 1) / rtile;
+    return a < n_blocks ? (int)a : n_blocks;
+}
+__device__ __forceinline__ int64_t scan_length(int64_t n, const SelInfo* info, int rtile) {
+    if (!info || rtile == 0) return n;
+    const int64_t m = 256 * (((int64_t)info->M + rtile - 1) / rtile);
+    return m < n ? m : n;
+}
+
+__global__ __launch_bounds__(256) void scan_chunk_sums_kernel(const uint32_t* __restrict__ data, int64_t n, uint32_t* __restrict__ sums,
+                                                              const SelInfo* __restrict__ info, int pass, int rtile) {
+    if (pass_skipped(info, pass)) return;
+    n = scan_length(n, info, rtile);
+    if ((int64_t)blockIdx.x * SCAN_CHUNK >= n) return;
     int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + threadIdx.x * 8;
     uint32_t c = 0;
     for (int j = 0; j < 8; ++j)
@@ -187,7 +292,10 @@ __global__ __launch_bounds__(256) void scan_chunk_sums_kernel(const uint32_t* __
     if (threadIdx.x == 0) sums[blockIdx.x] = total;
 }
 
-__global__ __launch_bounds__(256) void scan_sums_kernel(uint32_t* __restrict__ sums, int n_chunks) {
+__global__ __launch_bounds__(256) void scan_sums_kernel(uint32_t* __restrict__ sums, int n_chunks, int64_t n, const SelInfo* __restrict__ info, int pass,
+                                                        int rtile) {
+    if (pass_skipped(info, pass)) return;
+    n_chunks = (int)((scan_length(n, info, rtile) + SCAN_CHUNK - 1) / SCAN_CHUNK);
     uint32_t carry = 0;
     for (int b0 = 0; b0 < n_chunks; b0 += 256) {
         int i = b0 + threadIdx.x;
@@ -198,7 +306,11 @@ __global__ __launch_bounds__(256) void scan_sums_kernel(uint32_t* __restrict__ s
     }
 }
 
-__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ data, int64_t n, const uint32_t* __restrict__ sums) {
+__global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ data, int64_t n, const uint32_t* __restrict__ sums,
+                                                         const SelInfo* __restrict__ info, int pass, int rtile) {
+    if (pass_skipped(info, pass)) return;
+    n = scan_length(n, info, rtile);
+    if ((int64_t)blockIdx.x * SCAN_CHUNK >= n) return;
     int64_t base = (int64_t)blockIdx.x * SCAN_CHUNK + threadIdx.x * 8;
     uint32_t v[8], c = 0;
     for (int j = 0; j < 8; ++j) {
@@ -217,7 +329,10 @@ __global__ __launch_bounds__(256) void scan_apply_kernel(uint32_t* __restrict__ 
 // per-thread loads cost more than the two launches saved): thread t of the one workgroup owns entries
 // [t * per, (t + 1) * per), all loaded before anything else so that the loads overlap.
 #define SCAN_ONE_LAUNCH_MAX 8192
-__global__ __launch_bounds__(256) void scan_small_kernel(uint32_t* __restrict__ data, int n, int per) {
+__global__ __launch_bounds__(256) void scan_small_kernel(uint32_t* __restrict__ data, int n, int per, const SelInfo* __restrict__ info, int pass,
+                                                         int rtile) {
+    if (pass_skipped(info, pass)) return;
+    n = (int)scan_length(n, info, rtile);
     uint32_t v[32];
     const int base = threadIdx.x * per;
 #pragma unroll
@@ -234,36 +349,37 @@ __global__ __launch_bounds__(256) void scan_small_kernel(uint32_t* __restrict__ 
         }
 }
 
-static void exclusive_scan_u32(hipStream_t s, uint32_t* data, int64_t n, uint32_t* sums) {
+static void exclusive_scan_u32(hipStream_t s, uint32_t* data, int64_t n, uint32_t* sums, const SelInfo* info = nullptr, int pass = 0, int rtile = 0) {
     if (n <= SCAN_ONE_LAUNCH_MAX) {
-        hipLaunchKernelGGL(scan_small_kernel, dim3(1), dim3(256), 0, s, data, (int)n, (int)((n + 255) / 256));
+        hipLaunchKernelGGL(scan_small_kernel, dim3(1), dim3(256), 0, s, data, (int)n, (int)((n + 255) / 256), info, pass, rtile);
         return;
     }
     int n_chunks = (int)((n + SCAN_CHUNK - 1) / SCAN_CHUNK);
-    hipLaunchKernelGGL(scan_chunk_sums_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums);
-    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sums, n_chunks);
-    hipLaunchKernelGGL(scan_apply_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums);
+    hipLaunchKernelGGL(scan_chunk_sums_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums, info, pass, rtile);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(1), dim3(256), 0, s, sums, n_chunks, n, info, pass, rtile);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(n_chunks), dim3(256), 0, s, data, n, sums, info, pass, rtile);
 }
 
 // ---- radix sort passes --------------------------------------------------------------------------------
 
-// table[d * n_blocks + b] = number of elements of block b's tile with digit d (zero for tiles past M)
+// table[d * tiles + b] = number of elements of block b's tile with digit d, tiles = the tiles that hold pairs (active_tiles)
 template <int RITER>
 __global__ __launch_bounds__(256) void radix_count_kernel(const uint32_t* __restrict__ keys, const SelInfo* __restrict__ info,
                                                           int shift, uint32_t* __restrict__ table, int n_blocks) {
+    if ((uint32_t)(shift >> 3) >= info->n_passes) return;   // the key range does not reach these bits
     __shared__ uint32_t cnt[256];
     cnt[threadIdx.x] = 0u;
     __syncthreads();
     const uint32_t M = info->M;
     constexpr int RTILE = RITER * 256;
     int64_t base = (int64_t)blockIdx.x * RTILE;
-    if (base < M)
-        for (int j = 0; j < RITER; ++j) {
-            int64_t i = base + j * 256 + threadIdx.x;
-            if (i < M) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u);
-        }
+    if (base >= M) return;   // the table only has columns for tiles that hold pairs
+    for (int j = 0; j < RITER; ++j) {
+        int64_t i = base + j * 256 + threadIdx.x;
+        if (i < M) atomicAdd(&cnt[(keys[i] >> shift) & 255u], 1u);
+    }
     __syncthreads();
-    table[(int64_t)threadIdx.x * n_blocks + blockIdx.x] = cnt[threadIdx.x];
+    table[(int64_t)threadIdx.x * active_tiles(info, RTILE, n_blocks) + blockIdx.x] = cnt[threadIdx.x];
 }
 
 // table has been exclusive-scanned: table[d * n_blocks + b] = first output slot of digit d in block b.
@@ -282,6 +398,7 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __re
     __shared__ uint32_t cnt[4][256];
     __shared__ uint32_t to_global[256];   // global slot of a digit's first element minus its slot in the tile
     __shared__ uint32_t kbuf[STAGED ? RTILE : 1], ibuf[STAGED ? RTILE : 1];
+    if ((uint32_t)(shift >> 3) >= info->n_passes) return;   // the key range does not reach these bits
     const uint32_t M = info->M;
     const int64_t base = (int64_t)blockIdx.x * RTILE;
     if (base >= M) return;
@@ -305,7 +422,7 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t* __re
             c[w] = cnt[w][threadIdx.x];
             tile_count += c[w];
         }
-        uint32_t run = table[(int64_t)threadIdx.x * n_blocks + blockIdx.x];   // direct: global slots
+        uint32_t run = table[(int64_t)threadIdx.x * active_tiles(info, RTILE, n_blocks) + blockIdx.x];   // direct: global slots
         if (STAGED) {
             const uint32_t in_tile = block_exclusive_scan_256(tile_count, nullptr);
             to_global[threadIdx.x] = run - in_tile;
@@ -364,23 +481,29 @@ __device__ __forceinline__ bool key_to_loss(uint32_t key, float* v) {
     return true;
 }
 
-__global__ __launch_bounds__(256) void topk_emit_kernel(const uint32_t* __restrict__ keys_sorted, const uint32_t* __restrict__ idx_sorted,
-                                                        const float* __restrict__ losses, int64_t k, int32_t* __restrict__ idx_out,
-                                                        float* __restrict__ val_out) {
+// The sorted pairs sit in the first or the second pair of arrays, depending on the number of passes that ran.
+__global__ __launch_bounds__(256) void topk_emit_kernel(const uint32_t* __restrict__ keys_a, const uint32_t* __restrict__ idx_a,
+                                                        const uint32_t* __restrict__ keys_b, const uint32_t* __restrict__ idx_b,
+                                                        const SelInfo* __restrict__ info, const float* __restrict__ losses, int64_t k,
+                                                        int32_t* __restrict__ idx_out, float* __restrict__ val_out) {
+    const bool second = (info->n_passes & 1u) != 0u;
+    const uint32_t* keys_sorted = second ? keys_b : keys_a;
+    const uint32_t* idx_sorted = second ? idx_b : idx_a;
+    const uint32_t hi = info->hi;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < k; r += stride) {
         uint32_t i = idx_sorted[r];
         idx_out[r] = (int32_t)i;
         if (val_out) {
             float v;
-            if (!key_to_loss(~keys_sorted[r], &v)) v = losses[i];
+            if (!key_to_loss(hi - keys_sorted[r], &v)) v = losses[i];
             val_out[r] = v;
         }
     }
 }
 
 struct TopkScratch {
-    uint32_t *hist, *counts, *sums, *table, *keys_a, *idx_a, *keys_b, *idx_b;
+    uint32_t *hist, *hist2, *counts, *sums, *table, *keys_a, *idx_a, *keys_b, *idx_b;
     SelInfo* info;
     int n_blocks;    // selection tiles (TILE elements)
     int r_iter;      // rounds per wave in the radix passes (8 or 16)
@@ -392,7 +515,8 @@ static TopkScratch carve_topk(Carver& c, int64_t N) {
     t.n_blocks = (int)((N + TILE - 1) / TILE);
     t.r_iter = N >= (int64_t(1) << 22) ? 16 : 8;
     t.r_blocks = (int)((N + t.r_iter * 256 - 1) / (t.r_iter * 256));
-    t.hist = c.take<uint32_t>(SEL_BINS);
+    t.hist = c.take<uint32_t>(2 * SEL_BINS);   // both levels, cleared together
+    t.hist2 = t.hist + SEL_BINS;
     t.info = c.take<SelInfo>(1);
     t.counts = c.take<uint32_t>(t.n_blocks);
     t.table = c.take<uint32_t>((size_t)256 * t.r_blocks);
@@ -418,18 +542,26 @@ static int launch_topk_large(bls_ctx* ctx, char* scratch_base, const float* loss
     TopkScratch t = carve_topk(c, N);
     hipStream_t s = ctx->stream;
     const int nb = t.n_blocks, rb = t.r_blocks;
-    int hist_blocks = nb < ctx->num_cus * 8 ? nb : ctx->num_cus * 8;
-    hipLaunchKernelGGL(zero_u32_kernel, dim3(8), dim3(256), 0, s, t.hist, (int64_t)SEL_BINS);
-    hipLaunchKernelGGL(sel_hist_kernel, dim3(hist_blocks), dim3(256), 0, s, losses, N, t.hist);
-    hipLaunchKernelGGL(sel_threshold_kernel, dim3(1), dim3(256), 0, s, t.hist, (uint32_t)k, t.info);
-    hipLaunchKernelGGL(sel_count_kernel, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts);
+    const int64_t quads = (N + 3) / 4;
+    int hist_blocks = (int)((quads + 255) / 256 < ctx->num_cus * 8 ? (quads + 255) / 256 : ctx->num_cus * 8);
+    const bool vec = reinterpret_cast<uintptr_t>(losses) % 16 == 0;   // 16-byte loads where the array allows them
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(16), dim3(256), 0, s, t.hist, (int64_t)2 * SEL_BINS);
+    if (vec) hipLaunchKernelGGL((sel_hist_kernel<1, true>), dim3(hist_blocks), dim3(256), 0, s, losses, N, t.info, t.hist);
+    else hipLaunchKernelGGL((sel_hist_kernel<1, false>), dim3(hist_blocks), dim3(256), 0, s, losses, N, t.info, t.hist);
+    hipLaunchKernelGGL(sel_threshold_kernel<1>, dim3(1), dim3(256), 0, s, t.hist, (uint32_t)k, t.info);
+    if (vec) hipLaunchKernelGGL((sel_hist_kernel<2, true>), dim3(hist_blocks), dim3(256), 0, s, losses, N, t.info, t.hist2);
+    else hipLaunchKernelGGL((sel_hist_kernel<2, false>), dim3(hist_blocks), dim3(256), 0, s, losses, N, t.info, t.hist2);
+    hipLaunchKernelGGL(sel_threshold_kernel<2>, dim3(1), dim3(256), 0, s, t.hist2, (uint32_t)k, t.info);
+    if (vec) hipLaunchKernelGGL(sel_count_kernel<true>, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts);
+    else hipLaunchKernelGGL(sel_count_kernel<false>, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts);
     exclusive_scan_u32(s, t.counts, nb, t.sums);
-    hipLaunchKernelGGL(sel_compact_kernel, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts, t.keys_a, t.idx_a);
+    if (vec) hipLaunchKernelGGL(sel_compact_kernel<true>, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts, t.keys_a, t.idx_a);
+    else hipLaunchKernelGGL(sel_compact_kernel<false>, dim3(nb), dim3(256), 0, s, losses, N, t.info, t.counts, t.keys_a, t.idx_a);
     uint32_t *ka = t.keys_a, *ia = t.idx_a, *kb = t.keys_b, *ib = t.idx_b;
     for (int pass = 0; pass < 4; ++pass) {
         if (t.r_iter == 16) hipLaunchKernelGGL(radix_count_kernel<16>, dim3(rb), dim3(256), 0, s, ka, t.info, pass * 8, t.table, rb);
         else hipLaunchKernelGGL(radix_count_kernel<8>, dim3(rb), dim3(256), 0, s, ka, t.info, pass * 8, t.table, rb);
-        exclusive_scan_u32(s, t.table, (int64_t)256 * rb, t.sums);
+        exclusive_scan_u32(s, t.table, (int64_t)256 * rb, t.sums, t.info, pass, t.r_iter * 256);
         if (t.r_iter == 16)
             hipLaunchKernelGGL(radix_scatter_kernel<16>, dim3(rb), dim3(256), 0, s, ka, ia, kb, ib, t.info, pass * 8, t.table, rb);
         else
@@ -439,7 +571,7 @@ static int launch_topk_large(bls_ctx* ctx, char* scratch_base, const float* loss
     }
     int64_t eb = (k + 255) / 256;
     if (eb > 2048) eb = 2048;
-    hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)eb), dim3(256), 0, s, ka, ia, losses, k, idx_out, val_out);
+    hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)eb), dim3(256), 0, s, t.keys_a, t.idx_a, t.keys_b, t.idx_b, t.info, losses, k, idx_out, val_out);
     BLS_HIP(ctx, hipGetLastError());
     return BLS_OK;
 }
