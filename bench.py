@@ -23,11 +23,11 @@ sys.path.insert(0, ROOT)
 # dispatch averaged over all launches of a bench run), each scaled by what the same counter reads for a plain
 # 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
 MEASURED_TRAFFIC = {
-    "wgrad_kernel": {"fetch_kib": 5266.7, "fetch_scale": 2.0, "write_kib": 4608.0, "write_scale": 1.0,
-                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "8b326a228c1421c2"},
+    "wgrad_kernel": {"fetch_kib": 5267.8, "fetch_scale": 2.0, "write_kib": 4608.0, "write_scale": 1.0,
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "c291a74d16e7b162"},
     # launch-weighted mean over the 18 input-gradient launches of a local step
-    "conv_kernel (input-gradient launches)": {"fetch_kib": 14979.3, "fetch_scale": 2.0, "write_kib": 12224.2, "write_scale": 1.0,
-                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "8b326a228c1421c2"},
+    "conv_kernel (input-gradient launches)": {"fetch_kib": 14987.5, "fetch_scale": 2.0, "write_kib": 12224.2, "write_scale": 1.0,
+                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "c291a74d16e7b162"},
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
