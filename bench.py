@@ -98,6 +98,9 @@ def main():
                          "256 MiB in, 256 MiB out) three times: the reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the workload step, time top-k and aggregation stand-alone over a range of sizes")
+    ap.add_argument("--topk-n", type=int, default=0,
+                    help="instead of the workload step, run top-k alone on one pool of this size (k = N/4, three calls and a plain "
+                         "256 MiB copy for the counter scale): the program behind the top-k profiles")
     ap.add_argument("--round-mode", default=None, choices=["sequential", "2 lanes", "4 lanes", "8 lanes", "batched"],
                     help="with --round: time only this way of running the workers (for profiles)")
     ap.add_argument("--round", action="store_true",
@@ -108,6 +111,8 @@ def main():
         sys.exit("bench.py measures one GPU: the path has no multi-GPU part in this build (run with --gpus 1)")
     if args.sweep:
         return sweep()
+    if args.topk_n:
+        return topk_alone(args.topk_n)
     if args.round:
         return round_lanes(args.round_mode)
 
@@ -418,6 +423,27 @@ def sweep():
         out["aggregate"].append({"P": P, "d": d, "us": round(t * 1e6, 2), "GB/s": round(gbs, 1), "frac_hbm": round(gbs / HBM_PEAK_GBS, 4)})
         del reps_sets
     print(json.dumps(out))
+
+
+def topk_alone(N, calls=3):
+    """Top-k on one pool of N losses (k = N/4, |N(0,1)| + ln 10), `calls` times, then one plain copy of 256 MiB (aggregation of
+    one replica with weight 1) whose FETCH_SIZE / WRITE_SIZE give the scale of the counters; one JSON line."""
+    import math
+    import torch
+    import paper_2508_08540_amd as bls
+    ctx = bls.Context(0)
+    torch.manual_seed(250808540)
+    k = N // 4
+    a = torch.randn(N, device="cuda").abs_() + math.log(10.0)
+    idx = torch.empty(k, dtype=torch.int32, device="cuda")
+    val = torch.empty(k, dtype=torch.float32, device="cuda")
+    bls.topk_by_loss(ctx, a, k, idx, val)   # sizes the workspace
+    t = _time_calls(torch, lambda i=0: bls.topk_by_loss(ctx, a, k, idx, val), calls)
+    src, dst = torch.ones(1 << 26, device="cuda"), torch.empty(1 << 26, device="cuda")
+    bls.weighted_aggregate(ctx, [src], [1.0], dst)
+    torch.cuda.synchronize()
+    print(json.dumps({"metric": "top-k alone", "N": N, "k": k, "us": round(t * 1e6, 2), "algorithmic_bytes": 4 * N + 8 * k,
+                      "GB/s": round((4 * N + 8 * k) / t / 1e9, 2)}))
 
 
 def round_lanes(only=None):

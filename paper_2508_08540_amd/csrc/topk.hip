@@ -543,7 +543,11 @@ static int launch_topk_large(bls_ctx* ctx, char* scratch_base, const float* loss
     hipStream_t s = ctx->stream;
     const int nb = t.n_blocks, rb = t.r_blocks;
     const int64_t quads = (N + 3) / 4;
-    int hist_blocks = (int)((quads + 255) / 256 < ctx->num_cus * 8 ? (quads + 255) / 256 : ctx->num_cus * 8);
+    // Histogram workgroups per compute unit: each one clears and folds its LDS bins and adds every non-empty bin to the global
+    // histogram (all 2048 of them on the second level), which outweighs the shorter rounds of a finer grid below 2^25 keys
+    // (measured, N = 2^20 / 2^24 / 2^26: 118 / 282 / 869 us with two per unit, 133 / 313 / 863 us with eight).
+    const int per_cu = N >= (int64_t(1) << 25) ? 8 : 2;
+    int hist_blocks = (int)((quads + 255) / 256 < ctx->num_cus * per_cu ? (quads + 255) / 256 : ctx->num_cus * per_cu);
     const bool vec = reinterpret_cast<uintptr_t>(losses) % 16 == 0;   // 16-byte loads where the array allows them
     hipLaunchKernelGGL(zero_u32_kernel, dim3(16), dim3(256), 0, s, t.hist, (int64_t)2 * SEL_BINS);
     if (vec) hipLaunchKernelGGL((sel_hist_kernel<1, true>), dim3(hist_blocks), dim3(256), 0, s, losses, N, t.info, t.hist);
