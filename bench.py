@@ -23,11 +23,11 @@ sys.path.insert(0, ROOT)
 # dispatch averaged over all launches of a bench run), each scaled by what the same counter reads for a plain
 # 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
 MEASURED_TRAFFIC = {
-    "wgrad_kernel": {"fetch_kib": 5267.8, "fetch_scale": 2.0, "write_kib": 4608.0, "write_scale": 1.0,
-                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "c291a74d16e7b162"},
+    "wgrad_kernel": {"fetch_kib": 5267.9, "fetch_scale": 2.0, "write_kib": 4608.0, "write_scale": 1.0,
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "1b83f04833b4c838"},
     # launch-weighted mean over the 18 input-gradient launches of a local step
-    "conv_kernel (input-gradient launches)": {"fetch_kib": 14987.5, "fetch_scale": 2.0, "write_kib": 12224.2, "write_scale": 1.0,
-                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "c291a74d16e7b162"},
+    "conv_kernel (input-gradient launches)": {"fetch_kib": 12238.4, "fetch_scale": 2.0, "write_kib": 9948.7, "write_scale": 1.0,
+                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "1b83f04833b4c838"},
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
@@ -49,10 +49,10 @@ def resnet_conv_flops(widths, blocks, hw, in_ch):
 def resnet_dgrad_bytes(widths, blocks, hw, batch, elt):
     """Algorithmic bytes of the input-gradient launches of one local step (layers 1 .. L-1), each tensor counted once.
 
-    The launch of layer l reads its upstream gradient, activation and convolution output (it applies the layer's
-    batch-norm backward itself; the top layer reads a finished dy instead), the packed weights, the activation and
-    convolution output of layer l-1 (batch-norm backward sums of that layer) and, for the first layer of a block,
-    the shortcut gradient; it writes dy (plus the masked gradient for the last layer of a block) and dx."""
+    The launch of layer l reads its upstream gradient (as the launch above stored it, behind the layer's ReLU) and the
+    layer's convolution output (it applies the layer's batch-norm backward itself; the top layer reads a finished dy
+    instead), the packed weights, the activation and convolution output of layer l-1 (ReLU mask and batch-norm backward
+    sums of that layer) and, for the first layer of a block, the shortcut gradient; it writes dy and dx."""
     layers, c_prev, h = [], widths[0], hw      # (c_in, c_out, h_in, h_out) of layers 1 .. L-1
     for s, c in enumerate(widths):
         for b in range(blocks):
@@ -64,7 +64,7 @@ def resnet_dgrad_bytes(widths, blocks, hw, batch, elt):
     for i, (c_in, c_out, h_in, h_out) in enumerate(layers):
         out, inn = batch * h_out * h_out * c_out, batch * h_in * h_in * c_in
         conv2, top = i % 2 == 1, i == len(layers) - 1
-        elems = (out if top else 3 * out + out + (out if conv2 else 0)) + 2 * inn + inn + 9 * c_in * c_out
+        elems = (out if top else 2 * out + out) + 2 * inn + inn + 9 * c_in * c_out
         if not conv2:
             elems += batch * h_out * h_out * c_in    # shortcut gradient: the block's output positions, this layer's input channels
         total += elems * elt

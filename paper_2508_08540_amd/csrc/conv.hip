@@ -167,24 +167,22 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
 
 // ---- batch-norm backward of the layer applied while its input gradient stages dy -----------------------------------------
 // s_bw[0..4][c] = sum of g, sum of g * xhat, mean, 1/std, scale of channel c; the expression is bn_bwd_apply_kernel's.
-__device__ __forceinline__ f32x4 bn_bwd4(f32x4 d, f32x4 o, f32x4 v, const float (*s_bw)[64], int c, float inv_count, f32x4& gq) {
+// g is the upstream gradient as the launch of the layer above stored it: already zero where this layer's ReLU is.
+__device__ __forceinline__ f32x4 bn_bwd4(f32x4 g, f32x4 v, const float (*s_bw)[64], int c, float inv_count) {
     f32x4 r;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        float g = o[j] > 0.f ? d[j] : 0.f;
         float xhat = (v[j] - s_bw[2][c + j]) * s_bw[3][c + j];
-        gq[j] = g;
-        r[j] = s_bw[4][c + j] * s_bw[3][c + j] * (g - s_bw[0][c + j] * inv_count - xhat * (s_bw[1][c + j] * inv_count));
+        r[j] = s_bw[4][c + j] * s_bw[3][c + j] * (g[j] - s_bw[0][c + j] * inv_count - xhat * (s_bw[1][c + j] * inv_count));
     }
     return r;
 }
 
-// Stages dy = batch-norm backward of (dout, out, y) for the tile, zero outside the image; the rows that are not halo are
-// stored to dy_out (and the masked gradient to g_out), every pixel exactly once.
+// Stages dy = batch-norm backward of (dout, y) for the tile, zero outside the image; the rows that are not halo are
+// stored to dy_out, every pixel exactly once.
 template <typename T, int CIN, int THREADS>
-__device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ dout, const T* __restrict__ out,
-                                                const T* __restrict__ y, const ConvGeom& g, int tile, const float (*s_bw)[64], float inv_count,
-                                                T* __restrict__ dy_out, T* __restrict__ g_out) {
+__device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ dout, const T* __restrict__ y,
+                                                const ConvGeom& g, int tile, const float (*s_bw)[64], float inv_count, T* __restrict__ dy_out) {
     typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = clog2(CQ);
@@ -202,7 +200,7 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
         const int64_t colo = (int64_t)(wok ? (g.ups ? wi >> 1 : wi) : 0) * CIN + cq * 4;
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
         for (int r0 = 0; r0 < rows_total; r0 += R) {
-            raw4 vd[R], vo[R], vy[R];
+            raw4 vd[R], vy[R];
             int64_t at[R];
             bool ok[R], inner[R];
 #pragma unroll
@@ -215,10 +213,9 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
                 ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok && !(g.ups && (hi & 1));
                 inner[r] = li >= g.pad && li < g.pad + rpi;
                 at[r] = ((int64_t)n * src_h + (g.ups ? hi >> 1 : hi)) * src_h * CIN + colo;
-                vd[r] = vo[r] = vy[r] = Act<T>::zero();
+                vd[r] = vy[r] = Act<T>::zero();
                 if (ok[r]) {
                     vd[r] = Act<T>::load_raw(dout + at[r]);
-                    vo[r] = Act<T>::load_raw(out + at[r]);
                     vy[r] = Act<T>::load_raw(y + at[r]);
                 }
             }
@@ -227,14 +224,10 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
                 if (r0 + r < rows_total) {
                     raw4 o = Act<T>::zero();
                     if (ok[r]) {
-                        f32x4 gq;
-                        const f32x4 t = bn_bwd4(Act<T>::widen(vd[r]), Act<T>::widen(vo[r]), Act<T>::widen(vy[r]), s_bw, cq * 4, inv_count, gq);
+                        const f32x4 t = bn_bwd4(Act<T>::widen(vd[r]), Act<T>::widen(vy[r]), s_bw, cq * 4, inv_count);
                         if constexpr (sizeof(T) == 4) o = t;
                         else o = Act<T>::narrow(t);
-                        if (inner[r]) {
-                            *reinterpret_cast<raw4*>(dy_out + at[r]) = o;
-                            if (g_out) Act<T>::store4(g_out + at[r], gq);
-                        }
+                        if (inner[r]) *reinterpret_cast<raw4*>(dy_out + at[r]) = o;
                     }
                     dst[(r0 + r) * g.lw * CP4] = o;
                 }
@@ -249,10 +242,9 @@ __device__ __forceinline__ void epi_at(ConvEpi& e, int64_t ro) {
     e.in_sums = rep_at(e.in_sums, ro); e.in_mean = rep_at(e.in_mean, ro); e.in_invstd = rep_at(e.in_invstd, ro);
     e.in_rmean = rep_at(e.in_rmean, ro); e.in_rvar = rep_at(e.in_rvar, ro); e.in_gamma = rep_at(e.in_gamma, ro); e.in_beta = rep_at(e.in_beta, ro);
     e.in_res = rep_at(e.in_res, ro); e.a_out = rep_at(e.a_out, ro);
-    e.bw_dout = rep_at(e.bw_dout, ro); e.bw_out = rep_at(e.bw_out, ro); e.bw_y = rep_at(e.bw_y, ro); e.bw_mean = rep_at(e.bw_mean, ro);
+    e.bw_dout = rep_at(e.bw_dout, ro); e.bw_y = rep_at(e.bw_y, ro); e.bw_mean = rep_at(e.bw_mean, ro);
     e.bw_invstd = rep_at(e.bw_invstd, ro); e.bw_gamma = rep_at(e.bw_gamma, ro); e.bw_sums = rep_at(e.bw_sums, ro);
     e.bw_dgamma = rep_at(e.bw_dgamma, ro); e.bw_dbeta = rep_at(e.bw_dbeta, ro); e.bw_dy_out = rep_at(e.bw_dy_out, ro);
-    e.bw_g_out = rep_at(e.bw_g_out, ro);
 }
 
 template <typename T, int CIN, int MT, int NW, int EPI>
@@ -351,15 +343,18 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
                     // gradient that bypassed the block below through its shortcut (zero when there is none)
                     v += Act<T>::widen(pre_s[m]);
                     v = Act<T>::rounded(v);  // the sums below see what later kernels read back
-                    Act<T>::store4(y + p * NO + c0, v);
                     const f32x4 av = Act<T>::widen(pre_a[m]);
                     const f32x4 yv = Act<T>::widen(pre_y[m]);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float gq = av[j] > 0.f ? v[j] : 0.f;
+                        v[j] = gq;
                         ssum[j] += gq;
                         ssq[j] = __fmaf_rn(gq, (yv[j] - ch_mu[j]) * ch_is[j], ssq[j]);
                     }
+                    // what goes out is the gradient behind the ReLU of the layer below: that layer's batch-norm backward, its
+                    // block's shortcut and nothing else read it, and none of them has to look the activation up again
+                    Act<T>::store4(y + p * NO + c0, v);
                 } else if (EPI == 3) {
                     // inference: batch norm with running statistics, shortcut, ReLU
                     f32x4 r = {0.f, 0.f, 0.f, 0.f};
@@ -499,8 +494,8 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
     } else {
         for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
             if constexpr (XF == 3)
-                stage_input_bwd<T, CIN, NW * 64>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_out), static_cast<const T*>(e.bw_y), g,
-                                                 tile, s_bn, e.bw_inv_count, static_cast<T*>(e.bw_dy_out), static_cast<T*>(e.bw_g_out));
+                stage_input_bwd<T, CIN, NW * 64>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_y), g, tile, s_bn, e.bw_inv_count,
+                                                 static_cast<T*>(e.bw_dy_out));
             else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out, e.in_res_c, e.in_res_lo, e.in_res_stride);
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();

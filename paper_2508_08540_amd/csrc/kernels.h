@@ -177,7 +177,8 @@ void launch_pack_weights(hipStream_t s, int act, const float* params, void* pack
 struct ConvEpi {
     fixsum_t* sums;
     double scale;
-    // input gradient: shortcut gradient to add (sc_g may be nullptr), then batch-norm backward sums of the layer below
+    // input gradient: shortcut gradient to add (sc_g may be nullptr), then the ReLU of the layer below (the output is stored
+    // with zeros where a_prev is zero: the gradient behind that ReLU), then batch-norm backward sums of the layer below
     const void* sc_g;  // activations (storage type of the launch)
     int sc_c, sc_lo, sc_stride;
     const void *a_prev, *y_prev;  // activations
@@ -197,15 +198,16 @@ struct ConvEpi {
     int in_res_c, in_res_lo, in_res_stride;   // x's channels in_res_lo .. (zeros elsewhere), read at every in_res_stride-th pixel
     void* a_out;
     // input gradient with bw_dout != nullptr (stride-1 layers): the launch's input dy does not exist yet.  The kernel computes
-    // it while staging, as bn_bwd_apply does, from the gradient bw_dout of the layer's activation bw_out, the layer's
-    // convolution output bw_y, its statistics and the backward sums bw_sums [2][C] (workgroup 0 stores the scale and shift
-    // gradients), and stores it to bw_dy_out for the weight gradient; bw_g_out (optional) takes dout * (out > 0).
-    const void *bw_dout, *bw_out, *bw_y;
+    // it while staging, as bn_bwd_apply does, from the gradient bw_dout behind the layer's ReLU (zero where the activation
+    // is: the input-gradient launch of the layer above stored it that way), the layer's convolution output bw_y, its
+    // statistics and the backward sums bw_sums [2][C] (workgroup 0 stores the scale and shift gradients), and stores it to
+    // bw_dy_out for the weight gradient.
+    const void *bw_dout, *bw_y;
     const float *bw_mean, *bw_invstd, *bw_gamma;
     const fixsum_t* bw_sums;
     float *bw_dgamma, *bw_dbeta;
     float bw_inv_count;
-    void *bw_dy_out, *bw_g_out;
+    void* bw_dy_out;
 };
 int conv_fwd_tiles(const ConvShape& cs);
 // x, y, dy, dx are activations of storage type `act`.  In the three launchers below `w` is the packed copy (forward form for fwd, input-gradient form for dgrad).

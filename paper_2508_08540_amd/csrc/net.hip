@@ -286,6 +286,11 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
     const ConvBn& last = m->layers[L - 1];
     const void* dout = s.dfeat;
     int shared = last.h_out * last.h_out;
+    // Every input-gradient launch stores the gradient behind the ReLU of the layer below (zero where that activation is).
+    // The one a block's second convolution receives is also the gradient of the block's shortcut: `block_g` keeps it until
+    // the input-gradient launch of the block's first convolution has added it, so the three tensors rotate.
+    act_t* const ring[3] = {s.d1, s.d2, s.g};
+    const void* block_g = nullptr;
     for (int l = L - 1; l >= 0; --l) {
         const ConvBn& cb = m->layers[l];
         ConvShape cs = shape_of(cb, B);
@@ -311,15 +316,20 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(side, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt, s.reps));
             return BLS_OK;
         };
+        if (is_conv2 && !shared) block_g = dout;   // as stored by the launch of the layer above
         if (!fused_bwd) {
+            // the head's gradient is one row per sample: the element-wise kernel leaves the gradient behind the ReLU as a tensor
+            act_t* g_out = (is_conv2 && shared) ? s.g : nullptr;
             PROF(ctx, PROF_NORM, launch_bn_bwd_apply(st, s.act, dout, shared, s.a[l], s.y[l], pixels, cb.c_out, s.mean[l], s.invstd[l], params + cb.gamma_off,
-                                s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], is_conv2 ? s.g : nullptr,
-                                nullptr, s.reps));
+                                s.sums + ((size_t)l * 2 + 1) * FIX_SET, s.grad + cb.gamma_off, s.grad + cb.beta_off, s.dy[l], g_out, nullptr, s.reps));
+            if (g_out) block_g = g_out;
             int rcw = weight_gradient();
             if (rcw != BLS_OK) return rcw;
         }
         if (l == 0) break;
-        act_t* dx = dout == s.d2 ? s.d1 : s.d2;   // never the tensor the fused staging reads
+        act_t* dx = nullptr;   // neither the tensor the fused staging reads nor the shortcut gradient still to be added
+        for (act_t* cand : ring)
+            if (cand != dout && cand != block_g) dx = cand;
         {
             // input gradient; its epilogue adds the shortcut gradient (conv1 of a block) and reduces the
             // batch-norm backward sums of layer l-1
@@ -329,15 +339,15 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             e.a_prev = s.a[l - 1]; e.y_prev = s.y[l - 1]; e.mean_prev = s.mean[l - 1]; e.invstd_prev = s.invstd[l - 1];
             if (!is_conv2) {
                 const ConvBn& c2 = m->layers[l + 1];
-                e.sc_g = s.g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
+                e.sc_g = block_g; e.sc_c = c2.c_out; e.sc_lo = (c2.c_out - cb.c_in) / 2; e.sc_stride = cb.stride;
             }
             if (fused_bwd) {
-                e.bw_dout = dout; e.bw_out = s.a[l]; e.bw_y = s.y[l];
+                e.bw_dout = dout; e.bw_y = s.y[l];
                 e.bw_mean = s.mean[l]; e.bw_invstd = s.invstd[l]; e.bw_gamma = params + cb.gamma_off;
                 e.bw_sums = s.sums + ((size_t)l * 2 + 1) * FIX_SET;
                 e.bw_dgamma = s.grad + cb.gamma_off; e.bw_dbeta = s.grad + cb.beta_off;
                 e.bw_inv_count = 1.f / (float)pixels;
-                e.bw_dy_out = s.dy[l]; e.bw_g_out = is_conv2 ? s.g : nullptr;
+                e.bw_dy_out = s.dy[l];
             }
             PROF_KERNEL(ctx, PROF_CONV_DGRAD, launch_conv_dgrad(st, s.act, cs, s.dy[l], s.wpack + s.dgrad_off[l], dx, &e, kt, s.reps));
         }
@@ -345,6 +355,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             int rcw = weight_gradient();   // dy[l] exists once the input gradient has run
             if (rcw != BLS_OK) return rcw;
         }
+        if (!is_conv2) block_g = nullptr;   // added by this launch
         dout = dx;
         shared = 0;
     }
