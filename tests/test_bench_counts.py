@@ -27,13 +27,13 @@ def test_input_gradient_bytes_by_enumeration():
     t = lambda c, h: B * h * h * c
     total = 0
     # block 1 (16 -> 16 at 8x8): first layer of the block
-    total += 3 * t(16, 8) + t(16, 8) + 3 * t(16, 8) + 9 * 16 * 16 + t(16, 8)        # dout,a,y | dy | a',y',dx | w | shortcut grad
-    # block 1: second layer (writes the masked gradient as well)
-    total += 3 * t(16, 8) + 2 * t(16, 8) + 3 * t(16, 8) + 9 * 16 * 16
+    total += 2 * t(16, 8) + t(16, 8) + 3 * t(16, 8) + 9 * 16 * 16 + t(16, 8)        # dout,y | dy | a',y',dx | w | shortcut grad
+    # block 1: second layer (the gradient it receives doubles as the shortcut gradient: nothing extra is written)
+    total += 2 * t(16, 8) + t(16, 8) + 3 * t(16, 8) + 9 * 16 * 16
     # block 2 (16 -> 32, stride 2): first layer; its shortcut gradient covers the block's 4x4 output positions, 16 channels
-    total += 3 * t(32, 4) + t(32, 4) + 3 * t(16, 8) + 9 * 16 * 32 + B * 4 * 4 * 16
-    total += 3 * t(32, 4) + 2 * t(32, 4) + 3 * t(32, 4) + 9 * 32 * 32
+    total += 2 * t(32, 4) + t(32, 4) + 3 * t(16, 8) + 9 * 16 * 32 + B * 4 * 4 * 16
+    total += 2 * t(32, 4) + t(32, 4) + 3 * t(32, 4) + 9 * 32 * 32
     # block 3 (32 -> 64, stride 2); the top layer reads a finished dy instead of computing it
-    total += 3 * t(64, 2) + t(64, 2) + 3 * t(32, 4) + 9 * 32 * 64 + B * 2 * 2 * 32
+    total += 2 * t(64, 2) + t(64, 2) + 3 * t(32, 4) + 9 * 32 * 64 + B * 2 * 2 * 32
     total += t(64, 2) + 3 * t(64, 2) + 9 * 64 * 64
     assert b.resnet_dgrad_bytes((16, 32, 64), 1, 8, B, elt) == total * elt
