@@ -24,8 +24,10 @@
  *   - Results are bit-reproducible run to run (no floating-point atomics).  Sums over a whole batch that many
  *     workgroups contribute to (batch-norm statistics, the two sums of the batch-norm backward pass, convolution
  *     weight gradients, token-embedding gradients) are accumulated as 64-bit fixed-point integers, which bounds what one
- *     workgroup may contribute (bls_sum_limits): 2^24 to a forward sum (the sum of squares of 256 convolution outputs,
- *     i.e. an rms below 256 per tile), 2^9 to a backward sum, 2^13 to a weight-gradient sum.  A contribution beyond its
+ *     tile of a launch may contribute (bls_sum_limits): 2^24 to a forward sum (the sum of squares of 256 convolution
+ *     outputs, i.e. an rms below 256 per tile), 2^9 to a backward sum, 2^13 to a weight-gradient sum; convolution
+ *     launches of more than 2048 tiles (batches above 512 images of 32 x 32) halve the first two with every doubling
+ *     of the tile count.  A contribution beyond its
  *     limit, or one that is not finite, does not wrap around and is not dropped: the sum becomes NaN, and with it the
  *     statistics, gradients, parameters and every later loss, as an overflow in floating point would end.  Inputs
  *     normalised to unit scale (the convention of the paper's image pipelines) stay four orders of magnitude below
@@ -351,9 +353,9 @@ int train_epochs(bls_ctx* ctx, const bls_model* model, const bls_epoch_plan* pla
                  float* worker_params, float* worker_buffers, float* worker_momentum, const void* x_pool, const int32_t* y_pool,
                  int64_t N, const float* u_fast, const float* u_slow, float* loss_table, int32_t* idx_work, int64_t* rounds_out);
 
-/* Largest magnitude one workgroup may add to a forward statistic (sum or sum of squares of its tile of a convolution
- * output), to a batch-norm backward sum, and to a weight-gradient sum (see the conventions at the top); any pointer may
- * be NULL.  Host only. */
+/* Largest magnitude one tile may add to a forward statistic (sum or sum of squares of a tile of a convolution output),
+ * to a batch-norm backward sum, and one workgroup to a weight-gradient sum (see the conventions at the top); any pointer
+ * may be NULL.  Host only. */
 int bls_sum_limits(double* forward_partial, double* backward_partial, double* weight_gradient_partial);
 
 /* w_i = tau_i / sum_j tau_j (Eq. 4), computed in double and rounded once.  Host only. */

@@ -398,7 +398,8 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
 // XF 1, 2: the input is the raw convolution output of the layer below; its batch norm (XF == 2: plus an identity
 // shortcut) and ReLU are applied while staging (ConvEpi::in_sums and the fields after it).  XF 3 (input gradient): the
 // input dy is computed while staging, by the layer's batch-norm backward (ConvEpi::bw_dout and the fields after it).
-template <typename T, int CIN, int MT, int NW, int EPI, int XF>
+// MULTI: a workgroup may own several tiles; the sums of the epilogue are then folded and converted tile by tile.
+template <typename T, int CIN, int MT, int NW, int EPI, int XF, bool MULTI>
 __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
                                                             T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined, int64_t rstride) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
@@ -474,6 +475,39 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             for (int s = 0; s < S; ++s) wr[t][s] = wp[(t * S + s) * 64];
     }
     f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
+    // Per-channel sums of the epilogue (EPI 1, 2): after every tile the waves fold their lanes (fixed shuffle tree) into
+    // red[parity], and after the next barrier thread (which, c) adds the waves in wave order, converts the tile's partial to
+    // fixed point and keeps the integer sum; one atomic per thread leaves the workgroup at the end.
+    __shared__ float red[2][NW * 2 * 16];
+    long long fx_sum = 0;
+    bool fx_poisoned = false;
+    auto fold_write = [&](int par) {
+        // lanes of one group hold the same 4 channels for 16 different pixels: fold the pixels
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                ssum[j] += __shfl_xor(ssum[j], o, 64);
+                ssq[j] += __shfl_xor(ssq[j], o, 64);
+            }
+        if (r16 == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                red[par][(wave * 2 + 0) * 16 + 4 * grp + j] = ssum[j];
+                red[par][(wave * 2 + 1) * 16 + 4 * grp + j] = ssq[j];
+            }
+        }
+        ssum = ssq = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto fold_read = [&](int par) {
+        if (threadIdx.x < 2 * NO) {
+            const int which = threadIdx.x / NO, c = threadIdx.x % NO;
+            const int cb = c >> 4;
+            float acc = 0.f;
+            for (int wv = cb; wv < NW; wv += NOB) acc += red[par][(wv * 2 + which) * 16 + (c & 15)];
+            fixsum_collect(fx_sum, fx_poisoned, (double)acc * e.scale, e.tile_limit);
+        }
+    };
 
     // the transforming variants stage without prefetching: their launches have at most one or two tiles per workgroup
     // at the batch sizes of a local step, and the prefetch registers would cost them a wave of occupancy
@@ -488,11 +522,14 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             const int next = tile + gridDim.x;
             if (next < g.n_tiles) tile_load<T, CIN>(pre, x, g, next);
             conv_tile<T, CIN, MT, NW, EPI>(lds4 + (it & 1) * buf_f4, wr, y, e, g, tile, ssum, ssq);
+            if (MULTI && (EPI == 1 || EPI == 2)) fold_write(it & 1);
             if (next < g.n_tiles) tile_store<T, CIN>(pre, lds4 + ((it + 1) & 1) * buf_f4, g);
             __syncthreads();
+            if (MULTI && (EPI == 1 || EPI == 2)) fold_read(it & 1);
         }
     } else {
-        for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x) {
+        int it = 0;
+        for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x, ++it) {
             if constexpr (XF == 3)
                 stage_input_bwd<T, CIN, NW * 64>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_y), g, tile, s_bn, e.bw_inv_count,
                                                  static_cast<T*>(e.bw_dy_out));
@@ -500,50 +537,49 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();
             conv_tile<T, CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
+            if (MULTI && (EPI == 1 || EPI == 2)) fold_write(it & 1);
             __syncthreads();
+            if (MULTI && (EPI == 1 || EPI == 2)) fold_read(it & 1);   // the next write into this half of red is two barriers away
         }
     }
 
-    if (EPI == 1 || EPI == 2) {
-        // lanes of one group hold the same 4 channels for 16 different pixels: fold the pixels
-#pragma unroll
-        for (int o = 1; o < 16; o <<= 1)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                ssum[j] += __shfl_xor(ssum[j], o, 64);
-                ssq[j] += __shfl_xor(ssq[j], o, 64);
-            }
-        float* red = lds;  // [wave][2][16]; every wave is past its last tile read (barrier above)
-        if (r16 == 0) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                red[(wave * 2 + 0) * 16 + 4 * grp + j] = ssum[j];
-                red[(wave * 2 + 1) * 16 + 4 * grp + j] = ssq[j];
-            }
-        }
+    if (!MULTI && (EPI == 1 || EPI == 2)) {   // one tile: its sums are still in the lanes
+        fold_write(0);
         __syncthreads();
-        if (threadIdx.x < 2 * NO) {
-            int which = threadIdx.x / NO, c = threadIdx.x % NO;
-            int cb = c >> 4;
-            float acc = 0.f;
-            for (int wv = cb; wv < NW; wv += NOB) acc += red[(wv * 2 + which) * 16 + (c & 15)];
-            // order-independent accumulation across workgroups: 64-bit fixed point, integer atomic add
-            // at most CONV_GRID_CAP / FIX_REPLICAS = 32 workgroups add to one word
-            fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + c, (double)acc * e.scale, 2.0 * FIX_PARTIAL_LIMIT);
-        }
+        fold_read(0);
+    }
+    // order-independent accumulation across workgroups: 64-bit fixed point, integer atomic add
+    if ((EPI == 1 || EPI == 2) && threadIdx.x < 2 * NO) {
+        const int which = threadIdx.x / NO, c = threadIdx.x % NO;
+        fixsum_flush(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + c, fx_sum, fx_poisoned);
     }
 }
 
-// Workgroups per launch: at most CONV_GRID_CAP (two per compute unit on a 256-CU part; the range of the epilogue's
-// fixed-point sums counts on this cap).
+// Workgroups per launch: at most CONV_GRID_CAP (two per compute unit on a 256-CU part).  With several replicas in one
+// launch the cap is shared: a workgroup then walks several tiles of its replica with one set of weights and one prologue
+// (and, without a transform on load, with the next tile prefetched), which is where launches of 2048 and more one-tile
+// workgroups lost their time.  The sums do not depend on the split (fixsum_collect).
 #define CONV_GRID_CAP 512
-static int conv_grid(const ConvGeom& g) { return g.n_tiles < CONV_GRID_CAP ? g.n_tiles : CONV_GRID_CAP; }
+static int conv_grid(const ConvGeom& g, int replicas) {
+    int cap = CONV_GRID_CAP / (replicas < 1 ? 1 : replicas);
+    if (cap < 1) cap = 1;
+    return g.n_tiles < cap ? g.n_tiles : cap;
+}
+// One tile's scaled partial sum may reach 2^54; a word takes the tiles of n_tiles / FIX_REPLICAS workgroups-worth of them,
+// so beyond 2048 tiles per launch the bound shrinks in proportion and the word still cannot wrap.
+static double conv_tile_limit(const ConvGeom& g) {
+    double limit = 2.0 * FIX_PARTIAL_LIMIT;
+    for (int t = 2048; t < g.n_tiles; t *= 2) limit *= 0.5;
+    return limit;
+}
 
 template <typename T, int CIN, int EPI>
-static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const void* w, T* y, const ConvEpi& e,
+static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const void* w, T* y, const ConvEpi& e_in,
                           const KernelTiming* kt, Reps reps) {
     constexpr int MT = CONV_MT, NW = CONV_NW;
-    const int grid = conv_grid(g);
+    ConvEpi e = e_in;
+    e.tile_limit = conv_tile_limit(g);
+    const int grid = conv_grid(g, reps.n);
     // prefetching needs the whole tile in PRE_ROWS registers per thread, one column per thread, and more
     // than one tile per workgroup to pay off
     bool transforming = false;   // batch norm applied while staging: no prefetching path
@@ -553,12 +589,16 @@ static void launch_conv_t(hipStream_t s, const ConvGeom& g, const T* x, const vo
     const int pipelined = (!transforming && g.imgs * g.in_rows <= PRE_ROWS && g.lw * (CIN / 4 / Tile<T>::VQ) <= NW * 64 && g.n_tiles > grid) ? 1 : 0;
     size_t lds = input_lds_bytes<T, CIN>(g) * (pipelined ? 2 : 1);
     if ((EPI == 1 || EPI == 2) && lds < 1024) lds = 1024;  // per-wave partial sums
-    auto kern = conv_kernel<T, CIN, MT, NW, EPI, 0>;
+    // a workgroup that owns one tile keeps the epilogue's sums in its lanes until the end; one that owns several folds them
+    // tile by tile (inference and plain launches have no sums: one instantiation)
+    const bool multi = (EPI == 1 || EPI == 2) && g.n_tiles > grid;
+    auto kern = multi ? conv_kernel<T, CIN, MT, NW, EPI, 0, true> : conv_kernel<T, CIN, MT, NW, EPI, 0, false>;
     if constexpr (EPI == 1) {
-        if (e.in_sums) kern = e.in_res ? conv_kernel<T, CIN, MT, NW, EPI, 2> : conv_kernel<T, CIN, MT, NW, EPI, 1>;
+        if (e.in_sums && e.in_res) kern = multi ? conv_kernel<T, CIN, MT, NW, EPI, 2, true> : conv_kernel<T, CIN, MT, NW, EPI, 2, false>;
+        else if (e.in_sums) kern = multi ? conv_kernel<T, CIN, MT, NW, EPI, 1, true> : conv_kernel<T, CIN, MT, NW, EPI, 1, false>;
     }
     if constexpr (EPI == 2) {
-        if (fused_bwd) kern = conv_kernel<T, CIN, MT, NW, EPI, 3>;
+        if (fused_bwd) kern = multi ? conv_kernel<T, CIN, MT, NW, EPI, 3, true> : conv_kernel<T, CIN, MT, NW, EPI, 3, false>;
     }
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     // with timing events the dispatch itself is stamped (start and end of this kernel only)

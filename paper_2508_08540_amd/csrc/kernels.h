@@ -36,6 +36,17 @@ __device__ __forceinline__ void fixsum_add(fixsum_t* dst, double scaled, double 
     if (fabs(scaled) < limit) atomicAdd(dst, (fixsum_t)__double2ll_rn(scaled));
     else atomicMax(reinterpret_cast<long long*>(dst), FIX_POISON);   // also taken by NaN
 }
+// The same in two steps for a workgroup that walks several tiles: every tile's partial is converted and range-checked by
+// itself and added up as integers in a register, one atomic goes out at the end.  The word then receives exactly what
+// one workgroup per tile would have added, so the result does not depend on how tiles are dealt to workgroups.
+__device__ __forceinline__ void fixsum_collect(long long& sum, bool& poisoned, double scaled, double limit) {
+    if (fabs(scaled) < limit) sum += __double2ll_rn(scaled);
+    else poisoned = true;   // also taken by NaN
+}
+__device__ __forceinline__ void fixsum_flush(fixsum_t* dst, long long sum, bool poisoned) {
+    if (poisoned) atomicMax(reinterpret_cast<long long*>(dst), FIX_POISON);
+    else atomicAdd(dst, (fixsum_t)sum);
+}
 // ReLU that keeps NaN (the hardware maximum returns the other operand): a poisoned statistic or a diverged weight has to
 // reach the losses instead of being clamped to zero on the way.
 __device__ __forceinline__ float relu_keep_nan(float t) { return t < 0.f ? 0.f : t; }
@@ -177,6 +188,7 @@ void launch_pack_weights(hipStream_t s, int act, const float* params, void* pack
 struct ConvEpi {
     fixsum_t* sums;
     double scale;
+    double tile_limit;   // bound of one tile's scaled partial sum (set by the launcher)
     // input gradient: shortcut gradient to add (sc_g may be nullptr), then the ReLU of the layer below (the output is stored
     // with zeros where a_prev is zero: the gradient behind that ReLU), then batch-norm backward sums of the layer below
     const void* sc_g;  // activations (storage type of the launch)
