@@ -26,7 +26,7 @@
  *     weight gradients, token-embedding gradients) are accumulated as 64-bit fixed-point integers, which bounds what one
  *     tile of a launch may contribute (bls_sum_limits): 2^24 to a forward sum (the sum of squares of 256 convolution
  *     outputs, i.e. an rms below 256 per tile), 2^9 to a backward sum, 2^13 to a weight-gradient sum; convolution
- *     launches of more than 2048 tiles (batches above 512 images of 32 x 32) halve the first two with every doubling
+ *     launches of more than 512 tiles (batches above 128 images of 32 x 32) halve the first two with every doubling
  *     of the tile count.  A contribution beyond its
  *     limit, or one that is not finite, does not wrap around and is not dropped: the sum becomes NaN, and with it the
  *     statistics, gradients, parameters and every later loss, as an overflow in floating point would end.  Inputs

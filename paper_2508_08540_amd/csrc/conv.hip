@@ -565,11 +565,12 @@ static int conv_grid(const ConvGeom& g, int replicas) {
     if (cap < 1) cap = 1;
     return g.n_tiles < cap ? g.n_tiles : cap;
 }
-// One tile's scaled partial sum may reach 2^54; a word takes the tiles of n_tiles / FIX_REPLICAS workgroups-worth of them,
-// so beyond 2048 tiles per launch the bound shrinks in proportion and the word still cannot wrap.
+// One tile's scaled partial sum may reach 2^54 in a launch of up to CONV_GRID_CAP tiles: a word then holds less than 2^59
+// and the sum of its FIX_REPLICAS replicas, which the readers take in 64-bit integers, less than 2^63.  Launches of more
+// tiles lower the bound per tile in proportion (the same rms per tile, as their tiles are smaller or their batches larger).
 static double conv_tile_limit(const ConvGeom& g) {
     double limit = 2.0 * FIX_PARTIAL_LIMIT;
-    for (int t = 2048; t < g.n_tiles; t *= 2) limit *= 0.5;
+    for (int t = CONV_GRID_CAP; t < g.n_tiles; t *= 2) limit *= 0.5;
     return limit;
 }
 
