@@ -729,10 +729,14 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 #define WG_DK 2
 #define WG_PIPE_PIXELS (WGRAD_THREADS / 2)
 
-template <typename T, int TAPS, bool PIPE>
+// MULTI (launches over several replicas): a workgroup takes `groups_per_wg` consecutive pixel groups.  At the end of each
+// it folds and converts its sums exactly as a one-group workgroup does and keeps them as integers in registers, the
+// prefetch of the next tile runs across the boundary, and one set of atomics leaves at the end: the same bits from an
+// eighth of the workgroups, first loads and atomics.
+template <typename T, int TAPS, bool PIPE, bool MULTI>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
-                                                              int NI, int NO, int replicas, int64_t rstride) {
+                                                              int NI, int NO, int replicas, int64_t rstride, int groups_per_wg) {
     if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
         const int64_t ro = (int64_t)blockIdx.z * rstride;
         x = rep_at(x, ro); dy = rep_at(dy, ro); gacc = rep_at(gacc, ro);
@@ -757,9 +761,38 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
 #pragma unroll
     for (int t = 0; t < TAPS; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int tile_begin = blockIdx.x * tiles_per_group;
-    const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
+    const int tile_begin = blockIdx.x * tiles_per_group * (MULTI ? groups_per_wg : 1);
+    const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group * (MULTI ? groups_per_wg : 1));
     typedef typename Act<T>::raw4 raw4;
+    // MULTI: fixed-point sums of the pixel groups finished so far, element threadIdx.x + i * WGRAD_THREADS of the block
+    constexpr int FX = (BLOCK_FLOATS + WGRAD_THREADS - 1) / WGRAD_THREADS;
+    long long fx_sum[MULTI ? FX : 1];
+    bool fx_poisoned = false;
+#pragma unroll
+    for (int i = 0; i < (MULTI ? FX : 1); ++i) fx_sum[i] = 0;
+    // Fold the waves in wave order.  LDS and the partial are lane-major, element (t*4 + j)*64 + lane
+    // holds dW[o = 4*(lane/16) + j][t][i = lane%16] of the block: conflict-free writes, coalesced stores.
+    auto fold_group = [&]() {
+        __syncthreads();   // the tile in LDS is consumed
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                lds[wave * BLOCK_FLOATS + (t * 4 + j) * 64 + lane] = acc[t][j];
+                acc[t][j] = 0.f;
+            }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < FX; ++i) {
+            const int e = threadIdx.x + i * WGRAD_THREADS;
+            if (e < BLOCK_FLOATS) {
+                float v = lds[e];
+#pragma unroll
+                for (int wv = 1; wv < WG_WAVES; ++wv) v += lds[wv * BLOCK_FLOATS + e];
+                fixsum_collect(fx_sum[MULTI ? i : 0], fx_poisoned, (double)v * FIX_WGRAD_SCALE, FIX_PARTIAL_LIMIT);
+            }
+        }
+    };
     // slot k of this thread: element threadIdx.x + k * WGRAD_THREADS of the tile (rows x columns x 4 channel quads)
     int x_dst[WG_XK], x_part[WG_XK], x_li[WG_XK], x_off[WG_XK];
     raw4 xv[WG_XK], dv[WG_DK];
@@ -856,17 +889,24 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
                 }
             }
         }
+        if (MULTI && ((tile + 1 - tile_begin) % tiles_per_group == 0 || tile + 1 == tile_end)) fold_group();   // a pixel group ends here
     }
-    // Fold the four waves in wave order.  LDS and the partial are lane-major, element (t*4 + j)*64 + lane
-    // holds dW[o = 4*(lane/16) + j][t][i = lane%16] of the block: conflict-free writes, coalesced stores.
+    // order-independent accumulation across pixel groups: replicated 64-bit fixed point, integer atomic add
+    fixsum_t* out = gacc + ((int64_t)(blockIdx.x % replicas) * gridDim.y + blockIdx.y) * BLOCK_FLOATS;
+    if (MULTI) {
+#pragma unroll
+        for (int i = 0; i < FX; ++i) {
+            const int e = threadIdx.x + i * WGRAD_THREADS;
+            if (e < BLOCK_FLOATS) fixsum_flush(out + e, fx_sum[i], fx_poisoned);
+        }
+        return;
+    }
     __syncthreads();
 #pragma unroll
     for (int t = 0; t < TAPS; ++t)
 #pragma unroll
         for (int j = 0; j < 4; ++j) lds[wave * BLOCK_FLOATS + (t * 4 + j) * 64 + lane] = acc[t][j];
     __syncthreads();
-    // order-independent accumulation across pixel groups: replicated 64-bit fixed point, integer atomic add
-    fixsum_t* out = gacc + ((int64_t)(blockIdx.x % replicas) * gridDim.y + blockIdx.y) * BLOCK_FLOATS;
     for (int e = threadIdx.x; e < BLOCK_FLOATS; e += WGRAD_THREADS) {
         float v = lds[e];
 #pragma unroll
@@ -1019,14 +1059,18 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
     int groups = wgrad_groups(cs, g.n_tiles);
     int tiles_per_group = (g.n_tiles + groups - 1) / groups;  // trailing groups may be empty and then write zeros
     size_t lds = ((size_t)g.imgs * g.in_rows * g.lw * 16 + (size_t)(g.rows_tile << g.wout_log2) * 16) * sizeof(float);
-    const bool pipe = wgrad_fits_pipe(g) && tiles_per_group > 1;
-    auto kern = pipe ? wgrad_kernel<T, TAPS, true> : wgrad_kernel<T, TAPS, false>;
+    // several replicas in one launch: a workgroup takes as many consecutive pixel groups as there are replicas
+    int groups_per_wg = reps.n > 1 ? (reps.n < groups ? reps.n : groups) : 1;
+    const bool multi = groups_per_wg > 1;
+    const bool pipe = wgrad_fits_pipe(g) && tiles_per_group * groups_per_wg > 1;
+    auto kern = multi ? (pipe ? wgrad_kernel<T, TAPS, true, true> : wgrad_kernel<T, TAPS, false, true>)
+                      : (pipe ? wgrad_kernel<T, TAPS, true, false> : wgrad_kernel<T, TAPS, false, false>);
     if (lds < WG_WAVES * 16 * TAPS * 16 * sizeof(float)) lds = WG_WAVES * 16 * TAPS * 16 * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
-    hipExtLaunchKernelGGL(kern, dim3(groups, blocks, reps.n), dim3(WGRAD_THREADS), lds, s, kt ? kt->start : nullptr,
-                          kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out, groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS,
-                          reps.stride);
+    hipExtLaunchKernelGGL(kern, dim3((groups + groups_per_wg - 1) / groups_per_wg, blocks, reps.n), dim3(WGRAD_THREADS), lds, s,
+                          kt ? kt->start : nullptr, kt ? kt->stop : nullptr, 0, x, dy, gacc, g, tiles_per_group, cs.c_in, cs.c_out,
+                          groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS, reps.stride, groups_per_wg);
 }
 
 void launch_conv_wgrad(hipStream_t s, int act, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc,
