@@ -726,6 +726,7 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 // PIPE: a thread owns up to WG_XK fixed 4-channel slots of the x tile and WG_DK of the dy tile; the next tile's slots are
 // loaded into registers while the current tile multiplies (tiles small enough for that, see wgrad_geom).
 #define WG_XK 4
+#define WG_XK_STRIDE2 10   // stride-2 layers stage (2 rows + 1) x (2 columns + 2) input pixels per output pixel
 #define WG_DK 2
 #define WG_PIPE_PIXELS (WGRAD_THREADS / 2)
 
@@ -733,7 +734,7 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 // it folds and converts its sums exactly as a one-group workgroup does and keeps them as integers in registers, the
 // prefetch of the next tile runs across the boundary, and one set of atomics leaves at the end: the same bits from an
 // eighth of the workgroups, first loads and atomics.
-template <typename T, int TAPS, bool PIPE, bool MULTI>
+template <typename T, int TAPS, bool PIPE, bool MULTI, int XK = WG_XK>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
                                                               int NI, int NO, int replicas, int64_t rstride, int groups_per_wg) {
@@ -794,12 +795,12 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
         }
     };
     // slot k of this thread: element threadIdx.x + k * WGRAD_THREADS of the tile (rows x columns x 4 channel quads)
-    int x_dst[WG_XK], x_part[WG_XK], x_li[WG_XK], x_off[WG_XK];
-    raw4 xv[WG_XK], dv[WG_DK];
+    int x_dst[XK], x_part[XK], x_li[XK], x_off[XK];
+    raw4 xv[XK], dv[WG_DK];
     if constexpr (PIPE) {
         const int n_cols = g.lw * 4, slots = g.imgs * g.in_rows * n_cols;
 #pragma unroll
-        for (int k = 0; k < WG_XK; ++k) {
+        for (int k = 0; k < XK; ++k) {
             const int e = threadIdx.x + k * WGRAD_THREADS;
             const int lr = e / n_cols, col = e - lr * n_cols;
             const int lc = col >> 2, cq = col & 3, wi = lc - g.pad;
@@ -813,7 +814,7 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
         const int rpi = 1 << g.rpi_log2;
         const int row0 = tile * g.rows_tile;
 #pragma unroll
-        for (int k = 0; k < WG_XK; ++k) {
+        for (int k = 0; k < XK; ++k) {
             xv[k] = Act<T>::zero();
             if (x_off[k] >= 0) {
                 const int grow = row0 + x_part[k] * rpi;
@@ -838,7 +839,7 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
         __syncthreads();  // previous tile fully consumed
         if constexpr (PIPE) {
 #pragma unroll
-            for (int k = 0; k < WG_XK; ++k)
+            for (int k = 0; k < XK; ++k)
                 if (x_dst[k] >= 0) lds4[x_dst[k]] = Act<T>::widen(xv[k]);
 #pragma unroll
             for (int k = 0; k < WG_DK; ++k) {
@@ -1007,8 +1008,9 @@ void launch_update(hipStream_t s, int act, float* params, float* momentum, const
 
 // Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller
 // when the staged 16-channel input slice would exceed 40 KB of LDS.
-static bool wgrad_fits_pipe(const ConvGeom& g) {
-    return g.imgs * g.in_rows * g.lw * 4 <= WG_XK * WGRAD_THREADS && (g.rows_tile << g.wout_log2) * 4 <= WG_DK * WGRAD_THREADS;
+static int wgrad_slots(const ConvShape& cs) { return cs.stride == 2 ? WG_XK_STRIDE2 : WG_XK; }
+static bool wgrad_fits_pipe(const ConvGeom& g, int xk) {
+    return g.imgs * g.in_rows * g.lw * 4 <= xk * WGRAD_THREADS && (g.rows_tile << g.wout_log2) * 4 <= WG_DK * WGRAD_THREADS;
 }
 
 static ConvGeom wgrad_geom(const ConvShape& cs) {
@@ -1018,7 +1020,7 @@ static ConvGeom wgrad_geom(const ConvShape& cs) {
         int rows = WG_PIPE_PIXELS / h_out;
         if (rows >= 1 && h_out >= 4) {
             ConvGeom g = make_geom(cs.B, cs.h_in, h_out, cs.c_out, cs.stride, 0, cs.c_in_real, rows, cs.taps == 9 ? 1 : 0);
-            if (wgrad_fits_pipe(g)) return g;
+            if (wgrad_fits_pipe(g, wgrad_slots(cs))) return g;
         }
     }
     int rows = 256 / h_out;
@@ -1062,9 +1064,13 @@ static void launch_conv_wgrad_t(hipStream_t s, const ConvShape& cs, const T* x, 
     // several replicas in one launch: a workgroup takes as many consecutive pixel groups as there are replicas
     int groups_per_wg = reps.n > 1 ? (reps.n < groups ? reps.n : groups) : 1;
     const bool multi = groups_per_wg > 1;
-    const bool pipe = wgrad_fits_pipe(g) && tiles_per_group * groups_per_wg > 1;
+    // stride-2 layers take the slot-based staging for a single tile as well: the row-wise one would leave three quarters
+    // of the threads without a column
+    const bool wide = cs.stride == 2 && wgrad_fits_pipe(g, WG_XK_STRIDE2);
+    const bool pipe = wide || (wgrad_fits_pipe(g, WG_XK) && tiles_per_group * groups_per_wg > 1);
     auto kern = multi ? (pipe ? wgrad_kernel<T, TAPS, true, true> : wgrad_kernel<T, TAPS, false, true>)
                       : (pipe ? wgrad_kernel<T, TAPS, true, false> : wgrad_kernel<T, TAPS, false, false>);
+    if (wide) kern = multi ? wgrad_kernel<T, TAPS, true, true, WG_XK_STRIDE2> : wgrad_kernel<T, TAPS, true, false, WG_XK_STRIDE2>;
     if (lds < WG_WAVES * 16 * TAPS * 16 * sizeof(float)) lds = WG_WAVES * 16 * TAPS * 16 * sizeof(float);
     if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     int blocks = (cs.c_in / 16) * (cs.c_out / 16);
