@@ -957,13 +957,16 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
             const int64_t pitch = (int64_t)blocks * block_floats;
             if (e.replicas > 0) {
                 fixsum_t* acc_l = gacc + e.acc_off;
-                long long acc = 0;
+                long long acc = 0, w[WGRAD_REPLICAS];
                 bool poisoned = false;
-                for (int rep = 0; rep < e.replicas; ++rep) {
-                    const long long w = (long long)acc_l[rep * pitch + src];
-                    poisoned |= w >= FIX_POISON_MIN;
-                    acc += w;
-                    acc_l[rep * pitch + src] = 0ull;
+                // all replicas requested at once (a loop over e.replicas waits for one load after the other)
+#pragma unroll
+                for (int rep = 0; rep < WGRAD_REPLICAS; ++rep) w[rep] = rep < e.replicas ? (long long)acc_l[rep * pitch + src] : 0ll;
+#pragma unroll
+                for (int rep = 0; rep < WGRAD_REPLICAS; ++rep) {
+                    poisoned |= w[rep] >= FIX_POISON_MIN;
+                    acc += w[rep];
+                    if (rep < e.replicas) acc_l[rep * pitch + src] = 0ull;
                 }
                 g = poisoned ? FIX_NAN : (float)((double)acc * (1.0 / FIX_WGRAD_SCALE));   // out of range: NaN, as a float sum would end
             } else {
