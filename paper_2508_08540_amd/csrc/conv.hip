@@ -129,20 +129,29 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
         const bool rch = RES && cq * 4 >= res_lo && cq * 4 < res_lo + res_c;
         const int64_t rcolo = (int64_t)(wok ? wi : 0) * res_stride * res_c + (cq * 4 - res_lo);
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
-        for (int r0 = 0; r0 < rows_total; r0 += R) {
+        int part0 = 0, li0 = 0;   // image part and row inside it of row r0
+        for (int r0 = 0; r0 < rows_total; r0 += R, li0 += R) {
+            while (li0 >= g.in_rows) {
+                li0 -= g.in_rows;
+                ++part0;
+            }
             raw4 v[R], vr[R];
             int64_t at[R];
             bool ok[R], inner[R];
+            int part = part0, li = li0;                              // of row r0 + r, without a division per row
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int lr = r0 + r;                               // wave-uniform
-                const int part = lr / g.in_rows, li = lr - part * g.in_rows;
                 const int grow = row0 + part * rpi;
                 const int n = grow >> g.wout_log2;
                 const int hi = (grow & (g.h_out - 1)) * g.stride - g.pad + li;
                 ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok;
                 inner[r] = li >= g.pad && li < g.pad + rpi * g.stride;
                 at[r] = ((int64_t)n * g.h_in + hi) * g.h_in * CIN + colo;
+                if (++li == g.in_rows) {
+                    li = 0;
+                    ++part;
+                }
                 v[r] = vr[r] = Act<T>::zero();
                 if (ok[r]) {
                     v[r] = Act<T>::load_raw(x + at[r]);
@@ -199,20 +208,29 @@ __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restri
         const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
         const int64_t colo = (int64_t)(wok ? (g.ups ? wi >> 1 : wi) : 0) * CIN + cq * 4;
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
-        for (int r0 = 0; r0 < rows_total; r0 += R) {
+        int part0 = 0, li0 = 0;   // image part and row inside it of row r0
+        for (int r0 = 0; r0 < rows_total; r0 += R, li0 += R) {
+            while (li0 >= g.in_rows) {
+                li0 -= g.in_rows;
+                ++part0;
+            }
             raw4 vd[R], vy[R];
             int64_t at[R];
             bool ok[R], inner[R];
+            int part = part0, li = li0;                              // of row r0 + r, without a division per row
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int lr = r0 + r;                               // wave-uniform
-                const int part = lr / g.in_rows, li = lr - part * g.in_rows;
                 const int grow = row0 + part * rpi;
                 const int n = grow >> g.wout_log2;
                 const int hi = (grow & (g.h_out - 1)) - g.pad + li;
                 ok[r] = lr < rows_total && n < g.B && (unsigned)hi < (unsigned)g.h_in && wok && !(g.ups && (hi & 1));
                 inner[r] = li >= g.pad && li < g.pad + rpi;
                 at[r] = ((int64_t)n * src_h + (g.ups ? hi >> 1 : hi)) * src_h * CIN + colo;
+                if (++li == g.in_rows) {
+                    li = 0;
+                    ++part;
+                }
                 vd[r] = vy[r] = Act<T>::zero();
                 if (ok[r]) {
                     vd[r] = Act<T>::load_raw(dout + at[r]);
