@@ -84,27 +84,15 @@ __device__ __forceinline__ void tile_store(const typename Tile<T>::vec16 (&v)[PR
 // ---- batch norm + ReLU of the layer below applied while staging (training forward) ------------------------------------
 // s_bn[0..3][c] = mean, 1/std, scale, shift of input channel c.  The arithmetic is bn_apply_kernel's, so the staged and
 // the stored values are the ones that kernel would have written.
-__device__ __forceinline__ f32x4 bn_relu4(f32x4 v, f32x4 res, const float (*s_bn)[64], int c) {
+__device__ __forceinline__ f32x4 bn_relu4(f32x4 v, f32x4 res, const float (&k)[4][4]) {
     f32x4 o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float t = __fmaf_rn((v[j] - s_bn[0][c + j]) * s_bn[1][c + j], s_bn[2][c + j], s_bn[3][c + j]) + res[j];
+        const float t = __fmaf_rn((v[j] - k[0][j]) * k[1][j], k[2][j], k[3][j]) + res[j];
         o[j] = relu_keep_nan(t);
     }
     return o;
 }
-// v and res (the shortcut, zeros where there is none) as loaded: 4 fp32 or 8 bf16 channels from c on
-template <typename T>
-__device__ __forceinline__ typename Tile<T>::vec16 bn_relu16(typename Tile<T>::vec16 v, typename Tile<T>::vec16 res, const float (*s_bn)[64], int c) {
-    if constexpr (sizeof(T) == 4) {
-        return bn_relu4(v, res, s_bn, c);
-    } else {
-        const uint2 lo = Act<T>::narrow(bn_relu4(Act<T>::widen(make_uint2(v.x, v.y)), Act<T>::widen(make_uint2(res.x, res.y)), s_bn, c));
-        const uint2 hi = Act<T>::narrow(bn_relu4(Act<T>::widen(make_uint2(v.z, v.w)), Act<T>::widen(make_uint2(res.z, res.w)), s_bn, c + 4));
-        return make_uint4(lo.x, lo.y, hi.x, hi.y);
-    }
-}
-
 // stage_input with that transform: rows and columns outside the image stay zero; the rows the tile's own output rows
 // sit on (everything but the halo) also go to a_out, so that every pixel of the activation is written exactly once.
 template <typename T, int CIN, int THREADS, bool RES>
@@ -129,6 +117,11 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
         const bool rch = RES && cq * 4 >= res_lo && cq * 4 < res_lo + res_c;
         const int64_t rcolo = (int64_t)(wok ? wi : 0) * res_stride * res_c + (cq * 4 - res_lo);
         typename Tile<T>::quad* dst = lds4 + lc * CP4 + cq;
+        float k_bn[4][4];   // the column's four channels' constants, read once
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) k_bn[a][j] = s_bn[a][cq * 4 + j];
         int part0 = 0, li0 = 0;   // image part and row inside it of row r0
         for (int r0 = 0; r0 < rows_total; r0 += R, li0 += R) {
             while (li0 >= g.in_rows) {
@@ -163,7 +156,7 @@ __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restric
                 if (r0 + r < rows_total) {
                     raw4 o = v[r];
                     if (ok[r]) {
-                        const f32x4 t = bn_relu4(Act<T>::widen(o), Act<T>::widen(vr[r]), s_bn, cq * 4);
+                        const f32x4 t = bn_relu4(Act<T>::widen(o), Act<T>::widen(vr[r]), k_bn);
                         if constexpr (sizeof(T) == 4) o = t;
                         else o = Act<T>::narrow(t);
                         if (inner[r]) *reinterpret_cast<raw4*>(a_out + at[r]) = o;
