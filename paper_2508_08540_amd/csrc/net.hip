@@ -1,6 +1,7 @@
 // Network passes: scoring (inference-mode forward + per-sample loss) and the local SGD steps
 // (train-mode forward, backward, update) for the MLP and the CIFAR residual network.
 #include "net.h"
+#include <utility>
 
 #include "kernels.h"
 
@@ -78,6 +79,8 @@ struct ResScratch {
     PackTable tab;
     act_t* xpad;
     int32_t* yb;
+    act_t* xpad_next;                  // training: the batch of the next step, gathered on the side stream meanwhile
+    int32_t* yb_next;
     std::vector<act_t*> y, a, dy;      // per layer
     std::vector<float*> mean, invstd;  // per layer
     act_t *stats, *d1, *d2, *g;
@@ -117,6 +120,10 @@ ResScratch carve_resnet(Carver& c, const bls_model* m, int B, bool train) {
     s.wpack = c.take<act_t>(vec4 * 4 * esz);
     s.xpad = c.take<act_t>((size_t)B * hw * hw * PAD_C * esz);
     s.yb = c.take<int32_t>(B);
+    if (train) {
+        s.xpad_next = c.take<act_t>((size_t)B * hw * hw * PAD_C * esz);
+        s.yb_next = c.take<int32_t>(B);
+    }
     s.loss = c.take<float>(B);
     s.y.resize(L); s.a.resize(L); s.mean.resize(L); s.invstd.resize(L); s.dy.assign(L, nullptr);
     int64_t max_act = 0, max_wpart = 0;
@@ -529,11 +536,25 @@ int net_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         const int hw = m->desc.image_hw;
         // the weight-gradient accumulators start at zero; every reduction leaves them at zero again
         PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.wacc), s.wacc_count * 2));
+        // The batch of step j + 1 does not depend on step j: it is gathered on the side stream while step j runs, into the
+        // other pair of buffers.  That stream is in order and every step joins it before its update, so the gather follows
+        // the last reader of its buffers (the stem's weight gradient of step j - 1) and precedes the first of step j + 1.
+        PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, 0, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
         for (int64_t j = 0; j < tau; ++j) {
             float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
-            PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
+            if (j + 1 < tau) {
+                if (j == 0) {   // the side stream has not seen this call's work yet: behind the first gather, whose launch is the latest so far
+                    BLS_HIP(ctx, hipEventRecord(ctx->head_event, st));
+                    BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->head_event, 0));
+                }
+                ProfScope prof_(ctx, PROF_GATHER, ctx->aux);
+                launch_gather_images(ctx->aux, x_pool, y_pool, sel, k, (j + 1) * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad_next,
+                                     s.yb_next);
+            }
             rc = resnet_train_step(ctx, st, m, params, buffers, momentum, B, s, loss, opt, j == 0);
             if (rc != BLS_OK) return rc;
+            std::swap(s.xpad, s.xpad_next);
+            std::swap(s.yb, s.yb_next);
         }
     }
     BLS_HIP(ctx, hipGetLastError());
@@ -589,14 +610,32 @@ int net_round_batched(bls_ctx* ctx, const bls_model* m, const float* global_para
     // the weight-gradient accumulators start at zero; every update leaves them at zero again
     PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.wacc), s.wacc_count * 2, s.reps));
     const int hw = m->desc.image_hw;
-    for (int64_t j = 0; j < tau_max; ++j) {
+    // replicas still training at step j: the first R_j slots
+    auto training_at = [&](int64_t j) {
         int rj = 0;
         while (rj < R && workers[order[rj]].tau > j) ++rj;
-        s.reps.n = rj;
-        PROF(ctx, PROF_GATHER, launch_gather_images_reps(st, x_pool, y_pool, lists, j * B, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb,
-                                                         s.reps));
+        return rj;
+    };
+    // as in net_local_step: the batches of step j + 1 are gathered on the side stream while step j runs
+    s.reps.n = training_at(0);
+    PROF(ctx, PROF_GATHER, launch_gather_images_reps(st, x_pool, y_pool, lists, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb, s.reps));
+    for (int64_t j = 0; j < tau_max; ++j) {
+        if (j + 1 < tau_max) {
+            if (j == 0) {
+                BLS_HIP(ctx, hipEventRecord(ctx->head_event, st));
+                BLS_HIP(ctx, hipStreamWaitEvent(ctx->aux, ctx->head_event, 0));
+            }
+            Reps next = s.reps;
+            next.n = training_at(j + 1);
+            ProfScope prof_(ctx, PROF_GATHER, ctx->aux);
+            launch_gather_images_reps(ctx->aux, x_pool, y_pool, lists, (j + 1) * B, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad_next,
+                                      s.yb_next, next);
+        }
+        s.reps.n = training_at(j);
         rc = resnet_train_step(ctx, st, m, h.params, h.buffers, h.momentum, B, s, h.losses + j * B, opt, j == 0);
         if (rc != BLS_OK) return rc;
+        std::swap(s.xpad, s.xpad_next);
+        std::swap(s.yb, s.yb_next);
     }
     s.reps.n = R;
     PROF(ctx, PROF_UPDATE, hipLaunchKernelGGL(round_copy_out_kernel, dim3((unsigned)blocks, 1, R), dim3(256), 0, st, io, h, d, nb, s.reps.stride));
