@@ -955,7 +955,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params, float* __restrict__ momentum,
                                                      const float* __restrict__ grad, int64_t d, float lr, float mu, float wd,
                                                      fixsum_t* __restrict__ gacc, T* __restrict__ packed, UpdateTable tab,
-                                                     fixsum_t* __restrict__ sums, int64_t n_sums, int64_t rstride) {
+                                                     fixsum_t* __restrict__ sums, int64_t n_sums, int64_t rstride, int64_t begin) {
     if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
         const int64_t ro = (int64_t)blockIdx.z * rstride;
         params = rep_at(params, ro); momentum = rep_at(momentum, ro); grad = rep_at(grad, ro); gacc = rep_at(gacc, ro); packed = rep_at(packed, ro);
@@ -964,7 +964,7 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     for (int64_t i = first; i < n_sums; i += stride) sums[i] = 0ull;
-    for (int64_t i = first; i < d; i += stride) {
+    for (int64_t i = begin + first; i < d; i += stride) {   // parameters begin .. d - 1
         int l = -1;
         for (int q = 0; q < tab.n; ++q)
             if (i >= tab.e[q].w_off && i < tab.e[q].w_off + tab.e[q].n) l = q;
@@ -1029,11 +1029,14 @@ __global__ __launch_bounds__(256) void update_kernel(float* __restrict__ params,
 }
 
 void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
-                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums, Reps reps) {
-    int64_t blocks = (d + 255) / 256;
+                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums, Reps reps, int64_t begin,
+                   int64_t end) {
+    if (end < 0) end = d;
+    int64_t blocks = (end - begin + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    ACT_DISPATCH(act, hipLaunchKernelGGL(update_kernel<T>, dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, params, momentum, grad, d, lr, mu,
-                                         wd, gacc, (T*)packed, tab, sums, n_sums, reps.stride));
+    if (blocks < 1) blocks = 1;
+    ACT_DISPATCH(act, hipLaunchKernelGGL(update_kernel<T>, dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, params, momentum, grad, end, lr, mu,
+                                         wd, gacc, (T*)packed, tab, sums, n_sums, reps.stride, begin));
 }
 
 // Tiles of the weight-gradient kernel: up to 256 pixels (a power-of-two number of output rows), smaller

@@ -253,8 +253,10 @@ struct UpdateTable {
     int n;
     UpdateEntry e[WGRAD_MAX_ENTRIES];
 };
+// Parameters begin .. end - 1 (end < 0: d); the batch-norm accumulators `sums` (n_sums words, may be 0) are cleared as well.
 void launch_update(hipStream_t s, int act, float* params, float* momentum, const float* grad, int64_t d, float lr, float mu,
-                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums, Reps reps = Reps{});
+                   float wd, fixsum_t* gacc, void* packed, const UpdateTable& tab, fixsum_t* sums, int64_t n_sums, Reps reps = Reps{},
+                   int64_t begin = 0, int64_t end = -1);
 
 // ---- wconv.hip --------------------------------------------------------------------------------------
 // Convolution for wide layers: y = conv(x, w) [+ add] with a 3x3 (taps 9, padding 1) or 1x1 (taps 1) filter;

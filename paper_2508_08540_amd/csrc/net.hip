@@ -279,9 +279,12 @@ const act_t* resnet_forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, co
 // The weight gradients are off the critical path (only the update needs them), so they run on the
 // context's side stream, each after the event that marks its dy as ready; the caller joins the side
 // stream before the update.
-int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s) {
+// `early_from`: the caller updates the parameters of layers early_from .. L-1 (and everything behind the last layer) as soon
+// as their weight gradients are in, while those of the layers below still run; the events that mark the two moments are
+// fork_events[L] / [L + 1] (one per side stream) and the join events.
+int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, int B, ResScratch& s, int early_from) {
     const int L = (int)m->layers.size();
-    while ((int)ctx->fork_events.size() < L) {
+    while ((int)ctx->fork_events.size() < L + 2) {
         hipEvent_t e;
         BLS_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
         ctx->fork_events.push_back(e);
@@ -321,6 +324,8 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
             hipStream_t side = (two_sides && (l & 1)) ? ctx->aux2 : ctx->aux;
             BLS_HIP(ctx, hipStreamWaitEvent(side, ctx->fork_events[l], 0));
             PROF_KERNEL(ctx, PROF_CONV_WGRAD, launch_conv_wgrad(side, s.act, cs, x_in, s.dy[l], s.wacc + s.utab.e[l].acc_off, kt, s.reps));
+            // the last weight gradient of the early part on this stream (two streams take the layers in turn)
+            if (l >= early_from && l < early_from + (two_sides ? 2 : 1)) BLS_HIP(ctx, hipEventRecord(ctx->fork_events[L + (side == ctx->aux ? 0 : 1)], side));
             return BLS_OK;
         };
         if (is_conv2 && !shared) block_g = dout;   // as stored by the launch of the layer above
@@ -367,11 +372,7 @@ int resnet_backward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const floa
         shared = 0;
     }
     BLS_HIP(ctx, hipEventRecord(ctx->join_event, ctx->aux));
-    BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
-    if (two_sides) {
-        BLS_HIP(ctx, hipEventRecord(ctx->join_event2, ctx->aux2));
-        BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event2, 0));
-    }
+    if (two_sides) BLS_HIP(ctx, hipEventRecord(ctx->join_event2, ctx->aux2));
     return BLS_OK;
 }
 
@@ -391,11 +392,28 @@ int resnet_train_step(bls_ctx* ctx, hipStream_t st, const bls_model* m, float* p
         ProfScope prof_(ctx, PROF_HEAD, ctx->aux);
         launch_head_wgrad(ctx->aux, s.dlogits, s.feat, B, C, m->final_c, s.grad + m->fc_w, s.grad + m->fc_b, s.reps);
     }
-    int rc = resnet_backward(ctx, st, m, params, B, s);
+    // The update comes in two launches: the layers from `early` up (nearly all parameters) as soon as their weight gradients
+    // are in, behind which the side stream still works on the weight gradients of the first layers; those layers, and the
+    // clearing of the batch-norm accumulators, after the join.
+    const int L = (int)m->layers.size();
+    const int early = L > 3 ? 3 : L;
+    const bool two_sides = s.act == ACT_BF16;
+    int rc = resnet_backward(ctx, st, m, params, B, s, early);
     if (rc != BLS_OK) return rc;
+    const int64_t split = early < L ? m->layers[early].w_off : m->layers[L - 1].beta_off + m->layers[L - 1].c_out;
     // gradients of the convolution weights are still in the accumulators: the update reads them there
+    if (early < L) {
+        BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->fork_events[L], 0));
+        if (two_sides && early + 1 < L) BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->fork_events[L + 1], 0));
+    } else {
+        BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));   // nothing below: the head's weight gradient is all there is to wait for
+    }
     PROF(ctx, PROF_UPDATE, launch_update(st, s.act, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay,
-                                         s.wacc, s.wpack, s.utab, s.sums, (int64_t)m->layers.size() * 2 * FIX_SET, s.reps));
+                                         s.wacc, s.wpack, s.utab, nullptr, 0, s.reps, split, -1));
+    BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event, 0));
+    if (two_sides) BLS_HIP(ctx, hipStreamWaitEvent(st, ctx->join_event2, 0));
+    PROF(ctx, PROF_UPDATE, launch_update(st, s.act, params, momentum, s.grad, m->num_params, opt.lr, opt.momentum, opt.weight_decay,
+                                         s.wacc, s.wpack, s.utab, s.sums, (int64_t)L * 2 * FIX_SET, s.reps, 0, split));
     return BLS_OK;
 }
 
