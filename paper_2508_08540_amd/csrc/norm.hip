@@ -67,6 +67,29 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
     int64_t total = pixels * cq;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int lo = (C - c_res) >> 1;
+    if (WIDE && cq_log2 >= 0 && (stride & (cq - 1)) == 0 && (res == nullptr || res_stride == 1)) {
+        // wide layers: the grid's stride is a multiple of the quads per pixel, so a thread keeps its four channels and their
+        // constants for all its pixels (the loop below re-reads 48 bytes of them for every 8 or 16 bytes of payload)
+        const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const int c = (int)(first & (cq - 1)) << 2;
+        const f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c), be = *reinterpret_cast<const f32x4*>(beta + c);
+        const f32x4 mu = *reinterpret_cast<const f32x4*>(&s_mean[c]), is = *reinterpret_cast<const f32x4*>(&s_invstd[c]);
+        const bool with_res = res && c >= lo && c < lo + c_res;
+        for (int64_t i = first; i < total; i += stride) {
+            const int64_t p = i >> cq_log2;
+            const f32x4 v = Act<T>::load4(y + p * C + c);
+            f32x4 r = {0.f, 0.f, 0.f, 0.f};
+            if (with_res) r = Act<T>::load4(res + p * c_res + (c - lo));
+            f32x4 o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float t = __fmaf_rn((v[j] - mu[j]) * is[j], ga[j], be[j]) + r[j];
+                o[j] = relu_keep_nan(t);
+            }
+            Act<T>::store4(out + p * C + c, o);
+        }
+        return;
+    }
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         const int64_t p = cq_log2 >= 0 ? i >> cq_log2 : i / cq;   // (a 64-bit division costs as much as the rest of the body)
         int c = (int)(i - p * cq) << 2;
@@ -100,7 +123,9 @@ void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int 
                      const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out, Reps reps) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
+    // every workgroup derives the statistics of all C channels first: wide layers take fewer, longer-lived workgroups
+    const int64_t cap = C > 64 ? 1024 : 4096;
+    if (blocks > cap) blocks = cap;
     const int cq_log2 = quads_log2(C);
     const dim3 grid((unsigned)blocks, 1, reps.n);
     ACT_DISPATCH(act, {
@@ -228,6 +253,32 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* __restric
     const int cq = C >> 2;
     int64_t total = pixels * cq;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    if (WIDE && cq_log2 >= 0 && (stride & (cq - 1)) == 0) {
+        // wide layers: a thread keeps its four channels and their constants for all its pixels (as in bn_apply_kernel)
+        const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const int c = (int)(first & (cq - 1)) << 2;
+        const f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c), is = *reinterpret_cast<const f32x4*>(invstd + c);
+        const f32x4 ga = *reinterpret_cast<const f32x4*>(gamma + c);
+        const f32x4 db = *reinterpret_cast<const f32x4*>(&s_db[c]), dg = *reinterpret_cast<const f32x4*>(&s_dg[c]);
+        for (int64_t i = first; i < total; i += stride) {
+            const int64_t p = i >> cq_log2;
+            const f32x4 d = load_dout<T>(dout, shared, p, C, c);
+            const f32x4 o = Act<T>::load4(out + p * C + c);
+            const f32x4 v = Act<T>::load4(y + p * C + c);
+            f32x4 r, gq;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float g = o[j] > 0.f ? d[j] : 0.f;
+                float xhat = (v[j] - mu[j]) * is[j];
+                gq[j] = g;
+                r[j] = ga[j] * is[j] * (g - db[j] * inv_count - xhat * (dg[j] * inv_count));
+            }
+            if (HAS_ADD) r += Act<T>::load4(add + p * C + c);  // gradient arriving through an identity shortcut
+            Act<T>::store4(dy + p * C + c, r);
+            if (g_out) Act<T>::store4(g_out + p * C + c, gq);
+        }
+        return;
+    }
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         const int64_t p = cq_log2 >= 0 ? i >> cq_log2 : i / cq;
         int c = (int)(i - p * cq) << 2;
@@ -256,7 +307,8 @@ void launch_bn_bwd_apply(hipStream_t s, int act, const void* dout, int dout_posi
                          const fixsum_t* sums, float* dgamma, float* dbeta, void* dy, void* g_out, const void* add, Reps reps) {
     int64_t total = pixels * (C / 4);
     int64_t blocks = (total + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
+    const int64_t cap = (C > 64 || add) ? 1024 : 4096;   // as in launch_bn_apply
+    if (blocks > cap) blocks = cap;
 #define BN_BWD_APPLY(MAXC, HAS_ADD)                                                                                                   \
     hipLaunchKernelGGL((bn_bwd_apply_kernel<T, MAXC, HAS_ADD>), dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, dout, dout_positions_shared,   \
                        (const T*)out, (const T*)y, pixels, C, mean, invstd, gamma, sums, dgamma, dbeta, 1.f / (float)pixels, (T*)dy,  \
