@@ -26,6 +26,8 @@
 
 #define FIX_WGRAD_SCALE 1099511627776.0  // 2^40, as in wgrad_kernel
 #define W16_TILE_PX 128
+#define W16_XT 4   // staging tasks of x and of dy that a thread prefetches for the next tile
+#define W16_DT 2
 
 struct W16Geom {
     int lwp;   // LDS row width of an xT plane: w_out + 4 (3x3) or w_out (1x1)
@@ -60,51 +62,78 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const bf16_t* __restrict__
 
     const int tile_begin = blockIdx.x * tiles_per_group;
     const int tile_end = min(g.n_tiles, tile_begin + tiles_per_group);
+    // Staging.  A task is (4 channels, 4 consecutive pixels): four 8-byte loads, a 4x4 transpose in registers, four 8-byte
+    // LDS writes; for x the pixels are padded columns of one staged row.  The loads of a thread's first W16_XT + W16_DT
+    // tasks of the next tile are requested before the matrix instructions of the current one (a tile has 800 .. 1100 tasks of
+    // x and 512 of dy for 256 threads; taken one after the other they cost five to six memory round trips per tile, ten
+    // times the tile's matrix work); tasks beyond those are loaded when the tile is written.
+    const int rows_total = g.imgs * g.in_rows;
+    const int x_tasks = 16 * rows_total * lwq, d_tasks = 16 * (W16_TILE_PX / 4);
+    uint2 rx[W16_XT][4], rd[W16_DT][4];
+    auto x_task = [&](int tile, int id, uint2 (&r)[4]) {   // requests the four pixels of task id; returns its LDS quad or -1
+        if (id >= x_tasks) return -1;
+        const int cq = id & 15, rest = id >> 4;
+        const int lr = rest / lwq, pq = rest - lr * lwq;
+        const int part = lr / g.in_rows, li = lr - part * g.in_rows;
+        const int grow = tile * g.rows_tile + part * rpi;
+        const int n = grow >> g.wout_log2;
+        const int hi = (grow & (g.h_out - 1)) - pad + li;
+        const bool rok = n < g.B && (unsigned)hi < (unsigned)g.h_in;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int wi = pq * 4 + j - pad;
+            r[j] = make_uint2(0u, 0u);
+            if (rok && (unsigned)wi < (unsigned)W)
+                r[j] = *reinterpret_cast<const uint2*>(x + (((int64_t)n * g.h_in + hi) * g.h_in + wi) * NI + cib * 64 + cq * 4);
+        }
+        return (cq * 4) * xq + lr * lwq + pq;
+    };
+    auto d_task = [&](int tile, int id, uint2 (&r)[4]) {
+        if (id >= d_tasks) return -1;
+        const int cq = id & 15, pq = id >> 4;
+        const int64_t pix0 = (int64_t)tile * W16_TILE_PX;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t p = pix0 + pq * 4 + j;
+            r[j] = make_uint2(0u, 0u);
+            if (p < total_pixels) r[j] = *reinterpret_cast<const uint2*>(dy + p * NO + cob * 64 + cq * 4);
+        }
+        return (cq * 4) * dq + pq;
+    };
+    auto transpose_store = [](uint2* dst, int pitch, const uint2 (&r)[4]) {
+        dst[0 * pitch] = make_uint2((r[0].x & 0xffffu) | (r[1].x << 16), (r[2].x & 0xffffu) | (r[3].x << 16));
+        dst[1 * pitch] = make_uint2((r[0].x >> 16) | (r[1].x & 0xffff0000u), (r[2].x >> 16) | (r[3].x & 0xffff0000u));
+        dst[2 * pitch] = make_uint2((r[0].y & 0xffffu) | (r[1].y << 16), (r[2].y & 0xffffu) | (r[3].y << 16));
+        dst[3 * pitch] = make_uint2((r[0].y >> 16) | (r[1].y & 0xffff0000u), (r[2].y >> 16) | (r[3].y & 0xffff0000u));
+    };
+    int x_at[W16_XT], d_at[W16_DT];
+    auto request = [&](int tile) {
+#pragma unroll
+        for (int k = 0; k < W16_XT; ++k) x_at[k] = x_task(tile, k * 256 + (int)threadIdx.x, rx[k]);
+#pragma unroll
+        for (int k = 0; k < W16_DT; ++k) d_at[k] = d_task(tile, k * 256 + (int)threadIdx.x, rd[k]);
+    };
+    if (tile_begin < tile_end) request(tile_begin);
     for (int tile = tile_begin; tile < tile_end; ++tile) {
         __syncthreads();  // previous tile consumed
-        const int row0 = tile * g.rows_tile;
-        // ---- stage x: task = (4 channels, 4 consecutive padded columns of one staged row) -----------------
-        const int rows_total = g.imgs * g.in_rows;
-        for (int id = threadIdx.x; id < 16 * rows_total * lwq; id += 256) {
-            const int cq = id & 15, rest = id >> 4;
-            const int lr = rest / lwq, pq = rest - lr * lwq;
-            const int part = lr / g.in_rows, li = lr - part * g.in_rows;
-            const int grow = row0 + part * rpi;
-            const int n = grow >> g.wout_log2;
-            const int hi = (grow & (g.h_out - 1)) - pad + li;
-            const bool rok = n < g.B && (unsigned)hi < (unsigned)g.h_in;
-            uint2 r[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int wi = pq * 4 + j - pad;
-                r[j] = make_uint2(0u, 0u);
-                if (rok && (unsigned)wi < (unsigned)W)
-                    r[j] = *reinterpret_cast<const uint2*>(x + (((int64_t)n * g.h_in + hi) * g.h_in + wi) * NI + cib * 64 + cq * 4);
-            }
-            uint2* dst = xT + (cq * 4) * xq + lr * lwq + pq;
-            dst[0 * xq] = make_uint2((r[0].x & 0xffffu) | (r[1].x << 16), (r[2].x & 0xffffu) | (r[3].x << 16));
-            dst[1 * xq] = make_uint2((r[0].x >> 16) | (r[1].x & 0xffff0000u), (r[2].x >> 16) | (r[3].x & 0xffff0000u));
-            dst[2 * xq] = make_uint2((r[0].y & 0xffffu) | (r[1].y << 16), (r[2].y & 0xffffu) | (r[3].y << 16));
-            dst[3 * xq] = make_uint2((r[0].y >> 16) | (r[1].y & 0xffff0000u), (r[2].y >> 16) | (r[3].y & 0xffff0000u));
+        for (int k = 0; k < W16_XT; ++k)
+            if (x_at[k] >= 0) transpose_store(xT + x_at[k], xq, rx[k]);
+#pragma unroll
+        for (int k = 0; k < W16_DT; ++k)
+            if (d_at[k] >= 0) transpose_store(dyT + d_at[k], dq, rd[k]);
+        for (int id = W16_XT * 256 + threadIdx.x; id < x_tasks; id += 256) {   // what the prefetch registers do not cover
+            uint2 r[4];
+            const int at = x_task(tile, id, r);
+            transpose_store(xT + at, xq, r);
         }
-        // ---- stage dy ---------------------------------------------------------------------------------------
-        const int64_t pix0 = (int64_t)tile * W16_TILE_PX;
-        for (int id = threadIdx.x; id < 16 * (W16_TILE_PX / 4); id += 256) {
-            const int cq = id & 15, pq = id >> 4;
+        for (int id = W16_DT * 256 + threadIdx.x; id < d_tasks; id += 256) {
             uint2 r[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int64_t p = pix0 + pq * 4 + j;
-                r[j] = make_uint2(0u, 0u);
-                if (p < total_pixels) r[j] = *reinterpret_cast<const uint2*>(dy + p * NO + cob * 64 + cq * 4);
-            }
-            uint2* dst = dyT + (cq * 4) * dq + pq;
-            dst[0 * dq] = make_uint2((r[0].x & 0xffffu) | (r[1].x << 16), (r[2].x & 0xffffu) | (r[3].x << 16));
-            dst[1 * dq] = make_uint2((r[0].x >> 16) | (r[1].x & 0xffff0000u), (r[2].x >> 16) | (r[3].x & 0xffff0000u));
-            dst[2 * dq] = make_uint2((r[0].y & 0xffffu) | (r[1].y << 16), (r[2].y & 0xffffu) | (r[3].y << 16));
-            dst[3 * dq] = make_uint2((r[0].y >> 16) | (r[1].y & 0xffff0000u), (r[2].y >> 16) | (r[3].y & 0xffff0000u));
+            const int at = d_task(tile, id, r);
+            transpose_store(dyT + at, dq, r);
         }
         __syncthreads();
+        if (tile + 1 < tile_end) request(tile + 1);
         // ---- 8 k-steps of 16 pixels -------------------------------------------------------------------------
         const uint2* arow = dyT + (wave * 16 + r16) * dq + grp;
         const uint2* brow = xT + r16 * xq;
