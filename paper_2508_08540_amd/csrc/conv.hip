@@ -182,13 +182,15 @@ __device__ __forceinline__ f32x4 bn_bwd4(f32x4 g, f32x4 v, const float (&k)[5][4
 
 // Stages dy = batch-norm backward of (dout, y) for the tile, zero outside the image; the rows that are not halo are
 // stored to dy_out, every pixel exactly once.
-template <typename T, int CIN, int THREADS>
+// R rows of loads are in flight per thread and round: five (the 10 rows of an 8-row tile in two rounds), or three for the
+// 64-channel launches over several replicas, which have the fewest registers to spare (measured: + 3.5 % on the
+// eight-worker round, - 1.5 % on a single worker, which keeps five).
+template <typename T, int CIN, int THREADS, int R>
 __device__ __forceinline__ void stage_input_bwd(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ dout, const T* __restrict__ y,
                                                 const ConvGeom& g, int tile, const float (*s_bw)[64], float inv_count, T* __restrict__ dy_out) {
     typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = clog2(CQ);
-    constexpr int R = 5;   // the 10 rows of an 8-row tile in two rounds of loads
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
     const int n_cols = g.lw * CQ;
@@ -558,7 +560,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
         int it = 0;
         for (int tile = blockIdx.x; tile < g.n_tiles; tile += gridDim.x, ++it) {
             if constexpr (XF == 3)
-                stage_input_bwd<T, CIN, NW * 64>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_y), g, tile, s_bn, e.bw_inv_count,
+                stage_input_bwd<T, CIN, NW * 64, (MULTI && CIN == 64) ? 3 : 5>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_y), g, tile, s_bn, e.bw_inv_count,
                                                  static_cast<T*>(e.bw_dy_out));
             else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out, e.in_res_c, e.in_res_lo, e.in_res_stride);
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
