@@ -95,14 +95,13 @@ __device__ __forceinline__ f32x4 bn_relu4(f32x4 v, f32x4 res, const float (&k)[4
 }
 // stage_input with that transform: rows and columns outside the image stay zero; the rows the tile's own output rows
 // sit on (everything but the halo) also go to a_out, so that every pixel of the activation is written exactly once.
-template <typename T, int CIN, int THREADS, bool RES>
+template <typename T, int CIN, int THREADS, bool RES, int R>
 __device__ __forceinline__ void stage_input_bn(typename Tile<T>::quad* __restrict__ lds4, const T* __restrict__ x, const T* __restrict__ res,
                                                const ConvGeom& g, int tile, const float (*s_bn)[64], T* __restrict__ a_out,
                                                int res_c, int res_lo, int res_stride) {
     typedef typename Act<T>::raw4 raw4;
     constexpr int CP4 = (CIN + 4) / 4, CQ = CIN / 4;
     constexpr int CQ_LOG2 = clog2(CQ);
-    constexpr int R = 6;
     const int res_h = g.h_in * res_stride;
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
@@ -562,7 +561,7 @@ __global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, 
             if constexpr (XF == 3)
                 stage_input_bwd<T, CIN, NW * 64, (MULTI && CIN == 64) ? 3 : 5>(lds4, static_cast<const T*>(e.bw_dout), static_cast<const T*>(e.bw_y), g, tile, s_bn, e.bw_inv_count,
                                                  static_cast<T*>(e.bw_dy_out));
-            else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES>(lds4, x, in_res, g, tile, s_bn, a_out, e.in_res_c, e.in_res_lo, e.in_res_stride);
+            else if constexpr (XF != 0) stage_input_bn<T, CIN, NW * 64, RES, (MULTI && CIN == 64) ? 3 : 6>(lds4, x, in_res, g, tile, s_bn, a_out, e.in_res_c, e.in_res_lo, e.in_res_stride);
             else stage_input<T, quad, CIN, NW * 64>(lds4, x, g, tile);
             __syncthreads();
             conv_tile<T, CIN, MT, NW, EPI>(lds4, wr, y, e, g, tile, ssum, ssq);
