@@ -428,7 +428,7 @@ __device__ __forceinline__ void conv_tile(const typename Tile<T>::quad* __restri
 // input dy is computed while staging, by the layer's batch-norm backward (ConvEpi::bw_dout and the fields after it).
 // MULTI: a workgroup may own several tiles; the sums of the epilogue are then folded and converted tile by tile.
 template <typename T, int CIN, int MT, int NW, int EPI, int XF, bool MULTI>
-__global__ __launch_bounds__(NW * 64) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
+__global__ __launch_bounds__(NW * 64, (MULTI && CIN == 64) ? 2 : 1) void conv_kernel(const T* __restrict__ x, const void* __restrict__ w,
                                                             T* __restrict__ y, ConvEpi e, ConvGeom g, int pipelined, int64_t rstride) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
