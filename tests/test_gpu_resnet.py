@@ -48,6 +48,14 @@ def test_gradients_at_the_benchmarked_launch_geometry(env, widths, hw):
     _grad_case(env, widths, 1, hw, 128)
 
 
+def test_gradients_with_several_tiles_per_workgroup(env):
+    """Batch 160 on a one-block net of the three widths: the 16-channel launches have 640 tiles for 512 workgroups (the
+    32-channel forward launches as well), so a quarter of the workgroups own two tiles and the kernels that fold and
+    convert their batch-norm sums tile by tile run in a launch over one replica, against the oracle (a round of several
+    workers reaches them too, but is only compared with the same kernels run one worker after the other)."""
+    _grad_case(env, (16, 32, 64), 1, 32, 160)
+
+
 @pytest.mark.parametrize("widths,blocks,hw,batch", [
     ((16, 32, 64), 1, 8, 4),      # tiles spanning several images, ragged last tile
     ((16, 32, 64), 1, 16, 6),
