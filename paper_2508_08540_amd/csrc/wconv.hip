@@ -13,6 +13,7 @@
 #include "conv_tile.h"
 
 #include <type_traits>
+#include <utility>
 
 struct WEpi {
     const void* add;   // tensor of the output's shape added before the store, or nullptr
@@ -205,12 +206,23 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
     const T* add = static_cast<const T*>(e.add);
     f32x4 ssum = {0.f, 0.f, 0.f, 0.f}, ssq = {0.f, 0.f, 0.f, 0.f};
     if (active) {
+        // the added tensor is requested for the whole tile before the first store: behind a store the compiler would have to
+        // keep every later load (the two tensors may be the same memory for all it knows), one memory round trip per pixel block
+        typename Act<T>::raw4 addv[NPT];
+        if (add) {
+#pragma unroll
+            for (int pt = 0; pt < NPT; ++pt) {
+                const int64_t p = pix0 + pt * 16 + r16;
+                addv[pt] = Act<T>::zero();
+                if (p < total_pixels) addv[pt] = Act<T>::load_raw(add + p * NO + c0);
+            }
+        }
 #pragma unroll
         for (int pt = 0; pt < NPT; ++pt) {
             const int64_t p = pix0 + pt * 16 + r16;
             if (p < total_pixels) {
                 f32x4 v = acc[pt];
-                if (add) v += Act<T>::load4(add + p * NO + c0);
+                if (add) v += Act<T>::widen(addv[pt]);
                 v = Act<T>::rounded(v);  // the sums see what later kernels read back
                 Act<T>::store4(y + p * NO + c0, v);
                 ssum += v;
@@ -244,6 +256,292 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
     }
 }
 
+// calls f(std::integral_constant<int, 0>) .. f(std::integral_constant<int, N - 1>) in order: a loop whose index is a constant
+// expression in the body, unrolled whatever its size
+template <class F, int... I>
+__device__ __forceinline__ void static_for_seq(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_seq(f, std::make_integer_sequence<int, N>{});
+}
+
+// bf16 3x3 stride-1 layers whose output channels come in multiples of 128, in launches large enough to fill the chip
+// with workgroups of 256 pixels x 128 output channels.
+//
+// In wconv_kernel every matrix instruction has an LDS read of its own (a wave holds one block of 16 output channels), and
+// four waves reading 1 KB per instruction keep the LDS pipe (128 bytes per clock) busier than the matrix pipe can be.
+// Here a wave holds WB_OB x WB_PB accumulator blocks (output channels x pixels): one pixel operand read from LDS feeds
+// WB_OB instructions, one weight operand (registers, from the lane-major packed copy) feeds WB_PB.  The waves of a
+// workgroup are a 2 x 2 arrangement of (64 output channels, 128 pixels).
+//
+// The chunk tile goes from global memory straight into LDS (global_load_lds, 16 bytes per lane: the 64 lanes of an
+// instruction fill 1 KB of consecutive LDS), so it passes through no registers and a wave stays within 128 vector + 128
+// accumulation registers: two workgroups per compute unit, one computing while the other waits for memory, stores its
+// tile or sits at a barrier.  Consecutive LDS per instruction means no padding between pixels: a pixel's 32 channels
+// are 64 bytes, positions follow each other ([row][column] of the halo'd tile), and the 16-byte reads of the matrix
+// operands run at 93 % of the padded layout's rate (measured).  Positions outside the image are never written by a
+// load; they are zeroed once, in both buffers, before the first chunk.
+//
+// Chunks, taps and the K = 32 grouping of the channels are consumed in wconv_kernel's order, and the batch-norm sums of a
+// 256-pixel tile are taken in its order too (the waves of the second pixel half continue the lane sums of the first),
+// so both kernels give the same bits.
+#define WB_OB 4
+#define WB_PB 8
+#define WB_NV 7        // 16-byte slots of a chunk tile per thread, at most
+#define WB_AHEAD 3     // pixel operands requested from LDS ahead of their matrix instructions
+#define WB_WSETS 3     // weight register sets (one tap each): the tap in use and the two requested behind it
+// The matrix instruction as an assembly statement: accumulator in place in the accumulation registers, operands in
+// vector registers.  (Written as the builtin, the compiler keeps moving the 128 accumulator registers between the two
+// register files: two moves per matrix instruction.)  The compiler does not see the instruction's latency: a wait stands
+// between the last matrix instruction and the first other reader of an accumulator.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+#define WB_MFMA(acc, a, b) \
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(__builtin_bit_cast(u32x4, a)), "v"(__builtin_bit_cast(u32x4, b)))
+typedef __attribute__((address_space(1))) const void wb_global_ptr;
+typedef __attribute__((address_space(3))) void wb_lds_ptr;
+
+template <int LW>
+__global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __restrict__ x, const void* __restrict__ wpk, bf16_t* __restrict__ y,
+                                                             WEpi e, ConvGeom g, int c_in) {
+    __builtin_amdgcn_s_setprio(2);
+    typedef bf16_t T;
+    typedef Tile<T>::quad quad;
+    constexpr int TAPS = 9, STEPS = TAPS * WB_PB;
+    constexpr int IN_ROWS = LW == 18 ? 18 : 10;   // rows of an image part with halo: the whole 16-row image, or 8 rows
+    extern __shared__ f32x4 lds_raw[];
+    char* lds_bytes = reinterpret_cast<char*>(lds_raw);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction; says so to the compiler
+    const int r16 = lane & 15, grp = lane >> 4;
+    const int wo = wave & 1, wpx = wave >> 1;   // output-channel half and pixel half of this wave
+    const int NO = g.c_out;
+    const int ob0 = blockIdx.y * (2 * WB_OB) + wo * WB_OB;
+    const int tile = blockIdx.x;
+    const int s_total = c_in >> 4;
+    const int n_chunks = c_in >> 5;
+    const int n_slots = g.imgs * IN_ROWS * LW * 4;             // 16-byte slots of one buffer: [position][4]
+    const int buf_bytes = ((n_slots + 255) & ~255) * 16;       // whole 1 KB blocks of a load instruction
+
+    int base[WB_PB];   // byte offset of the lane's 8 channels of the pixel block's tap (0, 0)
+    f32x4 acc[WB_OB][WB_PB];
+#pragma unroll
+    for (int pt = 0; pt < WB_PB; ++pt) {
+        base[pt] = pixel_lds_base<32, 0>(g, (wpx * WB_PB + pt) * 16 + r16) * (int)sizeof(T) + 16 * grp;
+#pragma unroll
+        for (int o = 0; o < WB_OB; ++o) acc[o][pt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // channels 32*ch + 8*grp .. +7 of a tap: 16-channel block 2*ch + grp/2 of the packed copy, lane groups 2*(grp%2) and
+    // 2*(grp%2) + 1, i.e. two 8-byte pieces 16 lanes apart.  Uniform base plus a per-lane byte offset: one address
+    // register per lane for all weight loads.
+    const char* wbase = static_cast<const char*>(wpk) + (int64_t)ob0 * TAPS * s_total * 512;
+    const unsigned lane_off = (unsigned)(((grp >> 1) * 64 + r16 + 32 * (grp & 1)) * 8);
+    // the weights of block o, tap t, chunk ch
+    auto weights_of = [&](int o, int t, int ch) {
+        const char* p = wbase + (int64_t)((o * TAPS + t) * s_total + 2 * ch) * 512;
+        const quad lo = *reinterpret_cast<const quad*>(p + lane_off), hi = *reinterpret_cast<const quad*>(p + lane_off + 128);
+        return make_uint4(lo.x, lo.y, hi.x, hi.y);
+    };
+
+    // staging: slot v = 256*i + thread of a buffer holds channels 8*(v%4) .. +7 of position v/4; its place in the
+    // tensor does not depend on the chunk
+    const int rpi = 1 << g.rpi_log2;
+    const int row0 = tile * g.rows_tile;
+    const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
+    int goff[WB_NV];   // element offset of the slot's channels in chunk 0, or -1 for a slot that stays zero
+#pragma unroll
+    for (int i = 0; i < WB_NV; ++i) {
+        const int v = threadIdx.x + 256 * i;
+        const int cq = v & 3, pos = v >> 2;
+        const int lc = pos % LW, lr = pos / LW;
+        const int part = lr / IN_ROWS, li = lr - part * IN_ROWS;
+        const int grow = row0 + part * rpi;
+        const int n = grow >> g.wout_log2;
+        const int hi = (grow & (g.h_out - 1)) - g.pad + li;
+        const int wi = lc - g.pad;
+        bool ok = v < n_slots && n < g.B && (unsigned)hi < (unsigned)g.h_in && (unsigned)wi < (unsigned)g.h_in;
+        int hs = hi, ws = wi;
+        if (g.ups) {
+            ok = ok && ((hi | wi) & 1) == 0;
+            hs = hi >> 1;
+            ws = wi >> 1;
+        }
+        goff[i] = ok ? ((n * src_h + hs) * src_h + ws) * c_in + cq * 8 : -1;
+        if (!ok && v < n_slots) {
+            *reinterpret_cast<uint4*>(lds_bytes + v * 16) = make_uint4(0u, 0u, 0u, 0u);
+            *reinterpret_cast<uint4*>(lds_bytes + buf_bytes + v * 16) = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+    auto tile_request = [&](int ch, int buf) {
+#pragma unroll
+        for (int i = 0; i < WB_NV; ++i)
+            if (goff[i] >= 0)
+                __builtin_amdgcn_global_load_lds((wb_global_ptr*)(x + (unsigned)(goff[i] + ch * 32)),
+                                                 (wb_lds_ptr*)(lds_bytes + buf * buf_bytes + (i * 256 + wave * 64) * 16), 16, 0, 0);
+    };
+
+    // The chunk loop is scheduled by hand; every step ends in a scheduling barrier, so the compiler keeps the order.  A
+    // step is one pixel block of one tap: WB_OB matrix instructions.  Before them the pixel operand of step i + WB_AHEAD
+    // is requested from LDS, and in the first WB_OB steps of a tap the weights of one block for the tap after next (the
+    // sets rotate: nine taps, three sets, no copies).  The next chunk's tile is requested at the top of a chunk into the
+    // buffer that every wave left at the barrier.  Loads return in order: the weights requested behind the tile wait for
+    // it (this is where the second workgroup of the compute unit takes over), and by the time the last taps of a chunk
+    // have their weights the tile has landed, so the barrier at the end of the chunk is all that the next chunk needs.
+    uint4 ws[WB_WSETS][WB_OB];
+    tile_request(0, 0);
+#pragma unroll
+    for (int k = 0; k < WB_WSETS - 1; ++k)
+#pragma unroll
+        for (int o = 0; o < WB_OB; ++o) ws[k][o] = weights_of(o, k, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const bool more = ch + 1 < n_chunks;
+        if (more) tile_request(ch + 1, (ch + 1) & 1);
+        // byte addresses of the pixel blocks in this chunk's buffer, as opaque values: the reads below are base register
+        // plus immediate offset of the tap (left to itself the compiler re-adds the terms of base[] before every read)
+        int cur[WB_PB];
+#pragma unroll
+        for (int pt = 0; pt < WB_PB; ++pt) {
+            cur[pt] = base[pt] + (ch & 1) * buf_bytes;
+            asm volatile("" : "+v"(cur[pt]));
+        }
+        auto pixel_operand = [&](int step) {
+            const int t = step / WB_PB, pt = step % WB_PB;
+            const int tap_off = ((t / 3) * LW + (t % 3)) * 64;
+            return *reinterpret_cast<const uint4*>(lds_bytes + cur[pt] + tap_off);
+        };
+        uint4 ring[WB_AHEAD + 1];
+#pragma unroll
+        for (int i = 0; i < WB_AHEAD; ++i) ring[i] = pixel_operand(i);
+        static_for<STEPS>([&](auto step_c) {
+            constexpr int step = decltype(step_c)::value;
+            constexpr int t = step / WB_PB, pt = step % WB_PB;
+            if constexpr (step + WB_AHEAD < STEPS) ring[(step + WB_AHEAD) % (WB_AHEAD + 1)] = pixel_operand(step + WB_AHEAD);
+            if constexpr (pt < WB_OB) {
+                // tap t + 2, possibly of the next chunk (the last chunk reads its own first taps again: unused)
+                constexpr int tn = (t + WB_WSETS - 1) % TAPS;
+                const int nch = (t + WB_WSETS - 1 >= TAPS && more) ? ch + 1 : ch;
+                ws[(t + WB_WSETS - 1) % WB_WSETS][pt] = weights_of(pt, tn, nch);
+            }
+            const uint4 b = ring[step % (WB_AHEAD + 1)];
+#pragma unroll
+            for (int o = 0; o < WB_OB; ++o) WB_MFMA(acc[o][pt], ws[t % WB_WSETS][o], b);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // everything but the 2 * WB_OB * (WB_WSETS - 1) weight loads of the last two taps has returned: the tile, requested
+        // before them, is in LDS
+        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        static_assert(2 * WB_OB * (WB_WSETS - 1) == 16, "the wait above counts the weight loads of the taps requested ahead");
+        __syncthreads();
+    }
+
+    // the results of the last matrix instructions are not interlocked against vector-unit readers: wait them out, in
+    // statements the accumulators pass through, so that no reader moves ahead of the wait
+#pragma unroll
+    for (int o = 0; o < WB_OB; ++o)
+        asm volatile("s_nop 15\n\ts_nop 15"
+                     : "+a"(acc[o][0]), "+a"(acc[o][1]), "+a"(acc[o][2]), "+a"(acc[o][3]), "+a"(acc[o][4]), "+a"(acc[o][5]), "+a"(acc[o][6]), "+a"(acc[o][7]));
+    // epilogue: the lane holds channels (ob0 + o)*16 + 4*grp .. +3 of pixel ((wpx*WB_PB + pt)*16 + r16) of the tile
+    const int64_t pix0 = (int64_t)tile * (2 * WB_PB * 16);
+    const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
+    const T* add = static_cast<const T*>(e.add);
+    // the added tensor is requested for half of the wave's pixel blocks before their first store (see wconv_kernel); what was
+    // stored goes back into the accumulation registers for the batch-norm sums, so that the vector registers stay free
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        constexpr int HP = WB_PB / 2;
+        typename Act<T>::raw4 addv[HP][WB_OB];
+        if (add) {
+#pragma unroll
+            for (int k = 0; k < HP; ++k) {
+                const int64_t p = pix0 + (wpx * WB_PB + half * HP + k) * 16 + r16;
+#pragma unroll
+                for (int o = 0; o < WB_OB; ++o) {
+                    addv[k][o] = Act<T>::zero();
+                    if (p < total_pixels) addv[k][o] = Act<T>::load_raw(add + p * NO + (ob0 + o) * 16 + 4 * grp);
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < HP; ++k) {
+            const int pt = half * HP + k;
+            const int64_t p = pix0 + (wpx * WB_PB + pt) * 16 + r16;
+#pragma unroll
+            for (int o = 0; o < WB_OB; ++o) {
+                const int c0 = (ob0 + o) * 16 + 4 * grp;
+                f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (p < total_pixels) {
+                    v = acc[o][pt];
+                    if (add) v += Act<T>::widen(addv[k][o]);
+                    v = Act<T>::rounded(v);  // the sums see what later kernels read back
+                    Act<T>::store4(y + p * NO + c0, v);
+                }
+                acc[o][pt] = v;
+                asm volatile("" : "+a"(acc[o][pt]));
+            }
+        }
+    }
+    if (e.sums) {
+        // every wave is past its last tile read (barrier after the last chunk): the tile's space carries the lane sums of the
+        // first pixel half ([wo][o][sum, sum of squares][lane] vectors) and the per-wave partials ([block][2][16])
+        f32x4* hand = lds_raw;
+        float* red = reinterpret_cast<float*>(lds_raw + 2 * WB_OB * 2 * 64);
+        f32x4 ssum[WB_OB], ssq[WB_OB];
+#pragma unroll
+        for (int o = 0; o < WB_OB; ++o) ssum[o] = ssq[o] = f32x4{0.f, 0.f, 0.f, 0.f};
+        auto lane_sums = [&]() {
+#pragma unroll
+            for (int o = 0; o < WB_OB; ++o)
+#pragma unroll
+                for (int pt = 0; pt < WB_PB; ++pt) {
+                    const f32x4 v = acc[o][pt];
+                    ssum[o] += v;
+                    ssq[o] += v * v;
+                }
+        };
+        if (wpx == 0) {
+            lane_sums();
+#pragma unroll
+            for (int o = 0; o < WB_OB; ++o) {
+                hand[((wo * WB_OB + o) * 2 + 0) * 64 + lane] = ssum[o];
+                hand[((wo * WB_OB + o) * 2 + 1) * 64 + lane] = ssq[o];
+            }
+        }
+        __syncthreads();
+        if (wpx == 1) {
+#pragma unroll
+            for (int o = 0; o < WB_OB; ++o) {
+                ssum[o] = hand[((wo * WB_OB + o) * 2 + 0) * 64 + lane];
+                ssq[o] = hand[((wo * WB_OB + o) * 2 + 1) * 64 + lane];
+            }
+            lane_sums();
+#pragma unroll
+            for (int o = 0; o < WB_OB; ++o) {
+#pragma unroll
+                for (int s = 1; s < 16; s <<= 1)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        ssum[o][j] += __shfl_xor(ssum[o][j], s, 64);
+                        ssq[o][j] += __shfl_xor(ssq[o][j], s, 64);
+                    }
+                if (r16 == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        red[((wo * WB_OB + o) * 2 + 0) * 16 + 4 * grp + j] = ssum[o][j];
+                        red[((wo * WB_OB + o) * 2 + 1) * 16 + 4 * grp + j] = ssq[o][j];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const int which = threadIdx.x >> 7, c = threadIdx.x & 127;   // channel c of this workgroup's 128
+        fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + blockIdx.y * 128 + c,
+                   (double)red[((c >> 4) * 2 + which) * 16 + (c & 15)] * e.scale, e.limit);
+    }
+}
+
 // Tile: 256 pixels when the staged chunk fits 64 KB (two workgroups per compute unit), else 128.  The prefetching
 // path needs the chunk tile to fit WC_NV vectors per thread and two buffers to fit 80 KB.
 template <typename T, int TAPS, int CK>
@@ -253,6 +551,24 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
     const int pad = TAPS == 9 ? 1 : 0;
     auto geom = [&](int npt) { return make_geom(B, h_in, h_out, c_out, stride, ups, c_in, (npt * 16) / h_out, pad); };
     if (h_out > 128) return -1;
+    if constexpr (sizeof(T) == 2 && TAPS == 9 && CK == 32) {
+        // large launches of stride-1 layers with output channels in multiples of 128: the register-blocked kernel
+        if (stride == 1 && c_out % 128 == 0 && c_in % 32 == 0 && (int64_t)B * h_in * h_in * c_in < (int64_t(1) << 31)) {
+            const ConvGeom gb = geom(2 * WB_PB);
+            const int n_slots = gb.imgs * gb.in_rows * gb.lw * 4;
+            const bool shape = (gb.lw == 34 && gb.in_rows == 10) || (gb.lw == 18 && gb.in_rows == 18) || (gb.lw == 10 && gb.in_rows == 10);
+            if (shape && n_slots <= 256 * WB_NV && (int64_t)gb.n_tiles * (c_out / 128) >= 128) {
+                size_t lds_b = 2 * (size_t)((n_slots + 255) & ~255) * 16;
+                const size_t fold = (2 * WB_OB * 2 * 64) * sizeof(f32x4) + 2 * WB_OB * 2 * 16 * sizeof(float);   // lane sums + per-wave partials
+                if (lds_b < fold) lds_b = fold;
+                WEpi eb = e_in;
+                eb.limit = 576460752303423488.0 / (double)((gb.n_tiles + FIX_REPLICAS - 1) / FIX_REPLICAS);   // 2^59 over the partials one word takes
+                auto kern = gb.lw == 34 ? wconv_block_kernel<34> : gb.lw == 18 ? wconv_block_kernel<18> : wconv_block_kernel<10>;
+                hipLaunchKernelGGL(kern, dim3(gb.n_tiles, c_out / 128), dim3(256), lds_b, s, x, w, y, eb, gb, c_in);
+                return 0;
+            }
+        }
+    }
     ConvGeom g = geom(16);
     int npt = 16;
     size_t lds = wconv_lds_bytes<T, TAPS, CK>(g);

@@ -191,3 +191,38 @@ def test_bf16_weight_gradient_several_tiles_per_workgroup(env):
     _, g64, _ = oracle.loss_and_grads(oracle.WideResNet(widths, 1, stem), p, b, x[sel], y[sel])
     for k in grads:
         assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
+
+
+@pytest.mark.parametrize("hw,blocks,n,tail", [
+    (16, 2, 522, 22),    # 16x16 maps: one image per 256-pixel tile; 8x8 maps: four images per tile, the last tile half empty
+    (32, 1, 40, 6),      # 32x32 maps: tiles of 8 rows
+])
+def test_bf16_large_launches_score_like_small_ones(env, hw, blocks, n, tail):
+    """Stride-1 3x3 layers with 128 output channels go through the register-blocked kernel (256 pixels x 128 channels per
+    workgroup, tile loaded straight into LDS) once a launch has 128 workgroups, and through the one-block-per-wave kernel
+    below that.  Both consume chunks and taps in the same order: the losses of the last images must not depend on whether they
+    are scored with the large launch or by themselves, and they match the oracle."""
+    widths, classes, stem = (128, 128, 128), 10, 16
+    h = _harness(env, widths, blocks, hw, classes, stem, "bf16")
+    p, b = synth.wrn_init(CFG["id"], widths, blocks, classes, stem, perturb_bn=0.2)
+    x, y = synth.image_pool(CFG["id"], n, classes, hw=hw)
+    full = h.score(p, b, x, y)
+    assert np.array_equal(full[n - tail:], h.score(p, b, x[n - tail:], y[n - tail:]))
+    assert_losses_close(full[n - tail:], oracle.score_losses(h.oracle_model, p, b, x[n - tail:], y[n - tail:]), rtol=5e-3)
+
+
+def test_bf16_large_launches_training_step(env):
+    """128 images of 16x16 with 128 channels: the forward launch of the first stage's second convolution (with batch-norm sums
+    across the two pixel halves of a workgroup), its input gradient and the input gradient of the stride-2 layer above it (zeros
+    inserted on load) all have 128 tiles and take the register-blocked kernel.  Some bf16 roundings flip at this size, so the
+    criterion is the envelope one: no further from the float64 oracle than the bf16 oracle itself is (x 1.5, + 0.03)."""
+    widths, blocks, hw, classes, stem, batch = (128, 128, 128), 1, 16, 10, 16, 128
+    h = _harness(env, widths, blocks, hw, classes, stem, "bf16")
+    p, b, x, y, sel = _case(widths, blocks, hw, batch, classes, stem)
+    losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses, rtol=2e-2)
+    assert_tensors_close(gb, new_b, 5e-3, "running statistics")
+    _, g64, _ = oracle.loss_and_grads(oracle.WideResNet(widths, blocks, stem), p, b, x[sel], y[sel])
+    for k in grads:
+        assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
