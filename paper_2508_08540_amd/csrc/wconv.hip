@@ -289,7 +289,8 @@ __device__ __forceinline__ void static_for(F&& f) {
 // so both kernels give the same bits.
 #define WB_OB 4
 #define WB_PB 8
-#define WB_NV 7        // 16-byte slots of a chunk tile per thread, at most
+#define WB_NV 7            // 16-byte slots of a chunk tile per thread, at most
+#define WB_NV_STRIDE2 10   // the same for a stride-2 layer (17 input rows of 34 positions)
 #define WB_AHEAD 3     // pixel operands requested from LDS ahead of their matrix instructions
 #define WB_WSETS 3     // weight register sets (one tap each): the tap in use and the two requested behind it
 // The matrix instruction as an assembly statement: accumulator in place in the accumulation registers, operands in
@@ -302,22 +303,27 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void wb_global_ptr;
 typedef __attribute__((address_space(3))) void wb_lds_ptr;
 
-template <int LW>
+template <int LW, int STRIDE>
 __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __restrict__ x, const void* __restrict__ wpk, bf16_t* __restrict__ y,
                                                              WEpi e, ConvGeom g, int c_in) {
     __builtin_amdgcn_s_setprio(2);
     typedef bf16_t T;
     typedef Tile<T>::quad quad;
     constexpr int TAPS = 9, STEPS = TAPS * WB_PB;
-    constexpr int IN_ROWS = LW == 18 ? 18 : 10;   // rows of an image part with halo: the whole 16-row image, or 8 rows
+    // Stride 1: 2 x 2 waves of (64 channels, 128 pixels).  Stride 2: the input rows of 256 output pixels do not fit two
+    // buffers, so the tile has 128 pixels and the four waves hold 64 channels each (WIDE).
+    constexpr bool WIDE = STRIDE == 2;
+    constexpr int OCW = WIDE ? 4 : 2;                                     // 64-channel groups of a workgroup
+    constexpr int IN_ROWS = WIDE ? 17 : (LW == 18 ? 18 : 10);             // rows of an image part with halo (8 output rows, or a whole 16-row image)
+    constexpr int NV = WIDE ? WB_NV_STRIDE2 : WB_NV;
     extern __shared__ f32x4 lds_raw[];
     char* lds_bytes = reinterpret_cast<char*>(lds_raw);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform by construction; says so to the compiler
     const int r16 = lane & 15, grp = lane >> 4;
-    const int wo = wave & 1, wpx = wave >> 1;   // output-channel half and pixel half of this wave
+    const int wo = WIDE ? wave : wave & 1, wpx = WIDE ? 0 : wave >> 1;   // 64-channel group and pixel half of this wave
     const int NO = g.c_out;
-    const int ob0 = blockIdx.y * (2 * WB_OB) + wo * WB_OB;
+    const int ob0 = blockIdx.y * (OCW * WB_OB) + wo * WB_OB;
     const int tile = blockIdx.x;
     const int s_total = c_in >> 4;
     const int n_chunks = c_in >> 5;
@@ -349,16 +355,16 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
     const int rpi = 1 << g.rpi_log2;
     const int row0 = tile * g.rows_tile;
     const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
-    int goff[WB_NV];   // element offset of the slot's channels in chunk 0, or -1 for a slot that stays zero
+    int goff[NV];   // element offset of the slot's channels in chunk 0, or -1 for a slot that stays zero
 #pragma unroll
-    for (int i = 0; i < WB_NV; ++i) {
+    for (int i = 0; i < NV; ++i) {
         const int v = threadIdx.x + 256 * i;
         const int cq = v & 3, pos = v >> 2;
         const int lc = pos % LW, lr = pos / LW;
         const int part = lr / IN_ROWS, li = lr - part * IN_ROWS;
         const int grow = row0 + part * rpi;
         const int n = grow >> g.wout_log2;
-        const int hi = (grow & (g.h_out - 1)) - g.pad + li;
+        const int hi = (grow & (g.h_out - 1)) * STRIDE - g.pad + li;
         const int wi = lc - g.pad;
         bool ok = v < n_slots && n < g.B && (unsigned)hi < (unsigned)g.h_in && (unsigned)wi < (unsigned)g.h_in;
         int hs = hi, ws = wi;
@@ -375,7 +381,7 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
     }
     auto tile_request = [&](int ch, int buf) {
 #pragma unroll
-        for (int i = 0; i < WB_NV; ++i)
+        for (int i = 0; i < NV; ++i)
             if (goff[i] >= 0)
                 __builtin_amdgcn_global_load_lds((wb_global_ptr*)(x + (unsigned)(goff[i] + ch * 32)),
                                                  (wb_lds_ptr*)(lds_bytes + buf * buf_bytes + (i * 256 + wave * 64) * 16), 16, 0, 0);
@@ -444,7 +450,7 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
         asm volatile("s_nop 15\n\ts_nop 15"
                      : "+a"(acc[o][0]), "+a"(acc[o][1]), "+a"(acc[o][2]), "+a"(acc[o][3]), "+a"(acc[o][4]), "+a"(acc[o][5]), "+a"(acc[o][6]), "+a"(acc[o][7]));
     // epilogue: the lane holds channels (ob0 + o)*16 + 4*grp .. +3 of pixel ((wpx*WB_PB + pt)*16 + r16) of the tile
-    const int64_t pix0 = (int64_t)tile * (2 * WB_PB * 16);
+    const int64_t pix0 = (int64_t)tile * ((WIDE ? 1 : 2) * WB_PB * 16);
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
     const T* add = static_cast<const T*>(e.add);
     // the added tensor is requested for half of the wave's pixel blocks before their first store (see wconv_kernel); what was
@@ -501,22 +507,7 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
                     ssq[o] += v * v;
                 }
         };
-        if (wpx == 0) {
-            lane_sums();
-#pragma unroll
-            for (int o = 0; o < WB_OB; ++o) {
-                hand[((wo * WB_OB + o) * 2 + 0) * 64 + lane] = ssum[o];
-                hand[((wo * WB_OB + o) * 2 + 1) * 64 + lane] = ssq[o];
-            }
-        }
-        __syncthreads();
-        if (wpx == 1) {
-#pragma unroll
-            for (int o = 0; o < WB_OB; ++o) {
-                ssum[o] = hand[((wo * WB_OB + o) * 2 + 0) * 64 + lane];
-                ssq[o] = hand[((wo * WB_OB + o) * 2 + 1) * 64 + lane];
-            }
-            lane_sums();
+        auto fold_lanes = [&]() {   // the 16 pixels of a lane group, then one lane per group writes its four channels
 #pragma unroll
             for (int o = 0; o < WB_OB; ++o) {
 #pragma unroll
@@ -534,11 +525,37 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
                     }
                 }
             }
+        };
+        if constexpr (WIDE) {   // a wave has all pixel blocks of its channels
+            lane_sums();
+            fold_lanes();
+        } else {
+            if (wpx == 0) {
+                lane_sums();
+#pragma unroll
+                for (int o = 0; o < WB_OB; ++o) {
+                    hand[((wo * WB_OB + o) * 2 + 0) * 64 + lane] = ssum[o];
+                    hand[((wo * WB_OB + o) * 2 + 1) * 64 + lane] = ssq[o];
+                }
+            }
+            __syncthreads();
+            if (wpx == 1) {
+#pragma unroll
+                for (int o = 0; o < WB_OB; ++o) {
+                    ssum[o] = hand[((wo * WB_OB + o) * 2 + 0) * 64 + lane];
+                    ssq[o] = hand[((wo * WB_OB + o) * 2 + 1) * 64 + lane];
+                }
+                lane_sums();
+                fold_lanes();
+            }
         }
         __syncthreads();
-        const int which = threadIdx.x >> 7, c = threadIdx.x & 127;   // channel c of this workgroup's 128
-        fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + blockIdx.y * 128 + c,
-                   (double)red[((c >> 4) * 2 + which) * 16 + (c & 15)] * e.scale, e.limit);
+        constexpr int CH = OCW * 64;   // channels of this workgroup
+        for (int k = threadIdx.x; k < 2 * CH; k += 256) {
+            const int which = k / CH, c = k % CH;
+            fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + blockIdx.y * CH + c,
+                       (double)red[((c >> 4) * 2 + which) * 16 + (c & 15)] * e.scale, e.limit);
+        }
     }
 }
 
@@ -552,19 +569,35 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
     auto geom = [&](int npt) { return make_geom(B, h_in, h_out, c_out, stride, ups, c_in, (npt * 16) / h_out, pad); };
     if (h_out > 128) return -1;
     if constexpr (sizeof(T) == 2 && TAPS == 9 && CK == 32) {
-        // large launches of stride-1 layers with output channels in multiples of 128: the register-blocked kernel
-        if (stride == 1 && c_out % 128 == 0 && c_in % 32 == 0 && (int64_t)B * h_in * h_in * c_in < (int64_t(1) << 31)) {
-            const ConvGeom gb = geom(2 * WB_PB);
+        // launches of at least 128 workgroups of the register-blocked kernel: stride 1 with output channels in multiples of 128,
+        // stride 2 in multiples of 256
+        const bool small_offsets = (int64_t)B * (ups ? h_in / 2 : h_in) * (ups ? h_in / 2 : h_in) * c_in < (int64_t(1) << 31);
+        const size_t fold = (2 * WB_OB * 2 * 64) * sizeof(f32x4) + 4 * WB_OB * 2 * 16 * sizeof(float);   // lane sums + per-wave partials
+        auto launch_block = [&](auto kern, const ConvGeom& gb, int oc_wg) {
             const int n_slots = gb.imgs * gb.in_rows * gb.lw * 4;
+            size_t lds_b = 2 * (size_t)((n_slots + 255) & ~255) * 16;
+            if (lds_b < fold) lds_b = fold;
+            WEpi eb = e_in;
+            eb.limit = 576460752303423488.0 / (double)((gb.n_tiles + FIX_REPLICAS - 1) / FIX_REPLICAS);   // 2^59 over the partials one word takes
+            if (lds_b > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_b);
+            hipLaunchKernelGGL(kern, dim3(gb.n_tiles, c_out / oc_wg), dim3(256), lds_b, s, x, w, y, eb, gb, c_in);
+        };
+        if (stride == 1 && c_out % 128 == 0 && c_in % 32 == 0 && small_offsets) {
+            const ConvGeom gb = geom(2 * WB_PB);
             const bool shape = (gb.lw == 34 && gb.in_rows == 10) || (gb.lw == 18 && gb.in_rows == 18) || (gb.lw == 10 && gb.in_rows == 10);
-            if (shape && n_slots <= 256 * WB_NV && (int64_t)gb.n_tiles * (c_out / 128) >= 128) {
-                size_t lds_b = 2 * (size_t)((n_slots + 255) & ~255) * 16;
-                const size_t fold = (2 * WB_OB * 2 * 64) * sizeof(f32x4) + 2 * WB_OB * 2 * 16 * sizeof(float);   // lane sums + per-wave partials
-                if (lds_b < fold) lds_b = fold;
-                WEpi eb = e_in;
-                eb.limit = 576460752303423488.0 / (double)((gb.n_tiles + FIX_REPLICAS - 1) / FIX_REPLICAS);   // 2^59 over the partials one word takes
-                auto kern = gb.lw == 34 ? wconv_block_kernel<34> : gb.lw == 18 ? wconv_block_kernel<18> : wconv_block_kernel<10>;
-                hipLaunchKernelGGL(kern, dim3(gb.n_tiles, c_out / 128), dim3(256), lds_b, s, x, w, y, eb, gb, c_in);
+            if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV && (int64_t)gb.n_tiles * (c_out / 128) >= 128) {
+                if (gb.lw == 34) launch_block(wconv_block_kernel<34, 1>, gb, 128);
+                else if (gb.lw == 18) launch_block(wconv_block_kernel<18, 1>, gb, 128);
+                else launch_block(wconv_block_kernel<10, 1>, gb, 128);
+                return 0;
+            }
+        }
+        if (stride == 2 && !ups && c_out % 256 == 0 && c_in % 32 == 0 && small_offsets) {
+            const ConvGeom gb = geom(WB_PB);
+            const bool shape = (gb.lw == 34 || gb.lw == 18) && gb.in_rows == 17;
+            if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV_STRIDE2 && (int64_t)gb.n_tiles * (c_out / 256) >= 128) {
+                if (gb.lw == 34) launch_block(wconv_block_kernel<34, 2>, gb, 256);
+                else launch_block(wconv_block_kernel<18, 2>, gb, 256);
                 return 0;
             }
         }

@@ -193,16 +193,18 @@ def test_bf16_weight_gradient_several_tiles_per_workgroup(env):
         assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
 
 
-@pytest.mark.parametrize("hw,blocks,n,tail", [
-    (16, 2, 522, 22),    # 16x16 maps: one image per 256-pixel tile; 8x8 maps: four images per tile, the last tile half empty
-    (32, 1, 40, 6),      # 32x32 maps: tiles of 8 rows
+@pytest.mark.parametrize("widths,hw,blocks,n,tail", [
+    ((128, 128, 128), 16, 2, 522, 22),   # 16x16 maps: one image per 256-pixel tile; 8x8 maps: four images per tile, the last tile half empty
+    ((128, 128, 128), 32, 1, 40, 6),     # 32x32 maps: tiles of 8 rows
+    ((128, 256, 256), 16, 1, 259, 9),    # stride 2 from 16x16 to 8x8 with 256 output channels: two images per 128-pixel tile, the last one half empty
+    ((128, 256, 256), 32, 1, 70, 6),     # stride 2 from 32x32 to 16x16: tiles of 8 output rows, 17 input rows
 ])
-def test_bf16_large_launches_score_like_small_ones(env, hw, blocks, n, tail):
-    """Stride-1 3x3 layers with 128 output channels go through the register-blocked kernel (256 pixels x 128 channels per
-    workgroup, tile loaded straight into LDS) once a launch has 128 workgroups, and through the one-block-per-wave kernel
+def test_bf16_large_launches_score_like_small_ones(env, widths, hw, blocks, n, tail):
+    """3x3 layers go through the register-blocked kernel (stride 1: 256 pixels x 128 channels per workgroup, stride 2: 128 x
+    256; tile loaded straight into LDS) once a launch has 128 workgroups, and through the one-block-per-wave kernel
     below that.  Both consume chunks and taps in the same order: the losses of the last images must not depend on whether they
     are scored with the large launch or by themselves, and they match the oracle."""
-    widths, classes, stem = (128, 128, 128), 10, 16
+    classes, stem = 10, 16
     h = _harness(env, widths, blocks, hw, classes, stem, "bf16")
     p, b = synth.wrn_init(CFG["id"], widths, blocks, classes, stem, perturb_bn=0.2)
     x, y = synth.image_pool(CFG["id"], n, classes, hw=hw)
