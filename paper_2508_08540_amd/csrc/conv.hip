@@ -485,7 +485,6 @@ __global__ __launch_bounds__(NW * 64, (MULTI && CIN == 64) ? 2 : 1) void conv_ke
     constexpr bool RES = XF == 2;
     extern __shared__ f32x4 lds_raw[];  // vector-typed so that tile reads and writes are single 16- or 8-byte LDS accesses
     quad* lds4 = reinterpret_cast<quad*>(lds_raw);
-    float* lds = reinterpret_cast<float*>(lds_raw);
     constexpr int S = CIN / 16;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r16 = lane & 15, grp = lane >> 4;

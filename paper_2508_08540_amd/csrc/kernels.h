@@ -150,6 +150,9 @@ struct BnStats {
     double count;
     float *mean, *invstd, *running_mean, *running_var;
 };
+// mean[c] = running_mean[c], invstd[c] = 1 / sqrt(running_var[c] + BN_EPS) rounded as bn_apply_kernel rounds it: the
+// constants of a batch norm in inference, for kernels that apply it in their epilogue
+void launch_bn_inference_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean, float* invstd);
 // a = relu(gamma * (y - mean) * invstd + beta [+ shortcut(res)]); res has c_res channels at res_stride x resolution
 void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int C, const BnStats& st, const float* gamma,
                      const float* beta, const void* res, int c_res, int res_stride, int h_out, void* out, Reps reps = Reps{});
@@ -265,8 +268,15 @@ void launch_update(hipStream_t s, int act, float* params, float* momentum, const
 // stride is 1 and ups = 1 reads x with zeros inserted, which undoes a stride-2 layer).  With `sums` the
 // (sum, sum of squares) of the stored values are added into [replica][2][c_out] accumulators scaled by `scale`.
 // Returns 0, or -1 for a shape the kernel does not cover (nothing is launched).
+// With `bn` (inference) the batch norm with running statistics and the ReLU of the layer that reads the result are applied
+// before the store: y = relu(bn(r)) with r the result rounded to the storage type, which also goes to bn->raw when that is
+// not null (a later identity shortcut adds it).  The arithmetic is bn_apply_kernel's.  Not together with `sums`.
+struct WconvBn {
+    const float *mean, *invstd, *gamma, *beta;   // per output channel
+    void* raw;
+};
 int launch_wconv(hipStream_t s, int act, int taps, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const void* x,
-                 const void* w, void* y, const void* add, fixsum_t* sums, double scale);
+                 const void* w, void* y, const void* add, fixsum_t* sums, double scale, const WconvBn* bn = nullptr);
 
 // ---- gemm_tiled.hip -----------------------------------------------------------------------------------
 // C[m][n] = alpha * sum_k A(m,k) B(n,k) [+ bias[n]] [+ R[m][n]]; A(m,k) = a_kmajor ? A[k*lda + m] : A[m*lda + k], same for B.

@@ -223,11 +223,11 @@ size_t scratch_bytes(const bls_model* m, int B, bool train) {
 
 // y = conv(x) [+ add], optional statistics of y into `stats` (forward accumulators of the batch norm that reads y)
 int conv_fwd(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const ConvRef& cr, int B, const act_t* x, act_t* y, const act_t* add,
-             fixsum_t* stats) {
+             fixsum_t* stats, const WconvBn* bn = nullptr) {
     const ConvSlot& c = *cr.slot;
     ProfScope prof_(ctx, PROF_CONV_FWD);
     if (launch_wconv(st, s.act, c.taps, B, c.h_in, c.h_out, padded(c.c_in), c.c_out, c.stride, 0, x, s.wpack + cr.fwd_off, y, add, stats,
-                     FIX_FWD_SCALE) != 0)
+                     FIX_FWD_SCALE, bn) != 0)
         return bls_fail(ctx, BLS_EUNSUPPORTED, "convolution %dx%d, %d -> %d channels, map %d is outside what the kernels cover",
                         c.taps == 9 ? 3 : 1, c.taps == 9 ? 3 : 1, c.c_in, c.c_out, c.h_in);
     return BLS_OK;
@@ -325,9 +325,9 @@ void conv_wgrad(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const ConvRef
 }
 
 void bn_forward(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const BnRef& bn, const float* params, float* buffers, int64_t pixels,
-                const act_t* y, act_t* out, bool train) {
+                const act_t* y, act_t* out) {
     BnStats bs{};
-    bs.sums = train ? bn.fsums : nullptr;
+    bs.sums = bn.fsums;
     bs.count = (double)pixels;
     bs.mean = bn.mean; bs.invstd = bn.invstd;
     bs.running_mean = buffers + bn.slot->rmean_off; bs.running_var = buffers + bn.slot->rvar_off;
@@ -344,12 +344,16 @@ void bn_backward(bls_ctx* ctx, hipStream_t st, const WrnScratch& s, const BnRef&
                         s.grad + bn.slot->gamma_off, s.grad + bn.slot->beta_off, dy, nullptr, add);
 }
 
-// Forward over a batch gathered into s.xpad.  Training keeps what the backward pass needs; inference rotates four buffers.
-int forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, WrnScratch& s, bool train,
-            bool prepare, const act_t** final_act) {
+// Inference forward over a batch gathered into s.xpad.  Every batch norm uses running statistics, which are known before
+// the convolution that produces its input runs: that convolution applies it (and the ReLU) in its epilogue and stores the
+// activation the next layer reads; the raw sum of a block goes to memory as well only where the next block adds it back
+// through an identity shortcut.  No batch-norm launches; four buffers rotate.
+int forward_inference(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, const float* buffers, int B, WrnScratch& s,
+                      bool prepare, const act_t** final_act) {
     if (prepare) {
         PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab));
-        if (train) PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), s.n_sums * 2));
+        for (const BnRef& bn : s.bns)
+            PROF(ctx, PROF_NORM, launch_bn_inference_stats(st, buffers + bn.slot->rmean_off, buffers + bn.slot->rvar_off, bn.slot->c, bn.mean, bn.invstd));
     }
     act_t* rot[4] = {s.g1, s.g2, s.g3, s.g4};
     int next = 0;
@@ -360,44 +364,90 @@ int forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* param
             if (p != k0 && p != k1 && p != k2) return p;
         }
     };
-    const int hw = m->desc.image_hw;
+    auto fused = [&](const BnRef& bn, act_t* raw) {
+        return WconvBn{bn.mean, bn.invstd, params + bn.slot->gamma_off, params + bn.slot->beta_off, raw};
+    };
+    const size_t nb = m->wrn_blocks.size();
     int rc;
-    act_t* cur = train ? s.y0 : take(nullptr, nullptr, nullptr);
     size_t ci = 0, bi = 0;
-    rc = conv_fwd(ctx, st, s, s.convs[ci++], B, s.xpad, cur, nullptr, train ? s.bns[0].fsums : nullptr);
+    // the stem's output: normalised by the first block's first batch norm, raw as well when that block's shortcut is the identity
+    act_t* cur = take(nullptr, nullptr, nullptr);                                   // relu(bn1(block input))
+    act_t* cur_raw = (nb && !m->wrn_blocks[0].proj) ? take(cur, nullptr, nullptr) : nullptr;   // block input
+    {
+        const WconvBn f = fused(s.bns[0], cur_raw);
+        rc = conv_fwd(ctx, st, s, s.convs[ci++], B, s.xpad, cur, nullptr, nullptr, &f);
+        if (rc != BLS_OK) return rc;
+    }
+    for (size_t i = 0; i < nb; ++i) {
+        const WrnBlock& b = m->wrn_blocks[i];
+        ++bi;                                    // bn1 was applied by the producer of `cur`
+        const BnRef& bn2 = s.bns[bi++];
+        const BnRef& bn_next = s.bns[bi];        // the batch norm that reads this block's output
+        act_t* o2 = take(cur, cur_raw, nullptr);
+        {
+            const WconvBn f = fused(bn2, nullptr);
+            rc = conv_fwd(ctx, st, s, s.convs[ci++], B, cur, o2, nullptr, nullptr, &f);
+            if (rc != BLS_OK) return rc;
+        }
+        const ConvRef& c2 = s.convs[ci++];
+        const act_t* shortcut = cur_raw;
+        if (b.proj) {
+            act_t* sc = take(cur, o2, nullptr);
+            rc = conv_fwd(ctx, st, s, s.convs[ci++], B, cur, sc, nullptr, nullptr);
+            if (rc != BLS_OK) return rc;
+            shortcut = sc;
+        }
+        const bool raw_needed = i + 1 < nb && !m->wrn_blocks[i + 1].proj;
+        act_t* out = take(o2, shortcut, nullptr);
+        act_t* out_raw = raw_needed ? take(o2, shortcut, out) : nullptr;
+        {
+            const WconvBn f = fused(bn_next, out_raw);
+            rc = conv_fwd(ctx, st, s, c2, B, o2, out, shortcut, nullptr, &f);
+            if (rc != BLS_OK) return rc;
+        }
+        cur = out;
+        cur_raw = out_raw;
+    }
+    *final_act = cur;
+    return BLS_OK;
+}
+
+// Training forward over a batch gathered into s.xpad: batch statistics, and everything the backward pass needs is kept.
+int forward(bls_ctx* ctx, hipStream_t st, const bls_model* m, const float* params, float* buffers, int B, WrnScratch& s, bool prepare,
+            const act_t** final_act) {
+    if (prepare) {
+        PROF(ctx, PROF_UPDATE, launch_pack_weights(st, s.act, params, s.wpack, s.tab));
+        PROF(ctx, PROF_UPDATE, launch_fill_zero(st, reinterpret_cast<float*>(s.sums), s.n_sums * 2));
+    }
+    int rc;
+    act_t* cur = s.y0;
+    size_t ci = 0, bi = 0;
+    rc = conv_fwd(ctx, st, s, s.convs[ci++], B, s.xpad, cur, nullptr, s.bns[0].fsums);
     if (rc != BLS_OK) return rc;
-    (void)hw;
     for (size_t i = 0; i < m->wrn_blocks.size(); ++i) {
         const WrnBlock& b = m->wrn_blocks[i];
         const int64_t px_in = (int64_t)B * b.conv1.h_in * b.conv1.h_in, px_out = (int64_t)B * b.conv1.h_out * b.conv1.h_out;
         const BnRef& bn1 = s.bns[bi++];
         const BnRef& bn2 = s.bns[bi++];
         const BnRef& bn_next = s.bns[bi];  // the batch norm that reads this block's output
-        act_t* o1 = train ? s.o1[i] : take(cur, nullptr, nullptr);
-        bn_forward(ctx, st, s, bn1, params, buffers, px_in, cur, o1, train);
-        act_t* y1 = train ? s.y1[i] : take(cur, o1, nullptr);
-        rc = conv_fwd(ctx, st, s, s.convs[ci++], B, o1, y1, nullptr, train ? bn2.fsums : nullptr);
+        bn_forward(ctx, st, s, bn1, params, buffers, px_in, cur, s.o1[i]);
+        rc = conv_fwd(ctx, st, s, s.convs[ci++], B, s.o1[i], s.y1[i], nullptr, bn2.fsums);
         if (rc != BLS_OK) return rc;
         const ConvRef& c2 = s.convs[ci++];
         const act_t* shortcut = cur;
         if (b.proj) {
-            act_t* sc = train ? s.sc[i] : take(cur, o1, y1);
-            rc = conv_fwd(ctx, st, s, s.convs[ci++], B, o1, sc, nullptr, nullptr);
+            rc = conv_fwd(ctx, st, s, s.convs[ci++], B, s.o1[i], s.sc[i], nullptr, nullptr);
             if (rc != BLS_OK) return rc;
-            shortcut = sc;
+            shortcut = s.sc[i];
         }
-        // o2 may reuse o1's buffer in inference once the shortcut branch has been taken from it
-        act_t* o2 = train ? s.o2[i] : take(y1, shortcut, nullptr);
-        bn_forward(ctx, st, s, bn2, params, buffers, px_out, y1, o2, train);
-        act_t* out = train ? s.out[i] : take(o2, shortcut, nullptr);
-        rc = conv_fwd(ctx, st, s, c2, B, o2, out, shortcut, train ? bn_next.fsums : nullptr);
+        bn_forward(ctx, st, s, bn2, params, buffers, px_out, s.y1[i], s.o2[i]);
+        rc = conv_fwd(ctx, st, s, c2, B, s.o2[i], s.out[i], shortcut, bn_next.fsums);
         if (rc != BLS_OK) return rc;
-        cur = out;
+        cur = s.out[i];
     }
     const int64_t px = (int64_t)B * m->final_hw * m->final_hw;
-    act_t* fin = train ? s.a_final : take(cur, nullptr, nullptr);
-    bn_forward(ctx, st, s, s.bns[bi], params, buffers, px, cur, fin, train);
-    *final_act = fin;
+    bn_forward(ctx, st, s, s.bns[bi], params, buffers, px, cur, s.a_final);
+    *final_act = s.a_final;
     return BLS_OK;
 }
 
@@ -483,7 +533,7 @@ int wrn_score(bls_ctx* ctx, const bls_model* m, const float* params, const float
         int B = (int)(N - first < chunk ? N - first : chunk);
         PROF(ctx, PROF_GATHER, launch_gather_images(st, x, y, nullptr, 1, 0, first, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
         const act_t* fin = nullptr;
-        rc = forward(ctx, st, m, params, const_cast<float*>(buffers), B, s, false, first == 0, &fin);
+        rc = forward_inference(ctx, st, m, params, buffers, B, s, first == 0, &fin);
         if (rc != BLS_OK) return rc;
         PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b,
                                                  m->desc.classes, s.yb, losses_out + first, nullptr, nullptr, nullptr, 0.f, false));
@@ -509,7 +559,7 @@ int wrn_local_step(bls_ctx* ctx, const bls_model* m, float* params, float* buffe
         float* loss = step_losses_out ? step_losses_out + j * B : s.loss;
         PROF(ctx, PROF_GATHER, launch_gather_images(st, x_pool, y_pool, sel, k, j * B, 0, B, hw * hw, m->desc.in_channels, PAD_C, s.act, s.xpad, s.yb));
         const act_t* fin = nullptr;
-        rc = forward(ctx, st, m, params, buffers, B, s, true, j == 0, &fin);
+        rc = forward(ctx, st, m, params, buffers, B, s, j == 0, &fin);
         if (rc != BLS_OK) return rc;
         PROF(ctx, PROF_HEAD, launch_head_forward(st, s.act, fin, B, m->final_hw * m->final_hw, m->final_c, params + m->fc_w, params + m->fc_b, C,
                                                  s.yb, loss, s.feat, s.dlogits, s.dfeat, inv_b, false));

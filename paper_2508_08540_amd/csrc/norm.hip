@@ -138,6 +138,18 @@ void launch_bn_apply(hipStream_t s, int act, const void* y, int64_t pixels, int 
     });
 }
 
+__global__ __launch_bounds__(256) void bn_inference_stats_kernel(const float* __restrict__ running_mean, const float* __restrict__ running_var,
+                                                                 int C, float* __restrict__ mean, float* __restrict__ invstd) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    mean[c] = running_mean[c];
+    invstd[c] = (float)(1.0 / sqrt((double)running_var[c] + BN_EPS));
+}
+
+void launch_bn_inference_stats(hipStream_t s, const float* running_mean, const float* running_var, int C, float* mean, float* invstd) {
+    hipLaunchKernelGGL(bn_inference_stats_kernel, dim3((C + 255) / 256), dim3(256), 0, s, running_mean, running_var, C, mean, invstd);
+}
+
 // ---- backward -------------------------------------------------------------------------------------
 
 int bn_bwd_partials(int64_t pixels) {

@@ -20,7 +20,15 @@ struct WEpi {
     fixsum_t* sums;    // [replica][2][c_out] accumulators for (sum, sum of squares) of the stored values, or nullptr
     double scale;
     double limit;      // bound of one workgroup's partial in scaled units (the grid is not capped here: 2^61 / contributions per word)
+    WconvBn bn;        // bn.mean != nullptr: batch norm and ReLU of the reading layer before the store (inference)
 };
+
+// relu(bn(v)) for the four channels of a lane, exactly as bn_apply_kernel computes it (its residual term is zero here)
+__device__ __forceinline__ f32x4 wconv_bn_relu(f32x4 v, const f32x4& mu, const f32x4& is, const f32x4& ga, const f32x4& be) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = relu_keep_nan(__fmaf_rn((v[j] - mu[j]) * is[j], ga[j], be[j]) + 0.f);
+    return v;
+}
 
 // bf16 chunks of 32 channels run on v_mfma_f32_16x16x32_bf16: lane group g supplies channels 8g .. 8g+7 of both
 // operands, the pixel pitch in LDS is 96 bytes (16-byte reads of 16 pixels x 4 channel groups run at the full LDS rate
@@ -217,6 +225,14 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
                 if (p < total_pixels) addv[pt] = Act<T>::load_raw(add + p * NO + c0);
             }
         }
+        f32x4 bn_mu = {0.f, 0.f, 0.f, 0.f}, bn_is = bn_mu, bn_ga = bn_mu, bn_be = bn_mu;
+        T* raw = static_cast<T*>(e.bn.raw);
+        if (e.bn.mean) {
+            bn_mu = *reinterpret_cast<const f32x4*>(e.bn.mean + c0);
+            bn_is = *reinterpret_cast<const f32x4*>(e.bn.invstd + c0);
+            bn_ga = *reinterpret_cast<const f32x4*>(e.bn.gamma + c0);
+            bn_be = *reinterpret_cast<const f32x4*>(e.bn.beta + c0);
+        }
 #pragma unroll
         for (int pt = 0; pt < NPT; ++pt) {
             const int64_t p = pix0 + pt * 16 + r16;
@@ -224,6 +240,10 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
                 f32x4 v = acc[pt];
                 if (add) v += Act<T>::widen(addv[pt]);
                 v = Act<T>::rounded(v);  // the sums see what later kernels read back
+                if (e.bn.mean) {
+                    if (raw) Act<T>::store4(raw + p * NO + c0, v);
+                    v = wconv_bn_relu(v, bn_mu, bn_is, bn_ga, bn_be);
+                }
                 Act<T>::store4(y + p * NO + c0, v);
                 ssum += v;
                 ssq += v * v;
@@ -303,7 +323,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void wb_global_ptr;
 typedef __attribute__((address_space(3))) void wb_lds_ptr;
 
-template <int LW, int STRIDE>
+template <int LW, int STRIDE, bool BN>
 __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __restrict__ x, const void* __restrict__ wpk, bf16_t* __restrict__ y,
                                                              WEpi e, ConvGeom g, int c_in) {
     __builtin_amdgcn_s_setprio(2);
@@ -394,6 +414,24 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
     // buffer that every wave left at the barrier.  Loads return in order: the weights requested behind the tile wait for
     // it (this is where the second workgroup of the compute unit takes over), and by the time the last taps of a chunk
     // have their weights the tile has landed, so the barrier at the end of the chunk is all that the next chunk needs.
+    // constants of a batch norm applied in the epilogue (read from global memory there, every one of them would wait behind
+    // the stores before it).  Stride 1: mean and invstd in the unused tail of the first buffer's last 1 KB block, gamma and
+    // beta in the second buffer's, written now.  Stride 2 (the tails are too short for 256 channels): at the start of the
+    // first buffer, written after the last chunk.
+    constexpr int CH = OCW * 64;   // channels of this workgroup
+    auto bn_lds = [&](int k) {
+        return WIDE ? reinterpret_cast<float*>(lds_bytes) + k * CH : reinterpret_cast<float*>(lds_bytes + (k >> 1) * buf_bytes + n_slots * 16) + (k & 1) * CH;
+    };
+    auto bn_constants_to_lds = [&]() {
+        if (BN && threadIdx.x < CH) {
+            const int c = blockIdx.y * CH + threadIdx.x;
+            bn_lds(0)[threadIdx.x] = e.bn.mean[c];
+            bn_lds(1)[threadIdx.x] = e.bn.invstd[c];
+            bn_lds(2)[threadIdx.x] = e.bn.gamma[c];
+            bn_lds(3)[threadIdx.x] = e.bn.beta[c];
+        }
+    };
+    if constexpr (!WIDE) bn_constants_to_lds();
     uint4 ws[WB_WSETS][WB_OB];
     tile_request(0, 0);
 #pragma unroll
@@ -443,6 +481,10 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
         __syncthreads();
     }
 
+    if constexpr (WIDE && BN) {
+        bn_constants_to_lds();
+        __syncthreads();
+    }
     // the results of the last matrix instructions are not interlocked against vector-unit readers: wait them out, in
     // statements the accumulators pass through, so that no reader moves ahead of the wait
 #pragma unroll
@@ -453,6 +495,7 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
     const int64_t pix0 = (int64_t)tile * ((WIDE ? 1 : 2) * WB_PB * 16);
     const int64_t total_pixels = (int64_t)g.total_rows << g.wout_log2;
     const T* add = static_cast<const T*>(e.add);
+    T* raw = static_cast<T*>(e.bn.raw);
     // the added tensor is requested for half of the wave's pixel blocks before their first store (see wconv_kernel); what was
     // stored goes back into the accumulation registers for the batch-norm sums, so that the vector registers stay free
 #pragma unroll
@@ -471,25 +514,39 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
             }
         }
 #pragma unroll
-        for (int k = 0; k < HP; ++k) {
-            const int pt = half * HP + k;
-            const int64_t p = pix0 + (wpx * WB_PB + pt) * 16 + r16;
+        for (int o = 0; o < WB_OB; ++o) {
+            const int c0 = (ob0 + o) * 16 + 4 * grp;
+            f32x4 bn_mu = {0.f, 0.f, 0.f, 0.f}, bn_is = bn_mu, bn_ga = bn_mu, bn_be = bn_mu;
+            if constexpr (BN) {
+                const int cl = (wo * WB_OB + o) * 16 + 4 * grp;   // channel inside the workgroup's group
+                bn_mu = *reinterpret_cast<const f32x4*>(bn_lds(0) + cl);
+                bn_is = *reinterpret_cast<const f32x4*>(bn_lds(1) + cl);
+                bn_ga = *reinterpret_cast<const f32x4*>(bn_lds(2) + cl);
+                bn_be = *reinterpret_cast<const f32x4*>(bn_lds(3) + cl);
+            }
 #pragma unroll
-            for (int o = 0; o < WB_OB; ++o) {
-                const int c0 = (ob0 + o) * 16 + 4 * grp;
+            for (int k = 0; k < HP; ++k) {
+                const int pt = half * HP + k;
+                const int64_t p = pix0 + (wpx * WB_PB + pt) * 16 + r16;
                 f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
                 if (p < total_pixels) {
                     v = acc[o][pt];
                     if (add) v += Act<T>::widen(addv[k][o]);
                     v = Act<T>::rounded(v);  // the sums see what later kernels read back
+                    if constexpr (BN) {
+                        if (raw) Act<T>::store4(raw + p * NO + c0, v);
+                        v = wconv_bn_relu(v, bn_mu, bn_is, bn_ga, bn_be);
+                    }
                     Act<T>::store4(y + p * NO + c0, v);
                 }
-                acc[o][pt] = v;
-                asm volatile("" : "+a"(acc[o][pt]));
+                if (!BN && e.sums) {
+                    acc[o][pt] = v;
+                    asm volatile("" : "+a"(acc[o][pt]));
+                }
             }
         }
     }
-    if (e.sums) {
+    if (!BN && e.sums) {
         // every wave is past its last tile read (barrier after the last chunk): the tile's space carries the lane sums of the
         // first pixel half ([wo][o][sum, sum of squares][lane] vectors) and the per-wave partials ([block][2][16])
         f32x4* hand = lds_raw;
@@ -550,7 +607,6 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
             }
         }
         __syncthreads();
-        constexpr int CH = OCW * 64;   // channels of this workgroup
         for (int k = threadIdx.x; k < 2 * CH; k += 256) {
             const int which = k / CH, c = k % CH;
             fixsum_add(e.sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * NO + blockIdx.y * CH + c,
@@ -573,6 +629,11 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
         // stride 2 in multiples of 256
         const bool small_offsets = (int64_t)B * (ups ? h_in / 2 : h_in) * (ups ? h_in / 2 : h_in) * c_in < (int64_t(1) << 31);
         const size_t fold = (2 * WB_OB * 2 * 64) * sizeof(f32x4) + 4 * WB_OB * 2 * 16 * sizeof(float);   // lane sums + per-wave partials
+        // unused 16-byte slots behind a buffer's tile: the epilogue's batch-norm constants need half a slot per channel of the workgroup
+        auto tail_slots = [](const ConvGeom& gb) {
+            const int n_slots = gb.imgs * gb.in_rows * gb.lw * 4;
+            return ((n_slots + 255) & ~255) - n_slots;
+        };
         auto launch_block = [&](auto kern, const ConvGeom& gb, int oc_wg) {
             const int n_slots = gb.imgs * gb.in_rows * gb.lw * 4;
             size_t lds_b = 2 * (size_t)((n_slots + 255) & ~255) * 16;
@@ -585,10 +646,11 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
         if (stride == 1 && c_out % 128 == 0 && c_in % 32 == 0 && small_offsets) {
             const ConvGeom gb = geom(2 * WB_PB);
             const bool shape = (gb.lw == 34 && gb.in_rows == 10) || (gb.lw == 18 && gb.in_rows == 18) || (gb.lw == 10 && gb.in_rows == 10);
-            if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV && (int64_t)gb.n_tiles * (c_out / 128) >= 128) {
-                if (gb.lw == 34) launch_block(wconv_block_kernel<34, 1>, gb, 128);
-                else if (gb.lw == 18) launch_block(wconv_block_kernel<18, 1>, gb, 128);
-                else launch_block(wconv_block_kernel<10, 1>, gb, 128);
+            if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV && tail_slots(gb) >= 128 / 2 && (int64_t)gb.n_tiles * (c_out / 128) >= 128) {
+                const bool bn = e_in.bn.mean != nullptr;
+                if (gb.lw == 34) launch_block(bn ? wconv_block_kernel<34, 1, true> : wconv_block_kernel<34, 1, false>, gb, 128);
+                else if (gb.lw == 18) launch_block(bn ? wconv_block_kernel<18, 1, true> : wconv_block_kernel<18, 1, false>, gb, 128);
+                else launch_block(bn ? wconv_block_kernel<10, 1, true> : wconv_block_kernel<10, 1, false>, gb, 128);
                 return 0;
             }
         }
@@ -596,8 +658,9 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
             const ConvGeom gb = geom(WB_PB);
             const bool shape = (gb.lw == 34 || gb.lw == 18) && gb.in_rows == 17;
             if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV_STRIDE2 && (int64_t)gb.n_tiles * (c_out / 256) >= 128) {
-                if (gb.lw == 34) launch_block(wconv_block_kernel<34, 2>, gb, 256);
-                else launch_block(wconv_block_kernel<18, 2>, gb, 256);
+                const bool bn = e_in.bn.mean != nullptr;
+                if (gb.lw == 34) launch_block(bn ? wconv_block_kernel<34, 2, true> : wconv_block_kernel<34, 2, false>, gb, 256);
+                else launch_block(bn ? wconv_block_kernel<18, 2, true> : wconv_block_kernel<18, 2, false>, gb, 256);
                 return 0;
             }
         }
@@ -633,9 +696,9 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
 // c_in is 16 or a multiple of 32, c_out a multiple of 16, maps are squares with power-of-two sides.
 // Returns 0, or -1 when the shape is outside what the kernel is built for (nothing is launched then).
 int launch_wconv(hipStream_t s, int act, int taps, int B, int h_in, int h_out, int c_in, int c_out, int stride, int ups, const void* x,
-                 const void* w, void* y, const void* add, fixsum_t* sums, double scale) {
-    if (!(c_in == 16 || c_in % 32 == 0) || c_out % 16 != 0 || (taps != 9 && taps != 1)) return -1;
-    WEpi e{add, sums, scale, 0.0};
+                 const void* w, void* y, const void* add, fixsum_t* sums, double scale, const WconvBn* bn) {
+    if (!(c_in == 16 || c_in % 32 == 0) || c_out % 16 != 0 || (taps != 9 && taps != 1) || (bn && sums)) return -1;
+    WEpi e{add, sums, scale, 0.0, bn ? *bn : WconvBn{nullptr, nullptr, nullptr, nullptr, nullptr}};
     int rc = -1;
     ACT_DISPATCH(act, {
         if (taps == 9) rc = c_in == 16 ? launch_wconv_t<T, 9, 16>(s, B, h_in, h_out, c_in, c_out, stride, ups, (const T*)x, w, (T*)y, e)
