@@ -312,7 +312,12 @@ __device__ __forceinline__ void static_for(F&& f) {
 #define WB_NV 7            // 16-byte slots of a chunk tile per thread, at most
 #define WB_NV_STRIDE2 10   // the same for a stride-2 layer (17 input rows of 34 positions)
 #define WB_AHEAD 3     // pixel operands requested from LDS ahead of their matrix instructions
-#define WB_WSETS 3     // weight register sets (one tap each): the tap in use and the two requested behind it
+// Weight register sets (one tap each): the tap in use and the ones requested behind it.  Three sets leave a wave within
+// 128 + 128 registers: two workgroups per compute unit, which is what large launches want.  A launch with at most one
+// workgroup per compute unit has nobody to hide a wave's waits: it takes nine sets (a weight is requested eight taps, ~2 us,
+// before its use) and the registers of the absent second workgroup.
+#define WB_WSETS_SHARED 3
+#define WB_WSETS_ALONE 9
 // The matrix instruction as an assembly statement: accumulator in place in the accumulation registers, operands in
 // vector registers.  (Written as the builtin, the compiler keeps moving the 128 accumulator registers between the two
 // register files: two moves per matrix instruction.)  The compiler does not see the instruction's latency: a wait stands
@@ -323,8 +328,8 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(1))) const void wb_global_ptr;
 typedef __attribute__((address_space(3))) void wb_lds_ptr;
 
-template <int LW, int STRIDE, bool BN>
-__global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __restrict__ x, const void* __restrict__ wpk, bf16_t* __restrict__ y,
+template <int LW, int STRIDE, bool BN, int WSETS>
+__global__ __launch_bounds__(256, WSETS == WB_WSETS_SHARED ? 2 : 1) void wconv_block_kernel(const bf16_t* __restrict__ x, const void* __restrict__ wpk, bf16_t* __restrict__ y,
                                                              WEpi e, ConvGeom g, int c_in) {
     __builtin_amdgcn_s_setprio(2);
     typedef bf16_t T;
@@ -432,10 +437,10 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
         }
     };
     if constexpr (!WIDE) bn_constants_to_lds();
-    uint4 ws[WB_WSETS][WB_OB];
+    uint4 ws[WSETS][WB_OB];
     tile_request(0, 0);
 #pragma unroll
-    for (int k = 0; k < WB_WSETS - 1; ++k)
+    for (int k = 0; k < WSETS - 1; ++k)
 #pragma unroll
         for (int o = 0; o < WB_OB; ++o) ws[k][o] = weights_of(o, k, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -465,19 +470,22 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
             if constexpr (step + WB_AHEAD < STEPS) ring[(step + WB_AHEAD) % (WB_AHEAD + 1)] = pixel_operand(step + WB_AHEAD);
             if constexpr (pt < WB_OB) {
                 // tap t + 2, possibly of the next chunk (the last chunk reads its own first taps again: unused)
-                constexpr int tn = (t + WB_WSETS - 1) % TAPS;
-                const int nch = (t + WB_WSETS - 1 >= TAPS && more) ? ch + 1 : ch;
-                ws[(t + WB_WSETS - 1) % WB_WSETS][pt] = weights_of(pt, tn, nch);
+                constexpr int tn = (t + WSETS - 1) % TAPS;
+                const int nch = (t + WSETS - 1 >= TAPS && more) ? ch + 1 : ch;
+                ws[(t + WSETS - 1) % WSETS][pt] = weights_of(pt, tn, nch);
             }
             const uint4 b = ring[step % (WB_AHEAD + 1)];
 #pragma unroll
-            for (int o = 0; o < WB_OB; ++o) WB_MFMA(acc[o][pt], ws[t % WB_WSETS][o], b);
+            for (int o = 0; o < WB_OB; ++o) WB_MFMA(acc[o][pt], ws[t % WSETS][o], b);
             __builtin_amdgcn_sched_barrier(0);
         });
-        // everything but the 2 * WB_OB * (WB_WSETS - 1) weight loads of the last two taps has returned: the tile, requested
-        // before them, is in LDS
-        asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-        static_assert(2 * WB_OB * (WB_WSETS - 1) == 16, "the wait above counts the weight loads of the taps requested ahead");
+        // The tile was requested before this chunk's weight loads, of which 2 * WB_OB * (WSETS - 1) are still wanted in flight
+        // (the taps requested ahead).  With three sets that is what the wait allows; with nine it is more than the counter
+        // holds, and the wait (all but the 56 youngest have returned) is the one the next chunk's first tap would make anyway.
+        if constexpr (WSETS == WB_WSETS_SHARED) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(56)" ::: "memory");
+        static_assert(2 * WB_OB * (WB_WSETS_SHARED - 1) == 16 && 2 * WB_OB * (WB_WSETS_ALONE - 1) - 2 * WB_OB == 56 && TAPS % WSETS == 0,
+                      "the waits above count the weight loads of the taps requested ahead; the sets rotate once per chunk");
         __syncthreads();
     }
 
@@ -615,6 +623,12 @@ __global__ __launch_bounds__(256, 2) void wconv_block_kernel(const bf16_t* __res
     }
 }
 
+// the instantiation for a row width and stride: batch norm in the epilogue or not, alone on its compute unit or not
+#define WB_ALONE_MAX 256
+#define WB_PICK(LW, STRIDE)                                                                                                                 \
+    (bn ? (alone ? wconv_block_kernel<LW, STRIDE, true, WB_WSETS_ALONE> : wconv_block_kernel<LW, STRIDE, true, WB_WSETS_SHARED>)            \
+        : (alone ? wconv_block_kernel<LW, STRIDE, false, WB_WSETS_ALONE> : wconv_block_kernel<LW, STRIDE, false, WB_WSETS_SHARED>))
+
 // Tile: 256 pixels when the staged chunk fits 64 KB (two workgroups per compute unit), else 128.  The prefetching
 // path needs the chunk tile to fit WC_NV vectors per thread and two buffers to fit 80 KB.
 template <typename T, int TAPS, int CK>
@@ -648,9 +662,10 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
             const bool shape = (gb.lw == 34 && gb.in_rows == 10) || (gb.lw == 18 && gb.in_rows == 18) || (gb.lw == 10 && gb.in_rows == 10);
             if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV && tail_slots(gb) >= 128 / 2 && (int64_t)gb.n_tiles * (c_out / 128) >= 128) {
                 const bool bn = e_in.bn.mean != nullptr;
-                if (gb.lw == 34) launch_block(bn ? wconv_block_kernel<34, 1, true> : wconv_block_kernel<34, 1, false>, gb, 128);
-                else if (gb.lw == 18) launch_block(bn ? wconv_block_kernel<18, 1, true> : wconv_block_kernel<18, 1, false>, gb, 128);
-                else launch_block(bn ? wconv_block_kernel<10, 1, true> : wconv_block_kernel<10, 1, false>, gb, 128);
+                const bool alone = (int64_t)gb.n_tiles * (c_out / 128) <= WB_ALONE_MAX;
+                if (gb.lw == 34) launch_block(WB_PICK(34, 1), gb, 128);
+                else if (gb.lw == 18) launch_block(WB_PICK(18, 1), gb, 128);
+                else launch_block(WB_PICK(10, 1), gb, 128);
                 return 0;
             }
         }
@@ -659,8 +674,9 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
             const bool shape = (gb.lw == 34 || gb.lw == 18) && gb.in_rows == 17;
             if (shape && gb.imgs * gb.in_rows * gb.lw * 4 <= 256 * WB_NV_STRIDE2 && (int64_t)gb.n_tiles * (c_out / 256) >= 128) {
                 const bool bn = e_in.bn.mean != nullptr;
-                if (gb.lw == 34) launch_block(bn ? wconv_block_kernel<34, 2, true> : wconv_block_kernel<34, 2, false>, gb, 256);
-                else launch_block(bn ? wconv_block_kernel<18, 2, true> : wconv_block_kernel<18, 2, false>, gb, 256);
+                const bool alone = (int64_t)gb.n_tiles * (c_out / 256) <= WB_ALONE_MAX;
+                if (gb.lw == 34) launch_block(WB_PICK(34, 2), gb, 256);
+                else launch_block(WB_PICK(18, 2), gb, 256);
                 return 0;
             }
         }
