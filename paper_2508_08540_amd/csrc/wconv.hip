@@ -54,7 +54,7 @@ static size_t wconv_lds_bytes(const ConvGeom& g) {
 
 template <typename T, int TAPS, int CK, int NPT>
 __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, const void* __restrict__ wpk, T* __restrict__ y, WEpi e,
-                                                    ConvGeom g, int c_in, int pipelined) {
+                                                    ConvGeom g, int c_in, int pipelined, int sub) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     typedef typename Tile<T>::quad quad;
     typedef typename Tile<T>::vec16 vec16;
@@ -139,7 +139,9 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
         const int buf_quads = g.imgs * g.in_rows * g.lw * CPQ;
         const int rpi = 1 << g.rpi_log2;
         const int row0 = tile * g.rows_tile;
-        const int src_h = g.ups ? (g.h_in >> 1) : g.h_in;
+        // sub: the geometry describes a stride-1 layer over every second row and column of a map twice the size (a 1x1
+        // stride-2 filter reads nothing else)
+        const int src_h = sub ? 2 * g.h_in : g.ups ? (g.h_in >> 1) : g.h_in;
         int goff[WC_NV], loff[WC_NV];
 #pragma unroll
         for (int i = 0; i < WC_NV; ++i) {
@@ -157,6 +159,10 @@ __global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, con
                 ok = ok && ((hi | wi) & 1) == 0;
                 hs = hi >> 1;
                 ws = wi >> 1;
+            }
+            if (sub) {
+                hs = 2 * hi;
+                ws = 2 * wi;
             }
             goff[i] = ok ? ((n * src_h + hs) * src_h + ws) * c_in + cv * (4 * Tile<T>::VQ) : -1;
             loff[i] = v < nvec ? px * CPQ + cv * Tile<T>::VQ : -1;
@@ -681,6 +687,17 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
             }
         }
     }
+    int sub = 0;
+    if (TAPS == 1 && stride == 2 && !ups && h_in == 2 * h_out) {
+        // a 1x1 stride-2 filter as a stride-1 layer over the pixels it reads; only the prefetching path knows how to fetch them
+        const ConvGeom gs = make_geom(B, h_out, h_out, c_out, 1, 0, c_in, 256 / h_out, 0);
+        const size_t ls = wconv_lds_bytes<T, TAPS, CK>(gs);
+        if (256 / h_out >= 1 && ls <= 65536 && gs.imgs * gs.in_rows * gs.lw * TR::CV <= 256 * WC_NV && 2 * ls <= 80 * 1024 && c_in / CK > 1) {
+            sub = 1;
+            h_in = h_out;
+            stride = 1;
+        }
+    }
     ConvGeom g = geom(16);
     int npt = 16;
     size_t lds = wconv_lds_bytes<T, TAPS, CK>(g);
@@ -700,11 +717,11 @@ static int launch_wconv_t(hipStream_t s, int B, int h_in, int h_out, int c_in, i
     if (npt == 16) {
         auto kern = wconv_kernel<T, TAPS, CK, 16>;
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, x, w, y, e, g, c_in, pipelined);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, x, w, y, e, g, c_in, pipelined, sub);
     } else {
         auto kern = wconv_kernel<T, TAPS, CK, 8>;
         if (lds > 65536) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, x, w, y, e, g, c_in, pipelined);
+        hipLaunchKernelGGL(kern, grid, dim3(256), lds, s, x, w, y, e, g, c_in, pipelined, sub);
     }
     return 0;
 }
