@@ -231,7 +231,7 @@ def main():
     symbol = {"conv_fwd": "conv_kernel (forward launches)", "conv_dgrad": "conv_kernel (input-gradient launches)",
               "conv_wgrad": "wgrad_kernel"}[dom]
     if wide and dom != "conv_wgrad":
-        symbol = symbol.replace("conv_kernel", "wconv_kernel")
+        symbol = symbol.replace("conv_kernel", "wconv_block_kernel and wconv_kernel")
     # forward and input-gradient convolutions run on the matrix instruction of the storage type; the weight
     # gradient always multiplies in fp32
     peak = BF16_MFMA_PEAK_TFLOPS if (act_dtype == "bf16" and dom != "conv_wgrad") else FP32_MFMA_PEAK_TFLOPS
