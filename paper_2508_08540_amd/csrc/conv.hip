@@ -761,6 +761,10 @@ void launch_conv_dgrad(hipStream_t s, int act, const ConvShape& cs, const void* 
 // it folds and converts its sums exactly as a one-group workgroup does and keeps them as integers in registers, the
 // prefetch of the next tile runs across the boundary, and one set of atomics leaves at the end: the same bits from an
 // eighth of the workgroups, first loads and atomics.
+// (the unroll request on the loop over pixel quads is declined in the instantiations where the row width is not known:
+// expected, not worth a line per instantiation in every build)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Wpass-failed"
 template <typename T, int TAPS, bool PIPE, bool MULTI, int XK = WG_XK>
 __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                               fixsum_t* __restrict__ gacc, ConvGeom g, int tiles_per_group,
@@ -942,6 +946,7 @@ __global__ __launch_bounds__(WGRAD_THREADS) void wgrad_kernel(const T* __restric
         fixsum_add(out + e, (double)v * FIX_WGRAD_SCALE);
     }
 }
+#pragma clang diagnostic pop
 
 // End of a local step, one launch: for every parameter take the gradient, apply the SGD update
 // (g += wd*x; buf = mu*buf + g; x -= lr*buf), and for convolution weights also write the new value into the
