@@ -1082,15 +1082,19 @@ bool wgrad16_covers(int act, const ConvShape& cs);
 int wgrad16_groups(const ConvShape& cs);
 void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt,
                     Reps reps);
+int64_t wgrad16_partial_words(const ConvShape& cs);
 
-// Accumulator replicas of a layer: as many as there are pixel groups, at most WGRAD_REPLICAS.
+// Accumulator replicas of a layer: as many as there are pixel groups, at most WGRAD_REPLICAS; one where the pixel groups
+// leave partial sums that a second launch adds.
 int conv_wgrad_replicas(int act, const ConvShape& cs) {
+    if (wgrad16_covers(act, cs) && wgrad16_partial_words(cs) > 0) return 1;
     int groups = wgrad16_covers(act, cs) ? wgrad16_groups(cs) : wgrad_groups(cs, wgrad_geom(cs).n_tiles);
     return groups < WGRAD_REPLICAS ? groups : WGRAD_REPLICAS;
 }
 
 int64_t conv_wgrad_accumulators(int act, const ConvShape& cs) {
-    return (int64_t)conv_wgrad_replicas(act, cs) * cs.c_out * cs.taps * cs.c_in;
+    const int64_t words = (int64_t)conv_wgrad_replicas(act, cs) * cs.c_out * cs.taps * cs.c_in;
+    return words + (wgrad16_covers(act, cs) ? wgrad16_partial_words(cs) : 0);
 }
 
 template <typename T, int TAPS>

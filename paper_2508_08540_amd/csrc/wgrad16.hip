@@ -315,6 +315,282 @@ __global__ __launch_bounds__(256) void wgrad16_pair_kernel(const bf16_t* __restr
     }
 }
 
+// ---- 3x3 layers on 8 x 8, 16 x 16 and 32 x 32 maps: 32 x 32 channel blocks per wave, 32 pixels per matrix instruction --------
+// Workgroup = (pixel group, 64 output channels, 64 input channels) of two teams of four waves; a team walks every other tile
+// of the group with accumulators of its own (folded through LDS in team order at the end, so the workgroup adds its sums
+// once).  A wave owns 32 x 32 channels: 2 x 2 blocks x 9 taps of v_mfma_f32_16x16x32_bf16.
+// A tile is 128 consecutive output pixels (four rows of a 32-wide map, half a 16 x 16 map, two 8 x 8 maps) in four steps
+// of 32; lane group g of a step takes 8 consecutive pixels of one row, and the assignment of pixels to (step, group) is the
+// same for dy and x, which is all the contraction needs: group g keeps its columns and moves one row down per step.
+// LDS holds one plane per channel (dy: the 128 pixels; x: the staged rows of the tile with their halo rows, each row
+// followed by eight zero pixels that serve as the right border of this row and the left border of the next).  An operand
+// is one aligned 16-byte read of 8 pixels; the operands of the left and right taps are cut out of it and the two
+// neighbouring pixel pairs with alignbit.  Planes of channel group c / 8 start 16 bytes later than those of the group
+// before (measured: 8-byte staging writes of eight channel groups then spread over the banks; the 16-byte reads run at
+// full rate at either pitch).
+// Staging: a task is 8 channels x 4 pixels: four 16-byte loads (eight lanes cover the 128 contiguous bytes of a pixel's 64
+// channels), a transpose in registers, eight 8-byte LDS writes.  A thread has one task of dy and up to two of x per tile;
+// their loads for the next tile are requested before the matrix instructions of the current one.
+#define WT_PX 128
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+template <int WLOG>
+struct WtGeom {
+    static constexpr int W = 1 << WLOG;                        // map width and height
+    static constexpr int BANDS = W == 8 ? 2 : 1;               // image parts per tile (two whole 8 x 8 maps)
+    static constexpr int BROWS = WT_PX / W / BANDS;            // output rows per band: 4, 8, 8
+    static constexpr int RB = BROWS + 2;                       // staged rows per band
+    static constexpr int RP = W + 8;                           // pixels per staged row, the zeros included
+    static constexpr int XPX = BANDS * RB * RP;                // pixels per x plane
+    static constexpr int PPX = 16 + 2 * XPX + 112 + (W == 8 ? 16 : 0);   // bytes from plane to plane: 608, 608, 784
+    static constexpr int PPD = 2 * WT_PX + 112;                // 368
+    static constexpr int TEAM_BYTES = 64 * (PPX + PPD);
+    static constexpr int XTASKS = 8 * BANDS * RB * (W / 4);    // 384, 320, 320
+};
+
+template <int WLOG>
+__global__ __launch_bounds__(512) void wgrad16_tile_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy, fixsum_t* __restrict__ gacc,
+                                                           int B, int NI, int NO, int n_tiles, int tiles_per_group, int64_t rstride) {
+    typedef WtGeom<WLOG> G;
+    constexpr int W = G::W, RP = G::RP, PPX = G::PPX, PPD = G::PPD;
+    if (rstride) {   // one replica of several: every buffer sits blockIdx.z slots further
+        const int64_t ro = (int64_t)blockIdx.z * rstride;
+        x = rep_at(x, ro); dy = rep_at(dy, ro); gacc = rep_at(gacc, ro);
+    }
+    extern __shared__ uint4 lds16[];
+    const int team = threadIdx.x >> 8, tid = threadIdx.x & 255;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nib = NI >> 6;
+    const int cob = blockIdx.y / nib, cib = blockIdx.y - cob * nib;
+    char* const xT = reinterpret_cast<char*>(lds16) + team * G::TEAM_BYTES;
+    char* const dT = xT + 64 * PPX;
+    const int64_t total_px = (int64_t)B * W * W;
+
+    // pads and borders are zero for the whole launch: the staging only ever writes pixels of the map
+    for (int i = tid; i < G::TEAM_BYTES / 16; i += 256) reinterpret_cast<uint4*>(xT)[i] = make_uint4(0u, 0u, 0u, 0u);
+
+    f32x4 acc[2][2][9];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc[a][b][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- staging tasks of this thread -----------------------------------------------------------------------------------
+    const int cg = tid & 7;
+    const int qd = tid >> 3;                                   // pixel quad of the dy task
+    char* const d_dst = dT + 8 * cg * PPD + cg * 16 + 8 * qd;
+    int x_row[2], x_band[2], x_col[2];
+    char* x_dst[2];
+    bool x_on[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int id = tid + 256 * k;
+        x_on[k] = id < G::XTASKS;
+        const int qx = id >> 3;
+        const int row = qx >> (WLOG - 2);
+        x_col[k] = 4 * (qx & (W / 4 - 1));
+        x_band[k] = (G::BANDS == 2 && row >= G::RB) ? 1 : 0;
+        x_row[k] = row - x_band[k] * G::RB;
+        x_dst[k] = xT + 8 * cg * PPX + cg * 16 + 16 + 2 * (row * RP + x_col[k]);
+    }
+    u32x4_t rd[4], rx[2][4];
+    auto request = [&](int tile) {
+        const int64_t p0 = (int64_t)tile * WT_PX + 4 * qd;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            rd[j] = u32x4_t{0u, 0u, 0u, 0u};
+            if (tile < n_tiles && p0 + j < total_px) rd[j] = *reinterpret_cast<const u32x4_t*>(dy + (p0 + j) * NO + cob * 64 + 8 * cg);
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int grow = tile * (WT_PX / W) + x_band[k] * G::BROWS;   // first output row of the band, counted over all images
+            const int n = grow >> WLOG;
+            const int h = (grow & (W - 1)) - 1 + x_row[k];
+            const bool ok = x_on[k] && tile < n_tiles && n < B && (unsigned)h < (unsigned)W;
+            const bf16_t* p = x + ((((int64_t)n << WLOG) + h) * W + x_col[k]) * NI + cib * 64 + 8 * cg;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                rx[k][j] = u32x4_t{0u, 0u, 0u, 0u};
+                if (ok) rx[k][j] = *reinterpret_cast<const u32x4_t*>(p + (int64_t)j * NI);
+            }
+        }
+    };
+    // v[j] = 8 channels of pixel j; plane e of the task's channel group receives pixels 0 .. 3 of channel e
+    auto put = [](char* dst, int pp, const u32x4_t (&v)[4]) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t lo0 = __builtin_amdgcn_perm(v[1][m], v[0][m], 0x05040100u), lo1 = __builtin_amdgcn_perm(v[3][m], v[2][m], 0x05040100u);
+            const uint32_t hi0 = __builtin_amdgcn_perm(v[1][m], v[0][m], 0x07060302u), hi1 = __builtin_amdgcn_perm(v[3][m], v[2][m], 0x07060302u);
+            *reinterpret_cast<u32x2_t*>(dst + (2 * m) * pp) = u32x2_t{lo0, lo1};
+            *reinterpret_cast<u32x2_t*>(dst + (2 * m + 1) * pp) = u32x2_t{hi0, hi1};
+        }
+    };
+    auto store_tile = [&]() {
+        put(d_dst, PPD, rd);
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+            if (x_on[k]) put(x_dst[k], PPX, rx[k]);
+    };
+
+    // ---- operand addresses of this lane ------------------------------------------------------------------------------------
+    // pixel offsets of lane group g at step 0, tap row 0: in the dy plane and in the x plane (whose row 0 is the halo row)
+    int d_off, x_off;
+    if (W == 32) { d_off = 8 * g; x_off = 8 * g; }
+    else if (W == 16) { d_off = 64 * (g >> 1) + 8 * (g & 1); x_off = 4 * (g >> 1) * RP + 8 * (g & 1); }
+    else { d_off = 32 * g; x_off = (g >> 1) * G::RB * RP + 4 * (g & 1) * RP; }
+    const int ca = 32 * wm + r, cb = 32 * wn + r;   // channels of block 0; block 1 is 16 channels = two channel groups further
+    const char* const a_base = dT + ca * PPD + (ca >> 3) * 16 + 2 * d_off;
+    const char* const b_base = xT + cb * PPX + (cb >> 3) * 16 + 16 + 2 * x_off;
+    auto compute = [&]() {
+#pragma unroll 1
+        for (int step = 0; step < 4; ++step) {
+            bf16x8_t a[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+                a[mb] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(a_base + mb * (16 * PPD + 32) + 2 * W * step));
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    const char* p = b_base + nb * (16 * PPX + 32) + 2 * RP * (step + kh);
+                    const u32x4_t c = *reinterpret_cast<const u32x4_t*>(p);
+                    const uint32_t left = *reinterpret_cast<const uint32_t*>(p - 4), right = *reinterpret_cast<const uint32_t*>(p + 16);
+                    const uint32_t s01 = __builtin_amdgcn_alignbit(c[1], c[0], 16), s12 = __builtin_amdgcn_alignbit(c[2], c[1], 16),
+                                   s23 = __builtin_amdgcn_alignbit(c[3], c[2], 16);
+                    const bf16x8_t o0 = __builtin_bit_cast(bf16x8_t, (u32x4_t{__builtin_amdgcn_alignbit(c[0], left, 16), s01, s12, s23}));
+                    const bf16x8_t o1 = __builtin_bit_cast(bf16x8_t, c);
+                    const bf16x8_t o2 = __builtin_bit_cast(bf16x8_t, (u32x4_t{s01, s12, s23, __builtin_amdgcn_alignbit(right, c[3], 16)}));
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        acc[mb][nb][kh * 3 + 0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mb], o0, acc[mb][nb][kh * 3 + 0], 0, 0, 0);
+                        acc[mb][nb][kh * 3 + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mb], o1, acc[mb][nb][kh * 3 + 1], 0, 0, 0);
+                        acc[mb][nb][kh * 3 + 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mb], o2, acc[mb][nb][kh * 3 + 2], 0, 0, 0);
+                    }
+                }
+        }
+    };
+
+    // ---- the team's tiles: tile_begin + team, + 2, ...; both teams make the same number of turns ----------------------------
+    const int tile_begin = blockIdx.x * tiles_per_group;
+    const int tile_end = min(n_tiles, tile_begin + tiles_per_group);
+    const int turns = (tile_end - tile_begin + 1) >> 1;
+    int tile = tile_begin + team;
+    if (turns > 0) request(tile < tile_end ? tile : n_tiles);
+    __syncthreads();   // zeros in place
+    for (int turn = 0; turn < turns; ++turn, tile += 2) {
+        store_tile();
+        __syncthreads();
+        if (turn + 1 < turns) request(tile + 2 < tile_end ? tile + 2 : n_tiles);
+        if (tile < tile_end) compute();
+        __syncthreads();   // the tile is consumed
+    }
+
+    // ---- team 1's sums go to team 0 through LDS, block row by block row; team 0 adds the sums of the workgroup ---------------
+    float* const fold = reinterpret_cast<float*>(lds16);   // [4 waves][18 blocks][4][64]
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+        if (team == 1) {
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) fold[((wave * 18 + nb * 9 + t) * 4 + j) * 64 + lane] = acc[mb][nb][t][j];
+        }
+        __syncthreads();
+        if (team == 0) {
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[mb][nb][t][j] += fold[((wave * 18 + nb * 9 + t) * 4 + j) * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (team != 0) return;
+    // The sums leave as floats, one copy per pixel group behind the layer's accumulator words (block (ob, ib) of
+    // 16 * 9 * 16 values, element (t*4 + j)*64 + lane, as in the accumulators); wgrad16_fold_kernel converts and adds them.
+    constexpr int BLOCK_FLOATS = 16 * 9 * 16;
+    const int64_t weights = (int64_t)NO * 9 * NI;
+    float* part = reinterpret_cast<float*>(gacc + weights) + (int64_t)blockIdx.x * weights;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            float* out = part + (int64_t)((cob * 4 + 2 * wm + mb) * (NI >> 4) + cib * 4 + 2 * wn + nb) * BLOCK_FLOATS + lane;
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[(t * 4 + j) * 64] = acc[mb][nb][t][j];
+        }
+}
+
+// Every pixel group's partial sum of a weight is converted to fixed point by itself, range-checked, and the integers are
+// added to the layer's accumulator word: the word ends as if every workgroup had added its sums with an atomic, without
+// the 9.4 million 64-bit atomics that cost more than the matrix work.  A thread owns four consecutive words; with SL = 4
+// (layers with many pixel groups and few weights) wave w takes the groups w, w + 4, ... and the four waves' integers meet
+// in LDS.  Eight loads are in flight per thread.  The launch is the only writer of the layer's words while it runs.
+template <int SL>
+__global__ __launch_bounds__(256) void wgrad16_fold_kernel(fixsum_t* __restrict__ gacc, int64_t weights, int groups, int64_t rstride) {
+    if (rstride) gacc = rep_at(gacc, (int64_t)blockIdx.z * rstride);
+    const float* part = reinterpret_cast<const float*>(gacc + weights);
+    constexpr int QB = 256 / SL;   // quads of words per workgroup and turn
+    __shared__ long long red[SL > 1 ? SL - 1 : 1][QB][4];
+    __shared__ int red_bad[SL > 1 ? SL - 1 : 1][QB];
+    const int ql = threadIdx.x % QB, sl = threadIdx.x / QB;
+    const int64_t quads = weights >> 2;
+    for (int64_t q0 = (int64_t)blockIdx.x * QB; q0 < quads; q0 += (int64_t)gridDim.x * QB) {
+        const int64_t q = q0 + ql;
+        const bool on = q < quads;
+        long long sum[4] = {0ll, 0ll, 0ll, 0ll};
+        bool bad[4] = {false, false, false, false};
+        for (int g0 = sl; g0 < groups; g0 += 8 * SL) {
+            f32x4 p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                p[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (on && g0 + SL * u < groups) p[u] = *reinterpret_cast<const f32x4*>(part + (int64_t)(g0 + SL * u) * weights + 4 * q);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) fixsum_collect(sum[i], bad[i], (double)p[u][i] * FIX_WGRAD_SCALE, FIX_PARTIAL_LIMIT);
+        }
+        if (SL > 1) {
+            if (sl > 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) red[sl - 1][ql][i] = sum[i];
+                red_bad[sl - 1][ql] = (bad[0] ? 1 : 0) | (bad[1] ? 2 : 0) | (bad[2] ? 4 : 0) | (bad[3] ? 8 : 0);
+            }
+            __syncthreads();
+        }
+        if (sl == 0 && on) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                long long t = sum[i];
+                bool b = bad[i];
+                if (SL > 1) {
+#pragma unroll
+                    for (int w = 0; w < SL - 1; ++w) {
+                        t += red[w][ql][i];
+                        b = b || ((red_bad[w][ql] >> i) & 1);
+                    }
+                }
+                const long long old = (long long)gacc[4 * q + i];
+                gacc[4 * q + i] = (b || old >= FIX_POISON_MIN) ? (fixsum_t)FIX_POISON : (fixsum_t)(old + t);
+            }
+        }
+        if (SL > 1) __syncthreads();
+    }
+}
+
 // Layers of the narrow network: one 16 x 16 channel block per workgroup.
 static bool pair_layer(const ConvShape& cs) { return cs.c_in <= 64 && cs.c_out <= 64; }
 
@@ -347,6 +623,36 @@ static void launch_w16(K kern, dim3 grid, size_t lds, hipStream_t s, const Kerne
                           g, wg, tiles_per_group, cs.c_in, cs.c_out, replicas, reps.stride);
 }
 
+// 3x3 layers of more than 64 channels on 8 x 8, 16 x 16 or 32 x 32 maps run on wgrad16_tile_kernel
+static bool tile_layer(const ConvShape& cs) { return !pair_layer(cs) && cs.taps == 9 && (cs.h_in == 8 || cs.h_in == 16 || cs.h_in == 32); }
+
+template <int WLOG>
+static void launch_w16t(dim3 grid, hipStream_t s, const KernelTiming* kt, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int n_tiles,
+                        int tiles_per_group, Reps reps) {
+    constexpr int lds = 2 * WtGeom<WLOG>::TEAM_BYTES;
+    static bool attr_set = false;   // the limit is a property of the function; setting it again is harmless
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_tile_kernel<WLOG>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        attr_set = true;
+    }
+    hipExtLaunchKernelGGL(wgrad16_tile_kernel<WLOG>, grid, dim3(512), lds, s, kt ? kt->start : nullptr, nullptr, 0, (const bf16_t*)x, (const bf16_t*)dy, gacc,
+                          cs.B, cs.c_in, cs.c_out, n_tiles, tiles_per_group, reps.stride);
+    const int64_t weights = (int64_t)cs.c_out * 9 * cs.c_in;
+    const int groups = (int)grid.x;
+    const int qb = groups >= 16 ? 64 : 256;   // many groups: four waves share a word's groups
+    int64_t blocks = (weights / 4 + qb - 1) / qb;
+    if (blocks > 4096) blocks = 4096;
+    auto fold = groups >= 16 ? wgrad16_fold_kernel<4> : wgrad16_fold_kernel<1>;
+    hipExtLaunchKernelGGL(fold, dim3((unsigned)blocks, 1, reps.n), dim3(256), 0, s, nullptr, kt ? kt->stop : nullptr, 0, gacc, weights, groups, reps.stride);
+}
+
+// Layers whose pixel groups leave float partial sums behind one accumulator replica: the number of accumulator words that
+// space takes (0 for the layers that add with atomics into their replicas).
+int64_t wgrad16_partial_words(const ConvShape& cs) {
+    if (!tile_layer(cs)) return 0;
+    return ((int64_t)wgrad16_groups(cs) * cs.c_out * 9 * cs.c_in + 1) / 2;
+}
+
 void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int replicas, const KernelTiming* kt,
                     Reps reps) {
     ConvGeom g = wgrad16_geom(cs);
@@ -370,8 +676,14 @@ void launch_wgrad16(hipStream_t s, const ConvShape& cs, const void* x, const voi
         else launch_w16(wgrad16_pair_kernel<1>, grid, lds, s, kt, cs, x, dy, gacc, g, wg, tiles_per_group, replicas, reps);
         return;
     }
-    const size_t lds = (size_t)64 * (wg.xp + wg.dp) * sizeof(bf16_t);
     dim3 grid(groups, (cs.c_in / 64) * (cs.c_out / 64), reps.n);
+    if (tile_layer(cs)) {
+        if (cs.h_in == 32) launch_w16t<5>(grid, s, kt, cs, x, dy, gacc, g.n_tiles, tiles_per_group, reps);
+        else if (cs.h_in == 16) launch_w16t<4>(grid, s, kt, cs, x, dy, gacc, g.n_tiles, tiles_per_group, reps);
+        else launch_w16t<3>(grid, s, kt, cs, x, dy, gacc, g.n_tiles, tiles_per_group, reps);
+        return;
+    }
+    const size_t lds = (size_t)64 * (wg.xp + wg.dp) * sizeof(bf16_t);
     if (cs.taps == 9) launch_w16(wgrad16_kernel<9>, grid, lds, s, kt, cs, x, dy, gacc, g, wg, tiles_per_group, replicas, reps);
     else launch_w16(wgrad16_kernel<1>, grid, lds, s, kt, cs, x, dy, gacc, g, wg, tiles_per_group, replicas, reps);
 }
