@@ -152,12 +152,17 @@ void launch_bn_inference_stats(hipStream_t s, const float* running_mean, const f
 
 // ---- backward -------------------------------------------------------------------------------------
 
-int bn_bwd_partials(int64_t pixels) {
-    int64_t n = pixels / 128;
+// Pixel chunks of the backward reduction: at most 1024 (each of the 16 replicas of a sum then takes 64 partials); 128 pixels
+// per chunk, 32 for the layers that are cut into channel slices (they have few pixels).
+int bn_bwd_partials(int64_t pixels, int C) {
+    int64_t n = pixels / (C > 128 && C % 128 == 0 ? 32 : 128);
     if (n < 1) n = 1;
     if (n > 1024) n = 1024;
     return (int)n;
 }
+// Channels per workgroup of the backward reduction: layers of more than 128 channels are cut into slices of 128 (blockIdx.y),
+// so that a workgroup always has eight or more pixels in flight and a layer of few pixels still fills the chip.
+static int bn_bwd_slice(int C) { return (C > 128 && C % 128 == 0) ? 128 : C; }
 
 // Upstream gradient of pixel p, channels c..c+3: either a full tensor of the storage type, or one fp32
 // vector per sample shared by all `shared` positions of that sample (gradient of a global average pool).
@@ -167,11 +172,12 @@ __device__ __forceinline__ f32x4 load_dout(const void* __restrict__ dout, int sh
     return Act<T>::load4(static_cast<const T*>(dout) + p * C + c);
 }
 
-// adds (sum g, sum g*xhat), g = dout * (out > 0), into the fixed-point accumulators sums[2][C]
+// adds (sum g, sum g*xhat), g = dout * (out > 0), into the fixed-point accumulators sums[2][C]; a workgroup takes a chunk of
+// pixels and the CS channels from blockIdx.y * CS on; two pixels per thread are in flight
 template <typename T, bool WIDE>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restrict__ dout, int shared,
                                                             const T* __restrict__ out, const T* __restrict__ y,
-                                                            int64_t pixels, int C, const float* __restrict__ mean,
+                                                            int64_t pixels, int C, int CS, const float* __restrict__ mean,
                                                             const float* __restrict__ invstd, fixsum_t* __restrict__ sums, int64_t rstride) {
     if (rstride) {
         const int64_t ro = (int64_t)blockIdx.z * rstride;
@@ -179,24 +185,42 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
         sums = rep_at(sums, ro);
     }
     __shared__ float red[2][256][4];
-    const int cq = C >> 2;              // threads per pixel (C <= BN_MAX_C: at most 128)
+    const int cq = CS >> 2;             // threads per pixel (CS <= BN_MAX_C: at most 128)
     const int lanes_p = 256 / cq;       // pixels in flight per block; threads beyond lanes_p * cq idle
     const int cg = threadIdx.x % cq, pl = threadIdx.x / cq;
-    const int c = cg << 2;
+    const int c = blockIdx.y * CS + (cg << 2);
     int64_t chunk = (pixels + gridDim.x - 1) / gridDim.x;
     int64_t p0 = (int64_t)blockIdx.x * chunk, p1 = p0 + chunk < pixels ? p0 + chunk : pixels;
     f32x4 mu = *reinterpret_cast<const f32x4*>(mean + c);
     f32x4 is = *reinterpret_cast<const f32x4*>(invstd + c);
     f32x4 sg = {0.f, 0.f, 0.f, 0.f}, sgx = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t p = p0 + pl; p < p1 && pl < lanes_p; p += lanes_p) {
-        f32x4 d = load_dout<T>(dout, shared, p, C, c);
-        f32x4 o = Act<T>::load4(out + p * C + c);
-        f32x4 v = Act<T>::load4(y + p * C + c);
+    if (pl < lanes_p) {
+        int64_t p = p0 + pl;
+        for (; p + lanes_p < p1; p += 2 * lanes_p) {   // pixels p and p + lanes_p, added in this order
+            const int64_t q = p + lanes_p;
+            f32x4 d0 = load_dout<T>(dout, shared, p, C, c), d1 = load_dout<T>(dout, shared, q, C, c);
+            f32x4 o0 = Act<T>::load4(out + p * C + c), o1 = Act<T>::load4(out + q * C + c);
+            f32x4 v0 = Act<T>::load4(y + p * C + c), v1 = Act<T>::load4(y + q * C + c);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float g = o[j] > 0.f ? d[j] : 0.f;
-            sg[j] += g;
-            sgx[j] = __fmaf_rn(g, (v[j] - mu[j]) * is[j], sgx[j]);
+            for (int j = 0; j < 4; ++j) {
+                float g = o0[j] > 0.f ? d0[j] : 0.f;
+                sg[j] += g;
+                sgx[j] = __fmaf_rn(g, (v0[j] - mu[j]) * is[j], sgx[j]);
+                g = o1[j] > 0.f ? d1[j] : 0.f;
+                sg[j] += g;
+                sgx[j] = __fmaf_rn(g, (v1[j] - mu[j]) * is[j], sgx[j]);
+            }
+        }
+        if (p < p1) {
+            f32x4 d = load_dout<T>(dout, shared, p, C, c);
+            f32x4 o = Act<T>::load4(out + p * C + c);
+            f32x4 v = Act<T>::load4(y + p * C + c);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float g = o[j] > 0.f ? d[j] : 0.f;
+                sg[j] += g;
+                sgx[j] = __fmaf_rn(g, (v[j] - mu[j]) * is[j], sgx[j]);
+            }
         }
     }
 #pragma unroll
@@ -206,27 +230,28 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(const void* __restri
     }
     __syncthreads();
     // column (which, channel) is summed over the pixel lanes in a fixed order
-    for (int t0 = 0; t0 < (WIDE ? 2 * C : 1); t0 += 256) {
+    for (int t0 = 0; t0 < (WIDE ? 2 * CS : 1); t0 += 256) {
         const int t = t0 + (int)threadIdx.x;
-        if (t >= 2 * C) continue;
-        int which = t / C, ch = t % C;
+        if (t >= 2 * CS) continue;
+        int which = t / CS, ch = t % CS;
         float acc = 0.f;
         for (int l = 0; l < lanes_p; ++l) acc += red[which][l * cq + (ch >> 2)][ch & 3];
-        fixsum_add(sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * C + ch, (double)acc * FIX_BWD_SCALE);
+        fixsum_add(sums + ((blockIdx.x % FIX_REPLICAS) * 2 + which) * C + blockIdx.y * CS + ch, (double)acc * FIX_BWD_SCALE);
     }
 }
 
 void launch_bn_bwd_reduce(hipStream_t s, int act, const void* dout, int dout_positions_shared, const void* out, const void* y,
                           int64_t pixels, int C, const float* mean, const float* invstd, fixsum_t* sums, Reps reps) {
-    int n = bn_bwd_partials(pixels);
-    const dim3 grid(n, 1, reps.n);
+    int n = bn_bwd_partials(pixels, C);
+    const int CS = bn_bwd_slice(C);
+    const dim3 grid(n, C / CS, reps.n);
     ACT_DISPATCH(act, {
-        if (2 * C > 256)
+        if (2 * CS > 256)
             hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, true>), grid, dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
-                               (const T*)y, pixels, C, mean, invstd, sums, reps.stride);
+                               (const T*)y, pixels, C, CS, mean, invstd, sums, reps.stride);
         else
             hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, false>), grid, dim3(256), 0, s, dout, dout_positions_shared, (const T*)out,
-                               (const T*)y, pixels, C, mean, invstd, sums, reps.stride);
+                               (const T*)y, pixels, C, CS, mean, invstd, sums, reps.stride);
     });
 }
 
