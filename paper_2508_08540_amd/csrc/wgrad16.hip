@@ -630,11 +630,7 @@ template <int WLOG>
 static void launch_w16t(dim3 grid, hipStream_t s, const KernelTiming* kt, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int n_tiles,
                         int tiles_per_group, Reps reps) {
     constexpr int lds = 2 * WtGeom<WLOG>::TEAM_BYTES;
-    static bool attr_set = false;   // the limit is a property of the function; setting it again is harmless
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_tile_kernel<WLOG>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        attr_set = true;
-    }
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad16_tile_kernel<WLOG>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     hipExtLaunchKernelGGL(wgrad16_tile_kernel<WLOG>, grid, dim3(512), lds, s, kt ? kt->start : nullptr, nullptr, 0, (const bf16_t*)x, (const bf16_t*)dy, gacc,
                           cs.B, cs.c_in, cs.c_out, n_tiles, tiles_per_group, reps.stride);
     const int64_t weights = (int64_t)cs.c_out * 9 * cs.c_in;

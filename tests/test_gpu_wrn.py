@@ -193,6 +193,23 @@ def test_bf16_weight_gradient_several_tiles_per_workgroup(env):
         assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
 
 
+def test_bf16_weight_gradient_tiles_of_32_and_16_wide_maps(env):
+    """128 -> 128 channels at 32x32 maps and 256 -> 256 at 16x16, 17 images: the tiled bf16 weight-gradient kernel with four
+    rows of a 32-wide map and half a 16x16 map per tile (the 8x8 variant is covered above).  136 and 34 tiles over 64 and 16
+    pixel groups: three tiles per workgroup, two for the first team and one for the second, whose sums are folded; at 8x8 the
+    last tile is half empty.  The stride-2 layers between them take the product path.  Criterion as above: no further from
+    the float64 oracle than the bf16 oracle itself is (x 1.5, + 0.03)."""
+    widths, stem, batch = (128, 256, 256), 16, 17
+    h = _harness(env, widths, 1, 32, 10, stem, "bf16")
+    p, b, x, y, sel = _case(widths, 1, 32, batch, 10, stem)
+    losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses, rtol=2e-2)
+    _, g64, _ = oracle.loss_and_grads(oracle.WideResNet(widths, 1, stem), p, b, x[sel], y[sel])
+    for k in grads:
+        assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
+
+
 @pytest.mark.parametrize("widths,hw,blocks,n,tail", [
     ((128, 128, 128), 16, 2, 522, 22),   # 16x16 maps: one image per 256-pixel tile; 8x8 maps: four images per tile, the last tile half empty
     ((128, 128, 128), 32, 1, 40, 6),     # 32x32 maps: tiles of 8 rows
