@@ -24,10 +24,10 @@ sys.path.insert(0, ROOT)
 # 256 MiB copy (profiles/bench_resnet20_fp32_hbm_traffic.txt).  Valid only for the kernel source it was taken on.
 MEASURED_TRAFFIC = {
     "wgrad_kernel": {"fetch_kib": 5268.4, "fetch_scale": 2.0, "write_kib": 4608.0, "write_scale": 1.0,
-                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "2d2d63945a4eb4ae"},
+                     "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "ba26845e9a8a20c1"},
     # launch-weighted mean over the 18 input-gradient launches of a local step
     "conv_kernel (input-gradient launches)": {"fetch_kib": 12235.5, "fetch_scale": 2.0, "write_kib": 9948.7, "write_scale": 1.0,
-                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "2d2d63945a4eb4ae"},
+                                              "source": "paper_2508_08540_amd/csrc/conv.hip", "sha256_16": "ba26845e9a8a20c1"},
 }
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
