@@ -460,7 +460,12 @@ __global__ __launch_bounds__(512) void wgrad16_tile_kernel(const bf16_t* __restr
                 for (int nb = 0; nb < 2; ++nb) {
                     const char* p = b_base + nb * (16 * PPX + 32) + 2 * RP * (step + kh);
                     const u32x4_t c = *reinterpret_cast<const u32x4_t*>(p);
-                    const uint32_t left = *reinterpret_cast<const uint32_t*>(p - 4), right = *reinterpret_cast<const uint32_t*>(p + 16);
+                    // the pixel pairs on either side of the eight; on 8-wide maps they are always the zeros between two rows
+                    uint32_t left = 0u, right = 0u;
+                    if (W >= 16) {
+                        left = *reinterpret_cast<const uint32_t*>(p - 4);
+                        right = *reinterpret_cast<const uint32_t*>(p + 16);
+                    }
                     const uint32_t s01 = __builtin_amdgcn_alignbit(c[1], c[0], 16), s12 = __builtin_amdgcn_alignbit(c[2], c[1], 16),
                                    s23 = __builtin_amdgcn_alignbit(c[3], c[2], 16);
                     const bf16x8_t o0 = __builtin_bit_cast(bf16x8_t, (u32x4_t{__builtin_amdgcn_alignbit(c[0], left, 16), s01, s12, s23}));
