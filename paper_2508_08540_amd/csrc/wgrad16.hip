@@ -597,7 +597,11 @@ __global__ __launch_bounds__(256) void wgrad16_fold_kernel(fixsum_t* __restrict_
 }
 
 // Layers of the narrow network: one 16 x 16 channel block per workgroup.
-static bool pair_layer(const ConvShape& cs) { return cs.c_in <= 64 && cs.c_out <= 64; }
+// ... and layers with 16 input channels, whatever their width (the first block of the wide network)
+static bool pair_layer(const ConvShape& cs) { return (cs.c_in <= 64 && cs.c_out <= 64) || cs.c_in == 16; }
+
+// 3x3 layers of more than 64 channels on 8 x 8, 16 x 16 or 32 x 32 maps run on wgrad16_tile_kernel
+static bool tile_layer(const ConvShape& cs) { return !pair_layer(cs) && cs.taps == 9 && (cs.h_in == 8 || cs.h_in == 16 || cs.h_in == 32); }
 
 bool wgrad16_covers(int act, const ConvShape& cs) {
     if (act != ACT_BF16 || cs.stride != 1 || cs.c_in_real != cs.c_in || cs.h_in < 4 || cs.h_in > 64) return false;
@@ -610,11 +614,14 @@ static ConvGeom wgrad16_geom(const ConvShape& cs) {
     return make_geom(cs.B, cs.h_in, cs.h_in, cs.c_out, 1, 0, cs.c_in, tile_px / cs.h_in, cs.taps == 9 ? 1 : 0);
 }
 
-// Pixel groups: about 256 workgroups in total (each dumps all its sums once, so fewer groups mean fewer atomics)
+// Pixel groups: about 256 workgroups in total (each dumps all its sums once, so fewer groups mean fewer atomics).  The
+// tiled kernel takes 128: one of its workgroups fills a compute unit's registers and most of its LDS for its whole life,
+// and the launches run beside the convolutions of the main stream, which then find half of the compute units free
+// (measured on the WRN-16-8 pass: 22.0 / 20.3 / 20.65 / 21.2 ms with 64 / 128 / 192 / 256 workgroups).
 int wgrad16_groups(const ConvShape& cs) {
     const int pairs = pair_layer(cs) ? (cs.c_in / 16) * (cs.c_out / 16) : (cs.c_in / 64) * (cs.c_out / 64);
     const int n_tiles = wgrad16_geom(cs).n_tiles;
-    int groups = 256 / pairs;
+    int groups = (tile_layer(cs) ? 128 : 256) / pairs;
     if (groups < 1) groups = 1;
     return groups < n_tiles ? groups : n_tiles;
 }
@@ -628,8 +635,6 @@ static void launch_w16(K kern, dim3 grid, size_t lds, hipStream_t s, const Kerne
                           g, wg, tiles_per_group, cs.c_in, cs.c_out, replicas, reps.stride);
 }
 
-// 3x3 layers of more than 64 channels on 8 x 8, 16 x 16 or 32 x 32 maps run on wgrad16_tile_kernel
-static bool tile_layer(const ConvShape& cs) { return !pair_layer(cs) && cs.taps == 9 && (cs.h_in == 8 || cs.h_in == 16 || cs.h_in == 32); }
 
 template <int WLOG>
 static void launch_w16t(dim3 grid, hipStream_t s, const KernelTiming* kt, const ConvShape& cs, const void* x, const void* dy, fixsum_t* gacc, int n_tiles,
