@@ -348,6 +348,11 @@ struct WtGeom {
     static constexpr int PPD = 2 * WT_PX + 112;                // 368
     static constexpr int TEAM_BYTES = 64 * (PPX + PPD);
     static constexpr int XTASKS = 8 * BANDS * RB * (W / 4);    // 384, 320, 320
+    // a plane holds its lead, the largest skew (7 channel groups) and its pixels; a thread has at most two x tasks; both teams'
+    // tiles fit the 160 KB of a compute unit and are at least as large as the fold buffer of the epilogue
+    static_assert(PPX >= 16 + 7 * 16 + 2 * XPX && PPD >= 7 * 16 + 2 * WT_PX && PPX % 16 == 0 && PPD % 16 == 0, "plane pitch");
+    static_assert(XTASKS <= 512, "staging tasks per thread");
+    static_assert(2 * TEAM_BYTES <= 160 * 1024 && 2 * TEAM_BYTES >= 4 * 18 * 4 * 64 * 4, "LDS of a workgroup");
 };
 
 template <int WLOG>
