@@ -52,8 +52,10 @@ static size_t wconv_lds_bytes(const ConvGeom& g) {
     return (size_t)g.imgs * g.in_rows * g.lw * WcTraits<T, TAPS, CK>::CPQ * sizeof(typename Tile<T>::quad);
 }
 
+// (two workgroups per compute unit for the 16-channel inputs of bf16 layers: they have a single chunk, so nothing inside a
+// workgroup overlaps its loads, its few matrix instructions and its stores)
 template <typename T, int TAPS, int CK, int NPT>
-__global__ __launch_bounds__(256) void wconv_kernel(const T* __restrict__ x, const void* __restrict__ wpk, T* __restrict__ y, WEpi e,
+__global__ __launch_bounds__(256, (sizeof(T) == 2 && CK == 16) ? 2 : 1) void wconv_kernel(const T* __restrict__ x, const void* __restrict__ wpk, T* __restrict__ y, WEpi e,
                                                     ConvGeom g, int c_in, int pipelined, int sub) {
     __builtin_amdgcn_s_setprio(2);   // ahead of the weight-gradient kernels of the side stream, which only the update waits for
     typedef typename Tile<T>::quad quad;
