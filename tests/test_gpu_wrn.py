@@ -210,6 +210,23 @@ def test_bf16_weight_gradient_tiles_of_32_and_16_wide_maps(env):
         assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
 
 
+def test_bf16_non_finite_partial_sums_end_in_nan(env):
+    """The tiled weight-gradient kernel leaves float partial sums that a second launch converts to fixed point: a partial
+    that is not finite must poison the accumulator word (NaN gradient, NaN parameters, NaN losses at the next step), as a
+    float sum would end, and must not come out as a finite integer; the scratch carries nothing over to the next call."""
+    widths, stem, batch = (128, 128, 128), 16, 4
+    h = _harness(env, widths, 1, 8, 10, stem, "bf16")
+    p, b, x, y, sel = _case(widths, 1, 8, batch, 10, stem)
+    bad = x.copy()
+    bad[sel[1], 3, 5, 1] = np.nan
+    newp, gb, mom, sl = h.local_step(p, b, _zeros(p), bad, y, sel, batch, 2, lr=0.05, mu=0.9)
+    conv = [k for k in mom if "conv" in k and k.endswith("weight")]
+    assert conv and all(np.isnan(mom[k]).all() for k in conv), {k: float(np.isnan(mom[k]).mean()) for k in conv}
+    assert all(np.isnan(newp[k]).all() for k in conv) and np.isnan(sl[1]).all()
+    newp, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 2, lr=0.05, mu=0.9)
+    assert all(np.isfinite(v).all() for v in newp.values()) and np.isfinite(sl).all()
+
+
 @pytest.mark.parametrize("widths,hw,blocks,n,tail", [
     ((128, 128, 128), 16, 2, 522, 22),   # 16x16 maps: one image per 256-pixel tile; 8x8 maps: four images per tile, the last tile half empty
     ((128, 128, 128), 32, 1, 40, 6),     # 32x32 maps: tiles of 8 rows
