@@ -210,6 +210,22 @@ def test_bf16_weight_gradient_tiles_of_32_and_16_wide_maps(env):
         assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
 
 
+def test_bf16_weight_gradient_tiles_with_three_channel_blocks(env):
+    """192 -> 192 channels at 8x8 maps (nine 64 x 64 channel-block pairs, fourteen pixel groups) and 128 -> 128 at 16x16, 40
+    images: channel-block counts that are not powers of two, pixel groups that do not divide the tiles evenly.  Criterion
+    as for the other sizes at which bf16 roundings flip: no further from the float64 oracle than the bf16 oracle itself is
+    (x 1.5, + 0.03)."""
+    widths, stem, batch = (128, 192, 192), 16, 40
+    h = _harness(env, widths, 1, 16, 10, stem, "bf16")
+    p, b, x, y, sel = _case(widths, 1, 16, batch, 10, stem)
+    losses, grads, new_b = oracle.loss_and_grads(h.oracle_model, p, b, x[sel], y[sel])
+    _, gb, mom, sl = h.local_step(p, b, _zeros(p), x, y, sel, batch, 1, lr=0.0, mu=0.9)
+    assert_losses_close(sl[0], losses, rtol=2e-2)
+    _, g64, _ = oracle.loss_and_grads(oracle.WideResNet(widths, 1, stem), p, b, x[sel], y[sel])
+    for k in grads:
+        assert rel_err(mom[k], g64[k]) < 1.5 * rel_err(grads[k], g64[k]) + 0.03, k
+
+
 def test_bf16_non_finite_partial_sums_end_in_nan(env):
     """The tiled weight-gradient kernel leaves float partial sums that a second launch converts to fixed point: a partial
     that is not finite must poison the accumulator word (NaN gradient, NaN parameters, NaN losses at the next step), as a
