@@ -1,4 +1,5 @@
-// Weight gradient of wide bf16 layers on the bf16 matrix instruction.
+// Weight gradient of wide bf16 layers on the bf16 matrix instruction: the convolution part of the stochastic gradient in the
+// local SGD update of a fast worker (Section 2, the local update rule; fast-worker branch of Algorithm 1).
 //
 // dW[o][tap][i] = sum over pixels p of dy[p][o] * x[p + tap][i] contracts over pixels, so both operands of
 // v_mfma_f32_16x16x16_bf16 must supply four *consecutive pixels* of one channel per lane.  Activations are
